@@ -1,0 +1,356 @@
+/*
+ * CPU oracle for the masked-autoencoder input pipeline.  TEST INFRASTRUCTURE ONLY -- see
+ * mae_oracle.h.  Plain scalar C, fp64 arithmetic, no blocking or fusion: each function is the
+ * definition of its step written out.  Build with -ffp-contract=off so that the crop-parameter
+ * arithmetic is the sequence of correctly rounded +, -, *, /, sqrt that is written here.
+ */
+#include "mae_oracle.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ------------------------------------------------------------------------------------------------
+ * Random numbers.  The paper does not name a generator; the reading taken is a counter-based one
+ * so that every draw is a pure function of (seed, batch, sample, stream, counter): the finaliser
+ * of SplitMix64 applied to state + (n+1)*golden-gamma is the n-th output of that generator.
+ * ---------------------------------------------------------------------------------------------- */
+static const uint64_t GOLDEN_GAMMA = 0x9E3779B97F4A7C15ull;
+
+uint64_t mae_oracle_mix64(uint64_t z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+uint64_t mae_oracle_draw(uint64_t seed, uint64_t batch_index, uint32_t sample, uint32_t stream,
+                         uint32_t ctr) {
+  uint64_t k0 = mae_oracle_mix64(seed + GOLDEN_GAMMA);
+  uint64_t k1 = mae_oracle_mix64(k0 + GOLDEN_GAMMA * (batch_index + 1));
+  uint64_t w = ((uint64_t)sample << 32) | ((uint64_t)(stream & 0xFFu) << 24) |
+               (uint64_t)(ctr & 0xFFFFFFu);
+  return mae_oracle_mix64(k1 + GOLDEN_GAMMA * (w + 1));
+}
+
+static uint32_t draw_u32(uint64_t seed, uint64_t batch, uint32_t sample, uint32_t stream,
+                         uint32_t ctr) {
+  return (uint32_t)(mae_oracle_draw(seed, batch, sample, stream, ctr) >> 32);
+}
+
+/* uniform in [0,1) with 53 random bits; exact in fp64 */
+static double draw_unit(uint64_t seed, uint64_t batch, uint32_t sample, uint32_t stream,
+                        uint32_t ctr) {
+  uint64_t u53 = mae_oracle_draw(seed, batch, sample, stream, ctr) >> 11;
+  return (double)u53 * (1.0 / 9007199254740992.0);
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * RandomResizedCrop parameters (Sec. 5.1).  The area fraction is uniform on [scale_lo, scale_hi]
+ * (the paper's sigma is its square root), the logarithm of the aspect ratio width/height is
+ * uniform on [ln ratio_lo, ln ratio_hi].  The paper is silent on rounding, acceptance and the
+ * fallback; the reading is the common one: up to ten proposals, sides rounded half-to-even, a
+ * proposal is accepted when it fits inside the image, the corner is then uniform over the
+ * positions that fit; after ten rejections the largest centred box whose ratio is inside the
+ * range is taken.
+ * ---------------------------------------------------------------------------------------------- */
+double mae_oracle_exp_poly(double x) {
+  double e = 1.0;
+  for (int k = 13; k >= 1; --k) {
+    double xe = x * e;
+    double q = xe / (double)k;
+    e = 1.0 + q;
+  }
+  return e;
+}
+
+void mae_oracle_rrc_proposal(int32_t H, int32_t W, float scale_lo, float scale_hi, float ratio_lo,
+                             float ratio_hi, uint64_t seed, uint64_t batch_index, uint32_t sample,
+                             int32_t attempt, int64_t out_hw[2]) {
+  double lo = (double)scale_lo, hi = (double)scale_hi;
+  double ln_lo = log((double)ratio_lo), ln_hi = log((double)ratio_hi);
+  double area = (double)((int64_t)H * (int64_t)W);
+
+  double u_scale = draw_unit(seed, batch_index, sample, 0u, (uint32_t)attempt);
+  double u_ratio = draw_unit(seed, batch_index, sample, 1u, (uint32_t)attempt);
+  double s = lo + (hi - lo) * u_scale;
+  double T = area * s;
+  double x = ln_lo + (ln_hi - ln_lo) * u_ratio;
+  double r = mae_oracle_exp_poly(x);
+  double cw = rint(sqrt(T * r));
+  double ch = rint(sqrt(T / r));
+  out_hw[0] = (int64_t)ch;
+  out_hw[1] = (int64_t)cw;
+}
+
+int32_t mae_oracle_rrc_params(int32_t H, int32_t W, float scale_lo, float scale_hi, float ratio_lo,
+                              float ratio_hi, uint64_t seed, uint64_t batch_index, uint32_t sample,
+                              int32_t box[4]) {
+  for (int32_t a = 0; a < 10; ++a) {
+    int64_t hw[2];
+    mae_oracle_rrc_proposal(H, W, scale_lo, scale_hi, ratio_lo, ratio_hi, seed, batch_index,
+                            sample, a, hw);
+    int64_t ch = hw[0], cw = hw[1];
+    if (cw >= 1 && cw <= W && ch >= 1 && ch <= H) {
+      uint64_t ut = draw_u32(seed, batch_index, sample, 2u, (uint32_t)a);
+      uint64_t ul = draw_u32(seed, batch_index, sample, 3u, (uint32_t)a);
+      /* uniform integer on 0 .. H-ch (resp. 0 .. W-cw): floor(u32 * n / 2^32) */
+      int64_t top = (int64_t)((ut * (uint64_t)(H - ch + 1)) >> 32);
+      int64_t left = (int64_t)((ul * (uint64_t)(W - cw + 1)) >> 32);
+      box[0] = (int32_t)top;
+      box[1] = (int32_t)left;
+      box[2] = (int32_t)ch;
+      box[3] = (int32_t)cw;
+      return a + 1;
+    }
+  }
+  /* fallback: centred box, ratio clamped into the range */
+  double R = (double)W / (double)H;
+  int64_t ch, cw;
+  if (R < (double)ratio_lo) {
+    cw = W;
+    ch = (int64_t)rint((double)W / (double)ratio_lo);
+  } else if (R > (double)ratio_hi) {
+    ch = H;
+    cw = (int64_t)rint((double)H * (double)ratio_hi);
+  } else {
+    ch = H;
+    cw = W;
+  }
+  if (ch > H) ch = H;
+  if (cw > W) cw = W;
+  if (ch < 1) ch = 1;
+  if (cw < 1) cw = 1;
+  box[0] = (int32_t)((H - ch) / 2);
+  box[1] = (int32_t)((W - cw) / 2);
+  box[2] = (int32_t)ch;
+  box[3] = (int32_t)cw;
+  return 11;
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * Horizontal flip (App. B, first part of the "Simple" augmentation): a 24-bit uniform compared
+ * with the probability in single precision.
+ * ---------------------------------------------------------------------------------------------- */
+int32_t mae_oracle_flip_bit(uint64_t seed, uint64_t batch_index, uint32_t sample, float flip_p) {
+  uint32_t u24 = draw_u32(seed, batch_index, sample, 4u, 0u) >> 8;
+  float u = (float)u24 * (1.0f / 16777216.0f);
+  return u < flip_p ? 1 : 0;
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * Crop + resize (Sec. 4.1: crop, then resize the cropped region to the output size).  Filter is
+ * not named in the paper; reading: bilinear, sample positions at pixel centres
+ * (src = (o + 1/2) * crop_len / out_size - 1/2), two taps per axis, taps clamped to the crop box,
+ * no prefilter, no rounding back to bytes.  The position is kept as the exact rational n / den.
+ * ---------------------------------------------------------------------------------------------- */
+void mae_oracle_resize_taps(int32_t out_size, int32_t crop_len, int32_t o, int32_t* i0, int32_t* i1,
+                            double* f) {
+  int64_t n = (2 * (int64_t)o + 1) * (int64_t)crop_len - (int64_t)out_size;
+  int64_t den = 2 * (int64_t)out_size;
+  if (n <= 0) {
+    *i0 = 0;
+    *f = 0.0;
+  } else {
+    *i0 = (int32_t)(n / den);
+    *f = (double)(n % den) / (double)den;
+  }
+  *i1 = (*i0 + 1 < crop_len) ? *i0 + 1 : crop_len - 1;
+}
+
+void mae_oracle_crop_resize(const uint8_t* img, int32_t H, int32_t W, const int32_t box[4],
+                            int32_t S, int32_t flip, double* out) {
+  (void)H;
+  int32_t top = box[0], left = box[1], ch = box[2], cw = box[3];
+  for (int32_t oy = 0; oy < S; ++oy) {
+    int32_t y0, y1;
+    double fy;
+    mae_oracle_resize_taps(S, ch, oy, &y0, &y1, &fy);
+    for (int32_t ox = 0; ox < S; ++ox) {
+      /* a flipped output column shows what the mirrored column would have shown */
+      int32_t sx = flip ? (S - 1 - ox) : ox;
+      int32_t x0, x1;
+      double fx;
+      mae_oracle_resize_taps(S, cw, sx, &x0, &x1, &fx);
+      for (int32_t c = 0; c < 3; ++c) {
+        double a00 = img[((int64_t)(top + y0) * W + (left + x0)) * 3 + c];
+        double a01 = img[((int64_t)(top + y0) * W + (left + x1)) * 3 + c];
+        double a10 = img[((int64_t)(top + y1) * W + (left + x0)) * 3 + c];
+        double a11 = img[((int64_t)(top + y1) * W + (left + x1)) * 3 + c];
+        double rt = a00 + fx * (a01 - a00);
+        double rb = a10 + fx * (a11 - a10);
+        out[((int64_t)oy * S + ox) * 3 + c] = rt + fy * (rb - rt);
+      }
+    }
+  }
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * Normalisation (App. B): byte range to [0,1], then mean / standard deviation per channel.
+ * ---------------------------------------------------------------------------------------------- */
+double mae_oracle_normalise(double v, double mean, double std) { return (v / 255.0 - mean) / std; }
+
+/* ------------------------------------------------------------------------------------------------
+ * Patchify (Sec. 3, ViT-B/16).  Patches in row-major order over the grid; inside a patch the
+ * element order is (row, column, channel), which is the order the pixels have in memory.
+ * ---------------------------------------------------------------------------------------------- */
+void mae_oracle_patchify(const double* img, int32_t S, int32_t p, double* out) {
+  int32_t G = S / p;
+  int64_t D = 3 * (int64_t)p * p;
+  for (int32_t y = 0; y < S; ++y)
+    for (int32_t x = 0; x < S; ++x)
+      for (int32_t c = 0; c < 3; ++c) {
+        int64_t l = (int64_t)(y / p) * G + (x / p);
+        int64_t e = ((int64_t)(y % p) * p + (x % p)) * 3 + c;
+        out[l * D + e] = img[((int64_t)y * S + x) * 3 + c];
+      }
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * Random masking (Sec. 2: the encoder drops the masked patches; Sec. 5.3: the masking ratio is
+ * the fraction of patches that is masked).  One noise key per patch; the K patches with the
+ * smallest keys stay visible; equal keys are ordered by patch index.  The rank of a patch is the
+ * number of patches that come before it -- written as that count, with no sorting routine.
+ * ---------------------------------------------------------------------------------------------- */
+int32_t mae_oracle_num_keep(int32_t L, double mask_ratio) {
+  return (int32_t)floor((double)L * (1.0 - mask_ratio));
+}
+
+void mae_oracle_mask(uint64_t seed, uint64_t batch_index, uint32_t sample, int32_t L, int32_t K,
+                     int32_t noise_bits, int32_t* ids_restore, int32_t* ids_keep, uint8_t* mask) {
+  uint32_t* key = (uint32_t*)malloc(sizeof(uint32_t) * (size_t)L);
+  for (int32_t l = 0; l < L; ++l) {
+    uint32_t u = draw_u32(seed, batch_index, sample, 5u, (uint32_t)l);
+    key[l] = (noise_bits >= 32) ? u : (u >> (32 - noise_bits));
+  }
+  for (int32_t l = 0; l < L; ++l) {
+    int32_t rank = 0;
+    for (int32_t j = 0; j < L; ++j)
+      if (key[j] < key[l] || (key[j] == key[l] && j < l)) ++rank;
+    if (ids_restore) ids_restore[l] = rank;
+    if (mask) mask[l] = (rank >= K) ? 1 : 0;
+    if (ids_keep && rank < K) ids_keep[rank] = l;
+  }
+  free(key);
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * Whole input pipeline.
+ * ---------------------------------------------------------------------------------------------- */
+int32_t mae_oracle_prep_batch(const mae_oracle_prep_args* a, int32_t b_begin, int32_t b_end,
+                              float* visible, uint8_t* mask, int32_t* ids_restore,
+                              int32_t* ids_keep, float* target, int32_t* crop) {
+  if (!a || !a->images || !a->offsets || !a->heights || !a->widths) return -1;
+  if (b_begin < 0 || b_end > a->B || b_begin > b_end) return -1;
+  int32_t S = a->out_size, p = a->patch, K = a->num_keep;
+  if (S < 1 || p < 1 || S % p != 0) return -1;
+  int32_t G = S / p, L = G * G;
+  int64_t D = 3 * (int64_t)p * p;
+  if (K < 1 || K > L) return -1;
+  if (a->noise_bits < 1 || a->noise_bits > 32) return -1;
+
+  int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int32_t b = b_begin; b < b_end; ++b) {
+    int64_t n = b - b_begin;
+    int32_t H = a->heights[b], W = a->widths[b];
+    const uint8_t* img = a->images + a->offsets[b];
+
+    int32_t box[4];
+    mae_oracle_rrc_params(H, W, a->scale_lo, a->scale_hi, a->ratio_lo, a->ratio_hi, a->seed,
+                          a->batch_index, (uint32_t)b, box);
+    int32_t flip = mae_oracle_flip_bit(a->seed, a->batch_index, (uint32_t)b, a->flip_p);
+    if (crop) {
+      memcpy(crop + n * 5, box, sizeof(box));
+      crop[n * 5 + 4] = flip;
+    }
+
+    int32_t* restore = (int32_t*)malloc(sizeof(int32_t) * (size_t)L);
+    int32_t* keep = (int32_t*)malloc(sizeof(int32_t) * (size_t)K);
+    uint8_t* msk = (uint8_t*)malloc((size_t)L);
+    mae_oracle_mask(a->seed, a->batch_index, (uint32_t)b, L, K, a->noise_bits, restore, keep, msk);
+    if (ids_restore) memcpy(ids_restore + n * L, restore, sizeof(int32_t) * (size_t)L);
+    if (ids_keep) memcpy(ids_keep + n * K, keep, sizeof(int32_t) * (size_t)K);
+    if (mask) memcpy(mask + n * L, msk, (size_t)L);
+
+    if (visible || target) {
+      double* resized = (double*)malloc(sizeof(double) * (size_t)S * S * 3);
+      double* patches = (double*)malloc(sizeof(double) * (size_t)L * D);
+      if (!resized || !patches) {
+        failed = 1;
+      } else {
+        mae_oracle_crop_resize(img, H, W, box, S, flip, resized);
+        for (int64_t i = 0; i < (int64_t)S * S; ++i)
+          for (int32_t c = 0; c < 3; ++c)
+            resized[i * 3 + c] =
+                mae_oracle_normalise(resized[i * 3 + c], (double)a->mean[c], (double)a->std[c]);
+        mae_oracle_patchify(resized, S, p, patches);
+        if (target)
+          for (int64_t i = 0; i < (int64_t)L * D; ++i) target[n * L * D + i] = (float)patches[i];
+        if (visible)
+          for (int32_t r = 0; r < K; ++r)
+            for (int64_t e = 0; e < D; ++e)
+              visible[(n * K + r) * D + e] = (float)patches[(int64_t)keep[r] * D + e];
+      }
+      free(resized);
+      free(patches);
+    }
+    free(restore);
+    free(keep);
+    free(msk);
+  }
+  return failed ? -1 : 0;
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * Normalised-pixel reconstruction loss (Sec. 3 adopts the official MAE objective; its formula is
+ * not printed in the paper).  For every patch row t[0..D): mu = mean, var = sum (t-mu)^2 / (D-1),
+ * that = (t - mu) / sqrt(var + eps).  Row loss = mean over the D elements of (pred - that)^2.
+ * loss = sum of the row losses of masked rows / M.  d loss / d pred = 2 (pred - that) / (D M) on
+ * masked rows, zero elsewhere; multiplied by the upstream factor grad_scale.
+ * ---------------------------------------------------------------------------------------------- */
+int32_t mae_oracle_normpix_loss(int32_t B, int32_t L, int32_t D, const float* pred,
+                                const float* target, const uint8_t* mask, int64_t num_masked,
+                                double eps, double grad_scale, double* loss_out, float* grad,
+                                double* that) {
+  if (B < 1 || L < 1 || D < 2 || !pred || !target || !mask || !loss_out || num_masked < 1)
+    return -1;
+  int64_t rows = (int64_t)B * L;
+  double M = (double)num_masked;
+  double total = 0.0;
+  for (int64_t row = 0; row < rows; ++row) {
+    const float* t = target + row * D;
+    const float* q = pred + row * D;
+    double mu = 0.0;
+    for (int32_t e = 0; e < D; ++e) mu += (double)t[e];
+    mu /= (double)D;
+    double ss = 0.0;
+    for (int32_t e = 0; e < D; ++e) ss += ((double)t[e] - mu) * ((double)t[e] - mu);
+    double var = ss / (double)(D - 1);
+    double sd = sqrt(var + eps);
+    double row_loss = 0.0;
+    for (int32_t e = 0; e < D; ++e) {
+      double th = ((double)t[e] - mu) / sd;
+      double diff = (double)q[e] - th;
+      if (that) that[row * D + e] = th;
+      row_loss += diff * diff;
+      if (grad)
+        grad[row * D + e] =
+            mask[row] ? (float)(grad_scale * 2.0 * diff / ((double)D * M)) : 0.0f;
+    }
+    row_loss /= (double)D;
+    if (mask[row]) total += row_loss;
+  }
+  *loss_out = total / M;
+  return 0;
+}
+
+int32_t mae_oracle_threads(void) {
+#ifdef _OPENMP
+  return (int32_t)omp_get_max_threads();
+#else
+  return 1;
+#endif
+}

@@ -1,0 +1,119 @@
+/*
+ * CPU oracle for the masked-autoencoder input pipeline (DailyMAE, arXiv 2404.00509).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This is a slow, plain, scalar implementation whose single purpose is
+ * to say what the GPU library must compute.  It shares no source, header, table or helper with the
+ * HIP path, and nothing in the product path may call it.  Every pointer is a HOST pointer.
+ *
+ * Steps, in the order the paper's loader and model apply them:
+ *   RandomResizedCrop parameters (Sec. 5.1: area scale uniform, aspect ratio log-uniform, crop a
+ *   region then resize it to the output size), the crop + resize itself (Sec. 4.1), the "Simple"
+ *   augmentation = horizontal flip + tensor conversion + mean/std normalisation (App. B), the
+ *   ViT patch split (Sec. 3, Sec. 5), random masking at a masking ratio with the encoder seeing
+ *   only the visible patches (Sec. 2, Sec. 5.3 "Masking Ratio"), and the reconstruction loss of
+ *   the official MAE recipe the paper adopts (Sec. 3): mean squared error against per-patch
+ *   normalised pixels on the masked patches, with its gradient.
+ *
+ * The paper leaves rounding, retry, tie-break and random-number details open; the readings taken
+ * here are written next to each function.
+ *
+ * Every function is pinned by tests that do not depend on this file's own arithmetic (closed
+ * forms, printed vectors, brute force, library cross-checks); none is "parity unpinned".
+ */
+#ifndef MAE_ORACLE_H
+#define MAE_ORACLE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- counter-based random numbers (SplitMix64 output function, Steele/Lea/Flood 2014) -------- */
+uint64_t mae_oracle_mix64(uint64_t z);
+/* (w+1)-th output of a SplitMix64 stream whose state is derived from (seed, batch_index);
+ * w = sample<<32 | stream<<24 | ctr.  Streams: 0 scale, 1 log-ratio, 2 top, 3 left (ctr =
+ * attempt), 4 flip, 5 mask noise (ctr = patch index). */
+uint64_t mae_oracle_draw(uint64_t seed, uint64_t batch_index, uint32_t sample, uint32_t stream,
+                         uint32_t ctr);
+
+/* ---- RandomResizedCrop parameters (Sec. 5.1) -------------------------------------------------- */
+/* exp(x) as the degree-13 Taylor polynomial in Horner form, fp64, no fused operations. */
+double mae_oracle_exp_poly(double x);
+/* Proposal of attempt `attempt` (0..9) before the accept test: out = {ch, cw}. */
+void mae_oracle_rrc_proposal(int32_t H, int32_t W, float scale_lo, float scale_hi, float ratio_lo,
+                             float ratio_hi, uint64_t seed, uint64_t batch_index, uint32_t sample,
+                             int32_t attempt, int64_t out_hw[2]);
+/* Accepted crop box: box = {top, left, ch, cw}.  Returns the number of attempts used (1..10), or
+ * 11 when all ten were rejected and the centred fallback box was taken. */
+int32_t mae_oracle_rrc_params(int32_t H, int32_t W, float scale_lo, float scale_hi, float ratio_lo,
+                              float ratio_hi, uint64_t seed, uint64_t batch_index, uint32_t sample,
+                              int32_t box[4]);
+
+/* ---- flip (App. B) ---------------------------------------------------------------------------- */
+int32_t mae_oracle_flip_bit(uint64_t seed, uint64_t batch_index, uint32_t sample, float flip_p);
+
+/* ---- crop + bilinear resize (Sec. 4.1, Sec. 5.1) ---------------------------------------------- */
+/* Source taps of output index o when `crop_len` source pixels are resized to `out_size`:
+ * half-pixel centres, two taps, clamped to the crop.  f is the exact rational weight of tap i1. */
+void mae_oracle_resize_taps(int32_t out_size, int32_t crop_len, int32_t o, int32_t* i0, int32_t* i1,
+                            double* f);
+/* img: H x W x 3 uint8 (rows tightly packed).  out: S x S x 3 doubles in pixel units (0..255),
+ * row-major HWC, already flipped when flip != 0. */
+void mae_oracle_crop_resize(const uint8_t* img, int32_t H, int32_t W, const int32_t box[4],
+                            int32_t S, int32_t flip, double* out);
+
+/* ---- normalise (App. B) ----------------------------------------------------------------------- */
+double mae_oracle_normalise(double v, double mean, double std);
+
+/* ---- patchify (Sec. 3: ViT-B/16 patches) ------------------------------------------------------ */
+/* img: S x S x 3 doubles (HWC).  out: L x D doubles, L = (S/p)^2 row-major over patches,
+ * D = 3 p^2 with element order (row in patch, column in patch, channel). */
+void mae_oracle_patchify(const double* img, int32_t S, int32_t p, double* out);
+
+/* ---- random masking (Sec. 2, Sec. 5.3) -------------------------------------------------------- */
+/* floor(L * (1 - mask_ratio)) evaluated in fp64. */
+int32_t mae_oracle_num_keep(int32_t L, double mask_ratio);
+/* ids_restore[L], ids_keep[K], mask[L] (1 = masked) for one sample.  Rank by counting. */
+void mae_oracle_mask(uint64_t seed, uint64_t batch_index, uint32_t sample, int32_t L, int32_t K,
+                     int32_t noise_bits, int32_t* ids_restore, int32_t* ids_keep, uint8_t* mask);
+
+/* ---- the whole input pipeline for samples [b_begin, b_end) of a batch ------------------------- */
+typedef struct {
+  int32_t B;
+  const uint8_t* images;   /* packed HWC uint8; image b starts at images + offsets[b] */
+  const int64_t* offsets;  /* [B] */
+  const int32_t* heights;  /* [B] */
+  const int32_t* widths;   /* [B] */
+  int32_t out_size, patch, num_keep;
+  float scale_lo, scale_hi, ratio_lo, ratio_hi, flip_p;
+  float mean[3], std[3];
+  uint64_t seed, batch_index;
+  int32_t noise_bits;
+} mae_oracle_prep_args;
+
+/* Outputs are indexed by (b - b_begin); any may be NULL.  The hash is keyed by the global sample
+ * index b, so a slice gives the same values as the full batch.
+ *   visible [n,K,D] fp32, target [n,L,D] fp32 (fp64 result rounded once), mask [n,L] uint8,
+ *   ids_restore [n,L], ids_keep [n,K], crop [n,5] = top,left,ch,cw,flip.
+ * Returns 0, or -1 on an invalid argument. */
+int32_t mae_oracle_prep_batch(const mae_oracle_prep_args* a, int32_t b_begin, int32_t b_end,
+                              float* visible, uint8_t* mask, int32_t* ids_restore,
+                              int32_t* ids_keep, float* target, int32_t* crop);
+
+/* ---- normalised-pixel loss and gradient (Sec. 3: official MAE objective) ---------------------- */
+/* pred, target: [B,L,D] fp32 (target NOT yet per-patch normalised); mask [B,L]; num_masked = the
+ * divisor M (masked patches of the whole batch).  loss_out: one double.  grad (nullable): [B,L,D]
+ * fp32, the fp64 gradient rounded once; rows with mask 0 are +0.  that (nullable): [B,L,D]
+ * doubles, the per-patch normalised target.  Returns 0 or -1. */
+int32_t mae_oracle_normpix_loss(int32_t B, int32_t L, int32_t D, const float* pred,
+                                const float* target, const uint8_t* mask, int64_t num_masked,
+                                double eps, double grad_scale, double* loss_out, float* grad,
+                                double* that);
+
+int32_t mae_oracle_threads(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,529 @@
+"""Pins for the CPU oracle: closed forms, printed vectors, invariants, brute force and library
+cross-checks.  None of these tests touches the GPU library; each is chosen so that a plausible
+mistake in one step of the oracle (dropped term, wrong sign or index, transposed operand) fails.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2404_00509_amd import synth
+
+SCALE = (0.2, 1.0)
+RATIO = (3.0 / 4.0, 4.0 / 3.0)
+
+
+# ------------------------------------------------------------------------------------ hash
+def test_hash_known_answers(golden):
+    gold = 0x9E3779B97F4A7C15
+    for row in golden("hash_vectors.txt"):
+        if row[0] == "splitmix_seed0":
+            n = int(row[1])
+            assert oracle.mix64((n * gold) & (2**64 - 1)) == int(row[2], 16)
+        elif row[0] == "mix64":
+            assert oracle.mix64(int(row[1], 16)) == int(row[2], 16)
+        elif row[0] == "draw":
+            args = [int(v) for v in row[1:6]]
+            assert oracle.draw(*args) == int(row[6], 16), row
+        else:
+            raise AssertionError(row)
+
+
+def test_hash_fields_do_not_alias():
+    base = oracle.draw(3, 4, 5, 2, 7)
+    others = {oracle.draw(4, 3, 5, 2, 7), oracle.draw(3, 4, 2, 5, 7), oracle.draw(3, 4, 5, 7, 2),
+              oracle.draw(3, 4, 7, 2, 5), oracle.draw(3, 5, 5, 2, 7), oracle.draw(3, 4, 5, 2, 8)}
+    assert base not in others and len(others) == 6
+
+
+def test_hash_uniformity():
+    u = np.array([oracle.draw(0, 0, s, 5, l) >> 32 for s in range(64) for l in range(196)],
+                 dtype=np.float64) / 2.0**32
+    assert abs(u.mean() - 0.5) < 0.01
+    assert abs(u.var() - 1.0 / 12.0) < 0.005
+    hist, _ = np.histogram(u, bins=8, range=(0, 1))
+    assert hist.min() > 0.8 * len(u) / 8
+
+
+# ------------------------------------------------------------------------------------ exp
+def test_exp_polynomial_matches_libm():
+    a = math.log(4.0 / 3.0)                  # the aspect-ratio range the paper's recipe uses
+    for x in np.linspace(-a, a, 2001):
+        e, ref = oracle.exp_poly(float(x)), math.exp(float(x))
+        assert abs(e - ref) <= 4 * math.ulp(ref)
+    for x in np.linspace(-0.5, 0.5, 501):    # widest range accepted: truncation error x^14/14!
+        e, ref = oracle.exp_poly(float(x)), math.exp(float(x))
+        assert abs(e - ref) <= 2e-15 * ref
+    assert oracle.exp_poly(0.0) == 1.0
+
+
+# ------------------------------------------------------------------------------------ RRC
+def test_rrc_full_image_when_scale_and_ratio_are_one():
+    for n in (1, 7, 112, 224, 255):
+        box, attempts = oracle.rrc_params(n, n, (1.0, 1.0), (1.0, 1.0), 9, 3, 11)
+        assert box == (0, 0, n, n) and attempts == 1
+
+
+def test_rrc_fallback_is_centred_square():
+    # area fraction 1 with ratio 1 proposes a sqrt(H*W) square, which never fits when H != W
+    box, attempts = oracle.rrc_params(100, 200, (1.0, 1.0), (1.0, 1.0), 0, 0, 0)
+    assert attempts == 11 and box == (0, 50, 100, 100)
+    box, attempts = oracle.rrc_params(200, 100, (1.0, 1.0), (1.0, 1.0), 0, 0, 0)
+    assert attempts == 11 and box == (50, 0, 100, 100)
+    # ratio range that excludes the image's own ratio on either side
+    box, attempts = oracle.rrc_params(100, 300, (1.0, 1.0), (0.75, 4.0 / 3.0), 0, 0, 0)
+    assert attempts == 11 and box == (0, (300 - 133) // 2, 100, 133)     # cw = rint(100 * 4/3)
+    box, attempts = oracle.rrc_params(300, 100, (1.0, 1.0), (0.75, 4.0 / 3.0), 0, 0, 0)
+    assert attempts == 11 and box == ((300 - 133) // 2, 0, 133, 100)     # ch = rint(100 / 0.75)
+    # image ratio inside the range -> whole image
+    box, attempts = oracle.rrc_params(100, 110, (1.0, 1.0), (0.75, 4.0 / 3.0), 0, 0, 5)
+    if attempts == 11:
+        assert box == (0, 0, 100, 110)
+
+
+def test_rrc_fixed_ratio_orientation():
+    # ratio is width / height: a 4:3 proposal at half the area of a 1000 x 1000 image
+    r = 4.0 / 3.0
+    ch, cw = oracle.rrc_proposal(1000, 1000, (0.5, 0.5), (r, r), 1, 2, 3, 0)
+    assert cw == round(math.sqrt(500000.0 * r)) == 816
+    assert ch == round(math.sqrt(500000.0 / r)) == 612
+    ch, cw = oracle.rrc_proposal(1000, 1000, (0.5, 0.5), (0.75, 0.75), 1, 2, 3, 4)
+    assert (ch, cw) == (816, 612)
+
+
+def test_rrc_invariants():
+    rng = np.random.default_rng(5)
+    fallbacks = 0
+    for s in range(3000):
+        H, W = (int(v) for v in rng.integers(1, 300, size=2))
+        (top, left, ch, cw), attempts = oracle.rrc_params(H, W, SCALE, RATIO, 7, s % 5, s)
+        assert 1 <= ch <= H and 1 <= cw <= W
+        assert 0 <= top <= H - ch and 0 <= left <= W - cw
+        assert 1 <= attempts <= 11
+        fallbacks += attempts == 11
+    assert 0 < fallbacks < 1500          # very elongated images do reach the fallback
+    # images shaped like the max-side-256 workload: a stand-alone simulation of the sampling law
+    # (different generator) gave 1.37 attempts on average and a fallback rate of a few 1e-5
+    h, w = synth.image_shapes("gradient", 4000, seed=1)
+    tries = np.array([oracle.rrc_params(int(h[s]), int(w[s]), SCALE, RATIO, 0, 0, s)[1]
+                      for s in range(4000)])
+    assert (tries == 11).sum() <= 2
+    assert abs(tries[tries < 11].mean() - 1.37) < 0.05
+
+
+def test_rrc_proposal_statistics_match_eq2(golden):
+    H = W = 6000      # large, so that rounding the sides to integers is negligible
+    n = 20000
+    for lo, hi, e_sqrt, e_area in ((float(r[0]), float(r[1]), float(r[2]), float(r[3]))
+                                   for r in golden("rrc_expectations.txt")):
+        frac, logr = np.empty(n), np.empty(n)
+        for s in range(n):
+            ch, cw = oracle.rrc_proposal(H, W, (lo, hi), RATIO, 123, 0, s, 0)
+            frac[s] = ch * cw / float(H * W)
+            logr[s] = math.log(cw / ch)
+        assert abs(np.sqrt(frac).mean() - e_sqrt) < 0.004
+        assert abs(frac.mean() - e_area) < 0.006
+        assert frac.min() >= lo - 1e-3 and frac.max() <= hi + 1e-3
+        assert abs(logr.mean()) < 0.006                      # log-uniform, symmetric range
+        assert abs(logr.max() - math.log(4 / 3)) < 1e-3 and abs(logr.min() + math.log(4 / 3)) < 1e-3
+        # uniform in log space: variance of U(-a, a) is a^2 / 3
+        assert abs(logr.var() - math.log(4 / 3) ** 2 / 3) < 0.002
+
+
+def test_rrc_offsets_are_uniform_over_positions_that_fit():
+    # fixed crop size (scale and ratio pinned) in a larger image: H - ch + 1 = 3 row positions
+    tops, lefts = [], []
+    for s in range(3000):
+        (top, left, ch, cw), attempts = oracle.rrc_params(10, 12, (0.5333334, 0.5333334),
+                                                          (1.0, 1.0), 1, 0, s)
+        assert attempts == 1 and (ch, cw) == (8, 8)
+        tops.append(top)
+        lefts.append(left)
+    for vals, npos in ((tops, 3), (lefts, 5)):
+        counts = np.bincount(vals, minlength=npos)
+        assert len(counts) == npos
+        assert np.all(np.abs(counts / 3000.0 - 1.0 / npos) < 0.04)
+
+
+def test_rrc_proposal_recomputed_with_libm():
+    # independent route: Python ints for the hash, libm exp instead of the polynomial
+    mask = 2**64 - 1
+    gold = 0x9E3779B97F4A7C15
+
+    def mix(z):
+        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & mask
+        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & mask
+        return z ^ (z >> 31)
+
+    def unit(seed, batch, sample, stream, ctr):
+        k1 = mix((mix((seed + gold) & mask) + gold * (batch + 1)) & mask)
+        w = (sample << 32) | (stream << 24) | ctr
+        return (mix((k1 + gold * (w + 1)) & mask) >> 11) / 2.0**53
+
+    lo, hi = np.float32(SCALE[0]), np.float32(SCALE[1])
+    rl, rh = np.float32(RATIO[0]), np.float32(RATIO[1])
+    for s in range(500):
+        H, W = 200 + s % 57, 256
+        a = s % 3
+        sc = float(lo) + (float(hi) - float(lo)) * unit(5, 2, s, 0, a)
+        x = math.log(float(rl)) + (math.log(float(rh)) - math.log(float(rl))) * unit(5, 2, s, 1, a)
+        T = float(H * W) * sc
+        ref = (round(math.sqrt(T / math.exp(x))), round(math.sqrt(T * math.exp(x))))
+        assert oracle.rrc_proposal(H, W, SCALE, RATIO, 5, 2, s, a) == ref
+
+
+# ------------------------------------------------------------------------------------ flip
+def test_flip_probability_extremes_and_rate():
+    bits = [oracle.flip_bit(0, 0, s, 0.5) for s in range(4096)]
+    assert abs(np.mean(bits) - 0.5) < 0.03
+    assert all(oracle.flip_bit(0, 0, s, 0.0) == 0 for s in range(256))
+    assert all(oracle.flip_bit(0, 0, s, 1.0) == 1 for s in range(256))
+    # threshold semantics: u < p with u = top 24 bits of the stream-4 draw
+    for s in range(64):
+        u = ((oracle.draw(3, 1, s, 4, 0) >> 32) >> 8) / 2.0**24
+        assert oracle.flip_bit(3, 1, s, 0.3) == int(u < np.float32(0.3))
+
+
+def test_flip_twice_is_identity_and_mirrors_columns():
+    rng = np.random.default_rng(0)
+    img = rng.integers(0, 256, size=(37, 41, 3), dtype=np.uint8)
+    box = (3, 5, 20, 30)
+    a = oracle.crop_resize(img, box, 16, 0)
+    f = oracle.crop_resize(img, box, 16, 1)
+    assert np.array_equal(f, a[:, ::-1, :])
+    assert np.array_equal(f[:, ::-1, :], a)
+    # mirroring the source image and its box instead gives the same picture (exact arithmetic)
+    mirrored = np.ascontiguousarray(img[:, ::-1, :])
+    mbox = (3, 41 - 5 - 30, 20, 30)
+    np.testing.assert_allclose(oracle.crop_resize(mirrored, mbox, 16, 0), f, rtol=0, atol=1e-9)
+
+
+# ------------------------------------------------------------------------------------ resize
+def test_resize_taps_printed_example():
+    # two source pixels resized to four: positions -0.25, 0.25, 0.75, 1.25
+    taps = [oracle.resize_taps(4, 2, o) for o in range(4)]
+    assert taps == [(0, 1, 0.0), (0, 1, 0.25), (0, 1, 0.75), (1, 1, 0.25)]
+    img = np.array([[[0, 0, 0], [255, 255, 255]]], np.uint8)
+    out = oracle.crop_resize(img, (0, 0, 1, 2), 4, 0)
+    np.testing.assert_array_equal(out[0, :, 0], [0.0, 63.75, 191.25, 255.0])
+    np.testing.assert_array_equal(out[3, :, 2], [0.0, 63.75, 191.25, 255.0])
+
+
+def test_resize_identity_constant_and_single_pixel():
+    rng = np.random.default_rng(1)
+    img = rng.integers(0, 256, size=(48, 48, 3), dtype=np.uint8)
+    np.testing.assert_array_equal(oracle.crop_resize(img, (0, 0, 48, 48), 48, 0), img)
+    np.testing.assert_array_equal(oracle.crop_resize(img, (5, 9, 32, 32), 32, 0),
+                                  img[5:37, 9:41])
+    const = np.full((20, 30, 3), 77, np.uint8)
+    assert np.all(oracle.crop_resize(const, (2, 3, 11, 17), 24, 1) == 77.0)
+    one = oracle.crop_resize(img, (7, 8, 1, 1), 8, 0)
+    assert np.all(one == img[7, 8].astype(np.float64)[None, None, :])
+    col = oracle.crop_resize(img, (7, 8, 6, 1), 6, 0)      # one column wide, identity in y
+    np.testing.assert_array_equal(col, np.repeat(img[7:13, 8:9].astype(np.float64), 6, axis=1))
+
+
+@pytest.mark.parametrize("box,S", [((3, 4, 20, 30), 16), ((3, 4, 10, 12), 16), ((0, 0, 30, 40), 7)])
+def test_resize_reproduces_affine_ramps(box, S):
+    H, W = 30, 40
+    ys, xs = np.mgrid[0:H, 0:W]
+    coef = [(2, 3, 5), (1, 4, 0), (3, 1, 20)]
+    img = np.stack([a * xs + b * ys + c for a, b, c in coef], axis=-1).astype(np.uint8)
+    top, left, ch, cw = box
+    out = oracle.crop_resize(img, box, S, 0)
+    sx = ((2 * np.arange(S) + 1) * cw - S) / (2.0 * S)
+    sy = ((2 * np.arange(S) + 1) * ch - S) / (2.0 * S)
+    sx = np.clip(sx, 0, cw - 1) + left          # edge taps replicate the border of the crop
+    sy = np.clip(sy, 0, ch - 1) + top
+    for c, (a, b, k) in enumerate(coef):
+        ref = a * sx[None, :] + b * sy[:, None] + k
+        np.testing.assert_allclose(out[:, :, c], ref, rtol=0, atol=1e-10)
+
+
+def test_resize_clamps_to_crop_box_not_image():
+    img = np.zeros((10, 10, 3), np.uint8)
+    img[:, :5] = 200            # left half bright; crop the dark right half and upscale
+    out = oracle.crop_resize(img, (0, 5, 10, 5), 20, 0)
+    assert np.all(out == 0.0)
+
+
+@pytest.mark.parametrize("S", [7, 16, 31])
+def test_resize_against_library_bilinear(S):
+    rng = np.random.default_rng(S)
+    img = rng.integers(0, 256, size=(23, 29, 3), dtype=np.uint8)
+    box = (2, 3, 14, 19)
+    top, left, ch, cw = box
+    crop = torch.from_numpy(img[top:top + ch, left:left + cw].astype(np.float64))
+    ref = torch.nn.functional.interpolate(crop.permute(2, 0, 1)[None], size=(S, S),
+                                          mode="bilinear", align_corners=False, antialias=False)
+    ref = ref[0].permute(1, 2, 0).numpy()
+    np.testing.assert_allclose(oracle.crop_resize(img, box, S, 0), ref, rtol=0, atol=1e-9)
+
+
+# ------------------------------------------------------------------------------------ normalise
+def test_normalise_end_points():
+    for m, s in zip(oracle.IMAGENET_MEAN, oracle.IMAGENET_STD):
+        assert oracle.normalise(0.0, m, s) == pytest.approx(-m / s, abs=1e-15)
+        assert oracle.normalise(255.0, m, s) == pytest.approx((1.0 - m) / s, abs=1e-15)
+        assert oracle.normalise(255.0 * m, m, s) == pytest.approx(0.0, abs=1e-15)
+        d = oracle.normalise(128.0, m, s) - oracle.normalise(127.0, m, s)
+        assert d == pytest.approx(1.0 / (255.0 * s), rel=1e-12)
+
+
+# ------------------------------------------------------------------------------------ patchify
+@pytest.mark.parametrize("S,p", [(32, 16), (28, 14), (12, 3)])
+def test_patchify_layout(S, p):
+    rng = np.random.default_rng(2)
+    img = rng.standard_normal((S, S, 3))
+    G = S // p
+    out = oracle.patchify(img, p)
+    ref = img.reshape(G, p, G, p, 3).transpose(0, 2, 1, 3, 4).reshape(G * G, p * p * 3)
+    np.testing.assert_array_equal(out, ref)
+    np.testing.assert_array_equal(out[0, 0:3], img[0, 0])
+    assert out[1, 0] == img[0, p, 0] and out[G, 0] == img[p, 0, 0]
+    assert out[0, 3] == img[0, 1, 0] and out[0, 3 * p] == img[1, 0, 0]
+    back = out.reshape(G, G, p, p, 3).transpose(0, 2, 1, 3, 4).reshape(S, S, 3)
+    np.testing.assert_array_equal(back, img)
+
+
+# ------------------------------------------------------------------------------------ masking
+def test_num_keep_values():
+    assert [oracle.num_keep(L, 0.75) for L in (49, 100, 144, 196, 256)] == [12, 25, 36, 49, 64]
+    assert oracle.num_keep(100, 0.8) == 19           # 100 * (1 - 0.8) is just below 20 in fp64
+    assert oracle.num_keep(196, 0.8) == 39 and oracle.num_keep(196, 0.85) == 29
+    assert oracle.num_keep(196, 0.5) == 98 and oracle.num_keep(144, 0.66) == 48
+
+
+def test_masking_worked_example(golden):
+    rows = {r[0]: [int(v) for v in r[1:]] for r in golden("masking_example.txt")}
+    ids_restore, ids_keep, m = oracle.mask(0, 0, 0, 16, 4)
+    assert list(ids_restore) == rows["ids_restore"]
+    assert list(ids_keep) == rows["ids_shuffle"][:4]
+    assert sorted(np.flatnonzero(m == 0)) == rows["kept"]
+    assert list(np.argsort(ids_restore)) == rows["ids_shuffle"]
+
+
+@pytest.mark.parametrize("L,K", [(49, 12), (100, 25), (144, 36), (196, 49), (256, 64), (196, 29),
+                                 (5, 5), (7, 1)])
+def test_masking_invariants_and_library_argsort(L, K):
+    for sample in range(20):
+        for bits in (32, 8, 3, 1):
+            ids_restore, ids_keep, m = oracle.mask(11, 2, sample, L, K, bits)
+            assert sorted(ids_restore) == list(range(L))
+            assert int((m == 0).sum()) == K
+            assert np.array_equal(m, (ids_restore >= K).astype(np.uint8))
+            key = np.array([(oracle.draw(11, 2, sample, 5, l) >> 32) >> (32 - bits)
+                            for l in range(L)], dtype=np.uint64)
+            shuffle = np.argsort((key << np.uint64(32)) | np.arange(L, dtype=np.uint64),
+                                 kind="stable")
+            assert np.array_equal(ids_keep, shuffle[:K])
+            assert np.array_equal(ids_restore[shuffle], np.arange(L))     # restore inverts shuffle
+            assert np.array_equal(np.argsort(key, kind="stable"), shuffle)
+
+
+def test_masking_all_keys_equal_keeps_first_patches():
+    # one noise bit, and a sample whose first draws agree: emulate "all equal" through the
+    # definition instead -- with ties everywhere the order must be the index order
+    L, K = 32, 8
+    for sample in range(50):
+        ids_restore, ids_keep, m = oracle.mask(0, 0, sample, L, K, 1)
+        key = np.array([(oracle.draw(0, 0, sample, 5, l) >> 63) for l in range(L)])
+        zeros, ones = np.flatnonzero(key == 0), np.flatnonzero(key == 1)
+        assert np.array_equal(np.argsort(ids_restore), np.concatenate([zeros, ones]))
+
+
+def test_masking_keep_frequency_is_uniform():
+    L, K, n = 49, 12, 4000
+    kept = np.zeros(L)
+    for sample in range(n):
+        _, _, m = oracle.mask(1, 0, sample, L, K)
+        kept += (m == 0)
+    assert np.all(np.abs(kept / n - K / L) < 0.035)
+
+
+# ------------------------------------------------------------------------------------ pipeline
+def _identity_batch(S, B=3):
+    rng = np.random.default_rng(3)
+    imgs = rng.integers(0, 256, size=(B, S, S, 3), dtype=np.uint8)
+    offsets = np.arange(B, dtype=np.int64) * S * S * 3
+    hw = np.full(B, S, np.int32)
+    return imgs, offsets, hw
+
+
+def test_prep_identity_crop_returns_normalised_input():
+    S, p = 32, 16
+    imgs, offsets, hw = _identity_batch(S)
+    out = oracle.prep_batch(imgs.reshape(-1), offsets, hw, hw, out_size=S, patch=p, num_keep=1,
+                            scale=(1.0, 1.0), ratio=(1.0, 1.0), flip_p=0.0)
+    mean = np.array(oracle.IMAGENET_MEAN, np.float32).astype(np.float64)
+    std = np.array(oracle.IMAGENET_STD, np.float32).astype(np.float64)
+    for b in range(imgs.shape[0]):
+        norm = (imgs[b].astype(np.float64) / 255.0 - mean) / std
+        ref = norm.reshape(2, p, 2, p, 3).transpose(0, 2, 1, 3, 4).reshape(4, 768)
+        np.testing.assert_array_equal(out["target"][b], ref.astype(np.float32))
+        assert tuple(out["crop"][b]) == (0, 0, S, S, 0)
+    flipped = oracle.prep_batch(imgs.reshape(-1), offsets, hw, hw, out_size=S, patch=p,
+                                num_keep=1, scale=(1.0, 1.0), ratio=(1.0, 1.0), flip_p=1.0)
+    for b in range(imgs.shape[0]):
+        norm = (imgs[b, :, ::-1].astype(np.float64) / 255.0 - mean) / std
+        ref = norm.reshape(2, p, 2, p, 3).transpose(0, 2, 1, 3, 4).reshape(4, 768)
+        np.testing.assert_array_equal(flipped["target"][b], ref.astype(np.float32))
+
+
+def test_prep_gather_and_slicing():
+    wl = synth.WORKLOADS["c1"]
+    images, offsets, heights, widths = synth.make_images(wl.kind, 12, seed=0)
+    K = oracle.num_keep(wl.L, wl.mask_ratio)
+    kw = dict(out_size=wl.out_size, patch=wl.patch, num_keep=K, seed=4, batch_index=9)
+    full = oracle.prep_batch(images, offsets, heights, widths, **kw)
+    assert full["visible"].shape == (12, K, wl.D) and full["target"].shape == (12, wl.L, wl.D)
+    for b in range(12):
+        np.testing.assert_array_equal(full["visible"][b], full["target"][b][full["ids_keep"][b]])
+        scattered = np.zeros_like(full["target"][b])
+        scattered[full["ids_keep"][b]] = full["visible"][b]
+        kept_rows = full["mask"][b] == 0
+        np.testing.assert_array_equal(scattered[kept_rows], full["target"][b][kept_rows])
+        box, _ = oracle.rrc_params(int(heights[b]), int(widths[b]), SCALE, RATIO, 4, 9, b)
+        assert tuple(full["crop"][b][:4]) == box
+        assert full["crop"][b][4] == oracle.flip_bit(4, 9, b, 0.5)
+    part = oracle.prep_batch(images, offsets, heights, widths, b_begin=5, b_end=8, **kw)
+    for k in full:
+        np.testing.assert_array_equal(part[k], full[k][5:8])
+    other = oracle.prep_batch(images, offsets, heights, widths,
+                              **{**kw, "batch_index": 10})
+    assert not np.array_equal(other["ids_restore"], full["ids_restore"])
+
+
+def test_prep_constant_image_gives_constant_target():
+    S, p = 28, 14
+    img = np.full((40, 50, 3), 255, np.uint8)
+    out = oracle.prep_batch(img.reshape(-1), np.zeros(1, np.int64), np.array([40], np.int32),
+                            np.array([50], np.int32), out_size=S, patch=p, num_keep=1)
+    for c in range(3):
+        ref = np.float32((1.0 - float(np.float32(oracle.IMAGENET_MEAN[c])))
+                         / float(np.float32(oracle.IMAGENET_STD[c])))
+        assert np.all(out["target"][0][:, c::3] == ref)
+
+
+# ------------------------------------------------------------------------------------ loss
+def _loss_inputs(B=2, L=4, D=12, seed=0):
+    rng = np.random.default_rng(seed)
+    target = (rng.integers(-4096, 4096, size=(B, L, D)) / 1024.0).astype(np.float32)
+    pred = (rng.integers(-4096, 4096, size=(B, L, D)) / 1024.0).astype(np.float32)
+    mask = np.array([[1, 0, 1, 1], [0, 1, 0, 0]], np.uint8)[:B, :L]
+    return pred, target, mask
+
+
+def test_loss_normalised_target_statistics():
+    pred, target, mask = _loss_inputs(D=48)
+    eps = 1e-6
+    _, _, that = oracle.normpix_loss(pred, target, mask, eps=eps, want_that=True)
+    var = target.astype(np.float64).var(axis=-1, ddof=1)
+    np.testing.assert_allclose(that.mean(axis=-1), 0.0, atol=1e-12)
+    np.testing.assert_allclose(that.var(axis=-1, ddof=1), var / (var + eps), rtol=1e-12)
+    mu = target.astype(np.float64).mean(axis=-1, keepdims=True)
+    np.testing.assert_allclose(that, (target - mu) / np.sqrt(var + eps)[..., None], rtol=1e-12,
+                               atol=1e-14)
+
+
+def test_loss_zero_when_prediction_equals_normalised_target():
+    pred, target, mask = _loss_inputs(D=48)
+    _, _, that = oracle.normpix_loss(pred, target, mask, want_that=True)
+    exact = that.astype(np.float32)
+    loss, grad, _ = oracle.normpix_loss(exact, target, mask)
+    assert loss < 1e-13                      # only the fp32 rounding of the prediction remains
+    assert np.abs(grad).max() < 1e-8
+    assert np.all(grad[mask == 0] == 0.0)
+
+
+def test_loss_constant_offset_closed_form():
+    B, L, D = 2, 4, 16
+    pred, target, mask = _loss_inputs(B, L, D)
+    # target rows on a lattice whose normalised form is exactly representable is not possible in
+    # general; instead use a target whose rows are +-1 alternating: mean 0, unbiased var D/(D-1)
+    target = np.tile(np.array([1.0, -1.0], np.float32), (B, L, D // 2))
+    eps = 0.0
+    sd = math.sqrt(D / (D - 1.0))
+    offsets = np.array([[0.5, 9.0, -1.0, 2.0], [7.0, 0.25, 3.0, 5.0]])
+    pred64 = target / sd + offsets[..., None]
+    pred = pred64.astype(np.float32)
+    M = int(mask.sum())
+    loss, grad, _ = oracle.normpix_loss(pred, target, mask, eps=eps)
+    assert loss == pytest.approx((offsets ** 2 * mask).sum() / M, rel=1e-6)
+    ref_grad = (2.0 * offsets / (D * M) * mask)[..., None] * np.ones(D)
+    np.testing.assert_allclose(grad, ref_grad, rtol=1e-5, atol=0)
+    # divisor is the batch-wide count handed in, not a per-sample count
+    loss2, grad2, _ = oracle.normpix_loss(pred, target, mask, num_masked=8, eps=eps,
+                                          grad_scale=3.0)
+    assert loss2 == pytest.approx(loss * M / 8, rel=1e-12)
+    np.testing.assert_allclose(grad2, ref_grad * 3.0 * M / 8, rtol=1e-5)
+
+
+def test_loss_constant_row_has_no_nan():
+    pred, target, mask = _loss_inputs()
+    target[0, 0, :] = 0.75
+    loss, grad, that = oracle.normpix_loss(pred, target, mask, want_that=True)
+    assert np.isfinite(loss) and np.all(np.isfinite(grad))
+    assert np.all(that[0, 0] == 0.0)
+
+
+def test_loss_euler_identity_and_finite_differences():
+    pred, target, mask = _loss_inputs(seed=7)
+    gs = 1.5
+    loss, grad, that = oracle.normpix_loss(pred, target, mask, grad_scale=gs, want_that=True)
+    assert (grad.astype(np.float64) * (pred - that)).sum() == pytest.approx(2 * loss * gs, rel=1e-6)
+    h = 2.0 ** -6                   # exactly representable step; the loss is quadratic in pred
+    B, L, D = pred.shape
+    for (b, l, e) in [(0, 0, 0), (0, 2, 5), (1, 1, 11), (0, 1, 3), (1, 0, 0), (0, 3, 7)]:
+        up, dn = pred.copy(), pred.copy()
+        up[b, l, e] += h
+        dn[b, l, e] -= h
+        lu, _, _ = oracle.normpix_loss(up, target, mask, want_grad=False)
+        ld, _, _ = oracle.normpix_loss(dn, target, mask, want_grad=False)
+        assert grad[b, l, e] == pytest.approx(gs * (lu - ld) / (2 * h), rel=1e-5, abs=1e-12)
+
+
+def test_loss_against_library_autograd():
+    rng = np.random.default_rng(9)
+    B, L, D = 3, 5, 24
+    pred = rng.standard_normal((B, L, D)).astype(np.float32)
+    target = rng.standard_normal((B, L, D)).astype(np.float32) * 2 + 1
+    mask = (rng.random((B, L)) < 0.6).astype(np.uint8)
+    mask[0, 0] = 1
+    loss, grad, _ = oracle.normpix_loss(pred, target, mask, eps=1e-6)
+    p = torch.tensor(pred, dtype=torch.float64, requires_grad=True)
+    t = torch.tensor(target, dtype=torch.float64)
+    m = torch.tensor(mask, dtype=torch.float64)
+    tn = (t - t.mean(-1, keepdim=True)) / (t.var(-1, keepdim=True, unbiased=True) + 1e-6).sqrt()
+    ref = (((p - tn) ** 2).mean(-1) * m).sum() / m.sum()
+    ref.backward()
+    assert loss == pytest.approx(ref.item(), rel=1e-12)
+    np.testing.assert_allclose(grad, p.grad.numpy(), rtol=2e-7, atol=1e-12)
+    # all-ones and single-row masks
+    ones = np.ones_like(mask)
+    l1, g1, _ = oracle.normpix_loss(pred, target, ones)
+    assert l1 == pytest.approx(((p.detach() - tn) ** 2).mean().item(), rel=1e-12)
+    single = np.zeros_like(mask)
+    single[2, 3] = 1
+    l2, g2, _ = oracle.normpix_loss(pred, target, single)
+    assert l2 == pytest.approx(((p.detach()[2, 3] - tn[2, 3]) ** 2).mean().item(), rel=1e-12)
+    assert np.count_nonzero(np.abs(g2).sum(-1)) == 1
+
+
+# ------------------------------------------------------------------------------------ inputs
+def test_synthetic_inputs_are_reproducible_and_shaped():
+    for kind, B in (("uniform", 5), ("gradient", 6)):
+        a = synth.make_images(kind, B, seed=0)
+        b = synth.make_images(kind, B + 3, seed=0)
+        assert np.array_equal(a[2], b[2][:B]) and np.array_equal(a[3], b[3][:B])
+        for i in range(B):
+            assert np.array_equal(synth.image_view(*a, i), synth.image_view(*b, i))
+        h, w = a[2], a[3]
+        if kind == "uniform":
+            assert h.min() >= 64 and h.max() <= 128 and w.min() >= 64 and w.max() <= 128
+        else:
+            assert np.all(np.maximum(h, w) == 256) and np.all(np.minimum(h, w) >= 160)
+    p = synth.make_pred(0, 3, 4, 8)
+    assert np.array_equal(p[2], synth.make_pred_rows(0, 2, 4, 8)) and p.dtype == np.float32
