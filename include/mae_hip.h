@@ -1,0 +1,166 @@
+/*
+ * mae_hip.h -- C ABI of the MI355X (gfx950) library for the per-batch masked-autoencoder input
+ * pipeline and its reconstruction loss (DailyMAE, arXiv 2404.00509).
+ *
+ * Two calls make up the path:
+ *
+ *   mae_prep_batch     decoded uint8 images in device memory -> training tensors.
+ *                      RandomResizedCrop (Sec. 5.1: area scale uniform, aspect ratio log-uniform,
+ *                      crop then resize to the training resolution of the progressive schedule,
+ *                      Sec. 5.3 / Table 9), bilinear resampling (Sec. 4.1), the "Simple"
+ *                      augmentation = horizontal flip + tensor conversion + mean/std
+ *                      normalisation (App. B), the ViT patch split (Sec. 3), random masking at a
+ *                      masking ratio with only the visible patches handed to the encoder
+ *                      (Sec. 2, Sec. 5.3 "Masking Ratio").
+ *   mae_normpix_loss   the reconstruction objective of the official MAE recipe that the paper
+ *                      adopts (Sec. 3): mean squared error against per-patch normalised pixels on
+ *                      the masked patches, and its gradient with respect to the prediction.
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless its name starts with host_.  The descriptor
+ *     structs themselves live in host memory and are read during the call only.
+ *   - The caller allocates and owns every buffer, the workspace included.  The library keeps no
+ *     global state, never allocates or frees device memory and keeps no pointer after a call.
+ *   - Calls validate their arguments on the host, enqueue kernels on `hip_stream` (a hipStream_t
+ *     passed as void*, NULL = the default stream) and return without synchronising.  Outputs are
+ *     valid once the stream has reached that point.  Calls are re-entrant; two calls that share a
+ *     workspace must be ordered by the stream.
+ *   - Return value: MAE_OK or a negative mae_status.  Argument errors are found before anything
+ *     is launched, so a failed call has no side effect.
+ *   - Image geometry (heights, widths, offsets) lives in device memory and cannot be checked on
+ *     the host.  The kernels check every sample (1 <= H, W <= 32767, the image lies inside
+ *     [0, images_bytes)); a sample that fails is skipped (its outputs are left untouched), is
+ *     reported with valid = 0 in crop_out, and is counted in the workspace status word that
+ *     mae_prep_status reads back.
+ */
+#ifndef MAE_HIP_H
+#define MAE_HIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MAE_OK = 0,
+  MAE_ERR_NULL = -1,      /* a required pointer is NULL                                        */
+  MAE_ERR_SHAPE = -2,     /* sizes that do not fit together (B <= 0, S % p != 0, K outside ...) */
+  MAE_ERR_RANGE = -3,     /* a value outside the supported range (see each field)              */
+  MAE_ERR_DTYPE = -4,     /* unknown mae_dtype                                                 */
+  MAE_ERR_WORKSPACE = -5, /* workspace missing, misaligned (256 B) or too small                */
+  MAE_ERR_NO_DEVICE = -6, /* no HIP device visible to this process                             */
+  MAE_ERR_HIP = -7        /* a HIP runtime call failed (launch error)                          */
+} mae_status;
+
+typedef enum { MAE_F32 = 0, MAE_BF16 = 1 } mae_dtype;
+
+/* ------------------------------------------------------------------------------------------------
+ * mae_prep_batch
+ *
+ * Notation: B images; image b is H_b x W_b x 3 uint8, HWC, rows tightly packed (stride 3 W_b);
+ * S = out_size, p = patch, G = S / p, L = G * G patches, D = 3 p^2 values per patch,
+ * K = num_keep visible patches.
+ *
+ * Random numbers: every draw is a pure function of (seed, batch_index, sample_base + b, stream,
+ * counter) -- the SplitMix64 output function applied to a keyed counter -- so a batch can be
+ * recomputed, and a shard of a batch gives the same values as the whole batch.
+ *
+ * Limits: 1 <= L <= 256; 1 <= p <= 32; S <= 512; exp(-1/2) <= ratio_lo <= ratio_hi <= exp(1/2).
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct {
+  int32_t B;               /* images in this call, > 0                                          */
+  const uint8_t* images;   /* packed images; image b starts at images + offsets[b]              */
+  int64_t images_bytes;    /* size of the `images` buffer; used for device-side bounds checks   */
+  const int64_t* offsets;  /* [B] byte offsets, >= 0                                            */
+  const int32_t* heights;  /* [B]                                                               */
+  const int32_t* widths;   /* [B]                                                               */
+  int32_t out_size;        /* S                                                                 */
+  int32_t patch;           /* p, S % p == 0                                                     */
+  int32_t num_keep;        /* K in [1, L]; see mae_num_keep                                     */
+  float scale_lo, scale_hi; /* area fraction of the crop, 0 < lo <= hi <= 1 (paper: 0.2 .. 1)   */
+  float ratio_lo, ratio_hi; /* width / height of the crop, lo <= hi (paper: 3/4 .. 4/3)         */
+  float flip_p;            /* probability of the horizontal flip, in [0, 1]                     */
+  float mean[3], std[3];   /* per channel, applied as (v / 255 - mean) / std; std > 0           */
+  uint64_t seed;           /* random-number key                                                 */
+  uint64_t batch_index;    /* random-number key; vary per step                                  */
+  uint32_t sample_base;    /* global index of sample 0 of this call (0 unless sharding a batch) */
+  int32_t noise_bits;      /* 1..32 bits of masking noise per patch; 32 in production, small
+                              values force ties (equal keys keep index order)                   */
+  int32_t out_dtype;       /* mae_dtype of `visible`                                            */
+} mae_prep_desc;
+
+/* Outputs (device):
+ *   visible      [B, K, D] out_dtype  visible[b, r, :] = patch ids_keep[b, r] of image b; r runs
+ *                                     in order of increasing noise.                   required
+ *   mask         [B, L] uint8         0 = visible, 1 = masked.                        required
+ *   ids_restore  [B, L] int32         rank of patch l in the noise order; the patch is visible
+ *                                     iff rank < K.                                   required
+ *   ids_keep     [B, K] int32         patch index at rank r.                          nullable
+ *   target       [B, L, D] float      all patches, image-normalised (not per-patch normalised);
+ *                                     element order inside a patch is (row, column, channel);
+ *                                     patches in row-major grid order.                nullable
+ *   crop_out     [B, 6] int32         top, left, height, width of the crop box, flip bit, valid
+ *                                     flag.                                           nullable
+ *   workspace    mae_prep_workspace_bytes(d) bytes, 256-byte aligned.                 required
+ * Pixel values are never rounded back to bytes between resize and normalisation.
+ * bf16 `visible` is the float value rounded to nearest even. */
+int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t* ids_restore,
+                   int32_t* ids_keep, float* target, int32_t* crop_out, void* workspace,
+                   size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of workspace mae_prep_batch needs for this descriptor (0 if the descriptor is invalid). */
+size_t mae_prep_workspace_bytes(const mae_prep_desc* d);
+
+/* Waits for `hip_stream`, then stores in *host_invalid_samples how many samples of the last
+ * mae_prep_batch call on this workspace failed the device-side geometry check.  Synchronises. */
+int mae_prep_status(const void* workspace, void* hip_stream, int32_t* host_invalid_samples);
+
+/* floor(L * (1 - mask_ratio)) in double precision: 49 for L = 196 at ratio 0.75, 19 (not 20) for
+ * L = 100 at ratio 0.8.  Returns -1 when the arguments are out of range. */
+int32_t mae_num_keep(int32_t L, double mask_ratio);
+
+/* ------------------------------------------------------------------------------------------------
+ * mae_normpix_loss
+ *
+ * For every patch row t = target[b, l, :]: mu = mean(t), var = sum (t - mu)^2 / (D - 1),
+ * that = (t - mu) / sqrt(var + eps).  With M = num_masked:
+ *   loss = sum over masked rows of mean_e (pred - that)^2  /  M
+ *   grad = grad_scale * 2 (pred - that) / (D * M) on masked rows, +0 on visible rows.
+ * Statistics and sums are accumulated in single precision per row and double precision across
+ * rows; the result does not depend on scheduling (fixed reduction order).
+ *
+ * Limits: 2 <= D <= 3072.
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct {
+  int32_t B, L, D;
+  const void* pred;      /* [B, L, D] pred_dtype                                                */
+  const float* target;   /* [B, L, D] float, as written by mae_prep_batch                       */
+  const uint8_t* mask;   /* [B, L], non-zero = masked                                           */
+  int64_t num_masked;    /* M > 0: masked patches of the WHOLE batch (B_global * (L - K)); the
+                            caller knows it in closed form, so shards need no exchange for grad */
+  float eps;             /* >= 0, 1e-6 in the MAE recipe                                        */
+  float grad_scale;      /* upstream derivative of the loss, normally 1                         */
+  int32_t pred_dtype;    /* mae_dtype of pred and grad                                          */
+} mae_loss_desc;
+
+/* Outputs (device):
+ *   loss       [1] float     required
+ *   grad       [B, L, D] pred_dtype, every element written     nullable (loss only)
+ *   workspace  mae_loss_workspace_bytes(d) bytes, 256-byte aligned   required */
+int mae_normpix_loss(const mae_loss_desc* d, float* loss, void* grad, void* workspace,
+                     size_t workspace_bytes, void* hip_stream);
+
+size_t mae_loss_workspace_bytes(const mae_loss_desc* d);
+
+/* Static, NUL-terminated description of a status code. */
+const char* mae_error_string(int status);
+
+/* Version of this ABI: major * 10000 + minor * 100 + patch. */
+int mae_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MAE_HIP_H */

@@ -1,0 +1,227 @@
+"""ctypes binding of ``libmae_hip.so`` -- argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; PyTorch is used for device memory and
+for the stream handle.  There is no CPU fallback: if the library is missing, or no GPU is visible,
+the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmae_hip.so")
+
+MAE_OK = 0
+MAE_ERR_NULL, MAE_ERR_SHAPE, MAE_ERR_RANGE, MAE_ERR_DTYPE = -1, -2, -3, -4
+MAE_ERR_WORKSPACE, MAE_ERR_NO_DEVICE, MAE_ERR_HIP = -5, -6, -7
+MAE_F32, MAE_BF16 = 0, 1
+
+IMAGENET_MEAN = (0.485, 0.456, 0.406)
+IMAGENET_STD = (0.229, 0.224, 0.225)
+
+# Entry points declared in include/mae_hip.h.
+EXPORTS = ("mae_prep_batch", "mae_prep_workspace_bytes", "mae_prep_status", "mae_num_keep",
+           "mae_normpix_loss", "mae_loss_workspace_bytes", "mae_error_string", "mae_version")
+
+
+class MaePrepDesc(C.Structure):
+    _fields_ = [
+        ("B", C.c_int32),
+        ("images", C.c_void_p),
+        ("images_bytes", C.c_int64),
+        ("offsets", C.c_void_p),
+        ("heights", C.c_void_p),
+        ("widths", C.c_void_p),
+        ("out_size", C.c_int32),
+        ("patch", C.c_int32),
+        ("num_keep", C.c_int32),
+        ("scale_lo", C.c_float),
+        ("scale_hi", C.c_float),
+        ("ratio_lo", C.c_float),
+        ("ratio_hi", C.c_float),
+        ("flip_p", C.c_float),
+        ("mean", C.c_float * 3),
+        ("std", C.c_float * 3),
+        ("seed", C.c_uint64),
+        ("batch_index", C.c_uint64),
+        ("sample_base", C.c_uint32),
+        ("noise_bits", C.c_int32),
+        ("out_dtype", C.c_int32),
+    ]
+
+
+class MaeLossDesc(C.Structure):
+    _fields_ = [
+        ("B", C.c_int32),
+        ("L", C.c_int32),
+        ("D", C.c_int32),
+        ("pred", C.c_void_p),
+        ("target", C.c_void_p),
+        ("mask", C.c_void_p),
+        ("num_masked", C.c_int64),
+        ("eps", C.c_float),
+        ("grad_scale", C.c_float),
+        ("pred_dtype", C.c_int32),
+    ]
+
+
+class MaeError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {mae_error_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def load():
+    """Load the shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2404_00509_amd.build`")
+        lib = C.CDLL(LIB_PATH)
+        lib.mae_prep_batch.restype = C.c_int
+        lib.mae_prep_batch.argtypes = [C.POINTER(MaePrepDesc)] + [C.c_void_p] * 7 + [C.c_size_t,
+                                                                                       C.c_void_p]
+        lib.mae_prep_workspace_bytes.restype = C.c_size_t
+        lib.mae_prep_workspace_bytes.argtypes = [C.POINTER(MaePrepDesc)]
+        lib.mae_prep_status.restype = C.c_int
+        lib.mae_prep_status.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32)]
+        lib.mae_num_keep.restype = C.c_int32
+        lib.mae_num_keep.argtypes = [C.c_int32, C.c_double]
+        lib.mae_normpix_loss.restype = C.c_int
+        lib.mae_normpix_loss.argtypes = [C.POINTER(MaeLossDesc), C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.mae_loss_workspace_bytes.restype = C.c_size_t
+        lib.mae_loss_workspace_bytes.argtypes = [C.POINTER(MaeLossDesc)]
+        lib.mae_error_string.restype = C.c_char_p
+        lib.mae_error_string.argtypes = [C.c_int]
+        lib.mae_version.restype = C.c_int
+        lib.mae_version.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def mae_error_string(status: int) -> str:
+    return load().mae_error_string(status).decode()
+
+
+def mae_version() -> int:
+    return int(load().mae_version())
+
+
+def mae_num_keep(L: int, mask_ratio: float) -> int:
+    return int(load().mae_num_keep(L, mask_ratio))
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def make_prep_desc(images, offsets, heights, widths, *, out_size, patch, num_keep,
+                   scale=(0.2, 1.0), ratio=(3.0 / 4.0, 4.0 / 3.0), flip_p=0.5, mean=IMAGENET_MEAN,
+                   std=IMAGENET_STD, seed=0, batch_index=0, sample_base=0, noise_bits=32,
+                   out_dtype=MAE_F32) -> MaePrepDesc:
+    d = MaePrepDesc()
+    d.B = int(heights.numel())
+    d.images = images.data_ptr()
+    d.images_bytes = int(images.numel())
+    d.offsets, d.heights, d.widths = offsets.data_ptr(), heights.data_ptr(), widths.data_ptr()
+    d.out_size, d.patch, d.num_keep = out_size, patch, num_keep
+    d.scale_lo, d.scale_hi = scale
+    d.ratio_lo, d.ratio_hi = ratio
+    d.flip_p = flip_p
+    d.mean = (C.c_float * 3)(*mean)
+    d.std = (C.c_float * 3)(*std)
+    d.seed, d.batch_index, d.sample_base = seed, batch_index, sample_base
+    d.noise_bits, d.out_dtype = noise_bits, out_dtype
+    return d
+
+
+def mae_prep_workspace_bytes(desc: MaePrepDesc) -> int:
+    return int(load().mae_prep_workspace_bytes(C.byref(desc)))
+
+
+def mae_prep_batch(desc: MaePrepDesc, visible, mask, ids_restore, ids_keep=None, target=None,
+                   crop_out=None, workspace=None, stream=None) -> None:
+    """Enqueue the input pipeline; all tensors are preallocated device tensors."""
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load().mae_prep_batch(C.byref(desc), _ptr(visible), _ptr(mask), _ptr(ids_restore),
+                               _ptr(ids_keep), _ptr(target), _ptr(crop_out), _ptr(workspace),
+                               ws_bytes, _stream(stream))
+    if rc != MAE_OK:
+        raise MaeError(rc, "mae_prep_batch")
+
+
+def mae_prep_status(workspace, stream=None) -> int:
+    """Synchronises; number of samples the device-side geometry check rejected."""
+    n = C.c_int32(-1)
+    rc = load().mae_prep_status(_ptr(workspace), _stream(stream), C.byref(n))
+    if rc != MAE_OK:
+        raise MaeError(rc, "mae_prep_status")
+    return n.value
+
+
+def make_loss_desc(pred, target, mask, *, num_masked, eps=1e-6, grad_scale=1.0) -> MaeLossDesc:
+    d = MaeLossDesc()
+    d.B, d.L, d.D = (int(v) for v in pred.shape)
+    d.pred, d.target, d.mask = pred.data_ptr(), target.data_ptr(), mask.data_ptr()
+    d.num_masked = int(num_masked)
+    d.eps, d.grad_scale = eps, grad_scale
+    d.pred_dtype = MAE_BF16 if pred.dtype == torch.bfloat16 else MAE_F32
+    return d
+
+
+def mae_loss_workspace_bytes(desc: MaeLossDesc) -> int:
+    return int(load().mae_loss_workspace_bytes(C.byref(desc)))
+
+
+def mae_normpix_loss(desc: MaeLossDesc, loss, grad=None, workspace=None, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load().mae_normpix_loss(C.byref(desc), _ptr(loss), _ptr(grad), _ptr(workspace), ws_bytes,
+                                 _stream(stream))
+    if rc != MAE_OK:
+        raise MaeError(rc, "mae_normpix_loss")
+
+
+# ------------------------------------------------------------------------------------------------
+# Preallocated buffers for one workload: device memory only, no arithmetic.
+# ------------------------------------------------------------------------------------------------
+@dataclass
+class PrepBuffers:
+    visible: torch.Tensor
+    mask: torch.Tensor
+    ids_restore: torch.Tensor
+    ids_keep: torch.Tensor
+    target: torch.Tensor
+    crop: torch.Tensor
+    workspace: torch.Tensor
+
+
+def alloc_prep_buffers(desc: MaePrepDesc, device="cuda", want_target=True) -> PrepBuffers:
+    B, p, K = desc.B, desc.patch, desc.num_keep
+    G = desc.out_size // p
+    L, D = G * G, 3 * p * p
+    vis_dtype = torch.bfloat16 if desc.out_dtype == MAE_BF16 else torch.float32
+    ws = max(mae_prep_workspace_bytes(desc), 256)
+    return PrepBuffers(
+        visible=torch.empty((B, K, D), dtype=vis_dtype, device=device),
+        mask=torch.empty((B, L), dtype=torch.uint8, device=device),
+        ids_restore=torch.empty((B, L), dtype=torch.int32, device=device),
+        ids_keep=torch.empty((B, K), dtype=torch.int32, device=device),
+        target=torch.empty((B, L, D), dtype=torch.float32, device=device) if want_target else None,
+        crop=torch.empty((B, 6), dtype=torch.int32, device=device),
+        workspace=torch.empty(ws, dtype=torch.uint8, device=device),
+    )

@@ -1,0 +1,234 @@
+// C ABI of the library: host-side validation of the caller's descriptors, then kernel launches.
+// No device memory is allocated here and no pointer is kept after a call.
+#include "../../include/mae_hip.h"
+
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+
+#include "mae_device.hpp"
+#include "mae_kernels.hpp"
+
+namespace {
+
+constexpr int kVersion = 100;  // 0.1.0
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+struct PrepShape {
+  int32_t G, L, D;
+};
+
+// Checks everything that can be checked without touching device memory.
+int validate_prep(const mae_prep_desc* d, PrepShape* shape) {
+  if (!d) return MAE_ERR_NULL;
+  if (!d->images || !d->offsets || !d->heights || !d->widths) return MAE_ERR_NULL;
+  if (d->B <= 0 || d->out_size <= 0 || d->patch <= 0) return MAE_ERR_SHAPE;
+  if (d->out_size % d->patch != 0) return MAE_ERR_SHAPE;
+  if (d->patch > 32 || d->out_size > 512) return MAE_ERR_RANGE;
+  const int64_t G = d->out_size / d->patch;
+  const int64_t L = G * G;
+  if (L > mae::kMaxPatches) return MAE_ERR_RANGE;
+  if (d->num_keep < 1 || d->num_keep > L) return MAE_ERR_SHAPE;
+  if (d->images_bytes <= 0) return MAE_ERR_RANGE;
+  if (!(d->scale_lo > 0.0f) || !(d->scale_lo <= d->scale_hi) || !(d->scale_hi <= 1.0f))
+    return MAE_ERR_RANGE;
+  if (!(d->ratio_lo > 0.0f) || !(d->ratio_lo <= d->ratio_hi)) return MAE_ERR_RANGE;
+  // the exponential of the log-ratio is a fixed polynomial, accurate for |x| <= 1/2
+  if (log((double)d->ratio_lo) < -0.5 || log((double)d->ratio_hi) > 0.5) return MAE_ERR_RANGE;
+  if (!(d->flip_p >= 0.0f) || !(d->flip_p <= 1.0f)) return MAE_ERR_RANGE;
+  for (int c = 0; c < 3; ++c) {
+    if (!(d->std[c] > 0.0f) || !isfinite(d->std[c]) || !isfinite(d->mean[c])) return MAE_ERR_RANGE;
+  }
+  if (d->noise_bits < 1 || d->noise_bits > 32) return MAE_ERR_RANGE;
+  if ((uint64_t)d->sample_base + (uint64_t)d->B > 0x100000000ull) return MAE_ERR_RANGE;
+  if (d->out_dtype != MAE_F32 && d->out_dtype != MAE_BF16) return MAE_ERR_DTYPE;
+  if (shape) {
+    shape->G = (int32_t)G;
+    shape->L = (int32_t)L;
+    shape->D = 3 * d->patch * d->patch;
+  }
+  return MAE_OK;
+}
+
+int validate_loss(const mae_loss_desc* d) {
+  if (!d) return MAE_ERR_NULL;
+  if (!d->pred || !d->target || !d->mask) return MAE_ERR_NULL;
+  if (d->B <= 0 || d->L <= 0) return MAE_ERR_SHAPE;
+  if (d->D < 2 || d->D > 3072) return MAE_ERR_RANGE;
+  if (d->num_masked <= 0) return MAE_ERR_RANGE;
+  if (!(d->eps >= 0.0f) || !isfinite(d->eps) || !isfinite(d->grad_scale)) return MAE_ERR_RANGE;
+  if (d->pred_dtype != MAE_F32 && d->pred_dtype != MAE_BF16) return MAE_ERR_DTYPE;
+  return MAE_OK;
+}
+
+int have_device() {
+  int n = 0;
+  if (hipGetDeviceCount(&n) != hipSuccess || n <= 0) {
+    (void)hipGetLastError();  // do not leave a sticky error for the caller's next HIP call
+    return MAE_ERR_NO_DEVICE;
+  }
+  return MAE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mae_version(void) { return kVersion; }
+
+const char* mae_error_string(int status) {
+  switch (status) {
+    case MAE_OK: return "success";
+    case MAE_ERR_NULL: return "a required pointer is NULL";
+    case MAE_ERR_SHAPE: return "sizes do not fit together";
+    case MAE_ERR_RANGE: return "a value is outside the supported range";
+    case MAE_ERR_DTYPE: return "unknown dtype";
+    case MAE_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case MAE_ERR_NO_DEVICE: return "no HIP device visible";
+    case MAE_ERR_HIP: return "a HIP runtime call failed";
+    default: return "unknown status";
+  }
+}
+
+int32_t mae_num_keep(int32_t L, double mask_ratio) {
+  if (L < 1 || !(mask_ratio >= 0.0) || !(mask_ratio <= 1.0)) return -1;
+  return (int32_t)floor((double)L * (1.0 - mask_ratio));
+}
+
+size_t mae_prep_workspace_bytes(const mae_prep_desc* d) {
+  if (validate_prep(d, nullptr) != MAE_OK) return 0;
+  return mae::kWorkspaceHeader + (size_t)d->B * sizeof(mae::CropRec);
+}
+
+int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t* ids_restore,
+                   int32_t* ids_keep, float* target, int32_t* crop_out, void* workspace,
+                   size_t workspace_bytes, void* hip_stream) {
+  PrepShape sh;
+  int rc = validate_prep(d, &sh);
+  if (rc != MAE_OK) return rc;
+  if (!visible || !mask || !ids_restore) return MAE_ERR_NULL;
+  if (!aligned(visible, 16) || (target && !aligned(target, 16))) return MAE_ERR_RANGE;
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < mae_prep_workspace_bytes(d))
+    return MAE_ERR_WORKSPACE;
+  rc = have_device();
+  if (rc != MAE_OK) return rc;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+  mae::ParamArgs pa;
+  memset(&pa, 0, sizeof(pa));
+  pa.B = d->B;
+  pa.L = sh.L;
+  pa.K = d->num_keep;
+  pa.noise_bits = d->noise_bits;
+  pa.sample_base = d->sample_base;
+  pa.key1 = mae::batch_key(d->seed, d->batch_index);
+  pa.scale_lo = (double)d->scale_lo;
+  pa.scale_span = (double)d->scale_hi - (double)d->scale_lo;
+  const double ln_lo = log((double)d->ratio_lo), ln_hi = log((double)d->ratio_hi);
+  pa.ln_ratio_lo = ln_lo;
+  pa.ln_ratio_span = ln_hi - ln_lo;
+  pa.ratio_lo = (double)d->ratio_lo;
+  pa.ratio_hi = (double)d->ratio_hi;
+  pa.flip_p = d->flip_p;
+  pa.images_bytes = d->images_bytes;
+  pa.offsets = d->offsets;
+  pa.heights = d->heights;
+  pa.widths = d->widths;
+  pa.mask = mask;
+  pa.ids_restore = ids_restore;
+  pa.ids_keep = ids_keep;
+  pa.crop_out = crop_out;
+  pa.workspace = static_cast<uint8_t*>(workspace);
+  if (mae::launch_params_mask(pa, stream) != hipSuccess) return MAE_ERR_HIP;
+
+  mae::CropArgs ca;
+  memset(&ca, 0, sizeof(ca));
+  ca.B = d->B;
+  ca.S = d->out_size;
+  ca.p = d->patch;
+  ca.G = sh.G;
+  ca.L = sh.L;
+  ca.K = d->num_keep;
+  ca.D = sh.D;
+  ca.visible_bf16 = d->out_dtype == MAE_BF16;
+  for (int c = 0; c < 3; ++c) {
+    ca.nscale[c] = (float)(1.0 / (255.0 * (double)d->std[c]));
+    ca.nbias[c] = (float)(-(double)d->mean[c] / (double)d->std[c]);
+  }
+  ca.images = d->images;
+  ca.offsets = d->offsets;
+  ca.widths = d->widths;
+  ca.ids_restore = ids_restore;
+  ca.workspace = static_cast<const uint8_t*>(workspace);
+  ca.visible = visible;
+  ca.target = target;
+  if (mae::launch_crop_patch(ca, stream) != hipSuccess) return MAE_ERR_HIP;
+  return MAE_OK;
+}
+
+int mae_prep_status(const void* workspace, void* hip_stream, int32_t* host_invalid_samples) {
+  if (!workspace || !host_invalid_samples) return MAE_ERR_NULL;
+  int rc = have_device();
+  if (rc != MAE_OK) return rc;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (hipStreamSynchronize(stream) != hipSuccess) return MAE_ERR_HIP;
+  mae::WorkspaceHeader hdr;
+  if (hipMemcpy(&hdr, workspace, sizeof(hdr), hipMemcpyDeviceToHost) != hipSuccess)
+    return MAE_ERR_HIP;
+  if (hdr.magic != mae::kWorkspaceMagic || hdr.B <= 0) return MAE_ERR_WORKSPACE;
+  int32_t invalid = 0;
+  const uint8_t* recs = static_cast<const uint8_t*>(workspace) + mae::kWorkspaceHeader;
+  mae::CropRec chunk[256];
+  for (int32_t done = 0; done < hdr.B; done += 256) {
+    const int32_t n = hdr.B - done < 256 ? hdr.B - done : 256;
+    if (hipMemcpy(chunk, recs + (size_t)done * sizeof(mae::CropRec), (size_t)n * sizeof(mae::CropRec),
+                  hipMemcpyDeviceToHost) != hipSuccess)
+      return MAE_ERR_HIP;
+    for (int32_t i = 0; i < n; ++i) invalid += chunk[i].valid ? 0 : 1;
+  }
+  *host_invalid_samples = invalid;
+  return MAE_OK;
+}
+
+size_t mae_loss_workspace_bytes(const mae_loss_desc* d) {
+  if (validate_loss(d) != MAE_OK) return 0;
+  const int waves = mae::loss_grid_waves((int64_t)d->B * d->L);
+  return (size_t)waves * sizeof(double);
+}
+
+int mae_normpix_loss(const mae_loss_desc* d, float* loss, void* grad, void* workspace,
+                     size_t workspace_bytes, void* hip_stream) {
+  int rc = validate_loss(d);
+  if (rc != MAE_OK) return rc;
+  if (!loss) return MAE_ERR_NULL;
+  if (!aligned(d->pred, 16) || !aligned(d->target, 16) || (grad && !aligned(grad, 16)))
+    return MAE_ERR_RANGE;
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < mae_loss_workspace_bytes(d))
+    return MAE_ERR_WORKSPACE;
+  rc = have_device();
+  if (rc != MAE_OK) return rc;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+  mae::LossArgs la;
+  memset(&la, 0, sizeof(la));
+  la.rows = (int64_t)d->B * d->L;
+  la.D = d->D;
+  la.pred_bf16 = d->pred_dtype == MAE_BF16;
+  la.eps = d->eps;
+  const double count = (double)d->D * (double)d->num_masked;
+  la.gscale = (float)((double)d->grad_scale * 2.0 / count);
+  la.inv_count = 1.0 / count;
+  la.pred = d->pred;
+  la.target = d->target;
+  la.mask = d->mask;
+  la.grad = grad;
+  la.loss = loss;
+  la.partials = static_cast<double*>(workspace);
+  la.num_partials = mae::loss_grid_waves(la.rows);
+  if (mae::launch_normpix_loss(la, stream) != hipSuccess) return MAE_ERR_HIP;
+  return MAE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,73 @@
+// Shared device-side helpers of the gfx950 kernels: keyed random draws, workgroup remapping for
+// the 8 XCDs, packed conversions.  HIP path only.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mae {
+
+constexpr int kWave = 64;         // CDNA wavefront
+constexpr int kXcds = 8;          // MI355X: 8 accelerator dies, one L2 each
+constexpr int kMaxPatches = 256;  // per image: one wavefront sorts 4 keys per lane
+
+// Per-sample record handed from the parameter kernel to the resampling kernel (workspace).
+struct CropRec {
+  int32_t top, left, ch, cw;  // crop box inside the image
+  int32_t flip;               // 1 = mirror output columns
+  int32_t valid;              // 0 = geometry check failed, sample skipped
+  int32_t pad0, pad1;
+};
+static_assert(sizeof(CropRec) == 32, "CropRec is 32 bytes");
+
+// The workspace starts with a 256-byte header, followed by CropRec[B].
+constexpr size_t kWorkspaceHeader = 256;
+constexpr int32_t kWorkspaceMagic = 0x4D414531;  // "MAE1"
+struct WorkspaceHeader {
+  int32_t magic;
+  int32_t B;  // number of records written by the last call
+};
+
+// ---- SplitMix64 output function (Steele, Lea, Flood 2014), used as a keyed counter hash --------
+constexpr uint64_t kGamma = 0x9E3779B97F4A7C15ull;
+
+__host__ __device__ inline uint64_t mix64(uint64_t z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+// key1 = state after keying with (seed, batch_index); computed once per call on the host.
+__host__ __device__ inline uint64_t batch_key(uint64_t seed, uint64_t batch_index) {
+  uint64_t k0 = mix64(seed + kGamma);
+  return mix64(k0 + kGamma * (batch_index + 1));
+}
+
+enum Stream : uint32_t { kScale = 0, kRatio = 1, kTop = 2, kLeft = 3, kFlip = 4, kNoise = 5 };
+
+__device__ inline uint64_t draw(uint64_t key1, uint32_t sample, uint32_t stream, uint32_t ctr) {
+  uint64_t w = ((uint64_t)sample << 32) | ((uint64_t)stream << 24) | (uint64_t)ctr;
+  return mix64(key1 + kGamma * (w + 1));
+}
+
+// ---- workgroup id -> logical tile id, so that consecutive tiles share an XCD (and its L2) ------
+// Hardware hands workgroup i to XCD i % 8.  Tiles are split into 8 contiguous ranges, one per XCD.
+__device__ inline uint32_t xcd_remap(uint32_t wg, uint32_t n) {
+  uint32_t q = n / kXcds, r = n % kXcds;
+  uint32_t xcd = wg % kXcds, pos = wg / kXcds;
+  return xcd < r ? xcd * (q + 1) + pos : r * (q + 1) + (xcd - r) * q + pos;
+}
+
+// ---- float -> bfloat16, round to nearest even (finite inputs) ----------------------------------
+__device__ inline uint32_t bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ inline uint32_t pack_bf16x2(float lo, float hi) {
+  return bf16_rne(lo) | (bf16_rne(hi) << 16);
+}
+__device__ inline float bf16_lo(uint32_t v) { return __uint_as_float(v << 16); }
+__device__ inline float bf16_hi(uint32_t v) { return __uint_as_float(v & 0xFFFF0000u); }
+
+}  // namespace mae

@@ -1,0 +1,66 @@
+// Kernel argument blocks and launchers of the gfx950 path.  Filled in by the C-ABI layer after it
+// has validated the caller's descriptor; every launcher only enqueues work on `stream`.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mae {
+
+// ---- per-sample parameters + masking order -----------------------------------------------------
+struct ParamArgs {
+  int32_t B, L, K, noise_bits;
+  uint32_t sample_base;
+  uint64_t key1;                      // batch_key(seed, batch_index)
+  double scale_lo, scale_span;        // area fraction = lo + span * u
+  double ln_ratio_lo, ln_ratio_span;  // ln(width/height) = lo + span * u (logs taken on the host)
+  double ratio_lo, ratio_hi;          // for the fallback box
+  float flip_p;
+  int64_t images_bytes;
+  const int64_t* offsets;
+  const int32_t* heights;
+  const int32_t* widths;
+  uint8_t* mask;
+  int32_t* ids_restore;
+  int32_t* ids_keep;   // nullable
+  int32_t* crop_out;   // nullable, [B,6]
+  uint8_t* workspace;  // header + CropRec[B]
+};
+hipError_t launch_params_mask(const ParamArgs& a, hipStream_t stream);
+
+// ---- crop + resize + flip + normalise + patchify + gather --------------------------------------
+struct CropArgs {
+  int32_t B, S, p, G, L, K, D;
+  int32_t visible_bf16;  // 0: float, 1: bfloat16
+  float nscale[3];       // 1 / (255 std_c)
+  float nbias[3];        // -mean_c / std_c
+  const uint8_t* images;
+  const int64_t* offsets;
+  const int32_t* widths;
+  const int32_t* ids_restore;
+  const uint8_t* workspace;
+  void* visible;
+  float* target;  // nullable
+};
+hipError_t launch_crop_patch(const CropArgs& a, hipStream_t stream);
+
+// ---- normalised-pixel loss ---------------------------------------------------------------------
+struct LossArgs {
+  int64_t rows;  // B * L
+  int32_t D;
+  int32_t pred_bf16;
+  float eps;
+  float gscale;      // grad_scale * 2 / (D * M)
+  double inv_count;  // 1 / (D * M)
+  const void* pred;
+  const float* target;
+  const uint8_t* mask;
+  void* grad;        // nullable
+  float* loss;
+  double* partials;  // workspace: one per wavefront of the grid
+  int32_t num_partials;
+};
+int loss_grid_waves(int64_t rows);
+hipError_t launch_normpix_loss(const LossArgs& a, hipStream_t stream);
+
+}  // namespace mae

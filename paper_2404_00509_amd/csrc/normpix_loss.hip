@@ -1,0 +1,214 @@
+// Normalised-pixel reconstruction loss and its gradient (the official MAE objective that Sec. 3
+// of the paper adopts): per patch row, target statistics -> normalised target -> squared error
+// against the prediction on masked rows.
+//
+// Streaming kernel: one wavefront per patch row, the row held in registers (16-byte loads, lane i
+// takes the i-th, (i+64)-th, ... group), two butterfly reductions for mean and variance, gradient
+// written with 16-byte stores.  Visible rows only get zeros written and read nothing.  Each
+// wavefront adds its rows' squared errors in double precision and leaves one partial; a second,
+// single-workgroup kernel adds the partials in a fixed order, so the loss is reproducible.
+#include "mae_device.hpp"
+#include "mae_kernels.hpp"
+
+namespace mae {
+
+constexpr int kLossThreads = 256;
+constexpr int kLossWaves = kLossThreads / kWave;
+constexpr int kLossMaxBlocks = 256 * 8;  // 8 workgroups per compute unit
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ static inline float wave_sum(float v) {
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+
+__device__ static inline double wave_sum(double v) {
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+
+template <bool kBf16>
+__device__ static inline f32x4 load_pred4(const void* pred, int64_t elem) {
+  if (kBf16) {
+    const u32x2 raw = *reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(pred) + elem);
+    return f32x4{bf16_lo(raw.x), bf16_hi(raw.x), bf16_lo(raw.y), bf16_hi(raw.y)};
+  }
+  return *reinterpret_cast<const f32x4*>(static_cast<const float*>(pred) + elem);
+}
+
+template <bool kBf16>
+__device__ static inline void store_grad4(void* grad, int64_t elem, f32x4 g) {
+  if (kBf16) {
+    *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(grad) + elem) =
+        u32x2{pack_bf16x2(g.x, g.y), pack_bf16x2(g.z, g.w)};
+  } else {
+    *reinterpret_cast<f32x4*>(static_cast<float*>(grad) + elem) = g;
+  }
+}
+
+// NV = 16-byte groups per lane; D / 4 <= 64 NV.
+template <int NV, bool kBf16>
+__global__ __launch_bounds__(kLossThreads) void normpix_loss_kernel(LossArgs a) {
+  const int lane = threadIdx.x % kWave;
+  const int wave_in_grid = blockIdx.x * kLossWaves + threadIdx.x / kWave;
+  const int waves = gridDim.x * kLossWaves;
+  const int D = a.D, D4 = a.D >> 2;
+  const float inv_d = 1.0f / (float)D;
+  const float inv_dm1 = 1.0f / (float)(D - 1);
+  double acc = 0.0;
+
+  for (int64_t row = wave_in_grid; row < a.rows; row += waves) {
+    const int64_t row_elem = row * D;
+    if (a.mask[row] == 0) {
+      if (a.grad) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+          const int g = lane + v * kWave;
+          if (g < D4) store_grad4<kBf16>(a.grad, row_elem + 4 * g, f32x4{0.f, 0.f, 0.f, 0.f});
+        }
+      }
+      continue;
+    }
+    f32x4 t[NV], q[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const int g = lane + v * kWave;
+      if (g < D4) {
+        t[v] = *reinterpret_cast<const f32x4*>(a.target + row_elem + 4 * g);
+        q[v] = load_pred4<kBf16>(a.pred, row_elem + 4 * g);
+      } else {
+        t[v] = f32x4{0.f, 0.f, 0.f, 0.f};
+        q[v] = t[v];
+      }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) s += (t[v].x + t[v].y) + (t[v].z + t[v].w);
+    const float mu = wave_sum(s) * inv_d;
+    float ss = 0.f;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const int g = lane + v * kWave;
+      t[v] = t[v] - mu;
+      if (g < D4) ss += (t[v].x * t[v].x + t[v].y * t[v].y) + (t[v].z * t[v].z + t[v].w * t[v].w);
+    }
+    const float var = wave_sum(ss) * inv_dm1;
+    const float rstd = 1.0f / sqrtf(var + a.eps);
+    float sq = 0.f;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const int g = lane + v * kWave;
+      const f32x4 diff = q[v] - t[v] * rstd;
+      if (g < D4) {
+        sq += (diff.x * diff.x + diff.y * diff.y) + (diff.z * diff.z + diff.w * diff.w);
+        if (a.grad) store_grad4<kBf16>(a.grad, row_elem + 4 * g, diff * a.gscale);
+      }
+    }
+    acc += (double)sq;
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) a.partials[wave_in_grid] = acc;
+}
+
+// Any D (not a multiple of four, or too long for registers): three passes over the row.
+template <bool kBf16>
+__global__ __launch_bounds__(kLossThreads) void normpix_loss_scalar_kernel(LossArgs a) {
+  const int lane = threadIdx.x % kWave;
+  const int wave_in_grid = blockIdx.x * kLossWaves + threadIdx.x / kWave;
+  const int waves = gridDim.x * kLossWaves;
+  const int D = a.D;
+  double acc = 0.0;
+  for (int64_t row = wave_in_grid; row < a.rows; row += waves) {
+    const int64_t row_elem = row * D;
+    const float* t = a.target + row_elem;
+    if (a.mask[row] == 0) {
+      if (a.grad) {
+        for (int e = lane; e < D; e += kWave) {
+          if (kBf16) static_cast<uint16_t*>(a.grad)[row_elem + e] = 0;
+          else static_cast<float*>(a.grad)[row_elem + e] = 0.f;
+        }
+      }
+      continue;
+    }
+    float s = 0.f;
+    for (int e = lane; e < D; e += kWave) s += t[e];
+    const float mu = wave_sum(s) / (float)D;
+    float ss = 0.f;
+    for (int e = lane; e < D; e += kWave) ss += (t[e] - mu) * (t[e] - mu);
+    const float var = wave_sum(ss) / (float)(D - 1);
+    const float rstd = 1.0f / sqrtf(var + a.eps);
+    float sq = 0.f;
+    for (int e = lane; e < D; e += kWave) {
+      float q;
+      if (kBf16) q = __uint_as_float((uint32_t)static_cast<const uint16_t*>(a.pred)[row_elem + e] << 16);
+      else q = static_cast<const float*>(a.pred)[row_elem + e];
+      const float diff = q - (t[e] - mu) * rstd;
+      sq += diff * diff;
+      if (a.grad) {
+        if (kBf16) static_cast<uint16_t*>(a.grad)[row_elem + e] = (uint16_t)bf16_rne(diff * a.gscale);
+        else static_cast<float*>(a.grad)[row_elem + e] = diff * a.gscale;
+      }
+    }
+    acc += (double)sq;
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) a.partials[wave_in_grid] = acc;
+}
+
+// Adds the per-wavefront partials in a fixed order: thread i takes partials i, i + 256, ...,
+// then a tree over the 256 threads.
+__global__ __launch_bounds__(kLossThreads) void loss_finish_kernel(const double* partials, int n,
+                                                                  double inv_count, float* loss) {
+  __shared__ double red[kLossThreads];
+  double s = 0.0;
+  for (int i = threadIdx.x; i < n; i += kLossThreads) s += partials[i];
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int off = kLossThreads / 2; off > 0; off >>= 1) {
+    if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *loss = (float)(red[0] * inv_count);
+}
+
+int loss_grid_waves(int64_t rows) {
+  int64_t blocks = (rows + kLossWaves - 1) / kLossWaves;
+  if (blocks > kLossMaxBlocks) blocks = kLossMaxBlocks;
+  if (blocks < 1) blocks = 1;
+  return (int)blocks * kLossWaves;
+}
+
+template <bool kBf16>
+static void launch_vec(const LossArgs& a, dim3 grid, dim3 block, hipStream_t stream) {
+  const int nv = ((a.D >> 2) + kWave - 1) / kWave;
+  if (nv <= 1) hipLaunchKernelGGL((normpix_loss_kernel<1, kBf16>), grid, block, 0, stream, a);
+  else if (nv <= 2) hipLaunchKernelGGL((normpix_loss_kernel<2, kBf16>), grid, block, 0, stream, a);
+  else if (nv <= 3) hipLaunchKernelGGL((normpix_loss_kernel<3, kBf16>), grid, block, 0, stream, a);
+  else if (nv <= 4) hipLaunchKernelGGL((normpix_loss_kernel<4, kBf16>), grid, block, 0, stream, a);
+  else if (nv <= 6) hipLaunchKernelGGL((normpix_loss_kernel<6, kBf16>), grid, block, 0, stream, a);
+  else if (nv <= 8) hipLaunchKernelGGL((normpix_loss_kernel<8, kBf16>), grid, block, 0, stream, a);
+  else hipLaunchKernelGGL((normpix_loss_kernel<12, kBf16>), grid, block, 0, stream, a);
+}
+
+hipError_t launch_normpix_loss(const LossArgs& a, hipStream_t stream) {
+  dim3 grid(a.num_partials / kLossWaves), block(kLossThreads);
+  const bool vec = (a.D & 3) == 0 && (a.D >> 2) <= 12 * kWave;
+  if (vec) {
+    if (a.pred_bf16) launch_vec<true>(a, grid, block, stream);
+    else launch_vec<false>(a, grid, block, stream);
+  } else {
+    if (a.pred_bf16) hipLaunchKernelGGL(normpix_loss_scalar_kernel<true>, grid, block, 0, stream, a);
+    else hipLaunchKernelGGL(normpix_loss_scalar_kernel<false>, grid, block, 0, stream, a);
+  }
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  hipLaunchKernelGGL(loss_finish_kernel, dim3(1), block, 0, stream, a.partials, a.num_partials,
+                     a.inv_count, a.loss);
+  return hipGetLastError();
+}
+
+}  // namespace mae

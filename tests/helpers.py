@@ -1,0 +1,106 @@
+"""Shared plumbing of the GPU parity tests: upload inputs, call the C ABI through the binding,
+bring results back as NumPy arrays, and the tolerance checks written out."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import paper_2404_00509_amd as mae
+
+# fp32 tolerance of the path (pixels, loss, gradient): |gpu - ref| <= ATOL + RTOL * |ref|
+ATOL = 1e-5
+RTOL = 1e-5
+# bf16 outputs: relative 1e-2 (bf16 rounding is 2^-9), plus the fp32 tolerance near zero
+BF16_RTOL = 1e-2
+
+
+def assert_close(gpu, ref, atol=ATOL, rtol=RTOL, what=""):
+    gpu = np.asarray(gpu, np.float64)
+    ref = np.asarray(ref, np.float64)
+    assert gpu.shape == ref.shape, (what, gpu.shape, ref.shape)
+    err = np.abs(gpu - ref)
+    bound = atol + rtol * np.abs(ref)
+    bad = err > bound
+    if bad.any():
+        i = np.unravel_index(np.argmax(err - bound), err.shape)
+        raise AssertionError(f"{what}: {int(bad.sum())} of {bad.size} values out of tolerance; "
+                             f"worst at {i}: gpu {gpu[i]!r} ref {ref[i]!r} err {err[i]:.3e}")
+
+
+def to_device(images, offsets, heights, widths):
+    dev = "cuda"
+    return (torch.from_numpy(images).to(dev), torch.from_numpy(offsets).to(dev),
+            torch.from_numpy(heights).to(dev), torch.from_numpy(widths).to(dev))
+
+
+def gpu_prep(images, offsets, heights, widths, *, want_target=True, bf16=False, device_inputs=None,
+             poison=True, **kw):
+    """Run mae_prep_batch once.  Returns (dict of torch device tensors, desc)."""
+    dimg = device_inputs if device_inputs is not None else to_device(images, offsets, heights,
+                                                                     widths)
+    desc = mae.make_prep_desc(*dimg, out_dtype=mae.MAE_BF16 if bf16 else mae.MAE_F32, **kw)
+    buf = mae.alloc_prep_buffers(desc, want_target=want_target)
+    if poison:  # make values the kernels fail to write visible
+        buf.visible.fill_(float("nan"))
+        buf.mask.fill_(0xEE)
+        buf.ids_restore.fill_(-7)
+        buf.ids_keep.fill_(-7)
+        buf.crop.fill_(-7)
+        if buf.target is not None:
+            buf.target.fill_(float("nan"))
+    mae.mae_prep_batch(desc, buf.visible, buf.mask, buf.ids_restore, buf.ids_keep, buf.target,
+                       buf.crop, buf.workspace)
+    torch.cuda.synchronize()
+    return buf, desc, dimg
+
+
+def prep_to_numpy(buf, rows=None):
+    sel = slice(None) if rows is None else torch.as_tensor(rows, device=buf.mask.device)
+    out = {
+        "visible": buf.visible[sel].float().cpu().numpy(),
+        "mask": buf.mask[sel].cpu().numpy(),
+        "ids_restore": buf.ids_restore[sel].cpu().numpy(),
+        "ids_keep": buf.ids_keep[sel].cpu().numpy(),
+        "crop": buf.crop[sel].cpu().numpy(),
+    }
+    if buf.target is not None:
+        out["target"] = buf.target[sel].cpu().numpy()
+    return out
+
+
+def check_prep_against_oracle(gpu, ref, bf16=False, what=""):
+    """Integers bit-exact, pixels within the stated tolerance."""
+    np.testing.assert_array_equal(gpu["crop"][:, :5], ref["crop"], err_msg=what + " crop/flip")
+    assert np.all(gpu["crop"][:, 5] == 1), what + " valid flag"
+    np.testing.assert_array_equal(gpu["ids_restore"], ref["ids_restore"], err_msg=what)
+    np.testing.assert_array_equal(gpu["ids_keep"], ref["ids_keep"], err_msg=what)
+    np.testing.assert_array_equal(gpu["mask"], ref["mask"], err_msg=what)
+    if "target" in gpu and ref.get("target") is not None:
+        assert_close(gpu["target"], ref["target"], what=what + " target")
+    if ref.get("visible") is not None:
+        if bf16:
+            assert_close(gpu["visible"], ref["visible"], atol=ATOL, rtol=BF16_RTOL,
+                         what=what + " visible(bf16)")
+        else:
+            assert_close(gpu["visible"], ref["visible"], what=what + " visible")
+
+
+def gpu_loss(pred, target, mask, *, num_masked, eps=1e-6, grad_scale=1.0, want_grad=True):
+    """pred/target/mask: torch device tensors.  Returns (loss float, grad tensor or None)."""
+    desc = mae.make_loss_desc(pred, target, mask, num_masked=num_masked, eps=eps,
+                              grad_scale=grad_scale)
+    ws = torch.empty(max(mae.mae_loss_workspace_bytes(desc), 256), dtype=torch.uint8,
+                     device=pred.device)
+    loss = torch.full((1,), float("nan"), dtype=torch.float32, device=pred.device)
+    grad = torch.full_like(pred, float("nan")) if want_grad else None
+    mae.mae_normpix_loss(desc, loss, grad, ws)
+    torch.cuda.synchronize()
+    return float(loss.item()), grad
+
+
+def check_grad(gpu_grad, ref_grad, D, M, grad_scale=1.0, bf16=False, what=""):
+    """Gradients are O(1/(D M)); compare them in units of 2 grad_scale / (D M)."""
+    unit = 2.0 * abs(grad_scale) / (float(D) * float(M))
+    g = np.asarray(gpu_grad, np.float64) / unit
+    r = np.asarray(ref_grad, np.float64) / unit
+    assert_close(g, r, atol=ATOL, rtol=BF16_RTOL if bf16 else RTOL, what=what + " grad")

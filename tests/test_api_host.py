@@ -1,0 +1,184 @@
+"""Host-side behaviour of the C ABI that needs no GPU: the library loads, exports every symbol the
+public header declares, and rejects bad descriptors before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+import torch
+
+import oracle
+import paper_2404_00509_amd as mae
+from paper_2404_00509_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000  # never dereferenced: argument errors are found before any launch
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(mae.LIB_PATH):
+        from paper_2404_00509_amd.build import build_hip
+        build_hip()
+    return mae.load()
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "mae_hip.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(mae_[a-z_]+)\s*\(", header))
+    assert declared == set(mae.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert mae.mae_version() >= 100
+
+
+def test_error_strings(lib):
+    seen = {mae.mae_error_string(s) for s in range(-7, 1)}
+    assert len(seen) == 8 and "unknown status" not in seen
+    assert mae.mae_error_string(-99) == "unknown status"
+
+
+def test_num_keep_matches_the_oracle(lib):
+    for L in (1, 16, 49, 100, 144, 196, 256):
+        for m in (0.0, 0.5, 0.66, 0.75, 0.8, 0.85, 1.0):
+            assert mae.mae_num_keep(L, m) == oracle.num_keep(L, m)
+    assert mae.mae_num_keep(100, 0.8) == 19
+    assert mae.mae_num_keep(0, 0.5) == -1 and mae.mae_num_keep(10, 1.5) == -1
+
+
+def _prep_desc(**over):
+    d = binding.MaePrepDesc()
+    d.B = 4
+    d.images = d.offsets = d.heights = d.widths = FAKE
+    d.images_bytes = 1 << 20
+    d.out_size, d.patch, d.num_keep = 224, 16, 49
+    d.scale_lo, d.scale_hi, d.ratio_lo, d.ratio_hi, d.flip_p = 0.2, 1.0, 0.75, 4 / 3, 0.5
+    d.mean = (C.c_float * 3)(*mae.IMAGENET_MEAN)
+    d.std = (C.c_float * 3)(*mae.IMAGENET_STD)
+    d.seed, d.batch_index, d.sample_base, d.noise_bits, d.out_dtype = 0, 0, 0, 32, 0
+    for k, v in over.items():
+        if k == "std":
+            d.std = (C.c_float * 3)(*v)
+        else:
+            setattr(d, k, v)
+    return d
+
+
+def _call_prep(lib, d, visible=FAKE, mask=FAKE, ids_restore=FAKE, workspace=FAKE, ws_bytes=1 << 20):
+    return lib.mae_prep_batch(C.byref(d), visible, mask, ids_restore, None, None, None, workspace,
+                              ws_bytes, None)
+
+
+@pytest.mark.parametrize("over,status", [
+    (dict(images=None), binding.MAE_ERR_NULL),
+    (dict(offsets=None), binding.MAE_ERR_NULL),
+    (dict(heights=None), binding.MAE_ERR_NULL),
+    (dict(widths=None), binding.MAE_ERR_NULL),
+    (dict(B=0), binding.MAE_ERR_SHAPE),
+    (dict(B=-3), binding.MAE_ERR_SHAPE),
+    (dict(out_size=230), binding.MAE_ERR_SHAPE),        # not a multiple of the patch
+    (dict(out_size=0), binding.MAE_ERR_SHAPE),
+    (dict(patch=0), binding.MAE_ERR_SHAPE),
+    (dict(num_keep=0), binding.MAE_ERR_SHAPE),
+    (dict(num_keep=197), binding.MAE_ERR_SHAPE),
+    (dict(out_size=272), binding.MAE_ERR_RANGE),        # 17 x 17 = 289 patches > 256
+    (dict(out_size=66, patch=33, num_keep=1), binding.MAE_ERR_RANGE),
+    (dict(images_bytes=0), binding.MAE_ERR_RANGE),
+    (dict(scale_lo=0.0), binding.MAE_ERR_RANGE),
+    (dict(scale_lo=0.9, scale_hi=0.5), binding.MAE_ERR_RANGE),
+    (dict(scale_hi=1.5), binding.MAE_ERR_RANGE),
+    (dict(ratio_lo=0.0), binding.MAE_ERR_RANGE),
+    (dict(ratio_lo=1.2, ratio_hi=1.1), binding.MAE_ERR_RANGE),
+    (dict(ratio_lo=0.5), binding.MAE_ERR_RANGE),        # ln below -1/2
+    (dict(ratio_hi=2.0), binding.MAE_ERR_RANGE),
+    (dict(flip_p=-0.1), binding.MAE_ERR_RANGE),
+    (dict(flip_p=1.1), binding.MAE_ERR_RANGE),
+    (dict(flip_p=float("nan")), binding.MAE_ERR_RANGE),
+    (dict(std=(0.2, 0.0, 0.2)), binding.MAE_ERR_RANGE),
+    (dict(noise_bits=0), binding.MAE_ERR_RANGE),
+    (dict(noise_bits=33), binding.MAE_ERR_RANGE),
+    (dict(sample_base=0xFFFFFFFF), binding.MAE_ERR_RANGE),
+    (dict(out_dtype=7), binding.MAE_ERR_DTYPE),
+])
+def test_prep_rejects_bad_descriptors(lib, over, status):
+    d = _prep_desc(**over)
+    assert _call_prep(lib, d) == status
+    assert lib.mae_prep_workspace_bytes(C.byref(d)) == 0
+
+
+def test_prep_rejects_bad_buffers(lib):
+    d = _prep_desc()
+    need = lib.mae_prep_workspace_bytes(C.byref(d))
+    assert need == 256 + 4 * 32
+    assert lib.mae_prep_batch(None, FAKE, FAKE, FAKE, None, None, None, FAKE, 1 << 20,
+                              None) == binding.MAE_ERR_NULL
+    assert _call_prep(lib, d, visible=None) == binding.MAE_ERR_NULL
+    assert _call_prep(lib, d, mask=None) == binding.MAE_ERR_NULL
+    assert _call_prep(lib, d, ids_restore=None) == binding.MAE_ERR_NULL
+    assert _call_prep(lib, d, visible=FAKE + 4) == binding.MAE_ERR_RANGE        # 16-byte alignment
+    assert _call_prep(lib, d, workspace=None) == binding.MAE_ERR_WORKSPACE
+    assert _call_prep(lib, d, workspace=FAKE + 64) == binding.MAE_ERR_WORKSPACE  # 256-byte alignment
+    assert _call_prep(lib, d, ws_bytes=need - 1) == binding.MAE_ERR_WORKSPACE
+
+
+def _loss_desc(**over):
+    d = binding.MaeLossDesc()
+    d.B, d.L, d.D = 2, 196, 768
+    d.pred = d.target = d.mask = FAKE
+    d.num_masked, d.eps, d.grad_scale, d.pred_dtype = 294, 1e-6, 1.0, 0
+    for k, v in over.items():
+        setattr(d, k, v)
+    return d
+
+
+@pytest.mark.parametrize("over,status", [
+    (dict(pred=None), binding.MAE_ERR_NULL),
+    (dict(target=None), binding.MAE_ERR_NULL),
+    (dict(mask=None), binding.MAE_ERR_NULL),
+    (dict(B=0), binding.MAE_ERR_SHAPE),
+    (dict(L=0), binding.MAE_ERR_SHAPE),
+    (dict(D=1), binding.MAE_ERR_RANGE),
+    (dict(D=4000), binding.MAE_ERR_RANGE),
+    (dict(num_masked=0), binding.MAE_ERR_RANGE),
+    (dict(eps=-1.0), binding.MAE_ERR_RANGE),
+    (dict(grad_scale=float("inf")), binding.MAE_ERR_RANGE),
+    (dict(pred_dtype=2), binding.MAE_ERR_DTYPE),
+])
+def test_loss_rejects_bad_descriptors(lib, over, status):
+    d = _loss_desc(**over)
+    assert lib.mae_normpix_loss(C.byref(d), FAKE, FAKE, FAKE, 1 << 20, None) == status
+    assert lib.mae_loss_workspace_bytes(C.byref(d)) == 0
+
+
+def test_loss_rejects_bad_buffers(lib):
+    d = _loss_desc()
+    need = lib.mae_loss_workspace_bytes(C.byref(d))
+    assert need > 0 and need % 8 == 0
+    assert lib.mae_normpix_loss(C.byref(d), None, FAKE, FAKE, need, None) == binding.MAE_ERR_NULL
+    assert lib.mae_normpix_loss(C.byref(d), FAKE, FAKE + 8, FAKE, need,
+                                None) == binding.MAE_ERR_RANGE
+    assert lib.mae_normpix_loss(C.byref(d), FAKE, FAKE, None, need,
+                                None) == binding.MAE_ERR_WORKSPACE
+    assert lib.mae_normpix_loss(C.byref(d), FAKE, FAKE, FAKE, need - 8,
+                                None) == binding.MAE_ERR_WORKSPACE
+    assert lib.mae_normpix_loss(None, FAKE, FAKE, FAKE, need, None) == binding.MAE_ERR_NULL
+
+
+@pytest.mark.skipif(torch.cuda.is_available(), reason="a GPU is visible")
+def test_valid_calls_report_no_device_without_a_gpu(lib):
+    # all arguments pass validation; with no device nothing is launched and nothing is read
+    assert _call_prep(lib, _prep_desc()) == binding.MAE_ERR_NO_DEVICE
+    d = _loss_desc()
+    assert lib.mae_normpix_loss(C.byref(d), FAKE, FAKE, FAKE, 1 << 20,
+                                None) == binding.MAE_ERR_NO_DEVICE
+    n = C.c_int32(0)
+    assert lib.mae_prep_status(FAKE, None, C.byref(n)) == binding.MAE_ERR_NO_DEVICE
+    assert lib.mae_prep_status(None, None, C.byref(n)) == binding.MAE_ERR_NULL
+
+
+def test_binding_does_not_fall_back_when_the_library_is_missing(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "libmae_hip.so"))
+    with pytest.raises(FileNotFoundError):
+        binding.load()
