@@ -1,0 +1,199 @@
+"""Benchmark of the MAE input-pipeline hot path on one MI355X.
+
+A step is one pass of the whole path over one batch: mae_prep_batch (crop parameters, masking
+order, fused crop/resize/flip/normalise/patchify/gather) followed by mae_normpix_loss (loss and
+gradient), on synthetic images already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E
+
+
+def algorithmic_bytes(wl, K):
+    """Bytes the method must move per launch (plain dataflow, target materialised once).
+
+    prep : read the crop bytes is data dependent (about half of each image); counted from the
+           crop boxes of the run.  write visible K*D*e + target L*D*4 + mask/ids.
+    loss : read pred and target of the masked rows, write the whole gradient.
+    """
+    e = 2 if wl.dtype == "bf16" else 4
+    prep_write = wl.B * (K * wl.D * e + wl.L * wl.D * 4 + wl.L * 5 + K * 4)
+    masked = wl.L - K
+    loss = wl.B * (masked * wl.D * (e + 4) + wl.L * wl.D * e + wl.L)
+    return prep_write, loss
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c4", choices=["c3", "c4", "c5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=4096, help="images timed on the CPU oracle")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="after the timed region, run one plain device copy of known size "
+                         "(grad <- pred) so that a counter run has a reference kernel")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this path has no multi-GPU part (samples are "
+              "independent; see DESIGN.md for how it would shard). Run with --gpus 1.",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2404_00509_amd as mae
+    from paper_2404_00509_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    mae.load()  # fail loudly if the HIP library is missing
+
+    wl = synth.WORKLOADS[args.workload]
+    bf16 = wl.dtype == "bf16"
+    K = mae.mae_num_keep(wl.L, wl.mask_ratio)
+    M = wl.B * (wl.L - K)
+
+    t0 = time.time()
+    images, offsets, heights, widths = synth.make_images(wl.kind, wl.B, seed=0)
+    gen_s = time.time() - t0
+    dev = [torch.from_numpy(a).cuda() for a in (images, offsets, heights, widths)]
+    desc = mae.make_prep_desc(*dev, out_size=wl.out_size, patch=wl.patch, num_keep=K, seed=0,
+                              batch_index=0, out_dtype=mae.MAE_BF16 if bf16 else mae.MAE_F32)
+    buf = mae.alloc_prep_buffers(desc)
+    gen = torch.Generator(device="cuda").manual_seed(1)
+    pred = torch.randn((wl.B, wl.L, wl.D), generator=gen, device="cuda", dtype=torch.float32)
+    if bf16:
+        pred = pred.to(torch.bfloat16)
+    grad = torch.empty_like(pred)
+    loss = torch.zeros(1, device="cuda")
+    ldesc = mae.make_loss_desc(pred, buf.target, buf.mask, num_masked=M)
+    lws = torch.empty(max(mae.mae_loss_workspace_bytes(ldesc), 256), dtype=torch.uint8,
+                      device="cuda")
+    stream = torch.cuda.current_stream()  # the stream the library launches on
+
+    def step(i, ev=None):
+        desc.batch_index = i
+        if ev is not None:
+            ev[0].record(stream)
+        mae.mae_prep_batch(desc, buf.visible, buf.mask, buf.ids_restore, buf.ids_keep, buf.target,
+                           buf.crop, buf.workspace, stream=stream)
+        if ev is not None:
+            ev[1].record(stream)
+        mae.mae_normpix_loss(ldesc, loss, grad, lws, stream=stream)
+        if ev is not None:
+            ev[2].record(stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, events[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    value = wl.B * args.steps / elapsed
+    prep_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    loss_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+    assert mae.mae_prep_status(buf.workspace) == 0
+    final_loss = float(loss.item())
+    if args.calibration_copy:
+        grad.copy_(pred)  # reads and writes pred.numel() * element_size bytes each
+        torch.cuda.synchronize()
+
+    crop = buf.crop.cpu().numpy().astype(np.int64)
+    crop_bytes = int((crop[:, 2] * crop[:, 3] * 3).sum())
+    prep_write, loss_bytes = algorithmic_bytes(wl, K)
+    prep_bytes = prep_write + crop_bytes
+    loss_gbps = loss_bytes / (loss_ms * 1e-3) / 1e9
+    prep_gbps = prep_bytes / (prep_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "images/sec and achieved HBM GB/s (% of peak) at 224px, B=4096, 1 MI355X",
+        "value": round(value, 1),
+        "unit": "images/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if bf16 else "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{wl.name}: B={wl.B} uint8 images (max side 256) -> {wl.out_size}px, "
+                        f"patch {wl.patch}, L={wl.L}, keep {K}, prep + normpix loss + grad",
+            "B": wl.B, "out_size": wl.out_size, "patch": wl.patch, "L": wl.L, "K": K, "D": wl.D,
+            "input_generation_s": round(gen_s, 1),
+        },
+        "roofline": {
+            "kernel": "normpix_loss_kernel (mae_normpix_loss; includes its 1-workgroup finish "
+                      "kernel)",
+            "bound": "hbm",
+            "achieved": round(loss_gbps, 1),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(loss_gbps / HBM_PEAK_GBPS, 4),
+            "traffic": None,
+            "algorithmic_bytes": loss_bytes,
+            "avg_ms": round(loss_ms, 4),
+        },
+        "kernels": {
+            "mae_prep_batch": {"avg_ms": round(prep_ms, 4), "algorithmic_bytes": prep_bytes,
+                               "achieved_GBps": round(prep_gbps, 1),
+                               "frac": round(prep_gbps / HBM_PEAK_GBPS, 4)},
+            "mae_normpix_loss": {"avg_ms": round(loss_ms, 4), "algorithmic_bytes": loss_bytes,
+                                 "achieved_GBps": round(loss_gbps, 1),
+                                 "frac": round(loss_gbps / HBM_PEAK_GBPS, 4)},
+        },
+        "step_GBps": round((prep_bytes + loss_bytes) / (ms_per_step * 1e-3) / 1e9, 1),
+        "step_frac_of_hbm_peak": round((prep_bytes + loss_bytes) / (ms_per_step * 1e-3) / 1e9
+                                       / HBM_PEAK_GBPS, 4),
+        "loss_value": final_loss,
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+
+        n = min(args.cpu_sample, wl.B)
+        pred_host = pred[:n].float().cpu().numpy()
+        kw = dict(out_size=wl.out_size, patch=wl.patch, num_keep=K, seed=0, batch_index=0)
+        t0 = time.perf_counter()
+        ref = oracle.prep_batch(images, offsets, heights, widths, b_begin=0, b_end=n, **kw)
+        oracle.normpix_loss(pred_host, ref["target"], ref["mask"], num_masked=n * (wl.L - K))
+        cpu_s = time.perf_counter() - t0
+        out["cpu_baseline"] = {
+            "value": round(n / cpu_s, 1),
+            "unit": "images/s",
+            "cores": oracle.threads(),
+            "kind": "oracle",
+            "sample": f"first {n} images of the same batch, prep + loss + grad, "
+                      f"{cpu_s:.2f} s wall",
+        }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -89,6 +89,9 @@ typedef struct {
   int32_t noise_bits;      /* 1..32 bits of masking noise per patch; 32 in production, small
                               values force ties (equal keys keep index order)                   */
   int32_t out_dtype;       /* mae_dtype of `visible`                                            */
+  int32_t max_image_side;  /* tuning hint: largest H or W in the batch, 0 = 256 (the "maximum
+                              side 256" dataset variant).  It sizes the on-chip staging buffer;
+                              larger images than hinted stay correct but take a slower path     */
 } mae_prep_desc;
 
 /* Outputs (device):

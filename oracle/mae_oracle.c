@@ -319,7 +319,10 @@ int32_t mae_oracle_normpix_loss(int32_t B, int32_t L, int32_t D, const float* pr
     return -1;
   int64_t rows = (int64_t)B * L;
   double M = (double)num_masked;
-  double total = 0.0;
+  double* row_losses = (double*)malloc(sizeof(double) * (size_t)rows);
+  if (!row_losses) return -1;
+  /* rows are independent; the sum over rows below is taken in row order */
+#pragma omp parallel for schedule(static)
   for (int64_t row = 0; row < rows; ++row) {
     const float* t = target + row * D;
     const float* q = pred + row * D;
@@ -340,9 +343,12 @@ int32_t mae_oracle_normpix_loss(int32_t B, int32_t L, int32_t D, const float* pr
         grad[row * D + e] =
             mask[row] ? (float)(grad_scale * 2.0 * diff / ((double)D * M)) : 0.0f;
     }
-    row_loss /= (double)D;
-    if (mask[row]) total += row_loss;
+    row_losses[row] = row_loss / (double)D;
   }
+  double total = 0.0;
+  for (int64_t row = 0; row < rows; ++row)
+    if (mask[row]) total += row_losses[row];
+  free(row_losses);
   *loss_out = total / M;
   return 0;
 }

@@ -51,6 +51,7 @@ class MaePrepDesc(C.Structure):
         ("sample_base", C.c_uint32),
         ("noise_bits", C.c_int32),
         ("out_dtype", C.c_int32),
+        ("max_image_side", C.c_int32),
     ]
 
 
@@ -133,7 +134,7 @@ def _stream(stream):
 def make_prep_desc(images, offsets, heights, widths, *, out_size, patch, num_keep,
                    scale=(0.2, 1.0), ratio=(3.0 / 4.0, 4.0 / 3.0), flip_p=0.5, mean=IMAGENET_MEAN,
                    std=IMAGENET_STD, seed=0, batch_index=0, sample_base=0, noise_bits=32,
-                   out_dtype=MAE_F32) -> MaePrepDesc:
+                   out_dtype=MAE_F32, max_image_side=0) -> MaePrepDesc:
     d = MaePrepDesc()
     d.B = int(heights.numel())
     d.images = images.data_ptr()
@@ -147,6 +148,7 @@ def make_prep_desc(images, offsets, heights, widths, *, out_size, patch, num_kee
     d.std = (C.c_float * 3)(*std)
     d.seed, d.batch_index, d.sample_base = seed, batch_index, sample_base
     d.noise_bits, d.out_dtype = noise_bits, out_dtype
+    d.max_image_side = max_image_side
     return d
 
 

@@ -44,6 +44,7 @@ int validate_prep(const mae_prep_desc* d, PrepShape* shape) {
   if (d->noise_bits < 1 || d->noise_bits > 32) return MAE_ERR_RANGE;
   if ((uint64_t)d->sample_base + (uint64_t)d->B > 0x100000000ull) return MAE_ERR_RANGE;
   if (d->out_dtype != MAE_F32 && d->out_dtype != MAE_BF16) return MAE_ERR_DTYPE;
+  if (d->max_image_side < 0 || d->max_image_side > 32767) return MAE_ERR_RANGE;
   if (shape) {
     shape->G = (int32_t)G;
     shape->L = (int32_t)L;
@@ -153,11 +154,14 @@ int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t
   ca.K = d->num_keep;
   ca.D = sh.D;
   ca.visible_bf16 = d->out_dtype == MAE_BF16;
+  ca.tile_pixels = mae::crop_tile_pixels(d->out_size, d->patch,
+                                         d->max_image_side > 0 ? d->max_image_side : 256);
   for (int c = 0; c < 3; ++c) {
     ca.nscale[c] = (float)(1.0 / (255.0 * (double)d->std[c]));
     ca.nbias[c] = (float)(-(double)d->mean[c] / (double)d->std[c]);
   }
   ca.images = d->images;
+  ca.images_bytes = d->images_bytes;
   ca.offsets = d->offsets;
   ca.widths = d->widths;
   ca.ids_restore = ids_restore;

@@ -2,12 +2,20 @@
 // + ViT patch split (Sec. 3) + gather of the visible patches (Sec. 2), in one pass: every source
 // byte is read from HBM once and every output value is written once, straight into patch order.
 //
-// One workgroup per (image, row of patches).  The source rows that this patch row taps are staged
-// in LDS as 4-byte RGBx pixels, together with one table of horizontal taps (S entries) and one of
-// vertical taps (p entries).  Then each wavefront produces whole patches: lane i writes the i-th
-// 16-byte group of the patch, so that every store instruction covers 1 KiB of contiguous memory.
-// A group of four consecutive values spans two neighbouring pixels; one byte-permute per tap row
-// pulls exactly the four bytes needed out of the two RGBx words.
+// One workgroup per (image, row of patches).
+//  * Staging.  The source rows that this patch row taps are brought into LDS as 4-byte RGBx pixel
+//    words.  Lane i of a wavefront loads the 16 bytes that hold pixels 4i..4i+3 of a row (one
+//    4-byte-aligned global_load_dwordx4; the row's misalignment is taken out with byte-align
+//    operations in registers) and writes four pixel words with one ds_write_b128.  All loads of a
+//    wavefront (up to six rows) are issued before the first is consumed, and the tap tables
+//    (S horizontal entries, p vertical entries, integer tap positions + fp32 weights) are built
+//    while they are in flight.
+//  * Compute + store.  Each wavefront then produces whole patches: lane i writes the i-th 16-byte
+//    group of the patch, so every store instruction covers 1 KiB of contiguous memory.  A group
+//    of four consecutive values spans two neighbouring pixels; the taps x and x+1 come from one
+//    ds_read2_b32 per row, and one byte-permute per tap row pulls exactly the four bytes needed
+//    out of the two pixel words.  Nothing inside the loop reads global memory, so the stores of
+//    one patch never have to complete before the next patch is computed.
 #include "mae_device.hpp"
 #include "mae_kernels.hpp"
 
@@ -15,12 +23,13 @@ namespace mae {
 
 constexpr int kCropThreads = 256;
 constexpr int kCropWaves = kCropThreads / kWave;
-constexpr int kTilePixels = 8192;  // 32 KiB of staged source pixels per workgroup
-constexpr int kMaxOut = 512;       // S
-constexpr int kMaxPatch = 32;      // p
+constexpr int kStageRows = 6;  // rows per wavefront whose loads are issued together
+constexpr int kCropMaxLds = 64 * 1024;  // dynamic LDS available without opting in to more
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
 
 // Source taps of output index o when `len` source pixels are resized to S: sample position
 // (o + 1/2) len / S - 1/2 kept as the exact fraction n / (2 S); taps clamped to [0, len).
@@ -41,11 +50,18 @@ __device__ static inline uint32_t load_rgbx(const uint8_t* p) {
   return (uint32_t)p[0] | ((uint32_t)p[1] << 8) | ((uint32_t)p[2] << 16);
 }
 
+// Pixel words at x and x + 1 of one row.  In the tile the word after the last pixel of a row is
+// readable (its weight is zero); in global memory the second tap is clamped instead.
 template <bool kLds>
-__device__ static inline uint32_t fetch(const uint32_t* tile, const uint8_t* base, int row_off,
-                                        int x) {
-  if (kLds) return tile[row_off + x];
-  return load_rgbx(base + row_off + 3 * x);
+__device__ static inline void fetch2(const uint32_t* tile, const uint8_t* base, uint32_t row_off,
+                                     int x, int cw, uint32_t& v0, uint32_t& v1) {
+  if (kLds) {
+    v0 = tile[row_off + x];
+    v1 = tile[row_off + x + 1];
+  } else {
+    v0 = load_rgbx(base + ((size_t)row_off + (size_t)(3 * x)));
+    v1 = load_rgbx(base + ((size_t)row_off + (size_t)(3 * min(x + 1, cw - 1))));
+  }
 }
 
 template <int J>
@@ -53,17 +69,41 @@ __device__ static inline float byte_to_float(uint32_t v) {
   return (float)((v >> (8 * J)) & 0xFFu);
 }
 
-// The compute + store phase of one workgroup.  kLds: taps come from the staged tile, otherwise
-// straight from global memory (crops too large to stage).
+// 16 bytes at a 4-byte-aligned address; `safe` says that they all lie inside the image buffer.
+__device__ static inline u32x4 load16(const uint8_t* p, bool safe, const uint8_t* lo,
+                                      const uint8_t* hi) {
+  if (safe) return *reinterpret_cast<const u32x4_a4*>(p);
+  uint32_t w[4] = {0u, 0u, 0u, 0u};  // first or last bytes of the buffer: take what is inside
+  for (int q = 0; q < 16; ++q) {
+    if (p + q >= lo && p + q < hi) w[q >> 2] |= (uint32_t)p[q] << (8 * (q & 3));
+  }
+  return u32x4{w[0], w[1], w[2], w[3]};
+}
+
+// 16 loaded bytes, of which the 12 bytes of four pixels start at byte s (0..3) -> 4 RGBx words.
+__device__ static inline u32x4 to_pixels(u32x4 d, uint32_t s) {
+  const uint32_t e0 = __builtin_amdgcn_alignbyte(d.y, d.x, s);
+  const uint32_t e1 = __builtin_amdgcn_alignbyte(d.z, d.y, s);
+  const uint32_t e2 = __builtin_amdgcn_alignbyte(d.w, d.z, s);
+  return u32x4{e0, __builtin_amdgcn_alignbyte(e1, e0, 3u), __builtin_amdgcn_alignbyte(e2, e1, 2u),
+               e2 >> 8};
+}
+
+// The compute + store phase of one workgroup.  kLds: taps come from the staged tile (row offsets
+// in pixel words), otherwise straight from global memory (row offsets in bytes; crops too large
+// to stage).  my_rank holds, in lane i, the noise rank of patch i of this row of patches.
 template <bool kLds, bool kBf16>
 __device__ static void produce_patches(const CropArgs& a, const uint32_t* tile, const u32x2* xtab,
-                                       const u32x2* ytab, const uint8_t* base, int row_stride,
-                                       int b, int gy, float inv_p) {
+                                       const u32x4* ytab, const uint8_t* base, int b, int gy,
+                                       int cw, int my_rank) {
   const int lane = threadIdx.x % kWave;
-  const int wave = threadIdx.x / kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int p = a.p, D = a.D, G = a.G;
   const int D4 = D >> 2;
   const int pp = p * p;
+  const float inv_p = 1.0f / (float)p;
+  const float ns0 = a.nscale[0], ns1 = a.nscale[1], ns2 = a.nscale[2];
+  const float nb0 = a.nbias[0], nb1 = a.nbias[1], nb2 = a.nbias[2];
 
   for (int k0 = 0; k0 < D4; k0 += kWave) {
     const int e4 = k0 + lane;
@@ -77,54 +117,48 @@ __device__ static void produce_patches(const CropArgs& a, const uint32_t* tile, 
     const int pxA = qA - pyA * p;
     const int pyB = (int)(((float)qB + 0.5f) * inv_p);
     const int pxB = qB - pyB * p;
-    const u32x2 ya = ytab[pyA], yb = ytab[pyB];
-    const int rowA0 = (int)(ya.x & 0xFFFFu) * row_stride, rowA1 = (int)(ya.x >> 16) * row_stride;
-    const int rowB0 = (int)(yb.x & 0xFFFFu) * row_stride, rowB1 = (int)(yb.x >> 16) * row_stride;
-    const float fyA = __uint_as_float(ya.y), fyB = __uint_as_float(yb.y);
+    const u32x4 ya = ytab[pyA], yb = ytab[pyB];
+    const uint32_t rowA0 = ya.x, rowA1 = ya.y, rowB0 = yb.x, rowB1 = yb.y;
+    const float fyA = __uint_as_float(ya.z), fyB = __uint_as_float(yb.z);
     // byte selectors: A's bytes are 0..2, B's bytes are 4..6 of the 64-bit pair {B, A}
     const uint32_t sel = cA == 0 ? 0x04020100u : (cA == 1 ? 0x05040201u : 0x06050402u);
-    const int nA = 3 - cA;  // how many of the four values come from pixel A
+    const int nA = 3 - cA;  // how many of the four values come from pixel A (1..3)
     float sc[4], bi[4], fy[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       int c = cA + j;
       c = c >= 3 ? c - 3 : c;
       c = c >= 3 ? c - 3 : c;
-      sc[j] = c == 0 ? a.nscale[0] : (c == 1 ? a.nscale[1] : a.nscale[2]);
-      bi[j] = c == 0 ? a.nbias[0] : (c == 1 ? a.nbias[1] : a.nbias[2]);
-      fy[j] = j < nA ? fyA : fyB;
+      sc[j] = c == 0 ? ns0 : (c == 1 ? ns1 : ns2);
+      bi[j] = c == 0 ? nb0 : (c == 1 ? nb1 : nb2);
+      fy[j] = j == 0 ? fyA : (j == 3 ? fyB : (j < nA ? fyA : fyB));
     }
 
     for (int gx = wave; gx < G; gx += kCropWaves) {
       const int l = gy * G + gx;
-      const int rank = a.ids_restore[(int64_t)b * a.L + l];
+      const int rank = __builtin_amdgcn_readlane(my_rank, gx);
       const u32x2 xa = xtab[gx * p + pxA], xb = xtab[gx * p + pxB];
-      const int xa0 = (int)(xa.x & 0xFFFFu), xa1 = (int)(xa.x >> 16);
-      const int xb0 = (int)(xb.x & 0xFFFFu), xb1 = (int)(xb.x >> 16);
       const float fxA = __uint_as_float(xa.y), fxB = __uint_as_float(xb.y);
-      const uint32_t A00 = fetch<kLds>(tile, base, rowA0, xa0);
-      const uint32_t A01 = fetch<kLds>(tile, base, rowA0, xa1);
-      const uint32_t A10 = fetch<kLds>(tile, base, rowA1, xa0);
-      const uint32_t A11 = fetch<kLds>(tile, base, rowA1, xa1);
-      const uint32_t B00 = fetch<kLds>(tile, base, rowB0, xb0);
-      const uint32_t B01 = fetch<kLds>(tile, base, rowB0, xb1);
-      const uint32_t B10 = fetch<kLds>(tile, base, rowB1, xb0);
-      const uint32_t B11 = fetch<kLds>(tile, base, rowB1, xb1);
+      uint32_t A00, A01, A10, A11, B00, B01, B10, B11;
+      fetch2<kLds>(tile, base, rowA0, (int)xa.x, cw, A00, A01);
+      fetch2<kLds>(tile, base, rowA1, (int)xa.x, cw, A10, A11);
+      fetch2<kLds>(tile, base, rowB0, (int)xb.x, cw, B00, B01);
+      fetch2<kLds>(tile, base, rowB1, (int)xb.x, cw, B10, B11);
       const uint32_t P00 = __builtin_amdgcn_perm(B00, A00, sel);
       const uint32_t P01 = __builtin_amdgcn_perm(B01, A01, sel);
       const uint32_t P10 = __builtin_amdgcn_perm(B10, A10, sel);
       const uint32_t P11 = __builtin_amdgcn_perm(B11, A11, sel);
 
       float out[4];
-#define MAE_BLEND(J)                                                   \
-  {                                                                    \
-    const float fx = (J) < nA ? fxA : fxB;                             \
-    const float a00 = byte_to_float<J>(P00), a01 = byte_to_float<J>(P01); \
-    const float a10 = byte_to_float<J>(P10), a11 = byte_to_float<J>(P11); \
-    const float rt = a00 + fx * (a01 - a00);                           \
-    const float rb = a10 + fx * (a11 - a10);                           \
-    const float v = rt + fy[J] * (rb - rt);                            \
-    out[J] = v * sc[J] + bi[J];                                        \
+#define MAE_BLEND(J)                                                                 \
+  {                                                                                  \
+    const float fx = (J) == 0 ? fxA : ((J) == 3 ? fxB : ((J) < nA ? fxA : fxB));     \
+    const float a00 = byte_to_float<J>(P00), a01 = byte_to_float<J>(P01);            \
+    const float a10 = byte_to_float<J>(P10), a11 = byte_to_float<J>(P11);            \
+    const float rt = a00 + fx * (a01 - a00);                                         \
+    const float rb = a10 + fx * (a11 - a10);                                         \
+    const float v = rt + fy[J] * (rb - rt);                                          \
+    out[J] = v * sc[J] + bi[J];                                                      \
   }
       MAE_BLEND(0) MAE_BLEND(1) MAE_BLEND(2) MAE_BLEND(3)
 #undef MAE_BLEND
@@ -149,11 +183,13 @@ __device__ static void produce_patches(const CropArgs& a, const uint32_t* tile, 
   }
 }
 
+// Dynamic LDS: [ tile: a.tile_pixels + 4 words | xtab: S x 8 bytes | ytab: p x 16 bytes ].
 template <bool kBf16>
 __global__ __launch_bounds__(kCropThreads) void crop_patch_kernel(CropArgs a) {
-  __shared__ uint32_t tile[kTilePixels];
-  __shared__ u32x2 xtab[kMaxOut];
-  __shared__ u32x2 ytab[kMaxPatch];
+  extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+  uint32_t* tile = lds;
+  u32x4* ytab = reinterpret_cast<u32x4*>(lds + a.tile_pixels + 4);  // row y0, row y1, weight
+  u32x2* xtab = reinterpret_cast<u32x2*>(ytab + a.p);                // x0, weight of x0 + 1
 
   const uint32_t tile_id = xcd_remap(blockIdx.x, gridDim.x);
   const int b = (int)(tile_id / (uint32_t)a.G);
@@ -164,6 +200,7 @@ __global__ __launch_bounds__(kCropThreads) void crop_patch_kernel(CropArgs a) {
   const int S = a.S, p = a.p;
   const int W = a.widths[b];
   const int tid = threadIdx.x;
+  const int lane = tid % kWave, wave = tid / kWave;
 
   // rows of the crop that this row of patches taps
   int ylo, yhi, t0, t1;
@@ -171,37 +208,77 @@ __global__ __launch_bounds__(kCropThreads) void crop_patch_kernel(CropArgs a) {
   resize_taps(gy * p, rec.ch, S, ylo, t1, tf);
   resize_taps(gy * p + p - 1, rec.ch, S, t0, yhi, tf);
   const int nrows = yhi - ylo + 1;
-  const bool use_lds = nrows * rec.cw <= kTilePixels;
+  const int ng = (rec.cw + 3) >> 2;  // groups of four pixels per staged row
+  const int pitch = 4 * ng;          // pixel words per staged row
+  const bool use_lds = nrows * pitch <= a.tile_pixels;
+  const bool batched = use_lds && ng <= kWave;
 
+  // first pixel of the first tapped row
   const uint8_t* base = a.images + a.offsets[b] + ((int64_t)(rec.top + ylo) * W + rec.left) * 3;
+  const int row_bytes = 3 * W;
+  const uint8_t* img_end = a.images + a.images_bytes;
+  u32x4* tile4 = reinterpret_cast<u32x4*>(tile);
+
+  // noise rank of each patch of this row, one per lane; read back with readlane in the loop
+  const int my_rank = lane < a.G ? a.ids_restore[(int64_t)b * a.L + gy * a.G + lane] : 0x7fffffff;
+
+  u32x4 d[kStageRows];
+  if (batched) {  // these loads stay in flight while the tap tables are built
+#pragma unroll
+    for (int u = 0; u < kStageRows; ++u) {
+      const int r = wave + u * kCropWaves;
+      d[u] = u32x4{0u, 0u, 0u, 0u};
+      if (r < nrows && lane < ng) {
+        const uint8_t* row = base + (int64_t)r * row_bytes;
+        const uint8_t* arow = row - (reinterpret_cast<uintptr_t>(row) & 3u);
+        const bool safe = arow >= a.images && arow + 12 * ng + 4 <= img_end;
+        d[u] = load16(arow + 12 * lane, safe, a.images, img_end);
+      }
+    }
+  }
 
   for (int ox = tid; ox < S; ox += kCropThreads) {
     int x0, x1;
     float f;
     resize_taps(rec.flip ? S - 1 - ox : ox, rec.cw, S, x0, x1, f);
-    xtab[ox] = u32x2{(uint32_t)x0 | ((uint32_t)x1 << 16), __float_as_uint(f)};
+    // at the right edge both taps are the last pixel: weight 0 makes the second tap irrelevant
+    xtab[ox] = u32x2{(uint32_t)x0, __float_as_uint(x1 == x0 ? 0.0f : f)};
   }
   if (tid < p) {
     int y0, y1;
     float f;
     resize_taps(gy * p + tid, rec.ch, S, y0, y1, f);
-    ytab[tid] = u32x2{(uint32_t)(y0 - ylo) | ((uint32_t)(y1 - ylo) << 16), __float_as_uint(f)};
+    const uint32_t stride = use_lds ? (uint32_t)pitch : (uint32_t)row_bytes;
+    ytab[tid] = u32x4{(uint32_t)(y0 - ylo) * stride, (uint32_t)(y1 - ylo) * stride,
+                      __float_as_uint(f), 0u};
   }
 
-  if (use_lds) {
-    const int lane = tid % kWave, wave = tid / kWave;
-    for (int yy = wave; yy < nrows; yy += kCropWaves) {
-      const uint8_t* src = base + (int64_t)yy * W * 3;
-      for (int xx = lane; xx < rec.cw; xx += kWave) tile[yy * rec.cw + xx] = load_rgbx(src + 3 * xx);
+  if (batched) {
+#pragma unroll
+    for (int u = 0; u < kStageRows; ++u) {
+      const int r = wave + u * kCropWaves;
+      if (r < nrows && lane < ng) {
+        const uint32_t s = (uint32_t)reinterpret_cast<uintptr_t>(base + (int64_t)r * row_bytes) & 3u;
+        tile4[r * ng + lane] = to_pixels(d[u], s);
+      }
+    }
+  }
+  if (use_lds) {  // rows beyond the first batch, and crops wider than 256 pixels
+    for (int r = batched ? wave + kStageRows * kCropWaves : wave; r < nrows; r += kCropWaves) {
+      const uint8_t* row = base + (int64_t)r * row_bytes;
+      const uint32_t s = (uint32_t)reinterpret_cast<uintptr_t>(row) & 3u;
+      const uint8_t* arow = row - s;
+      const bool safe = arow >= a.images && arow + 12 * ng + 4 <= img_end;
+      for (int g = lane; g < ng; g += kWave)
+        tile4[r * ng + g] = to_pixels(load16(arow + 12 * g, safe, a.images, img_end), s);
     }
   }
   __syncthreads();
 
-  const float inv_p = 1.0f / (float)p;
   if (use_lds) {
-    produce_patches<true, kBf16>(a, tile, xtab, ytab, base, rec.cw, b, gy, inv_p);
+    produce_patches<true, kBf16>(a, tile, xtab, ytab, base, b, gy, rec.cw, my_rank);
   } else {
-    produce_patches<false, kBf16>(a, tile, xtab, ytab, base, 3 * W, b, gy, inv_p);
+    produce_patches<false, kBf16>(a, tile, xtab, ytab, base, b, gy, rec.cw, my_rank);
   }
 }
 
@@ -248,13 +325,29 @@ __global__ __launch_bounds__(kCropThreads) void crop_patch_scalar_kernel(CropArg
   }
 }
 
+// Staging tile for one row of patches when no image side exceeds max_side: the rows tapped are
+// at most ceil((p - 1) max_side / S) + 2, each up to max_side pixels (rounded up to 4).
+int crop_tile_pixels(int S, int p, int max_side) {
+  const int64_t rows = ((int64_t)(p - 1) * max_side + S - 1) / S + 2;
+  int64_t px = rows * ((max_side + 3) & ~3);
+  const int64_t cap = (kCropMaxLds - 16 - 8 * (int64_t)S - 16 * (int64_t)p) / 4;
+  if (px > cap) px = cap;
+  if (px < 1024) px = 1024;
+  return (int)(px & ~3);
+}
+
+size_t crop_lds_bytes(int tile_pixels, int S, int p) {
+  return (size_t)(tile_pixels + 4) * 4 + (size_t)S * 8 + (size_t)p * 16;
+}
+
 hipError_t launch_crop_patch(const CropArgs& a, hipStream_t stream) {
   if ((a.D & 3) == 0) {
     dim3 grid((uint32_t)a.B * (uint32_t)a.G), block(kCropThreads);
+    const size_t lds = crop_lds_bytes(a.tile_pixels, a.S, a.p);
     if (a.visible_bf16) {
-      hipLaunchKernelGGL(crop_patch_kernel<true>, grid, block, 0, stream, a);
+      hipLaunchKernelGGL(crop_patch_kernel<true>, grid, block, lds, stream, a);
     } else {
-      hipLaunchKernelGGL(crop_patch_kernel<false>, grid, block, 0, stream, a);
+      hipLaunchKernelGGL(crop_patch_kernel<false>, grid, block, lds, stream, a);
     }
   } else {
     const int64_t total = (int64_t)a.B * a.L * a.D;

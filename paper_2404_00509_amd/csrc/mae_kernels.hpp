@@ -32,9 +32,11 @@ hipError_t launch_params_mask(const ParamArgs& a, hipStream_t stream);
 struct CropArgs {
   int32_t B, S, p, G, L, K, D;
   int32_t visible_bf16;  // 0: float, 1: bfloat16
+  int32_t tile_pixels;   // staging tile of the resampling kernel, in 4-byte pixel words
   float nscale[3];       // 1 / (255 std_c)
   float nbias[3];        // -mean_c / std_c
   const uint8_t* images;
+  int64_t images_bytes;
   const int64_t* offsets;
   const int32_t* widths;
   const int32_t* ids_restore;
@@ -42,6 +44,8 @@ struct CropArgs {
   void* visible;
   float* target;  // nullable
 };
+int crop_tile_pixels(int S, int p, int max_side);
+size_t crop_lds_bytes(int tile_pixels, int S, int p);
 hipError_t launch_crop_patch(const CropArgs& a, hipStream_t stream);
 
 // ---- normalised-pixel loss ---------------------------------------------------------------------

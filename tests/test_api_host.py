@@ -57,6 +57,7 @@ def _prep_desc(**over):
     d.mean = (C.c_float * 3)(*mae.IMAGENET_MEAN)
     d.std = (C.c_float * 3)(*mae.IMAGENET_STD)
     d.seed, d.batch_index, d.sample_base, d.noise_bits, d.out_dtype = 0, 0, 0, 32, 0
+    d.max_image_side = 0
     for k, v in over.items():
         if k == "std":
             d.std = (C.c_float * 3)(*v)
@@ -100,6 +101,8 @@ def _call_prep(lib, d, visible=FAKE, mask=FAKE, ids_restore=FAKE, workspace=FAKE
     (dict(noise_bits=33), binding.MAE_ERR_RANGE),
     (dict(sample_base=0xFFFFFFFF), binding.MAE_ERR_RANGE),
     (dict(out_dtype=7), binding.MAE_ERR_DTYPE),
+    (dict(max_image_side=-1), binding.MAE_ERR_RANGE),
+    (dict(max_image_side=40000), binding.MAE_ERR_RANGE),
 ])
 def test_prep_rejects_bad_descriptors(lib, over, status):
     d = _prep_desc(**over)
