@@ -4,9 +4,12 @@
 //
 // Streaming kernel: one wavefront per patch row, the row held in registers (16-byte loads, lane i
 // takes the i-th, (i+64)-th, ... group), two butterfly reductions for mean and variance, gradient
-// written with 16-byte stores.  Visible rows only get zeros written and read nothing.  Each
-// wavefront adds its rows' squared errors in double precision and leaves one partial; a second,
-// single-workgroup kernel adds the partials in a fixed order, so the loss is reproducible.
+// written with 16-byte stores.  Nothing is read twice, so loads and stores carry the
+// non-temporal hint.  Rows are dealt to the wavefronts of the grid round-robin, which keeps the
+// rows in flight at any moment inside one small window of each tensor.  Visible rows only get
+// zeros written and read nothing.  Each wavefront adds its rows' squared errors in double
+// precision and leaves one partial; a second, single-workgroup kernel adds the partials in a
+// fixed order, so the loss is reproducible.
 #include "mae_device.hpp"
 #include "mae_kernels.hpp"
 
@@ -14,7 +17,7 @@ namespace mae {
 
 constexpr int kLossThreads = 256;
 constexpr int kLossWaves = kLossThreads / kWave;
-constexpr int kLossMaxBlocks = 256 * 8;  // 8 workgroups per compute unit
+constexpr int kLossMaxBlocks = 256 * 4;  // 4 workgroups (16 wavefronts) per compute unit
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -34,19 +37,21 @@ __device__ static inline double wave_sum(double v) {
 template <bool kBf16>
 __device__ static inline f32x4 load_pred4(const void* pred, int64_t elem) {
   if (kBf16) {
-    const u32x2 raw = *reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(pred) + elem);
+    const u32x2 raw = __builtin_nontemporal_load(
+        reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(pred) + elem));
     return f32x4{bf16_lo(raw.x), bf16_hi(raw.x), bf16_lo(raw.y), bf16_hi(raw.y)};
   }
-  return *reinterpret_cast<const f32x4*>(static_cast<const float*>(pred) + elem);
+  return __builtin_nontemporal_load(
+      reinterpret_cast<const f32x4*>(static_cast<const float*>(pred) + elem));
 }
 
 template <bool kBf16>
 __device__ static inline void store_grad4(void* grad, int64_t elem, f32x4 g) {
   if (kBf16) {
-    *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(grad) + elem) =
-        u32x2{pack_bf16x2(g.x, g.y), pack_bf16x2(g.z, g.w)};
+    __builtin_nontemporal_store(u32x2{pack_bf16x2(g.x, g.y), pack_bf16x2(g.z, g.w)},
+                                reinterpret_cast<u32x2*>(static_cast<uint16_t*>(grad) + elem));
   } else {
-    *reinterpret_cast<f32x4*>(static_cast<float*>(grad) + elem) = g;
+    __builtin_nontemporal_store(g, reinterpret_cast<f32x4*>(static_cast<float*>(grad) + elem));
   }
 }
 
@@ -78,7 +83,8 @@ __global__ __launch_bounds__(kLossThreads) void normpix_loss_kernel(LossArgs a) 
     for (int v = 0; v < NV; ++v) {
       const int g = lane + v * kWave;
       if (g < D4) {
-        t[v] = *reinterpret_cast<const f32x4*>(a.target + row_elem + 4 * g);
+        t[v] = __builtin_nontemporal_load(
+            reinterpret_cast<const f32x4*>(a.target + row_elem + 4 * g));
         q[v] = load_pred4<kBf16>(a.pred, row_elem + 4 * g);
       } else {
         t[v] = f32x4{0.f, 0.f, 0.f, 0.f};
