@@ -20,12 +20,18 @@ IMAGENET_MEAN = (0.485, 0.456, 0.406)
 IMAGENET_STD = (0.229, 0.224, 0.225)
 
 
+def compile_source(src: str, out: str) -> str:
+    """gcc, plain -O2, no contraction, OpenMP over samples / rows only."""
+    cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
+           "-Wall", "-Wextra", "-I", _HERE, "-o", out, src, "-lm"]
+    subprocess.run(cmd, check=True, cwd=_HERE)
+    return out
+
+
 def build(force: bool = False) -> str:
-    """Compile the oracle with gcc (plain -O2, no contraction, OpenMP over samples only)."""
+    """Compile the oracle if it is missing or older than its source."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
-               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
-        subprocess.run(cmd, check=True, cwd=_HERE)
+        compile_source(_SRC, _LIB)
     return _LIB
 
 
@@ -55,48 +61,54 @@ class _PrepArgs(C.Structure):
 _lib = None
 
 
+def load_library(path: str):
+    """Open an oracle shared library and declare its signatures (also used by the tests that
+    plant mistakes in a copy of the source)."""
+    L = C.CDLL(path)
+    L.mae_oracle_mix64.restype = C.c_uint64
+    L.mae_oracle_mix64.argtypes = [C.c_uint64]
+    L.mae_oracle_draw.restype = C.c_uint64
+    L.mae_oracle_draw.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32]
+    L.mae_oracle_exp_poly.restype = C.c_double
+    L.mae_oracle_exp_poly.argtypes = [C.c_double]
+    rrc = [C.c_int32, C.c_int32, C.c_float, C.c_float, C.c_float, C.c_float, C.c_uint64,
+           C.c_uint64, C.c_uint32]
+    L.mae_oracle_rrc_proposal.restype = None
+    L.mae_oracle_rrc_proposal.argtypes = rrc + [C.c_int32, C.c_void_p]
+    L.mae_oracle_rrc_params.restype = C.c_int32
+    L.mae_oracle_rrc_params.argtypes = rrc + [C.c_void_p]
+    L.mae_oracle_flip_bit.restype = C.c_int32
+    L.mae_oracle_flip_bit.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_float]
+    L.mae_oracle_resize_taps.restype = None
+    L.mae_oracle_resize_taps.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                         C.c_void_p, C.c_void_p]
+    L.mae_oracle_crop_resize.restype = None
+    L.mae_oracle_crop_resize.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                         C.c_int32, C.c_int32, C.c_void_p]
+    L.mae_oracle_normalise.restype = C.c_double
+    L.mae_oracle_normalise.argtypes = [C.c_double, C.c_double, C.c_double]
+    L.mae_oracle_patchify.restype = None
+    L.mae_oracle_patchify.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+    L.mae_oracle_num_keep.restype = C.c_int32
+    L.mae_oracle_num_keep.argtypes = [C.c_int32, C.c_double]
+    L.mae_oracle_mask.restype = None
+    L.mae_oracle_mask.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_int32, C.c_int32,
+                                  C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.mae_oracle_prep_batch.restype = C.c_int32
+    L.mae_oracle_prep_batch.argtypes = [C.c_void_p, C.c_int32, C.c_int32] + [C.c_void_p] * 6
+    L.mae_oracle_normpix_loss.restype = C.c_int32
+    L.mae_oracle_normpix_loss.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                          C.c_void_p, C.c_void_p, C.c_int64, C.c_double,
+                                          C.c_double, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.mae_oracle_threads.restype = C.c_int32
+    L.mae_oracle_threads.argtypes = []
+    return L
+
+
 def lib():
     global _lib
     if _lib is None:
-        L = C.CDLL(build())
-        L.mae_oracle_mix64.restype = C.c_uint64
-        L.mae_oracle_mix64.argtypes = [C.c_uint64]
-        L.mae_oracle_draw.restype = C.c_uint64
-        L.mae_oracle_draw.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32]
-        L.mae_oracle_exp_poly.restype = C.c_double
-        L.mae_oracle_exp_poly.argtypes = [C.c_double]
-        rrc = [C.c_int32, C.c_int32, C.c_float, C.c_float, C.c_float, C.c_float, C.c_uint64,
-               C.c_uint64, C.c_uint32]
-        L.mae_oracle_rrc_proposal.restype = None
-        L.mae_oracle_rrc_proposal.argtypes = rrc + [C.c_int32, C.c_void_p]
-        L.mae_oracle_rrc_params.restype = C.c_int32
-        L.mae_oracle_rrc_params.argtypes = rrc + [C.c_void_p]
-        L.mae_oracle_flip_bit.restype = C.c_int32
-        L.mae_oracle_flip_bit.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_float]
-        L.mae_oracle_resize_taps.restype = None
-        L.mae_oracle_resize_taps.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
-                                             C.c_void_p, C.c_void_p]
-        L.mae_oracle_crop_resize.restype = None
-        L.mae_oracle_crop_resize.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
-                                             C.c_int32, C.c_int32, C.c_void_p]
-        L.mae_oracle_normalise.restype = C.c_double
-        L.mae_oracle_normalise.argtypes = [C.c_double, C.c_double, C.c_double]
-        L.mae_oracle_patchify.restype = None
-        L.mae_oracle_patchify.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
-        L.mae_oracle_num_keep.restype = C.c_int32
-        L.mae_oracle_num_keep.argtypes = [C.c_int32, C.c_double]
-        L.mae_oracle_mask.restype = None
-        L.mae_oracle_mask.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_int32, C.c_int32,
-                                      C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
-        L.mae_oracle_prep_batch.restype = C.c_int32
-        L.mae_oracle_prep_batch.argtypes = [C.c_void_p, C.c_int32, C.c_int32] + [C.c_void_p] * 6
-        L.mae_oracle_normpix_loss.restype = C.c_int32
-        L.mae_oracle_normpix_loss.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
-                                              C.c_void_p, C.c_void_p, C.c_int64, C.c_double,
-                                              C.c_double, C.c_void_p, C.c_void_p, C.c_void_p]
-        L.mae_oracle_threads.restype = C.c_int32
-        L.mae_oracle_threads.argtypes = []
-        _lib = L
+        _lib = load_library(build())
     return _lib
 
 

@@ -1,0 +1,115 @@
+"""Checks of the pins themselves: plant one plausible mistake at a time in a COPY of the oracle's
+source (CPU only), and require that at least one pin fails.  A mistake that every pin accepts
+would mean that the oracle is not pinned where the mistake sits."""
+import os
+
+import pytest
+
+import oracle
+import test_oracle_pins as pins
+
+SRC = os.path.join(os.path.dirname(os.path.abspath(oracle.__file__)), "mae_oracle.c")
+
+
+class _Golden:
+    def __call__(self, name):
+        from conftest import read_golden
+        return read_golden(name)
+
+
+# (label, text in the source, replacement, pins that must notice)
+MUTATIONS = [
+    ("hash shift", "(z ^ (z >> 30))", "(z ^ (z >> 31))", ["test_hash_known_answers"]),
+    ("hash stream field", "(stream & 0xFFu) << 24", "(stream & 0xFFu) << 23",
+     ["test_hash_known_answers"]),
+    ("batch key offset", "(batch_index + 1)", "(batch_index)", ["test_hash_known_answers"]),
+    ("exp degree", "for (int k = 13; k >= 1; --k) {", "for (int k = 3; k >= 1; --k) {",
+     ["test_exp_polynomial_matches_libm"]),
+    ("scale law on the side, not the area", "double T = area * s;", "double T = area * s * s;",
+     ["test_rrc_proposal_statistics_match_eq2"]),
+    ("ratio transposed", "double cw = rint(sqrt(T * r));\n  double ch = rint(sqrt(T / r));",
+     "double cw = rint(sqrt(T / r));\n  double ch = rint(sqrt(T * r));",
+     ["test_rrc_fixed_ratio_orientation"]),
+    ("ratio uniform instead of log-uniform", "double r = mae_oracle_exp_poly(x);",
+     "double r = 0.75 + (4.0 / 3.0 - 0.75) * u_ratio;",
+     ["test_rrc_proposal_statistics_match_eq2", "test_rrc_proposal_recomputed_with_libm"]),
+    ("offset range off by one", "(uint64_t)(H - ch + 1)", "(uint64_t)(H - ch)",
+     ["test_rrc_offsets_are_uniform_over_positions_that_fit"]),
+    ("fallback not centred", "box[1] = (int32_t)((W - cw) / 2);", "box[1] = 0;",
+     ["test_rrc_fallback_is_centred_square"]),
+    ("fallback ratio side", "ch = (int64_t)rint((double)W / (double)ratio_lo);",
+     "ch = (int64_t)rint((double)W * (double)ratio_lo);", ["test_rrc_fallback_is_centred_square"]),
+    ("flip threshold", "return u < flip_p ? 1 : 0;", "return u > flip_p ? 1 : 0;",
+     ["test_flip_probability_extremes_and_rate"]),
+    ("pixel centres dropped", "(2 * (int64_t)o + 1) * (int64_t)crop_len - (int64_t)out_size",
+     "(2 * (int64_t)o) * (int64_t)crop_len",
+     ["test_resize_taps_printed_example", "test_resize_against_library_bilinear"]),
+    ("second tap not clamped", "*i1 = (*i0 + 1 < crop_len) ? *i0 + 1 : crop_len - 1;",
+     "*i1 = *i0 + 1;", ["test_resize_clamps_to_crop_box_not_image",
+                        "test_resize_identity_constant_and_single_pixel"]),
+    ("weights swapped", "double rt = a00 + fx * (a01 - a00);",
+     "double rt = a01 + fx * (a00 - a01);", ["test_resize_taps_printed_example"]),
+    ("rows and columns swapped in the blend", "out[((int64_t)oy * S + ox) * 3 + c] = rt + fy * (rb - rt);",
+     "out[((int64_t)oy * S + ox) * 3 + c] = rt + fx * (rb - rt);",
+     ["test_resize_reproduces_affine_ramps"]),
+    ("crop offset ignored", "double a00 = img[((int64_t)(top + y0) * W + (left + x0)) * 3 + c];",
+     "double a00 = img[((int64_t)(top + y0) * W + (x0)) * 3 + c];",
+     ["test_resize_identity_constant_and_single_pixel", "test_resize_reproduces_affine_ramps"]),
+    ("flip ignored", "int32_t sx = flip ? (S - 1 - ox) : ox;", "int32_t sx = ox;",
+     ["test_flip_twice_is_identity_and_mirrors_columns"]),
+    ("normalise order", "return (v / 255.0 - mean) / std;", "return (v / 255.0) / std - mean;",
+     ["test_normalise_end_points"]),
+    ("patch order transposed", "int64_t l = (int64_t)(y / p) * G + (x / p);",
+     "int64_t l = (int64_t)(x / p) * G + (y / p);", ["test_patchify_layout"]),
+    ("channel not fastest", "int64_t e = ((int64_t)(y % p) * p + (x % p)) * 3 + c;",
+     "int64_t e = (int64_t)c * p * p + (int64_t)(y % p) * p + (x % p);", ["test_patchify_layout"]),
+    ("ties broken the other way", "(key[j] == key[l] && j < l)", "(key[j] == key[l] && j > l)",
+     ["test_masking_invariants_and_library_argsort"]),
+    ("descending noise", "if (key[j] < key[l] ||", "if (key[j] > key[l] ||",
+     ["test_masking_worked_example"]),
+    ("mask polarity", "mask[l] = (rank >= K) ? 1 : 0;", "mask[l] = (rank >= K) ? 0 : 1;",
+     ["test_masking_worked_example"]),
+    ("num_keep rounds", "return (int32_t)floor((double)L * (1.0 - mask_ratio));",
+     "return (int32_t)rint((double)L * (1.0 - mask_ratio));", ["test_num_keep_values"]),
+    ("gather uses rank as index", "(float)patches[(int64_t)keep[r] * D + e];",
+     "(float)patches[(int64_t)r * D + e];", ["test_prep_gather_and_slicing"]),
+    ("biased variance", "double var = ss / (double)(D - 1);", "double var = ss / (double)D;",
+     ["test_loss_normalised_target_statistics"]),
+    ("eps outside the root", "double sd = sqrt(var + eps);", "double sd = sqrt(var) + eps;",
+     ["test_loss_normalised_target_statistics"]),
+    ("gradient factor", "grad_scale * 2.0 * diff", "grad_scale * diff",
+     ["test_loss_euler_identity_and_finite_differences"]),
+    ("loss over all rows", "if (mask[row]) total += row_losses[row];",
+     "total += row_losses[row];", ["test_loss_constant_offset_closed_form"]),
+    ("per-row mean dropped", "row_losses[row] = row_loss / (double)D;",
+     "row_losses[row] = row_loss;", ["test_loss_constant_offset_closed_form"]),
+    ("gradient on visible rows", "mask[row] ? (float)(grad_scale", "1 ? (float)(grad_scale",
+     ["test_loss_against_library_autograd"]),
+]
+
+
+@pytest.mark.parametrize("label,old,new,watchers", MUTATIONS, ids=[m[0] for m in MUTATIONS])
+def test_planted_mistake_is_caught(label, old, new, watchers, tmp_path, monkeypatch):
+    text = open(SRC).read()
+    assert text.count(old) == 1, f"mutation site for '{label}' not unique in the oracle source"
+    mutated = tmp_path / "mutated_oracle.c"
+    mutated.write_text(text.replace(old, new))
+    so = oracle.compile_source(str(mutated), str(tmp_path / "libmutated.so"))
+    monkeypatch.setattr(oracle, "_lib", oracle.load_library(so))
+    caught = []
+    for name in watchers:
+        fn = getattr(pins, name)
+        kwargs = {"golden": _Golden()} if "golden" in fn.__code__.co_varnames[:fn.__code__.co_argcount] else {}
+        params = [m.args for m in getattr(fn, "pytestmark", []) if m.name == "parametrize"]
+        calls = [kwargs]
+        if params:
+            names = [n.strip() for n in params[0][0].split(",")]
+            calls = [dict(kwargs, **dict(zip(names, v if isinstance(v, tuple) else (v,))))
+                     for v in params[0][1]]
+        for kw in calls:
+            try:
+                fn(**kw)
+            except AssertionError:
+                caught.append(name)
+                break
+    assert caught, f"no pin noticed the planted mistake '{label}'"
