@@ -100,6 +100,16 @@ def load_library(path: str):
     L.mae_oracle_normpix_loss.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                           C.c_void_p, C.c_void_p, C.c_int64, C.c_double,
                                           C.c_double, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.mae_oracle_pixel_loss.restype = C.c_int32
+    L.mae_oracle_pixel_loss.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                        C.c_void_p, C.c_int64, C.c_double, C.c_void_p, C.c_void_p]
+    L.mae_oracle_pretrain_stage.restype = C.c_int32
+    L.mae_oracle_pretrain_stage.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    L.mae_oracle_finetune_stage.restype = C.c_int32
+    L.mae_oracle_finetune_stage.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                            C.c_void_p]
+    L.mae_oracle_stage_of_epoch.restype = C.c_int32
+    L.mae_oracle_stage_of_epoch.argtypes = [C.c_int32, C.c_void_p, C.c_int32]
     L.mae_oracle_threads.restype = C.c_int32
     L.mae_oracle_threads.argtypes = []
     return L
@@ -253,6 +263,45 @@ def normpix_loss(pred, target, mask, num_masked=None, eps=1e-6, grad_scale=1.0, 
     if rc != 0:
         raise ValueError("mae_oracle_normpix_loss: invalid argument")
     return loss.value, grad, that
+
+
+def pixel_loss(pred, target, mask, num_masked=None, grad_scale=1.0, want_grad=True):
+    """Un-normalised variant: -> (loss float64, grad fp32 [B,L,D] or None)."""
+    pred = np.ascontiguousarray(pred, np.float32)
+    target = np.ascontiguousarray(target, np.float32)
+    mask = np.ascontiguousarray(mask, np.uint8)
+    B, L, D = pred.shape
+    if num_masked is None:
+        num_masked = int(mask.astype(np.int64).sum())
+    loss = C.c_double()
+    grad = np.empty((B, L, D), np.float32) if want_grad else None
+    rc = lib().mae_oracle_pixel_loss(B, L, D, _p(pred), _p(target), _p(mask), num_masked,
+                                     grad_scale, C.byref(loss), _p(grad))
+    if rc != 0:
+        raise ValueError("mae_oracle_pixel_loss: invalid argument")
+    return loss.value, grad
+
+
+def pretrain_stage(scheme: int, stage: int):
+    """-> (resolution, mask_ratio) of Table 9, or None for an unknown scheme / stage."""
+    res, m = C.c_int32(), C.c_double()
+    if lib().mae_oracle_pretrain_stage(scheme, stage, C.byref(res), C.byref(m)) != 0:
+        return None
+    return res.value, m.value
+
+
+def finetune_stage(scheme: int, stage: int):
+    """-> (resolution, sigma_lo, sigma_hi) of Table 7, or None."""
+    res, lo, hi = C.c_int32(), C.c_double(), C.c_double()
+    if lib().mae_oracle_finetune_stage(scheme, stage, C.byref(res), C.byref(lo),
+                                       C.byref(hi)) != 0:
+        return None
+    return res.value, lo.value, hi.value
+
+
+def stage_of_epoch(epoch: int, lengths) -> int:
+    arr = np.ascontiguousarray(lengths, np.int32)
+    return int(lib().mae_oracle_stage_of_epoch(epoch, _p(arr), len(arr)))
 
 
 def threads() -> int:

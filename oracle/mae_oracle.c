@@ -353,6 +353,77 @@ int32_t mae_oracle_normpix_loss(int32_t B, int32_t L, int32_t D, const float* pr
   return 0;
 }
 
+/* The un-normalised variant of the objective: the target is the image-normalised patch itself. */
+int32_t mae_oracle_pixel_loss(int32_t B, int32_t L, int32_t D, const float* pred,
+                              const float* target, const uint8_t* mask, int64_t num_masked,
+                              double grad_scale, double* loss_out, float* grad) {
+  if (B < 1 || L < 1 || D < 1 || !pred || !target || !mask || !loss_out || num_masked < 1)
+    return -1;
+  int64_t rows = (int64_t)B * L;
+  double M = (double)num_masked;
+  double total = 0.0;
+  for (int64_t row = 0; row < rows; ++row) {
+    double row_loss = 0.0;
+    for (int32_t e = 0; e < D; ++e) {
+      double diff = (double)pred[row * D + e] - (double)target[row * D + e];
+      row_loss += diff * diff;
+      if (grad)
+        grad[row * D + e] =
+            mask[row] ? (float)(grad_scale * 2.0 * diff / ((double)D * M)) : 0.0f;
+    }
+    if (mask[row]) total += row_loss / (double)D;
+  }
+  *loss_out = total / M;
+  return 0;
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * Progressive schedules.  Sec. 5.3, Table 9: six pretraining schemes of three stages, each stage a
+ * training resolution and a masking ratio.  Sec. 5.2, Table 7: finetuning schemes of three stages,
+ * each a resolution and the range of the crop's side ratio sigma.
+ * ---------------------------------------------------------------------------------------------- */
+int32_t mae_oracle_pretrain_stage(int32_t scheme, int32_t stage, int32_t* res, double* mask_ratio) {
+  if (scheme < 1 || scheme > 6 || stage < 1 || stage > 3 || !res || !mask_ratio) return -1;
+  static const int32_t R[6][3] = {
+      {160, 192, 224},  /* 1: resolution and masking ratio both grow            */
+      {160, 192, 224},  /* 2: resolution grows, ratio fixed                     */
+      {224, 192, 160},  /* 3: resolution shrinks                                */
+      {160, 192, 224},  /* 4: resolution grows, ratio grows from the default    */
+      {224, 192, 224},  /* 5: palindrome                                        */
+      {224, 192, 224},  /* 6: palindrome, harder last stage                     */
+  };
+  static const double Mr[6][3] = {
+      {0.50, 0.66, 0.75}, {0.75, 0.75, 0.75}, {0.75, 0.75, 0.75},
+      {0.75, 0.80, 0.85}, {0.75, 0.75, 0.75}, {0.75, 0.75, 0.85},
+  };
+  *res = R[scheme - 1][stage - 1];
+  *mask_ratio = Mr[scheme - 1][stage - 1];
+  return 0;
+}
+
+int32_t mae_oracle_finetune_stage(int32_t scheme, int32_t stage, int32_t* res, double* sigma_lo,
+                                  double* sigma_hi) {
+  if ((scheme != 1 && scheme != 3) || stage < 1 || stage > 3 || !res || !sigma_lo || !sigma_hi)
+    return -1;
+  static const int32_t R[3] = {160, 192, 224};
+  static const double hi3[3] = {0.68, 0.84, 1.0};
+  *res = R[stage - 1];
+  *sigma_lo = 0.28;
+  *sigma_hi = scheme == 1 ? 1.0 : hi3[stage - 1];
+  return 0;
+}
+
+int32_t mae_oracle_stage_of_epoch(int32_t epoch, const int32_t* lengths, int32_t n) {
+  if (epoch < 0 || !lengths || n < 1) return -1;
+  int64_t end = 0;
+  for (int32_t s = 0; s < n; ++s) {
+    if (lengths[s] < 0) return -1;
+    end += lengths[s];
+    if (epoch < end) return s + 1;
+  }
+  return n;
+}
+
 int32_t mae_oracle_threads(void) {
 #ifdef _OPENMP
   return (int32_t)omp_get_max_threads();

@@ -110,6 +110,23 @@ int32_t mae_oracle_normpix_loss(int32_t B, int32_t L, int32_t D, const float* pr
                                 const float* target, const uint8_t* mask, int64_t num_masked,
                                 double eps, double grad_scale, double* loss_out, float* grad,
                                 double* that);
+/* Same objective against the image-normalised pixels themselves (no per-patch normalisation):
+ * that = target. */
+int32_t mae_oracle_pixel_loss(int32_t B, int32_t L, int32_t D, const float* pred,
+                              const float* target, const uint8_t* mask, int64_t num_masked,
+                              double grad_scale, double* loss_out, float* grad);
+
+/* ---- progressive schedules (Sec. 5.2 Table 7, Sec. 5.3 Table 9) ------------------------------- */
+/* Pretraining scheme 1..6, stage 1..3 -> training resolution and masking ratio.  Returns 0, or
+ * -1 for an unknown scheme or stage. */
+int32_t mae_oracle_pretrain_stage(int32_t scheme, int32_t stage, int32_t* res, double* mask_ratio);
+/* Finetuning scheme (1 = scheme 1/1-/1+, 3 = scheme 3), stage 1..3 -> resolution and the bounds
+ * sigma-, sigma+ of the crop's side ratio (the crop's area fraction is their square). */
+int32_t mae_oracle_finetune_stage(int32_t scheme, int32_t stage, int32_t* res, double* sigma_lo,
+                                  double* sigma_hi);
+/* Stage (1-based) that epoch `epoch` (0-based) falls in when the stages last lengths[0..n) epochs;
+ * epochs past the end belong to the last stage.  Returns -1 on bad arguments. */
+int32_t mae_oracle_stage_of_epoch(int32_t epoch, const int32_t* lengths, int32_t n);
 
 int32_t mae_oracle_threads(void);
 

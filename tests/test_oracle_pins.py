@@ -527,3 +527,68 @@ def test_synthetic_inputs_are_reproducible_and_shaped():
             assert np.all(np.maximum(h, w) == 256) and np.all(np.minimum(h, w) >= 160)
     p = synth.make_pred(0, 3, 4, 8)
     assert np.array_equal(p[2], synth.make_pred_rows(0, 2, 4, 8)) and p.dtype == np.float32
+
+
+# ------------------------------------------------------------------------------------ schedules
+def test_progressive_schemes_match_the_printed_tables(golden):
+    seen = 0
+    for row in golden("progressive_schemes.txt"):
+        if row[0] == "pretrain":
+            scheme, stage, res, m = int(row[1]), int(row[2]), int(row[3]), float(row[4])
+            assert oracle.pretrain_stage(scheme, stage) == (res, m)
+            seen += 1
+        elif row[0] == "finetune":
+            scheme, stage, res = int(row[1]), int(row[2]), int(row[3])
+            assert oracle.finetune_stage(scheme, stage) == (res, float(row[4]), float(row[5]))
+            seen += 1
+        elif row[0] == "lengths":
+            lengths = [int(v) for v in row[1:]]
+            assert [oracle.stage_of_epoch(e, lengths) for e in (0, 29, 30, 59, 60, 99, 100, 500)] \
+                == [1, 1, 2, 2, 3, 3, 3, 3]
+    assert seen == 24
+    assert oracle.pretrain_stage(0, 1) is None and oracle.pretrain_stage(7, 1) is None
+    assert oracle.pretrain_stage(1, 0) is None and oracle.pretrain_stage(1, 4) is None
+    assert oracle.finetune_stage(2, 1) is None
+    assert oracle.stage_of_epoch(-1, [1, 2]) == -1
+    assert oracle.stage_of_epoch(0, [0, 0, 5]) == 3       # empty stages are skipped
+    # text of Sec. 5.3: scheme 5 lowers then raises the resolution; scheme 4 raises the masking
+    # ratio from 0.75 to 0.85; scheme 3 only shrinks the resolution
+    assert [oracle.pretrain_stage(5, s)[0] for s in (1, 2, 3)] == [224, 192, 224]
+    assert [oracle.pretrain_stage(4, s)[1] for s in (1, 2, 3)] == [0.75, 0.80, 0.85]
+    assert [oracle.pretrain_stage(3, s)[0] for s in (1, 2, 3)] == [224, 192, 160]
+
+
+def test_progressive_stage_token_counts():
+    # tokens the encoder sees per image in each stage: K = floor(L (1 - m)), L = (res / 16)^2
+    want = {(1, 1): 50, (1, 2): 48, (1, 3): 49, (4, 2): 28, (4, 3): 29, (6, 3): 29, (3, 3): 25}
+    for (scheme, stage), K in want.items():
+        res, m = oracle.pretrain_stage(scheme, stage)
+        assert oracle.num_keep((res // 16) ** 2, m) == K
+
+
+# ------------------------------------------------------------------------------------ pixel loss
+def test_pixel_loss_against_library_and_closed_form():
+    rng = np.random.default_rng(11)
+    B, L, D = 3, 5, 24
+    pred = rng.standard_normal((B, L, D)).astype(np.float32)
+    target = rng.standard_normal((B, L, D)).astype(np.float32) * 2 + 1
+    mask = (rng.random((B, L)) < 0.6).astype(np.uint8)
+    mask[0, 0] = 1
+    loss, grad = oracle.pixel_loss(pred, target, mask, grad_scale=0.5)
+    p = torch.tensor(pred, dtype=torch.float64, requires_grad=True)
+    t = torch.tensor(target, dtype=torch.float64)
+    m = torch.tensor(mask, dtype=torch.float64)
+    ref = (torch.nn.functional.mse_loss(p, t, reduction="none").mean(-1) * m).sum() / m.sum()
+    (0.5 * ref).backward()
+    assert loss == pytest.approx(ref.item(), rel=1e-12)
+    np.testing.assert_allclose(grad, p.grad.numpy(), rtol=2e-7, atol=1e-12)
+    # prediction = target + c on every row: loss c^2, and it is zero for c = 0
+    zero, gz = oracle.pixel_loss(target, target, mask)
+    assert zero == 0.0 and not gz.any()
+    off, _ = oracle.pixel_loss(target + np.float32(0.5), target, mask)
+    assert off == pytest.approx(0.25, rel=1e-6)
+    # same number as the normalised objective when the rows already have mean 0, variance 1
+    tn = oracle.normpix_loss(pred, target, mask, eps=0.0, want_that=True)[2].astype(np.float32)
+    a = oracle.pixel_loss(pred, tn, mask)[0]
+    b = oracle.normpix_loss(pred, tn, mask, eps=0.0)[0]
+    assert a == pytest.approx(b, rel=1e-5)
