@@ -58,6 +58,52 @@ def algorithmic_bytes(wl, K):
     return prep_write, loss
 
 
+def time_scheme(args, mae, synth, torch, dev, wl, bf16):
+    """Per-stage step time of a progressive pretraining scheme; one allocation for all stages."""
+    stages = [mae.mae_pretrain_stage(args.scheme, s) for s in (1, 2, 3)]
+    bufs = mae.ProgressiveBuffers(wl.B, wl.patch, stages, bf16=bf16)
+    D = 3 * wl.patch * wl.patch
+    max_l = max(sh[1] for sh in bufs.shapes)
+    gen = torch.Generator(device="cuda").manual_seed(2)
+    pred_store = torch.randn(wl.B * max_l * D, generator=gen, device="cuda")
+    if bf16:
+        pred_store = pred_store.to(torch.bfloat16)
+    grad_store = torch.empty_like(pred_store)
+    loss = torch.zeros(1, device="cuda")
+    stream = torch.cuda.current_stream()
+    rows = []
+    for i, (res, m) in enumerate(stages):
+        _, L, K, _ = bufs.shapes[i]
+        buf = bufs.stage(i)
+        pred = pred_store[:wl.B * L * D].view(wl.B, L, D)
+        grad = grad_store[:wl.B * L * D].view(wl.B, L, D)
+        desc = mae.make_prep_desc(*dev, out_size=res, patch=wl.patch, num_keep=K, seed=0,
+                                  batch_index=0,
+                                  out_dtype=mae.MAE_BF16 if bf16 else mae.MAE_F32)
+        ldesc = mae.make_loss_desc(pred, buf.target, buf.mask, num_masked=wl.B * (L - K))
+        lws = torch.empty(max(mae.mae_loss_workspace_bytes(ldesc), 256), dtype=torch.uint8,
+                          device="cuda")
+
+        def step(j):
+            desc.batch_index = 1000 * (i + 1) + j
+            mae.mae_prep_batch(desc, buf.visible, buf.mask, buf.ids_restore, buf.ids_keep,
+                               buf.target, buf.crop, buf.workspace, stream=stream)
+            mae.mae_normpix_loss(ldesc, loss, grad, lws, stream=stream)
+
+        for j in range(args.warmup):
+            step(j)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for j in range(args.steps):
+            step(args.warmup + j)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        rows.append({"stage": i + 1, "out_size": res, "mask_ratio": m, "L": L, "K": K,
+                     "ms_per_step": round(dt * 1e3 / args.steps, 4),
+                     "images_per_s": round(wl.B * args.steps / dt, 1)})
+    return rows
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -66,6 +112,9 @@ def main() -> int:
     ap.add_argument("--workload", default="c4", choices=["c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=4096, help="images timed on the CPU oracle")
+    ap.add_argument("--scheme", type=int, default=0,
+                    help="also time the three stages of pretraining scheme 1..6 (Table 9) on "
+                         "buffers allocated once; adds a 'stages' list to the JSON line")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed region, run one plain device copy of known size "
                          "(grad <- pred) so that a counter run has a reference kernel")
@@ -195,6 +244,9 @@ def main() -> int:
                                        / HBM_PEAK_GBPS, 4),
         "loss_value": final_loss,
     }
+
+    if args.scheme:
+        out["stages"] = time_scheme(args, mae, synth, torch, dev, wl, bf16)
 
     if not args.no_cpu_baseline:
         import oracle

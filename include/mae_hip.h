@@ -146,6 +146,8 @@ typedef struct {
   float eps;             /* >= 0, 1e-6 in the MAE recipe                                        */
   float grad_scale;      /* upstream derivative of the loss, normally 1                         */
   int32_t pred_dtype;    /* mae_dtype of pred and grad                                          */
+  int32_t norm_pix;      /* 1: the objective above (per-patch normalised pixels); 0: the
+                            un-normalised variant, that = t, eps unused                          */
 } mae_loss_desc;
 
 /* Outputs (device):
@@ -156,6 +158,31 @@ int mae_normpix_loss(const mae_loss_desc* d, float* loss, void* grad, void* work
                      size_t workspace_bytes, void* hip_stream);
 
 size_t mae_loss_workspace_bytes(const mae_loss_desc* d);
+
+/* ------------------------------------------------------------------------------------------------
+ * Progressive schedules (host-side tables; nothing is launched).
+ *
+ * The paper trains in three stages that change the resolution and the masking ratio (pretraining,
+ * Sec. 5.3 Table 9, schemes 1..6; scheme 5 is the 224 -> 192 -> 224 palindrome) or the resolution
+ * and the crop's scale range (finetuning, Sec. 5.2 Table 7).  A stage switch needs no new buffers:
+ * every call takes its sizes from its descriptor, so buffers sized for the largest stage serve
+ * all of them.
+ * ---------------------------------------------------------------------------------------------- */
+
+/* Pretraining scheme 1..6, stage 1..3 -> *out_size (training resolution) and *mask_ratio. */
+int mae_pretrain_stage(int32_t scheme, int32_t stage, int32_t* host_out_size,
+                       double* host_mask_ratio);
+
+/* Finetuning scheme 1 (also 1-, 1+, which differ in augmentation only) or 3, stage 1..3 ->
+ * resolution and the bounds of the crop's side ratio sigma; the area-fraction bounds that
+ * mae_prep_desc takes are sigma^2: *host_scale_lo = sigma_lo^2, *host_scale_hi = sigma_hi^2. */
+int mae_finetune_stage(int32_t scheme, int32_t stage, int32_t* host_out_size,
+                       float* host_scale_lo, float* host_scale_hi);
+
+/* 1-based stage that 0-based `epoch` falls in when the stages last host_lengths[0..n) epochs
+ * (finetuning: 30, 30, 40; the paper gives none for pretraining).  Epochs past the end belong to
+ * the last stage.  Negative return: MAE_ERR_NULL / MAE_ERR_RANGE. */
+int mae_stage_of_epoch(int32_t epoch, const int32_t* host_lengths, int32_t n);
 
 /* Static, NUL-terminated description of a status code. */
 const char* mae_error_string(int status);

@@ -15,9 +15,13 @@ from .binding import (  # noqa: F401
     MaeLossDesc,
     MaePrepDesc,
     PrepBuffers,
+    ProgressiveBuffers,
     alloc_prep_buffers,
     load,
     mae_error_string,
+    mae_finetune_stage,
+    mae_pretrain_stage,
+    mae_stage_of_epoch,
     mae_loss_workspace_bytes,
     mae_normpix_loss,
     mae_num_keep,

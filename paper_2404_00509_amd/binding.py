@@ -25,7 +25,8 @@ IMAGENET_STD = (0.229, 0.224, 0.225)
 
 # Entry points declared in include/mae_hip.h.
 EXPORTS = ("mae_prep_batch", "mae_prep_workspace_bytes", "mae_prep_status", "mae_num_keep",
-           "mae_normpix_loss", "mae_loss_workspace_bytes", "mae_error_string", "mae_version")
+           "mae_normpix_loss", "mae_loss_workspace_bytes", "mae_pretrain_stage",
+           "mae_finetune_stage", "mae_stage_of_epoch", "mae_error_string", "mae_version")
 
 
 class MaePrepDesc(C.Structure):
@@ -67,6 +68,7 @@ class MaeLossDesc(C.Structure):
         ("eps", C.c_float),
         ("grad_scale", C.c_float),
         ("pred_dtype", C.c_int32),
+        ("norm_pix", C.c_int32),
     ]
 
 
@@ -101,6 +103,14 @@ def load():
                                          C.c_void_p, C.c_size_t, C.c_void_p]
         lib.mae_loss_workspace_bytes.restype = C.c_size_t
         lib.mae_loss_workspace_bytes.argtypes = [C.POINTER(MaeLossDesc)]
+        lib.mae_pretrain_stage.restype = C.c_int
+        lib.mae_pretrain_stage.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_int32),
+                                           C.POINTER(C.c_double)]
+        lib.mae_finetune_stage.restype = C.c_int
+        lib.mae_finetune_stage.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_int32),
+                                           C.POINTER(C.c_float), C.POINTER(C.c_float)]
+        lib.mae_stage_of_epoch.restype = C.c_int
+        lib.mae_stage_of_epoch.argtypes = [C.c_int32, C.POINTER(C.c_int32), C.c_int32]
         lib.mae_error_string.restype = C.c_char_p
         lib.mae_error_string.argtypes = [C.c_int]
         lib.mae_version.restype = C.c_int
@@ -119,6 +129,32 @@ def mae_version() -> int:
 
 def mae_num_keep(L: int, mask_ratio: float) -> int:
     return int(load().mae_num_keep(L, mask_ratio))
+
+
+def mae_pretrain_stage(scheme: int, stage: int):
+    """-> (out_size, mask_ratio) of the paper's pretraining scheme / stage."""
+    res, m = C.c_int32(), C.c_double()
+    rc = load().mae_pretrain_stage(scheme, stage, C.byref(res), C.byref(m))
+    if rc != MAE_OK:
+        raise MaeError(rc, "mae_pretrain_stage")
+    return res.value, m.value
+
+
+def mae_finetune_stage(scheme: int, stage: int):
+    """-> (out_size, scale_lo, scale_hi): area-fraction bounds for mae_prep_desc."""
+    res, lo, hi = C.c_int32(), C.c_float(), C.c_float()
+    rc = load().mae_finetune_stage(scheme, stage, C.byref(res), C.byref(lo), C.byref(hi))
+    if rc != MAE_OK:
+        raise MaeError(rc, "mae_finetune_stage")
+    return res.value, lo.value, hi.value
+
+
+def mae_stage_of_epoch(epoch: int, lengths) -> int:
+    arr = (C.c_int32 * len(lengths))(*lengths)
+    rc = load().mae_stage_of_epoch(epoch, arr, len(lengths))
+    if rc < 0:
+        raise MaeError(rc, "mae_stage_of_epoch")
+    return rc
 
 
 def _ptr(t):
@@ -176,13 +212,15 @@ def mae_prep_status(workspace, stream=None) -> int:
     return n.value
 
 
-def make_loss_desc(pred, target, mask, *, num_masked, eps=1e-6, grad_scale=1.0) -> MaeLossDesc:
+def make_loss_desc(pred, target, mask, *, num_masked, eps=1e-6, grad_scale=1.0,
+                   norm_pix=True) -> MaeLossDesc:
     d = MaeLossDesc()
     d.B, d.L, d.D = (int(v) for v in pred.shape)
     d.pred, d.target, d.mask = pred.data_ptr(), target.data_ptr(), mask.data_ptr()
     d.num_masked = int(num_masked)
     d.eps, d.grad_scale = eps, grad_scale
     d.pred_dtype = MAE_BF16 if pred.dtype == torch.bfloat16 else MAE_F32
+    d.norm_pix = 1 if norm_pix else 0
     return d
 
 
@@ -227,3 +265,42 @@ def alloc_prep_buffers(desc: MaePrepDesc, device="cuda", want_target=True) -> Pr
         crop=torch.empty((B, 6), dtype=torch.int32, device=device),
         workspace=torch.empty(ws, dtype=torch.uint8, device=device),
     )
+
+
+class ProgressiveBuffers:
+    """Device buffers allocated once for the largest stage of a progressive schedule (Sec. 5.2,
+    5.3: the resolution and the masking ratio change between stages).  `stage(i)` returns views of
+    the same storage shaped for stage i, so a stage switch allocates nothing."""
+
+    def __init__(self, B, patch, stages, device="cuda", bf16=False, want_target=True):
+        self.B, self.patch, self.bf16 = B, patch, bf16
+        self.shapes = []
+        for out_size, mask_ratio in stages:
+            G = out_size // patch
+            L = G * G
+            self.shapes.append((out_size, L, mae_num_keep(L, mask_ratio), 3 * patch * patch))
+        max_l = max(s[1] for s in self.shapes)
+        max_k = max(s[2] for s in self.shapes)
+        D = self.shapes[0][3]
+        vis_dtype = torch.bfloat16 if bf16 else torch.float32
+        self._visible = torch.empty(B * max_k * D, dtype=vis_dtype, device=device)
+        self._mask = torch.empty(B * max_l, dtype=torch.uint8, device=device)
+        self._ids_restore = torch.empty(B * max_l, dtype=torch.int32, device=device)
+        self._ids_keep = torch.empty(B * max_k, dtype=torch.int32, device=device)
+        self._target = (torch.empty(B * max_l * D, dtype=torch.float32, device=device)
+                        if want_target else None)
+        self._crop = torch.empty((B, 6), dtype=torch.int32, device=device)
+        self._workspace = torch.empty(256 + 32 * B, dtype=torch.uint8, device=device)
+
+    def stage(self, i) -> PrepBuffers:
+        out_size, L, K, D = self.shapes[i]
+        B = self.B
+        return PrepBuffers(
+            visible=self._visible[:B * K * D].view(B, K, D),
+            mask=self._mask[:B * L].view(B, L),
+            ids_restore=self._ids_restore[:B * L].view(B, L),
+            ids_keep=self._ids_keep[:B * K].view(B, K),
+            target=None if self._target is None else self._target[:B * L * D].view(B, L, D),
+            crop=self._crop,
+            workspace=self._workspace,
+        )

@@ -61,6 +61,7 @@ int validate_loss(const mae_loss_desc* d) {
   if (d->num_masked <= 0) return MAE_ERR_RANGE;
   if (!(d->eps >= 0.0f) || !isfinite(d->eps) || !isfinite(d->grad_scale)) return MAE_ERR_RANGE;
   if (d->pred_dtype != MAE_F32 && d->pred_dtype != MAE_BF16) return MAE_ERR_DTYPE;
+  if (d->norm_pix != 0 && d->norm_pix != 1) return MAE_ERR_RANGE;
   return MAE_OK;
 }
 
@@ -220,6 +221,7 @@ int mae_normpix_loss(const mae_loss_desc* d, float* loss, void* grad, void* work
   la.rows = (int64_t)d->B * d->L;
   la.D = d->D;
   la.pred_bf16 = d->pred_dtype == MAE_BF16;
+  la.norm_pix = d->norm_pix;
   la.eps = d->eps;
   const double count = (double)d->D * (double)d->num_masked;
   la.gscale = (float)((double)d->grad_scale * 2.0 / count);
@@ -233,6 +235,57 @@ int mae_normpix_loss(const mae_loss_desc* d, float* loss, void* grad, void* work
   la.num_partials = mae::loss_grid_waves(la.rows);
   if (mae::launch_normpix_loss(la, stream) != hipSuccess) return MAE_ERR_HIP;
   return MAE_OK;
+}
+
+// ---- progressive schedules: the stage tables of the paper ---------------------------------------
+namespace {
+struct PretrainStage {
+  int16_t res;
+  double m;
+};
+// Table 9, rows = stages, one block per scheme
+const PretrainStage kPretrain[6][3] = {
+    {{160, 0.50}, {192, 0.66}, {224, 0.75}},  // scheme 1
+    {{160, 0.75}, {192, 0.75}, {224, 0.75}},  // scheme 2
+    {{224, 0.75}, {192, 0.75}, {160, 0.75}},  // scheme 3
+    {{160, 0.75}, {192, 0.80}, {224, 0.85}},  // scheme 4
+    {{224, 0.75}, {192, 0.75}, {224, 0.75}},  // scheme 5
+    {{224, 0.75}, {192, 0.75}, {224, 0.85}},  // scheme 6
+};
+}  // namespace
+
+int mae_pretrain_stage(int32_t scheme, int32_t stage, int32_t* host_out_size,
+                       double* host_mask_ratio) {
+  if (!host_out_size || !host_mask_ratio) return MAE_ERR_NULL;
+  if (scheme < 1 || scheme > 6 || stage < 1 || stage > 3) return MAE_ERR_RANGE;
+  *host_out_size = kPretrain[scheme - 1][stage - 1].res;
+  *host_mask_ratio = kPretrain[scheme - 1][stage - 1].m;
+  return MAE_OK;
+}
+
+int mae_finetune_stage(int32_t scheme, int32_t stage, int32_t* host_out_size,
+                       float* host_scale_lo, float* host_scale_hi) {
+  if (!host_out_size || !host_scale_lo || !host_scale_hi) return MAE_ERR_NULL;
+  if ((scheme != 1 && scheme != 3) || stage < 1 || stage > 3) return MAE_ERR_RANGE;
+  // Table 7: sigma- = 0.28 throughout; scheme 3 raises sigma+ with the resolution
+  const double sigma_lo = 0.28;
+  const double sigma_hi = scheme == 1 ? 1.0 : (stage == 1 ? 0.68 : (stage == 2 ? 0.84 : 1.0));
+  *host_out_size = 128 + 32 * stage;  // 160, 192, 224
+  *host_scale_lo = (float)(sigma_lo * sigma_lo);
+  *host_scale_hi = (float)(sigma_hi * sigma_hi);
+  return MAE_OK;
+}
+
+int mae_stage_of_epoch(int32_t epoch, const int32_t* host_lengths, int32_t n) {
+  if (!host_lengths) return MAE_ERR_NULL;
+  if (epoch < 0 || n < 1) return MAE_ERR_RANGE;
+  int64_t end = 0;
+  for (int32_t s = 0; s < n; ++s) {
+    if (host_lengths[s] < 0) return MAE_ERR_RANGE;
+    end += host_lengths[s];
+    if (epoch < end) return s + 1;
+  }
+  return n;
 }
 
 }  // extern "C"

@@ -53,6 +53,7 @@ struct LossArgs {
   int64_t rows;  // B * L
   int32_t D;
   int32_t pred_bf16;
+  int32_t norm_pix;  // 1: per-patch normalised target, 0: target as it is
   float eps;
   float gscale;      // grad_scale * 2 / (D * M)
   double inv_count;  // 1 / (D * M)

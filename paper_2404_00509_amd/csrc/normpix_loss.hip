@@ -56,7 +56,8 @@ __device__ static inline void store_grad4(void* grad, int64_t elem, f32x4 g) {
 }
 
 // NV = 16-byte groups per lane; D / 4 <= 64 NV.
-template <int NV, bool kBf16>
+// kNorm: per-patch normalised target (the recipe's objective); otherwise the target as it is.
+template <int NV, bool kBf16, bool kNorm>
 __global__ __launch_bounds__(kLossThreads) void normpix_loss_kernel(LossArgs a) {
   const int lane = threadIdx.x % kWave;
   const int wave_in_grid = blockIdx.x * kLossWaves + threadIdx.x / kWave;
@@ -91,24 +92,28 @@ __global__ __launch_bounds__(kLossThreads) void normpix_loss_kernel(LossArgs a) 
         q[v] = t[v];
       }
     }
-    float s = 0.f;
+    float rstd = 1.0f;
+    if (kNorm) {
+      float s = 0.f;
 #pragma unroll
-    for (int v = 0; v < NV; ++v) s += (t[v].x + t[v].y) + (t[v].z + t[v].w);
-    const float mu = wave_sum(s) * inv_d;
-    float ss = 0.f;
+      for (int v = 0; v < NV; ++v) s += (t[v].x + t[v].y) + (t[v].z + t[v].w);
+      const float mu = wave_sum(s) * inv_d;
+      float ss = 0.f;
 #pragma unroll
-    for (int v = 0; v < NV; ++v) {
-      const int g = lane + v * kWave;
-      t[v] = t[v] - mu;
-      if (g < D4) ss += (t[v].x * t[v].x + t[v].y * t[v].y) + (t[v].z * t[v].z + t[v].w * t[v].w);
+      for (int v = 0; v < NV; ++v) {
+        const int g = lane + v * kWave;
+        t[v] = t[v] - mu;
+        if (g < D4)
+          ss += (t[v].x * t[v].x + t[v].y * t[v].y) + (t[v].z * t[v].z + t[v].w * t[v].w);
+      }
+      const float var = wave_sum(ss) * inv_dm1;
+      rstd = 1.0f / sqrtf(var + a.eps);
     }
-    const float var = wave_sum(ss) * inv_dm1;
-    const float rstd = 1.0f / sqrtf(var + a.eps);
     float sq = 0.f;
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
       const int g = lane + v * kWave;
-      const f32x4 diff = q[v] - t[v] * rstd;
+      const f32x4 diff = kNorm ? q[v] - t[v] * rstd : q[v] - t[v];
       if (g < D4) {
         sq += (diff.x * diff.x + diff.y * diff.y) + (diff.z * diff.z + diff.w * diff.w);
         if (a.grad) store_grad4<kBf16>(a.grad, row_elem + 4 * g, diff * a.gscale);
@@ -121,7 +126,7 @@ __global__ __launch_bounds__(kLossThreads) void normpix_loss_kernel(LossArgs a) 
 }
 
 // Any D (not a multiple of four, or too long for registers): three passes over the row.
-template <bool kBf16>
+template <bool kBf16, bool kNorm>
 __global__ __launch_bounds__(kLossThreads) void normpix_loss_scalar_kernel(LossArgs a) {
   const int lane = threadIdx.x % kWave;
   const int wave_in_grid = blockIdx.x * kLossWaves + threadIdx.x / kWave;
@@ -140,19 +145,22 @@ __global__ __launch_bounds__(kLossThreads) void normpix_loss_scalar_kernel(LossA
       }
       continue;
     }
-    float s = 0.f;
-    for (int e = lane; e < D; e += kWave) s += t[e];
-    const float mu = wave_sum(s) / (float)D;
-    float ss = 0.f;
-    for (int e = lane; e < D; e += kWave) ss += (t[e] - mu) * (t[e] - mu);
-    const float var = wave_sum(ss) / (float)(D - 1);
-    const float rstd = 1.0f / sqrtf(var + a.eps);
+    float mu = 0.f, rstd = 1.0f;
+    if (kNorm) {
+      float s = 0.f;
+      for (int e = lane; e < D; e += kWave) s += t[e];
+      mu = wave_sum(s) / (float)D;
+      float ss = 0.f;
+      for (int e = lane; e < D; e += kWave) ss += (t[e] - mu) * (t[e] - mu);
+      const float var = wave_sum(ss) / (float)(D - 1);
+      rstd = 1.0f / sqrtf(var + a.eps);
+    }
     float sq = 0.f;
     for (int e = lane; e < D; e += kWave) {
       float q;
       if (kBf16) q = __uint_as_float((uint32_t)static_cast<const uint16_t*>(a.pred)[row_elem + e] << 16);
       else q = static_cast<const float*>(a.pred)[row_elem + e];
-      const float diff = q - (t[e] - mu) * rstd;
+      const float diff = kNorm ? q - (t[e] - mu) * rstd : q - t[e];
       sq += diff * diff;
       if (a.grad) {
         if (kBf16) static_cast<uint16_t*>(a.grad)[row_elem + e] = (uint16_t)bf16_rne(diff * a.gscale);
@@ -188,27 +196,39 @@ int loss_grid_waves(int64_t rows) {
   return (int)blocks * kLossWaves;
 }
 
-template <bool kBf16>
+template <bool kBf16, bool kNorm>
 static void launch_vec(const LossArgs& a, dim3 grid, dim3 block, hipStream_t stream) {
   const int nv = ((a.D >> 2) + kWave - 1) / kWave;
-  if (nv <= 1) hipLaunchKernelGGL((normpix_loss_kernel<1, kBf16>), grid, block, 0, stream, a);
-  else if (nv <= 2) hipLaunchKernelGGL((normpix_loss_kernel<2, kBf16>), grid, block, 0, stream, a);
-  else if (nv <= 3) hipLaunchKernelGGL((normpix_loss_kernel<3, kBf16>), grid, block, 0, stream, a);
-  else if (nv <= 4) hipLaunchKernelGGL((normpix_loss_kernel<4, kBf16>), grid, block, 0, stream, a);
-  else if (nv <= 6) hipLaunchKernelGGL((normpix_loss_kernel<6, kBf16>), grid, block, 0, stream, a);
-  else if (nv <= 8) hipLaunchKernelGGL((normpix_loss_kernel<8, kBf16>), grid, block, 0, stream, a);
-  else hipLaunchKernelGGL((normpix_loss_kernel<12, kBf16>), grid, block, 0, stream, a);
+#define MAE_LAUNCH(NV) \
+  hipLaunchKernelGGL((normpix_loss_kernel<NV, kBf16, kNorm>), grid, block, 0, stream, a)
+  if (nv <= 1) MAE_LAUNCH(1);
+  else if (nv <= 2) MAE_LAUNCH(2);
+  else if (nv <= 3) MAE_LAUNCH(3);
+  else if (nv <= 4) MAE_LAUNCH(4);
+  else if (nv <= 6) MAE_LAUNCH(6);
+  else if (nv <= 8) MAE_LAUNCH(8);
+  else MAE_LAUNCH(12);
+#undef MAE_LAUNCH
+}
+
+template <bool kBf16, bool kNorm>
+static void launch_any(const LossArgs& a, dim3 grid, dim3 block, hipStream_t stream) {
+  const bool vec = (a.D & 3) == 0 && (a.D >> 2) <= 12 * kWave;
+  if (vec) {
+    launch_vec<kBf16, kNorm>(a, grid, block, stream);
+  } else {
+    hipLaunchKernelGGL((normpix_loss_scalar_kernel<kBf16, kNorm>), grid, block, 0, stream, a);
+  }
 }
 
 hipError_t launch_normpix_loss(const LossArgs& a, hipStream_t stream) {
   dim3 grid(a.num_partials / kLossWaves), block(kLossThreads);
-  const bool vec = (a.D & 3) == 0 && (a.D >> 2) <= 12 * kWave;
-  if (vec) {
-    if (a.pred_bf16) launch_vec<true>(a, grid, block, stream);
-    else launch_vec<false>(a, grid, block, stream);
+  if (a.pred_bf16) {
+    if (a.norm_pix) launch_any<true, true>(a, grid, block, stream);
+    else launch_any<true, false>(a, grid, block, stream);
   } else {
-    if (a.pred_bf16) hipLaunchKernelGGL(normpix_loss_scalar_kernel<true>, grid, block, 0, stream, a);
-    else hipLaunchKernelGGL(normpix_loss_scalar_kernel<false>, grid, block, 0, stream, a);
+    if (a.norm_pix) launch_any<false, true>(a, grid, block, stream);
+    else launch_any<false, false>(a, grid, block, stream);
   }
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;

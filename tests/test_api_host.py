@@ -130,6 +130,7 @@ def _loss_desc(**over):
     d.B, d.L, d.D = 2, 196, 768
     d.pred = d.target = d.mask = FAKE
     d.num_masked, d.eps, d.grad_scale, d.pred_dtype = 294, 1e-6, 1.0, 0
+    d.norm_pix = 1
     for k, v in over.items():
         setattr(d, k, v)
     return d
@@ -147,6 +148,7 @@ def _loss_desc(**over):
     (dict(eps=-1.0), binding.MAE_ERR_RANGE),
     (dict(grad_scale=float("inf")), binding.MAE_ERR_RANGE),
     (dict(pred_dtype=2), binding.MAE_ERR_DTYPE),
+    (dict(norm_pix=2), binding.MAE_ERR_RANGE),
 ])
 def test_loss_rejects_bad_descriptors(lib, over, status):
     d = _loss_desc(**over)
@@ -185,3 +187,30 @@ def test_binding_does_not_fall_back_when_the_library_is_missing(monkeypatch, tmp
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "libmae_hip.so"))
     with pytest.raises(FileNotFoundError):
         binding.load()
+
+
+def test_progressive_tables_match_the_paper(lib, golden):
+    for row in golden("progressive_schemes.txt"):
+        if row[0] == "pretrain":
+            assert mae.mae_pretrain_stage(int(row[1]), int(row[2])) == (int(row[3]), float(row[4]))
+        elif row[0] == "finetune":
+            res, lo, hi = mae.mae_finetune_stage(int(row[1]), int(row[2]))
+            assert res == int(row[3])
+            assert lo == pytest.approx(float(row[4]) ** 2, rel=1e-6)
+            assert hi == pytest.approx(float(row[5]) ** 2, rel=1e-6)
+        elif row[0] == "lengths":
+            lengths = [int(v) for v in row[1:]]
+            for epoch in (0, 29, 30, 59, 60, 99, 100, 1000):
+                assert mae.mae_stage_of_epoch(epoch, lengths) == oracle.stage_of_epoch(epoch,
+                                                                                      lengths)
+    for scheme in range(1, 7):
+        for stage in (1, 2, 3):
+            assert mae.mae_pretrain_stage(scheme, stage) == oracle.pretrain_stage(scheme, stage)
+    for bad in ((0, 1), (7, 1), (1, 0), (1, 4)):
+        with pytest.raises(mae.MaeError):
+            mae.mae_pretrain_stage(*bad)
+    with pytest.raises(mae.MaeError):
+        mae.mae_finetune_stage(2, 1)
+    with pytest.raises(mae.MaeError):
+        mae.mae_stage_of_epoch(-1, [1, 2])
+    assert mae.mae_stage_of_epoch(0, [0, 0, 5]) == 3

@@ -77,13 +77,28 @@ MUTATIONS = [
      ["test_loss_normalised_target_statistics"]),
     ("eps outside the root", "double sd = sqrt(var + eps);", "double sd = sqrt(var) + eps;",
      ["test_loss_normalised_target_statistics"]),
-    ("gradient factor", "grad_scale * 2.0 * diff", "grad_scale * diff",
+    ("gradient factor", "mask[row] ? (float)(grad_scale * 2.0 * diff / ((double)D * M)) : 0.0f;\n    }\n    row_losses",
+     "mask[row] ? (float)(grad_scale * diff / ((double)D * M)) : 0.0f;\n    }\n    row_losses",
      ["test_loss_euler_identity_and_finite_differences"]),
+    ("pixel loss normalises anyway", "double diff = (double)pred[row * D + e] - (double)target[row * D + e];",
+     "double diff = (double)pred[row * D + e] - 0.5 * (double)target[row * D + e];",
+     ["test_pixel_loss_against_library_and_closed_form"]),
+    ("pixel loss divisor", "if (mask[row]) total += row_loss / (double)D;",
+     "if (mask[row]) total += row_loss;", ["test_pixel_loss_against_library_and_closed_form"]),
+    ("scheme 5 not a palindrome", "{224, 192, 224},  /* 5: palindrome   ",
+     "{224, 192, 160},  /* 5: palindrome   ", ["test_progressive_schemes_match_the_printed_tables"]),
+    ("scheme 4 ratios", "{0.75, 0.80, 0.85}, {0.75, 0.75, 0.75}, {0.75, 0.75, 0.85},",
+     "{0.75, 0.80, 0.80}, {0.75, 0.75, 0.75}, {0.75, 0.75, 0.85},",
+     ["test_progressive_schemes_match_the_printed_tables"]),
+    ("stage boundary", "if (epoch < end) return s + 1;", "if (epoch <= end) return s + 1;",
+     ["test_progressive_schemes_match_the_printed_tables"]),
     ("loss over all rows", "if (mask[row]) total += row_losses[row];",
      "total += row_losses[row];", ["test_loss_constant_offset_closed_form"]),
     ("per-row mean dropped", "row_losses[row] = row_loss / (double)D;",
      "row_losses[row] = row_loss;", ["test_loss_constant_offset_closed_form"]),
-    ("gradient on visible rows", "mask[row] ? (float)(grad_scale", "1 ? (float)(grad_scale",
+    ("gradient on visible rows",
+     "mask[row] ? (float)(grad_scale * 2.0 * diff / ((double)D * M)) : 0.0f;\n    }\n    row_losses",
+     "(float)(grad_scale * 2.0 * diff / ((double)D * M));\n    }\n    row_losses",
      ["test_loss_against_library_autograd"]),
 ]
 
