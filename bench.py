@@ -27,7 +27,8 @@ LOSS_KERNEL_SOURCES = ("paper_2404_00509_amd/csrc/normpix_loss.hip",
                        "paper_2404_00509_amd/csrc/mae_device.hpp")
 MEASURED_TRAFFIC = {
     # workload: (sha256 of the sources above, bytes read + written per launch)
-    "c4": ("75ab182b4c9711279cc5b328d23c738b9c16f24371b4abebb8fa708da1ba5c2e", 6.172e9),
+    "c4": ("593cd9679e77dfa300422701f1a4e5673c14a5996482c16b0f6f7d2392f20fd5", 6.172e9),
+    "c5": ("593cd9679e77dfa300422701f1a4e5673c14a5996482c16b0f6f7d2392f20fd5", 4.416e9),
 }
 
 

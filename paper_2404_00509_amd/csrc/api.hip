@@ -199,8 +199,9 @@ int mae_prep_status(const void* workspace, void* hip_stream, int32_t* host_inval
 
 size_t mae_loss_workspace_bytes(const mae_loss_desc* d) {
   if (validate_loss(d) != MAE_OK) return 0;
-  const int waves = mae::loss_grid_waves((int64_t)d->B * d->L);
-  return (size_t)waves * sizeof(double);
+  const mae::LossShape sh =
+      mae::loss_shape((int64_t)d->B * d->L, d->D, d->pred_dtype == MAE_BF16);
+  return (size_t)sh.waves * sizeof(double);
 }
 
 int mae_normpix_loss(const mae_loss_desc* d, float* loss, void* grad, void* workspace,
@@ -232,7 +233,9 @@ int mae_normpix_loss(const mae_loss_desc* d, float* loss, void* grad, void* work
   la.grad = grad;
   la.loss = loss;
   la.partials = static_cast<double*>(workspace);
-  la.num_partials = mae::loss_grid_waves(la.rows);
+  const mae::LossShape sh = mae::loss_shape(la.rows, la.D, la.pred_bf16 != 0);
+  la.num_partials = sh.waves;
+  la.rows_per_iter = sh.rows_per_iter;
   if (mae::launch_normpix_loss(la, stream) != hipSuccess) return MAE_ERR_HIP;
   return MAE_OK;
 }

@@ -64,8 +64,13 @@ struct LossArgs {
   float* loss;
   double* partials;  // workspace: one per wavefront of the grid
   int32_t num_partials;
+  int32_t rows_per_iter;  // adjacent rows a wavefront handles per pass (1 or 2)
 };
-int loss_grid_waves(int64_t rows);
+struct LossShape {
+  int waves;          // wavefronts of the grid = number of partials
+  int rows_per_iter;
+};
+LossShape loss_shape(int64_t rows, int D, bool pred_bf16);
 hipError_t launch_normpix_loss(const LossArgs& a, hipStream_t stream);
 
 }  // namespace mae

@@ -2,7 +2,7 @@
 // of the paper adopts): per patch row, target statistics -> normalised target -> squared error
 // against the prediction on masked rows.
 //
-// Streaming kernel: one wavefront per patch row, the row held in registers (16-byte loads, lane i
+// Streaming kernel: one wavefront per pair of adjacent patch rows, the rows held in registers (16-byte loads, lane i
 // takes the i-th, (i+64)-th, ... group), two butterfly reductions for mean and variance, gradient
 // written with 16-byte stores.  Nothing is read twice, so loads and stores carry the
 // non-temporal hint.  Rows are dealt to the wavefronts of the grid round-robin, which keeps the
@@ -17,7 +17,7 @@ namespace mae {
 
 constexpr int kLossThreads = 256;
 constexpr int kLossWaves = kLossThreads / kWave;
-constexpr int kLossMaxBlocks = 256 * 4;  // 4 workgroups (16 wavefronts) per compute unit
+constexpr int kComputeUnits = 256;
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -57,7 +57,8 @@ __device__ static inline void store_grad4(void* grad, int64_t elem, f32x4 g) {
 
 // NV = 16-byte groups per lane; D / 4 <= 64 NV.
 // kNorm: per-patch normalised target (the recipe's objective); otherwise the target as it is.
-template <int NV, bool kBf16, bool kNorm>
+// kRowsPerIter: adjacent rows a wavefront handles per pass.
+template <int NV, int kRowsPerIter, bool kBf16, bool kNorm>
 __global__ __launch_bounds__(kLossThreads) void normpix_loss_kernel(LossArgs a) {
   const int lane = threadIdx.x % kWave;
   const int wave_in_grid = blockIdx.x * kLossWaves + threadIdx.x / kWave;
@@ -67,59 +68,74 @@ __global__ __launch_bounds__(kLossThreads) void normpix_loss_kernel(LossArgs a) 
   const float inv_dm1 = 1.0f / (float)(D - 1);
   double acc = 0.0;
 
-  for (int64_t row = wave_in_grid; row < a.rows; row += waves) {
-    const int64_t row_elem = row * D;
-    if (a.mask[row] == 0) {
-      if (a.grad) {
+  // kRowsPerIter adjacent rows per pass: all their loads are issued before the first reduction,
+  // and each wavefront touches one contiguous span of every tensor.
+  for (int64_t row0 = kRowsPerIter * (int64_t)wave_in_grid; row0 < a.rows;
+       row0 += kRowsPerIter * (int64_t)waves) {
+    f32x4 t[kRowsPerIter][NV], q[kRowsPerIter][NV];
+    bool masked[kRowsPerIter];
 #pragma unroll
-        for (int v = 0; v < NV; ++v) {
-          const int g = lane + v * kWave;
-          if (g < D4) store_grad4<kBf16>(a.grad, row_elem + 4 * g, f32x4{0.f, 0.f, 0.f, 0.f});
-        }
-      }
-      continue;
-    }
-    f32x4 t[NV], q[NV];
-#pragma unroll
-    for (int v = 0; v < NV; ++v) {
-      const int g = lane + v * kWave;
-      if (g < D4) {
-        t[v] = __builtin_nontemporal_load(
-            reinterpret_cast<const f32x4*>(a.target + row_elem + 4 * g));
-        q[v] = load_pred4<kBf16>(a.pred, row_elem + 4 * g);
-      } else {
-        t[v] = f32x4{0.f, 0.f, 0.f, 0.f};
-        q[v] = t[v];
-      }
-    }
-    float rstd = 1.0f;
-    if (kNorm) {
-      float s = 0.f;
-#pragma unroll
-      for (int v = 0; v < NV; ++v) s += (t[v].x + t[v].y) + (t[v].z + t[v].w);
-      const float mu = wave_sum(s) * inv_d;
-      float ss = 0.f;
+    for (int u = 0; u < kRowsPerIter; ++u) {
+      const int64_t row = row0 + u;
+      masked[u] = row < a.rows && a.mask[row] != 0;
+      const int64_t row_elem = row * D;
 #pragma unroll
       for (int v = 0; v < NV; ++v) {
         const int g = lane + v * kWave;
-        t[v] = t[v] - mu;
-        if (g < D4)
-          ss += (t[v].x * t[v].x + t[v].y * t[v].y) + (t[v].z * t[v].z + t[v].w * t[v].w);
+        t[u][v] = f32x4{0.f, 0.f, 0.f, 0.f};
+        q[u][v] = t[u][v];
+        if (masked[u] && g < D4) {
+          t[u][v] = __builtin_nontemporal_load(
+              reinterpret_cast<const f32x4*>(a.target + row_elem + 4 * g));
+          q[u][v] = load_pred4<kBf16>(a.pred, row_elem + 4 * g);
+        }
       }
-      const float var = wave_sum(ss) * inv_dm1;
-      rstd = 1.0f / sqrtf(var + a.eps);
     }
-    float sq = 0.f;
 #pragma unroll
-    for (int v = 0; v < NV; ++v) {
-      const int g = lane + v * kWave;
-      const f32x4 diff = kNorm ? q[v] - t[v] * rstd : q[v] - t[v];
-      if (g < D4) {
-        sq += (diff.x * diff.x + diff.y * diff.y) + (diff.z * diff.z + diff.w * diff.w);
-        if (a.grad) store_grad4<kBf16>(a.grad, row_elem + 4 * g, diff * a.gscale);
+    for (int u = 0; u < kRowsPerIter; ++u) {
+      const int64_t row = row0 + u;
+      if (row >= a.rows) continue;
+      const int64_t row_elem = row * D;
+      if (!masked[u]) {  // visible patch: the gradient is zero, nothing was read
+        if (a.grad) {
+#pragma unroll
+          for (int v = 0; v < NV; ++v) {
+            const int g = lane + v * kWave;
+            if (g < D4) store_grad4<kBf16>(a.grad, row_elem + 4 * g, f32x4{0.f, 0.f, 0.f, 0.f});
+          }
+        }
+        continue;
       }
+      float rstd = 1.0f;
+      if (kNorm) {
+        float s = 0.f;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) s += (t[u][v].x + t[u][v].y) + (t[u][v].z + t[u][v].w);
+        const float mu = wave_sum(s) * inv_d;
+        float ss = 0.f;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+          const int g = lane + v * kWave;
+          t[u][v] = t[u][v] - mu;
+          if (g < D4)
+            ss += (t[u][v].x * t[u][v].x + t[u][v].y * t[u][v].y) +
+                  (t[u][v].z * t[u][v].z + t[u][v].w * t[u][v].w);
+        }
+        const float var = wave_sum(ss) * inv_dm1;
+        rstd = 1.0f / sqrtf(var + a.eps);
+      }
+      float sq = 0.f;
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        const int g = lane + v * kWave;
+        const f32x4 diff = kNorm ? q[u][v] - t[u][v] * rstd : q[u][v] - t[u][v];
+        if (g < D4) {
+          sq += (diff.x * diff.x + diff.y * diff.y) + (diff.z * diff.z + diff.w * diff.w);
+          if (a.grad) store_grad4<kBf16>(a.grad, row_elem + 4 * g, diff * a.gscale);
+        }
+      }
+      acc += (double)sq;
     }
-    acc += (double)sq;
   }
   acc = wave_sum(acc);
   if (lane == 0) a.partials[wave_in_grid] = acc;
@@ -189,25 +205,44 @@ __global__ __launch_bounds__(kLossThreads) void loss_finish_kernel(const double*
   if (threadIdx.x == 0) *loss = (float)(red[0] * inv_count);
 }
 
-int loss_grid_waves(int64_t rows) {
-  int64_t blocks = (rows + kLossWaves - 1) / kLossWaves;
-  if (blocks > kLossMaxBlocks) blocks = kLossMaxBlocks;
+// Launch shape.  What counts is the amount of row data in flight per compute unit (about 144 KiB
+// measured best on MI355X) and that every compute unit gets the same number of workgroups.  Rows
+// that bring 6 KiB or more of loads (D = 768 in fp32) go two per pass with 3 workgroups per compute
+// unit; shorter rows one per pass with 6.
+LossShape loss_shape(int64_t rows, int D, bool pred_bf16) {
+  LossShape sh;
+  const int nv = ((D >> 2) + kWave - 1) / kWave;
+  const int64_t load_bytes = (int64_t)D * (pred_bf16 ? 6 : 8);
+  const bool vec = (D & 3) == 0 && (D >> 2) <= 12 * kWave;
+  sh.rows_per_iter = (vec && nv <= 4 && load_bytes >= 6144) ? 2 : 1;
+  const int64_t rows_per_block = (int64_t)kLossWaves * sh.rows_per_iter;
+  int64_t blocks = (rows + rows_per_block - 1) / rows_per_block;
+  const int64_t cap = (int64_t)kComputeUnits * (sh.rows_per_iter == 2 ? 3 : 6);
+  if (blocks > cap) blocks = cap;
   if (blocks < 1) blocks = 1;
-  return (int)blocks * kLossWaves;
+  sh.waves = (int)blocks * kLossWaves;
+  return sh;
 }
 
 template <bool kBf16, bool kNorm>
 static void launch_vec(const LossArgs& a, dim3 grid, dim3 block, hipStream_t stream) {
   const int nv = ((a.D >> 2) + kWave - 1) / kWave;
-#define MAE_LAUNCH(NV) \
-  hipLaunchKernelGGL((normpix_loss_kernel<NV, kBf16, kNorm>), grid, block, 0, stream, a)
-  if (nv <= 1) MAE_LAUNCH(1);
-  else if (nv <= 2) MAE_LAUNCH(2);
-  else if (nv <= 3) MAE_LAUNCH(3);
-  else if (nv <= 4) MAE_LAUNCH(4);
-  else if (nv <= 6) MAE_LAUNCH(6);
-  else if (nv <= 8) MAE_LAUNCH(8);
-  else MAE_LAUNCH(12);
+#define MAE_LAUNCH(NV, RPI) \
+  hipLaunchKernelGGL((normpix_loss_kernel<NV, RPI, kBf16, kNorm>), grid, block, 0, stream, a)
+  if (a.rows_per_iter == 2) {
+    if (nv <= 1) MAE_LAUNCH(1, 2);
+    else if (nv <= 2) MAE_LAUNCH(2, 2);
+    else if (nv <= 3) MAE_LAUNCH(3, 2);
+    else MAE_LAUNCH(4, 2);
+  } else {
+    if (nv <= 1) MAE_LAUNCH(1, 1);
+    else if (nv <= 2) MAE_LAUNCH(2, 1);
+    else if (nv <= 3) MAE_LAUNCH(3, 1);
+    else if (nv <= 4) MAE_LAUNCH(4, 1);
+    else if (nv <= 6) MAE_LAUNCH(6, 1);
+    else if (nv <= 8) MAE_LAUNCH(8, 1);
+    else MAE_LAUNCH(12, 1);
+  }
 #undef MAE_LAUNCH
 }
 
