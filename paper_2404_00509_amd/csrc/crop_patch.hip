@@ -7,12 +7,14 @@
 //    words.  Lane i of a wavefront loads the 16 bytes that hold pixels 4i..4i+3 of a row (one
 //    4-byte-aligned global_load_dwordx4; the row's misalignment is taken out with byte-align
 //    operations in registers) and writes four pixel words with one ds_write_b128.  All loads of a
-//    wavefront (up to six rows) are issued before the first is consumed, and the tap tables
+//    wavefront (up to seven rows) are issued before the first is consumed, and the tap tables
 //    (S horizontal entries, p vertical entries, integer tap positions + fp32 weights) are built
 //    while they are in flight.
-//  * Compute + store.  Each wavefront then produces whole patches: lane i writes the i-th 16-byte
-//    group of the patch, so every store instruction covers 1 KiB of contiguous memory.  A group
-//    of four consecutive values spans two neighbouring pixels; the taps x and x+1 come from one
+//  * Compute + store.  A patch is D/4 groups of 16 bytes; wavefront w of the workgroup owns groups
+//    64w .. 64w+63 (one per lane) of EVERY patch of the row, so what depends only on the position
+//    inside the patch (rows tapped, vertical weights, channel constants, byte selectors) is set
+//    up once, and every store instruction covers 1 KiB of contiguous memory.  A group of four
+//    consecutive values spans two neighbouring pixels; the taps x and x+1 come from one
 //    ds_read2_b32 per row, and one byte-permute per tap row pulls exactly the four bytes needed
 //    out of the two pixel words.  Nothing inside the loop reads global memory, so the stores of
 //    one patch never have to complete before the next patch is computed.
@@ -21,9 +23,9 @@
 
 namespace mae {
 
-constexpr int kCropThreads = 256;
-constexpr int kCropWaves = kCropThreads / kWave;
-constexpr int kStageRows = 6;  // rows per wavefront whose loads are issued together
+constexpr int kCropThreads = 256;      // scalar kernel
+constexpr int kCropMaxThreads = 1024;  // resampling kernel: 64 threads per 64 groups of a patch
+constexpr int kStageRows = 7;  // rows per wavefront whose loads are issued together
 constexpr int kCropMaxLds = 64 * 1024;  // dynamic LDS available without opting in to more
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -89,9 +91,10 @@ __device__ static inline u32x4 to_pixels(u32x4 d, uint32_t s) {
                e2 >> 8};
 }
 
-// The compute + store phase of one workgroup.  kLds: taps come from the staged tile (row offsets
-// in pixel words), otherwise straight from global memory (row offsets in bytes; crops too large
-// to stage).  my_rank holds, in lane i, the noise rank of patch i of this row of patches.
+// The compute + store phase of one wavefront: its 64 groups of every patch.  kLds: taps come from
+// the staged tile (row offsets in pixel words), otherwise straight from global memory (row offsets
+// in bytes; crops too large to stage).  my_rank holds, in lane i, the noise rank of patch i of
+// this row of patches.
 template <bool kLds, bool kBf16>
 __device__ static void produce_patches(const CropArgs& a, const uint32_t* tile, const u32x2* xtab,
                                        const u32x4* ytab, const uint8_t* base, int b, int gy,
@@ -105,78 +108,76 @@ __device__ static void produce_patches(const CropArgs& a, const uint32_t* tile, 
   const float ns0 = a.nscale[0], ns1 = a.nscale[1], ns2 = a.nscale[2];
   const float nb0 = a.nbias[0], nb1 = a.nbias[1], nb2 = a.nbias[2];
 
-  for (int k0 = 0; k0 < D4; k0 += kWave) {
-    const int e4 = k0 + lane;
-    const bool active = e4 < D4;
-    const int e = active ? 4 * e4 : 0;
-    // elements e .. e+3 belong to pixel qA (channels cA ..) and to the next pixel qB
-    const int qA = e / 3;
-    const int cA = e - 3 * qA;
-    const int qB = min(qA + 1, pp - 1);
-    const int pyA = (int)(((float)qA + 0.5f) * inv_p);
-    const int pxA = qA - pyA * p;
-    const int pyB = (int)(((float)qB + 0.5f) * inv_p);
-    const int pxB = qB - pyB * p;
-    const u32x4 ya = ytab[pyA], yb = ytab[pyB];
-    const uint32_t rowA0 = ya.x, rowA1 = ya.y, rowB0 = yb.x, rowB1 = yb.y;
-    const float fyA = __uint_as_float(ya.z), fyB = __uint_as_float(yb.z);
-    // byte selectors: A's bytes are 0..2, B's bytes are 4..6 of the 64-bit pair {B, A}
-    const uint32_t sel = cA == 0 ? 0x04020100u : (cA == 1 ? 0x05040201u : 0x06050402u);
-    const int nA = 3 - cA;  // how many of the four values come from pixel A (1..3)
-    float sc[4], bi[4], fy[4];
+  const int e4 = wave * kWave + lane;
+  const bool active = e4 < D4;
+  const int e = active ? 4 * e4 : 0;
+  // elements e .. e+3 belong to pixel qA (channels cA ..) and to the next pixel qB
+  const int qA = e / 3;
+  const int cA = e - 3 * qA;
+  const int qB = min(qA + 1, pp - 1);
+  const int pyA = (int)(((float)qA + 0.5f) * inv_p);
+  const int pxA = qA - pyA * p;
+  const int pyB = (int)(((float)qB + 0.5f) * inv_p);
+  const int pxB = qB - pyB * p;
+  const u32x4 ya = ytab[pyA], yb = ytab[pyB];
+  const uint32_t rowA0 = ya.x, rowA1 = ya.y, rowB0 = yb.x, rowB1 = yb.y;
+  const float fyA = __uint_as_float(ya.z), fyB = __uint_as_float(yb.z);
+  // byte selectors: A's bytes are 0..2, B's bytes are 4..6 of the 64-bit pair {B, A}
+  const uint32_t sel = cA == 0 ? 0x04020100u : (cA == 1 ? 0x05040201u : 0x06050402u);
+  const int nA = 3 - cA;  // how many of the four values come from pixel A (1..3)
+  float sc[4], bi[4], fy[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      int c = cA + j;
-      c = c >= 3 ? c - 3 : c;
-      c = c >= 3 ? c - 3 : c;
-      sc[j] = c == 0 ? ns0 : (c == 1 ? ns1 : ns2);
-      bi[j] = c == 0 ? nb0 : (c == 1 ? nb1 : nb2);
-      fy[j] = j == 0 ? fyA : (j == 3 ? fyB : (j < nA ? fyA : fyB));
-    }
-
-    for (int gx = wave; gx < G; gx += kCropWaves) {
-      const int l = gy * G + gx;
-      const int rank = __builtin_amdgcn_readlane(my_rank, gx);
-      const u32x2 xa = xtab[gx * p + pxA], xb = xtab[gx * p + pxB];
-      const float fxA = __uint_as_float(xa.y), fxB = __uint_as_float(xb.y);
-      uint32_t A00, A01, A10, A11, B00, B01, B10, B11;
-      fetch2<kLds>(tile, base, rowA0, (int)xa.x, cw, A00, A01);
-      fetch2<kLds>(tile, base, rowA1, (int)xa.x, cw, A10, A11);
-      fetch2<kLds>(tile, base, rowB0, (int)xb.x, cw, B00, B01);
-      fetch2<kLds>(tile, base, rowB1, (int)xb.x, cw, B10, B11);
-      const uint32_t P00 = __builtin_amdgcn_perm(B00, A00, sel);
-      const uint32_t P01 = __builtin_amdgcn_perm(B01, A01, sel);
-      const uint32_t P10 = __builtin_amdgcn_perm(B10, A10, sel);
-      const uint32_t P11 = __builtin_amdgcn_perm(B11, A11, sel);
-
-      float out[4];
-#define MAE_BLEND(J)                                                                 \
-  {                                                                                  \
-    const float fx = (J) == 0 ? fxA : ((J) == 3 ? fxB : ((J) < nA ? fxA : fxB));     \
-    const float a00 = byte_to_float<J>(P00), a01 = byte_to_float<J>(P01);            \
-    const float a10 = byte_to_float<J>(P10), a11 = byte_to_float<J>(P11);            \
-    const float rt = a00 + fx * (a01 - a00);                                         \
-    const float rb = a10 + fx * (a11 - a10);                                         \
-    const float v = rt + fy[J] * (rb - rt);                                          \
-    out[J] = v * sc[J] + bi[J];                                                      \
+  for (int j = 0; j < 4; ++j) {
+    int c = cA + j;
+    c = c >= 3 ? c - 3 : c;
+    c = c >= 3 ? c - 3 : c;
+    sc[j] = c == 0 ? ns0 : (c == 1 ? ns1 : ns2);
+    bi[j] = c == 0 ? nb0 : (c == 1 ? nb1 : nb2);
+    fy[j] = j == 0 ? fyA : (j == 3 ? fyB : (j < nA ? fyA : fyB));
   }
-      MAE_BLEND(0) MAE_BLEND(1) MAE_BLEND(2) MAE_BLEND(3)
+
+  for (int gx = 0; gx < G; ++gx) {
+    const int l = gy * G + gx;
+    const int rank = __builtin_amdgcn_readlane(my_rank, gx);
+    const u32x2 xa = xtab[gx * p + pxA], xb = xtab[gx * p + pxB];
+    const float fxA = __uint_as_float(xa.y), fxB = __uint_as_float(xb.y);
+    uint32_t A00, A01, A10, A11, B00, B01, B10, B11;
+    fetch2<kLds>(tile, base, rowA0, (int)xa.x, cw, A00, A01);
+    fetch2<kLds>(tile, base, rowA1, (int)xa.x, cw, A10, A11);
+    fetch2<kLds>(tile, base, rowB0, (int)xb.x, cw, B00, B01);
+    fetch2<kLds>(tile, base, rowB1, (int)xb.x, cw, B10, B11);
+    const uint32_t P00 = __builtin_amdgcn_perm(B00, A00, sel);
+    const uint32_t P01 = __builtin_amdgcn_perm(B01, A01, sel);
+    const uint32_t P10 = __builtin_amdgcn_perm(B10, A10, sel);
+    const uint32_t P11 = __builtin_amdgcn_perm(B11, A11, sel);
+
+    float out[4];
+#define MAE_BLEND(J)                                                                 \
+{                                                                                  \
+  const float fx = (J) == 0 ? fxA : ((J) == 3 ? fxB : ((J) < nA ? fxA : fxB));     \
+  const float a00 = byte_to_float<J>(P00), a01 = byte_to_float<J>(P01);            \
+  const float a10 = byte_to_float<J>(P10), a11 = byte_to_float<J>(P11);            \
+  const float rt = a00 + fx * (a01 - a00);                                         \
+  const float rb = a10 + fx * (a11 - a10);                                         \
+  const float v = rt + fy[J] * (rb - rt);                                          \
+  out[J] = v * sc[J] + bi[J];                                                      \
+}
+    MAE_BLEND(0) MAE_BLEND(1) MAE_BLEND(2) MAE_BLEND(3)
 #undef MAE_BLEND
 
-      if (active) {
-        if (a.target) {
-          f32x4* dst = reinterpret_cast<f32x4*>(a.target + ((int64_t)b * a.L + l) * D + e);
+    if (active) {
+      if (a.target) {
+        f32x4* dst = reinterpret_cast<f32x4*>(a.target + ((int64_t)b * a.L + l) * D + e);
+        *dst = f32x4{out[0], out[1], out[2], out[3]};
+      }
+      if (rank < a.K) {
+        const int64_t vo = ((int64_t)b * a.K + rank) * D + e;
+        if (kBf16) {
+          u32x2* dst = reinterpret_cast<u32x2*>(static_cast<uint16_t*>(a.visible) + vo);
+          *dst = u32x2{pack_bf16x2(out[0], out[1]), pack_bf16x2(out[2], out[3])};
+        } else {
+          f32x4* dst = reinterpret_cast<f32x4*>(static_cast<float*>(a.visible) + vo);
           *dst = f32x4{out[0], out[1], out[2], out[3]};
-        }
-        if (rank < a.K) {
-          const int64_t vo = ((int64_t)b * a.K + rank) * D + e;
-          if (kBf16) {
-            u32x2* dst = reinterpret_cast<u32x2*>(static_cast<uint16_t*>(a.visible) + vo);
-            *dst = u32x2{pack_bf16x2(out[0], out[1]), pack_bf16x2(out[2], out[3])};
-          } else {
-            f32x4* dst = reinterpret_cast<f32x4*>(static_cast<float*>(a.visible) + vo);
-            *dst = f32x4{out[0], out[1], out[2], out[3]};
-          }
         }
       }
     }
@@ -185,7 +186,7 @@ __device__ static void produce_patches(const CropArgs& a, const uint32_t* tile, 
 
 // Dynamic LDS: [ tile: a.tile_pixels + 4 words | xtab: S x 8 bytes | ytab: p x 16 bytes ].
 template <bool kBf16>
-__global__ __launch_bounds__(kCropThreads) void crop_patch_kernel(CropArgs a) {
+__global__ __launch_bounds__(kCropMaxThreads) void crop_patch_kernel(CropArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
   uint32_t* tile = lds;
   u32x4* ytab = reinterpret_cast<u32x4*>(lds + a.tile_pixels + 4);  // row y0, row y1, weight
@@ -201,6 +202,7 @@ __global__ __launch_bounds__(kCropThreads) void crop_patch_kernel(CropArgs a) {
   const int W = a.widths[b];
   const int tid = threadIdx.x;
   const int lane = tid % kWave, wave = tid / kWave;
+  const int nwaves = (int)blockDim.x / kWave;
 
   // rows of the crop that this row of patches taps
   int ylo, yhi, t0, t1;
@@ -226,7 +228,7 @@ __global__ __launch_bounds__(kCropThreads) void crop_patch_kernel(CropArgs a) {
   if (batched) {  // these loads stay in flight while the tap tables are built
 #pragma unroll
     for (int u = 0; u < kStageRows; ++u) {
-      const int r = wave + u * kCropWaves;
+      const int r = wave + u * nwaves;
       d[u] = u32x4{0u, 0u, 0u, 0u};
       if (r < nrows && lane < ng) {
         const uint8_t* row = base + (int64_t)r * row_bytes;
@@ -237,26 +239,26 @@ __global__ __launch_bounds__(kCropThreads) void crop_patch_kernel(CropArgs a) {
     }
   }
 
-  for (int ox = tid; ox < S; ox += kCropThreads) {
+  for (int ox = tid; ox < S; ox += (int)blockDim.x) {
     int x0, x1;
     float f;
     resize_taps(rec.flip ? S - 1 - ox : ox, rec.cw, S, x0, x1, f);
     // at the right edge both taps are the last pixel: weight 0 makes the second tap irrelevant
     xtab[ox] = u32x2{(uint32_t)x0, __float_as_uint(x1 == x0 ? 0.0f : f)};
   }
-  if (tid < p) {
+  for (int py = tid; py < p; py += (int)blockDim.x) {
     int y0, y1;
     float f;
-    resize_taps(gy * p + tid, rec.ch, S, y0, y1, f);
+    resize_taps(gy * p + py, rec.ch, S, y0, y1, f);
     const uint32_t stride = use_lds ? (uint32_t)pitch : (uint32_t)row_bytes;
-    ytab[tid] = u32x4{(uint32_t)(y0 - ylo) * stride, (uint32_t)(y1 - ylo) * stride,
+    ytab[py] = u32x4{(uint32_t)(y0 - ylo) * stride, (uint32_t)(y1 - ylo) * stride,
                       __float_as_uint(f), 0u};
   }
 
   if (batched) {
 #pragma unroll
     for (int u = 0; u < kStageRows; ++u) {
-      const int r = wave + u * kCropWaves;
+      const int r = wave + u * nwaves;
       if (r < nrows && lane < ng) {
         const uint32_t s = (uint32_t)reinterpret_cast<uintptr_t>(base + (int64_t)r * row_bytes) & 3u;
         tile4[r * ng + lane] = to_pixels(d[u], s);
@@ -264,7 +266,7 @@ __global__ __launch_bounds__(kCropThreads) void crop_patch_kernel(CropArgs a) {
     }
   }
   if (use_lds) {  // rows beyond the first batch, and crops wider than 256 pixels
-    for (int r = batched ? wave + kStageRows * kCropWaves : wave; r < nrows; r += kCropWaves) {
+    for (int r = batched ? wave + kStageRows * nwaves : wave; r < nrows; r += nwaves) {
       const uint8_t* row = base + (int64_t)r * row_bytes;
       const uint32_t s = (uint32_t)reinterpret_cast<uintptr_t>(row) & 3u;
       const uint8_t* arow = row - s;
@@ -342,7 +344,7 @@ size_t crop_lds_bytes(int tile_pixels, int S, int p) {
 
 hipError_t launch_crop_patch(const CropArgs& a, hipStream_t stream) {
   if ((a.D & 3) == 0) {
-    dim3 grid((uint32_t)a.B * (uint32_t)a.G), block(kCropThreads);
+    dim3 grid((uint32_t)a.B * (uint32_t)a.G), block(kWave * (((a.D >> 2) + kWave - 1) / kWave));
     const size_t lds = crop_lds_bytes(a.tile_pixels, a.S, a.p);
     if (a.visible_bf16) {
       hipLaunchKernelGGL(crop_patch_kernel<true>, grid, block, lds, stream, a);
