@@ -369,3 +369,83 @@ def test_loss_zero_for_exact_prediction_and_reproducible():
     assert float(grad.abs().max().item()) * D * M < 1e-4
     loss2, grad2 = gpu_loss(*args, num_masked=M)
     assert loss2 == loss and torch.equal(grad, grad2)
+
+
+# ------------------------------------------------------------------------------------------------
+# buffer-edge and stream behaviour
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("shift", [1, 2, 3])
+def test_prep_image_buffer_with_unaligned_base_and_tight_end(shift):
+    # the staging loads are 4-byte aligned 16-byte reads; with an unaligned base pointer and no
+    # slack after the last image, the first and last bytes must come through the guarded path
+    shapes = [(40, 52), (64, 64), (33, 47), (80, 61)]
+    imgs = _random_images(shapes, seed=shift)
+    flat, offsets, h, w = _pack(imgs)
+    store = torch.zeros(flat.size + shift, dtype=torch.uint8, device="cuda")
+    store[shift:] = torch.from_numpy(flat).cuda()
+    dimg = (store[shift:], torch.from_numpy(offsets).cuda(), torch.from_numpy(h).cuda(),
+            torch.from_numpy(w).cuda())
+    assert dimg[0].data_ptr() % 4 == shift
+    for scale in ((1.0, 1.0), (0.2, 1.0)):
+        kw = dict(out_size=32, patch=16, num_keep=2, scale=scale, ratio=(1.0, 1.0), seed=shift)
+        ref = oracle.prep_batch(flat, offsets, h, w, **kw)
+        buf, _, _ = gpu_prep(flat, offsets, h, w, device_inputs=dimg, **kw)
+        check_prep_against_oracle(prep_to_numpy(buf), ref, what=f"shift{shift}")
+
+
+def test_path_on_a_side_stream_and_in_a_captured_graph():
+    wl = synth.WORKLOADS["c1"]
+    data = synth.make_images(wl.kind, 32, seed=2)
+    kw = _kw(wl, seed=1, batch_index=4)
+    ref = oracle.prep_batch(*data, **kw)
+    K, M = kw["num_keep"], 32 * (wl.L - kw["num_keep"])
+    pred_host = synth.make_pred(3, 32, wl.L, wl.D)
+    ref_loss, ref_grad, _ = oracle.normpix_loss(pred_host, ref["target"], ref["mask"],
+                                                num_masked=M)
+    dimg = to_device(*data)
+    pred = torch.from_numpy(pred_host).cuda()
+    desc = mae.make_prep_desc(*dimg, **kw)
+    buf = mae.alloc_prep_buffers(desc)
+    ldesc = mae.make_loss_desc(pred, buf.target, buf.mask, num_masked=M)
+    lws = torch.empty(max(mae.mae_loss_workspace_bytes(ldesc), 256), dtype=torch.uint8,
+                      device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    grad = torch.empty_like(pred)
+
+    def step(stream):
+        mae.mae_prep_batch(desc, buf.visible, buf.mask, buf.ids_restore, buf.ids_keep, buf.target,
+                           buf.crop, buf.workspace, stream=stream)
+        mae.mae_normpix_loss(ldesc, loss, grad, lws, stream=stream)
+
+    def check(what):
+        torch.cuda.synchronize()
+        check_prep_against_oracle(prep_to_numpy(buf), ref, what=what)
+        assert abs(loss.item() - ref_loss) <= ATOL + RTOL * abs(ref_loss), what
+        check_grad(grad.cpu().numpy(), ref_grad, wl.D, M, what=what)
+
+    def wipe():
+        for t in (buf.visible, buf.target, grad):
+            t.fill_(float("nan"))
+        buf.ids_restore.fill_(-1)
+        loss.fill_(-1.0)
+        torch.cuda.synchronize()
+
+    side = torch.cuda.Stream()
+    wipe()
+    with torch.cuda.stream(side):
+        step(side)
+    side.synchronize()
+    check("side stream")
+
+    # the calls enqueue only kernels (no memset, no copy, no sync), so they can be captured;
+    # every replay is checked against the oracle with eager work in between
+    graph = torch.cuda.CUDAGraph()
+    wipe()
+    with torch.cuda.graph(graph):
+        step(torch.cuda.current_stream())
+    for replay in range(3):
+        wipe()
+        graph.replay()
+        check(f"graph replay {replay}")
+        buf.target.mul_(1.0)          # eager work between replays
+        torch.cuda.synchronize()
