@@ -155,8 +155,11 @@ int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t
   ca.K = d->num_keep;
   ca.D = sh.D;
   ca.visible_bf16 = d->out_dtype == MAE_BF16;
-  ca.tile_pixels = mae::crop_tile_pixels(d->out_size, d->patch,
-                                         d->max_image_side > 0 ? d->max_image_side : 256);
+  const mae::CropPlan plan = mae::crop_plan(
+      d->out_size, d->patch, d->max_image_side > 0 ? d->max_image_side : 256, 0);
+  ca.tile_pixels = plan.tile_pixels;
+  ca.col_parts = plan.col_parts;
+  ca.part_patches = plan.part_patches;
   for (int c = 0; c < 3; ++c) {
     ca.nscale[c] = (float)(1.0 / (255.0 * (double)d->std[c]));
     ca.nbias[c] = (float)(-(double)d->mean[c] / (double)d->std[c]);

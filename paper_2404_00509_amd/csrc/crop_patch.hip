@@ -2,7 +2,8 @@
 // + ViT patch split (Sec. 3) + gather of the visible patches (Sec. 2), in one pass: every source
 // byte is read from HBM once and every output value is written once, straight into patch order.
 //
-// One workgroup per (image, row of patches).
+// One workgroup per (image, row of patches, column part): wide sources are split into column parts
+// (whole patches each) so that the staged tile stays small and many workgroups fit a compute unit.
 //  * Staging.  The source rows that this patch row taps are brought into LDS as 4-byte RGBx pixel
 //    words.  Lane i of a wavefront loads the 16 bytes that hold pixels 4i..4i+3 of a row (one
 //    4-byte-aligned global_load_dwordx4; the row's misalignment is taken out with byte-align
@@ -26,7 +27,8 @@ namespace mae {
 constexpr int kCropThreads = 256;      // scalar kernel
 constexpr int kCropMaxThreads = 1024;  // resampling kernel: 64 threads per 64 groups of a patch
 constexpr int kStageRows = 7;  // rows per wavefront whose loads are issued together
-constexpr int kCropMaxLds = 64 * 1024;  // dynamic LDS available without opting in to more
+constexpr int kCropMaxLds = 64 * 1024;      // dynamic LDS available without opting in to more
+constexpr int kCropTileTarget = 40 * 1024;  // LDS per workgroup that still leaves 4 per compute unit
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -94,14 +96,15 @@ __device__ static inline u32x4 to_pixels(u32x4 d, uint32_t s) {
 // The compute + store phase of one wavefront: its 64 groups of every patch.  kLds: taps come from
 // the staged tile (row offsets in pixel words), otherwise straight from global memory (row offsets
 // in bytes; crops too large to stage).  my_rank holds, in lane i, the noise rank of patch i of
-// this row of patches.
+// this part (patches gx0 .. gx0 + npatch - 1); cw is the number of source columns from the
+// part's first tapped column to the crop's right edge.
 template <bool kLds, bool kBf16>
 __device__ static void produce_patches(const CropArgs& a, const uint32_t* tile, const u32x2* xtab,
                                        const u32x4* ytab, const uint8_t* base, int b, int gy,
-                                       int cw, int my_rank) {
+                                       int gx0, int npatch, int cw, int my_rank) {
   const int lane = threadIdx.x % kWave;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-  const int p = a.p, D = a.D, G = a.G;
+  const int p = a.p, D = a.D;
   const int D4 = D >> 2;
   const int pp = p * p;
   const float inv_p = 1.0f / (float)p;
@@ -136,8 +139,8 @@ __device__ static void produce_patches(const CropArgs& a, const uint32_t* tile, 
     fy[j] = j == 0 ? fyA : (j == 3 ? fyB : (j < nA ? fyA : fyB));
   }
 
-  for (int gx = 0; gx < G; ++gx) {
-    const int l = gy * G + gx;
+  for (int gx = 0; gx < npatch; ++gx) {
+    const int l = gy * a.G + gx0 + gx;
     const int rank = __builtin_amdgcn_readlane(my_rank, gx);
     const u32x2 xa = xtab[gx * p + pxA], xb = xtab[gx * p + pxB];
     const float fxA = __uint_as_float(xa.y), fxB = __uint_as_float(xb.y);
@@ -184,7 +187,7 @@ __device__ static void produce_patches(const CropArgs& a, const uint32_t* tile, 
   }
 }
 
-// Dynamic LDS: [ tile: a.tile_pixels + 4 words | xtab: S x 8 bytes | ytab: p x 16 bytes ].
+// Dynamic LDS: [ tile: a.tile_pixels + 4 words | ytab: p x 16 bytes | xtab: a.part_patches p x 8 ].
 template <bool kBf16>
 __global__ __launch_bounds__(kCropMaxThreads) void crop_patch_kernel(CropArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
@@ -193,10 +196,15 @@ __global__ __launch_bounds__(kCropMaxThreads) void crop_patch_kernel(CropArgs a)
   u32x2* xtab = reinterpret_cast<u32x2*>(ytab + a.p);                // x0, weight of x0 + 1
 
   const uint32_t tile_id = xcd_remap(blockIdx.x, gridDim.x);
-  const int b = (int)(tile_id / (uint32_t)a.G);
-  const int gy = (int)(tile_id - (uint32_t)b * (uint32_t)a.G);
+  const uint32_t row_id = tile_id / (uint32_t)a.col_parts;
+  const int part = (int)(tile_id - row_id * (uint32_t)a.col_parts);
+  const int b = (int)(row_id / (uint32_t)a.G);
+  const int gy = (int)(row_id - (uint32_t)b * (uint32_t)a.G);
+  const int gx0 = part * a.G / a.col_parts;  // this part covers patches gx0 .. gx1 - 1
+  const int gx1 = (part + 1) * a.G / a.col_parts;
+  const int npatch = gx1 - gx0;
   const CropRec rec = reinterpret_cast<const CropRec*>(a.workspace + kWorkspaceHeader)[b];
-  if (!rec.valid) return;
+  if (!rec.valid || npatch <= 0) return;
 
   const int S = a.S, p = a.p;
   const int W = a.widths[b];
@@ -204,25 +212,30 @@ __global__ __launch_bounds__(kCropMaxThreads) void crop_patch_kernel(CropArgs a)
   const int lane = tid % kWave, wave = tid / kWave;
   const int nwaves = (int)blockDim.x / kWave;
 
-  // rows of the crop that this row of patches taps
-  int ylo, yhi, t0, t1;
+  // rows and columns of the crop that this part taps (taps are monotonic in the output index)
+  int ylo, yhi, xlo, xhi, t0, t1;
   float tf;
   resize_taps(gy * p, rec.ch, S, ylo, t1, tf);
   resize_taps(gy * p + p - 1, rec.ch, S, t0, yhi, tf);
+  const int ox_first = gx0 * p, ox_last = gx1 * p - 1;
+  resize_taps(rec.flip ? S - 1 - ox_last : ox_first, rec.cw, S, xlo, t1, tf);
+  resize_taps(rec.flip ? S - 1 - ox_first : ox_last, rec.cw, S, t0, xhi, tf);
   const int nrows = yhi - ylo + 1;
-  const int ng = (rec.cw + 3) >> 2;  // groups of four pixels per staged row
-  const int pitch = 4 * ng;          // pixel words per staged row
+  const int ng = (xhi - xlo + 4) >> 2;  // groups of four pixels per staged row
+  const int pitch = 4 * ng;             // pixel words per staged row
   const bool use_lds = nrows * pitch <= a.tile_pixels;
   const bool batched = use_lds && ng <= kWave;
 
-  // first pixel of the first tapped row
-  const uint8_t* base = a.images + a.offsets[b] + ((int64_t)(rec.top + ylo) * W + rec.left) * 3;
+  // first tapped pixel of the first tapped row
+  const uint8_t* base =
+      a.images + a.offsets[b] + ((int64_t)(rec.top + ylo) * W + rec.left + xlo) * 3;
   const int row_bytes = 3 * W;
   const uint8_t* img_end = a.images + a.images_bytes;
   u32x4* tile4 = reinterpret_cast<u32x4*>(tile);
 
-  // noise rank of each patch of this row, one per lane; read back with readlane in the loop
-  const int my_rank = lane < a.G ? a.ids_restore[(int64_t)b * a.L + gy * a.G + lane] : 0x7fffffff;
+  // noise rank of each patch of this part, one per lane; read back with readlane in the loop
+  const int my_rank =
+      lane < npatch ? a.ids_restore[(int64_t)b * a.L + gy * a.G + gx0 + lane] : 0x7fffffff;
 
   u32x4 d[kStageRows];
   if (batched) {  // these loads stay in flight while the tap tables are built
@@ -239,12 +252,13 @@ __global__ __launch_bounds__(kCropMaxThreads) void crop_patch_kernel(CropArgs a)
     }
   }
 
-  for (int ox = tid; ox < S; ox += (int)blockDim.x) {
+  for (int i = tid; i < npatch * p; i += (int)blockDim.x) {
+    const int ox = ox_first + i;
     int x0, x1;
     float f;
     resize_taps(rec.flip ? S - 1 - ox : ox, rec.cw, S, x0, x1, f);
     // at the right edge both taps are the last pixel: weight 0 makes the second tap irrelevant
-    xtab[ox] = u32x2{(uint32_t)x0, __float_as_uint(x1 == x0 ? 0.0f : f)};
+    xtab[i] = u32x2{(uint32_t)(x0 - xlo), __float_as_uint(x1 == x0 ? 0.0f : f)};
   }
   for (int py = tid; py < p; py += (int)blockDim.x) {
     int y0, y1;
@@ -252,7 +266,7 @@ __global__ __launch_bounds__(kCropMaxThreads) void crop_patch_kernel(CropArgs a)
     resize_taps(gy * p + py, rec.ch, S, y0, y1, f);
     const uint32_t stride = use_lds ? (uint32_t)pitch : (uint32_t)row_bytes;
     ytab[py] = u32x4{(uint32_t)(y0 - ylo) * stride, (uint32_t)(y1 - ylo) * stride,
-                      __float_as_uint(f), 0u};
+                     __float_as_uint(f), 0u};
   }
 
   if (batched) {
@@ -265,7 +279,7 @@ __global__ __launch_bounds__(kCropMaxThreads) void crop_patch_kernel(CropArgs a)
       }
     }
   }
-  if (use_lds) {  // rows beyond the first batch, and crops wider than 256 pixels
+  if (use_lds) {  // rows beyond the first batch, and parts wider than 256 source pixels
     for (int r = batched ? wave + kStageRows * nwaves : wave; r < nrows; r += nwaves) {
       const uint8_t* row = base + (int64_t)r * row_bytes;
       const uint32_t s = (uint32_t)reinterpret_cast<uintptr_t>(row) & 3u;
@@ -278,9 +292,11 @@ __global__ __launch_bounds__(kCropMaxThreads) void crop_patch_kernel(CropArgs a)
   __syncthreads();
 
   if (use_lds) {
-    produce_patches<true, kBf16>(a, tile, xtab, ytab, base, b, gy, rec.cw, my_rank);
+    produce_patches<true, kBf16>(a, tile, xtab, ytab, base, b, gy, gx0, npatch, rec.cw - xlo,
+                                 my_rank);
   } else {
-    produce_patches<false, kBf16>(a, tile, xtab, ytab, base, b, gy, rec.cw, my_rank);
+    produce_patches<false, kBf16>(a, tile, xtab, ytab, base, b, gy, gx0, npatch, rec.cw - xlo,
+                                  my_rank);
   }
 }
 
@@ -327,25 +343,46 @@ __global__ __launch_bounds__(kCropThreads) void crop_patch_scalar_kernel(CropArg
   }
 }
 
-// Staging tile for one row of patches when no image side exceeds max_side: the rows tapped are
-// at most ceil((p - 1) max_side / S) + 2, each up to max_side pixels (rounded up to 4).
-int crop_tile_pixels(int S, int p, int max_side) {
+// Launch plan of the resampling kernel when no image side exceeds max_side.  A row of patches
+// taps at most ceil((p - 1) max_side / S) + 2 source rows; a column part of n patches taps at most
+// min(max_side, ceil((n p - 1) max_side / S) + 2) source columns, rounded up to groups of four.  The row is split
+// into the fewest parts (whole patches, a power of two) whose tile stays within kCropTileTarget
+// bytes, so that several workgroups share a compute unit's LDS.
+CropPlan crop_plan(int S, int p, int max_side, int force_parts) {
+  const int G = S / p;
   const int64_t rows = ((int64_t)(p - 1) * max_side + S - 1) / S + 2;
-  int64_t px = rows * ((max_side + 3) & ~3);
-  const int64_t cap = (kCropMaxLds - 16 - 8 * (int64_t)S - 16 * (int64_t)p) / 4;
-  if (px > cap) px = cap;
-  if (px < 1024) px = 1024;
-  return (int)(px & ~3);
+  CropPlan plan;
+  int parts = 1;
+  for (;;) {
+    const int n = (G + parts - 1) / parts;  // patches per part
+    int64_t cols = ((int64_t)(n * p - 1) * max_side + S - 1) / S + 2;
+    if (cols > max_side) cols = max_side;
+    cols = (cols + 3) & ~(int64_t)3;
+    const int64_t px = rows * cols;
+    const int64_t fixed = 16 + 16 * (int64_t)p + 8 * (int64_t)n * p;
+    const bool forced = force_parts > 0;
+    const bool fits = px * 4 + fixed <= kCropTileTarget;
+    if ((forced && parts >= force_parts) || (!forced && fits) || parts * 2 > G) {
+      int64_t cap = (kCropMaxLds - fixed) / 4;
+      plan.col_parts = parts;
+      plan.part_patches = n;
+      plan.tile_pixels = (int)((px < cap ? px : cap) & ~(int64_t)3);
+      if (plan.tile_pixels < 256) plan.tile_pixels = 256;
+      return plan;
+    }
+    parts *= 2;
+  }
 }
 
-size_t crop_lds_bytes(int tile_pixels, int S, int p) {
-  return (size_t)(tile_pixels + 4) * 4 + (size_t)S * 8 + (size_t)p * 16;
+size_t crop_lds_bytes(const CropArgs& a) {
+  return (size_t)(a.tile_pixels + 4) * 4 + (size_t)a.p * 16 + (size_t)a.part_patches * a.p * 8;
 }
 
 hipError_t launch_crop_patch(const CropArgs& a, hipStream_t stream) {
   if ((a.D & 3) == 0) {
-    dim3 grid((uint32_t)a.B * (uint32_t)a.G), block(kWave * (((a.D >> 2) + kWave - 1) / kWave));
-    const size_t lds = crop_lds_bytes(a.tile_pixels, a.S, a.p);
+    dim3 grid((uint32_t)a.B * (uint32_t)a.G * (uint32_t)a.col_parts);
+    dim3 block(kWave * (((a.D >> 2) + kWave - 1) / kWave));
+    const size_t lds = crop_lds_bytes(a);
     if (a.visible_bf16) {
       hipLaunchKernelGGL(crop_patch_kernel<true>, grid, block, lds, stream, a);
     } else {

@@ -33,6 +33,8 @@ struct CropArgs {
   int32_t B, S, p, G, L, K, D;
   int32_t visible_bf16;  // 0: float, 1: bfloat16
   int32_t tile_pixels;   // staging tile of the resampling kernel, in 4-byte pixel words
+  int32_t col_parts;     // column parts a row of patches is split into
+  int32_t part_patches;  // patches per part (upper bound)
   float nscale[3];       // 1 / (255 std_c)
   float nbias[3];        // -mean_c / std_c
   const uint8_t* images;
@@ -44,8 +46,11 @@ struct CropArgs {
   void* visible;
   float* target;  // nullable
 };
-int crop_tile_pixels(int S, int p, int max_side);
-size_t crop_lds_bytes(int tile_pixels, int S, int p);
+struct CropPlan {
+  int col_parts, part_patches, tile_pixels;
+};
+CropPlan crop_plan(int S, int p, int max_side, int force_parts);
+size_t crop_lds_bytes(const CropArgs& a);
 hipError_t launch_crop_patch(const CropArgs& a, hipStream_t stream);
 
 // ---- normalised-pixel loss ---------------------------------------------------------------------

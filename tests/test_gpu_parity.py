@@ -171,9 +171,11 @@ def test_prep_shapes_and_tiny_or_large_images(S, p, K):
     check_prep_against_oracle(prep_to_numpy(buf), ref, what=f"S{S}p{p}")
     buf16, _, _ = gpu_prep(*data, bf16=True, **kw)
     check_prep_against_oracle(prep_to_numpy(buf16), ref, bf16=True, what=f"S{S}p{p}bf16")
-    # with the staging buffer sized for the largest image, wide crops are staged too
-    big, _, _ = gpu_prep(*data, max_image_side=1100, **kw)
-    check_prep_against_oracle(prep_to_numpy(big), ref, what=f"S{S}p{p}hint")
+    # with the staging buffer sized for larger images, rows of patches are split into column
+    # parts and wide crops are staged too
+    for hint in (500, 1100):
+        big, _, _ = gpu_prep(*data, max_image_side=hint, **kw)
+        check_prep_against_oracle(prep_to_numpy(big), ref, what=f"S{S}p{p}hint{hint}")
 
 
 def test_prep_single_image_and_keep_all():
