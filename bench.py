@@ -122,7 +122,8 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this path has no multi-GPU part (samples are "
-              "independent; see DESIGN.md for how it would shard). Run with --gpus 1.",
+              "independent, so a batch shards by sample and only the loss scalar would be "
+              "exchanged). Run with --gpus 1.",
               file=sys.stderr)
         return 2
 

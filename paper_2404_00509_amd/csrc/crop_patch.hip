@@ -37,15 +37,27 @@ typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
 
 // Source taps of output index o when `len` source pixels are resized to S: sample position
 // (o + 1/2) len / S - 1/2 kept as the exact fraction n / (2 S); taps clamped to [0, len).
-__device__ static inline void resize_taps(int o, int len, int S, int& i0, int& i1, float& f) {
+// The integer quotient comes from a float estimate (off by at most one for n < 2^26, quotient
+// < 2^15) that is corrected with the exact remainder; inv_den = 1 / (2 S).
+__device__ static inline void resize_taps(int o, int len, int S, float inv_den, int& i0, int& i1,
+                                          float& f) {
   const int n = (2 * o + 1) * len - S;
   const int den = 2 * S;
   if (n <= 0) {
     i0 = 0;
     f = 0.0f;
   } else {
-    i0 = n / den;
-    f = (float)(n - i0 * den) / (float)den;
+    int q = (int)((float)n * inv_den);
+    int r = n - q * den;
+    if (r < 0) {
+      --q;
+      r += den;
+    } else if (r >= den) {
+      ++q;
+      r -= den;
+    }
+    i0 = q;
+    f = (float)r * inv_den;
   }
   i1 = min(i0 + 1, len - 1);
 }
@@ -213,13 +225,14 @@ __global__ __launch_bounds__(kCropMaxThreads) void crop_patch_kernel(CropArgs a)
   const int nwaves = (int)blockDim.x / kWave;
 
   // rows and columns of the crop that this part taps (taps are monotonic in the output index)
+  const float inv_den = 1.0f / (float)(2 * S);
   int ylo, yhi, xlo, xhi, t0, t1;
   float tf;
-  resize_taps(gy * p, rec.ch, S, ylo, t1, tf);
-  resize_taps(gy * p + p - 1, rec.ch, S, t0, yhi, tf);
+  resize_taps(gy * p, rec.ch, S, inv_den, ylo, t1, tf);
+  resize_taps(gy * p + p - 1, rec.ch, S, inv_den, t0, yhi, tf);
   const int ox_first = gx0 * p, ox_last = gx1 * p - 1;
-  resize_taps(rec.flip ? S - 1 - ox_last : ox_first, rec.cw, S, xlo, t1, tf);
-  resize_taps(rec.flip ? S - 1 - ox_first : ox_last, rec.cw, S, t0, xhi, tf);
+  resize_taps(rec.flip ? S - 1 - ox_last : ox_first, rec.cw, S, inv_den, xlo, t1, tf);
+  resize_taps(rec.flip ? S - 1 - ox_first : ox_last, rec.cw, S, inv_den, t0, xhi, tf);
   const int nrows = yhi - ylo + 1;
   const int ng = (xhi - xlo + 4) >> 2;  // groups of four pixels per staged row
   const int pitch = 4 * ng;             // pixel words per staged row
@@ -256,14 +269,14 @@ __global__ __launch_bounds__(kCropMaxThreads) void crop_patch_kernel(CropArgs a)
     const int ox = ox_first + i;
     int x0, x1;
     float f;
-    resize_taps(rec.flip ? S - 1 - ox : ox, rec.cw, S, x0, x1, f);
+    resize_taps(rec.flip ? S - 1 - ox : ox, rec.cw, S, inv_den, x0, x1, f);
     // at the right edge both taps are the last pixel: weight 0 makes the second tap irrelevant
     xtab[i] = u32x2{(uint32_t)(x0 - xlo), __float_as_uint(x1 == x0 ? 0.0f : f)};
   }
   for (int py = tid; py < p; py += (int)blockDim.x) {
     int y0, y1;
     float f;
-    resize_taps(gy * p + py, rec.ch, S, y0, y1, f);
+    resize_taps(gy * p + py, rec.ch, S, inv_den, y0, y1, f);
     const uint32_t stride = use_lds ? (uint32_t)pitch : (uint32_t)row_bytes;
     ytab[py] = u32x4{(uint32_t)(y0 - ylo) * stride, (uint32_t)(y1 - ylo) * stride,
                      __float_as_uint(f), 0u};
@@ -319,8 +332,9 @@ __global__ __launch_bounds__(kCropThreads) void crop_patch_scalar_kernel(CropArg
     const int oy = gy * a.p + py, ox = gx * a.p + px;
     int x0, x1, y0, y1;
     float fx, fy;
-    resize_taps(rec.flip ? a.S - 1 - ox : ox, rec.cw, a.S, x0, x1, fx);
-    resize_taps(oy, rec.ch, a.S, y0, y1, fy);
+    const float inv_den = 1.0f / (float)(2 * a.S);
+    resize_taps(rec.flip ? a.S - 1 - ox : ox, rec.cw, a.S, inv_den, x0, x1, fx);
+    resize_taps(oy, rec.ch, a.S, inv_den, y0, y1, fy);
     const int W = a.widths[b];
     const uint8_t* img = a.images + a.offsets[b];
     const float a00 = img[((int64_t)(rec.top + y0) * W + rec.left + x0) * 3 + c];
