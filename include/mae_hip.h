@@ -67,7 +67,8 @@ typedef enum { MAE_F32 = 0, MAE_BF16 = 1 } mae_dtype;
  * counter) -- the SplitMix64 output function applied to a keyed counter -- so a batch can be
  * recomputed, and a shard of a batch gives the same values as the whole batch.
  *
- * Limits: 1 <= L <= 256; 1 <= p <= 32; S <= 512; exp(-1/2) <= ratio_lo <= ratio_hi <= exp(1/2).
+ * Limits: B <= 2^20; 1 <= L <= 256; 1 <= p <= 32; S <= 512;
+ * exp(-1/2) <= ratio_lo <= ratio_hi <= exp(1/2).
  * ---------------------------------------------------------------------------------------------- */
 typedef struct {
   int32_t B;               /* images in this call, > 0                                          */

@@ -25,6 +25,7 @@ int validate_prep(const mae_prep_desc* d, PrepShape* shape) {
   if (!d) return MAE_ERR_NULL;
   if (!d->images || !d->offsets || !d->heights || !d->widths) return MAE_ERR_NULL;
   if (d->B <= 0 || d->out_size <= 0 || d->patch <= 0) return MAE_ERR_SHAPE;
+  if (d->B > (1 << 20)) return MAE_ERR_RANGE;  // keeps every grid size below 2^31
   if (d->out_size % d->patch != 0) return MAE_ERR_SHAPE;
   if (d->patch > 32 || d->out_size > 512) return MAE_ERR_RANGE;
   const int64_t G = d->out_size / d->patch;

@@ -78,6 +78,7 @@ def _call_prep(lib, d, visible=FAKE, mask=FAKE, ids_restore=FAKE, workspace=FAKE
     (dict(widths=None), binding.MAE_ERR_NULL),
     (dict(B=0), binding.MAE_ERR_SHAPE),
     (dict(B=-3), binding.MAE_ERR_SHAPE),
+    (dict(B=(1 << 20) + 1), binding.MAE_ERR_RANGE),
     (dict(out_size=230), binding.MAE_ERR_SHAPE),        # not a multiple of the patch
     (dict(out_size=0), binding.MAE_ERR_SHAPE),
     (dict(patch=0), binding.MAE_ERR_SHAPE),
