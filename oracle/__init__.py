@@ -110,6 +110,8 @@ def load_library(path: str):
                                             C.c_void_p]
     L.mae_oracle_stage_of_epoch.restype = C.c_int32
     L.mae_oracle_stage_of_epoch.argtypes = [C.c_int32, C.c_void_p, C.c_int32]
+    L.mae_oracle_patch_embed.restype = C.c_int32
+    L.mae_oracle_patch_embed.argtypes = [C.c_int32] * 5 + [C.c_void_p] * 6
     L.mae_oracle_threads.restype = C.c_int32
     L.mae_oracle_threads.argtypes = []
     return L
@@ -302,6 +304,25 @@ def finetune_stage(scheme: int, stage: int):
 def stage_of_epoch(epoch: int, lengths) -> int:
     arr = np.ascontiguousarray(lengths, np.int32)
     return int(lib().mae_oracle_stage_of_epoch(epoch, _p(arr), len(arr)))
+
+
+def patch_embed(visible, ids_keep, weight, bias=None, pos=None):
+    """tokens [B,K,E] float64 = visible @ weight.T + bias + pos[ids_keep]."""
+    visible = np.ascontiguousarray(visible, np.float32)
+    weight = np.ascontiguousarray(weight, np.float32)
+    B, K, D = visible.shape
+    E = weight.shape[0]
+    assert weight.shape == (E, D)
+    ids = None if ids_keep is None else np.ascontiguousarray(ids_keep, np.int32)
+    b = None if bias is None else np.ascontiguousarray(bias, np.float32)
+    p = None if pos is None else np.ascontiguousarray(pos, np.float32)
+    L = 1 if p is None else p.shape[0]
+    out = np.empty((B, K, E), np.float64)
+    rc = lib().mae_oracle_patch_embed(B, K, D, E, L, _p(visible), _p(ids), _p(weight), _p(b),
+                                      _p(p), _p(out))
+    if rc != 0:
+        raise ValueError("mae_oracle_patch_embed: invalid argument")
+    return out
 
 
 def threads() -> int:

@@ -424,6 +424,35 @@ int32_t mae_oracle_stage_of_epoch(int32_t epoch, const int32_t* lengths, int32_t
   return n;
 }
 
+/* ------------------------------------------------------------------------------------------------
+ * Patch embedding of the visible tokens: the ViT's linear map of each flattened patch plus the
+ * positional embedding of the patch's place in the grid (Sec. 2, Sec. 5).
+ * ---------------------------------------------------------------------------------------------- */
+int32_t mae_oracle_patch_embed(int32_t B, int32_t K, int32_t D, int32_t E, int32_t L,
+                               const float* visible, const int32_t* ids_keep, const float* weight,
+                               const float* bias, const float* pos, double* tokens) {
+  if (B < 1 || K < 1 || D < 1 || E < 1 || L < 1 || !visible || !weight || !tokens) return -1;
+  if (pos && !ids_keep) return -1;
+  int bad = 0;
+#pragma omp parallel for schedule(static)
+  for (int64_t row = 0; row < (int64_t)B * K; ++row) {
+    const float* v = visible + row * D;
+    int32_t l = ids_keep ? ids_keep[row] : 0;
+    if (pos && (l < 0 || l >= L)) {
+      bad = 1;
+      continue;
+    }
+    for (int32_t e = 0; e < E; ++e) {
+      double acc = 0.0;
+      for (int32_t d = 0; d < D; ++d) acc += (double)v[d] * (double)weight[(int64_t)e * D + d];
+      if (bias) acc += (double)bias[e];
+      if (pos) acc += (double)pos[(int64_t)l * E + e];
+      tokens[row * E + e] = acc;
+    }
+  }
+  return bad ? -1 : 0;
+}
+
 int32_t mae_oracle_threads(void) {
 #ifdef _OPENMP
   return (int32_t)omp_get_max_threads();

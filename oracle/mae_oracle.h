@@ -128,6 +128,16 @@ int32_t mae_oracle_finetune_stage(int32_t scheme, int32_t stage, int32_t* res, d
  * epochs past the end belong to the last stage.  Returns -1 on bad arguments. */
 int32_t mae_oracle_stage_of_epoch(int32_t epoch, const int32_t* lengths, int32_t n);
 
+/* ---- patch embedding of the visible tokens (Sec. 2: the encoder sees only the visible patches;
+ * Sec. 5: "linear patch embeddings" of the ViT) -------------------------------------------------
+ * tokens[b, r, e] = sum_d visible[b, r, d] * weight[e, d] + bias[e] + pos[ids_keep[b, r], e].
+ * visible [B,K,D], weight [E,D] (columns in the patch's element order: row, column, channel),
+ * bias [E] (nullable), pos [L,E] (nullable; row l = positional embedding of patch l),
+ * tokens [B,K,E] doubles.  Returns 0 or -1. */
+int32_t mae_oracle_patch_embed(int32_t B, int32_t K, int32_t D, int32_t E, int32_t L,
+                               const float* visible, const int32_t* ids_keep, const float* weight,
+                               const float* bias, const float* pos, double* tokens);
+
 int32_t mae_oracle_threads(void);
 
 #ifdef __cplusplus

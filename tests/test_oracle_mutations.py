@@ -90,6 +90,14 @@ MUTATIONS = [
     ("scheme 4 ratios", "{0.75, 0.80, 0.85}, {0.75, 0.75, 0.75}, {0.75, 0.75, 0.85},",
      "{0.75, 0.80, 0.80}, {0.75, 0.75, 0.75}, {0.75, 0.75, 0.85},",
      ["test_progressive_schemes_match_the_printed_tables"]),
+    ("embedding weight transposed", "acc += (double)v[d] * (double)weight[(int64_t)e * D + d];",
+     "acc += (double)v[d] * (double)weight[((int64_t)d * E + e) % ((int64_t)E * D)];",
+     ["test_patch_embed_closed_forms_and_library_matmul"]),
+    ("positional embedding by rank", "if (pos) acc += (double)pos[(int64_t)l * E + e];",
+     "if (pos) acc += (double)pos[(row % K) * (int64_t)E + e];",
+     ["test_patch_embed_closed_forms_and_library_matmul"]),
+    ("bias dropped", "if (bias) acc += (double)bias[e];", "if (bias) acc += 0.0;",
+     ["test_patch_embed_closed_forms_and_library_matmul"]),
     ("stage boundary", "if (epoch < end) return s + 1;", "if (epoch <= end) return s + 1;",
      ["test_progressive_schemes_match_the_printed_tables"]),
     ("loss over all rows", "if (mask[row]) total += row_losses[row];",

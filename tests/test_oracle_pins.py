@@ -592,3 +592,36 @@ def test_pixel_loss_against_library_and_closed_form():
     a = oracle.pixel_loss(pred, tn, mask)[0]
     b = oracle.normpix_loss(pred, tn, mask, eps=0.0)[0]
     assert a == pytest.approx(b, rel=1e-5)
+
+
+# ------------------------------------------------------------------------------------ patch embed
+def test_patch_embed_closed_forms_and_library_matmul():
+    rng = np.random.default_rng(21)
+    B, K, D, E, L = 3, 5, 12, 7, 9
+    vis = rng.standard_normal((B, K, D)).astype(np.float32)
+    ids = np.stack([rng.permutation(L)[:K] for _ in range(B)]).astype(np.int32)
+    w = rng.standard_normal((E, D)).astype(np.float32)
+    bias = rng.standard_normal(E).astype(np.float32)
+    pos = rng.standard_normal((L, E)).astype(np.float32)
+    out = oracle.patch_embed(vis, ids, w, bias, pos)
+    ref = vis.astype(np.float64) @ w.astype(np.float64).T + bias + pos.astype(np.float64)[ids]
+    np.testing.assert_allclose(out, ref, rtol=1e-13, atol=1e-13)
+    # zero weight: what is left is the bias and the embedding of the PATCH index (not the rank)
+    z = oracle.patch_embed(vis, ids, np.zeros_like(w), bias, pos)
+    for b in range(B):
+        for r in range(K):
+            np.testing.assert_array_equal(z[b, r], bias.astype(np.float64) + pos[ids[b, r]])
+    # a weight with a single one copies element d of the patch to output e (orientation of W)
+    one = np.zeros((E, D), np.float32)
+    one[2, 5] = 1.0
+    o = oracle.patch_embed(vis, None, one)
+    assert np.array_equal(o[..., 2], vis[..., 5].astype(np.float64))
+    assert not o[..., [0, 1, 3, 4, 5, 6]].any()
+    # identity weight returns the tokens themselves
+    eye = oracle.patch_embed(vis, None, np.eye(D, dtype=np.float32))
+    np.testing.assert_array_equal(eye, vis.astype(np.float64))
+    # linear in the tokens
+    two = oracle.patch_embed(2 * vis, ids, w, None, None)
+    np.testing.assert_allclose(two, 2 * oracle.patch_embed(vis, ids, w, None, None), rtol=1e-14)
+    with pytest.raises(ValueError):
+        oracle.patch_embed(vis, np.full_like(ids, L), w, bias, pos)      # index out of range
