@@ -2,7 +2,7 @@
  * mae_hip.h -- C ABI of the MI355X (gfx950) library for the per-batch masked-autoencoder input
  * pipeline and its reconstruction loss (DailyMAE, arXiv 2404.00509).
  *
- * Two calls make up the path:
+ * Two calls make up the path, a third is the first consumer of its output:
  *
  *   mae_prep_batch     decoded uint8 images in device memory -> training tensors.
  *                      RandomResizedCrop (Sec. 5.1: area scale uniform, aspect ratio log-uniform,
@@ -15,6 +15,8 @@
  *   mae_normpix_loss   the reconstruction objective of the official MAE recipe that the paper
  *                      adopts (Sec. 3): mean squared error against per-patch normalised pixels on
  *                      the masked patches, and its gradient with respect to the prediction.
+ *   mae_patch_embed    linear patch embedding of the visible tokens with bias and positional
+ *                      embedding (Sec. 2, Sec. 5), on the matrix cores.
  *
  * Conventions
  *   - Every pointer is a DEVICE pointer unless its name starts with host_.  The descriptor
@@ -159,6 +161,37 @@ int mae_normpix_loss(const mae_loss_desc* d, float* loss, void* grad, void* work
                      size_t workspace_bytes, void* hip_stream);
 
 size_t mae_loss_workspace_bytes(const mae_loss_desc* d);
+
+/* ------------------------------------------------------------------------------------------------
+ * mae_patch_embed
+ *
+ * The first operation of the encoder on what mae_prep_batch hands it (Sec. 2: the encoder works on
+ * the visible patches only; Sec. 5: the ViT's linear patch embedding with positional embeddings):
+ *   tokens[m, e] = sum_d visible[m, d] * weight[e, d] + bias[e] + pos[ids_keep[m], e]
+ * for the M = B * K visible rows of a batch.  The products of the bf16 operands are exact in
+ * single precision and are accumulated in single precision on the matrix cores; bias and the
+ * positional row are added in single precision and the sum is rounded once to out_dtype.
+ *
+ * `weight` is the [E, 3, p, p] convolution kernel of the usual patch embedding with its last three
+ * axes reordered to (row, column, channel), the element order of a patch row.
+ *
+ * Limits: 1 <= M <= 2^28; 4 <= D <= 3072 with D % 4 == 0; 1 <= E <= 8192; 1 <= L.
+ * visible, weight, pos and tokens are 16-byte aligned (MAE_ERR_RANGE otherwise).
+ * An ids_keep value outside [0, L) is clamped into it before it indexes `pos`.
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct {
+  int64_t M;               /* token rows, B * K                                                 */
+  int32_t D, E, L;         /* values per patch, embedding width, patches per image              */
+  const void* visible;     /* [M, D] bf16, as written by mae_prep_batch with out_dtype MAE_BF16 */
+  const int32_t* ids_keep; /* [M] patch index of each row; required iff pos is given            */
+  const void* weight;      /* [E, D] bf16                                                       */
+  const float* bias;       /* [E] float, nullable                                               */
+  const float* pos;        /* [L, E] float, row l = positional embedding of patch l; nullable   */
+  int32_t out_dtype;       /* mae_dtype of tokens                                               */
+} mae_embed_desc;
+
+/* Output (device): tokens [M, E] out_dtype, every element written.  No workspace. */
+int mae_patch_embed(const mae_embed_desc* d, void* tokens, void* hip_stream);
 
 /* ------------------------------------------------------------------------------------------------
  * Progressive schedules (host-side tables; nothing is launched).

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     LIB_PATH,
     MAE_BF16,
     MAE_F32,
+    MaeEmbedDesc,
     MaeError,
     MaeLossDesc,
     MaePrepDesc,
@@ -25,10 +26,12 @@ from .binding import (  # noqa: F401
     mae_loss_workspace_bytes,
     mae_normpix_loss,
     mae_num_keep,
+    mae_patch_embed,
     mae_prep_batch,
     mae_prep_status,
     mae_prep_workspace_bytes,
     mae_version,
+    make_embed_desc,
     make_loss_desc,
     make_prep_desc,
 )

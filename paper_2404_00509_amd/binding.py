@@ -25,7 +25,7 @@ IMAGENET_STD = (0.229, 0.224, 0.225)
 
 # Entry points declared in include/mae_hip.h.
 EXPORTS = ("mae_prep_batch", "mae_prep_workspace_bytes", "mae_prep_status", "mae_num_keep",
-           "mae_normpix_loss", "mae_loss_workspace_bytes", "mae_pretrain_stage",
+           "mae_normpix_loss", "mae_loss_workspace_bytes", "mae_patch_embed", "mae_pretrain_stage",
            "mae_finetune_stage", "mae_stage_of_epoch", "mae_error_string", "mae_version")
 
 
@@ -72,6 +72,21 @@ class MaeLossDesc(C.Structure):
     ]
 
 
+class MaeEmbedDesc(C.Structure):
+    _fields_ = [
+        ("M", C.c_int64),
+        ("D", C.c_int32),
+        ("E", C.c_int32),
+        ("L", C.c_int32),
+        ("visible", C.c_void_p),
+        ("ids_keep", C.c_void_p),
+        ("weight", C.c_void_p),
+        ("bias", C.c_void_p),
+        ("pos", C.c_void_p),
+        ("out_dtype", C.c_int32),
+    ]
+
+
 class MaeError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -103,6 +118,8 @@ def load():
                                          C.c_void_p, C.c_size_t, C.c_void_p]
         lib.mae_loss_workspace_bytes.restype = C.c_size_t
         lib.mae_loss_workspace_bytes.argtypes = [C.POINTER(MaeLossDesc)]
+        lib.mae_patch_embed.restype = C.c_int
+        lib.mae_patch_embed.argtypes = [C.POINTER(MaeEmbedDesc), C.c_void_p, C.c_void_p]
         lib.mae_pretrain_stage.restype = C.c_int
         lib.mae_pretrain_stage.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_int32),
                                            C.POINTER(C.c_double)]
@@ -234,6 +251,26 @@ def mae_normpix_loss(desc: MaeLossDesc, loss, grad=None, workspace=None, stream=
                                  _stream(stream))
     if rc != MAE_OK:
         raise MaeError(rc, "mae_normpix_loss")
+
+
+def make_embed_desc(visible, ids_keep, weight, bias=None, pos=None, *,
+                    out_dtype=MAE_BF16) -> MaeEmbedDesc:
+    """visible [B, K, D] (or [M, D]) bf16, ids_keep [B, K] int32, weight [E, D] bf16,
+    bias [E] float32, pos [L, E] float32."""
+    d = MaeEmbedDesc()
+    d.D, d.E = int(visible.shape[-1]), int(weight.shape[0])
+    d.M = visible.numel() // d.D
+    d.L = int(pos.shape[0]) if pos is not None else 1
+    d.visible, d.weight = visible.data_ptr(), weight.data_ptr()
+    d.ids_keep, d.bias, d.pos = _ptr(ids_keep), _ptr(bias), _ptr(pos)
+    d.out_dtype = out_dtype
+    return d
+
+
+def mae_patch_embed(desc: MaeEmbedDesc, tokens, stream=None) -> None:
+    rc = load().mae_patch_embed(C.byref(desc), _ptr(tokens), _stream(stream))
+    if rc != MAE_OK:
+        raise MaeError(rc, "mae_patch_embed")
 
 
 # ------------------------------------------------------------------------------------------------

@@ -66,6 +66,19 @@ int validate_loss(const mae_loss_desc* d) {
   return MAE_OK;
 }
 
+int validate_embed(const mae_embed_desc* d) {
+  if (!d) return MAE_ERR_NULL;
+  if (!d->visible || !d->weight) return MAE_ERR_NULL;
+  if (d->pos && !d->ids_keep) return MAE_ERR_NULL;
+  if (d->M <= 0 || d->D <= 0 || d->E <= 0 || d->L <= 0) return MAE_ERR_SHAPE;
+  if (d->D % 4 != 0) return MAE_ERR_SHAPE;
+  if (d->M > (int64_t(1) << 28) || d->D > 3072 || d->E > 8192) return MAE_ERR_RANGE;
+  if (d->out_dtype != MAE_F32 && d->out_dtype != MAE_BF16) return MAE_ERR_DTYPE;
+  if (!aligned(d->visible, 16) || !aligned(d->weight, 16) || (d->pos && !aligned(d->pos, 16)))
+    return MAE_ERR_RANGE;
+  return MAE_OK;
+}
+
 int have_device() {
   int n = 0;
   if (hipGetDeviceCount(&n) != hipSuccess || n <= 0) {
@@ -241,6 +254,32 @@ int mae_normpix_loss(const mae_loss_desc* d, float* loss, void* grad, void* work
   la.num_partials = sh.waves;
   la.rows_per_iter = sh.rows_per_iter;
   if (mae::launch_normpix_loss(la, stream) != hipSuccess) return MAE_ERR_HIP;
+  return MAE_OK;
+}
+
+int mae_patch_embed(const mae_embed_desc* d, void* tokens, void* hip_stream) {
+  int rc = validate_embed(d);
+  if (rc != MAE_OK) return rc;
+  if (!tokens) return MAE_ERR_NULL;
+  if (!aligned(tokens, 16)) return MAE_ERR_RANGE;
+  rc = have_device();
+  if (rc != MAE_OK) return rc;
+
+  mae::EmbedArgs ea;
+  memset(&ea, 0, sizeof(ea));
+  ea.M = d->M;
+  ea.D = d->D;
+  ea.E = d->E;
+  ea.L = d->L;
+  ea.out_bf16 = d->out_dtype == MAE_BF16;
+  ea.visible = d->visible;
+  ea.ids_keep = d->ids_keep;
+  ea.weight = d->weight;
+  ea.bias = d->bias;
+  ea.pos = d->pos;
+  ea.tokens = tokens;
+  if (mae::launch_patch_embed(ea, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return MAE_ERR_HIP;
   return MAE_OK;
 }
 

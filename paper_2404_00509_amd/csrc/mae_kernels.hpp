@@ -78,4 +78,18 @@ struct LossShape {
 LossShape loss_shape(int64_t rows, int D, bool pred_bf16);
 hipError_t launch_normpix_loss(const LossArgs& a, hipStream_t stream);
 
+// ---- patch embedding of the visible tokens -----------------------------------------------------
+struct EmbedArgs {
+  int64_t M;  // B * K token rows
+  int32_t D, E, L;
+  int32_t out_bf16;
+  const void* visible;      // [M, D] bf16
+  const int32_t* ids_keep;  // [M], nullable when pos is null
+  const void* weight;       // [E, D] bf16
+  const float* bias;        // [E], nullable
+  const float* pos;         // [L, E], nullable
+  void* tokens;             // [M, E] bf16 or float
+};
+hipError_t launch_patch_embed(const EmbedArgs& a, hipStream_t stream);
+
 }  // namespace mae

@@ -112,3 +112,26 @@ def make_pred(seed: int, B: int, L: int, D: int) -> np.ndarray:
     for b in range(B):
         out[b] = make_pred_rows(seed, b, L, D)
     return out
+
+
+def make_embed_params(seed: int, D: int, E: int, L: int):
+    """Parameters of a patch embedding: weight [E, D] ~ N(0, 0.02^2) (the ViT initialisation
+    scale), bias [E] ~ N(0, 0.02^2), pos [L, E] uniform in [-1, 1] (the range of the fixed
+    sine-cosine positional embedding).  fp32; the caller rounds the weight to bf16."""
+    rng = np.random.default_rng([seed, 404, D, E, L])
+    weight = (0.02 * rng.standard_normal((E, D))).astype(np.float32)
+    bias = (0.02 * rng.standard_normal(E)).astype(np.float32)
+    pos = rng.uniform(-1.0, 1.0, (L, E)).astype(np.float32)
+    return weight, bias, pos
+
+
+def make_visible_rows(seed: int, M: int, D: int) -> np.ndarray:
+    """Stand-in for visible patch rows when the embedding is tested on its own: image-normalised
+    pixel values lie in about [-2.2, 2.7]; uniform over that range, fp32 [M, D]."""
+    rng = np.random.default_rng([seed, 505, D])
+    return rng.uniform(-2.2, 2.7, (M, D)).astype(np.float32)
+
+
+def make_ids(seed: int, M: int, L: int) -> np.ndarray:
+    rng = np.random.default_rng([seed, 606, L])
+    return rng.integers(0, L, M, dtype=np.int32)

@@ -171,6 +171,45 @@ def test_loss_rejects_bad_buffers(lib):
     assert lib.mae_normpix_loss(None, FAKE, FAKE, FAKE, need, None) == binding.MAE_ERR_NULL
 
 
+def _embed_desc(**over):
+    d = binding.MaeEmbedDesc()
+    d.M, d.D, d.E, d.L = 196, 768, 768, 196
+    d.visible = d.ids_keep = d.weight = d.bias = d.pos = FAKE
+    d.out_dtype = binding.MAE_BF16
+    for k, v in over.items():
+        setattr(d, k, v)
+    return d
+
+
+@pytest.mark.parametrize("over,status", [
+    (dict(visible=None), binding.MAE_ERR_NULL),
+    (dict(weight=None), binding.MAE_ERR_NULL),
+    (dict(ids_keep=None), binding.MAE_ERR_NULL),  # pos is given, so the indices are needed
+    (dict(M=0), binding.MAE_ERR_SHAPE),
+    (dict(E=0), binding.MAE_ERR_SHAPE),
+    (dict(L=0), binding.MAE_ERR_SHAPE),
+    (dict(D=0), binding.MAE_ERR_SHAPE),
+    (dict(D=27), binding.MAE_ERR_SHAPE),  # 3 x 3 x 3: not a multiple of four values
+    (dict(D=3076), binding.MAE_ERR_RANGE),
+    (dict(E=8193), binding.MAE_ERR_RANGE),
+    (dict(M=(1 << 28) + 1), binding.MAE_ERR_RANGE),
+    (dict(out_dtype=2), binding.MAE_ERR_DTYPE),
+    (dict(visible=FAKE + 8), binding.MAE_ERR_RANGE),
+    (dict(weight=FAKE + 2), binding.MAE_ERR_RANGE),
+    (dict(pos=FAKE + 4), binding.MAE_ERR_RANGE),
+])
+def test_embed_rejects_bad_descriptors(lib, over, status):
+    d = _embed_desc(**over)
+    assert lib.mae_patch_embed(C.byref(d), FAKE, None) == status
+
+
+def test_embed_rejects_bad_buffers(lib):
+    d = _embed_desc()
+    assert lib.mae_patch_embed(C.byref(d), None, None) == binding.MAE_ERR_NULL
+    assert lib.mae_patch_embed(C.byref(d), FAKE + 8, None) == binding.MAE_ERR_RANGE
+    assert lib.mae_patch_embed(None, FAKE, None) == binding.MAE_ERR_NULL
+
+
 @pytest.mark.skipif(torch.cuda.is_available(), reason="a GPU is visible")
 def test_valid_calls_report_no_device_without_a_gpu(lib):
     # all arguments pass validation; with no device nothing is launched and nothing is read
@@ -178,6 +217,10 @@ def test_valid_calls_report_no_device_without_a_gpu(lib):
     d = _loss_desc()
     assert lib.mae_normpix_loss(C.byref(d), FAKE, FAKE, FAKE, 1 << 20,
                                 None) == binding.MAE_ERR_NO_DEVICE
+    e = _embed_desc()
+    assert lib.mae_patch_embed(C.byref(e), FAKE, None) == binding.MAE_ERR_NO_DEVICE
+    e = _embed_desc(pos=None, ids_keep=None, bias=None)  # both additions are optional
+    assert lib.mae_patch_embed(C.byref(e), FAKE, None) == binding.MAE_ERR_NO_DEVICE
     n = C.c_int32(0)
     assert lib.mae_prep_status(FAKE, None, C.byref(n)) == binding.MAE_ERR_NO_DEVICE
     assert lib.mae_prep_status(None, None, C.byref(n)) == binding.MAE_ERR_NULL
