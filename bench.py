@@ -5,6 +5,9 @@ order, fused crop/resize/flip/normalise/patchify/gather) followed by mae_normpix
 gradient), on synthetic images already resident in HBM.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4] [--no-cpu-baseline]
+
+The first consumer of the path's output, mae_patch_embed, is timed by itself after the steps and
+reported under "patch_embed"; it is not part of the step or of `value`.
 """
 from __future__ import annotations
 
@@ -19,6 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix rate
 
 # HBM bytes per launch of the loss kernel from rocprofv3 counters (FETCH_SIZE and WRITE_SIZE runs,
 # each scaled by what the counter reads for a plain device copy of known size; the summaries are
@@ -105,6 +109,47 @@ def time_scheme(args, mae, synth, torch, dev, wl, bf16):
     return rows
 
 
+def time_embed(args, mae, synth, torch, dev, wl, K, E):
+    """mae_patch_embed on every visible row of the batch (bf16 in, bf16 out), timed by itself with
+    events on the launch stream.  Not part of the step above."""
+    import numpy as np
+
+    desc = mae.make_prep_desc(*dev, out_size=wl.out_size, patch=wl.patch, num_keep=K, seed=0,
+                              batch_index=0, out_dtype=mae.MAE_BF16)
+    buf = mae.alloc_prep_buffers(desc, want_target=False)
+    stream = torch.cuda.current_stream()
+    mae.mae_prep_batch(desc, buf.visible, buf.mask, buf.ids_restore, buf.ids_keep, None, buf.crop,
+                       buf.workspace, stream=stream)
+    weight, bias, pos = synth.make_embed_params(0, wl.D, E, wl.L)
+    w = torch.from_numpy(weight).cuda().to(torch.bfloat16)
+    b, p = torch.from_numpy(bias).cuda(), torch.from_numpy(pos).cuda()
+    tokens = torch.empty((wl.B, K, E), dtype=torch.bfloat16, device="cuda")
+    edesc = mae.make_embed_desc(buf.visible, buf.ids_keep, w, b, p, out_dtype=mae.MAE_BF16)
+    for _ in range(max(args.warmup, 1)):
+        mae.mae_patch_embed(edesc, tokens, stream=stream)
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+    for e in ev:
+        e[0].record(stream)
+        mae.mae_patch_embed(edesc, tokens, stream=stream)
+        e[1].record(stream)
+    torch.cuda.synchronize()
+    ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    M = wl.B * K
+    flops = 2.0 * M * wl.D * E
+    nbytes = 2 * M * wl.D + 2 * M * E + 2 * E * wl.D + 4 * M + 4 * wl.L * E + 4 * E
+    tflops = flops / (ms * 1e-3) / 1e12
+    return {
+        "kernel": "patch_embed_kernel (mae_patch_embed), bf16 x bf16 -> fp32 -> bf16",
+        "M": M, "D": wl.D, "E": E, "avg_ms": round(ms, 4),
+        "bound": "mfma", "achieved": round(tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+        "unit": "TFLOP/s", "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+        "flops": flops, "algorithmic_bytes": nbytes,
+        "achieved_GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+        "checksum": float(tokens.float().abs().mean().item()),
+    }
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -116,6 +161,9 @@ def main() -> int:
     ap.add_argument("--scheme", type=int, default=0,
                     help="also time the three stages of pretraining scheme 1..6 (Table 9) on "
                          "buffers allocated once; adds a 'stages' list to the JSON line")
+    ap.add_argument("--embed", type=int, default=768,
+                    help="embedding width E for the separately timed mae_patch_embed launch over "
+                         "the batch's visible rows (adds 'patch_embed' to the JSON line); 0 = skip")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed region, run one plain device copy of known size "
                          "(grad <- pred) so that a counter run has a reference kernel")
@@ -246,6 +294,9 @@ def main() -> int:
                                        / HBM_PEAK_GBPS, 4),
         "loss_value": final_loss,
     }
+
+    if args.embed > 0:
+        out["patch_embed"] = time_embed(args, mae, synth, torch, dev, wl, K, args.embed)
 
     if args.scheme:
         out["stages"] = time_scheme(args, mae, synth, torch, dev, wl, bf16)
