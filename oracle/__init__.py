@@ -55,6 +55,8 @@ class _PrepArgs(C.Structure):
         ("seed", C.c_uint64),
         ("batch_index", C.c_uint64),
         ("noise_bits", C.c_int32),
+        ("aug_mode", C.c_int32),
+        ("jitter", C.c_float),
     ]
 
 
@@ -94,6 +96,22 @@ def load_library(path: str):
     L.mae_oracle_mask.restype = None
     L.mae_oracle_mask.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_int32, C.c_int32,
                                   C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.mae_oracle_resize_u8.restype = None
+    L.mae_oracle_resize_u8.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32,
+                                       C.c_int32, C.c_void_p]
+    L.mae_oracle_aug_params.restype = None
+    L.mae_oracle_aug_params.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_double,
+                                        C.c_void_p, C.c_void_p, C.c_void_p]
+    L.mae_oracle_gray.restype = C.c_int32
+    L.mae_oracle_gray.argtypes = [C.c_int32] * 3
+    L.mae_oracle_solarise.restype = C.c_int32
+    L.mae_oracle_solarise.argtypes = [C.c_int32]
+    L.mae_oracle_blur_weights.restype = C.c_int32
+    L.mae_oracle_blur_weights.argtypes = [C.c_double, C.c_void_p]
+    L.mae_oracle_three_aug.restype = None
+    L.mae_oracle_three_aug.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_void_p]
+    L.mae_oracle_color_jitter.restype = None
+    L.mae_oracle_color_jitter.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
     L.mae_oracle_prep_batch.restype = C.c_int32
     L.mae_oracle_prep_batch.argtypes = [C.c_void_p, C.c_int32, C.c_int32] + [C.c_void_p] * 6
     L.mae_oracle_normpix_loss.restype = C.c_int32
@@ -177,6 +195,64 @@ def crop_resize(img: np.ndarray, box, S: int, flip: int) -> np.ndarray:
     return out
 
 
+def resize_u8(img: np.ndarray, box, S: int, flip: int) -> np.ndarray:
+    """img [H,W,3] uint8 -> [S,S,3] uint8: the bilinear value rounded to nearest, ties up."""
+    img = np.ascontiguousarray(img, np.uint8)
+    H, W, ch = img.shape
+    assert ch == 3
+    b = np.asarray(box, np.int32)
+    out = np.empty((S, S, 3), np.uint8)
+    lib().mae_oracle_resize_u8(_p(img), H, W, _p(b), S, int(flip), _p(out))
+    return out
+
+
+AUG_SIMPLE, AUG_THREE, AUG_THREE_PLUS = 0, 1, 2
+OP_GRAY, OP_SOLARISE, OP_BLUR = 0, 1, 2
+
+
+def aug_params(seed, batch_index, sample, jitter=0.3):
+    """-> (op, sigma, (brightness, contrast, saturation))."""
+    op = C.c_int32()
+    sigma = C.c_double()
+    bcs = np.empty(3, np.float64)
+    lib().mae_oracle_aug_params(seed, batch_index, sample, jitter, C.byref(op), C.byref(sigma),
+                                _p(bcs))
+    return op.value, sigma.value, tuple(float(v) for v in bcs)
+
+
+def gray(r: int, g: int, b: int) -> int:
+    return int(lib().mae_oracle_gray(r, g, b))
+
+
+def solarise(v: int) -> int:
+    return int(lib().mae_oracle_solarise(v))
+
+
+def blur_weights(sigma: float) -> np.ndarray:
+    w = np.zeros(13, np.float64)
+    r = lib().mae_oracle_blur_weights(sigma, _p(w))
+    return w[:2 * r + 1].copy()
+
+
+def three_aug(u8: np.ndarray, op: int, sigma: float = 1.0) -> np.ndarray:
+    """u8 [S,S,3] uint8 -> [S,S,3] float64 in pixel units."""
+    u8 = np.ascontiguousarray(u8, np.uint8)
+    S = u8.shape[0]
+    assert u8.shape == (S, S, 3)
+    out = np.empty((S, S, 3), np.float64)
+    lib().mae_oracle_three_aug(_p(u8), S, op, sigma, _p(out))
+    return out
+
+
+def color_jitter(img: np.ndarray, bcs) -> np.ndarray:
+    out = np.ascontiguousarray(img, np.float64).copy()
+    S = out.shape[0]
+    assert out.shape == (S, S, 3)
+    f = np.asarray(bcs, np.float64)
+    lib().mae_oracle_color_jitter(_p(out), S, _p(f))
+    return out
+
+
 def normalise(v: float, mean: float, std: float) -> float:
     return float(lib().mae_oracle_normalise(v, mean, std))
 
@@ -207,7 +283,7 @@ def mask(seed, batch_index, sample, L, K, noise_bits=32):
 def prep_batch(images, offsets, heights, widths, *, out_size, patch, num_keep, scale=(0.2, 1.0),
                ratio=(3.0 / 4.0, 4.0 / 3.0), flip_p=0.5, mean=IMAGENET_MEAN, std=IMAGENET_STD,
                seed=0, batch_index=0, noise_bits=32, b_begin=0, b_end=None, want_target=True,
-               want_visible=True):
+               want_visible=True, aug_mode=0, jitter=0.3):
     """Run the oracle pipeline on samples [b_begin, b_end).  Returns a dict of NumPy arrays."""
     images = np.ascontiguousarray(images, np.uint8)
     offsets = np.ascontiguousarray(offsets, np.int64)
@@ -231,6 +307,7 @@ def prep_batch(images, offsets, heights, widths, *, out_size, patch, num_keep, s
     a.mean = (C.c_float * 3)(*mean)
     a.std = (C.c_float * 3)(*std)
     a.seed, a.batch_index, a.noise_bits = seed, batch_index, noise_bits
+    a.aug_mode, a.jitter = aug_mode, jitter
     out = {
         "visible": np.empty((n, num_keep, D), np.float32) if want_visible else None,
         "mask": np.empty((n, Lp), np.uint8),

@@ -237,6 +237,137 @@ void mae_oracle_mask(uint64_t seed, uint64_t batch_index, uint32_t sample, int32
 }
 
 /* ------------------------------------------------------------------------------------------------
+ * Finetuning augmentation "3 Aug" / "3 Aug+" (Sec. 3, Sec. 4.4, Table 7).  The paper names the
+ * procedure and cites it; it prints no parameter.  Readings: the operations act on the 8-bit
+ * image that crop + resize produce (the cited procedure is defined on 8-bit images: a
+ * solarisation threshold only means something there), so the resized crop is first rounded to
+ * bytes -- exactly, the bilinear value being the rational num / den^2 with den = 2 S.  One of the
+ * three operations is drawn per image with equal probability.  After it nothing is rounded
+ * again.  "ColorJitter (0.3)" is brightness, contrast and saturation factors uniform on
+ * [0.7, 1.3], applied in that order.
+ * ---------------------------------------------------------------------------------------------- */
+static void taps_exact(int32_t out_size, int32_t crop_len, int32_t o, int32_t* i0, int32_t* i1,
+                       int64_t* r) {
+  int64_t n = (int64_t)crop_len * (2 * (int64_t)o + 1) - (int64_t)out_size;  /* 2 S src */
+  int64_t den = (int64_t)out_size * 2;
+  if (n <= 0) {
+    *i0 = 0;
+    *r = 0;
+  } else {
+    *i0 = (int32_t)(n / den); /* whole source pixels */
+    *r = n % den;
+  }
+  *i1 = (*i0 < crop_len - 1) ? *i0 + 1 : crop_len - 1;
+}
+
+void mae_oracle_resize_u8(const uint8_t* img, int32_t H, int32_t W, const int32_t box[4], int32_t S,
+                          int32_t flip, uint8_t* out) {
+  (void)H;
+  int32_t top = box[0], left = box[1], ch = box[2], cw = box[3];
+  int64_t den = 2 * (int64_t)S;
+  for (int32_t oy = 0; oy < S; ++oy) {
+    int32_t y0, y1;
+    int64_t ry;
+    taps_exact(S, ch, oy, &y0, &y1, &ry);
+    for (int32_t ox = 0; ox < S; ++ox) {
+      int32_t sx = flip ? (S - ox - 1) : ox; /* mirrored column */
+      int32_t x0, x1;
+      int64_t rx;
+      taps_exact(S, cw, sx, &x0, &x1, &rx);
+      for (int32_t c = 0; c < 3; ++c) {
+        int64_t a00 = img[((int64_t)(top + y0) * W + (left + x0)) * 3 + c];
+        int64_t a01 = img[((int64_t)(top + y0) * W + (left + x1)) * 3 + c];
+        int64_t a10 = img[((int64_t)(top + y1) * W + (left + x0)) * 3 + c];
+        int64_t a11 = img[((int64_t)(top + y1) * W + (left + x1)) * 3 + c];
+        /* value = num / den^2 */
+        int64_t num = (den - ry) * ((den - rx) * a00 + rx * a01) + ry * ((den - rx) * a10 + rx * a11);
+        out[((int64_t)oy * S + ox) * 3 + c] = (uint8_t)((2 * num + den * den) / (2 * den * den));
+      }
+    }
+  }
+}
+
+void mae_oracle_aug_params(uint64_t seed, uint64_t batch_index, uint32_t sample, double jitter,
+                           int32_t* op, double* sigma, double bcs[3]) {
+  int32_t k = (int32_t)floor(3.0 * draw_unit(seed, batch_index, sample, 6u, 0u));
+  *op = k > 2 ? 2 : k;
+  *sigma = 0.1 + 1.9 * draw_unit(seed, batch_index, sample, 7u, 0u);
+  for (uint32_t j = 0; j < 3; ++j)
+    bcs[j] = 1.0 + jitter * (2.0 * draw_unit(seed, batch_index, sample, 8u + j, 0u) - 1.0);
+}
+
+int32_t mae_oracle_gray(int32_t r, int32_t g, int32_t b) {
+  return (299 * r + 587 * g + 114 * b + 500) / 1000;
+}
+
+int32_t mae_oracle_solarise(int32_t v) { return v >= 128 ? 255 - v : v; }
+
+int32_t mae_oracle_blur_weights(double sigma, double* w) {
+  int32_t radius = (int32_t)ceil(3.0 * sigma);
+  if (radius < 1) radius = 1;
+  double sum = 0.0;
+  for (int32_t k = -radius; k <= radius; ++k) {
+    w[k + radius] = exp(-(double)(k * k) / (2.0 * sigma * sigma));
+    sum += w[k + radius];
+  }
+  for (int32_t k = 0; k <= 2 * radius; ++k) w[k] /= sum;
+  return radius;
+}
+
+static int32_t clampi(int32_t v, int32_t lo, int32_t hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+void mae_oracle_three_aug(const uint8_t* u8, int32_t S, int32_t op, double sigma, double* out) {
+  int64_t n = (int64_t)S * S;
+  if (op == 0) {
+    for (int64_t i = 0; i < n; ++i) {
+      double g = (double)mae_oracle_gray(u8[i * 3], u8[i * 3 + 1], u8[i * 3 + 2]);
+      out[i * 3] = out[i * 3 + 1] = out[i * 3 + 2] = g;
+    }
+  } else if (op == 1) {
+    for (int64_t i = 0; i < n * 3; ++i) out[i] = (double)mae_oracle_solarise(u8[i]);
+  } else {
+    double w[13];
+    int32_t radius = mae_oracle_blur_weights(sigma, w);
+    double* tmp = (double*)malloc(sizeof(double) * (size_t)n * 3);
+    /* along y, then along x; border pixels repeated */
+    for (int32_t y = 0; y < S; ++y)
+      for (int32_t x = 0; x < S; ++x)
+        for (int32_t c = 0; c < 3; ++c) {
+          double acc = 0.0;
+          for (int32_t k = -radius; k <= radius; ++k)
+            acc += w[k + radius] * (double)u8[((int64_t)clampi(y + k, 0, S - 1) * S + x) * 3 + c];
+          tmp[((int64_t)y * S + x) * 3 + c] = acc;
+        }
+    for (int32_t y = 0; y < S; ++y)
+      for (int32_t x = 0; x < S; ++x)
+        for (int32_t c = 0; c < 3; ++c) {
+          double acc = 0.0;
+          for (int32_t k = -radius; k <= radius; ++k)
+            acc += w[k + radius] * tmp[((int64_t)y * S + clampi(x + k, 0, S - 1)) * 3 + c];
+          out[((int64_t)y * S + x) * 3 + c] = acc;
+        }
+    free(tmp);
+  }
+}
+
+static double clampd(double v) { return v < 0.0 ? 0.0 : (v > 255.0 ? 255.0 : v); }
+static double luma(const double* px) { return 0.299 * px[0] + 0.587 * px[1] + 0.114 * px[2]; }
+
+void mae_oracle_color_jitter(double* img, int32_t S, const double bcs[3]) {
+  int64_t n = (int64_t)S * S;
+  for (int64_t i = 0; i < n * 3; ++i) img[i] = clampd(img[i] * bcs[0]);
+  double mean = 0.0;
+  for (int64_t i = 0; i < n; ++i) mean += luma(img + i * 3);
+  mean /= (double)n;
+  for (int64_t i = 0; i < n * 3; ++i) img[i] = clampd(bcs[1] * img[i] + (1.0 - bcs[1]) * mean);
+  for (int64_t i = 0; i < n; ++i) {
+    double g = luma(img + i * 3);
+    for (int32_t c = 0; c < 3; ++c)
+      img[i * 3 + c] = clampd(bcs[2] * img[i * 3 + c] + (1.0 - bcs[2]) * g);
+  }
+}
+
+/* ------------------------------------------------------------------------------------------------
  * Whole input pipeline.
  * ---------------------------------------------------------------------------------------------- */
 int32_t mae_oracle_prep_batch(const mae_oracle_prep_args* a, int32_t b_begin, int32_t b_end,
@@ -250,6 +381,7 @@ int32_t mae_oracle_prep_batch(const mae_oracle_prep_args* a, int32_t b_begin, in
   int64_t D = 3 * (int64_t)p * p;
   if (K < 1 || K > L) return -1;
   if (a->noise_bits < 1 || a->noise_bits > 32) return -1;
+  if (a->aug_mode < 0 || a->aug_mode > 2) return -1;
 
   int failed = 0;
 #pragma omp parallel for schedule(dynamic, 1)
@@ -281,7 +413,19 @@ int32_t mae_oracle_prep_batch(const mae_oracle_prep_args* a, int32_t b_begin, in
       if (!resized || !patches) {
         failed = 1;
       } else {
-        mae_oracle_crop_resize(img, H, W, box, S, flip, resized);
+        if (a->aug_mode == 0) {
+          mae_oracle_crop_resize(img, H, W, box, S, flip, resized);
+        } else {
+          uint8_t* u8 = (uint8_t*)malloc((size_t)S * S * 3);
+          int32_t op;
+          double sigma, bcs[3];
+          mae_oracle_resize_u8(img, H, W, box, S, flip, u8);
+          mae_oracle_aug_params(a->seed, a->batch_index, (uint32_t)b, (double)a->jitter, &op,
+                                &sigma, bcs);
+          mae_oracle_three_aug(u8, S, op, sigma, resized);
+          if (a->aug_mode == 2) mae_oracle_color_jitter(resized, S, bcs);
+          free(u8);
+        }
         for (int64_t i = 0; i < (int64_t)S * S; ++i)
           for (int32_t c = 0; c < 3; ++c)
             resized[i * 3 + c] =

@@ -78,6 +78,35 @@ int32_t mae_oracle_num_keep(int32_t L, double mask_ratio);
 void mae_oracle_mask(uint64_t seed, uint64_t batch_index, uint32_t sample, int32_t L, int32_t K,
                      int32_t noise_bits, int32_t* ids_restore, int32_t* ids_keep, uint8_t* mask);
 
+/* ---- finetuning augmentation: "3 Aug" and "3 Aug+" (Sec. 3 finetuning recipe, Sec. 4.4 "Data
+ * Augmentation", Sec. 5.2 Table 7; the procedure itself is the cited Three Augmentation: one of
+ * grayscale / solarisation / Gaussian blur per image, chosen uniformly, optionally followed by
+ * colour jitter).  The paper gives no parameters; the readings are written at each function. ---- */
+/* The resized crop as an 8-bit image: the bilinear value of mae_oracle_crop_resize rounded to the
+ * nearest integer, ties upwards, evaluated in exact integer arithmetic.  out: S x S x 3. */
+void mae_oracle_resize_u8(const uint8_t* img, int32_t H, int32_t W, const int32_t box[4], int32_t S,
+                          int32_t flip, uint8_t* out);
+/* Per-sample draws: op = 0 grayscale, 1 solarise, 2 blur (stream 6); sigma uniform on [0.1, 2]
+ * (stream 7); brightness, contrast, saturation factors uniform on [1 - jitter, 1 + jitter]
+ * (streams 8, 9, 10). */
+void mae_oracle_aug_params(uint64_t seed, uint64_t batch_index, uint32_t sample, double jitter,
+                           int32_t* op, double* sigma, double bcs[3]);
+/* Luma of an 8-bit pixel with the ITU-R BT.601 weights 0.299, 0.587, 0.114, rounded to the
+ * nearest integer in integer arithmetic. */
+int32_t mae_oracle_gray(int32_t r, int32_t g, int32_t b);
+/* Solarisation with threshold 128: values at or above it are inverted. */
+int32_t mae_oracle_solarise(int32_t v);
+/* Gaussian taps exp(-k^2 / (2 sigma^2)), k = -radius..radius, radius = ceil(3 sigma), scaled to
+ * sum 1.  w must hold 2 * radius + 1 <= 13 values.  Returns the radius. */
+int32_t mae_oracle_blur_weights(double sigma, double* w);
+/* One of the three operations on an 8-bit S x S x 3 image -> doubles in pixel units.  The blur is
+ * the separable Gaussian above with the image's border pixels repeated outwards. */
+void mae_oracle_three_aug(const uint8_t* u8, int32_t S, int32_t op, double sigma, double* out);
+/* Colour jitter in place on S x S x 3 doubles: brightness (v * b), then contrast (blend with the
+ * mean luma of the whole image, weight c), then saturation (blend with the pixel's luma, weight
+ * s); every step clamps to [0, 255]. */
+void mae_oracle_color_jitter(double* img, int32_t S, const double bcs[3]);
+
 /* ---- the whole input pipeline for samples [b_begin, b_end) of a batch ------------------------- */
 typedef struct {
   int32_t B;
@@ -90,6 +119,8 @@ typedef struct {
   float mean[3], std[3];
   uint64_t seed, batch_index;
   int32_t noise_bits;
+  int32_t aug_mode; /* 0 = "Simple" (App. B); 1 = "3 Aug"; 2 = "3 Aug+" = 3 Aug + ColorJitter */
+  float jitter;     /* ColorJitter strength (0.3 in Sec. 5.2), used by aug_mode 2 */
 } mae_oracle_prep_args;
 
 /* Outputs are indexed by (b - b_begin); any may be NULL.  The hash is keyed by the global sample

@@ -90,6 +90,59 @@ MUTATIONS = [
     ("scheme 4 ratios", "{0.75, 0.80, 0.85}, {0.75, 0.75, 0.75}, {0.75, 0.75, 0.85},",
      "{0.75, 0.80, 0.80}, {0.75, 0.75, 0.75}, {0.75, 0.75, 0.85},",
      ["test_progressive_schemes_match_the_printed_tables"]),
+    ("resize to bytes truncates", "(uint8_t)((2 * num + den * den) / (2 * den * den));",
+     "(uint8_t)((2 * num) / (2 * den * den));",
+     ["test_three_aug_worked_examples", "test_resize_u8_is_the_exactly_rounded_bilinear_value"]),
+    ("resize to bytes, weights of the rows swapped",
+     "(den - ry) * ((den - rx) * a00 + rx * a01) + ry * ((den - rx) * a10 + rx * a11);",
+     "ry * ((den - rx) * a00 + rx * a01) + (den - ry) * ((den - rx) * a10 + rx * a11);",
+     ["test_resize_u8_is_the_exactly_rounded_bilinear_value"]),
+    ("luma weights swapped", "(299 * r + 587 * g + 114 * b + 500) / 1000",
+     "(587 * r + 299 * g + 114 * b + 500) / 1000", ["test_three_aug_worked_examples"]),
+    ("luma truncated", "(299 * r + 587 * g + 114 * b + 500) / 1000",
+     "(299 * r + 587 * g + 114 * b) / 1000", ["test_gray_and_solarise_over_their_whole_domain"]),
+    ("solarise threshold off by one", "return v >= 128 ? 255 - v : v;",
+     "return v > 128 ? 255 - v : v;", ["test_three_aug_worked_examples"]),
+    ("blur radius", "(int32_t)ceil(3.0 * sigma);", "(int32_t)ceil(2.0 * sigma);",
+     ["test_blur_matches_the_library_gaussian_filter"]),
+    ("blur taps not scaled to one", "for (int32_t k = 0; k <= 2 * radius; ++k) w[k] /= sum;",
+     "for (int32_t k = 0; k <= 2 * radius; ++k) w[k] /= 1.0;",
+     ["test_blur_matches_the_library_gaussian_filter"]),
+    ("blur variance", "exp(-(double)(k * k) / (2.0 * sigma * sigma));",
+     "exp(-(double)(k * k) / (sigma * sigma));", ["test_blur_matches_the_library_gaussian_filter"]),
+    ("blur border wraps", "(double)u8[((int64_t)clampi(y + k, 0, S - 1) * S + x) * 3 + c];",
+     "(double)u8[((int64_t)((y + k + S) % S) * S + x) * 3 + c];",
+     ["test_blur_matches_the_library_gaussian_filter"]),
+    ("blur along one axis only", "acc += w[k + radius] * tmp[((int64_t)y * S + clampi(x + k, 0, S - 1)) * 3 + c];",
+     "acc += (k == 0 ? 1.0 : 0.0) * tmp[((int64_t)y * S + clampi(x + k, 0, S - 1)) * 3 + c];",
+     ["test_blur_matches_the_library_gaussian_filter"]),
+    ("operation drawn from the blur stream",
+     "floor(3.0 * draw_unit(seed, batch_index, sample, 6u, 0u));",
+     "floor(3.0 * draw_unit(seed, batch_index, sample, 7u, 0u));",
+     ["test_aug_draws_are_uniform_and_independent"]),
+    ("blur width range", "*sigma = 0.1 + 1.9 * draw_unit", "*sigma = 0.1 + 2.9 * draw_unit",
+     ["test_aug_draws_are_uniform_and_independent"]),
+    ("jitter factors one-sided", "bcs[j] = 1.0 + jitter * (2.0 * draw_unit(seed, batch_index, sample, 8u + j, 0u) - 1.0);",
+     "bcs[j] = 1.0 + jitter * (draw_unit(seed, batch_index, sample, 8u + j, 0u));",
+     ["test_aug_draws_are_uniform_and_independent"]),
+    ("brightness not clamped", "img[i] = clampd(img[i] * bcs[0]);", "img[i] = img[i] * bcs[0];",
+     ["test_three_aug_worked_examples"]),
+    ("contrast mean taken before brightness",
+     "for (int64_t i = 0; i < n; ++i) mean += luma(img + i * 3);\n  mean /= (double)n;",
+     "for (int64_t i = 0; i < n; ++i) mean += luma(img + i * 3);\n  mean /= (double)n * bcs[0];",
+     ["test_color_jitter_special_cases"]),
+    ("contrast blends with the wrong factor", "(1.0 - bcs[1]) * mean", "(1.0 - bcs[0]) * mean",
+     ["test_three_aug_worked_examples"]),
+    ("saturation blends with the image mean", "double g = luma(img + i * 3);\n    for",
+     "double g = mean;\n    for", ["test_color_jitter_special_cases"]),
+    ("luma weight of green", "0.299 * px[0] + 0.587 * px[1]", "0.299 * px[0] + 0.578 * px[1]",
+     ["test_three_aug_worked_examples"]),
+    ("jitter applied in plain 3 Aug", "if (a->aug_mode == 2) mae_oracle_color_jitter",
+     "if (a->aug_mode >= 1) mae_oracle_color_jitter",
+     ["test_prep_batch_with_finetune_augmentation_is_the_composition_of_its_steps"]),
+    ("augmentation before the flip is undone", "mae_oracle_resize_u8(img, H, W, box, S, flip, u8);",
+     "mae_oracle_resize_u8(img, H, W, box, S, 0, u8);",
+     ["test_prep_batch_with_finetune_augmentation_is_the_composition_of_its_steps"]),
     ("embedding weight transposed", "acc += (double)v[d] * (double)weight[(int64_t)e * D + d];",
      "acc += (double)v[d] * (double)weight[((int64_t)d * E + e) % ((int64_t)E * D)];",
      ["test_patch_embed_closed_forms_and_library_matmul"]),

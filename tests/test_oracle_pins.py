@@ -625,3 +625,209 @@ def test_patch_embed_closed_forms_and_library_matmul():
     np.testing.assert_allclose(two, 2 * oracle.patch_embed(vis, ids, w, None, None), rtol=1e-14)
     with pytest.raises(ValueError):
         oracle.patch_embed(vis, np.full_like(ids, L), w, bias, pos)      # index out of range
+
+
+# ------------------------------------------------------------------- 3 Aug / 3 Aug+ (finetuning)
+def _rand_u8(seed, S):
+    return np.random.default_rng(seed).integers(0, 256, (S, S, 3), dtype=np.uint8)
+
+
+def test_three_aug_worked_examples(golden):
+    rows = golden("three_aug_examples.txt")
+    j4 = {}
+    for row in rows:
+        if row[0] == "gray":
+            assert oracle.gray(*map(int, row[1:4])) == int(row[4]), row
+        elif row[0] == "solarise":
+            assert oracle.solarise(int(row[1])) == int(row[2]), row
+        elif row[0] == "jitter1":
+            px = np.array(row[1:4], np.float64).reshape(1, 1, 3)
+            out = oracle.color_jitter(px, [float(v) for v in row[4:7]])
+            np.testing.assert_allclose(out.reshape(3), [float(v) for v in row[7:10]], atol=1e-9)
+        elif row[0].startswith("jitter4"):
+            j4[row[0]] = [float(v) for v in row[1:]]
+        elif row[0] == "resize_tie":
+            a, b, c, d, want = map(int, row[1:])
+            img = np.repeat(np.array([[a, b], [c, d]], np.uint8)[:, :, None], 3, axis=2)
+            assert (oracle.resize_u8(img, (0, 0, 2, 2), 1, 0) == want).all(), row
+        else:
+            raise AssertionError(row)
+    out = oracle.color_jitter(np.array(j4["jitter4_in"]).reshape(2, 2, 3), j4["jitter4"])
+    np.testing.assert_allclose(out.reshape(-1), j4["jitter4_out"], atol=1e-9)
+
+
+def test_resize_u8_is_the_exactly_rounded_bilinear_value():
+    from fractions import Fraction
+    rng = np.random.default_rng(31)
+    img = rng.integers(0, 256, (23, 31, 3), dtype=np.uint8)
+    # identity: a crop as large as the output is returned unchanged, mirrored when flipped
+    box = (3, 5, 16, 16)
+    same = oracle.resize_u8(img, box, 16, 0)
+    np.testing.assert_array_equal(same, img[3:19, 5:21])
+    np.testing.assert_array_equal(oracle.resize_u8(img, box, 16, 1), same[:, ::-1])
+    # brute force in rational arithmetic from the sampling rule src = (o + 1/2) len / S - 1/2
+    box, S = (2, 4, 13, 22), 9
+    top, left, ch, cw = box
+    got = oracle.resize_u8(img, box, S, 0)
+
+    def taps(o, n):
+        pos = (Fraction(2 * o + 1, 2) * n) / S - Fraction(1, 2)
+        pos = max(pos, Fraction(0))
+        i0 = int(pos)               # floor of a non-negative rational
+        f = pos - i0
+        return i0, min(i0 + 1, n - 1), f
+
+    for oy in range(S):
+        y0, y1, fy = taps(oy, ch)
+        for ox in range(S):
+            x0, x1, fx = taps(ox, cw)
+            for c in range(3):
+                p = lambda y, x: int(img[top + y, left + x, c])
+                t = (1 - fx) * p(y0, x0) + fx * p(y0, x1)
+                b = (1 - fx) * p(y1, x0) + fx * p(y1, x1)
+                v = (1 - fy) * t + fy * b
+                want = int(v + Fraction(1, 2))  # ties upwards
+                assert got[oy, ox, c] == want, (oy, ox, c, float(v))
+    # and it is the rounding of the unrounded resize wherever that is not a near-tie
+    real = oracle.crop_resize(img, box, S, 0)
+    frac = real - np.floor(real)
+    clear = np.abs(frac - 0.5) > 1e-9
+    np.testing.assert_array_equal(got[clear], np.floor(real + 0.5)[clear].astype(np.uint8))
+
+
+def test_aug_draws_are_uniform_and_independent():
+    n = 30000
+    ops = np.empty(n, np.int64)
+    sig = np.empty(n)
+    bcs = np.empty((n, 3))
+    for s in range(n):
+        ops[s], sig[s], bcs[s] = oracle.aug_params(11, 2, s, 0.3)
+    freq = np.bincount(ops, minlength=3) / n
+    assert set(np.unique(ops)) == {0, 1, 2} and np.all(np.abs(freq - 1 / 3) < 0.01), freq
+    assert sig.min() >= 0.1 and sig.max() < 2.0
+    assert abs(sig.mean() - 1.05) < 0.01 and abs(sig.std() - 1.9 / math.sqrt(12)) < 0.01
+    assert bcs.min() >= 0.7 and bcs.max() < 1.3 and np.all(np.abs(bcs.mean(0) - 1.0) < 0.005)
+    assert np.all(np.abs(bcs.std(0) - 0.6 / math.sqrt(12)) < 0.005)
+    cols = np.column_stack([ops, sig, bcs])
+    corr = np.corrcoef(cols.T) - np.eye(5)
+    assert np.abs(corr).max() < 0.02, corr
+    # the op is the first third / second third / last third of stream 6, sigma is stream 7
+    for s in range(200):
+        u6 = (oracle.draw(11, 2, s, 6, 0) >> 11) / 2.0 ** 53
+        u7 = (oracle.draw(11, 2, s, 7, 0) >> 11) / 2.0 ** 53
+        assert ops[s] == int(3 * u6) and sig[s] == pytest.approx(0.1 + 1.9 * u7, abs=1e-15)
+    # strength 0 switches the jitter off, other strengths scale the same draw
+    assert oracle.aug_params(11, 2, 5, 0.0)[2] == (1.0, 1.0, 1.0)
+    a, b = oracle.aug_params(11, 2, 5, 0.3)[2], oracle.aug_params(11, 2, 5, 0.15)[2]
+    assert all((x - 1.0) == pytest.approx(2 * (y - 1.0), abs=1e-15) for x, y in zip(a, b))
+
+
+def test_gray_and_solarise_over_their_whole_domain():
+    from fractions import Fraction
+    rng = np.random.default_rng(32)
+    for r, g, b in rng.integers(0, 256, (4000, 3)):
+        v = Fraction(299, 1000) * int(r) + Fraction(587, 1000) * int(g) + Fraction(114, 1000) * int(b)
+        assert oracle.gray(int(r), int(g), int(b)) == int(v + Fraction(1, 2))
+    assert all(oracle.gray(v, v, v) == v for v in range(256))
+    sol = [oracle.solarise(v) for v in range(256)]
+    assert sol[:128] == list(range(128)) and max(sol) == 127 and sum(sol) == 2 * sum(range(128))
+    assert all(sol[v] + v == 255 for v in range(128, 256))
+
+
+def test_blur_matches_the_library_gaussian_filter():
+    from scipy import ndimage
+    for sigma, radius in ((0.1, 1), (0.33, 1), (0.34, 2), (1.0, 3), (1.7, 6), (1.99, 6)):
+        w = oracle.blur_weights(sigma)
+        assert len(w) == 2 * radius + 1, (sigma, len(w))
+        assert w.sum() == pytest.approx(1.0, abs=1e-15)
+        np.testing.assert_allclose(w, w[::-1], rtol=1e-15)
+        k = np.arange(-radius, radius + 1)
+        np.testing.assert_allclose(w / w[radius], np.exp(-k * k / (2 * sigma * sigma)), rtol=1e-13)
+        u8 = _rand_u8(int(sigma * 100), 20)
+        got = oracle.three_aug(u8, oracle.OP_BLUR, sigma)
+        want = ndimage.gaussian_filter(u8.astype(np.float64), sigma=(sigma, sigma, 0),
+                                       mode="nearest", radius=(radius, radius, 0))
+        np.testing.assert_allclose(got, want, rtol=0, atol=1e-10)
+    # a flat image stays flat, an impulse spreads into the outer product of the taps
+    flat = np.full((9, 9, 3), 77, np.uint8)
+    np.testing.assert_allclose(oracle.three_aug(flat, oracle.OP_BLUR, 1.3), 77.0, atol=1e-12)
+    imp = np.zeros((15, 15, 3), np.uint8)
+    imp[7, 7, 1] = 200
+    out = oracle.three_aug(imp, oracle.OP_BLUR, 1.0)
+    w = oracle.blur_weights(1.0)
+    np.testing.assert_allclose(out[4:11, 4:11, 1], 200 * np.outer(w, w), atol=1e-12)
+    assert out[..., 0].max() == 0 and out[..., 2].max() == 0
+    # mirrored input, mirrored output (the border rule is symmetric)
+    u8 = _rand_u8(5, 12)
+    np.testing.assert_allclose(oracle.three_aug(u8[:, ::-1], oracle.OP_BLUR, 0.8),
+                               oracle.three_aug(u8, oracle.OP_BLUR, 0.8)[:, ::-1], atol=1e-12)
+
+
+def test_three_aug_pointwise_operations():
+    u8 = _rand_u8(6, 10)
+    g = oracle.three_aug(u8, oracle.OP_GRAY)
+    assert np.array_equal(g[..., 0], g[..., 1]) and np.array_equal(g[..., 1], g[..., 2])
+    # per pixel it is the scalar luma (pinned in rational arithmetic above)
+    want = [[oracle.gray(*map(int, u8[y, x])) for x in range(10)] for y in range(10)]
+    np.testing.assert_array_equal(g[..., 0], want)
+    s = oracle.three_aug(u8, oracle.OP_SOLARISE)
+    want = [[[oracle.solarise(int(v)) for v in u8[y, x]] for x in range(10)] for y in range(10)]
+    np.testing.assert_array_equal(s, want)
+
+
+def test_color_jitter_special_cases():
+    img = _rand_u8(7, 8).astype(np.float64)
+    np.testing.assert_array_equal(oracle.color_jitter(img, (1, 1, 1)), img)
+    assert not oracle.color_jitter(img, (0.0, 0.9, 1.2)).any()          # black stays black
+    lum = img @ np.array([0.299, 0.587, 0.114])
+    np.testing.assert_allclose(oracle.color_jitter(img, (1, 0.0, 1)), lum.mean(), atol=1e-10)
+    zero_sat = oracle.color_jitter(img, (1, 1, 0.0))
+    np.testing.assert_allclose(zero_sat, np.repeat(lum[..., None], 3, axis=2), atol=1e-10)
+    flat = np.full((4, 4, 3), 90.0)
+    np.testing.assert_allclose(oracle.color_jitter(flat, (1, 1.3, 0.7)), 90.0, atol=1e-10)
+    np.testing.assert_allclose(oracle.color_jitter(flat, (1.3, 1, 1)), 117.0, atol=1e-10)
+    assert oracle.color_jitter(np.full((2, 2, 3), 250.0), (1.3, 1, 1)).max() == 255.0  # clamped
+    # brightness alone is a plain product, contrast alone keeps the mean luma (away from clamps)
+    mid = 64 + img / 2
+    np.testing.assert_allclose(oracle.color_jitter(mid, (1.1, 1, 1)), 1.1 * mid, atol=1e-10)
+    c = oracle.color_jitter(mid, (1, 1.2, 1))
+    lm = (mid @ np.array([0.299, 0.587, 0.114])).mean()
+    np.testing.assert_allclose(c, 1.2 * mid - 0.2 * lm, atol=1e-10)
+    # the contrast mean is taken AFTER the brightness step
+    both = oracle.color_jitter(mid, (1.1, 1.2, 1))
+    np.testing.assert_allclose(both, 1.2 * 1.1 * mid - 0.2 * 1.1 * lm, atol=1e-10)
+
+
+@pytest.mark.parametrize("mode", [1, 2])
+def test_prep_batch_with_finetune_augmentation_is_the_composition_of_its_steps(mode):
+    wl = synth.WORKLOADS["c1"]
+    B = 12
+    data = synth.make_images(wl.kind, B, seed=9)
+    K = wl.L  # finetuning keeps every patch
+    kw = dict(out_size=wl.out_size, patch=wl.patch, num_keep=K, seed=4, batch_index=6,
+              scale=(0.28 ** 2, 1.0))
+    out = oracle.prep_batch(*data, aug_mode=mode, jitter=0.3, **kw)
+    plain = oracle.prep_batch(*data, **kw)
+    for name in ("crop", "ids_restore", "ids_keep", "mask"):   # geometry and order do not change
+        np.testing.assert_array_equal(out[name], plain[name])
+    assert not out["mask"].any()
+    mean, std = np.array(oracle.IMAGENET_MEAN), np.array(oracle.IMAGENET_STD)
+    seen = set()
+    for b in range(B):
+        img = synth.image_view(*data, b)
+        box, flip = out["crop"][b, :4], out["crop"][b, 4]
+        op, sigma, bcs = oracle.aug_params(4, 6, b, 0.3)
+        seen.add(op)
+        v = oracle.three_aug(oracle.resize_u8(img, box, wl.out_size, flip), op, sigma)
+        if mode == 2:
+            v = oracle.color_jitter(v, bcs)
+        want = oracle.patchify((v / 255.0 - mean) / std, wl.patch)
+        np.testing.assert_allclose(out["target"][b], want.astype(np.float32), rtol=0, atol=1e-6)
+        np.testing.assert_array_equal(out["visible"][b], out["target"][b][out["ids_keep"][b]])
+        if mode == 1 and op == oracle.OP_GRAY:      # equal channels before normalisation
+            px = out["target"][b].reshape(-1, 3).astype(np.float64) * std + mean
+            assert np.abs(px - px[:, :1]).max() < 1e-6
+        if mode == 1 and op == oracle.OP_SOLARISE:  # nothing brighter than 127
+            px = out["target"][b].reshape(-1, 3).astype(np.float64) * std + mean
+            assert px.max() <= 127 / 255 + 1e-6
+    assert seen == {0, 1, 2}
