@@ -58,6 +58,23 @@ typedef enum {
 
 typedef enum { MAE_F32 = 0, MAE_BF16 = 1 } mae_dtype;
 
+/* Augmentation applied between resize and normalisation.
+ *   MAE_AUG_SIMPLE      nothing but the flip: the pretraining "Simple" augmentation (App. B).
+ *   MAE_AUG_THREE       the finetuning recipe's "3 Aug" (Sec. 3, Sec. 4.4, Table 7): per image one
+ *                       of grayscale / solarisation / Gaussian blur, each with probability 1/3.
+ *   MAE_AUG_THREE_PLUS  "3 Aug+" (Sec. 5.2): the same followed by colour jitter.
+ * The paper names these procedures without parameters; the library's definitions are:
+ *   - they act on the 8-bit image: the bilinear value is rounded to the nearest integer, ties
+ *     upwards, exactly; after the per-image operation nothing is rounded again;
+ *   - grayscale: luma (299 R + 587 G + 114 B) / 1000 rounded to nearest, in all three channels;
+ *   - solarisation: values >= 128 become 255 - v;
+ *   - blur: separable Gaussian, sigma uniform on [0.1, 2], taps k = -r..r with r = ceil(3 sigma),
+ *     scaled to sum 1, border pixels repeated;
+ *   - jitter: factors b, c, s uniform on [1 - jitter, 1 + jitter]; v <- clamp(b v);
+ *     v <- clamp(c v + (1 - c) m) with m the mean over the image of 0.299 R + 0.587 G + 0.114 B at
+ *     that point; v <- clamp(s v + (1 - s) luma(v)); clamp is to [0, 255]. */
+typedef enum { MAE_AUG_SIMPLE = 0, MAE_AUG_THREE = 1, MAE_AUG_THREE_PLUS = 2 } mae_aug_mode;
+
 /* ------------------------------------------------------------------------------------------------
  * mae_prep_batch
  *
@@ -71,6 +88,10 @@ typedef enum { MAE_F32 = 0, MAE_BF16 = 1 } mae_dtype;
  *
  * Limits: B <= 2^20; 1 <= L <= 256; 1 <= p <= 32; S <= 512;
  * exp(-1/2) <= ratio_lo <= ratio_hi <= exp(1/2).
+ *
+ * Finetuning (Sec. 5.2) uses the same call: every patch is kept (num_keep = L, so `visible` holds
+ * all patches in noise order and `target` all patches in grid order), the crop's scale range
+ * comes from mae_finetune_stage and aug_mode selects the augmentation.
  * ---------------------------------------------------------------------------------------------- */
 typedef struct {
   int32_t B;               /* images in this call, > 0                                          */
@@ -95,6 +116,9 @@ typedef struct {
   int32_t max_image_side;  /* tuning hint: largest H or W in the batch, 0 = 256 (the "maximum
                               side 256" dataset variant).  It sizes the on-chip staging buffer;
                               larger images than hinted stay correct but take a slower path     */
+  int32_t aug_mode;        /* mae_aug_mode.  Other than MAE_AUG_SIMPLE needs p % 4 == 0 and
+                              15 p S + 36 S <= 65536 (S = 224 with p = 16 fits; MAE_ERR_RANGE)  */
+  float jitter;            /* MAE_AUG_THREE_PLUS: strength in [0, 1], 0.3 in the paper            */
 } mae_prep_desc;
 
 /* Outputs (device):

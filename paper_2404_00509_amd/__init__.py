@@ -9,6 +9,9 @@ from .binding import (  # noqa: F401
     IMAGENET_MEAN,
     IMAGENET_STD,
     LIB_PATH,
+    MAE_AUG_SIMPLE,
+    MAE_AUG_THREE,
+    MAE_AUG_THREE_PLUS,
     MAE_BF16,
     MAE_F32,
     MaeEmbedDesc,

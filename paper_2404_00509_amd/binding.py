@@ -19,6 +19,7 @@ MAE_OK = 0
 MAE_ERR_NULL, MAE_ERR_SHAPE, MAE_ERR_RANGE, MAE_ERR_DTYPE = -1, -2, -3, -4
 MAE_ERR_WORKSPACE, MAE_ERR_NO_DEVICE, MAE_ERR_HIP = -5, -6, -7
 MAE_F32, MAE_BF16 = 0, 1
+MAE_AUG_SIMPLE, MAE_AUG_THREE, MAE_AUG_THREE_PLUS = 0, 1, 2
 
 IMAGENET_MEAN = (0.485, 0.456, 0.406)
 IMAGENET_STD = (0.229, 0.224, 0.225)
@@ -53,6 +54,8 @@ class MaePrepDesc(C.Structure):
         ("noise_bits", C.c_int32),
         ("out_dtype", C.c_int32),
         ("max_image_side", C.c_int32),
+        ("aug_mode", C.c_int32),
+        ("jitter", C.c_float),
     ]
 
 
@@ -187,7 +190,7 @@ def _stream(stream):
 def make_prep_desc(images, offsets, heights, widths, *, out_size, patch, num_keep,
                    scale=(0.2, 1.0), ratio=(3.0 / 4.0, 4.0 / 3.0), flip_p=0.5, mean=IMAGENET_MEAN,
                    std=IMAGENET_STD, seed=0, batch_index=0, sample_base=0, noise_bits=32,
-                   out_dtype=MAE_F32, max_image_side=0) -> MaePrepDesc:
+                   out_dtype=MAE_F32, max_image_side=0, aug_mode=0, jitter=0.3) -> MaePrepDesc:
     d = MaePrepDesc()
     d.B = int(heights.numel())
     d.images = images.data_ptr()
@@ -202,6 +205,7 @@ def make_prep_desc(images, offsets, heights, widths, *, out_size, patch, num_kee
     d.seed, d.batch_index, d.sample_base = seed, batch_index, sample_base
     d.noise_bits, d.out_dtype = noise_bits, out_dtype
     d.max_image_side = max_image_side
+    d.aug_mode, d.jitter = aug_mode, jitter
     return d
 
 

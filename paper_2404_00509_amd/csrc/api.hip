@@ -12,7 +12,7 @@
 
 namespace {
 
-constexpr int kVersion = 100;  // 0.1.0
+constexpr int kVersion = 200;  // 0.2.0
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -46,6 +46,15 @@ int validate_prep(const mae_prep_desc* d, PrepShape* shape) {
   if ((uint64_t)d->sample_base + (uint64_t)d->B > 0x100000000ull) return MAE_ERR_RANGE;
   if (d->out_dtype != MAE_F32 && d->out_dtype != MAE_BF16) return MAE_ERR_DTYPE;
   if (d->max_image_side < 0 || d->max_image_side > 32767) return MAE_ERR_RANGE;
+  if (d->aug_mode != MAE_AUG_SIMPLE && d->aug_mode != MAE_AUG_THREE &&
+      d->aug_mode != MAE_AUG_THREE_PLUS)
+    return MAE_ERR_RANGE;
+  if (d->aug_mode != MAE_AUG_SIMPLE) {
+    if (!(d->jitter >= 0.0f) || !(d->jitter <= 1.0f)) return MAE_ERR_RANGE;
+    // whole 16-byte groups per patch row, and a band of p rows (+ blur halo) has to fit the LDS
+    if (d->patch % 4 != 0) return MAE_ERR_SHAPE;
+    if (mae::three_aug_lds_bytes(d->out_size, d->patch) > 64 * 1024) return MAE_ERR_RANGE;
+  }
   if (shape) {
     shape->G = (int32_t)G;
     shape->L = (int32_t)L;
@@ -113,9 +122,31 @@ int32_t mae_num_keep(int32_t L, double mask_ratio) {
   return (int32_t)floor((double)L * (1.0 - mask_ratio));
 }
 
+namespace {
+// Workspace: header | CropRec[B] | (augmentation) 8-bit resized crops [B,S,S,3] | (jitter) one
+// double per (image, row of patches); every part starts on a 256-byte boundary.
+struct PrepWorkspace {
+  size_t u8_offset, partials_offset, total;
+};
+PrepWorkspace prep_workspace(const mae_prep_desc* d) {
+  auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
+  PrepWorkspace w;
+  w.u8_offset = up(mae::kWorkspaceHeader + (size_t)d->B * sizeof(mae::CropRec));
+  w.partials_offset = w.u8_offset;
+  w.total = mae::kWorkspaceHeader + (size_t)d->B * sizeof(mae::CropRec);
+  if (d->aug_mode != MAE_AUG_SIMPLE) {
+    w.partials_offset = up(w.u8_offset + (size_t)d->B * d->out_size * d->out_size * 3);
+    w.total = w.partials_offset;
+    if (d->aug_mode == MAE_AUG_THREE_PLUS)
+      w.total += (size_t)d->B * (d->out_size / d->patch) * sizeof(double);
+  }
+  return w;
+}
+}  // namespace
+
 size_t mae_prep_workspace_bytes(const mae_prep_desc* d) {
   if (validate_prep(d, nullptr) != MAE_OK) return 0;
-  return mae::kWorkspaceHeader + (size_t)d->B * sizeof(mae::CropRec);
+  return prep_workspace(d).total;
 }
 
 int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t* ids_restore,
@@ -186,7 +217,42 @@ int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t
   ca.workspace = static_cast<const uint8_t*>(workspace);
   ca.visible = visible;
   ca.target = target;
+  if (d->aug_mode == MAE_AUG_SIMPLE) {
+    if (mae::launch_crop_patch(ca, stream) != hipSuccess) return MAE_ERR_HIP;
+    return MAE_OK;
+  }
+
+  // finetuning augmentation: the resampling kernel leaves the rounded 8-bit crop in the
+  // workspace, a second kernel applies the per-image operation and writes the patch rows
+  const PrepWorkspace wsl = prep_workspace(d);
+  uint8_t* ws = static_cast<uint8_t*>(workspace);
+  ca.u8_out = ws + wsl.u8_offset;
   if (mae::launch_crop_patch(ca, stream) != hipSuccess) return MAE_ERR_HIP;
+  mae::AugArgs aa;
+  memset(&aa, 0, sizeof(aa));
+  aa.B = ca.B;
+  aa.S = ca.S;
+  aa.p = ca.p;
+  aa.G = ca.G;
+  aa.L = ca.L;
+  aa.K = ca.K;
+  aa.D = ca.D;
+  aa.visible_bf16 = ca.visible_bf16;
+  aa.mode = d->aug_mode;
+  aa.jitter = d->jitter;
+  aa.sample_base = d->sample_base;
+  aa.key1 = pa.key1;
+  for (int c = 0; c < 3; ++c) {
+    aa.nscale[c] = ca.nscale[c];
+    aa.nbias[c] = ca.nbias[c];
+  }
+  aa.u8 = ca.u8_out;
+  aa.ids_restore = ids_restore;
+  aa.workspace = ws;
+  aa.partials = reinterpret_cast<double*>(ws + wsl.partials_offset);
+  aa.visible = visible;
+  aa.target = target;
+  if (mae::launch_three_aug(aa, stream) != hipSuccess) return MAE_ERR_HIP;
   return MAE_OK;
 }
 

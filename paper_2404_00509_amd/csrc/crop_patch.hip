@@ -39,10 +39,12 @@ typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
 // (o + 1/2) len / S - 1/2 kept as the exact fraction n / (2 S); taps clamped to [0, len).
 // The integer quotient comes from a float estimate (off by at most one for n < 2^26, quotient
 // < 2^15) that is corrected with the exact remainder; inv_den = 1 / (2 S).
+// rem is the exact remainder n mod 2 S (the weight of the second tap is rem / (2 S)).
 __device__ static inline void resize_taps(int o, int len, int S, float inv_den, int& i0, int& i1,
-                                          float& f) {
+                                          float& f, int& rem) {
   const int n = (2 * o + 1) * len - S;
   const int den = 2 * S;
+  rem = 0;
   if (n <= 0) {
     i0 = 0;
     f = 0.0f;
@@ -57,9 +59,15 @@ __device__ static inline void resize_taps(int o, int len, int S, float inv_den, 
       r -= den;
     }
     i0 = q;
+    rem = r;
     f = (float)r * inv_den;
   }
   i1 = min(i0 + 1, len - 1);
+}
+__device__ static inline void resize_taps(int o, int len, int S, float inv_den, int& i0, int& i1,
+                                          float& f) {
+  int rem;
+  resize_taps(o, len, S, inv_den, i0, i1, f, rem);
 }
 
 __device__ static inline uint32_t load_rgbx(const uint8_t* p) {
@@ -110,7 +118,11 @@ __device__ static inline u32x4 to_pixels(u32x4 d, uint32_t s) {
 // in bytes; crops too large to stage).  my_rank holds, in lane i, the noise rank of patch i of
 // this part (patches gx0 .. gx0 + npatch - 1); cw is the number of source columns from the
 // part's first tapped column to the crop's right edge.
-template <bool kLds, bool kBf16>
+// kU8: instead of the normalised values, the bilinear value rounded to the nearest byte (ties
+// upwards, exact integer arithmetic on the numerator over (2 S)^2) goes to an 8-bit image in
+// row-major HWC order (a.u8_out) for the finetuning augmentation; the tap tables then hold the
+// integer remainders instead of float weights, and patch rows hold whole groups (3 p % 4 == 0).
+template <bool kLds, bool kBf16, bool kU8>
 __device__ static void produce_patches(const CropArgs& a, const uint32_t* tile, const u32x2* xtab,
                                        const u32x4* ytab, const uint8_t* base, int b, int gy,
                                        int gx0, int npatch, int cw, int my_rank) {
@@ -155,7 +167,7 @@ __device__ static void produce_patches(const CropArgs& a, const uint32_t* tile, 
     const int l = gy * a.G + gx0 + gx;
     const int rank = __builtin_amdgcn_readlane(my_rank, gx);
     const u32x2 xa = xtab[gx * p + pxA], xb = xtab[gx * p + pxB];
-    const float fxA = __uint_as_float(xa.y), fxB = __uint_as_float(xb.y);
+    const float fxA = __uint_as_float(xa.y), fxB = __uint_as_float(xb.y);  // kU8: remainders
     uint32_t A00, A01, A10, A11, B00, B01, B10, B11;
     fetch2<kLds>(tile, base, rowA0, (int)xa.x, cw, A00, A01);
     fetch2<kLds>(tile, base, rowA1, (int)xa.x, cw, A10, A11);
@@ -165,6 +177,36 @@ __device__ static void produce_patches(const CropArgs& a, const uint32_t* tile, 
     const uint32_t P01 = __builtin_amdgcn_perm(B01, A01, sel);
     const uint32_t P10 = __builtin_amdgcn_perm(B10, A10, sel);
     const uint32_t P11 = __builtin_amdgcn_perm(B11, A11, sel);
+
+    if (kU8) {
+      const uint32_t den = 2u * (uint32_t)a.S, dd2 = 2u * den * den;
+      const float inv_dd2 = 1.0f / (float)dd2;
+      const uint32_t ryA = ya.z, ryB = yb.z;
+      uint32_t word = 0;
+#define MAE_ROUND(J)                                                                 \
+{                                                                                  \
+  const uint32_t rx = (J) == 0 ? xa.y : ((J) == 3 ? xb.y : ((J) < nA ? xa.y : xb.y)); \
+  const uint32_t ry = (J) == 0 ? ryA : ((J) == 3 ? ryB : ((J) < nA ? ryA : ryB));  \
+  const uint32_t a00 = (P00 >> (8 * (J))) & 0xFFu, a01 = (P01 >> (8 * (J))) & 0xFFu; \
+  const uint32_t a10 = (P10 >> (8 * (J))) & 0xFFu, a11 = (P11 >> (8 * (J))) & 0xFFu; \
+  const uint32_t num = (den - ry) * ((den - rx) * a00 + rx * a01) +                \
+                       ry * ((den - rx) * a10 + rx * a11);                         \
+  const uint32_t x = 2u * num + den * den; /* floor(x / (2 den^2)) = rounded value */ \
+  int q = (int)((float)x * inv_dd2);                                               \
+  const int r = (int)x - q * (int)dd2;                                             \
+  q += r < 0 ? -1 : (r >= (int)dd2 ? 1 : 0);                                       \
+  word |= (uint32_t)q << (8 * (J));                                                \
+}
+      MAE_ROUND(0) MAE_ROUND(1) MAE_ROUND(2) MAE_ROUND(3)
+#undef MAE_ROUND
+      if (active) {
+        const int row_in_patch = e / (3 * p);
+        const int64_t pos = (((int64_t)b * a.S + gy * p + row_in_patch) * a.S +
+                             (int64_t)(gx0 + gx) * p) * 3 + (e - row_in_patch * 3 * p);
+        *reinterpret_cast<uint32_t*>(a.u8_out + pos) = word;
+      }
+      continue;
+    }
 
     float out[4];
 #define MAE_BLEND(J)                                                                 \
@@ -200,7 +242,7 @@ __device__ static void produce_patches(const CropArgs& a, const uint32_t* tile, 
 }
 
 // Dynamic LDS: [ tile: a.tile_pixels + 4 words | ytab: p x 16 bytes | xtab: a.part_patches p x 8 ].
-template <bool kBf16>
+template <bool kBf16, bool kU8>
 __global__ __launch_bounds__(kCropMaxThreads) void crop_patch_kernel(CropArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
   uint32_t* tile = lds;
@@ -267,19 +309,20 @@ __global__ __launch_bounds__(kCropMaxThreads) void crop_patch_kernel(CropArgs a)
 
   for (int i = tid; i < npatch * p; i += (int)blockDim.x) {
     const int ox = ox_first + i;
-    int x0, x1;
+    int x0, x1, rem;
     float f;
-    resize_taps(rec.flip ? S - 1 - ox : ox, rec.cw, S, inv_den, x0, x1, f);
+    resize_taps(rec.flip ? S - 1 - ox : ox, rec.cw, S, inv_den, x0, x1, f, rem);
     // at the right edge both taps are the last pixel: weight 0 makes the second tap irrelevant
-    xtab[i] = u32x2{(uint32_t)(x0 - xlo), __float_as_uint(x1 == x0 ? 0.0f : f)};
+    const uint32_t wx = kU8 ? (uint32_t)rem : __float_as_uint(f);
+    xtab[i] = u32x2{(uint32_t)(x0 - xlo), x1 == x0 ? 0u : wx};
   }
   for (int py = tid; py < p; py += (int)blockDim.x) {
-    int y0, y1;
+    int y0, y1, rem;
     float f;
-    resize_taps(gy * p + py, rec.ch, S, inv_den, y0, y1, f);
+    resize_taps(gy * p + py, rec.ch, S, inv_den, y0, y1, f, rem);
     const uint32_t stride = use_lds ? (uint32_t)pitch : (uint32_t)row_bytes;
     ytab[py] = u32x4{(uint32_t)(y0 - ylo) * stride, (uint32_t)(y1 - ylo) * stride,
-                     __float_as_uint(f), 0u};
+                     kU8 ? (uint32_t)rem : __float_as_uint(f), 0u};
   }
 
   if (batched) {
@@ -305,11 +348,11 @@ __global__ __launch_bounds__(kCropMaxThreads) void crop_patch_kernel(CropArgs a)
   __syncthreads();
 
   if (use_lds) {
-    produce_patches<true, kBf16>(a, tile, xtab, ytab, base, b, gy, gx0, npatch, rec.cw - xlo,
-                                 my_rank);
+    produce_patches<true, kBf16, kU8>(a, tile, xtab, ytab, base, b, gy, gx0, npatch,
+                                      rec.cw - xlo, my_rank);
   } else {
-    produce_patches<false, kBf16>(a, tile, xtab, ytab, base, b, gy, gx0, npatch, rec.cw - xlo,
-                                  my_rank);
+    produce_patches<false, kBf16, kU8>(a, tile, xtab, ytab, base, b, gy, gx0, npatch,
+                                       rec.cw - xlo, my_rank);
   }
 }
 
@@ -397,10 +440,12 @@ hipError_t launch_crop_patch(const CropArgs& a, hipStream_t stream) {
     dim3 grid((uint32_t)a.B * (uint32_t)a.G * (uint32_t)a.col_parts);
     dim3 block(kWave * (((a.D >> 2) + kWave - 1) / kWave));
     const size_t lds = crop_lds_bytes(a);
-    if (a.visible_bf16) {
-      hipLaunchKernelGGL(crop_patch_kernel<true>, grid, block, lds, stream, a);
+    if (a.u8_out) {
+      hipLaunchKernelGGL((crop_patch_kernel<false, true>), grid, block, lds, stream, a);
+    } else if (a.visible_bf16) {
+      hipLaunchKernelGGL((crop_patch_kernel<true, false>), grid, block, lds, stream, a);
     } else {
-      hipLaunchKernelGGL(crop_patch_kernel<false>, grid, block, lds, stream, a);
+      hipLaunchKernelGGL((crop_patch_kernel<false, false>), grid, block, lds, stream, a);
     }
   } else {
     const int64_t total = (int64_t)a.B * a.L * a.D;

@@ -43,11 +43,44 @@ __host__ __device__ inline uint64_t batch_key(uint64_t seed, uint64_t batch_inde
   return mix64(k0 + kGamma * (batch_index + 1));
 }
 
-enum Stream : uint32_t { kScale = 0, kRatio = 1, kTop = 2, kLeft = 3, kFlip = 4, kNoise = 5 };
+enum Stream : uint32_t {
+  kScale = 0, kRatio = 1, kTop = 2, kLeft = 3, kFlip = 4, kNoise = 5,
+  kAugOp = 6, kBlurSigma = 7, kBrightness = 8, kContrast = 9, kSaturation = 10
+};
 
 __device__ inline uint64_t draw(uint64_t key1, uint32_t sample, uint32_t stream, uint32_t ctr) {
   uint64_t w = ((uint64_t)sample << 32) | ((uint64_t)stream << 24) | (uint64_t)ctr;
   return mix64(key1 + kGamma * (w + 1));
+}
+
+// uniform in [0, 1) from the top 53 bits of a draw; exact in double precision
+__device__ inline double unit53(uint64_t bits) {
+  return (double)(bits >> 11) * (1.0 / 9007199254740992.0);
+}
+
+// ---- per-sample draws of the finetuning augmentation ("3 Aug" / "3 Aug+", Sec. 5.2 Table 7) -----
+// One of grayscale / solarise / Gaussian blur per image with equal probability, the blur's sigma
+// uniform on [0.1, 2], and brightness / contrast / saturation factors uniform on 1 +- jitter.
+enum AugOp : int32_t { kOpGray = 0, kOpSolarise = 1, kOpBlur = 2 };
+struct AugParams {
+  int32_t op;
+  int32_t radius;  // of the blur: ceil(3 sigma), 1..6
+  double sigma;
+  float brightness, contrast, saturation;
+};
+__device__ inline AugParams aug_params(uint64_t key1, uint32_t sample, float jitter) {
+#pragma clang fp contract(off)  // sigma decides the integer radius: no fused multiply-add here
+  AugParams ap;
+  const int k = (int)floor(3.0 * unit53(draw(key1, sample, kAugOp, 0)));
+  ap.op = k > 2 ? 2 : k;
+  ap.sigma = 0.1 + 1.9 * unit53(draw(key1, sample, kBlurSigma, 0));
+  const int r = (int)ceil(3.0 * ap.sigma);
+  ap.radius = r < 1 ? 1 : r;
+  const double j = (double)jitter;
+  ap.brightness = (float)(1.0 + j * (2.0 * unit53(draw(key1, sample, kBrightness, 0)) - 1.0));
+  ap.contrast = (float)(1.0 + j * (2.0 * unit53(draw(key1, sample, kContrast, 0)) - 1.0));
+  ap.saturation = (float)(1.0 + j * (2.0 * unit53(draw(key1, sample, kSaturation, 0)) - 1.0));
+  return ap;
 }
 
 // ---- workgroup id -> logical tile id, so that consecutive tiles share an XCD (and its L2) ------

@@ -44,7 +44,8 @@ struct CropArgs {
   const int32_t* ids_restore;
   const uint8_t* workspace;
   void* visible;
-  float* target;  // nullable
+  float* target;    // nullable
+  uint8_t* u8_out;  // when set: write only the rounded 8-bit resized image [B, S, S, 3] here
 };
 struct CropPlan {
   int col_parts, part_patches, tile_pixels;
@@ -52,6 +53,26 @@ struct CropPlan {
 CropPlan crop_plan(int S, int p, int max_side, int force_parts);
 size_t crop_lds_bytes(const CropArgs& a);
 hipError_t launch_crop_patch(const CropArgs& a, hipStream_t stream);
+
+// ---- finetuning augmentation on the 8-bit resized crop ("3 Aug", "3 Aug+") ------------------------
+struct AugArgs {
+  int32_t B, S, p, G, L, K, D;
+  int32_t visible_bf16;
+  int32_t mode;  // 1: one of grayscale / solarise / blur; 2: the same followed by colour jitter
+  float jitter;  // strength of the colour jitter (factors uniform on 1 +- jitter)
+  uint32_t sample_base;
+  uint64_t key1;
+  float nscale[3];
+  float nbias[3];
+  const uint8_t* u8;  // [B, S, S, 3]
+  const int32_t* ids_restore;
+  const uint8_t* workspace;  // header + CropRec[B] (valid flags)
+  double* partials;          // [B * G] luma sums of the bands, mode 2
+  void* visible;
+  float* target;  // nullable
+};
+size_t three_aug_lds_bytes(int S, int p);
+hipError_t launch_three_aug(const AugArgs& a, hipStream_t stream);
 
 // ---- normalised-pixel loss ---------------------------------------------------------------------
 struct LossArgs {

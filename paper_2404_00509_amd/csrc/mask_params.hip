@@ -41,10 +41,6 @@ __device__ static int64_t round_sqrt(double x) {
   return (int64_t)n;
 }
 
-__device__ static inline double unit53(uint64_t bits) {
-  return (double)(bits >> 11) * (1.0 / 9007199254740992.0);
-}
-
 template <int R>
 __device__ static void bitonic_sort(uint64_t (&v)[R], int lane) {
   constexpr int N = R * kWave;

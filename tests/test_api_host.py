@@ -58,6 +58,7 @@ def _prep_desc(**over):
     d.std = (C.c_float * 3)(*mae.IMAGENET_STD)
     d.seed, d.batch_index, d.sample_base, d.noise_bits, d.out_dtype = 0, 0, 0, 32, 0
     d.max_image_side = 0
+    d.aug_mode, d.jitter = 0, 0.3
     for k, v in over.items():
         if k == "std":
             d.std = (C.c_float * 3)(*v)
@@ -104,11 +105,28 @@ def _call_prep(lib, d, visible=FAKE, mask=FAKE, ids_restore=FAKE, workspace=FAKE
     (dict(out_dtype=7), binding.MAE_ERR_DTYPE),
     (dict(max_image_side=-1), binding.MAE_ERR_RANGE),
     (dict(max_image_side=40000), binding.MAE_ERR_RANGE),
+    (dict(aug_mode=3), binding.MAE_ERR_RANGE),
+    (dict(aug_mode=-1), binding.MAE_ERR_RANGE),
+    (dict(aug_mode=2, jitter=-0.1), binding.MAE_ERR_RANGE),
+    (dict(aug_mode=2, jitter=float("nan")), binding.MAE_ERR_RANGE),
+    (dict(aug_mode=1, out_size=224, patch=14, num_keep=64), binding.MAE_ERR_SHAPE),  # 3 p % 4 != 0
+    (dict(aug_mode=1, out_size=256, patch=16, num_keep=64), binding.MAE_ERR_RANGE),  # band > LDS
 ])
 def test_prep_rejects_bad_descriptors(lib, over, status):
     d = _prep_desc(**over)
     assert _call_prep(lib, d) == status
     assert lib.mae_prep_workspace_bytes(C.byref(d)) == 0
+
+
+def test_prep_workspace_grows_with_the_augmentation(lib):
+    plain = lib.mae_prep_workspace_bytes(C.byref(_prep_desc()))
+    assert plain == 256 + 4 * 32
+    three = lib.mae_prep_workspace_bytes(C.byref(_prep_desc(aug_mode=1)))
+    plus = lib.mae_prep_workspace_bytes(C.byref(_prep_desc(aug_mode=2)))
+    assert three == 512 + 4 * 224 * 224 * 3          # records rounded up to 256, then the bytes
+    assert plus == three + 4 * 14 * 8                 # one double per row of patches
+    d = _prep_desc(aug_mode=2)
+    assert _call_prep(lib, d, ws_bytes=plus - 1) == binding.MAE_ERR_WORKSPACE
 
 
 def test_prep_rejects_bad_buffers(lib):
