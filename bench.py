@@ -6,8 +6,9 @@ gradient), on synthetic images already resident in HBM.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4] [--no-cpu-baseline]
 
-The first consumer of the path's output, mae_patch_embed, is timed by itself after the steps and
-reported under "patch_embed"; it is not part of the step or of `value`.
+The first consumer of the path's output, mae_patch_embed, and the finetuning-mode input pipeline
+("3 Aug", "3 Aug+") are timed by themselves after the steps and reported under "patch_embed" and
+"finetune_prep"; they are not part of the step or of `value`.
 """
 from __future__ import annotations
 
@@ -150,6 +151,53 @@ def time_embed(args, mae, synth, torch, dev, wl, K, E):
     }
 
 
+def time_finetune(args, mae, torch, dev, wl):
+    """mae_prep_batch in finetuning mode (Table 7, last stage: 224 px, crop side ratio 0.28..1,
+    every patch kept, fp32 tokens in `visible`, no `target`) with "3 Aug" and "3 Aug+", timed by
+    itself with events on the launch stream.  Not part of the step above."""
+    import numpy as np
+
+    rows = []
+    res, lo, hi = mae.mae_finetune_stage(1, 3)
+    G = res // wl.patch
+    L = G * G
+    stream = torch.cuda.current_stream()
+    for mode, name in ((mae.MAE_AUG_THREE, "3 Aug"), (mae.MAE_AUG_THREE_PLUS, "3 Aug+")):
+        desc = mae.make_prep_desc(*dev, out_size=res, patch=wl.patch, num_keep=L, scale=(lo, hi),
+                                  seed=0, batch_index=0, aug_mode=mode, jitter=0.3)
+        buf = mae.alloc_prep_buffers(desc, want_target=False)
+
+        def run(i):
+            desc.batch_index = i
+            mae.mae_prep_batch(desc, buf.visible, buf.mask, buf.ids_restore, buf.ids_keep, None,
+                               buf.crop, buf.workspace, stream=stream)
+
+        for i in range(max(args.warmup, 1)):
+            run(i)
+        torch.cuda.synchronize()
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+        for i, e in enumerate(ev):
+            e[0].record(stream)
+            run(args.warmup + i)
+            e[1].record(stream)
+        torch.cuda.synchronize()
+        assert mae.mae_prep_status(buf.workspace) == 0
+        ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+        crop = buf.crop.cpu().numpy().astype(np.int64)
+        crop_bytes = int((crop[:, 2] * crop[:, 3] * 3).sum())
+        u8 = wl.B * res * res * 3
+        # crop read, 8-bit image written once and read once per pass over it, tokens written
+        nbytes = crop_bytes + u8 * (3 if mode == mae.MAE_AUG_THREE_PLUS else 2) \
+            + wl.B * (L * wl.D * 4 + L * 5 + L * 4)
+        rows.append({"augmentation": name, "out_size": res, "avg_ms": round(ms, 4),
+                     "images_per_s": round(wl.B / (ms * 1e-3), 1),
+                     "algorithmic_bytes": nbytes,
+                     "achieved_GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                     "frac": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)})
+        del buf
+    return rows
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -166,6 +214,8 @@ def main() -> int:
     ap.add_argument("--embed", type=int, default=768,
                     help="embedding width E for the separately timed mae_patch_embed launch over "
                          "the batch's visible rows (adds 'patch_embed' to the JSON line); 0 = skip")
+    ap.add_argument("--no-finetune", action="store_true",
+                    help="skip the separately timed finetuning-mode calls ('finetune_prep')")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed region, run one plain device copy of known size "
                          "(grad <- pred) so that a counter run has a reference kernel")
@@ -299,6 +349,9 @@ def main() -> int:
 
     if args.embed > 0:
         out["patch_embed"] = time_embed(args, mae, synth, torch, dev, wl, K, args.embed)
+
+    if not args.no_finetune and wl.patch % 4 == 0:
+        out["finetune_prep"] = time_finetune(args, mae, torch, dev, wl)
 
     if args.scheme:
         out["stages"] = time_scheme(args, mae, synth, torch, dev, wl, bf16)

@@ -117,7 +117,8 @@ typedef struct {
                               side 256" dataset variant).  It sizes the on-chip staging buffer;
                               larger images than hinted stay correct but take a slower path     */
   int32_t aug_mode;        /* mae_aug_mode.  Other than MAE_AUG_SIMPLE needs p % 4 == 0 and
-                              15 p S + 36 S <= 65536 (S = 224 with p = 16 fits; MAE_ERR_RANGE)  */
+                              15 p S + 144 p + 36 S <= 65536 (the blur's working set; S = 224
+                              with p = 16 fits, S = 256 does not: MAE_ERR_RANGE)                */
   float jitter;            /* MAE_AUG_THREE_PLUS: strength in [0, 1], 0.3 in the paper            */
 } mae_prep_desc;
 

@@ -5,17 +5,21 @@
 // resampling kernel wrote (row-major HWC); output is the same `target` / `visible` layout as the
 // pretraining path.
 //
-// One workgroup per (image, row of patches).  The p image rows of the band are first turned into
-// fp32 values after the per-image operation, in LDS:
-//   grayscale / solarise  pointwise on the bytes (integer arithmetic, exact);
-//   blur                  the band plus `radius` rows above and below (clamped at the image
-//                         border) is staged as bytes, the vertical pass writes fp32 rows, and the
-//                         horizontal pass is folded into the consumer below.
-// The consumer walks the band in OUTPUT order, two pixels per lane, so that `target` is written as
-// one contiguous run of G * D floats per workgroup; jitter and normalisation are applied on the
-// way.  The contrast step needs the mean luma of the whole image after the brightness step:
-// with jitter on, a first launch of the same code (kReduce) only accumulates that sum per band in
-// double precision, and the second launch adds the G partial sums of its image in fixed order.
+// Two kernels, both with one workgroup per (image, row of patches); a workgroup leaves at once
+// when its image drew an operation of the other kernel.
+//  * aug_point_kernel: grayscale and solarisation are pointwise, so nothing is staged: a lane takes
+//    the 12 bytes of four neighbouring pixels of a patch row (one aligned load), applies the
+//    operation in integer arithmetic, jitter and normalisation in fp32, and stores 48 contiguous
+//    bytes of `target` (and of `visible` for kept patches).  Lanes walk the band in OUTPUT order,
+//    so a workgroup writes one contiguous run of G * D floats.
+//  * aug_blur_kernel: the band plus `radius` rows above and below (clamped at the image border)
+//    is staged as bytes, the vertical pass writes fp32 rows into LDS with six border pixels
+//    repeated on either side, and the horizontal pass is folded into the same output-order walk:
+//    a lane reads the 16 pixels around its four with aligned 16-byte LDS reads and applies all
+//    13 taps (zero beyond the radius).
+// The contrast step needs the mean luma of the whole image after the brightness step: with jitter
+// on, a first launch of the same kernels (kReduce) only accumulates that sum per band in double
+// precision, and the second launch adds the G partial sums of its image in fixed order.
 #include "mae_device.hpp"
 #include "mae_kernels.hpp"
 
@@ -23,211 +27,282 @@ namespace mae {
 
 constexpr int kAugThreads = 256;
 constexpr int kMaxRadius = 6;  // ceil(3 * 2.0)
+constexpr int kTaps = 2 * kMaxRadius + 1;
 
-typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
+typedef u32x3 u32x3_a4 __attribute__((aligned(4)));
 
 __device__ static inline float clamp255(float v) { return fminf(fmaxf(v, 0.0f), 255.0f); }
 __device__ static inline float luma(float r, float g, float b) {
   return 0.299f * r + 0.587f * g + 0.114f * b;
 }
 
-// Dynamic LDS: [ vals: p x 3S floats | staged bytes: (p + 2 kMaxRadius) x 3S ].
-template <bool kReduce, bool kBf16>
-__global__ __launch_bounds__(kAugThreads) void three_aug_kernel(AugArgs a) {
-  extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
-  __shared__ double wd[2 * kMaxRadius + 1];
-  __shared__ float wf[2 * kMaxRadius + 1];
-  __shared__ double red[kAugThreads / kWave];
-
-  const int S = a.S, p = a.p, G = a.G;
-  const int rv = 3 * S;    // values (= bytes) per image row; a multiple of 4 because 3 p is
-  const int rv4 = rv >> 2;
-  float* vals = reinterpret_cast<float*>(lds);
-  uint32_t* staged = lds + p * rv;
-
+// What every workgroup needs first: its tile, the record of its image, the draws.
+struct BandCtx {
+  int b, gy;
+  bool valid;
+  AugParams ap;
+};
+__device__ static inline BandCtx band_ctx(const AugArgs& a) {
+  BandCtx c;
   const uint32_t tile = xcd_remap(blockIdx.x, gridDim.x);
-  const int b = (int)(tile / (uint32_t)G);
-  const int gy = (int)(tile - (uint32_t)b * (uint32_t)G);
-  const int tid = threadIdx.x;
-  const CropRec rec = reinterpret_cast<const CropRec*>(a.workspace + kWorkspaceHeader)[b];
-  if (!rec.valid) {
-    if (kReduce && tid == 0) a.partials[(int64_t)b * G + gy] = 0.0;
-    return;
-  }
-  const AugParams ap = aug_params(a.key1, a.sample_base + (uint32_t)b, a.jitter);
-  const uint8_t* img = a.u8 + (int64_t)b * S * rv;
-  const int y0 = gy * p;
-  const int radius = ap.radius;
+  c.b = (int)(tile / (uint32_t)a.G);
+  c.gy = (int)(tile - (uint32_t)c.b * (uint32_t)a.G);
+  c.valid = reinterpret_cast<const CropRec*>(a.workspace + kWorkspaceHeader)[c.b].valid != 0;
+  c.ap = aug_params(a.key1, a.sample_base + (uint32_t)c.b, a.jitter);
+  return c;
+}
 
-  if (ap.op == kOpBlur) {
-    // taps exp(-k^2 / (2 sigma^2)) in double precision, summed in index order, scaled to sum 1
-    if (tid <= 2 * radius) {
-      const double k = (double)(tid - radius);
-      wd[tid] = exp(-(k * k) / (2.0 * ap.sigma * ap.sigma));
-    }
-    __syncthreads();
-    if (tid <= 2 * radius) {
-      double sum = 0.0;
-      for (int k = 0; k <= 2 * radius; ++k) sum += wd[k];
-      wf[tid] = (float)(wd[tid] / sum);
-    }
-    // the band and its halo, border rows repeated
-    const int nrows = p + 2 * radius;
-    for (int i = tid; i < nrows * rv4; i += kAugThreads) {
-      const int j = i / rv4, d = i - j * rv4;
-      const int yy = min(max(y0 - radius + j, 0), S - 1);
-      staged[i] = reinterpret_cast<const uint32_t*>(img + (int64_t)yy * rv)[d];
-    }
-    __syncthreads();
-    // vertical pass: four neighbouring values (bytes of one word) per step
-    for (int i = tid; i < p * rv4; i += kAugThreads) {
-      const int y = i / rv4, d = i - y * rv4;
-      float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
-      for (int k = 0; k <= 2 * radius; ++k) {
-        const uint32_t w4 = staged[(y + k) * rv4 + d];
-        const float w = wf[k];
-        acc0 += w * (float)(w4 & 0xFFu);
-        acc1 += w * (float)((w4 >> 8) & 0xFFu);
-        acc2 += w * (float)((w4 >> 16) & 0xFFu);
-        acc3 += w * (float)(w4 >> 24);
-      }
-      reinterpret_cast<f32x4*>(vals)[i] = f32x4{acc0, acc1, acc2, acc3};
-    }
-  } else {
-    for (int i = tid; i < p * S; i += kAugThreads) {
-      const int y = i / S, x = i - y * S;
-      const uint8_t* px = img + (int64_t)(y0 + y) * rv + 3 * x;
-      const int r = px[0], g = px[1], bl = px[2];
-      float* dst = vals + y * rv + 3 * x;
-      if (ap.op == kOpGray) {
-        const float l = (float)((299 * r + 587 * g + 114 * bl + 500) / 1000);
-        dst[0] = dst[1] = dst[2] = l;
-      } else {
-        dst[0] = (float)(r >= 128 ? 255 - r : r);
-        dst[1] = (float)(g >= 128 ? 255 - g : g);
-        dst[2] = (float)(bl >= 128 ? 255 - bl : bl);
-      }
-    }
-  }
-  __syncthreads();
+// Mean luma after the brightness step, from the partial sums of the reduction launch.
+__device__ static inline float image_mean(const AugArgs& a, int b) {
+  double sum = 0.0;
+  for (int g = 0; g < a.G; ++g) sum += a.partials[(int64_t)b * a.G + g];
+  return (float)(sum / ((double)a.S * (double)a.S));
+}
 
-  // mean luma after the brightness step, from the partial sums of the first launch
-  float mean = 0.0f;
-  if (!kReduce && a.mode == 2) {
-    double sum = 0.0;
-    for (int g = 0; g < G; ++g) sum += a.partials[(int64_t)b * G + g];
-    mean = (float)(sum / ((double)S * (double)S));
-  }
+// Colour jitter of one pixel (fp32).  kReduce: only the brightness step, returns its luma.
+template <bool kReduce>
+__device__ static inline float jitter_pixel(const AugParams& ap, float mean, float& r, float& g,
+                                            float& bl) {
+  r = clamp255(r * ap.brightness);
+  g = clamp255(g * ap.brightness);
+  bl = clamp255(bl * ap.brightness);
+  if (kReduce) return luma(r, g, bl);
+  const float cm = (1.0f - ap.contrast) * mean;
+  r = clamp255(ap.contrast * r + cm);
+  g = clamp255(ap.contrast * g + cm);
+  bl = clamp255(ap.contrast * bl + cm);
+  const float sl = (1.0f - ap.saturation) * luma(r, g, bl);
+  r = clamp255(ap.saturation * r + sl);
+  g = clamp255(ap.saturation * g + sl);
+  bl = clamp255(ap.saturation * bl + sl);
+  return 0.0f;
+}
 
-  const bool blur = ap.op == kOpBlur;
-  const int pairs_per_patch = (p * p) >> 1;
-  float lsum = 0.0f;
-  for (int i = tid; i < G * pairs_per_patch; i += kAugThreads) {
-    const int gx = i / pairs_per_patch;
-    const int q = 2 * (i - gx * pairs_per_patch);  // first pixel of the pair inside the patch
-    const int py = q / p, x = gx * p + (q - py * p);
-    const float* row = vals + py * rv;
-    float v[6];
+// Normalise the 12 values of four pixels and store them to `target` and, for a kept patch, to
+// `visible`.  q = index of the first pixel inside the patch (a multiple of 4).
+template <bool kBf16>
+__device__ static inline void store_group(const AugArgs& a, int b, int l, int q, const float* v) {
+  float out[12];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      if (blur) {
-        float r = 0.f, g = 0.f, bl = 0.f;
-        for (int k = 0; k <= 2 * radius; ++k) {
-          const float* t = row + 3 * min(max(x + h + k - radius, 0), S - 1);
-          const float w = wf[k];
-          r += w * t[0];
-          g += w * t[1];
-          bl += w * t[2];
-        }
-        v[3 * h] = r;
-        v[3 * h + 1] = g;
-        v[3 * h + 2] = bl;
-      } else {
-        const float* t = row + 3 * (x + h);
-        v[3 * h] = t[0];
-        v[3 * h + 1] = t[1];
-        v[3 * h + 2] = t[2];
-      }
-      if (a.mode == 2) {
-        float r = clamp255(v[3 * h] * ap.brightness);
-        float g = clamp255(v[3 * h + 1] * ap.brightness);
-        float bl = clamp255(v[3 * h + 2] * ap.brightness);
-        if (kReduce) {
-          lsum += luma(r, g, bl);
-        } else {
-          const float cm = (1.0f - ap.contrast) * mean;
-          r = clamp255(ap.contrast * r + cm);
-          g = clamp255(ap.contrast * g + cm);
-          bl = clamp255(ap.contrast * bl + cm);
-          const float sl = (1.0f - ap.saturation) * luma(r, g, bl);
-          v[3 * h] = clamp255(ap.saturation * r + sl);
-          v[3 * h + 1] = clamp255(ap.saturation * g + sl);
-          v[3 * h + 2] = clamp255(ap.saturation * bl + sl);
-        }
-      }
-    }
-    if (kReduce) continue;
-
-    float out[6];
-#pragma unroll
-    for (int j = 0; j < 6; ++j) {
-      const int c = j % 3;
-      out[j] = v[j] * a.nscale[c] + a.nbias[c];
-    }
-    const int l = gy * G + gx;
-    const int64_t eo = (int64_t)3 * q;  // element offset inside the patch; 6 values, 8-byte aligned
-    if (a.target) {
-      f32x2* dst = reinterpret_cast<f32x2*>(a.target + ((int64_t)b * a.L + l) * a.D + eo);
-      dst[0] = f32x2{out[0], out[1]};
-      dst[1] = f32x2{out[2], out[3]};
-      dst[2] = f32x2{out[4], out[5]};
-    }
-    const int rank = a.ids_restore[(int64_t)b * a.L + l];
-    if (rank < a.K) {
-      const int64_t vo = ((int64_t)b * a.K + rank) * a.D + eo;
-      if (kBf16) {
-        uint32_t* dst = reinterpret_cast<uint32_t*>(static_cast<uint16_t*>(a.visible) + vo);
-        dst[0] = pack_bf16x2(out[0], out[1]);
-        dst[1] = pack_bf16x2(out[2], out[3]);
-        dst[2] = pack_bf16x2(out[4], out[5]);
-      } else {
-        f32x2* dst = reinterpret_cast<f32x2*>(static_cast<float*>(a.visible) + vo);
-        dst[0] = f32x2{out[0], out[1]};
-        dst[1] = f32x2{out[2], out[3]};
-        dst[2] = f32x2{out[4], out[5]};
-      }
-    }
+  for (int j = 0; j < 12; ++j) out[j] = v[j] * a.nscale[j % 3] + a.nbias[j % 3];
+  const int64_t eo = (int64_t)3 * q;  // 48-byte aligned run inside the patch row
+  if (a.target) {
+    f32x4* dst = reinterpret_cast<f32x4*>(a.target + ((int64_t)b * a.L + l) * a.D + eo);
+    dst[0] = f32x4{out[0], out[1], out[2], out[3]};
+    dst[1] = f32x4{out[4], out[5], out[6], out[7]};
+    dst[2] = f32x4{out[8], out[9], out[10], out[11]};
   }
-
-  if (kReduce) {
-    // fixed order: lanes by butterfly, then the wavefronts in index order
-    double s = (double)lsum;
-    for (int off = kWave / 2; off > 0; off >>= 1) s += __shfl_xor(s, off);
-    if ((tid % kWave) == 0) red[tid / kWave] = s;
-    __syncthreads();
-    if (tid == 0) {
-      double t = 0.0;
-      for (int w = 0; w < kAugThreads / kWave; ++w) t += red[w];
-      a.partials[(int64_t)b * G + gy] = t;
+  const int rank = a.ids_restore[(int64_t)b * a.L + l];
+  if (rank < a.K) {
+    const int64_t vo = ((int64_t)b * a.K + rank) * a.D + eo;
+    if (kBf16) {
+      u32x2* dst = reinterpret_cast<u32x2*>(static_cast<uint16_t*>(a.visible) + vo);
+      dst[0] = u32x2{pack_bf16x2(out[0], out[1]), pack_bf16x2(out[2], out[3])};
+      dst[1] = u32x2{pack_bf16x2(out[4], out[5]), pack_bf16x2(out[6], out[7])};
+      dst[2] = u32x2{pack_bf16x2(out[8], out[9]), pack_bf16x2(out[10], out[11])};
+    } else {
+      f32x4* dst = reinterpret_cast<f32x4*>(static_cast<float*>(a.visible) + vo);
+      dst[0] = f32x4{out[0], out[1], out[2], out[3]};
+      dst[1] = f32x4{out[4], out[5], out[6], out[7]};
+      dst[2] = f32x4{out[8], out[9], out[10], out[11]};
     }
   }
 }
 
+// Sum over the workgroup in a fixed order (lanes by butterfly, wavefronts in index order).
+__device__ static inline void store_band_sum(const AugArgs& a, int b, int gy, float lsum,
+                                             double* red) {
+  double s = (double)lsum;
+  for (int off = kWave / 2; off > 0; off >>= 1) s += __shfl_xor(s, off);
+  const int tid = threadIdx.x;
+  if ((tid % kWave) == 0) red[tid / kWave] = s;
+  __syncthreads();
+  if (tid == 0) {
+    double t = 0.0;
+    for (int w = 0; w < kAugThreads / kWave; ++w) t += red[w];
+    a.partials[(int64_t)b * a.G + gy] = t;
+  }
+}
+
+// ---- grayscale and solarisation ------------------------------------------------------------------
+template <bool kReduce, bool kBf16>
+__global__ __launch_bounds__(kAugThreads) void aug_point_kernel(AugArgs a) {
+  __shared__ double red[kAugThreads / kWave];
+  const BandCtx c = band_ctx(a);
+  if (!c.valid || c.ap.op == kOpBlur) return;
+  const int S = a.S, p = a.p, G = a.G;
+  const int b = c.b, gy = c.gy;
+  const int rv = 3 * S;  // bytes per image row; a multiple of 4 because 3 p is
+  const uint8_t* band = a.u8 + ((int64_t)b * S + gy * p) * rv;
+  const float mean = (!kReduce && a.mode == 2) ? image_mean(a, b) : 0.0f;
+  const bool gray = c.ap.op == kOpGray;
+  const int groups_per_patch = (p * p) >> 2;
+  float lsum = 0.0f;
+  for (int i = threadIdx.x; i < G * groups_per_patch; i += kAugThreads) {
+    const int gx = i / groups_per_patch;
+    const int q = 4 * (i - gx * groups_per_patch);  // first of the four pixels inside the patch
+    const int py = q / p, x = gx * p + (q - py * p);
+    const u32x3 w = *reinterpret_cast<const u32x3_a4*>(band + (int64_t)py * rv + 3 * x);
+    int by[12];
+#pragma unroll
+    for (int j = 0; j < 12; ++j) by[j] = (int)((w[j >> 2] >> (8 * (j & 3))) & 0xFFu);
+    float v[12];
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      if (gray) {
+        const int g = (299 * by[3 * h] + 587 * by[3 * h + 1] + 114 * by[3 * h + 2] + 500) / 1000;
+        v[3 * h] = v[3 * h + 1] = v[3 * h + 2] = (float)g;
+      } else {
+#pragma unroll
+        for (int ch = 0; ch < 3; ++ch) {
+          const int t = by[3 * h + ch];
+          v[3 * h + ch] = (float)(t >= 128 ? 255 - t : t);
+        }
+      }
+      if (a.mode == 2)
+        lsum += jitter_pixel<kReduce>(c.ap, mean, v[3 * h], v[3 * h + 1], v[3 * h + 2]);
+    }
+    if (!kReduce) store_group<kBf16>(a, b, gy * G + gx, q, v);
+  }
+  if (kReduce) store_band_sum(a, b, gy, lsum, red);
+}
+
+// ---- Gaussian blur ---------------------------------------------------------------------------------
+// Dynamic LDS: [ vals: p rows of 3 (S + 12) floats | staged bytes: (p + 12) rows of 3 S ].
+template <bool kReduce, bool kBf16>
+__global__ __launch_bounds__(kAugThreads) void aug_blur_kernel(AugArgs a) {
+  extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+  __shared__ double wd[kTaps];
+  __shared__ float wf[kTaps];  // tap k - 6 at index k; zero beyond the radius
+  __shared__ double red[kAugThreads / kWave];
+  const BandCtx c = band_ctx(a);
+  if (!c.valid || c.ap.op != kOpBlur) return;
+  const int S = a.S, p = a.p, G = a.G;
+  const int b = c.b, gy = c.gy, tid = threadIdx.x;
+  const int rv = 3 * S, rv4 = rv >> 2;
+  const int pv = 3 * (S + 2 * kMaxRadius);  // floats per padded row; 16-byte multiple
+  float* vals = reinterpret_cast<float*>(lds);
+  uint32_t* staged = lds + p * pv;
+  const uint8_t* img = a.u8 + (int64_t)b * S * rv;
+  const int y0 = gy * p;
+  const int radius = c.ap.radius;
+
+  // taps exp(-k^2 / (2 sigma^2)) in double precision, summed in index order, scaled to sum 1
+  if (tid < kTaps) {
+    const double k = (double)(tid - kMaxRadius);
+    wd[tid] = abs(tid - kMaxRadius) <= radius ? exp(-(k * k) / (2.0 * c.ap.sigma * c.ap.sigma))
+                                               : 0.0;
+  }
+  // the band and its halo, border rows repeated
+  const int nrows = p + 2 * radius;
+  for (int i = tid; i < nrows * rv4; i += kAugThreads) {
+    const int j = i / rv4, d = i - j * rv4;
+    const int yy = min(max(y0 - radius + j, 0), S - 1);
+    staged[i] = reinterpret_cast<const uint32_t*>(img + (int64_t)yy * rv)[d];
+  }
+  __syncthreads();
+  if (tid < kTaps) {
+    double sum = 0.0;
+    for (int k = kMaxRadius - radius; k <= kMaxRadius + radius; ++k) sum += wd[k];
+    wf[tid] = (float)(wd[tid] / sum);
+  }
+  __syncthreads();
+  // vertical pass: four neighbouring values (the bytes of one word) per step
+  for (int i = tid; i < p * rv4; i += kAugThreads) {
+    const int y = i / rv4, d = i - y * rv4;
+    float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
+    for (int k = 0; k <= 2 * radius; ++k) {
+      const uint32_t w4 = staged[(y + k) * rv4 + d];
+      const float w = wf[kMaxRadius - radius + k];
+      acc0 += w * (float)(w4 & 0xFFu);
+      acc1 += w * (float)((w4 >> 8) & 0xFFu);
+      acc2 += w * (float)((w4 >> 16) & 0xFFu);
+      acc3 += w * (float)(w4 >> 24);
+    }
+    float* dst = vals + y * pv + 3 * kMaxRadius + 4 * d;  // 4-byte aligned only
+    dst[0] = acc0;
+    dst[1] = acc1;
+    dst[2] = acc2;
+    dst[3] = acc3;
+  }
+  __syncthreads();
+  // six border pixels repeated on either side of every row
+  for (int i = tid; i < p * 2 * kMaxRadius * 3; i += kAugThreads) {
+    const int y = i / (2 * kMaxRadius * 3);
+    const int r = i - y * (2 * kMaxRadius * 3);
+    const int side = r / (kMaxRadius * 3), t = r - side * (kMaxRadius * 3);
+    const int ch = t % 3;
+    float* row = vals + y * pv;
+    if (side == 0) {
+      row[t] = row[3 * kMaxRadius + ch];
+    } else {
+      row[3 * (kMaxRadius + S) + t] = row[3 * (kMaxRadius + S - 1) + ch];
+    }
+  }
+  __syncthreads();
+
+  const float mean = (!kReduce && a.mode == 2) ? image_mean(a, b) : 0.0f;
+  float wt[kTaps];
+#pragma unroll
+  for (int k = 0; k < kTaps; ++k) wt[k] = wf[k];
+  const int groups_per_patch = (p * p) >> 2;
+  float lsum = 0.0f;
+  for (int i = tid; i < G * groups_per_patch; i += kAugThreads) {
+    const int gx = i / groups_per_patch;
+    const int q = 4 * (i - gx * groups_per_patch);
+    const int py = q / p, x = gx * p + (q - py * p);
+    // padded pixels x .. x + 15 are image pixels x - 6 .. x + 9: 48 floats, 16-byte aligned
+    const f32x4* src = reinterpret_cast<const f32x4*>(vals + py * pv + 3 * x);
+    float n[48];
+#pragma unroll
+    for (int j = 0; j < 12; ++j) {
+      const f32x4 t = src[j];
+      n[4 * j] = t.x;
+      n[4 * j + 1] = t.y;
+      n[4 * j + 2] = t.z;
+      n[4 * j + 3] = t.w;
+    }
+    float v[12];
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      float r = 0.f, g = 0.f, bl = 0.f;
+#pragma unroll
+      for (int k = 0; k < kTaps; ++k) {
+        r += wt[k] * n[3 * (h + k)];
+        g += wt[k] * n[3 * (h + k) + 1];
+        bl += wt[k] * n[3 * (h + k) + 2];
+      }
+      v[3 * h] = r;
+      v[3 * h + 1] = g;
+      v[3 * h + 2] = bl;
+      if (a.mode == 2)
+        lsum += jitter_pixel<kReduce>(c.ap, mean, v[3 * h], v[3 * h + 1], v[3 * h + 2]);
+    }
+    if (!kReduce) store_group<kBf16>(a, b, gy * G + gx, q, v);
+  }
+  if (kReduce) store_band_sum(a, b, gy, lsum, red);
+}
+
 size_t three_aug_lds_bytes(int S, int p) {
-  return (size_t)p * 3 * S * 4 + (size_t)(p + 2 * kMaxRadius) * 3 * S;
+  return (size_t)p * 3 * (S + 2 * kMaxRadius) * 4 + (size_t)(p + 2 * kMaxRadius) * 3 * S;
 }
 
 hipError_t launch_three_aug(const AugArgs& a, hipStream_t stream) {
   dim3 grid((uint32_t)a.B * (uint32_t)a.G), block(kAugThreads);
   const size_t lds = three_aug_lds_bytes(a.S, a.p);
   if (a.mode == 2) {
-    hipLaunchKernelGGL((three_aug_kernel<true, false>), grid, block, lds, stream, a);
+    hipLaunchKernelGGL((aug_point_kernel<true, false>), grid, block, 0, stream, a);
+    hipLaunchKernelGGL((aug_blur_kernel<true, false>), grid, block, lds, stream, a);
   }
   if (a.visible_bf16) {
-    hipLaunchKernelGGL((three_aug_kernel<false, true>), grid, block, lds, stream, a);
+    hipLaunchKernelGGL((aug_point_kernel<false, true>), grid, block, 0, stream, a);
+    hipLaunchKernelGGL((aug_blur_kernel<false, true>), grid, block, lds, stream, a);
   } else {
-    hipLaunchKernelGGL((three_aug_kernel<false, false>), grid, block, lds, stream, a);
+    hipLaunchKernelGGL((aug_point_kernel<false, false>), grid, block, 0, stream, a);
+    hipLaunchKernelGGL((aug_blur_kernel<false, false>), grid, block, lds, stream, a);
   }
   return hipGetLastError();
 }
