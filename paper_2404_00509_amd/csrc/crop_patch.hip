@@ -119,9 +119,10 @@ __device__ static inline u32x4 to_pixels(u32x4 d, uint32_t s) {
 // this part (patches gx0 .. gx0 + npatch - 1); cw is the number of source columns from the
 // part's first tapped column to the crop's right edge.
 // kU8: instead of the normalised values, the bilinear value rounded to the nearest byte (ties
-// upwards, exact integer arithmetic on the numerator over (2 S)^2) goes to an 8-bit image in
-// row-major HWC order (a.u8_out) for the finetuning augmentation; the tap tables then hold the
-// integer remainders instead of float weights, and patch rows hold whole groups (3 p % 4 == 0).
+// upwards, exact integer arithmetic on the numerator over (2 S)^2) goes to an 8-bit copy of the
+// patch rows (a.u8_out, [B, L, D] bytes, the layout of `target`) for the finetuning augmentation;
+// the tap tables then hold the integer remainders instead of float weights.  All factors stay
+// below 2^24, so the products are 24-bit multiplies.
 template <bool kLds, bool kBf16, bool kU8>
 __device__ static void produce_patches(const CropArgs& a, const uint32_t* tile, const u32x2* xtab,
                                        const u32x4* ytab, const uint8_t* base, int b, int gy,
@@ -189,9 +190,11 @@ __device__ static void produce_patches(const CropArgs& a, const uint32_t* tile, 
   const uint32_t ry = (J) == 0 ? ryA : ((J) == 3 ? ryB : ((J) < nA ? ryA : ryB));  \
   const uint32_t a00 = (P00 >> (8 * (J))) & 0xFFu, a01 = (P01 >> (8 * (J))) & 0xFFu; \
   const uint32_t a10 = (P10 >> (8 * (J))) & 0xFFu, a11 = (P11 >> (8 * (J))) & 0xFFu; \
-  const uint32_t num = (den - ry) * ((den - rx) * a00 + rx * a01) +                \
-                       ry * ((den - rx) * a10 + rx * a11);                         \
-  const uint32_t x = 2u * num + den * den; /* floor(x / (2 den^2)) = rounded value */ \
+  /* top = den a00 + rx (a01 - a00), bot likewise; num = den top + ry (bot - top) */ \
+  const int top = __mul24((int)den, (int)a00) + __mul24((int)rx, (int)a01 - (int)a00); \
+  const int bot = __mul24((int)den, (int)a10) + __mul24((int)rx, (int)a11 - (int)a10); \
+  const int num = __mul24((int)den, top) + __mul24((int)ry, bot - top);            \
+  const uint32_t x = 2u * (uint32_t)num + den * den; /* floor(x / (2 den^2)) = rounded value */ \
   int q = (int)((float)x * inv_dd2);                                               \
   const int r = (int)x - q * (int)dd2;                                             \
   q += r < 0 ? -1 : (r >= (int)dd2 ? 1 : 0);                                       \
@@ -199,12 +202,7 @@ __device__ static void produce_patches(const CropArgs& a, const uint32_t* tile, 
 }
       MAE_ROUND(0) MAE_ROUND(1) MAE_ROUND(2) MAE_ROUND(3)
 #undef MAE_ROUND
-      if (active) {
-        const int row_in_patch = e / (3 * p);
-        const int64_t pos = (((int64_t)b * a.S + gy * p + row_in_patch) * a.S +
-                             (int64_t)(gx0 + gx) * p) * 3 + (e - row_in_patch * 3 * p);
-        *reinterpret_cast<uint32_t*>(a.u8_out + pos) = word;
-      }
+      if (active) *reinterpret_cast<uint32_t*>(a.u8_out + ((int64_t)b * a.L + l) * D + e) = word;
       continue;
     }
 

@@ -2,19 +2,20 @@
 // Augmentation", Sec. 5.2 Table 7): per image one of grayscale / solarisation / Gaussian blur,
 // optionally colour jitter (brightness, contrast, saturation), then mean/std normalisation, the
 // ViT patch split and the gather of the kept patches.  Input is the 8-bit resized crop that the
-// resampling kernel wrote (row-major HWC); output is the same `target` / `visible` layout as the
-// pretraining path.
+// resampling kernel wrote, already in patch order ([B, L, D] bytes, the layout of `target`);
+// output is the same `target` / `visible` layout as the pretraining path.
 //
 // Two kernels, both with one workgroup per (image, row of patches); a workgroup leaves at once
 // when its image drew an operation of the other kernel.
-//  * aug_point_kernel: grayscale and solarisation are pointwise, so nothing is staged: a lane takes
-//    the 12 bytes of four neighbouring pixels of a patch row (one aligned load), applies the
-//    operation in integer arithmetic, jitter and normalisation in fp32, and stores 48 contiguous
-//    bytes of `target` (and of `visible` for kept patches).  Lanes walk the band in OUTPUT order,
-//    so a workgroup writes one contiguous run of G * D floats.
-//  * aug_blur_kernel: the band plus `radius` rows above and below (clamped at the image border)
-//    is staged as bytes, the vertical pass writes fp32 rows into LDS with six border pixels
-//    repeated on either side, and the horizontal pass is folded into the same output-order walk:
+//  * aug_point_kernel: grayscale and solarisation are pointwise, so nothing is staged and the band
+//    is one linear stream: a lane takes the 12 bytes of four neighbouring pixels of a patch row
+//    (one aligned load), applies the operation in integer arithmetic, jitter and normalisation
+//    in fp32, and stores the 48 bytes at the same position of `target` (and of `visible` for
+//    kept patches).
+//  * aug_blur_kernel: the image rows of the band plus `radius` rows above and below (clamped at
+//    the image border) are gathered from the patch rows and staged as bytes, the vertical pass
+//    writes fp32 rows into LDS with six border pixels repeated on either side, and the
+//    horizontal pass is folded into the walk over the band in output order:
 //    a lane reads the 16 pixels around its four with aligned 16-byte LDS reads and applies all
 //    13 taps (zero beyond the radius).
 // The contrast step needs the mean luma of the whole image after the brightness step: with jitter
@@ -25,10 +26,13 @@
 
 namespace mae {
 
-constexpr int kAugThreads = 256;
+constexpr int kAugThreads = 256;    // pointwise kernel
+constexpr int kBlurThreads = 1024;  // blur kernel: its LDS allows two workgroups per compute unit,
+                                    // so the wavefronts that hide latency have to come from its size
 constexpr int kMaxRadius = 6;  // ceil(3 * 2.0)
 constexpr int kTaps = 2 * kMaxRadius + 1;
 
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
@@ -38,6 +42,9 @@ __device__ static inline float clamp255(float v) { return fminf(fmaxf(v, 0.0f), 
 __device__ static inline float luma(float r, float g, float b) {
   return 0.299f * r + 0.587f * g + 0.114f * b;
 }
+
+// floor(n / d) for 0 <= n < 2^22 and small d, from the float reciprocal (inv = 1 / d)
+__device__ static inline int fast_div(int n, float inv) { return (int)(((float)n + 0.5f) * inv); }
 
 // What every workgroup needs first: its tile, the record of its image, the draws.
 struct BandCtx {
@@ -112,7 +119,59 @@ __device__ static inline void store_group(const AugArgs& a, int b, int l, int q,
   }
 }
 
+// The same for a whole wavefront whose lanes hold consecutive groups (first group `g0`, a multiple
+// of 64): the 64 x 12 values go through a wavefront-private strip of LDS so that every store
+// instruction writes 1 KiB of contiguous memory instead of 16 bytes out of every 48.
+template <bool kBf16>
+__device__ static inline void store_groups_wave(const AugArgs& a, int b, int gy, int g0,
+                                                int groups_per_patch, float inv_gpp, int ngroups,
+                                                float* strip, const float* v, bool have) {
+  const int lane = threadIdx.x % kWave;
+  f32x4* mine = reinterpret_cast<f32x4*>(strip + 12 * lane);
+  f32x4 o[3];
+#pragma unroll
+  for (int j = 0; j < 3; ++j) {
+    float t[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int idx = 4 * j + e;
+      t[e] = v[idx] * a.nscale[idx % 3] + a.nbias[idx % 3];
+    }
+    o[j] = f32x4{t[0], t[1], t[2], t[3]};
+  }
+  __builtin_amdgcn_wave_barrier();
+  if (have) {
+    mine[0] = o[0];
+    mine[1] = o[1];
+    mine[2] = o[2];
+  }
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll
+  for (int j = 0; j < 3; ++j) {
+    const int piece = j * kWave + lane;      // 16-byte piece of the strip
+    const int g = g0 + fast_div(piece, 1.0f / 3.0f);  // the group it belongs to
+    if (g >= ngroups) continue;
+    const f32x4 t = reinterpret_cast<const f32x4*>(strip)[piece];
+    const int gx = fast_div(g, inv_gpp);
+    const int l = gy * a.G + gx;
+    const int64_t eo = 12 * (int64_t)(g - gx * groups_per_patch) + 4 * (piece - 3 * (g - g0));
+    if (a.target)
+      *reinterpret_cast<f32x4*>(a.target + ((int64_t)b * a.L + l) * a.D + eo) = t;
+    const int rank = a.ids_restore[(int64_t)b * a.L + l];
+    if (rank < a.K) {
+      const int64_t vo = ((int64_t)b * a.K + rank) * a.D + eo;
+      if (kBf16) {
+        *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(a.visible) + vo) =
+            u32x2{pack_bf16x2(t.x, t.y), pack_bf16x2(t.z, t.w)};
+      } else {
+        *reinterpret_cast<f32x4*>(static_cast<float*>(a.visible) + vo) = t;
+      }
+    }
+  }
+}
+
 // Sum over the workgroup in a fixed order (lanes by butterfly, wavefronts in index order).
+template <int kThreads>
 __device__ static inline void store_band_sum(const AugArgs& a, int b, int gy, float lsum,
                                              double* red) {
   double s = (double)lsum;
@@ -122,7 +181,7 @@ __device__ static inline void store_band_sum(const AugArgs& a, int b, int gy, fl
   __syncthreads();
   if (tid == 0) {
     double t = 0.0;
-    for (int w = 0; w < kAugThreads / kWave; ++w) t += red[w];
+    for (int w = 0; w < kThreads / kWave; ++w) t += red[w];
     a.partials[(int64_t)b * a.G + gy] = t;
   }
 }
@@ -131,21 +190,25 @@ __device__ static inline void store_band_sum(const AugArgs& a, int b, int gy, fl
 template <bool kReduce, bool kBf16>
 __global__ __launch_bounds__(kAugThreads) void aug_point_kernel(AugArgs a) {
   __shared__ double red[kAugThreads / kWave];
+  __shared__ __attribute__((aligned(16))) float strips[kAugThreads * 12];
   const BandCtx c = band_ctx(a);
   if (!c.valid || c.ap.op == kOpBlur) return;
-  const int S = a.S, p = a.p, G = a.G;
+  const int p = a.p, G = a.G;
   const int b = c.b, gy = c.gy;
-  const int rv = 3 * S;  // bytes per image row; a multiple of 4 because 3 p is
-  const uint8_t* band = a.u8 + ((int64_t)b * S + gy * p) * rv;
+  const uint8_t* band = a.u8 + ((int64_t)b * a.L + gy * G) * a.D;  // G * D bytes, patch order
   const float mean = (!kReduce && a.mode == 2) ? image_mean(a, b) : 0.0f;
   const bool gray = c.ap.op == kOpGray;
   const int groups_per_patch = (p * p) >> 2;
+  const float inv_gpp = 1.0f / (float)groups_per_patch;
   float lsum = 0.0f;
-  for (int i = threadIdx.x; i < G * groups_per_patch; i += kAugThreads) {
-    const int gx = i / groups_per_patch;
-    const int q = 4 * (i - gx * groups_per_patch);  // first of the four pixels inside the patch
-    const int py = q / p, x = gx * p + (q - py * p);
-    const u32x3 w = *reinterpret_cast<const u32x3_a4*>(band + (int64_t)py * rv + 3 * x);
+  const int ngroups = G * groups_per_patch;
+  float* strip = strips + (threadIdx.x / kWave) * (kWave * 12);
+  // whole wavefronts stay in the loop (the stores are a wavefront's joint work)
+  for (int i0 = (threadIdx.x / kWave) * kWave; i0 < ngroups; i0 += kAugThreads) {
+    const int i = i0 + threadIdx.x % kWave;
+    const bool have = i < ngroups;
+    const u32x3 w = have ? *reinterpret_cast<const u32x3_a4*>(band + 12 * (int64_t)i)
+                         : u32x3{0u, 0u, 0u};
     int by[12];
 #pragma unroll
     for (int j = 0; j < 12; ++j) by[j] = (int)((w[j >> 2] >> (8 * (j & 3))) & 0xFFu);
@@ -162,22 +225,25 @@ __global__ __launch_bounds__(kAugThreads) void aug_point_kernel(AugArgs a) {
           v[3 * h + ch] = (float)(t >= 128 ? 255 - t : t);
         }
       }
-      if (a.mode == 2)
-        lsum += jitter_pixel<kReduce>(c.ap, mean, v[3 * h], v[3 * h + 1], v[3 * h + 2]);
+      if (a.mode == 2) {
+        const float lum = jitter_pixel<kReduce>(c.ap, mean, v[3 * h], v[3 * h + 1], v[3 * h + 2]);
+        lsum += have ? lum : 0.0f;
+      }
     }
-    if (!kReduce) store_group<kBf16>(a, b, gy * G + gx, q, v);
+    if (!kReduce)
+      store_groups_wave<kBf16>(a, b, gy, i0, groups_per_patch, inv_gpp, ngroups, strip, v, have);
   }
-  if (kReduce) store_band_sum(a, b, gy, lsum, red);
+  if (kReduce) store_band_sum<kAugThreads>(a, b, gy, lsum, red);
 }
 
 // ---- Gaussian blur ---------------------------------------------------------------------------------
 // Dynamic LDS: [ vals: p rows of 3 (S + 12) floats | staged bytes: (p + 12) rows of 3 S ].
 template <bool kReduce, bool kBf16>
-__global__ __launch_bounds__(kAugThreads) void aug_blur_kernel(AugArgs a) {
+__global__ __launch_bounds__(kBlurThreads) void aug_blur_kernel(AugArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
   __shared__ double wd[kTaps];
   __shared__ float wf[kTaps];  // tap k - 6 at index k; zero beyond the radius
-  __shared__ double red[kAugThreads / kWave];
+  __shared__ double red[kBlurThreads / kWave];
   const BandCtx c = band_ctx(a);
   if (!c.valid || c.ap.op != kOpBlur) return;
   const int S = a.S, p = a.p, G = a.G;
@@ -186,8 +252,11 @@ __global__ __launch_bounds__(kAugThreads) void aug_blur_kernel(AugArgs a) {
   const int pv = 3 * (S + 2 * kMaxRadius);  // floats per padded row; 16-byte multiple
   float* vals = reinterpret_cast<float*>(lds);
   uint32_t* staged = lds + p * pv;
-  const uint8_t* img = a.u8 + (int64_t)b * S * rv;
+  const uint8_t* img = a.u8 + (int64_t)b * a.L * a.D;  // patch order
   const int y0 = gy * p;
+  const int lane = tid % kWave, wave = tid / kWave;
+  const int prow4 = (3 * p) >> 2;  // words per patch row
+  const float inv_prow4 = 1.0f / (float)prow4, inv_p = 1.0f / (float)p;
   const int radius = c.ap.radius;
 
   // taps exp(-k^2 / (2 sigma^2)) in double precision, summed in index order, scaled to sum 1
@@ -198,10 +267,15 @@ __global__ __launch_bounds__(kAugThreads) void aug_blur_kernel(AugArgs a) {
   }
   // the band and its halo, border rows repeated
   const int nrows = p + 2 * radius;
-  for (int i = tid; i < nrows * rv4; i += kAugThreads) {
-    const int j = i / rv4, d = i - j * rv4;
+  for (int j = wave; j < nrows; j += kBlurThreads / kWave) {
     const int yy = min(max(y0 - radius + j, 0), S - 1);
-    staged[i] = reinterpret_cast<const uint32_t*>(img + (int64_t)yy * rv)[d];
+    const int gyy = fast_div(yy, inv_p), pyy = yy - gyy * p;
+    const uint8_t* row = img + (int64_t)gyy * G * a.D + pyy * 3 * p;  // patch 0 of that grid row
+    for (int d = lane; d < rv4; d += kWave) {
+      const int gx = fast_div(d, inv_prow4);
+      staged[j * rv4 + d] =
+          reinterpret_cast<const uint32_t*>(row + (int64_t)gx * a.D)[d - gx * prow4];
+    }
   }
   __syncthreads();
   if (tid < kTaps) {
@@ -211,26 +285,26 @@ __global__ __launch_bounds__(kAugThreads) void aug_blur_kernel(AugArgs a) {
   }
   __syncthreads();
   // vertical pass: four neighbouring values (the bytes of one word) per step
-  for (int i = tid; i < p * rv4; i += kAugThreads) {
-    const int y = i / rv4, d = i - y * rv4;
-    float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
-    for (int k = 0; k <= 2 * radius; ++k) {
-      const uint32_t w4 = staged[(y + k) * rv4 + d];
-      const float w = wf[kMaxRadius - radius + k];
-      acc0 += w * (float)(w4 & 0xFFu);
-      acc1 += w * (float)((w4 >> 8) & 0xFFu);
-      acc2 += w * (float)((w4 >> 16) & 0xFFu);
-      acc3 += w * (float)(w4 >> 24);
+  for (int y = wave; y < p; y += kBlurThreads / kWave) {
+    for (int d = lane; d < rv4; d += kWave) {
+      float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
+      for (int k = 0; k <= 2 * radius; ++k) {
+        const uint32_t w4 = staged[(y + k) * rv4 + d];
+        const float w = wf[kMaxRadius - radius + k];
+        acc0 += w * (float)(w4 & 0xFFu);
+        acc1 += w * (float)((w4 >> 8) & 0xFFu);
+        acc2 += w * (float)((w4 >> 16) & 0xFFu);
+        acc3 += w * (float)(w4 >> 24);
+      }
+      // 18 + 4 d floats into the row: 8-byte aligned
+      f32x2* dst = reinterpret_cast<f32x2*>(vals + y * pv + 3 * kMaxRadius + 4 * d);
+      dst[0] = f32x2{acc0, acc1};
+      dst[1] = f32x2{acc2, acc3};
     }
-    float* dst = vals + y * pv + 3 * kMaxRadius + 4 * d;  // 4-byte aligned only
-    dst[0] = acc0;
-    dst[1] = acc1;
-    dst[2] = acc2;
-    dst[3] = acc3;
   }
   __syncthreads();
   // six border pixels repeated on either side of every row
-  for (int i = tid; i < p * 2 * kMaxRadius * 3; i += kAugThreads) {
+  for (int i = tid; i < p * 2 * kMaxRadius * 3; i += kBlurThreads) {
     const int y = i / (2 * kMaxRadius * 3);
     const int r = i - y * (2 * kMaxRadius * 3);
     const int side = r / (kMaxRadius * 3), t = r - side * (kMaxRadius * 3);
@@ -249,11 +323,12 @@ __global__ __launch_bounds__(kAugThreads) void aug_blur_kernel(AugArgs a) {
 #pragma unroll
   for (int k = 0; k < kTaps; ++k) wt[k] = wf[k];
   const int groups_per_patch = (p * p) >> 2;
+  const float inv_gpp = 1.0f / (float)groups_per_patch;
   float lsum = 0.0f;
-  for (int i = tid; i < G * groups_per_patch; i += kAugThreads) {
-    const int gx = i / groups_per_patch;
+  for (int i = tid; i < G * groups_per_patch; i += kBlurThreads) {
+    const int gx = fast_div(i, inv_gpp);
     const int q = 4 * (i - gx * groups_per_patch);
-    const int py = q / p, x = gx * p + (q - py * p);
+    const int py = fast_div(q, inv_p), x = gx * p + (q - py * p);
     // padded pixels x .. x + 15 are image pixels x - 6 .. x + 9: 48 floats, 16-byte aligned
     const f32x4* src = reinterpret_cast<const f32x4*>(vals + py * pv + 3 * x);
     float n[48];
@@ -283,7 +358,7 @@ __global__ __launch_bounds__(kAugThreads) void aug_blur_kernel(AugArgs a) {
     }
     if (!kReduce) store_group<kBf16>(a, b, gy * G + gx, q, v);
   }
-  if (kReduce) store_band_sum(a, b, gy, lsum, red);
+  if (kReduce) store_band_sum<kBlurThreads>(a, b, gy, lsum, red);
 }
 
 size_t three_aug_lds_bytes(int S, int p) {
@@ -291,18 +366,18 @@ size_t three_aug_lds_bytes(int S, int p) {
 }
 
 hipError_t launch_three_aug(const AugArgs& a, hipStream_t stream) {
-  dim3 grid((uint32_t)a.B * (uint32_t)a.G), block(kAugThreads);
+  dim3 grid((uint32_t)a.B * (uint32_t)a.G), block(kAugThreads), bblock(kBlurThreads);
   const size_t lds = three_aug_lds_bytes(a.S, a.p);
   if (a.mode == 2) {
     hipLaunchKernelGGL((aug_point_kernel<true, false>), grid, block, 0, stream, a);
-    hipLaunchKernelGGL((aug_blur_kernel<true, false>), grid, block, lds, stream, a);
+    hipLaunchKernelGGL((aug_blur_kernel<true, false>), grid, bblock, lds, stream, a);
   }
   if (a.visible_bf16) {
     hipLaunchKernelGGL((aug_point_kernel<false, true>), grid, block, 0, stream, a);
-    hipLaunchKernelGGL((aug_blur_kernel<false, true>), grid, block, lds, stream, a);
+    hipLaunchKernelGGL((aug_blur_kernel<false, true>), grid, bblock, lds, stream, a);
   } else {
     hipLaunchKernelGGL((aug_point_kernel<false, false>), grid, block, 0, stream, a);
-    hipLaunchKernelGGL((aug_blur_kernel<false, false>), grid, block, lds, stream, a);
+    hipLaunchKernelGGL((aug_blur_kernel<false, false>), grid, bblock, lds, stream, a);
   }
   return hipGetLastError();
 }
