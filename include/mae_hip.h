@@ -116,9 +116,8 @@ typedef struct {
   int32_t max_image_side;  /* tuning hint: largest H or W in the batch, 0 = 256 (the "maximum
                               side 256" dataset variant).  It sizes the on-chip staging buffer;
                               larger images than hinted stay correct but take a slower path     */
-  int32_t aug_mode;        /* mae_aug_mode.  Other than MAE_AUG_SIMPLE needs p % 4 == 0 and
-                              15 p S + 144 p + 36 S <= 65536 (the blur's working set; S = 224
-                              with p = 16 fits, S = 256 does not: MAE_ERR_RANGE)                */
+  int32_t aug_mode;        /* mae_aug_mode.  Other than MAE_AUG_SIMPLE needs p % 4 == 0
+                              (MAE_ERR_SHAPE otherwise)                                         */
   float jitter;            /* MAE_AUG_THREE_PLUS: strength in [0, 1], 0.3 in the paper            */
 } mae_prep_desc;
 

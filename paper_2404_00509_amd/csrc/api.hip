@@ -51,9 +51,8 @@ int validate_prep(const mae_prep_desc* d, PrepShape* shape) {
     return MAE_ERR_RANGE;
   if (d->aug_mode != MAE_AUG_SIMPLE) {
     if (!(d->jitter >= 0.0f) || !(d->jitter <= 1.0f)) return MAE_ERR_RANGE;
-    // whole 16-byte groups per patch row, and a band of p rows (+ blur halo) has to fit the LDS
+    // four-pixel groups (12 bytes) must not straddle rows of a patch
     if (d->patch % 4 != 0) return MAE_ERR_SHAPE;
-    if (mae::three_aug_lds_bytes(d->out_size, d->patch) > 64 * 1024) return MAE_ERR_RANGE;
   }
   if (shape) {
     shape->G = (int32_t)G;
@@ -123,8 +122,9 @@ int32_t mae_num_keep(int32_t L, double mask_ratio) {
 }
 
 namespace {
-// Workspace: header | CropRec[B] | (augmentation) 8-bit resized crops [B,S,S,3] | (jitter) one
-// double per (image, row of patches); every part starts on a 256-byte boundary.
+// Workspace: header | CropRec[B] | (augmentation) 8-bit resized crops, S * S * 3 bytes each |
+// (jitter) one double per (image, row of patches, column part of the blur kernel); every part
+// starts on a 256-byte boundary.
 struct PrepWorkspace {
   size_t u8_offset, partials_offset, total;
 };
@@ -138,7 +138,8 @@ PrepWorkspace prep_workspace(const mae_prep_desc* d) {
     w.partials_offset = up(w.u8_offset + (size_t)d->B * d->out_size * d->out_size * 3);
     w.total = w.partials_offset;
     if (d->aug_mode == MAE_AUG_THREE_PLUS)
-      w.total += (size_t)d->B * (d->out_size / d->patch) * sizeof(double);
+      w.total += (size_t)d->B * (d->out_size / d->patch) *
+                 mae::three_aug_plan(d->out_size, d->patch).parts * sizeof(double);
   }
   return w;
 }
@@ -242,6 +243,9 @@ int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t
   aa.jitter = d->jitter;
   aa.sample_base = d->sample_base;
   aa.key1 = pa.key1;
+  const mae::AugPlan aplan = mae::three_aug_plan(d->out_size, d->patch);
+  aa.blur_parts = aplan.parts;
+  aa.blur_part_patches = aplan.part_patches;
   for (int c = 0; c < 3; ++c) {
     aa.nscale[c] = ca.nscale[c];
     aa.nbias[c] = ca.nbias[c];

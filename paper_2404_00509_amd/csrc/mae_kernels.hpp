@@ -45,7 +45,7 @@ struct CropArgs {
   const uint8_t* workspace;
   void* visible;
   float* target;    // nullable
-  uint8_t* u8_out;  // when set: write only the rounded 8-bit resized image [B, S, S, 3] here
+  uint8_t* u8_out;  // when set: write only the rounded 8-bit patch rows [B, L, D] here
 };
 struct CropPlan {
   int col_parts, part_patches, tile_pixels;
@@ -64,14 +64,20 @@ struct AugArgs {
   uint64_t key1;
   float nscale[3];
   float nbias[3];
-  const uint8_t* u8;  // [B, S, S, 3]
+  int32_t blur_parts;         // column parts a row of patches is split into by the blur kernel
+  int32_t blur_part_patches;  // patches per part (upper bound)
+  const uint8_t* u8;          // [B, L, D] bytes: the rounded resized crop in patch order
   const int32_t* ids_restore;
   const uint8_t* workspace;  // header + CropRec[B] (valid flags)
-  double* partials;          // [B * G] luma sums of the bands, mode 2
+  double* partials;          // [B * G * blur_parts] luma sums, mode 2
   void* visible;
   float* target;  // nullable
 };
-size_t three_aug_lds_bytes(int S, int p);
+struct AugPlan {
+  int parts, part_patches;
+  size_t lds_bytes;
+};
+AugPlan three_aug_plan(int S, int p);
 hipError_t launch_three_aug(const AugArgs& a, hipStream_t stream);
 
 // ---- normalised-pixel loss ---------------------------------------------------------------------

@@ -12,12 +12,11 @@
 //    (one aligned load), applies the operation in integer arithmetic, jitter and normalisation
 //    in fp32, and stores the 48 bytes at the same position of `target` (and of `visible` for
 //    kept patches).
-//  * aug_blur_kernel: the image rows of the band plus `radius` rows above and below (clamped at
-//    the image border) are gathered from the patch rows and staged as bytes, the vertical pass
-//    writes fp32 rows into LDS with six border pixels repeated on either side, and the
-//    horizontal pass is folded into the walk over the band in output order:
-//    a lane reads the 16 pixels around its four with aligned 16-byte LDS reads and applies all
-//    13 taps (zero beyond the radius).
+//  * aug_blur_kernel (bands split into column parts of whole patches): the vertical pass reads
+//    the bytes of the 13 image rows around each value from the patch rows in global memory and
+//    writes fp32 rows into LDS, six more pixels on either side included; the horizontal pass is
+//    folded into the walk over the part in output order: a lane reads the 16 pixels around its
+//    four with aligned 16-byte LDS reads and applies all 13 taps (zero beyond the radius).
 // The contrast step needs the mean luma of the whole image after the brightness step: with jitter
 // on, a first launch of the same kernels (kReduce) only accumulates that sum per band in double
 // precision, and the second launch adds the G partial sums of its image in fixed order.
@@ -26,9 +25,7 @@
 
 namespace mae {
 
-constexpr int kAugThreads = 256;    // pointwise kernel
-constexpr int kBlurThreads = 1024;  // blur kernel: its LDS allows two workgroups per compute unit,
-                                    // so the wavefronts that hide latency have to come from its size
+constexpr int kAugThreads = 256;
 constexpr int kMaxRadius = 6;  // ceil(3 * 2.0)
 constexpr int kTaps = 2 * kMaxRadius + 1;
 
@@ -64,8 +61,10 @@ __device__ static inline BandCtx band_ctx(const AugArgs& a) {
 
 // Mean luma after the brightness step, from the partial sums of the reduction launch.
 __device__ static inline float image_mean(const AugArgs& a, int b) {
+  // one slot per (row of patches, column part of the blur kernel); unused slots hold zero
+  const int slots = a.G * a.blur_parts;
   double sum = 0.0;
-  for (int g = 0; g < a.G; ++g) sum += a.partials[(int64_t)b * a.G + g];
+  for (int g = 0; g < slots; ++g) sum += a.partials[(int64_t)b * slots + g];
   return (float)(sum / ((double)a.S * (double)a.S));
 }
 
@@ -120,10 +119,10 @@ __device__ static inline void store_group(const AugArgs& a, int b, int l, int q,
 }
 
 // The same for a whole wavefront whose lanes hold consecutive groups (first group `g0`, a multiple
-// of 64): the 64 x 12 values go through a wavefront-private strip of LDS so that every store
+// of 64, of the run of patches that starts with patch l0): the 64 x 12 values go through a wavefront-private strip of LDS so that every store
 // instruction writes 1 KiB of contiguous memory instead of 16 bytes out of every 48.
 template <bool kBf16>
-__device__ static inline void store_groups_wave(const AugArgs& a, int b, int gy, int g0,
+__device__ static inline void store_groups_wave(const AugArgs& a, int b, int l0, int g0,
                                                 int groups_per_patch, float inv_gpp, int ngroups,
                                                 float* strip, const float* v, bool have) {
   const int lane = threadIdx.x % kWave;
@@ -153,7 +152,7 @@ __device__ static inline void store_groups_wave(const AugArgs& a, int b, int gy,
     if (g >= ngroups) continue;
     const f32x4 t = reinterpret_cast<const f32x4*>(strip)[piece];
     const int gx = fast_div(g, inv_gpp);
-    const int l = gy * a.G + gx;
+    const int l = l0 + gx;
     const int64_t eo = 12 * (int64_t)(g - gx * groups_per_patch) + 4 * (piece - 3 * (g - g0));
     if (a.target)
       *reinterpret_cast<f32x4*>(a.target + ((int64_t)b * a.L + l) * a.D + eo) = t;
@@ -172,7 +171,7 @@ __device__ static inline void store_groups_wave(const AugArgs& a, int b, int gy,
 
 // Sum over the workgroup in a fixed order (lanes by butterfly, wavefronts in index order).
 template <int kThreads>
-__device__ static inline void store_band_sum(const AugArgs& a, int b, int gy, float lsum,
+__device__ static inline void store_band_sum(const AugArgs& a, int b, int slot, float lsum,
                                              double* red) {
   double s = (double)lsum;
   for (int off = kWave / 2; off > 0; off >>= 1) s += __shfl_xor(s, off);
@@ -182,7 +181,7 @@ __device__ static inline void store_band_sum(const AugArgs& a, int b, int gy, fl
   if (tid == 0) {
     double t = 0.0;
     for (int w = 0; w < kThreads / kWave; ++w) t += red[w];
-    a.partials[(int64_t)b * a.G + gy] = t;
+    a.partials[(int64_t)b * a.G * a.blur_parts + slot] = t;
   }
 }
 
@@ -231,51 +230,64 @@ __global__ __launch_bounds__(kAugThreads) void aug_point_kernel(AugArgs a) {
       }
     }
     if (!kReduce)
-      store_groups_wave<kBf16>(a, b, gy, i0, groups_per_patch, inv_gpp, ngroups, strip, v, have);
+      store_groups_wave<kBf16>(a, b, gy * G, i0, groups_per_patch, inv_gpp, ngroups, strip, v,
+                               have);
   }
-  if (kReduce) store_band_sum<kAugThreads>(a, b, gy, lsum, red);
+  if (kReduce) {
+    store_band_sum<kAugThreads>(a, b, gy * a.blur_parts, lsum, red);
+    // the slots of the blur kernel's other column parts stay empty for this image
+    if (threadIdx.x > 0 && (int)threadIdx.x < a.blur_parts)
+      a.partials[((int64_t)b * G + gy) * a.blur_parts + threadIdx.x] = 0.0;
+  }
 }
 
 // ---- Gaussian blur ---------------------------------------------------------------------------------
-// Dynamic LDS: [ vals: p rows of 3 (S + 12) floats | staged bytes: (p + 12) rows of 3 S ].
+// One workgroup per (image, row of patches, column part of whole patches).  Dynamic LDS: p rows of
+// 3 (W + 12) floats, W = widest part in pixels: the vertically blurred values of the part's
+// columns and of six more pixels on either side (neighbouring columns, or the image's border
+// pixel repeated).  The vertical pass reads the 8-bit patch rows straight from global memory:
+// always 13 row taps per value (zero weight beyond the radius, rows clamped at the border), so
+// that all loads of a value are in flight together.
 template <bool kReduce, bool kBf16>
-__global__ __launch_bounds__(kBlurThreads) void aug_blur_kernel(AugArgs a) {
-  extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+__global__ __launch_bounds__(kAugThreads) void aug_blur_kernel(AugArgs a) {
+  extern __shared__ __attribute__((aligned(16))) float vals[];
   __shared__ double wd[kTaps];
   __shared__ float wf[kTaps];  // tap k - 6 at index k; zero beyond the radius
-  __shared__ double red[kBlurThreads / kWave];
-  const BandCtx c = band_ctx(a);
-  if (!c.valid || c.ap.op != kOpBlur) return;
-  const int S = a.S, p = a.p, G = a.G;
-  const int b = c.b, gy = c.gy, tid = threadIdx.x;
-  const int rv = 3 * S, rv4 = rv >> 2;
-  const int pv = 3 * (S + 2 * kMaxRadius);  // floats per padded row; 16-byte multiple
-  float* vals = reinterpret_cast<float*>(lds);
-  uint32_t* staged = lds + p * pv;
+  __shared__ int rowoff[48];   // byte offset of image row y0 - 6 + j inside patch 0 of its grid row
+  __shared__ double red[kAugThreads / kWave];
+  __shared__ __attribute__((aligned(16))) float strips[kAugThreads * 12];
+
+  const int S = a.S, p = a.p, G = a.G, parts = a.blur_parts;
+  const uint32_t tile = xcd_remap(blockIdx.x, gridDim.x);
+  const uint32_t band_id = tile / (uint32_t)parts;
+  const int part = (int)(tile - band_id * (uint32_t)parts);
+  const int b = (int)(band_id / (uint32_t)G);
+  const int gy = (int)(band_id - (uint32_t)b * (uint32_t)G);
+  const int gx0 = part * G / parts, gx1 = (part + 1) * G / parts;
+  const int npatch = gx1 - gx0;
+  const bool valid = reinterpret_cast<const CropRec*>(a.workspace + kWorkspaceHeader)[b].valid != 0;
+  const AugParams ap = aug_params(a.key1, a.sample_base + (uint32_t)b, a.jitter);
+  if (!valid || ap.op != kOpBlur || npatch <= 0) return;
+
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int pv = 3 * (a.blur_part_patches * p + 2 * kMaxRadius);  // floats per row, 16-byte multiple
+  const int Wp = npatch * p, x_lo = gx0 * p;
+  const int prow = 3 * p, prow4 = prow >> 2;  // bytes / words per patch row
+  const float inv_prow4 = 1.0f / (float)prow4, inv_p = 1.0f / (float)p;
   const uint8_t* img = a.u8 + (int64_t)b * a.L * a.D;  // patch order
   const int y0 = gy * p;
-  const int lane = tid % kWave, wave = tid / kWave;
-  const int prow4 = (3 * p) >> 2;  // words per patch row
-  const float inv_prow4 = 1.0f / (float)prow4, inv_p = 1.0f / (float)p;
-  const int radius = c.ap.radius;
+  const int radius = ap.radius;
 
   // taps exp(-k^2 / (2 sigma^2)) in double precision, summed in index order, scaled to sum 1
   if (tid < kTaps) {
     const double k = (double)(tid - kMaxRadius);
-    wd[tid] = abs(tid - kMaxRadius) <= radius ? exp(-(k * k) / (2.0 * c.ap.sigma * c.ap.sigma))
-                                               : 0.0;
+    wd[tid] = abs(tid - kMaxRadius) <= radius ? exp(-(k * k) / (2.0 * ap.sigma * ap.sigma)) : 0.0;
   }
-  // the band and its halo, border rows repeated
-  const int nrows = p + 2 * radius;
-  for (int j = wave; j < nrows; j += kBlurThreads / kWave) {
-    const int yy = min(max(y0 - radius + j, 0), S - 1);
-    const int gyy = fast_div(yy, inv_p), pyy = yy - gyy * p;
-    const uint8_t* row = img + (int64_t)gyy * G * a.D + pyy * 3 * p;  // patch 0 of that grid row
-    for (int d = lane; d < rv4; d += kWave) {
-      const int gx = fast_div(d, inv_prow4);
-      staged[j * rv4 + d] =
-          reinterpret_cast<const uint32_t*>(row + (int64_t)gx * a.D)[d - gx * prow4];
-    }
+  if (tid >= kWave && tid < kWave + p + 2 * kMaxRadius) {
+    const int j = tid - kWave;
+    const int yy = min(max(y0 - kMaxRadius + j, 0), S - 1);
+    const int gyy = fast_div(yy, inv_p);
+    rowoff[j] = gyy * G * a.D + (yy - gyy * p) * prow;
   }
   __syncthreads();
   if (tid < kTaps) {
@@ -284,17 +296,27 @@ __global__ __launch_bounds__(kBlurThreads) void aug_blur_kernel(AugArgs a) {
     wf[tid] = (float)(wd[tid] / sum);
   }
   __syncthreads();
-  // vertical pass: four neighbouring values (the bytes of one word) per step
-  for (int y = wave; y < p; y += kBlurThreads / kWave) {
-    for (int d = lane; d < rv4; d += kWave) {
+  float wt[kTaps];
+#pragma unroll
+  for (int k = 0; k < kTaps; ++k) wt[k] = wf[k];
+
+  // vertical pass over the part's own columns, four neighbouring values (one word) per step
+  const int words = npatch * prow4;
+  for (int y = wave; y < p; y += kAugThreads / kWave) {
+    for (int d = lane; d < words; d += kWave) {
+      const int gxl = fast_div(d, inv_prow4);
+      const int64_t col = (int64_t)(gx0 + gxl) * a.D + 4 * (d - gxl * prow4);
+      uint32_t w4[kTaps];
+#pragma unroll
+      for (int k = 0; k < kTaps; ++k)
+        w4[k] = *reinterpret_cast<const uint32_t*>(img + rowoff[y + k] + col);
       float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
-      for (int k = 0; k <= 2 * radius; ++k) {
-        const uint32_t w4 = staged[(y + k) * rv4 + d];
-        const float w = wf[kMaxRadius - radius + k];
-        acc0 += w * (float)(w4 & 0xFFu);
-        acc1 += w * (float)((w4 >> 8) & 0xFFu);
-        acc2 += w * (float)((w4 >> 16) & 0xFFu);
-        acc3 += w * (float)(w4 >> 24);
+#pragma unroll
+      for (int k = 0; k < kTaps; ++k) {
+        acc0 += wt[k] * (float)(w4[k] & 0xFFu);
+        acc1 += wt[k] * (float)((w4[k] >> 8) & 0xFFu);
+        acc2 += wt[k] * (float)((w4[k] >> 16) & 0xFFu);
+        acc3 += wt[k] * (float)(w4[k] >> 24);
       }
       // 18 + 4 d floats into the row: 8-byte aligned
       f32x2* dst = reinterpret_cast<f32x2*>(vals + y * pv + 3 * kMaxRadius + 4 * d);
@@ -302,34 +324,35 @@ __global__ __launch_bounds__(kBlurThreads) void aug_blur_kernel(AugArgs a) {
       dst[1] = f32x2{acc2, acc3};
     }
   }
-  __syncthreads();
-  // six border pixels repeated on either side of every row
-  for (int i = tid; i < p * 2 * kMaxRadius * 3; i += kBlurThreads) {
+  // ... and over the six pixels on either side of the part
+  for (int i = tid; i < p * 2 * kMaxRadius * 3; i += kAugThreads) {
     const int y = i / (2 * kMaxRadius * 3);
     const int r = i - y * (2 * kMaxRadius * 3);
     const int side = r / (kMaxRadius * 3), t = r - side * (kMaxRadius * 3);
-    const int ch = t % 3;
-    float* row = vals + y * pv;
-    if (side == 0) {
-      row[t] = row[3 * kMaxRadius + ch];
-    } else {
-      row[3 * (kMaxRadius + S) + t] = row[3 * (kMaxRadius + S - 1) + ch];
-    }
+    const int jpx = t / 3, ch = t - 3 * jpx;
+    const int x = min(max(side == 0 ? x_lo - kMaxRadius + jpx : x_lo + Wp + jpx, 0), S - 1);
+    const int gx = fast_div(x, inv_p);
+    const int64_t col = (int64_t)gx * a.D + 3 * (x - gx * p) + ch;
+    float acc = 0.f;
+#pragma unroll
+    for (int k = 0; k < kTaps; ++k) acc += wt[k] * (float)img[rowoff[y + k] + col];
+    vals[y * pv + (side == 0 ? t : 3 * (kMaxRadius + Wp) + t)] = acc;
   }
   __syncthreads();
 
   const float mean = (!kReduce && a.mode == 2) ? image_mean(a, b) : 0.0f;
-  float wt[kTaps];
-#pragma unroll
-  for (int k = 0; k < kTaps; ++k) wt[k] = wf[k];
   const int groups_per_patch = (p * p) >> 2;
   const float inv_gpp = 1.0f / (float)groups_per_patch;
+  const int ngroups = npatch * groups_per_patch;
+  float* strip = strips + wave * (kWave * 12);
   float lsum = 0.0f;
-  for (int i = tid; i < G * groups_per_patch; i += kBlurThreads) {
-    const int gx = fast_div(i, inv_gpp);
-    const int q = 4 * (i - gx * groups_per_patch);
-    const int py = fast_div(q, inv_p), x = gx * p + (q - py * p);
-    // padded pixels x .. x + 15 are image pixels x - 6 .. x + 9: 48 floats, 16-byte aligned
+  for (int i0 = wave * kWave; i0 < ngroups; i0 += kAugThreads) {
+    const int i = min(i0 + lane, ngroups - 1);
+    const bool have = i0 + lane < ngroups;
+    const int gxl = fast_div(i, inv_gpp);
+    const int q = 4 * (i - gxl * groups_per_patch);
+    const int py = fast_div(q, inv_p), x = gxl * p + (q - py * p);  // pixel inside the part
+    // padded pixels x .. x + 15 are the part's pixels x - 6 .. x + 9: 48 floats, 16-byte aligned
     const f32x4* src = reinterpret_cast<const f32x4*>(vals + py * pv + 3 * x);
     float n[48];
 #pragma unroll
@@ -353,31 +376,49 @@ __global__ __launch_bounds__(kBlurThreads) void aug_blur_kernel(AugArgs a) {
       v[3 * h] = r;
       v[3 * h + 1] = g;
       v[3 * h + 2] = bl;
-      if (a.mode == 2)
-        lsum += jitter_pixel<kReduce>(c.ap, mean, v[3 * h], v[3 * h + 1], v[3 * h + 2]);
+      if (a.mode == 2) {
+        const float lum = jitter_pixel<kReduce>(ap, mean, v[3 * h], v[3 * h + 1], v[3 * h + 2]);
+        lsum += have ? lum : 0.0f;
+      }
     }
-    if (!kReduce) store_group<kBf16>(a, b, gy * G + gx, q, v);
+    if (!kReduce)
+      store_groups_wave<kBf16>(a, b, gy * G + gx0, i0, groups_per_patch, inv_gpp, ngroups, strip,
+                               v, have);
   }
-  if (kReduce) store_band_sum<kBlurThreads>(a, b, gy, lsum, red);
+  if (kReduce) store_band_sum<kAugThreads>(a, b, (gy * parts + part), lsum, red);
 }
 
-size_t three_aug_lds_bytes(int S, int p) {
-  return (size_t)p * 3 * (S + 2 * kMaxRadius) * 4 + (size_t)(p + 2 * kMaxRadius) * 3 * S;
+// Column parts of the blur kernel: the fewest (whole patches each) whose rows fit 24 KiB of LDS,
+// so that four workgroups share a compute unit.
+AugPlan three_aug_plan(int S, int p) {
+  const int G = S / p;
+  AugPlan plan;
+  for (int parts = 1;; ++parts) {
+    const int n = (G + parts - 1) / parts;
+    const size_t lds = (size_t)p * 3 * (n * p + 2 * kMaxRadius) * 4;
+    if (lds <= 24 * 1024 || parts >= G) {
+      plan.parts = parts;
+      plan.part_patches = n;
+      plan.lds_bytes = lds;
+      return plan;
+    }
+  }
 }
 
 hipError_t launch_three_aug(const AugArgs& a, hipStream_t stream) {
-  dim3 grid((uint32_t)a.B * (uint32_t)a.G), block(kAugThreads), bblock(kBlurThreads);
-  const size_t lds = three_aug_lds_bytes(a.S, a.p);
+  dim3 grid((uint32_t)a.B * (uint32_t)a.G), block(kAugThreads);
+  dim3 bgrid((uint32_t)a.B * (uint32_t)a.G * (uint32_t)a.blur_parts);
+  const size_t lds = (size_t)a.p * 3 * (a.blur_part_patches * a.p + 2 * kMaxRadius) * 4;
   if (a.mode == 2) {
     hipLaunchKernelGGL((aug_point_kernel<true, false>), grid, block, 0, stream, a);
-    hipLaunchKernelGGL((aug_blur_kernel<true, false>), grid, bblock, lds, stream, a);
+    hipLaunchKernelGGL((aug_blur_kernel<true, false>), bgrid, block, lds, stream, a);
   }
   if (a.visible_bf16) {
     hipLaunchKernelGGL((aug_point_kernel<false, true>), grid, block, 0, stream, a);
-    hipLaunchKernelGGL((aug_blur_kernel<false, true>), grid, bblock, lds, stream, a);
+    hipLaunchKernelGGL((aug_blur_kernel<false, true>), bgrid, block, lds, stream, a);
   } else {
     hipLaunchKernelGGL((aug_point_kernel<false, false>), grid, block, 0, stream, a);
-    hipLaunchKernelGGL((aug_blur_kernel<false, false>), grid, bblock, lds, stream, a);
+    hipLaunchKernelGGL((aug_blur_kernel<false, false>), bgrid, block, lds, stream, a);
   }
   return hipGetLastError();
 }

@@ -110,7 +110,6 @@ def _call_prep(lib, d, visible=FAKE, mask=FAKE, ids_restore=FAKE, workspace=FAKE
     (dict(aug_mode=2, jitter=-0.1), binding.MAE_ERR_RANGE),
     (dict(aug_mode=2, jitter=float("nan")), binding.MAE_ERR_RANGE),
     (dict(aug_mode=1, out_size=224, patch=14, num_keep=64), binding.MAE_ERR_SHAPE),  # 3 p % 4 != 0
-    (dict(aug_mode=1, out_size=256, patch=16, num_keep=64), binding.MAE_ERR_RANGE),  # band > LDS
 ])
 def test_prep_rejects_bad_descriptors(lib, over, status):
     d = _prep_desc(**over)
@@ -124,7 +123,7 @@ def test_prep_workspace_grows_with_the_augmentation(lib):
     three = lib.mae_prep_workspace_bytes(C.byref(_prep_desc(aug_mode=1)))
     plus = lib.mae_prep_workspace_bytes(C.byref(_prep_desc(aug_mode=2)))
     assert three == 512 + 4 * 224 * 224 * 3          # records rounded up to 256, then the bytes
-    assert plus == three + 4 * 14 * 8                 # one double per row of patches
+    assert plus == three + 4 * 14 * 2 * 8             # a double per row of patches and column part
     d = _prep_desc(aug_mode=2)
     assert _call_prep(lib, d, ws_bytes=plus - 1) == binding.MAE_ERR_WORKSPACE
 

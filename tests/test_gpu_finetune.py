@@ -75,9 +75,11 @@ def test_jitter_of_strength_zero_is_plain_three_aug():
         assert torch.equal(getattr(a, t), getattr(c, t)), t
 
 
-def test_small_patch_and_small_images():
-    # p = 4 and p = 8 (rows of patches of 12 and 24 bytes), images smaller than the output
-    for S, p, kind in ((32, 4, "uniform"), (64, 8, "uniform"), (112, 16, "uniform")):
+def test_other_patch_sizes_and_resolutions():
+    # p = 4 and p = 8 (rows of patches of 12 and 24 bytes), images smaller than the output, an odd
+    # grid, and resolutions whose rows of patches the blur splits into two and three column parts
+    for S, p, kind in ((32, 4, "uniform"), (64, 8, "uniform"), (112, 16, "uniform"),
+                       (240, 16, "gradient"), (256, 16, "gradient"), (160, 32, "gradient")):
         L = (S // p) ** 2
         data = synth.make_images(kind, 16, seed=52)
         kw = dict(out_size=S, patch=p, num_keep=L, seed=11, batch_index=3,
