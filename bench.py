@@ -32,8 +32,8 @@ LOSS_KERNEL_SOURCES = ("paper_2404_00509_amd/csrc/normpix_loss.hip",
                        "paper_2404_00509_amd/csrc/mae_device.hpp")
 MEASURED_TRAFFIC = {
     # workload: (sha256 of the sources above, bytes read + written per launch)
-    "c4": ("593cd9679e77dfa300422701f1a4e5673c14a5996482c16b0f6f7d2392f20fd5", 6.172e9),
-    "c5": ("593cd9679e77dfa300422701f1a4e5673c14a5996482c16b0f6f7d2392f20fd5", 4.416e9),
+    "c4": ("b4f6f61afcea57f562a490d6423f934502b2f1575bf58f5f2e631299e8ee005a", 6.172e9),
+    "c5": ("b4f6f61afcea57f562a490d6423f934502b2f1575bf58f5f2e631299e8ee005a", 4.416e9),
 }
 
 
