@@ -130,6 +130,18 @@ def load_library(path: str):
     L.mae_oracle_stage_of_epoch.argtypes = [C.c_int32, C.c_void_p, C.c_int32]
     L.mae_oracle_patch_embed.restype = C.c_int32
     L.mae_oracle_patch_embed.argtypes = [C.c_int32] * 5 + [C.c_void_p] * 6
+    L.mae_oracle_jpeg_info.restype = C.c_int32
+    L.mae_oracle_jpeg_info.argtypes = [C.c_void_p, C.c_int64] + [C.c_void_p] * 5
+    L.mae_oracle_jpeg_decode.restype = C.c_int32
+    L.mae_oracle_jpeg_decode.argtypes = [C.c_void_p, C.c_int64, C.c_void_p]
+    L.mae_oracle_jpeg_decode_ycc.restype = C.c_int32
+    L.mae_oracle_jpeg_decode_ycc.argtypes = [C.c_void_p, C.c_int64, C.c_void_p]
+    L.mae_oracle_idct8x8.restype = None
+    L.mae_oracle_idct8x8.argtypes = [C.c_void_p, C.c_void_p]
+    L.mae_oracle_ycc_to_rgb.restype = None
+    L.mae_oracle_ycc_to_rgb.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
+    L.mae_oracle_huff_codes.restype = C.c_int32
+    L.mae_oracle_huff_codes.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
     L.mae_oracle_threads.restype = C.c_int32
     L.mae_oracle_threads.argtypes = []
     return L
@@ -400,6 +412,54 @@ def patch_embed(visible, ids_keep, weight, bias=None, pos=None):
     if rc != 0:
         raise ValueError("mae_oracle_patch_embed: invalid argument")
     return out
+
+
+def jpeg_info(data: bytes):
+    """-> dict(H, W, luma_h, luma_v, restart_interval); raises ValueError on an unsupported file."""
+    buf = np.frombuffer(data, np.uint8)
+    v = [C.c_int32() for _ in range(5)]
+    rc = lib().mae_oracle_jpeg_info(_p(buf), buf.size, *[C.byref(x) for x in v])
+    if rc != 0:
+        raise ValueError(f"mae_oracle_jpeg_info: {rc}")
+    return dict(zip(("H", "W", "luma_h", "luma_v", "restart_interval"), (x.value for x in v)))
+
+
+def jpeg_decode(data: bytes, ycc: bool = False) -> np.ndarray:
+    """Baseline JPEG -> [H, W, 3] uint8 RGB (the whole image); ycc=True: before the colour
+    conversion (Y, Cb, Cr per pixel)."""
+    info = jpeg_info(data)
+    buf = np.frombuffer(data, np.uint8)
+    out = np.empty((info["H"], info["W"], 3), np.uint8)
+    fn = lib().mae_oracle_jpeg_decode_ycc if ycc else lib().mae_oracle_jpeg_decode
+    rc = fn(_p(buf), buf.size, _p(out))
+    if rc != 0:
+        raise ValueError(f"mae_oracle_jpeg_decode: {rc}")
+    return out
+
+
+def idct8x8(coef) -> np.ndarray:
+    """coef [8, 8] int (dequantised, [v][u]) -> [8, 8] uint8 samples ([y][x])."""
+    cf = np.ascontiguousarray(coef, np.int32).reshape(64)
+    out = np.empty(64, np.uint8)
+    lib().mae_oracle_idct8x8(_p(cf), _p(out))
+    return out.reshape(8, 8)
+
+
+def ycc_to_rgb(y: int, cb: int, cr: int):
+    out = np.empty(3, np.uint8)
+    lib().mae_oracle_ycc_to_rgb(y, cb, cr, _p(out))
+    return tuple(int(v) for v in out)
+
+
+def huff_codes(counts):
+    """counts[16] -> list of (code, length) in table order."""
+    cnt = np.ascontiguousarray(counts, np.uint8)
+    n = int(cnt.sum())
+    codes = np.zeros(max(n, 1), np.uint16)
+    lengths = np.zeros(max(n, 1), np.uint8)
+    m = lib().mae_oracle_huff_codes(_p(cnt), _p(codes), _p(lengths))
+    assert m == n
+    return [(int(codes[i]), int(lengths[i])) for i in range(n)]
 
 
 def threads() -> int:

@@ -597,6 +597,359 @@ int32_t mae_oracle_patch_embed(int32_t B, int32_t K, int32_t D, int32_t E, int32
   return bad ? -1 : 0;
 }
 
+/* ------------------------------------------------------------------------------------------------
+ * Baseline JPEG (ITU-T T.81, JFIF).  Sec. 4.1 of the paper speeds up the loader by decoding only
+ * the crop; what a decoder computes is fixed by the standard up to the accuracy of the inverse
+ * DCT, the chroma upsampling filter and the colour arithmetic -- those three are fixed in the
+ * header of this library.  Everything here is the sequential procedure of the standard's Annex F
+ * written out: marker segments, canonical Huffman codes, DC prediction, zero runs, zig-zag.
+ * ---------------------------------------------------------------------------------------------- */
+static const uint8_t ZIGZAG[64] = {
+    0,  1,  8,  16, 9,  2,  3,  10, 17, 24, 32, 25, 18, 11, 4,  5,  12, 19, 26, 33, 40, 48,
+    41, 34, 27, 20, 13, 6,  7,  14, 21, 28, 35, 42, 49, 56, 57, 50, 43, 36, 29, 22, 15, 23,
+    30, 37, 44, 51, 58, 59, 52, 45, 38, 31, 39, 46, 53, 60, 61, 54, 47, 55, 62, 63};
+
+typedef struct {
+  uint8_t counts[16];
+  uint8_t symbols[256];
+  int32_t nsym;
+  int32_t first_code[17]; /* code of the first symbol of each length */
+  int32_t first_index[17];
+} huff_table;
+
+typedef struct {
+  int32_t H, W, ncomp;
+  int32_t hs[3], vs[3], tq[3], td[3], ta[3], cid[3];
+  uint16_t q[4][64]; /* zig-zag order, as stored */
+  int32_t have_q[4];
+  huff_table dc[4], ac[4];
+  int32_t have_dc[4], have_ac[4];
+  int32_t restart;
+  int64_t scan; /* offset of the first entropy-coded byte */
+} jpeg_header;
+
+static void huff_prepare(huff_table* t) {
+  int32_t code = 0, index = 0;
+  for (int32_t len = 1; len <= 16; ++len) {
+    t->first_code[len] = code;
+    t->first_index[len] = index;
+    code += t->counts[len - 1];
+    index += t->counts[len - 1];
+    code <<= 1;
+  }
+  t->nsym = index;
+}
+
+int32_t mae_oracle_huff_codes(const uint8_t counts[16], uint16_t* codes, uint8_t* lengths) {
+  int32_t code = 0, i = 0;
+  for (int32_t len = 1; len <= 16; ++len) {
+    for (int32_t j = 0; j < counts[len - 1]; ++j) {
+      codes[i] = (uint16_t)code++;
+      lengths[i++] = (uint8_t)len;
+    }
+    code <<= 1;
+  }
+  return i;
+}
+
+static int32_t be16(const uint8_t* p) { return (p[0] << 8) | p[1]; }
+
+static int32_t jpeg_parse(const uint8_t* d, int64_t n, jpeg_header* h) {
+  memset(h, 0, sizeof(*h));
+  if (n < 4 || d[0] != 0xFF || d[1] != 0xD8) return -2;
+  int64_t pos = 2;
+  int32_t have_frame = 0;
+  for (;;) {
+    if (pos + 4 > n) return -3;
+    if (d[pos] != 0xFF) return -3;
+    int32_t m = d[pos + 1];
+    if (m == 0xFF) { /* fill byte */
+      ++pos;
+      continue;
+    }
+    int32_t len = be16(d + pos + 2);
+    if (len < 2 || pos + 2 + len > n) return -3;
+    const uint8_t* s = d + pos + 4;
+    int32_t body = len - 2;
+    if (m == 0xDB) { /* quantisation tables */
+      int32_t o = 0;
+      while (o < body) {
+        int32_t pq = s[o] >> 4, tq = s[o] & 15;
+        if (pq != 0 || tq > 3 || o + 65 > body) return -2;
+        for (int32_t k = 0; k < 64; ++k) h->q[tq][k] = s[o + 1 + k];
+        h->have_q[tq] = 1;
+        o += 65;
+      }
+    } else if (m == 0xC0) { /* baseline frame */
+      if (body < 6) return -3;
+      if (s[0] != 8) return -2;
+      h->H = be16(s + 1);
+      h->W = be16(s + 3);
+      h->ncomp = s[5];
+      if (h->ncomp != 3 || body < 6 + 9 || h->H < 1 || h->W < 1) return -2;
+      for (int32_t c = 0; c < 3; ++c) {
+        h->cid[c] = s[6 + 3 * c];
+        h->hs[c] = s[7 + 3 * c] >> 4;
+        h->vs[c] = s[7 + 3 * c] & 15;
+        h->tq[c] = s[8 + 3 * c];
+        if (h->tq[c] > 3) return -2;
+      }
+      if (h->hs[1] != 1 || h->vs[1] != 1 || h->hs[2] != 1 || h->vs[2] != 1) return -2;
+      if (!((h->hs[0] == 1 && h->vs[0] == 1) || (h->hs[0] == 2 && h->vs[0] == 2))) return -2;
+      have_frame = 1;
+    } else if (m >= 0xC1 && m <= 0xCF && m != 0xC4 && m != 0xC8 && m != 0xCC) {
+      return -2; /* any other kind of frame */
+    } else if (m == 0xC4) { /* Huffman tables */
+      int32_t o = 0;
+      while (o < body) {
+        if (o + 17 > body) return -3;
+        int32_t tc = s[o] >> 4, th = s[o] & 15;
+        if (tc > 1 || th > 3) return -2;
+        huff_table* t = tc ? &h->ac[th] : &h->dc[th];
+        int32_t total = 0;
+        for (int32_t i = 0; i < 16; ++i) {
+          t->counts[i] = s[o + 1 + i];
+          total += t->counts[i];
+        }
+        if (total > 256 || o + 17 + total > body) return -3;
+        for (int32_t i = 0; i < total; ++i) t->symbols[i] = s[o + 17 + i];
+        huff_prepare(t);
+        if (tc) h->have_ac[th] = 1; else h->have_dc[th] = 1;
+        o += 17 + total;
+      }
+    } else if (m == 0xDD) {
+      if (body < 2) return -3;
+      h->restart = be16(s);
+    } else if (m == 0xDA) { /* start of scan */
+      if (!have_frame || body < 1 + 6 + 3 || s[0] != 3) return -2;
+      for (int32_t c = 0; c < 3; ++c) {
+        if (s[1 + 2 * c] != h->cid[c]) return -2; /* components in frame order */
+        h->td[c] = s[2 + 2 * c] >> 4;
+        h->ta[c] = s[2 + 2 * c] & 15;
+        if (h->td[c] > 3 || h->ta[c] > 3 || !h->have_dc[h->td[c]] || !h->have_ac[h->ta[c]] ||
+            !h->have_q[h->tq[c]])
+          return -2;
+      }
+      if (s[7] != 0 || s[8] != 63) return -2; /* sequential: whole spectrum in one scan */
+      h->scan = pos + 2 + len;
+      return 0;
+    } else if (m == 0xD9) {
+      return -3;
+    }
+    pos += 2 + len;
+  }
+}
+
+int32_t mae_oracle_jpeg_info(const uint8_t* data, int64_t n, int32_t* H, int32_t* W,
+                             int32_t* luma_h, int32_t* luma_v, int32_t* restart_interval) {
+  if (!data) return -1;
+  jpeg_header h;
+  int32_t rc = jpeg_parse(data, n, &h);
+  if (rc) return rc;
+  if (H) *H = h.H;
+  if (W) *W = h.W;
+  if (luma_h) *luma_h = h.hs[0];
+  if (luma_v) *luma_v = h.vs[0];
+  if (restart_interval) *restart_interval = h.restart;
+  return 0;
+}
+
+/* entropy-coded segment reader: bytes after the scan header, 0xFF00 stands for 0xFF, any other
+ * marker ends the data (zero bits are supplied beyond it) */
+typedef struct {
+  const uint8_t* d;
+  int64_t n, pos;
+  uint32_t acc;
+  int32_t nbits;
+  int32_t hit_marker;
+} bit_reader;
+
+static int32_t next_bit(bit_reader* r) {
+  if (r->nbits == 0) {
+    uint32_t byte = 0;
+    if (!r->hit_marker && r->pos < r->n) {
+      byte = r->d[r->pos];
+      if (byte == 0xFF) {
+        if (r->pos + 1 < r->n && r->d[r->pos + 1] == 0x00) {
+          r->pos += 2;
+        } else {
+          r->hit_marker = 1;
+          byte = 0;
+        }
+      } else {
+        r->pos += 1;
+      }
+    }
+    r->acc = byte;
+    r->nbits = 8;
+  }
+  r->nbits -= 1;
+  return (int32_t)((r->acc >> r->nbits) & 1u);
+}
+
+static int32_t receive(bit_reader* r, int32_t s) {
+  int32_t v = 0;
+  for (int32_t i = 0; i < s; ++i) v = (v << 1) | next_bit(r);
+  return v;
+}
+
+static int32_t extend(int32_t v, int32_t s) {
+  return (s && v < (1 << (s - 1))) ? v - (1 << s) + 1 : v;
+}
+
+static int32_t huff_decode(bit_reader* r, const huff_table* t) {
+  int32_t code = 0;
+  for (int32_t len = 1; len <= 16; ++len) {
+    code = (code << 1) | next_bit(r);
+    int32_t k = code - t->first_code[len];
+    if (k >= 0 && k < t->counts[len - 1]) return t->symbols[t->first_index[len] + k];
+  }
+  return -1;
+}
+
+static int32_t idct_basis(int32_t x, int32_t u) {
+  /* C(u) cos((2x+1) u pi / 16) in 13 fractional bits, C(0) = 1/sqrt(2), C(u>0) = 1 */
+  double c = (u == 0) ? sqrt(0.5) : cos((double)((2 * x + 1) * u) * 3.14159265358979323846 / 16.0);
+  return (int32_t)lrint(c * 8192.0);
+}
+
+static int32_t clamp16(int64_t v) { return v < -32767 ? -32767 : (v > 32767 ? 32767 : (int32_t)v); }
+static int64_t floor_shift(int64_t v, int32_t s) { return v >= 0 ? v >> s : -((-v + (1ll << s) - 1) >> s); }
+
+void mae_oracle_idct8x8(const int32_t coef[64], uint8_t out[64]) {
+  /* f(x, y) = 1/4 sum_u sum_v C(u) C(v) F(v, u) cos(..x..u) cos(..y..v); coef[v * 8 + u];
+   * out[y * 8 + x].  Pass 1 along v (columns), pass 2 along u (rows). */
+  int32_t tmp[64];
+  for (int32_t y = 0; y < 8; ++y)
+    for (int32_t u = 0; u < 8; ++u) {
+      int64_t acc = 0;
+      for (int32_t v = 0; v < 8; ++v) acc += (int64_t)idct_basis(y, v) * clamp16(coef[v * 8 + u]);
+      tmp[y * 8 + u] = clamp16(floor_shift(acc + (1 << 10), 11)); /* 1-D result, 3 more bits */
+    }
+  for (int32_t y = 0; y < 8; ++y)
+    for (int32_t x = 0; x < 8; ++x) {
+      int64_t acc = 0;
+      for (int32_t u = 0; u < 8; ++u) acc += (int64_t)idct_basis(x, u) * tmp[y * 8 + u];
+      int64_t v = floor_shift(acc + (1 << 16), 17) + 128;
+      out[y * 8 + x] = (uint8_t)(v < 0 ? 0 : (v > 255 ? 255 : v));
+    }
+}
+
+void mae_oracle_ycc_to_rgb(int32_t y, int32_t cb, int32_t cr, uint8_t rgb[3]) {
+  int64_t b = cb - 128, r = cr - 128;
+  int64_t R = y + floor_shift(91881 * r + 32768, 16);
+  int64_t G = y - floor_shift(22554 * b + 46802 * r + 32768, 16);
+  int64_t B = y + floor_shift(116130 * b + 32768, 16);
+  rgb[0] = (uint8_t)(R < 0 ? 0 : (R > 255 ? 255 : R));
+  rgb[1] = (uint8_t)(G < 0 ? 0 : (G > 255 ? 255 : G));
+  rgb[2] = (uint8_t)(B < 0 ? 0 : (B > 255 ? 255 : B));
+}
+
+static int32_t jpeg_decode_any(const uint8_t* data, int64_t n, uint8_t* rgb, int32_t want_ycc);
+
+int32_t mae_oracle_jpeg_decode(const uint8_t* data, int64_t n, uint8_t* rgb) {
+  return jpeg_decode_any(data, n, rgb, 0);
+}
+
+int32_t mae_oracle_jpeg_decode_ycc(const uint8_t* data, int64_t n, uint8_t* ycc) {
+  return jpeg_decode_any(data, n, ycc, 1);
+}
+
+static int32_t jpeg_decode_any(const uint8_t* data, int64_t n, uint8_t* rgb, int32_t want_ycc) {
+  if (!data || !rgb) return -1;
+  jpeg_header h;
+  int32_t rc = jpeg_parse(data, n, &h);
+  if (rc) return rc;
+  int32_t hmax = h.hs[0], vmax = h.vs[0];
+  int32_t mcux = (h.W + 8 * hmax - 1) / (8 * hmax), mcuy = (h.H + 8 * vmax - 1) / (8 * vmax);
+  /* component planes, whole MCUs */
+  uint8_t* plane[3];
+  int32_t pw[3], ph[3];
+  for (int32_t c = 0; c < 3; ++c) {
+    pw[c] = mcux * h.hs[c] * 8;
+    ph[c] = mcuy * h.vs[c] * 8;
+    plane[c] = (uint8_t*)malloc((size_t)pw[c] * ph[c]);
+    if (!plane[c]) return -1;
+  }
+  bit_reader r = {data, n, h.scan, 0, 0, 0};
+  int32_t pred[3] = {0, 0, 0};
+  int32_t status = 0;
+  int64_t total = (int64_t)mcux * mcuy;
+  for (int64_t m = 0; m < total && !status; ++m) {
+    if (h.restart && m > 0 && m % h.restart == 0) {
+      /* the interval ends on a byte boundary and is followed by RSTn */
+      r.nbits = 0;
+      if (!(r.pos + 1 < r.n && r.d[r.pos] == 0xFF && r.d[r.pos + 1] >= 0xD0 &&
+            r.d[r.pos + 1] <= 0xD7 &&
+            r.d[r.pos + 1] == 0xD0 + (int32_t)((m / h.restart - 1) % 8))) {
+        status = -3;
+        break;
+      }
+      r.pos += 2;
+      r.hit_marker = 0;
+      pred[0] = pred[1] = pred[2] = 0;
+    }
+    int32_t my = (int32_t)(m / mcux), mx = (int32_t)(m % mcux);
+    for (int32_t c = 0; c < 3 && !status; ++c)
+      for (int32_t bv = 0; bv < h.vs[c] && !status; ++bv)
+        for (int32_t bh = 0; bh < h.hs[c] && !status; ++bh) {
+          int32_t coef[64];
+          memset(coef, 0, sizeof(coef));
+          int32_t s = huff_decode(&r, &h.dc[h.td[c]]);
+          if (s < 0 || s > 11) {
+            status = -3;
+            break;
+          }
+          pred[c] += extend(receive(&r, s), s);
+          coef[0] = pred[c] * (int32_t)h.q[h.tq[c]][0];
+          for (int32_t k = 1; k < 64;) {
+            int32_t rs = huff_decode(&r, &h.ac[h.ta[c]]);
+            if (rs < 0) {
+              status = -3;
+              break;
+            }
+            int32_t run = rs >> 4, size = rs & 15;
+            if (size == 0) {
+              if (run != 15) break; /* end of block */
+              k += 16;
+              continue;
+            }
+            k += run;
+            if (k > 63) {
+              status = -3;
+              break;
+            }
+            coef[ZIGZAG[k]] = extend(receive(&r, size), size) * (int32_t)h.q[h.tq[c]][k];
+            ++k;
+          }
+          uint8_t px[64];
+          mae_oracle_idct8x8(coef, px);
+          int32_t x0 = (mx * h.hs[c] + bh) * 8, y0 = (my * h.vs[c] + bv) * 8;
+          for (int32_t y = 0; y < 8; ++y)
+            memcpy(plane[c] + (size_t)(y0 + y) * pw[c] + x0, px + 8 * y, 8);
+        }
+  }
+  if (!status) {
+    for (int32_t y = 0; y < h.H; ++y)
+      for (int32_t x = 0; x < h.W; ++x) {
+        int32_t Y = plane[0][(size_t)y * pw[0] + x];
+        int32_t cb = plane[1][(size_t)(y * h.vs[1] / vmax) * pw[1] + x * h.hs[1] / hmax];
+        int32_t cr = plane[2][(size_t)(y * h.vs[2] / vmax) * pw[2] + x * h.hs[2] / hmax];
+        uint8_t* px = rgb + ((size_t)y * h.W + x) * 3;
+        if (want_ycc) {
+          px[0] = (uint8_t)Y;
+          px[1] = (uint8_t)cb;
+          px[2] = (uint8_t)cr;
+        } else {
+          mae_oracle_ycc_to_rgb(Y, cb, cr, px);
+        }
+      }
+  }
+  for (int32_t c = 0; c < 3; ++c) free(plane[c]);
+  (void)ph;
+  return status;
+}
+
 int32_t mae_oracle_threads(void) {
 #ifdef _OPENMP
   return (int32_t)omp_get_max_threads();

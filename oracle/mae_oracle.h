@@ -169,6 +169,33 @@ int32_t mae_oracle_patch_embed(int32_t B, int32_t K, int32_t D, int32_t E, int32
                                const float* visible, const int32_t* ids_keep, const float* weight,
                                const float* bias, const float* pos, double* tokens);
 
+/* ---- baseline JPEG decoding (Sec. 4.1 "Crop Decode": the loader decodes JPEG files; the paper's
+ * contribution is to decode only the region that the crop needs) --------------------------------
+ * Plain sequential decoder of what the dataset writer produces: baseline DCT (SOF0), 8 bits, three
+ * components (YCbCr, JFIF), luma sampling 1x1 or 2x2 with 1x1 chroma, Huffman tables and
+ * quantisation tables as found in the file, optional restart intervals.  Written from the
+ * published standard (ITU-T T.81) and JFIF; the choices the standard leaves open are fixed here:
+ *   - inverse DCT: separable, 13-bit fixed-point cosines, first pass rounded to 3 fractional
+ *     bits, coefficients and first-pass values clamped to +-32767 (mae_oracle_idct8x8);
+ *   - chroma upsampling: each chroma sample is repeated over the pixels it covers;
+ *   - colour: 16-bit fixed-point JFIF matrix, floor after adding one half (mae_oracle_ycc_to_rgb).
+ * The whole image is decoded; cropping is somebody else's business.  Returns 0, or a negative
+ * code: -1 bad arguments, -2 not a baseline 3-component JPEG of the supported sampling,
+ * -3 truncated or corrupt stream. */
+int32_t mae_oracle_jpeg_info(const uint8_t* data, int64_t n, int32_t* H, int32_t* W,
+                             int32_t* luma_h, int32_t* luma_v, int32_t* restart_interval);
+/* rgb: H x W x 3, rows tightly packed. */
+int32_t mae_oracle_jpeg_decode(const uint8_t* data, int64_t n, uint8_t* rgb);
+/* The same image before the colour conversion: Y, Cb, Cr per pixel (chroma already repeated). */
+int32_t mae_oracle_jpeg_decode_ycc(const uint8_t* data, int64_t n, uint8_t* ycc);
+/* Dequantised coefficients in natural (row-major, [v][u]) order -> 64 samples, level-shifted by
+ * +128 and clamped to 0..255, row-major. */
+void mae_oracle_idct8x8(const int32_t coef[64], uint8_t out[64]);
+void mae_oracle_ycc_to_rgb(int32_t y, int32_t cb, int32_t cr, uint8_t rgb[3]);
+/* Canonical Huffman codes of a table given as the 16 counts of codes per length (DHT layout):
+ * code and length of the i-th symbol in the table's order.  Returns the number of symbols. */
+int32_t mae_oracle_huff_codes(const uint8_t counts[16], uint16_t* codes, uint8_t* lengths);
+
 int32_t mae_oracle_threads(void);
 
 #ifdef __cplusplus

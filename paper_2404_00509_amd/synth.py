@@ -135,3 +135,28 @@ def make_visible_rows(seed: int, M: int, D: int) -> np.ndarray:
 def make_ids(seed: int, M: int, L: int) -> np.ndarray:
     rng = np.random.default_rng([seed, 606, L])
     return rng.integers(0, L, M, dtype=np.int32)
+
+
+def make_jpegs(kind: str, B: int, seed: int = 0, quality: int = 90, subsampling: str = "4:2:0",
+               restart_rows: int = 1, optimize: bool = False):
+    """The images of make_images(kind, B, seed) as baseline JPEG files (Sec. 4.1: the dataset is
+    stored as JPEG at a chosen quality, 90 in the headline configuration), written by the imaging
+    library with one restart interval per row of MCUs.  Returns (files, offsets, sizes): the
+    concatenated bytes [sum] uint8, byte offsets [B] int64 and lengths [B] int32."""
+    import io
+
+    from PIL import Image
+
+    images, offs, hs, ws = make_images(kind, B, seed)
+    chunks, sizes = [], []
+    for b in range(B):
+        buf = io.BytesIO()
+        kw = {} if restart_rows <= 0 else {"restart_marker_rows": restart_rows}
+        Image.fromarray(image_view(images, offs, hs, ws, b)).save(
+            buf, format="JPEG", quality=quality, subsampling=subsampling, optimize=optimize, **kw)
+        chunks.append(np.frombuffer(buf.getvalue(), np.uint8))
+        sizes.append(chunks[-1].size)
+    sizes = np.asarray(sizes, np.int32)
+    offsets = np.zeros(B, np.int64)
+    offsets[1:] = np.cumsum(sizes.astype(np.int64))[:-1]
+    return np.concatenate(chunks), offsets, sizes

@@ -831,3 +831,172 @@ def test_prep_batch_with_finetune_augmentation_is_the_composition_of_its_steps(m
             px = out["target"][b].reshape(-1, 3).astype(np.float64) * std + mean
             assert px.max() <= 127 / 255 + 1e-6
     assert seen == {0, 1, 2}
+
+
+# ------------------------------------------------------------------------- baseline JPEG decoder
+def _encode(img, **kw):
+    import io
+
+    from PIL import Image
+    buf = io.BytesIO()
+    args = dict(format="JPEG", quality=90, subsampling="4:4:4", restart_marker_rows=1)
+    args.update(kw)
+    Image.fromarray(img).save(buf, **args)
+    return buf.getvalue()
+
+
+def _pil(data, mode="RGB", half=False):
+    import io
+
+    from PIL import Image
+    im = Image.open(io.BytesIO(data))
+    if mode == "YCbCr":  # the library's planes before its colour conversion
+        im.draft("YCbCr", (im.size[0] // 2, im.size[1] // 2) if half else im.size)
+        return np.array(im).astype(int)
+    return np.array(im.convert("RGB")).astype(int)
+
+
+def _photo(seed, h, w):
+    """Smooth colour ramps plus noise: every coefficient class occurs."""
+    img = synth._one_image("gradient", h, w, np.random.default_rng(seed))
+    return img
+
+
+def test_huffman_codes_are_the_canonical_ones():
+    # by hand: one code of length 2, two of length 3, one of length 4 -> 00, 010, 011, 1000
+    counts = [0, 1, 2, 1] + [0] * 12
+    assert oracle.huff_codes(counts) == [(0b00, 2), (0b010, 3), (0b011, 3), (0b1000, 4)]
+    rng = np.random.default_rng(41)
+    for _ in range(20):
+        # a random complete-or-not prefix code: draw lengths, keep the Kraft sum below one
+        counts, room = [0] * 16, 1.0
+        for length in range(1, 17):
+            most = int(room * 2 ** length) - (1 if length == 16 else 0)
+            counts[length - 1] = int(rng.integers(0, max(min(most, 12), 0) + 1))
+            room -= counts[length - 1] / 2 ** length
+        table = oracle.huff_codes(counts)
+        assert [length for _, length in table] == sorted(length for _, length in table)
+        words = [format(code, f"0{length}b") for code, length in table]
+        assert len(set(words)) == len(words)
+        for i, a in enumerate(words):          # prefix-free
+            assert not any(b.startswith(a) for j, b in enumerate(words) if j != i)
+        # increasing as binary fractions: the defining property of the canonical assignment
+        fr = [int(w, 2) / 2 ** len(w) for w in words]
+        assert fr == sorted(fr)
+        assert not words or set(words[0]) == {"0"}
+
+
+def test_idct_matches_the_library_transform():
+    from scipy.fft import idctn
+    rng = np.random.default_rng(42)
+    worst, total = 0, 0.0
+    for trial in range(300):
+        coef = np.zeros((8, 8))
+        k = int(rng.integers(1, 20))
+        coef.flat[rng.choice(64, k, replace=False)] = rng.integers(-300, 301, k)
+        coef[0, 0] = rng.integers(-1000, 1001)
+        want = idctn(coef, type=2, norm="ortho") + 128.0      # the standard's formula
+        got = oracle.idct8x8(coef.astype(np.int32)).astype(float)
+        inside = (want > 1) & (want < 254)
+        err = np.abs(got - np.rint(want))[inside]
+        assert err.max(initial=0) <= 1
+        # the fixed-point value stays within a tenth of a level of the real one before rounding
+        assert np.abs(got - want)[inside].max(initial=0) <= 0.6
+        worst = max(worst, err.max(initial=0))
+        total += err.mean() if err.size else 0.0
+    assert total / 300 < 0.05   # a few per cent of the samples round the other way
+    # a block with only the mean: flat, (F00 / 8) + 128 rounded
+    for f00 in (-1024, -8, -5, 0, 3, 8, 13, 800, 1016):   # no exact halves: ties may go either way
+        assert (oracle.idct8x8(np.array([[f00] + [0] * 7] + [[0] * 8] * 7)) ==
+                min(max(int(np.floor(f00 / 8 + 0.5)) + 128, 0), 255)).all()
+    # orientation: a coefficient in row v = 0, column u = 1 varies along x only
+    c = np.zeros((8, 8), np.int32)
+    c[0, 1] = 400
+    out = oracle.idct8x8(c).astype(int)
+    assert (out == out[0]).all() and out[0, 0] > out[0, 7]
+    np.testing.assert_array_equal(oracle.idct8x8(c.T), out.T)
+
+
+def test_colour_conversion_matches_the_jfif_matrix():
+    rng = np.random.default_rng(43)
+    for y, cb, cr in rng.integers(0, 256, (3000, 3)):
+        r = y + 1.402 * (cr - 128)
+        g = y - 0.344136 * (cb - 128) - 0.714136 * (cr - 128)
+        b = y + 1.772 * (cb - 128)
+        want = np.clip(np.rint([r, g, b]), 0, 255)
+        got = np.array(oracle.ycc_to_rgb(int(y), int(cb), int(cr)))
+        assert np.abs(got - want).max() <= 1, (y, cb, cr, got, want)
+    assert all(oracle.ycc_to_rgb(v, 128, 128) == (v, v, v) for v in range(256))
+    assert oracle.ycc_to_rgb(100, 128, 228) == (240, 29, 100)   # 100 + 140.2; 100 - 71.4136
+    assert oracle.ycc_to_rgb(100, 28, 128) == (100, 134, 0)     # 100 + 34.4136; 100 - 177.2 -> 0
+
+
+@pytest.mark.parametrize("sub,h,w", [("4:4:4", 61, 83), ("4:2:0", 61, 83), ("4:4:4", 128, 64),
+                                     ("4:2:0", 96, 112)])
+def test_jpeg_decoder_against_the_imaging_library(sub, h, w):
+    img = _photo(44, h, w)
+    data = _encode(img, subsampling=sub)
+    info = oracle.jpeg_info(data)
+    m = 16 if sub == "4:2:0" else 8
+    assert (info["H"], info["W"]) == (h, w)
+    assert (info["luma_h"], info["luma_v"]) == ((2, 2) if sub == "4:2:0" else (1, 1))
+    assert info["restart_interval"] == (w + m - 1) // m           # one row of MCUs
+    ours = oracle.jpeg_decode(data, ycc=True).astype(int)
+    lib_planes = _pil(data, "YCbCr")
+    # luma is untouched by upsampling: the two inverse transforms may round a sample differently
+    d = np.abs(ours[..., 0] - lib_planes[..., 0])
+    assert d.max() <= 1 and (d > 0).mean() < 0.08
+    if sub == "4:4:4":
+        d = np.abs(ours[..., 1:] - lib_planes[..., 1:])
+        assert d.max() <= 1 and (d > 0).mean() < 0.08
+        rgb = np.abs(oracle.jpeg_decode(data).astype(int) - _pil(data))
+        assert rgb.max() <= 4 and (rgb > 1).mean() < 0.03
+    else:
+        # the library at half size hands out the chroma samples as they are stored; here each
+        # of them is repeated over its 2 x 2 pixels
+        half = _pil(data, "YCbCr", half=True)
+        for c in (1, 2):
+            mine = ours[::2, ::2, c][:half.shape[0], :half.shape[1]]
+            d = np.abs(mine - half[:mine.shape[0], :mine.shape[1], c])
+            assert d.max() <= 1 and (d > 0).mean() < 0.08
+            np.testing.assert_array_equal(ours[0:h - h % 2:2, 0:w - w % 2:2, c],
+                                          ours[1:h:2, 1:w:2, c][:(h - h % 2) // 2, :(w - w % 2) // 2])
+
+
+def test_jpeg_decoder_does_not_depend_on_how_the_stream_is_organised():
+    img = _photo(45, 72, 100)
+    base = oracle.jpeg_decode(_encode(img, subsampling="4:2:0"))
+    # no restart markers, restart every two rows, tables optimised for the image: same pixels
+    for kw in (dict(restart_marker_rows=0), dict(restart_marker_rows=2), dict(optimize=True),
+               dict(restart_marker_blocks=3, restart_marker_rows=0)):
+        np.testing.assert_array_equal(oracle.jpeg_decode(_encode(img, subsampling="4:2:0", **kw)),
+                                      base, err_msg=str(kw))
+    # a flat image decodes flat, and to what the library decodes
+    flat = np.full((40, 56, 3), (200, 60, 90), np.uint8)
+    data = _encode(flat)
+    ours = oracle.jpeg_decode(data)
+    assert (ours == ours[0, 0]).all() and np.abs(ours[0, 0].astype(int) - _pil(data)[0, 0]).max() <= 1
+    # low quality: long zero runs and end-of-block codes everywhere
+    rough = _encode(img, quality=20)
+    assert np.abs(oracle.jpeg_decode(rough).astype(int) - _pil(rough)).max() <= 4
+
+
+def test_jpeg_decoder_rejects_what_it_does_not_decode():
+    img = _photo(46, 48, 48)
+    good = _encode(img)
+    with pytest.raises(ValueError):
+        oracle.jpeg_decode(_encode(img, progressive=True))
+    with pytest.raises(ValueError):
+        oracle.jpeg_decode(_encode(img[..., 0]))                   # one component
+    with pytest.raises(ValueError):
+        oracle.jpeg_decode(_encode(img, subsampling="4:2:2"))
+    with pytest.raises(ValueError):
+        oracle.jpeg_info(good[:100])                               # cut inside the tables
+    with pytest.raises(ValueError):
+        oracle.jpeg_info(b"\x00" + good[1:])
+    # a cut inside the entropy-coded data: decodes (zeros are supplied) or reports -3, never more
+    try:
+        out = oracle.jpeg_decode(good[:len(good) // 2] + b"\xff\xd9")
+        assert out.shape == img.shape
+    except ValueError:
+        pass
