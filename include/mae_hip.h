@@ -75,6 +75,25 @@ typedef enum { MAE_F32 = 0, MAE_BF16 = 1 } mae_dtype;
  *     that point; v <- clamp(s v + (1 - s) luma(v)); clamp is to [0, 255]. */
 typedef enum { MAE_AUG_SIMPLE = 0, MAE_AUG_THREE = 1, MAE_AUG_THREE_PLUS = 2 } mae_aug_mode;
 
+/* What `images` holds.
+ *   MAE_INPUT_DECODED  decoded pixels (see mae_prep_desc).
+ *   MAE_INPUT_JPEG     JPEG files, and only the region that the crop needs is decoded ("crop
+ *                      decode", Sec. 4.1): the rows of MCUs above and below the crop are skipped,
+ *                      a row is entropy-decoded up to the crop's right edge, and the inverse
+ *                      transform runs for the MCUs inside the crop only.  The result is the same
+ *                      as decoding the whole image first.
+ * Files the decoder takes: baseline sequential DCT, 8 bits, three components (JFIF YCbCr), luma
+ * sampled 1x1 or 2x2 against 1x1 chroma ("4:4:4", "4:2:0"), the two chroma components sharing
+ * their tables, ONE RESTART INTERVAL PER ROW OF MCUs (what makes the rows independent; a choice
+ * of the dataset writer), at most 64 rows of MCUs, and no side longer than max_image_side rounded
+ * up to 16 (in this mode the hint is a limit; 0 = 256).  Any other file makes its sample invalid
+ * (valid = 0 in crop_out, counted by mae_prep_status).  A decoder is specified by the standard
+ * only up to the accuracy of the inverse DCT, the chroma interpolation and the colour arithmetic;
+ * here: 13-bit fixed-point separable inverse DCT (first pass kept with 3 fractional bits, inputs
+ * of both passes clamped to +-32767), each chroma sample repeated over the pixels it covers,
+ * JFIF matrix in 16-bit fixed point (91881, 22554, 46802, 116130), floor after adding one half. */
+typedef enum { MAE_INPUT_DECODED = 0, MAE_INPUT_JPEG = 1 } mae_input_format;
+
 /* ------------------------------------------------------------------------------------------------
  * mae_prep_batch
  *
@@ -119,6 +138,10 @@ typedef struct {
   int32_t aug_mode;        /* mae_aug_mode.  Other than MAE_AUG_SIMPLE needs p % 4 == 0
                               (MAE_ERR_SHAPE otherwise)                                         */
   float jitter;            /* MAE_AUG_THREE_PLUS: strength in [0, 1], 0.3 in the paper            */
+  int32_t input_format;    /* mae_input_format.  MAE_INPUT_JPEG: `images` holds the files back to
+                              back, images_bytes their total size, offsets[b] the start of file
+                              b; heights and widths are not read (may be NULL)                   */
+  const int32_t* file_sizes; /* [B] length of each file in bytes; MAE_INPUT_JPEG only            */
 } mae_prep_desc;
 
 /* Outputs (device):

@@ -14,6 +14,8 @@ from .binding import (  # noqa: F401
     MAE_AUG_THREE_PLUS,
     MAE_BF16,
     MAE_F32,
+    MAE_INPUT_DECODED,
+    MAE_INPUT_JPEG,
     MaeEmbedDesc,
     MaeError,
     MaeLossDesc,

@@ -20,6 +20,7 @@ MAE_ERR_NULL, MAE_ERR_SHAPE, MAE_ERR_RANGE, MAE_ERR_DTYPE = -1, -2, -3, -4
 MAE_ERR_WORKSPACE, MAE_ERR_NO_DEVICE, MAE_ERR_HIP = -5, -6, -7
 MAE_F32, MAE_BF16 = 0, 1
 MAE_AUG_SIMPLE, MAE_AUG_THREE, MAE_AUG_THREE_PLUS = 0, 1, 2
+MAE_INPUT_DECODED, MAE_INPUT_JPEG = 0, 1
 
 IMAGENET_MEAN = (0.485, 0.456, 0.406)
 IMAGENET_STD = (0.229, 0.224, 0.225)
@@ -56,6 +57,8 @@ class MaePrepDesc(C.Structure):
         ("max_image_side", C.c_int32),
         ("aug_mode", C.c_int32),
         ("jitter", C.c_float),
+        ("input_format", C.c_int32),
+        ("file_sizes", C.c_void_p),
     ]
 
 
@@ -190,12 +193,23 @@ def _stream(stream):
 def make_prep_desc(images, offsets, heights, widths, *, out_size, patch, num_keep,
                    scale=(0.2, 1.0), ratio=(3.0 / 4.0, 4.0 / 3.0), flip_p=0.5, mean=IMAGENET_MEAN,
                    std=IMAGENET_STD, seed=0, batch_index=0, sample_base=0, noise_bits=32,
-                   out_dtype=MAE_F32, max_image_side=0, aug_mode=0, jitter=0.3) -> MaePrepDesc:
+                   out_dtype=MAE_F32, max_image_side=0, aug_mode=0, jitter=0.3,
+                   file_sizes=None) -> MaePrepDesc:
+    """Decoded input: images / offsets / heights / widths as device tensors.  JPEG input ("crop
+    decode"): images = the files back to back, offsets = their starts, file_sizes = their lengths
+    (int32); heights and widths are then ignored (pass None)."""
     d = MaePrepDesc()
-    d.B = int(heights.numel())
     d.images = images.data_ptr()
     d.images_bytes = int(images.numel())
-    d.offsets, d.heights, d.widths = offsets.data_ptr(), heights.data_ptr(), widths.data_ptr()
+    d.offsets = offsets.data_ptr()
+    if file_sizes is None:
+        d.B = int(heights.numel())
+        d.heights, d.widths = heights.data_ptr(), widths.data_ptr()
+        d.input_format = MAE_INPUT_DECODED
+    else:
+        d.B = int(file_sizes.numel())
+        d.file_sizes = file_sizes.data_ptr()
+        d.input_format = MAE_INPUT_JPEG
     d.out_size, d.patch, d.num_keep = out_size, patch, num_keep
     d.scale_lo, d.scale_hi = scale
     d.ratio_lo, d.ratio_hi = ratio

@@ -8,7 +8,7 @@ import sys
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 SOURCES = ["api.hip", "mask_params.hip", "crop_patch.hip", "normpix_loss.hip",
-           "patch_embed.hip", "three_aug.hip"]
+           "patch_embed.hip", "three_aug.hip", "jpeg_decode.hip"]
 OUT = os.path.join(_HERE, "libmae_hip.so")
 
 HIPCC_FLAGS = [

@@ -12,7 +12,7 @@
 
 namespace {
 
-constexpr int kVersion = 200;  // 0.2.0
+constexpr int kVersion = 300;  // 0.3.0
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -23,7 +23,11 @@ struct PrepShape {
 // Checks everything that can be checked without touching device memory.
 int validate_prep(const mae_prep_desc* d, PrepShape* shape) {
   if (!d) return MAE_ERR_NULL;
-  if (!d->images || !d->offsets || !d->heights || !d->widths) return MAE_ERR_NULL;
+  if (d->input_format != MAE_INPUT_DECODED && d->input_format != MAE_INPUT_JPEG)
+    return MAE_ERR_RANGE;
+  if (!d->images || !d->offsets) return MAE_ERR_NULL;
+  if (d->input_format == MAE_INPUT_DECODED && (!d->heights || !d->widths)) return MAE_ERR_NULL;
+  if (d->input_format == MAE_INPUT_JPEG && !d->file_sizes) return MAE_ERR_NULL;
   if (d->B <= 0 || d->out_size <= 0 || d->patch <= 0) return MAE_ERR_SHAPE;
   if (d->B > (1 << 20)) return MAE_ERR_RANGE;  // keeps every grid size below 2^31
   if (d->out_size % d->patch != 0) return MAE_ERR_SHAPE;
@@ -127,6 +131,10 @@ namespace {
 // starts on a 256-byte boundary.
 struct PrepWorkspace {
   size_t u8_offset, partials_offset, total;
+  // crop decode: per-file records, heights, widths, region widths, region offsets, regions
+  size_t recs_offset, heights_offset, widths_offset, region_widths_offset, region_offsets_offset,
+      regions_offset;
+  int slot_side;
 };
 PrepWorkspace prep_workspace(const mae_prep_desc* d) {
   auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
@@ -134,12 +142,26 @@ PrepWorkspace prep_workspace(const mae_prep_desc* d) {
   w.u8_offset = up(mae::kWorkspaceHeader + (size_t)d->B * sizeof(mae::CropRec));
   w.partials_offset = w.u8_offset;
   w.total = mae::kWorkspaceHeader + (size_t)d->B * sizeof(mae::CropRec);
+  w.recs_offset = w.heights_offset = w.widths_offset = w.region_widths_offset = 0;
+  w.region_offsets_offset = w.regions_offset = 0;
+  w.slot_side = 0;
   if (d->aug_mode != MAE_AUG_SIMPLE) {
     w.partials_offset = up(w.u8_offset + (size_t)d->B * d->out_size * d->out_size * 3);
     w.total = w.partials_offset;
     if (d->aug_mode == MAE_AUG_THREE_PLUS)
       w.total += (size_t)d->B * (d->out_size / d->patch) *
                  mae::three_aug_plan(d->out_size, d->patch).parts * sizeof(double);
+  }
+  if (d->input_format == MAE_INPUT_JPEG) {
+    const size_t B = (size_t)d->B;
+    w.slot_side = ((d->max_image_side > 0 ? d->max_image_side : 256) + 15) & ~15;
+    w.recs_offset = up(w.total);
+    w.heights_offset = up(w.recs_offset + B * sizeof(mae::JpegRec));
+    w.widths_offset = up(w.heights_offset + B * 4);
+    w.region_widths_offset = up(w.widths_offset + B * 4);
+    w.region_offsets_offset = up(w.region_widths_offset + B * 4);
+    w.regions_offset = up(w.region_offsets_offset + B * 8);
+    w.total = w.regions_offset + B * (size_t)w.slot_side * w.slot_side * 3;
   }
   return w;
 }
@@ -184,12 +206,41 @@ int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t
   pa.offsets = d->offsets;
   pa.heights = d->heights;
   pa.widths = d->widths;
+  const PrepWorkspace wsl = prep_workspace(d);
+  uint8_t* ws = static_cast<uint8_t*>(workspace);
+  mae::JpegArgs ja;
+  memset(&ja, 0, sizeof(ja));
+  if (d->input_format == MAE_INPUT_JPEG) {
+    // file headers first: the crop parameters need the image sizes
+    ja.B = d->B;
+    ja.slot_side = wsl.slot_side;
+    ja.files = d->images;
+    ja.files_bytes = d->images_bytes;
+    ja.offsets = d->offsets;
+    ja.sizes = d->file_sizes;
+    ja.recs = reinterpret_cast<mae::JpegRec*>(ws + wsl.recs_offset);
+    ja.heights = reinterpret_cast<int32_t*>(ws + wsl.heights_offset);
+    ja.widths = reinterpret_cast<int32_t*>(ws + wsl.widths_offset);
+    ja.region_offsets = reinterpret_cast<int64_t*>(ws + wsl.region_offsets_offset);
+    ja.region_widths = reinterpret_cast<int32_t*>(ws + wsl.region_widths_offset);
+    ja.regions = ws + wsl.regions_offset;
+    ja.workspace = ws;
+    ja.crop_out = crop_out;
+    if (mae::launch_jpeg_header(ja, stream) != hipSuccess) return MAE_ERR_HIP;
+    // from here on the "images" are the slots of the decoded-region buffer
+    pa.images_bytes = (int64_t)d->B * wsl.slot_side * wsl.slot_side * 3;
+    pa.offsets = ja.region_offsets;
+    pa.heights = ja.heights;
+    pa.widths = ja.widths;
+  }
   pa.mask = mask;
   pa.ids_restore = ids_restore;
   pa.ids_keep = ids_keep;
   pa.crop_out = crop_out;
   pa.workspace = static_cast<uint8_t*>(workspace);
   if (mae::launch_params_mask(pa, stream) != hipSuccess) return MAE_ERR_HIP;
+  if (d->input_format == MAE_INPUT_JPEG && mae::launch_jpeg_decode(ja, stream) != hipSuccess)
+    return MAE_ERR_HIP;
 
   mae::CropArgs ca;
   memset(&ca, 0, sizeof(ca));
@@ -202,7 +253,9 @@ int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t
   ca.D = sh.D;
   ca.visible_bf16 = d->out_dtype == MAE_BF16;
   const mae::CropPlan plan = mae::crop_plan(
-      d->out_size, d->patch, d->max_image_side > 0 ? d->max_image_side : 256, 0);
+      d->out_size, d->patch,
+      d->input_format == MAE_INPUT_JPEG ? wsl.slot_side
+                                        : (d->max_image_side > 0 ? d->max_image_side : 256), 0);
   ca.tile_pixels = plan.tile_pixels;
   ca.col_parts = plan.col_parts;
   ca.part_patches = plan.part_patches;
@@ -214,6 +267,12 @@ int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t
   ca.images_bytes = d->images_bytes;
   ca.offsets = d->offsets;
   ca.widths = d->widths;
+  if (d->input_format == MAE_INPUT_JPEG) {
+    ca.images = ja.regions;
+    ca.images_bytes = pa.images_bytes;
+    ca.offsets = ja.region_offsets;
+    ca.widths = ja.region_widths;
+  }
   ca.ids_restore = ids_restore;
   ca.workspace = static_cast<const uint8_t*>(workspace);
   ca.visible = visible;
@@ -225,8 +284,6 @@ int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t
 
   // finetuning augmentation: the resampling kernel leaves the rounded 8-bit crop in the
   // workspace, a second kernel applies the per-image operation and writes the patch rows
-  const PrepWorkspace wsl = prep_workspace(d);
-  uint8_t* ws = static_cast<uint8_t*>(workspace);
   ca.u8_out = ws + wsl.u8_offset;
   if (mae::launch_crop_patch(ca, stream) != hipSuccess) return MAE_ERR_HIP;
   mae::AugArgs aa;

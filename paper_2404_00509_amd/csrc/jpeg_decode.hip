@@ -1,0 +1,441 @@
+// Crop decode (Sec. 4.1 "Crop Decode"): the loader's images are JPEG files, and only the region
+// that the random crop needs is decoded.  Baseline sequential DCT (ITU-T T.81), 8 bits, three
+// components (JFIF YCbCr), luma sampled 1x1 or 2x2 against 1x1 chroma, tables as found in the file,
+// and one restart interval per row of MCUs -- the dataset writer's choice, which is what makes the
+// rows independent: the rows of MCUs above and below the crop are never touched, a row is entropy-
+// decoded only up to the crop's right edge, and the inverse transform runs only for the MCUs
+// inside it.
+//
+//  * jpeg_header_kernel: one lane per file walks the marker segments and leaves a record (size,
+//    sampling, restart interval, where the tables and the entropy-coded data start) plus the
+//    image's height and width for the crop-parameter kernel.
+//  * jpeg_decode_kernel: one wavefront per image.  The lanes first find the restart markers (16
+//    bytes per lane and step, positions ranked with a ballot), then lane r decodes MCU row
+//    first_row + r: canonical Huffman codes bit by bit (Annex F of the standard), DC prediction,
+//    zero runs, de-quantisation on insertion, fixed-point separable inverse DCT, repeated chroma,
+//    fixed-point JFIF colour matrix.  RGB bytes go to the image's slot of the decoded-region
+//    buffer, whose rows are the region's rows; the crop record is rewritten relative to the region.
+//
+// The integer arithmetic of the inverse DCT and of the colour conversion is part of the
+// definition of the output (a decoder is only specified up to that): 13-bit cosines, first pass
+// kept with 3 fractional bits, both passes' inputs clamped to +-32767, floor after adding one half.
+//
+// Every read of file bytes is clamped into the file, every table index is masked, and every loop
+// has a fixed bound, so a corrupt file gives wrong pixels or a sample flagged invalid, nothing else.
+#include "mae_device.hpp"
+#include "mae_kernels.hpp"
+
+namespace mae {
+
+constexpr int kJpegThreads = 64;  // one wavefront per image
+
+__constant__ uint8_t kZigzag[64] = {
+    0,  1,  8,  16, 9,  2,  3,  10, 17, 24, 32, 25, 18, 11, 4,  5,  12, 19, 26, 33, 40, 48,
+    41, 34, 27, 20, 13, 6,  7,  14, 21, 28, 35, 42, 49, 56, 57, 50, 43, 36, 29, 22, 15, 23,
+    30, 37, 44, 51, 58, 59, 52, 45, 38, 31, 39, 46, 53, 60, 61, 54, 47, 55, 62, 63};
+
+// C(u) cos((2x+1) u pi / 16) * 2^13 rounded, C(0) = 1/sqrt 2: row x, column u
+__constant__ int16_t kBasis[64] = {
+    5793, 8035,  7568,  6811,  5793,  4551,  3135,  1598,   //
+    5793, 6811,  3135,  -1598, -5793, -8035, -7568, -4551,  //
+    5793, 4551,  -3135, -8035, -5793, 1598,  7568,  6811,   //
+    5793, 1598,  -7568, -4551, 5793,  6811,  -3135, -8035,  //
+    5793, -1598, -7568, 4551,  5793,  -6811, -3135, 8035,   //
+    5793, -4551, -3135, 8035,  -5793, -1598, 7568,  -6811,  //
+    5793, -6811, 3135,  1598,  -5793, 8035,  -7568, 4551,   //
+    5793, -8035, 7568,  -6811, 5793,  -4551, 3135,  -1598};
+
+__device__ static inline int be16(const uint8_t* p) { return ((int)p[0] << 8) | (int)p[1]; }
+
+// ---- header ----------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kJpegThreads) void jpeg_header_kernel(JpegArgs a) {
+  const int b = (int)(blockIdx.x * kJpegThreads + threadIdx.x);
+  if (b >= a.B) return;
+  JpegRec rec;
+  memset(&rec, 0, sizeof(rec));
+  int H = 1, W = 1;  // what the crop-parameter kernel sees for an unusable file
+  const int64_t off = a.offsets[b];
+  const int64_t n = (int64_t)a.sizes[b];
+  bool ok = off >= 0 && n >= 4 && off + n <= a.files_bytes;
+  if (ok) {
+    const uint8_t* d = a.files + off;
+    ok = d[0] == 0xFF && d[1] == 0xD8;
+    int64_t pos = 2;
+    bool have_frame = false, have_scan = false;
+    int tq[3] = {0, 0, 0}, cid[3] = {0, 0, 0};
+    int q_off[4] = {0, 0, 0, 0}, dc_off[4] = {0, 0, 0, 0}, ac_off[4] = {0, 0, 0, 0};
+    for (int seg = 0; seg < 64 && ok && !have_scan; ++seg) {
+      if (pos + 4 > n || d[pos] != 0xFF) {
+        ok = false;
+        break;
+      }
+      const int m = d[pos + 1];
+      if (m == 0xFF) {
+        ++pos;
+        continue;
+      }
+      const int len = be16(d + pos + 2);
+      if (len < 2 || pos + 2 + len > n) {
+        ok = false;
+        break;
+      }
+      const uint8_t* s = d + pos + 4;
+      const int body = len - 2;
+      if (m == 0xDB) {
+        for (int o = 0; o + 65 <= body; o += 65) {
+          const int pq = s[o] >> 4, t = s[o] & 15;
+          if (pq != 0 || t > 3) {
+            ok = false;
+            break;
+          }
+          q_off[t] = (int)(pos + 4 + o + 1);
+        }
+      } else if (m == 0xC0) {
+        if (body < 15 || s[0] != 8 || s[5] != 3) {
+          ok = false;
+          break;
+        }
+        H = be16(s + 1);
+        W = be16(s + 3);
+        int hs[3], vs[3];
+        for (int c = 0; c < 3; ++c) {
+          cid[c] = s[6 + 3 * c];
+          hs[c] = s[7 + 3 * c] >> 4;
+          vs[c] = s[7 + 3 * c] & 15;
+          tq[c] = s[8 + 3 * c] & 3;
+        }
+        ok = H >= 1 && W >= 1 && hs[1] == 1 && vs[1] == 1 && hs[2] == 1 && vs[2] == 1 &&
+             ((hs[0] == 1 && vs[0] == 1) || (hs[0] == 2 && vs[0] == 2));
+        rec.hs = hs[0];
+        have_frame = true;
+      } else if (m >= 0xC1 && m <= 0xCF && m != 0xC4 && m != 0xC8 && m != 0xCC) {
+        ok = false;
+      } else if (m == 0xC4) {
+        int o = 0;
+        for (int t = 0; t < 8 && o + 17 <= body; ++t) {
+          const int tc = s[o] >> 4, th = s[o] & 15;
+          int total = 0;
+          for (int i = 0; i < 16; ++i) total += s[o + 1 + i];
+          if (tc > 1 || th > 3 || total > 256 || o + 17 + total > body) {
+            ok = false;
+            break;
+          }
+          (tc ? ac_off : dc_off)[th] = (int)(pos + 4 + o + 1);
+          o += 17 + total;
+        }
+      } else if (m == 0xDD) {
+        rec.restart = body >= 2 ? be16(s) : 0;
+      } else if (m == 0xDA) {
+        if (!have_frame || body < 10 || s[0] != 3 || s[7] != 0 || s[8] != 63) {
+          ok = false;
+          break;
+        }
+        for (int c = 0; c < 3; ++c) {
+          const int td = s[2 + 2 * c] >> 4, ta = s[2 + 2 * c] & 15;
+          if (s[1 + 2 * c] != cid[c] || td > 3 || ta > 3 || !dc_off[td] || !ac_off[ta] ||
+              !q_off[tq[c]])
+            ok = false;
+          // luma tables first, the two chroma components share theirs in files we accept
+          if (c < 2) {
+            rec.dc_off[c] = dc_off[td & 3];
+            rec.ac_off[c] = ac_off[ta & 3];
+            rec.q_off[c] = q_off[tq[c]];
+          } else if (dc_off[td & 3] != rec.dc_off[1] || ac_off[ta & 3] != rec.ac_off[1] ||
+                     q_off[tq[c]] != rec.q_off[1]) {
+            ok = false;
+          }
+        }
+        rec.scan_off = (int)(pos + 2 + len);
+        have_scan = true;
+      } else if (m == 0xD9) {
+        ok = false;
+      }
+      pos += 2 + len;
+    }
+    ok = ok && have_scan;
+  }
+  if (ok) {
+    const int mcu = 8 * rec.hs;
+    rec.mcux = (W + mcu - 1) / mcu;
+    rec.mcuy = (H + mcu - 1) / mcu;
+    // rows must be independent, and the image has to fit its slot of the region buffer
+    ok = rec.restart == rec.mcux && rec.mcuy <= kJpegThreads && rec.mcux * mcu <= a.slot_side &&
+         rec.mcuy * mcu <= a.slot_side;
+  }
+  if (!ok) {
+    H = 1;
+    W = 1;
+  }
+  rec.H = H;
+  rec.W = W;
+  rec.size = ok ? (int)n : 0;
+  rec.valid = ok ? 1 : 0;
+  a.recs[b] = rec;
+  a.heights[b] = H;
+  a.widths[b] = W;
+  a.region_offsets[b] = (int64_t)b * a.slot_side * a.slot_side * 3;
+  a.region_widths[b] = 1;
+}
+
+// ---- entropy decoding ------------------------------------------------------------------------------
+struct BitReader {
+  const uint8_t* d;  // file
+  int n;             // file size
+  int pos;           // next byte
+  uint32_t acc;
+  int nbits;
+  bool ended;  // a marker was reached: zero bits from here on
+};
+
+__device__ static inline int next_bit(BitReader& r) {
+  if (r.nbits == 0) {
+    uint32_t byte = 0;
+    if (!r.ended && r.pos < r.n) {
+      byte = r.d[r.pos];
+      if (byte == 0xFF) {
+        if (r.pos + 1 < r.n && r.d[r.pos + 1] == 0x00) {
+          r.pos += 2;
+        } else {
+          r.ended = true;
+          byte = 0;
+        }
+      } else {
+        r.pos += 1;
+      }
+    }
+    r.acc = byte;
+    r.nbits = 8;
+  }
+  r.nbits -= 1;
+  return (int)((r.acc >> r.nbits) & 1u);
+}
+
+__device__ static inline int receive_extend(BitReader& r, int s) {
+  int v = 0;
+  for (int i = 0; i < s; ++i) v = (v << 1) | next_bit(r);
+  return (s && v < (1 << (s - 1))) ? v - (1 << s) + 1 : v;
+}
+
+// One table in LDS: counts per length, first code and first symbol index per length, symbols.
+struct HuffLds {
+  uint8_t counts[16];
+  uint16_t first_code[16];
+  uint16_t first_index[16];
+  uint8_t symbols[256];
+};
+
+__device__ static inline int huff_decode(BitReader& r, const HuffLds& t) {
+  int code = 0;
+  for (int len = 0; len < 16; ++len) {
+    code = (code << 1) | next_bit(r);
+    const int k = code - (int)t.first_code[len];
+    if (k >= 0 && k < (int)t.counts[len]) return t.symbols[((int)t.first_index[len] + k) & 255];
+  }
+  return -1;
+}
+
+// Dequantised coefficients (natural order, 16-bit) -> 64 samples; the caller's lane-private LDS.
+__device__ static inline void idct8x8(const int16_t* coef, uint8_t* out) {
+  int tmp[64];
+#pragma unroll 1
+  for (int u = 0; u < 8; ++u) {
+    int c[8];
+#pragma unroll
+    for (int v = 0; v < 8; ++v) c[v] = coef[v * 8 + u];
+#pragma unroll
+    for (int y = 0; y < 8; ++y) {
+      int acc = 0;
+#pragma unroll
+      for (int v = 0; v < 8; ++v) acc += __mul24((int)kBasis[y * 8 + v], c[v]);
+      tmp[y * 8 + u] = min(max((acc + (1 << 10)) >> 11, -32767), 32767);
+    }
+  }
+#pragma unroll 1
+  for (int y = 0; y < 8; ++y) {
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
+      int acc = 0;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc += __mul24((int)kBasis[x * 8 + u], tmp[y * 8 + u]);
+      out[y * 8 + x] = (uint8_t)min(max(((acc + (1 << 16)) >> 17) + 128, 0), 255);
+    }
+  }
+}
+
+__device__ static inline uint32_t ycc_to_rgbx(int y, int cb, int cr) {
+  const int b = cb - 128, r = cr - 128;
+  const int R = min(max(y + ((91881 * r + 32768) >> 16), 0), 255);
+  const int G = min(max(y - ((22554 * b + 46802 * r + 32768) >> 16), 0), 255);
+  const int B = min(max(y + ((116130 * b + 32768) >> 16), 0), 255);
+  return (uint32_t)R | ((uint32_t)G << 8) | ((uint32_t)B << 16);
+}
+
+struct JpegLds {
+  HuffLds dc[2], ac[2];  // luma, chroma
+  uint8_t q[2][64];      // zig-zag order
+  int row_start[kJpegThreads];
+  int16_t coef[kJpegThreads][64];    // one block per lane
+  uint8_t pix[kJpegThreads][6][64];  // the blocks of one MCU per lane: Y (1 or 4), Cb, Cr
+};
+
+__global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
+  __shared__ JpegLds s;
+  const int b = (int)blockIdx.x;
+  const int lane = threadIdx.x;
+  const JpegRec rec = a.recs[b];
+  CropRec* crop = reinterpret_cast<CropRec*>(a.workspace + kWorkspaceHeader) + b;
+  CropRec cr = *crop;
+  if (!rec.valid) {
+    if (lane == 0) {
+      crop->valid = 0;
+      if (a.crop_out) a.crop_out[(int64_t)b * 6 + 5] = 0;
+    }
+    return;
+  }
+  if (!cr.valid) return;
+  const uint8_t* d = a.files + a.offsets[b];
+  const int n = rec.size;
+  const int mcu = 8 * rec.hs;
+  // rows and columns of MCUs that the crop touches
+  const int my0 = cr.top / mcu, my1 = min((cr.top + cr.ch - 1) / mcu, rec.mcuy - 1);
+  const int mx0 = cr.left / mcu, mx1 = min((cr.left + cr.cw - 1) / mcu, rec.mcux - 1);
+  const int nrows = my1 - my0 + 1;
+  const int region_w = (mx1 - mx0 + 1) * mcu;
+
+  // tables: one lane per length / symbol
+  for (int t = 0; t < 4; ++t) {
+    HuffLds& h = t < 2 ? s.dc[t] : s.ac[t - 2];
+    const int o = t < 2 ? rec.dc_off[t] : rec.ac_off[t - 2];
+    if (lane < 16) h.counts[lane] = d[min(o + lane, n - 1)];
+    for (int i = lane; i < 256; i += kJpegThreads) h.symbols[i] = d[min(o + 16 + i, n - 1)];
+  }
+  for (int i = lane; i < 128; i += kJpegThreads)
+    s.q[i >> 6][i & 63] = d[min(rec.q_off[i >> 6] + (i & 63), n - 1)];
+  __syncthreads();
+  if (lane < 4) {
+    HuffLds& h = lane < 2 ? s.dc[lane] : s.ac[lane - 2];
+    int code = 0, index = 0;
+    for (int len = 0; len < 16; ++len) {
+      h.first_code[len] = (uint16_t)code;
+      h.first_index[len] = (uint16_t)index;
+      code = (code + h.counts[len]) << 1;
+      index += h.counts[len];
+    }
+  }
+
+  // restart markers: marker m (0-based) ends MCU row m; row r starts after marker r - 1
+  s.row_start[lane] = -1;
+  __syncthreads();
+  int seen = 0;  // markers before the current step
+  for (int base = rec.scan_off; base < n - 1 && seen <= my1; base += kJpegThreads * 16) {
+    int mine[16], cnt = 0;
+    const int p0 = base + lane * 16;
+    for (int i = 0; i < 16; ++i) {
+      const int p = p0 + i;
+      if (p + 1 < n && d[p] == 0xFF && (d[p + 1] & 0xF8) == 0xD0) mine[cnt++] = p;
+    }
+    // rank of this lane's first marker among the wavefront's: counts of the lanes before it
+    int before = cnt;
+    for (int off = 1; off < kWave; off <<= 1) {
+      const int t = __shfl_up(before, off);
+      if (lane >= off) before += t;
+    }
+    const int total = __shfl(before, kWave - 1);
+    before -= cnt;
+    for (int i = 0; i < cnt; ++i) {
+      const int row = seen + before + i + 1;  // the row that starts after this marker
+      if (row >= my0 && row <= my1) s.row_start[row - my0] = mine[i] + 2;
+    }
+    seen += total;
+  }
+  if (my0 == 0 && lane == 0) s.row_start[0] = rec.scan_off;
+  __syncthreads();
+
+  // region geometry for the resampling kernel
+  uint8_t* region = a.regions + a.region_offsets[b];
+  if (lane == 0) {
+    a.region_widths[b] = region_w;
+    crop->top = cr.top - my0 * mcu;
+    crop->left = cr.left - mx0 * mcu;
+  }
+  if (lane >= nrows) return;
+
+  BitReader r = {d, n, my0 + lane == 0 ? rec.scan_off : s.row_start[lane], 0u, 0, false};
+  const bool found = my0 + lane == 0 || (r.pos > rec.scan_off && r.pos <= n);
+  if (!found) r.ended = true;  // marker missing: the row decodes to a flat block pattern
+  int pred[3] = {0, 0, 0};
+  const int nblk = rec.hs * rec.hs;  // luma blocks per MCU
+  int16_t* coef = s.coef[lane];
+  bool bad = !found;
+  for (int mx = 0; mx <= mx1; ++mx) {
+    const bool want = mx >= mx0;
+    for (int blk = 0; blk < nblk + 2; ++blk) {
+      const int c = blk < nblk ? 0 : blk - nblk + 1;  // component
+      const int t = c ? 1 : 0;                        // table set
+      if (want)
+        for (int i = 0; i < 64; ++i) coef[i] = 0;
+      int sym = huff_decode(r, s.dc[t]);
+      if (sym < 0 || sym > 11) {
+        bad = true;
+        sym = 0;
+      }
+      pred[c] += receive_extend(r, sym);
+      if (want) coef[0] = (int16_t)min(max(pred[c] * (int)s.q[t][0], -32767), 32767);
+      for (int k = 1; k < 64;) {
+        const int rs = huff_decode(r, s.ac[t]);
+        if (rs < 0) {
+          bad = true;
+          break;
+        }
+        const int run = rs >> 4, size = rs & 15;
+        if (size == 0) {
+          if (run != 15) break;
+          k += 16;
+          continue;
+        }
+        k += run;
+        if (k > 63) {
+          bad = true;
+          break;
+        }
+        const int v = receive_extend(r, size);
+        if (want) coef[kZigzag[k]] = (int16_t)min(max(v * (int)s.q[t][k], -32767), 32767);
+        ++k;
+      }
+      if (want) idct8x8(coef, s.pix[lane][blk < nblk ? blk : 4 + (blk - nblk)]);
+    }
+    if (!want) continue;
+    // colour conversion of the MCU into the region's rows; chroma repeated over hs x hs pixels
+    const int x0 = (mx - mx0) * mcu, y0 = lane * mcu;
+    for (int y = 0; y < mcu; ++y) {
+      uint8_t* dst = region + ((int64_t)(y0 + y) * region_w + x0) * 3;
+      for (int x = 0; x < mcu; ++x) {
+        const int yb = (y >> 3) * rec.hs + (x >> 3);  // luma block inside the MCU
+        const int Y = s.pix[lane][yb][(y & 7) * 8 + (x & 7)];
+        const int ci = (y / rec.hs) * 8 + (x / rec.hs);
+        const uint32_t px = ycc_to_rgbx(Y, s.pix[lane][4][ci], s.pix[lane][5][ci]);
+        dst[3 * x] = (uint8_t)px;
+        dst[3 * x + 1] = (uint8_t)(px >> 8);
+        dst[3 * x + 2] = (uint8_t)(px >> 16);
+      }
+    }
+  }
+  if (bad) {
+    crop->valid = 0;
+    if (a.crop_out) a.crop_out[(int64_t)b * 6 + 5] = 0;
+  }
+}
+
+hipError_t launch_jpeg_header(const JpegArgs& a, hipStream_t stream) {
+  dim3 grid((uint32_t)((a.B + kJpegThreads - 1) / kJpegThreads)), block(kJpegThreads);
+  hipLaunchKernelGGL(jpeg_header_kernel, grid, block, 0, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_jpeg_decode(const JpegArgs& a, hipStream_t stream) {
+  dim3 grid((uint32_t)a.B), block(kJpegThreads);
+  hipLaunchKernelGGL(jpeg_decode_kernel, grid, block, 0, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace mae

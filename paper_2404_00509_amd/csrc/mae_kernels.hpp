@@ -80,6 +80,37 @@ struct AugPlan {
 AugPlan three_aug_plan(int S, int p);
 hipError_t launch_three_aug(const AugArgs& a, hipStream_t stream);
 
+// ---- crop decode of baseline JPEG files ----------------------------------------------------------
+struct JpegRec {
+  int32_t H, W;
+  int32_t hs;               // luma sampling factor (1 or 2, both directions)
+  int32_t restart;          // restart interval in MCUs
+  int32_t mcux, mcuy;       // MCUs per row / rows of MCUs
+  int32_t scan_off, size;   // first entropy-coded byte, file length
+  int32_t valid;
+  int32_t dc_off[2], ac_off[2], q_off[2];  // luma, chroma: offsets of the table bodies in the file
+  int32_t pad;
+};
+static_assert(sizeof(JpegRec) == 64, "JpegRec is 64 bytes");
+struct JpegArgs {
+  int32_t B;
+  int32_t slot_side;  // the decoded-region buffer holds slot_side^2 * 3 bytes per image
+  const uint8_t* files;
+  int64_t files_bytes;
+  const int64_t* offsets;
+  const int32_t* sizes;
+  JpegRec* recs;
+  int32_t* heights;
+  int32_t* widths;
+  int64_t* region_offsets;
+  int32_t* region_widths;
+  uint8_t* regions;
+  uint8_t* workspace;  // header + CropRec[B]
+  int32_t* crop_out;   // nullable, [B,6]: the valid flag is cleared for files that cannot be used
+};
+hipError_t launch_jpeg_header(const JpegArgs& a, hipStream_t stream);
+hipError_t launch_jpeg_decode(const JpegArgs& a, hipStream_t stream);
+
 // ---- normalised-pixel loss ---------------------------------------------------------------------
 struct LossArgs {
   int64_t rows;  // B * L
