@@ -51,3 +51,102 @@ def test_crop_decode_matches_full_decode(sub, kind, S):
     buf, _ = _gpu_jpeg_prep(files, offsets, sizes, **kw)
     assert mae.mae_prep_status(buf.workspace) == 0
     check_prep_against_oracle(prep_to_numpy(buf), ref, what=f"{kind} {sub}")
+
+
+def test_whole_image_and_tiny_crops():
+    """Scale range at its ends: the crop is the whole image (every row and column of MCUs is
+    decoded), or a few per cent of it (most of the file is skipped)."""
+    B, S = 12, 96
+    files, offsets, sizes = synth.make_jpegs("gradient", B, seed=61)
+    decoded = _decode_all(files, offsets, sizes)
+    L = (S // 16) ** 2
+    for scale, ratio in (((1.0, 1.0), (1.0, 1.0)), ((0.02, 0.05), (0.75, 4 / 3))):
+        kw = dict(out_size=S, patch=16, num_keep=L, scale=scale, ratio=ratio, seed=14,
+                  batch_index=2)
+        ref = oracle.prep_batch(*decoded, **kw)
+        buf, _ = _gpu_jpeg_prep(files, offsets, sizes, **kw)
+        check_prep_against_oracle(prep_to_numpy(buf), ref, what=f"scale {scale}")
+
+
+def test_bf16_tokens_and_finetune_augmentation_from_jpeg():
+    B, S = 12, 160
+    files, offsets, sizes = synth.make_jpegs("gradient", B, seed=62, quality=75)
+    decoded = _decode_all(files, offsets, sizes)
+    L = (S // 16) ** 2
+    kw = dict(out_size=S, patch=16, num_keep=L, seed=15, batch_index=0,
+              aug_mode=mae.MAE_AUG_THREE_PLUS, jitter=0.3)
+    ref = oracle.prep_batch(*decoded, **kw)
+    buf, _ = _gpu_jpeg_prep(files, offsets, sizes, bf16=True, **kw)
+    check_prep_against_oracle(prep_to_numpy(buf), ref, bf16=True, what="jpeg + 3 Aug+")
+
+
+def test_files_the_decoder_does_not_take_are_flagged_and_the_rest_is_untouched():
+    import io
+
+    from PIL import Image
+    B, S = 8, 64
+    imgs = synth.make_images("uniform", B, seed=63)
+
+    def enc(b, **kw):
+        buf = io.BytesIO()
+        args = dict(format="JPEG", quality=90, subsampling="4:2:0", restart_marker_rows=1)
+        args.update(kw)
+        Image.fromarray(synth.image_view(*imgs, b)).save(buf, **args)
+        return np.frombuffer(buf.getvalue(), np.uint8)
+
+    good = [enc(b) for b in range(B)]
+    bad = {1: enc(1, restart_marker_rows=0),          # rows not independent
+           3: enc(3, progressive=True),
+           4: good[4][:200].copy(),                   # cut inside the tables
+           6: enc(6, subsampling="4:2:2")}
+    chunks = [bad.get(b, good[b]) for b in range(B)]
+    # a file whose entropy-coded data is cut short: decodes (zero bits are supplied), no fault
+    chunks[7] = np.concatenate([good[7][:len(good[7]) * 2 // 3], np.array([0xFF, 0xD9], np.uint8)])
+    sizes = np.array([c.size for c in chunks], np.int32)
+    offsets = np.zeros(B, np.int64)
+    offsets[1:] = np.cumsum(sizes.astype(np.int64))[:-1]
+    files = np.concatenate(chunks)
+    L = (S // 16) ** 2
+    kw = dict(out_size=S, patch=16, num_keep=L, seed=16, batch_index=3)
+    buf, _ = _gpu_jpeg_prep(files, offsets, sizes, **kw)
+    crop = buf.crop.cpu().numpy()
+    flagged = sorted(int(b) for b in np.nonzero(crop[:, 5] == 0)[0])
+    assert set(bad) <= set(flagged) <= set(bad) | {7}
+    assert mae.mae_prep_status(buf.workspace) == len(flagged)
+    # the good files give what they give on their own
+    keep = [b for b in range(B) if b not in flagged]
+    g_sizes = np.array([good[b].size for b in range(B)], np.int32)
+    g_offsets = np.zeros(B, np.int64)
+    g_offsets[1:] = np.cumsum(g_sizes.astype(np.int64))[:-1]
+    ref = oracle.prep_batch(*_decode_all(np.concatenate(good), g_offsets, g_sizes), **kw)
+    got = prep_to_numpy(buf, rows=keep)
+    sel = {k: (v[keep] if v is not None else None) for k, v in ref.items()}
+    check_prep_against_oracle(got, sel, what="good files next to bad ones")
+    # flagged samples leave their outputs untouched
+    for b in set(bad):
+        assert torch.isnan(buf.target[b]).all()
+
+
+def test_crop_decode_full_size_sampled():
+    """The bench's launch: 4096 files (max side 256, quality 90, 4:2:0) -> 224 px."""
+    wl = synth.WORKLOADS["c4"]
+    files, offsets, sizes = synth.make_jpegs(wl.kind, wl.B, seed=0)
+    K = oracle.num_keep(wl.L, wl.mask_ratio)
+    kw = dict(out_size=wl.out_size, patch=wl.patch, num_keep=K, seed=5, batch_index=9)
+    buf, _ = _gpu_jpeg_prep(files, offsets, sizes, **kw)
+    assert mae.mae_prep_status(buf.workspace) == 0
+    assert torch.isfinite(buf.target).all()
+    rows = [0, 1, 2, 2047, 2048, 4094, 4095]
+    sub = _decode_all(files, offsets[rows], sizes[rows])
+    # the oracle keys its draws by the sample index: run it once per sampled image
+    for i, b in enumerate(rows):
+        imgs, offs, hs, ws = sub
+        img = imgs[offs[i]:offs[i] + int(hs[i]) * int(ws[i]) * 3]
+        # a batch whose image b is the decoded one; the b images before it are 1 x 1 dummies
+        heights_b = np.concatenate([np.ones(b, np.int32), hs[i:i + 1]])
+        widths_b = np.concatenate([np.ones(b, np.int32), ws[i:i + 1]])
+        images = np.concatenate([np.zeros(3 * b, np.uint8), img])
+        offsets_b = np.concatenate([3 * np.arange(b, dtype=np.int64), [3 * b]])
+        ref = oracle.prep_batch(images, offsets_b, heights_b, widths_b, b_begin=b, b_end=b + 1,
+                                **kw)
+        check_prep_against_oracle(prep_to_numpy(buf, rows=[b]), ref, what=f"image {b}")
