@@ -8,7 +8,8 @@ gradient), on synthetic images already resident in HBM.  Prints ONE JSON line.
 
 The first consumer of the path's output, mae_patch_embed, and the finetuning-mode input pipeline
 ("3 Aug", "3 Aug+") are timed by themselves after the steps and reported under "patch_embed" and
-"finetune_prep"; they are not part of the step or of `value`.
+"finetune_prep", and so is the input pipeline on JPEG files ("crop decode", under "jpeg_prep");
+they are not part of the step or of `value`.
 """
 from __future__ import annotations
 
@@ -198,6 +199,48 @@ def time_finetune(args, mae, torch, dev, wl):
     return rows
 
 
+def time_jpeg(args, mae, synth, torch, wl, K):
+    """mae_prep_batch fed with JPEG files ("crop decode", Sec. 4.1): the same batch written as
+    baseline JPEG (quality 90, 4:2:0, one restart interval per row of MCUs), timed by itself with
+    events on the launch stream.  Not part of the step above."""
+    import numpy as np
+
+    t0 = time.time()
+    files, offsets, sizes = synth.make_jpegs(wl.kind, wl.B, seed=0)
+    enc_s = time.time() - t0
+    dev = [torch.from_numpy(a).cuda() for a in (files, offsets, sizes)]
+    desc = mae.make_prep_desc(dev[0], dev[1], None, None, file_sizes=dev[2], out_size=wl.out_size,
+                              patch=wl.patch, num_keep=K, seed=0, batch_index=0,
+                              out_dtype=mae.MAE_BF16 if wl.dtype == "bf16" else mae.MAE_F32)
+    buf = mae.alloc_prep_buffers(desc)
+    stream = torch.cuda.current_stream()
+
+    def run(i):
+        desc.batch_index = i
+        mae.mae_prep_batch(desc, buf.visible, buf.mask, buf.ids_restore, buf.ids_keep, buf.target,
+                           buf.crop, buf.workspace, stream=stream)
+
+    for i in range(max(args.warmup, 1)):
+        run(i)
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+    for i, e in enumerate(ev):
+        e[0].record(stream)
+        run(args.warmup + i)
+        e[1].record(stream)
+    torch.cuda.synchronize()
+    assert mae.mae_prep_status(buf.workspace) == 0
+    ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    crop = buf.crop.cpu().numpy().astype(np.int64)
+    return {
+        "input": "baseline JPEG, quality 90, 4:2:0, restart interval = one row of MCUs",
+        "file_bytes": int(files.size), "encode_s_on_host": round(enc_s, 1),
+        "avg_ms": round(ms, 4), "images_per_s": round(wl.B / (ms * 1e-3), 1),
+        "compressed_GBps": round(files.size / (ms * 1e-3) / 1e9, 1),
+        "mean_crop_area_px": round(float((crop[:, 2] * crop[:, 3]).mean()), 1),
+    }
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -214,6 +257,8 @@ def main() -> int:
     ap.add_argument("--embed", type=int, default=768,
                     help="embedding width E for the separately timed mae_patch_embed launch over "
                          "the batch's visible rows (adds 'patch_embed' to the JSON line); 0 = skip")
+    ap.add_argument("--no-jpeg", action="store_true",
+                    help="skip the separately timed calls on JPEG input ('jpeg_prep')")
     ap.add_argument("--no-finetune", action="store_true",
                     help="skip the separately timed finetuning-mode calls ('finetune_prep')")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -349,6 +394,9 @@ def main() -> int:
 
     if args.embed > 0:
         out["patch_embed"] = time_embed(args, mae, synth, torch, dev, wl, K, args.embed)
+
+    if not args.no_jpeg:
+        out["jpeg_prep"] = time_jpeg(args, mae, synth, torch, wl, K)
 
     if not args.no_finetune and wl.patch % 4 == 0:
         out["finetune_prep"] = time_finetune(args, mae, torch, dev, wl)

@@ -139,8 +139,9 @@ typedef struct {
                               (MAE_ERR_SHAPE otherwise)                                         */
   float jitter;            /* MAE_AUG_THREE_PLUS: strength in [0, 1], 0.3 in the paper            */
   int32_t input_format;    /* mae_input_format.  MAE_INPUT_JPEG: `images` holds the files back to
-                              back, images_bytes their total size, offsets[b] the start of file
-                              b; heights and widths are not read (may be NULL)                   */
+                              back (8-byte aligned buffer), images_bytes their total size,
+                              offsets[b] the start of file b; heights and widths are not read
+                              (may be NULL)                                                      */
   const int32_t* file_sizes; /* [B] length of each file in bytes; MAE_INPUT_JPEG only            */
 } mae_prep_desc;
 

@@ -28,6 +28,8 @@ int validate_prep(const mae_prep_desc* d, PrepShape* shape) {
   if (!d->images || !d->offsets) return MAE_ERR_NULL;
   if (d->input_format == MAE_INPUT_DECODED && (!d->heights || !d->widths)) return MAE_ERR_NULL;
   if (d->input_format == MAE_INPUT_JPEG && !d->file_sizes) return MAE_ERR_NULL;
+  // the decoder reads the files through aligned 8-byte windows
+  if (d->input_format == MAE_INPUT_JPEG && !aligned(d->images, 8)) return MAE_ERR_RANGE;
   if (d->B <= 0 || d->out_size <= 0 || d->patch <= 0) return MAE_ERR_SHAPE;
   if (d->B > (1 << 20)) return MAE_ERR_RANGE;  // keeps every grid size below 2^31
   if (d->out_size % d->patch != 0) return MAE_ERR_SHAPE;

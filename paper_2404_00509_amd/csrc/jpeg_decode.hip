@@ -179,21 +179,45 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_header_kernel(JpegArgs a) {
 
 // ---- entropy decoding ------------------------------------------------------------------------------
 struct BitReader {
-  const uint8_t* d;  // file
-  int n;             // file size
-  int pos;           // next byte
+  const uint8_t* files;  // all files; reads go through an 8-byte window on 8-byte boundaries
+  int64_t files_bytes;
+  int64_t origin;  // offset of this file
+  int n;           // file size
+  int pos;         // next byte of the file
+  uint64_t window;
+  int64_t window_at;  // offset of the window in `files`, -1 = none yet
   uint32_t acc;
   int nbits;
   bool ended;  // a marker was reached: zero bits from here on
 };
 
-__device__ static inline int next_bit(BitReader& r) {
-  if (r.nbits == 0) {
+// Byte `pos` of the file (pos < n).
+__device__ static inline uint32_t file_byte(BitReader& r, int pos) {
+  const int64_t at = r.origin + pos;
+  const int64_t base = at & ~(int64_t)7;
+  if (base != r.window_at) {
+    r.window_at = base;
+    if (base + 8 <= r.files_bytes) {
+      r.window = *reinterpret_cast<const uint64_t*>(r.files + base);
+    } else {  // the last bytes of the buffer
+      uint64_t w = 0;
+      for (int i = 0; i < 8; ++i)
+        if (base + i < r.files_bytes) w |= (uint64_t)r.files[base + i] << (8 * i);
+      r.window = w;
+    }
+  }
+  return (uint32_t)(r.window >> (8 * (int)(at & 7))) & 0xFFu;
+}
+
+// Tops the bit buffer up to at least 25 bits.  0xFF00 stands for a data byte 0xFF; any other
+// marker ends the data of this row, and zero bits are supplied from there on.
+__device__ static inline void fill(BitReader& r) {
+  while (r.nbits <= 24) {
     uint32_t byte = 0;
     if (!r.ended && r.pos < r.n) {
-      byte = r.d[r.pos];
+      byte = file_byte(r, r.pos);
       if (byte == 0xFF) {
-        if (r.pos + 1 < r.n && r.d[r.pos + 1] == 0x00) {
+        if (r.pos + 1 < r.n && file_byte(r, r.pos + 1) == 0x00) {
           r.pos += 2;
         } else {
           r.ended = true;
@@ -203,43 +227,56 @@ __device__ static inline int next_bit(BitReader& r) {
         r.pos += 1;
       }
     }
-    r.acc = byte;
-    r.nbits = 8;
+    r.acc = (r.acc << 8) | byte;
+    r.nbits += 8;
   }
-  r.nbits -= 1;
-  return (int)((r.acc >> r.nbits) & 1u);
+}
+// The next n <= 16 bits (after fill()).
+__device__ static inline int peek(const BitReader& r, int n) {
+  return (int)((r.acc >> (r.nbits - n)) & ((1u << n) - 1u));
 }
 
 __device__ static inline int receive_extend(BitReader& r, int s) {
-  int v = 0;
-  for (int i = 0; i < s; ++i) v = (v << 1) | next_bit(r);
-  return (s && v < (1 << (s - 1))) ? v - (1 << s) + 1 : v;
+  if (s == 0) return 0;
+  fill(r);
+  const int v = peek(r, s);
+  r.nbits -= s;
+  return v < (1 << (s - 1)) ? v - (1 << s) + 1 : v;
 }
 
-// One table in LDS: counts per length, first code and first symbol index per length, symbols.
+// One table in LDS: counts per length, first code and first symbol index per length, symbols, and
+// for every 9-bit prefix the symbol and length of the code that starts it (0 = a longer code).
+constexpr int kFastBits = 9;
 struct HuffLds {
   uint8_t counts[16];
   uint16_t first_code[16];
   uint16_t first_index[16];
   uint8_t symbols[256];
+  uint16_t fast[1 << kFastBits];
 };
 
 __device__ static inline int huff_decode(BitReader& r, const HuffLds& t) {
-  int code = 0;
-  for (int len = 0; len < 16; ++len) {
-    code = (code << 1) | next_bit(r);
-    const int k = code - (int)t.first_code[len];
-    if (k >= 0 && k < (int)t.counts[len]) return t.symbols[((int)t.first_index[len] + k) & 255];
+  fill(r);
+  const int e = t.fast[peek(r, kFastBits)];
+  if (e) {
+    r.nbits -= e >> 8;
+    return e & 255;
+  }
+  for (int len = kFastBits; len < 16; ++len) {  // codes of len + 1 bits
+    const int k = peek(r, len + 1) - (int)t.first_code[len];
+    if (k >= 0 && k < (int)t.counts[len]) {
+      r.nbits -= len + 1;
+      return t.symbols[((int)t.first_index[len] + k) & 255];
+    }
   }
   return -1;
 }
 
-// Dequantised coefficients (natural order, 16-bit) -> 64 samples; the caller's lane-private LDS.
-__device__ static inline void idct8x8(const int16_t* coef, uint8_t* out) {
-  int tmp[64];
-#pragma unroll 1
+// Dequantised coefficients (natural order, 16-bit, lane-private LDS) -> 64 samples.  The first
+// pass overwrites each column with its transform (the clamped values fit 16 bits).
+__device__ static inline void idct8x8(int16_t* coef, uint8_t* out) {
   for (int u = 0; u < 8; ++u) {
-    int c[8];
+    int c[8], t[8];
 #pragma unroll
     for (int v = 0; v < 8; ++v) c[v] = coef[v * 8 + u];
 #pragma unroll
@@ -247,16 +284,20 @@ __device__ static inline void idct8x8(const int16_t* coef, uint8_t* out) {
       int acc = 0;
 #pragma unroll
       for (int v = 0; v < 8; ++v) acc += __mul24((int)kBasis[y * 8 + v], c[v]);
-      tmp[y * 8 + u] = min(max((acc + (1 << 10)) >> 11, -32767), 32767);
+      t[y] = min(max((acc + (1 << 10)) >> 11, -32767), 32767);
     }
+#pragma unroll
+    for (int y = 0; y < 8; ++y) coef[y * 8 + u] = (int16_t)t[y];
   }
-#pragma unroll 1
   for (int y = 0; y < 8; ++y) {
+    int t[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) t[u] = coef[y * 8 + u];
 #pragma unroll
     for (int x = 0; x < 8; ++x) {
       int acc = 0;
 #pragma unroll
-      for (int u = 0; u < 8; ++u) acc += __mul24((int)kBasis[x * 8 + u], tmp[y * 8 + u]);
+      for (int u = 0; u < 8; ++u) acc += __mul24((int)kBasis[x * 8 + u], t[u]);
       out[y * 8 + x] = (uint8_t)min(max(((acc + (1 << 16)) >> 17) + 128, 0), 255);
     }
   }
@@ -322,18 +363,39 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
       index += h.counts[len];
     }
   }
+  for (int t = 0; t < 4; ++t) {
+    HuffLds& h = t < 2 ? s.dc[t] : s.ac[t - 2];
+    for (int i = lane; i < (1 << kFastBits); i += kJpegThreads) h.fast[i] = 0;
+  }
+  __syncthreads();
+  for (int t = 0; t < 4; ++t) {
+    HuffLds& h = t < 2 ? s.dc[t] : s.ac[t - 2];
+    for (int i = lane; i < 256; i += kJpegThreads) {
+      // symbol i of the table has the length whose run of symbols contains i
+      int len = -1;
+      for (int l = 0; l < 16; ++l)
+        if (i >= (int)h.first_index[l] && i < (int)h.first_index[l] + (int)h.counts[l]) len = l;
+      if (len < 0 || len >= kFastBits) continue;
+      const int code = (int)h.first_code[len] + i - (int)h.first_index[len];
+      const int shift = kFastBits - (len + 1);
+      const int first = (code << shift) & ((1 << kFastBits) - 1);
+      for (int j = 0; j < (1 << shift); ++j)
+        h.fast[(first + j) & ((1 << kFastBits) - 1)] = (uint16_t)(((len + 1) << 8) | h.symbols[i]);
+    }
+  }
 
   // restart markers: marker m (0-based) ends MCU row m; row r starts after marker r - 1
   s.row_start[lane] = -1;
   __syncthreads();
   int seen = 0;  // markers before the current step
   for (int base = rec.scan_off; base < n - 1 && seen <= my1; base += kJpegThreads * 16) {
-    int mine[16], cnt = 0;
+    uint32_t mask = 0;  // bit i: a restart marker starts at byte p0 + i
     const int p0 = base + lane * 16;
     for (int i = 0; i < 16; ++i) {
       const int p = p0 + i;
-      if (p + 1 < n && d[p] == 0xFF && (d[p + 1] & 0xF8) == 0xD0) mine[cnt++] = p;
+      if (p + 1 < n && d[p] == 0xFF && (d[p + 1] & 0xF8) == 0xD0) mask |= 1u << i;
     }
+    const int cnt = __popc(mask);
     // rank of this lane's first marker among the wavefront's: counts of the lanes before it
     int before = cnt;
     for (int off = 1; off < kWave; off <<= 1) {
@@ -342,9 +404,11 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
     }
     const int total = __shfl(before, kWave - 1);
     before -= cnt;
-    for (int i = 0; i < cnt; ++i) {
-      const int row = seen + before + i + 1;  // the row that starts after this marker
-      if (row >= my0 && row <= my1) s.row_start[row - my0] = mine[i] + 2;
+    for (int i = 0; i < 16; ++i) {
+      if (!((mask >> i) & 1u)) continue;
+      // the row that starts after this marker
+      const int row = seen + before + __popc(mask & ((1u << i) - 1u)) + 1;
+      if (row >= my0 && row <= my1) s.row_start[row - my0] = p0 + i + 2;
     }
     seen += total;
   }
@@ -360,10 +424,11 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
   }
   if (lane >= nrows) return;
 
-  BitReader r = {d, n, my0 + lane == 0 ? rec.scan_off : s.row_start[lane], 0u, 0, false};
+  BitReader r = {a.files, a.files_bytes, a.offsets[b], n,
+                 my0 + lane == 0 ? rec.scan_off : s.row_start[lane], 0ull, -1, 0u, 0, false};
   const bool found = my0 + lane == 0 || (r.pos > rec.scan_off && r.pos <= n);
   if (!found) r.ended = true;  // marker missing: the row decodes to a flat block pattern
-  int pred[3] = {0, 0, 0};
+  int pred_y = 0, pred_cb = 0, pred_cr = 0;
   const int nblk = rec.hs * rec.hs;  // luma blocks per MCU
   int16_t* coef = s.coef[lane];
   bool bad = !found;
@@ -379,8 +444,12 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
         bad = true;
         sym = 0;
       }
-      pred[c] += receive_extend(r, sym);
-      if (want) coef[0] = (int16_t)min(max(pred[c] * (int)s.q[t][0], -32767), 32767);
+      const int diff = receive_extend(r, sym);
+      pred_y += c == 0 ? diff : 0;
+      pred_cb += c == 1 ? diff : 0;
+      pred_cr += c == 2 ? diff : 0;
+      const int dcv = c == 0 ? pred_y : (c == 1 ? pred_cb : pred_cr);
+      if (want) coef[0] = (int16_t)min(max(dcv * (int)s.q[t][0], -32767), 32767);
       for (int k = 1; k < 64;) {
         const int rs = huff_decode(r, s.ac[t]);
         if (rs < 0) {
@@ -408,15 +477,22 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
     // colour conversion of the MCU into the region's rows; chroma repeated over hs x hs pixels
     const int x0 = (mx - mx0) * mcu, y0 = lane * mcu;
     for (int y = 0; y < mcu; ++y) {
-      uint8_t* dst = region + ((int64_t)(y0 + y) * region_w + x0) * 3;
-      for (int x = 0; x < mcu; ++x) {
-        const int yb = (y >> 3) * rec.hs + (x >> 3);  // luma block inside the MCU
-        const int Y = s.pix[lane][yb][(y & 7) * 8 + (x & 7)];
-        const int ci = (y / rec.hs) * 8 + (x / rec.hs);
-        const uint32_t px = ycc_to_rgbx(Y, s.pix[lane][4][ci], s.pix[lane][5][ci]);
-        dst[3 * x] = (uint8_t)px;
-        dst[3 * x + 1] = (uint8_t)(px >> 8);
-        dst[3 * x + 2] = (uint8_t)(px >> 16);
+      // rows of the region start on 4-byte boundaries (their width is a multiple of 8 pixels)
+      uint32_t* dst =
+          reinterpret_cast<uint32_t*>(region + ((int64_t)(y0 + y) * region_w + x0) * 3);
+      for (int x = 0; x < mcu; x += 4) {
+        uint32_t px[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int xx = x + j;
+          const int yb = (y >> 3) * rec.hs + (xx >> 3);  // luma block inside the MCU
+          const int Y = s.pix[lane][yb][(y & 7) * 8 + (xx & 7)];
+          const int ci = (y / rec.hs) * 8 + (xx / rec.hs);
+          px[j] = ycc_to_rgbx(Y, s.pix[lane][4][ci], s.pix[lane][5][ci]);
+        }
+        dst[3 * (x >> 2)] = px[0] | (px[1] << 24);
+        dst[3 * (x >> 2) + 1] = (px[1] >> 8) | (px[2] << 16);
+        dst[3 * (x >> 2) + 2] = (px[2] >> 16) | (px[3] << 8);
       }
     }
   }
