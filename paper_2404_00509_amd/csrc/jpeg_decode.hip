@@ -9,11 +9,13 @@
 //  * jpeg_header_kernel: one lane per file walks the marker segments and leaves a record (size,
 //    sampling, restart interval, where the tables and the entropy-coded data start) plus the
 //    image's height and width for the crop-parameter kernel.
-//  * jpeg_decode_kernel: one wavefront per image.  The lanes first find the restart markers (16
-//    bytes per lane and step, positions ranked with a ballot), then lane r decodes MCU row
-//    first_row + r: canonical Huffman codes bit by bit (Annex F of the standard), DC prediction,
-//    zero runs, de-quantisation on insertion, fixed-point separable inverse DCT, repeated chroma,
-//    fixed-point JFIF colour matrix.  RGB bytes go to the image's slot of the decoded-region
+//  * jpeg_decode_kernel: one wavefront per group of four images.  Per image the lanes build the
+//    Huffman tables in LDS (canonical codes of Annex F plus a direct table for codes of up to 8
+//    bits) and find the restart markers (16 bytes per lane and step, positions ranked with a
+//    prefix sum); then the rows of MCUs that the crops touch are dealt to the lanes, one row per
+//    lane: Huffman decoding from a 32-bit bit buffer, DC prediction, zero runs, de-quantisation
+//    on insertion, fixed-point separable inverse DCT, repeated chroma, fixed-point JFIF colour
+//    matrix.  RGB bytes go to the image's slot of the decoded-region
 //    buffer, whose rows are the region's rows; the crop record is rewritten relative to the region.
 //
 // The integer arithmetic of the inverse DCT and of the colour conversion is part of the
@@ -27,7 +29,7 @@
 
 namespace mae {
 
-constexpr int kJpegThreads = 64;  // one wavefront per image
+constexpr int kJpegThreads = 64;  // one wavefront per workgroup
 
 __constant__ uint8_t kZigzag[64] = {
     0,  1,  8,  16, 9,  2,  3,  10, 17, 24, 32, 25, 18, 11, 4,  5,  12, 19, 26, 33, 40, 48,
@@ -246,7 +248,7 @@ __device__ static inline int receive_extend(BitReader& r, int s) {
 
 // One table in LDS: counts per length, first code and first symbol index per length, symbols, and
 // for every 9-bit prefix the symbol and length of the code that starts it (0 = a longer code).
-constexpr int kFastBits = 9;
+constexpr int kFastBits = 8;
 struct HuffLds {
   uint8_t counts[16];
   uint16_t first_code[16];
@@ -272,13 +274,15 @@ __device__ static inline int huff_decode(BitReader& r, const HuffLds& t) {
   return -1;
 }
 
-// Dequantised coefficients (natural order, 16-bit, lane-private LDS) -> 64 samples.  The first
-// pass overwrites each column with its transform (the clamped values fit 16 bits).
+// Dequantised coefficients (natural order, 16-bit) -> 64 samples.  Both live in LDS with the lane
+// as the fastest index (element k of this lane at coef[k * 64], sample i at out[i * 64]): the
+// lanes of a wavefront then touch neighbouring addresses instead of one bank.  The first pass
+// overwrites each column with its transform (the clamped values fit 16 bits).
 __device__ static inline void idct8x8(int16_t* coef, uint8_t* out) {
   for (int u = 0; u < 8; ++u) {
     int c[8], t[8];
 #pragma unroll
-    for (int v = 0; v < 8; ++v) c[v] = coef[v * 8 + u];
+    for (int v = 0; v < 8; ++v) c[v] = coef[(v * 8 + u) * kJpegThreads];
 #pragma unroll
     for (int y = 0; y < 8; ++y) {
       int acc = 0;
@@ -287,18 +291,18 @@ __device__ static inline void idct8x8(int16_t* coef, uint8_t* out) {
       t[y] = min(max((acc + (1 << 10)) >> 11, -32767), 32767);
     }
 #pragma unroll
-    for (int y = 0; y < 8; ++y) coef[y * 8 + u] = (int16_t)t[y];
+    for (int y = 0; y < 8; ++y) coef[(y * 8 + u) * kJpegThreads] = (int16_t)t[y];
   }
   for (int y = 0; y < 8; ++y) {
     int t[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) t[u] = coef[y * 8 + u];
+    for (int u = 0; u < 8; ++u) t[u] = coef[(y * 8 + u) * kJpegThreads];
 #pragma unroll
     for (int x = 0; x < 8; ++x) {
       int acc = 0;
 #pragma unroll
       for (int u = 0; u < 8; ++u) acc += __mul24((int)kBasis[x * 8 + u], t[u]);
-      out[y * 8 + x] = (uint8_t)min(max(((acc + (1 << 16)) >> 17) + 128, 0), 255);
+      out[(y * 8 + x) * kJpegThreads] = (uint8_t)min(max(((acc + (1 << 16)) >> 17) + 128, 0), 255);
     }
   }
 }
@@ -311,50 +315,84 @@ __device__ static inline uint32_t ycc_to_rgbx(int y, int cb, int cr) {
   return (uint32_t)R | ((uint32_t)G << 8) | ((uint32_t)B << 16);
 }
 
-struct JpegLds {
+constexpr int kJpegGroup = 4;  // images per workgroup: their rows of MCUs share the 64 lanes
+
+// What the wavefront keeps per image of its group.
+struct JpegImage {
   HuffLds dc[2], ac[2];  // luma, chroma
   uint8_t q[2][64];      // zig-zag order
-  int row_start[kJpegThreads];
-  int16_t coef[kJpegThreads][64];    // one block per lane
-  uint8_t pix[kJpegThreads][6][64];  // the blocks of one MCU per lane: Y (1 or 4), Cb, Cr
+  int row_start[kJpegThreads];  // first byte of the crop's rows of MCUs, -1 = marker not found
+  int my0, mx0, mx1, nrows, region_w, hs, size, scan_off, live;
+  int64_t origin, region_off;
 };
 
-__global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
-  __shared__ JpegLds s;
-  const int b = (int)blockIdx.x;
+struct JpegLds {
+  JpegImage img[kJpegGroup];
+  int16_t coef[64][kJpegThreads];    // one block per lane, the lane is the fastest index
+  uint8_t pix[6][64][kJpegThreads];  // the blocks of one MCU per lane: Y (1 or 4), Cb, Cr
+};
+
+// Tables, crop geometry and restart-marker positions of image b into slot `im` (whole wavefront).
+__device__ static void jpeg_prepare_image(const JpegArgs& a, int b, JpegImage& im) {
   const int lane = threadIdx.x;
   const JpegRec rec = a.recs[b];
   CropRec* crop = reinterpret_cast<CropRec*>(a.workspace + kWorkspaceHeader) + b;
-  CropRec cr = *crop;
+  const CropRec cr = *crop;
+  __syncthreads();  // everybody has read the record before lane 0 rewrites it
   if (!rec.valid) {
     if (lane == 0) {
       crop->valid = 0;
       if (a.crop_out) a.crop_out[(int64_t)b * 6 + 5] = 0;
+      im.live = 0;
+      im.nrows = 0;
     }
     return;
   }
-  if (!cr.valid) return;
+  if (!cr.valid) {
+    if (lane == 0) {
+      im.live = 0;
+      im.nrows = 0;
+    }
+    return;
+  }
   const uint8_t* d = a.files + a.offsets[b];
   const int n = rec.size;
   const int mcu = 8 * rec.hs;
   // rows and columns of MCUs that the crop touches
   const int my0 = cr.top / mcu, my1 = min((cr.top + cr.ch - 1) / mcu, rec.mcuy - 1);
   const int mx0 = cr.left / mcu, mx1 = min((cr.left + cr.cw - 1) / mcu, rec.mcux - 1);
-  const int nrows = my1 - my0 + 1;
-  const int region_w = (mx1 - mx0 + 1) * mcu;
+  if (lane == 0) {
+    im.my0 = my0;
+    im.mx0 = mx0;
+    im.mx1 = mx1;
+    im.nrows = my1 - my0 + 1;
+    im.region_w = (mx1 - mx0 + 1) * mcu;
+    im.hs = rec.hs;
+    im.size = n;
+    im.scan_off = rec.scan_off;
+    im.live = 1;
+    im.origin = a.offsets[b];
+    im.region_off = a.region_offsets[b];
+    // region geometry for the resampling kernel
+    a.region_widths[b] = (mx1 - mx0 + 1) * mcu;
+    crop->top = cr.top - my0 * mcu;
+    crop->left = cr.left - mx0 * mcu;
+  }
 
   // tables: one lane per length / symbol
   for (int t = 0; t < 4; ++t) {
-    HuffLds& h = t < 2 ? s.dc[t] : s.ac[t - 2];
+    HuffLds& h = t < 2 ? im.dc[t] : im.ac[t - 2];
     const int o = t < 2 ? rec.dc_off[t] : rec.ac_off[t - 2];
     if (lane < 16) h.counts[lane] = d[min(o + lane, n - 1)];
     for (int i = lane; i < 256; i += kJpegThreads) h.symbols[i] = d[min(o + 16 + i, n - 1)];
+    for (int i = lane; i < (1 << kFastBits); i += kJpegThreads) h.fast[i] = 0;
   }
   for (int i = lane; i < 128; i += kJpegThreads)
-    s.q[i >> 6][i & 63] = d[min(rec.q_off[i >> 6] + (i & 63), n - 1)];
+    im.q[i >> 6][i & 63] = d[min(rec.q_off[i >> 6] + (i & 63), n - 1)];
+  im.row_start[lane] = -1;
   __syncthreads();
   if (lane < 4) {
-    HuffLds& h = lane < 2 ? s.dc[lane] : s.ac[lane - 2];
+    HuffLds& h = lane < 2 ? im.dc[lane] : im.ac[lane - 2];
     int code = 0, index = 0;
     for (int len = 0; len < 16; ++len) {
       h.first_code[len] = (uint16_t)code;
@@ -363,13 +401,9 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
       index += h.counts[len];
     }
   }
-  for (int t = 0; t < 4; ++t) {
-    HuffLds& h = t < 2 ? s.dc[t] : s.ac[t - 2];
-    for (int i = lane; i < (1 << kFastBits); i += kJpegThreads) h.fast[i] = 0;
-  }
   __syncthreads();
   for (int t = 0; t < 4; ++t) {
-    HuffLds& h = t < 2 ? s.dc[t] : s.ac[t - 2];
+    HuffLds& h = t < 2 ? im.dc[t] : im.ac[t - 2];
     for (int i = lane; i < 256; i += kJpegThreads) {
       // symbol i of the table has the length whose run of symbols contains i
       int len = -1;
@@ -385,8 +419,6 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
   }
 
   // restart markers: marker m (0-based) ends MCU row m; row r starts after marker r - 1
-  s.row_start[lane] = -1;
-  __syncthreads();
   int seen = 0;  // markers before the current step
   for (int base = rec.scan_off; base < n - 1 && seen <= my1; base += kJpegThreads * 16) {
     uint32_t mask = 0;  // bit i: a restart marker starts at byte p0 + i
@@ -408,97 +440,117 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
       if (!((mask >> i) & 1u)) continue;
       // the row that starts after this marker
       const int row = seen + before + __popc(mask & ((1u << i) - 1u)) + 1;
-      if (row >= my0 && row <= my1) s.row_start[row - my0] = p0 + i + 2;
+      if (row >= my0 && row <= my1) im.row_start[row - my0] = p0 + i + 2;
     }
     seen += total;
   }
-  if (my0 == 0 && lane == 0) s.row_start[0] = rec.scan_off;
+  if (my0 == 0 && lane == 0) im.row_start[0] = rec.scan_off;
+}
+
+__global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
+  __shared__ JpegLds s;
+  const int lane = threadIdx.x;
+  const int b0 = (int)blockIdx.x * kJpegGroup;
+  const int nimg = min(kJpegGroup, a.B - b0);
+  for (int i = 0; i < nimg; ++i) jpeg_prepare_image(a, b0 + i, s.img[i]);
   __syncthreads();
 
-  // region geometry for the resampling kernel
-  uint8_t* region = a.regions + a.region_offsets[b];
-  if (lane == 0) {
-    a.region_widths[b] = region_w;
-    crop->top = cr.top - my0 * mcu;
-    crop->left = cr.left - mx0 * mcu;
-  }
-  if (lane >= nrows) return;
+  // the rows of MCUs of the group's images, one after the other, are dealt to the lanes
+  int first_task[kJpegGroup + 1];
+  first_task[0] = 0;
+  for (int i = 0; i < kJpegGroup; ++i)
+    first_task[i + 1] = first_task[i] + (i < nimg ? s.img[i].nrows : 0);
+  const int ntasks = first_task[kJpegGroup];
 
-  BitReader r = {a.files, a.files_bytes, a.offsets[b], n,
-                 my0 + lane == 0 ? rec.scan_off : s.row_start[lane], 0ull, -1, 0u, 0, false};
-  const bool found = my0 + lane == 0 || (r.pos > rec.scan_off && r.pos <= n);
-  if (!found) r.ended = true;  // marker missing: the row decodes to a flat block pattern
-  int pred_y = 0, pred_cb = 0, pred_cr = 0;
-  const int nblk = rec.hs * rec.hs;  // luma blocks per MCU
-  int16_t* coef = s.coef[lane];
-  bool bad = !found;
-  for (int mx = 0; mx <= mx1; ++mx) {
-    const bool want = mx >= mx0;
-    for (int blk = 0; blk < nblk + 2; ++blk) {
-      const int c = blk < nblk ? 0 : blk - nblk + 1;  // component
-      const int t = c ? 1 : 0;                        // table set
-      if (want)
-        for (int i = 0; i < 64; ++i) coef[i] = 0;
-      int sym = huff_decode(r, s.dc[t]);
-      if (sym < 0 || sym > 11) {
-        bad = true;
-        sym = 0;
-      }
-      const int diff = receive_extend(r, sym);
-      pred_y += c == 0 ? diff : 0;
-      pred_cb += c == 1 ? diff : 0;
-      pred_cr += c == 2 ? diff : 0;
-      const int dcv = c == 0 ? pred_y : (c == 1 ? pred_cb : pred_cr);
-      if (want) coef[0] = (int16_t)min(max(dcv * (int)s.q[t][0], -32767), 32767);
-      for (int k = 1; k < 64;) {
-        const int rs = huff_decode(r, s.ac[t]);
-        if (rs < 0) {
+  int16_t* coef = &s.coef[0][lane];  // element k at coef[k * 64]
+  uint8_t* pix = &s.pix[0][0][lane];  // sample i of block blk at pix[(blk * 64 + i) * 64]
+  for (int task = lane; task < ntasks; task += kJpegThreads) {
+    int slot = 0;
+    for (int i = 1; i < kJpegGroup; ++i) slot += task >= first_task[i] ? 1 : 0;
+    const int row = task - first_task[slot];  // row of MCUs inside the crop's range
+    const JpegImage& im = s.img[slot];
+    const int b = b0 + slot;
+    const int hs = im.hs, mcu = 8 * hs;
+    const int mx0 = im.mx0, mx1 = im.mx1, region_w = im.region_w;
+    uint8_t* region = a.regions + im.region_off;
+    const int start = im.my0 + row == 0 ? im.scan_off : im.row_start[row];
+    BitReader r = {a.files, a.files_bytes, im.origin, im.size, start, 0ull, -1, 0u, 0, false};
+    const bool found = start >= im.scan_off && start <= im.size;
+    if (!found) r.ended = true;  // marker missing: the sample is flagged below
+    int pred_y = 0, pred_cb = 0, pred_cr = 0;
+    const int nblk = hs * hs;  // luma blocks per MCU
+    bool bad = !found;
+    for (int mx = 0; mx <= mx1; ++mx) {
+      const bool want = mx >= mx0;
+      for (int blk = 0; blk < nblk + 2; ++blk) {
+        const int c = blk < nblk ? 0 : blk - nblk + 1;  // component
+        const int t = c ? 1 : 0;                        // table set
+        if (want)
+          for (int i = 0; i < 64; ++i) coef[i * kJpegThreads] = 0;
+        int sym = huff_decode(r, im.dc[t]);
+        if (sym < 0 || sym > 11) {
           bad = true;
-          break;
+          sym = 0;
         }
-        const int run = rs >> 4, size = rs & 15;
-        if (size == 0) {
-          if (run != 15) break;
-          k += 16;
-          continue;
+        const int diff = receive_extend(r, sym);
+        pred_y += c == 0 ? diff : 0;
+        pred_cb += c == 1 ? diff : 0;
+        pred_cr += c == 2 ? diff : 0;
+        const int dcv = c == 0 ? pred_y : (c == 1 ? pred_cb : pred_cr);
+        if (want) coef[0] = (int16_t)min(max(dcv * (int)im.q[t][0], -32767), 32767);
+        for (int k = 1; k < 64;) {
+          const int rs = huff_decode(r, im.ac[t]);
+          if (rs < 0) {
+            bad = true;
+            break;
+          }
+          const int run = rs >> 4, size = rs & 15;
+          if (size == 0) {
+            if (run != 15) break;
+            k += 16;
+            continue;
+          }
+          k += run;
+          if (k > 63) {
+            bad = true;
+            break;
+          }
+          const int v = receive_extend(r, size);
+          if (want)
+            coef[kZigzag[k] * kJpegThreads] =
+                (int16_t)min(max(v * (int)im.q[t][k], -32767), 32767);
+          ++k;
         }
-        k += run;
-        if (k > 63) {
-          bad = true;
-          break;
-        }
-        const int v = receive_extend(r, size);
-        if (want) coef[kZigzag[k]] = (int16_t)min(max(v * (int)s.q[t][k], -32767), 32767);
-        ++k;
+        if (want) idct8x8(coef, pix + (blk < nblk ? blk : 4 + (blk - nblk)) * 64 * kJpegThreads);
       }
-      if (want) idct8x8(coef, s.pix[lane][blk < nblk ? blk : 4 + (blk - nblk)]);
-    }
-    if (!want) continue;
-    // colour conversion of the MCU into the region's rows; chroma repeated over hs x hs pixels
-    const int x0 = (mx - mx0) * mcu, y0 = lane * mcu;
-    for (int y = 0; y < mcu; ++y) {
-      // rows of the region start on 4-byte boundaries (their width is a multiple of 8 pixels)
-      uint32_t* dst =
-          reinterpret_cast<uint32_t*>(region + ((int64_t)(y0 + y) * region_w + x0) * 3);
-      for (int x = 0; x < mcu; x += 4) {
-        uint32_t px[4];
+      if (!want) continue;
+      // colour conversion of the MCU into the region's rows; chroma repeated over hs x hs pixels
+      const int x0 = (mx - mx0) * mcu, y0 = row * mcu;
+      for (int y = 0; y < mcu; ++y) {
+        // rows of the region start on 4-byte boundaries (their width is a multiple of 8 pixels)
+        uint32_t* dst =
+            reinterpret_cast<uint32_t*>(region + ((int64_t)(y0 + y) * region_w + x0) * 3);
+        for (int x = 0; x < mcu; x += 4) {
+          uint32_t px[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int xx = x + j;
-          const int yb = (y >> 3) * rec.hs + (xx >> 3);  // luma block inside the MCU
-          const int Y = s.pix[lane][yb][(y & 7) * 8 + (xx & 7)];
-          const int ci = (y / rec.hs) * 8 + (xx / rec.hs);
-          px[j] = ycc_to_rgbx(Y, s.pix[lane][4][ci], s.pix[lane][5][ci]);
+          for (int j = 0; j < 4; ++j) {
+            const int xx = x + j;
+            const int yb = (y >> 3) * hs + (xx >> 3);  // luma block inside the MCU
+            const int Y = pix[(yb * 64 + (y & 7) * 8 + (xx & 7)) * kJpegThreads];
+            const int ci = (y / hs) * 8 + (xx / hs);
+            px[j] = ycc_to_rgbx(Y, pix[(4 * 64 + ci) * kJpegThreads],
+                                pix[(5 * 64 + ci) * kJpegThreads]);
+          }
+          dst[3 * (x >> 2)] = px[0] | (px[1] << 24);
+          dst[3 * (x >> 2) + 1] = (px[1] >> 8) | (px[2] << 16);
+          dst[3 * (x >> 2) + 2] = (px[2] >> 16) | (px[3] << 8);
         }
-        dst[3 * (x >> 2)] = px[0] | (px[1] << 24);
-        dst[3 * (x >> 2) + 1] = (px[1] >> 8) | (px[2] << 16);
-        dst[3 * (x >> 2) + 2] = (px[2] >> 16) | (px[3] << 8);
       }
     }
-  }
-  if (bad) {
-    crop->valid = 0;
-    if (a.crop_out) a.crop_out[(int64_t)b * 6 + 5] = 0;
+    if (bad) {
+      reinterpret_cast<CropRec*>(a.workspace + kWorkspaceHeader)[b].valid = 0;
+      if (a.crop_out) a.crop_out[(int64_t)b * 6 + 5] = 0;
+    }
   }
 }
 
@@ -509,7 +561,7 @@ hipError_t launch_jpeg_header(const JpegArgs& a, hipStream_t stream) {
 }
 
 hipError_t launch_jpeg_decode(const JpegArgs& a, hipStream_t stream) {
-  dim3 grid((uint32_t)a.B), block(kJpegThreads);
+  dim3 grid((uint32_t)((a.B + kJpegGroup - 1) / kJpegGroup)), block(kJpegThreads);
   hipLaunchKernelGGL(jpeg_decode_kernel, grid, block, 0, stream, a);
   return hipGetLastError();
 }
