@@ -180,41 +180,56 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_header_kernel(JpegArgs a) {
 }
 
 // ---- entropy decoding ------------------------------------------------------------------------------
+// File bytes are read through two 8-byte windows on 8-byte boundaries of `files`: the one being
+// consumed and the one after it, loaded when the first is entered, so that the wait for memory
+// overlaps the decoding of eight bytes.
 struct BitReader {
-  const uint8_t* files;  // all files; reads go through an 8-byte window on 8-byte boundaries
+  const uint8_t* files;
   int64_t files_bytes;
   int64_t origin;  // offset of this file
   int n;           // file size
   int pos;         // next byte of the file
-  uint64_t window;
-  int64_t window_at;  // offset of the window in `files`, -1 = none yet
-  uint32_t acc;
+  int64_t window_at;  // offset of `window` in `files`
+  uint64_t window, ahead;
+  uint64_t acc;  // the low nbits bits are the unread ones, oldest on top
   int nbits;
   bool ended;  // a marker was reached: zero bits from here on
 };
 
-// Byte `pos` of the file (pos < n).
+__device__ static inline uint64_t load_window(const BitReader& r, int64_t base) {
+  if (base + 8 <= r.files_bytes) return *reinterpret_cast<const uint64_t*>(r.files + base);
+  uint64_t w = 0;  // the last bytes of the buffer
+  for (int i = 0; i < 8; ++i)
+    if (base + i < r.files_bytes) w |= (uint64_t)r.files[base + i] << (8 * i);
+  return w;
+}
+
+__device__ static inline void open_reader(BitReader& r, int start) {
+  r.pos = start;
+  r.window_at = (r.origin + start) & ~(int64_t)7;
+  r.window = load_window(r, r.window_at);
+  r.ahead = load_window(r, r.window_at + 8);
+  r.acc = 0;
+  r.nbits = 0;
+}
+
+// Byte `pos` of the file (pos < n); positions only move forward.
 __device__ static inline uint32_t file_byte(BitReader& r, int pos) {
   const int64_t at = r.origin + pos;
   const int64_t base = at & ~(int64_t)7;
   if (base != r.window_at) {
+    r.window = base == r.window_at + 8 ? r.ahead : load_window(r, base);
     r.window_at = base;
-    if (base + 8 <= r.files_bytes) {
-      r.window = *reinterpret_cast<const uint64_t*>(r.files + base);
-    } else {  // the last bytes of the buffer
-      uint64_t w = 0;
-      for (int i = 0; i < 8; ++i)
-        if (base + i < r.files_bytes) w |= (uint64_t)r.files[base + i] << (8 * i);
-      r.window = w;
-    }
+    r.ahead = load_window(r, base + 8);
   }
   return (uint32_t)(r.window >> (8 * (int)(at & 7))) & 0xFFu;
 }
 
-// Tops the bit buffer up to at least 25 bits.  0xFF00 stands for a data byte 0xFF; any other
-// marker ends the data of this row, and zero bits are supplied from there on.
+// Tops the bit buffer up to at least 33 bits: enough for the longest code (16) together with the
+// longest value (15).  0xFF00 stands for a data byte 0xFF; any other marker ends the data of this
+// row, and zero bits are supplied from there on.
 __device__ static inline void fill(BitReader& r) {
-  while (r.nbits <= 24) {
+  while (r.nbits <= 32) {
     uint32_t byte = 0;
     if (!r.ended && r.pos < r.n) {
       byte = file_byte(r, r.pos);
@@ -233,52 +248,65 @@ __device__ static inline void fill(BitReader& r) {
     r.nbits += 8;
   }
 }
-// The next n <= 16 bits (after fill()).
-__device__ static inline int peek(const BitReader& r, int n) {
-  return (int)((r.acc >> (r.nbits - n)) & ((1u << n) - 1u));
+// The next 32 bits (after fill()), the oldest on top.
+__device__ static inline uint32_t peek32(const BitReader& r) {
+  return (uint32_t)(r.acc >> (r.nbits - 32));
 }
 
-__device__ static inline int receive_extend(BitReader& r, int s) {
-  if (s == 0) return 0;
-  fill(r);
-  const int v = peek(r, s);
-  r.nbits -= s;
-  return v < (1 << (s - 1)) ? v - (1 << s) + 1 : v;
+// `size` >= 1 value bits that follow a code of `len` bits in `top`, as the signed value they stand
+// for (T.81 F.2.2.1: the lower half of the range is the negative numbers).
+__device__ static inline int value_bits(uint32_t top, int len, int size) {
+  const int v = (int)((top << len) >> (32 - size));
+  return v < (1 << (size - 1)) ? v - (1 << size) + 1 : v;
 }
 
-// One table in LDS: counts per length, first code and first symbol index per length, symbols, and
-// for every 9-bit prefix the symbol and length of the code that starts it (0 = a longer code).
+// Canonical code (Annex C) in the form the decoder wants.  With every code left-aligned in 16
+// bits, the codes of one length are a range, and the ranges follow each other with the length:
+// limit[l] is the end of the range of length l + 1, so the length of the code that starts the
+// 16 bits x is one more than the number of limits that x has reached.  delta[l] turns the leading
+// l + 1 bits into the index of the symbol.
+struct alignas(16) HuffDc {
+  uint32_t limit[16];
+  int32_t delta[16];
+  uint8_t symbols[16];  // categories 0..11
+};
 constexpr int kFastBits = 8;
-struct HuffLds {
-  uint8_t counts[16];
-  uint16_t first_code[16];
-  uint16_t first_index[16];
+struct alignas(16) HuffAc {
+  uint32_t limit[16];
+  int32_t delta[16];
   uint8_t symbols[256];
-  uint16_t fast[1 << kFastBits];
+  uint16_t fast[1 << kFastBits];  // per 8-bit prefix: length << 8 | symbol, 0 = a longer code
 };
 
-__device__ static inline int huff_decode(BitReader& r, const HuffLds& t) {
-  fill(r);
-  const int e = t.fast[peek(r, kFastBits)];
-  if (e) {
-    r.nbits -= e >> 8;
-    return e & 255;
-  }
-  for (int len = kFastBits; len < 16; ++len) {  // codes of len + 1 bits
-    const int k = peek(r, len + 1) - (int)t.first_code[len];
-    if (k >= 0 && k < (int)t.counts[len]) {
-      r.nbits -= len + 1;
-      return t.symbols[((int)t.first_index[len] + k) & 255];
-    }
-  }
-  return -1;
+// Index (length - 1) of the code that starts x, looking at lengths above kFrom only; 16 = none.
+template <int kFrom>
+__device__ static inline int code_length(const uint32_t* limit, uint32_t x) {
+  int len = kFrom;
+#pragma unroll
+  for (int l = kFrom; l < 16; ++l) len += x >= limit[l] ? 1 : 0;
+  return len;
 }
 
-// Dequantised coefficients (natural order, 16-bit) -> 64 samples.  Both live in LDS with the lane
-// as the fastest index (element k of this lane at coef[k * 64], sample i at out[i * 64]): the
+// One row of the second pass of the inverse DCT below.
+__device__ static inline void idct_row(const int16_t* coef, int y, int out[8]) {
+  int t[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) t[u] = coef[(y * 8 + u) * kJpegThreads];
+#pragma unroll
+  for (int x = 0; x < 8; ++x) {
+    int acc = 0;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += __mul24((int)kBasis[x * 8 + u], t[u]);
+    out[x] = min(max(((acc + (1 << 16)) >> 17) + 128, 0), 255);
+  }
+}
+
+// Dequantised coefficients (natural order, 16-bit) -> 64 samples, in two passes.  The coefficients
+// live in LDS with the lane as the fastest index (element k of this lane at coef[k * 64]): the
 // lanes of a wavefront then touch neighbouring addresses instead of one bank.  The first pass
-// overwrites each column with its transform (the clamped values fit 16 bits).
-__device__ static inline void idct8x8(int16_t* coef, uint8_t* out) {
+// overwrites each column with its transform (the clamped values fit 16 bits); the second gives
+// the samples row by row.
+__device__ static inline void idct_columns(int16_t* coef) {
   for (int u = 0; u < 8; ++u) {
     int c[8], t[8];
 #pragma unroll
@@ -293,18 +321,6 @@ __device__ static inline void idct8x8(int16_t* coef, uint8_t* out) {
 #pragma unroll
     for (int y = 0; y < 8; ++y) coef[(y * 8 + u) * kJpegThreads] = (int16_t)t[y];
   }
-  for (int y = 0; y < 8; ++y) {
-    int t[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) t[u] = coef[(y * 8 + u) * kJpegThreads];
-#pragma unroll
-    for (int x = 0; x < 8; ++x) {
-      int acc = 0;
-#pragma unroll
-      for (int u = 0; u < 8; ++u) acc += __mul24((int)kBasis[x * 8 + u], t[u]);
-      out[(y * 8 + x) * kJpegThreads] = (uint8_t)min(max(((acc + (1 << 16)) >> 17) + 128, 0), 255);
-    }
-  }
 }
 
 __device__ static inline uint32_t ycc_to_rgbx(int y, int cb, int cr) {
@@ -316,28 +332,36 @@ __device__ static inline uint32_t ycc_to_rgbx(int y, int cb, int cr) {
 }
 
 constexpr int kJpegGroup = 4;  // images per workgroup: their rows of MCUs share the 64 lanes
+constexpr int kJpegRounds = kJpegGroup;  // a lane gets at most this many rows (64 rows per image)
 
 // What the wavefront keeps per image of its group.
 struct JpegImage {
-  HuffLds dc[2], ac[2];  // luma, chroma
-  uint8_t q[2][64];      // zig-zag order
-  int row_start[kJpegThreads];  // first byte of the crop's rows of MCUs, -1 = marker not found
+  HuffDc dc[2];  // luma, chroma
+  HuffAc ac[2];
+  uint16_t qz[2][64];  // per zig-zag position: natural position << 8 | quantiser step
   int my0, mx0, mx1, nrows, region_w, hs, size, scan_off, live;
   int64_t origin, region_off;
 };
 
 struct JpegLds {
   JpegImage img[kJpegGroup];
-  int16_t coef[64][kJpegThreads];    // one block per lane, the lane is the fastest index
-  uint8_t pix[6][64][kJpegThreads];  // the blocks of one MCU per lane: Y (1 or 4), Cb, Cr
+  int16_t coef[64][kJpegThreads];  // one block per lane, the lane is the fastest index
+  union {
+    // the blocks of one MCU per lane, Y (1 or 4) and Cb; Cr goes from registers to the pixels
+    uint8_t pix[5][64][kJpegThreads];
+    // before decoding starts: first byte of each of the crop's rows of MCUs, -1 = marker not found
+    int row_start[kJpegGroup][kJpegThreads];
+  };
 };
 
 // Tables, crop geometry and restart-marker positions of image b into slot `im` (whole wavefront).
-__device__ static void jpeg_prepare_image(const JpegArgs& a, int b, JpegImage& im) {
+__device__ static void jpeg_prepare_image(const JpegArgs& a, int b, JpegImage& im,
+                                          int* row_start) {
   const int lane = threadIdx.x;
   const JpegRec rec = a.recs[b];
   CropRec* crop = reinterpret_cast<CropRec*>(a.workspace + kWorkspaceHeader) + b;
   const CropRec cr = *crop;
+  row_start[lane] = -1;
   __syncthreads();  // everybody has read the record before lane 0 rewrites it
   if (!rec.valid) {
     if (lane == 0) {
@@ -379,38 +403,43 @@ __device__ static void jpeg_prepare_image(const JpegArgs& a, int b, JpegImage& i
     crop->left = cr.left - mx0 * mcu;
   }
 
-  // tables: one lane per length / symbol
-  for (int t = 0; t < 4; ++t) {
-    HuffLds& h = t < 2 ? im.dc[t] : im.ac[t - 2];
-    const int o = t < 2 ? rec.dc_off[t] : rec.ac_off[t - 2];
-    if (lane < 16) h.counts[lane] = d[min(o + lane, n - 1)];
-    for (int i = lane; i < 256; i += kJpegThreads) h.symbols[i] = d[min(o + 16 + i, n - 1)];
-    for (int i = lane; i < (1 << kFastBits); i += kJpegThreads) h.fast[i] = 0;
+  // tables: symbols and quantiser steps by all lanes, the code ranges by one lane per table
+  for (int t = 0; t < 2; ++t) {
+    if (lane < 16) im.dc[t].symbols[lane] = d[min(rec.dc_off[t] + 16 + lane, n - 1)];
+    for (int i = lane; i < 256; i += kJpegThreads)
+      im.ac[t].symbols[i] = d[min(rec.ac_off[t] + 16 + i, n - 1)];
+    for (int i = lane; i < (1 << kFastBits); i += kJpegThreads) im.ac[t].fast[i] = 0;
   }
   for (int i = lane; i < 128; i += kJpegThreads)
-    im.q[i >> 6][i & 63] = d[min(rec.q_off[i >> 6] + (i & 63), n - 1)];
-  im.row_start[lane] = -1;
-  __syncthreads();
+    im.qz[i >> 6][i & 63] =
+        (uint16_t)(((int)kZigzag[i & 63] << 8) | d[min(rec.q_off[i >> 6] + (i & 63), n - 1)]);
   if (lane < 4) {
-    HuffLds& h = lane < 2 ? im.dc[lane] : im.ac[lane - 2];
+    const int t = lane & 1;
+    const bool is_ac = lane >= 2;
+    const int o = is_ac ? rec.ac_off[t] : rec.dc_off[t];
+    uint32_t* limit = is_ac ? im.ac[t].limit : im.dc[t].limit;
+    int32_t* delta = is_ac ? im.ac[t].delta : im.dc[t].delta;
     int code = 0, index = 0;
     for (int len = 0; len < 16; ++len) {
-      h.first_code[len] = (uint16_t)code;
-      h.first_index[len] = (uint16_t)index;
-      code = (code + h.counts[len]) << 1;
-      index += h.counts[len];
+      const int count = d[min(o + len, n - 1)];
+      delta[len] = index - code;
+      limit[len] = (uint32_t)(code + count) << (15 - len);
+      code = (code + count) << 1;
+      index += count;
     }
   }
   __syncthreads();
-  for (int t = 0; t < 4; ++t) {
-    HuffLds& h = t < 2 ? im.dc[t] : im.ac[t - 2];
+  for (int t = 0; t < 2; ++t) {
+    HuffAc& h = im.ac[t];
+    // the codes of up to 8 bits: code i of length l + 1 owns the prefixes that start with it
     for (int i = lane; i < 256; i += kJpegThreads) {
-      // symbol i of the table has the length whose run of symbols contains i
-      int len = -1;
-      for (int l = 0; l < 16; ++l)
-        if (i >= (int)h.first_index[l] && i < (int)h.first_index[l] + (int)h.counts[l]) len = l;
-      if (len < 0 || len >= kFastBits) continue;
-      const int code = (int)h.first_code[len] + i - (int)h.first_index[len];
+      int len = 0;  // symbol i belongs to the first length whose symbols reach past it
+      for (int l = 0; l < kFastBits; ++l) {
+        const int end = (int)(h.limit[l] >> (15 - l)) + h.delta[l];  // symbols up to this length
+        len += i >= end ? 1 : 0;
+      }
+      if (len >= kFastBits) continue;
+      const int code = i - h.delta[len];
       const int shift = kFastBits - (len + 1);
       const int first = (code << shift) & ((1 << kFastBits) - 1);
       for (int j = 0; j < (1 << shift); ++j)
@@ -440,11 +469,11 @@ __device__ static void jpeg_prepare_image(const JpegArgs& a, int b, JpegImage& i
       if (!((mask >> i) & 1u)) continue;
       // the row that starts after this marker
       const int row = seen + before + __popc(mask & ((1u << i) - 1u)) + 1;
-      if (row >= my0 && row <= my1) im.row_start[row - my0] = p0 + i + 2;
+      if (row >= my0 && row <= my1) row_start[row - my0] = p0 + i + 2;
     }
     seen += total;
   }
-  if (my0 == 0 && lane == 0) im.row_start[0] = rec.scan_off;
+  if (my0 == 0 && lane == 0) row_start[0] = rec.scan_off;
 }
 
 __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
@@ -452,59 +481,114 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
   const int lane = threadIdx.x;
   const int b0 = (int)blockIdx.x * kJpegGroup;
   const int nimg = min(kJpegGroup, a.B - b0);
-  for (int i = 0; i < nimg; ++i) jpeg_prepare_image(a, b0 + i, s.img[i]);
+  for (int i = 0; i < nimg; ++i) jpeg_prepare_image(a, b0 + i, s.img[i], s.row_start[i]);
   __syncthreads();
 
   // the rows of MCUs of the group's images, one after the other, are dealt to the lanes
   int first_task[kJpegGroup + 1];
   first_task[0] = 0;
+#pragma unroll
   for (int i = 0; i < kJpegGroup; ++i)
     first_task[i + 1] = first_task[i] + (i < nimg ? s.img[i].nrows : 0);
   const int ntasks = first_task[kJpegGroup];
+  // where this lane's rows start: read now, the pixel blocks take the place of the list
+  int starts[kJpegRounds];
+#pragma unroll
+  for (int it = 0; it < kJpegRounds; ++it) {
+    const int task = lane + it * kJpegThreads;
+    int slot = 0, slot_first = 0;
+#pragma unroll
+    for (int i = 1; i < kJpegGroup; ++i) {
+      if (task >= first_task[i]) {
+        slot = i;
+        slot_first = first_task[i];
+      }
+    }
+    starts[it] =
+        task < ntasks ? s.row_start[slot][(task - slot_first) & (kJpegThreads - 1)] : -1;
+  }
+  __syncthreads();
 
   int16_t* coef = &s.coef[0][lane];  // element k at coef[k * 64]
   uint8_t* pix = &s.pix[0][0][lane];  // sample i of block blk at pix[(blk * 64 + i) * 64]
-  for (int task = lane; task < ntasks; task += kJpegThreads) {
-    int slot = 0;
-    for (int i = 1; i < kJpegGroup; ++i) slot += task >= first_task[i] ? 1 : 0;
-    const int row = task - first_task[slot];  // row of MCUs inside the crop's range
+#pragma unroll 1
+  for (int it = 0; it < kJpegRounds; ++it) {
+    const int task = lane + it * kJpegThreads;
+    if (task >= ntasks) break;
+    int slot = 0, slot_first = 0, start = starts[0];
+#pragma unroll
+    for (int i = 1; i < kJpegGroup; ++i) {
+      if (task >= first_task[i]) {
+        slot = i;
+        slot_first = first_task[i];
+      }
+      if (it == i) start = starts[i];
+    }
+    const int row = task - slot_first;  // row of MCUs inside the crop's range
     const JpegImage& im = s.img[slot];
     const int b = b0 + slot;
     const int hs = im.hs, mcu = 8 * hs;
     const int mx0 = im.mx0, mx1 = im.mx1, region_w = im.region_w;
     uint8_t* region = a.regions + im.region_off;
-    const int start = im.my0 + row == 0 ? im.scan_off : im.row_start[row];
-    BitReader r = {a.files, a.files_bytes, im.origin, im.size, start, 0ull, -1, 0u, 0, false};
     const bool found = start >= im.scan_off && start <= im.size;
-    if (!found) r.ended = true;  // marker missing: the sample is flagged below
+    BitReader r;
+    r.files = a.files;
+    r.files_bytes = a.files_bytes;
+    r.origin = im.origin;
+    r.n = im.size;
+    r.ended = !found;  // marker missing: zero bits, and the sample is flagged below
+    open_reader(r, found ? start : im.scan_off);
     int pred_y = 0, pred_cb = 0, pred_cr = 0;
     const int nblk = hs * hs;  // luma blocks per MCU
     bool bad = !found;
     for (int mx = 0; mx <= mx1; ++mx) {
       const bool want = mx >= mx0;
+      const int x0 = (mx - mx0) * mcu, y0 = row * mcu;
       for (int blk = 0; blk < nblk + 2; ++blk) {
         const int c = blk < nblk ? 0 : blk - nblk + 1;  // component
         const int t = c ? 1 : 0;                        // table set
         if (want)
           for (int i = 0; i < 64; ++i) coef[i * kJpegThreads] = 0;
-        int sym = huff_decode(r, im.dc[t]);
-        if (sym < 0 || sym > 11) {
-          bad = true;
-          sym = 0;
-        }
-        const int diff = receive_extend(r, sym);
-        pred_y += c == 0 ? diff : 0;
-        pred_cb += c == 1 ? diff : 0;
-        pred_cr += c == 2 ? diff : 0;
-        const int dcv = c == 0 ? pred_y : (c == 1 ? pred_cb : pred_cr);
-        if (want) coef[0] = (int16_t)min(max(dcv * (int)im.q[t][0], -32767), 32767);
-        for (int k = 1; k < 64;) {
-          const int rs = huff_decode(r, im.ac[t]);
-          if (rs < 0) {
+        {  // DC difference (T.81 F.2.2.1)
+          const HuffDc& h = im.dc[t];
+          fill(r);
+          const uint32_t top = peek32(r);
+          const uint32_t x = top >> 16;
+          int len = code_length<0>(h.limit, x);
+          int sym = 16;
+          if (len < 16) sym = h.symbols[(h.delta[len] + (int)(x >> (15 - len))) & 15];
+          if (sym > 11) {  // no such code, or not a category of 8-bit data
             bad = true;
-            break;
+            sym = 0;
+            len = -1;
+          }
+          const int diff = sym ? value_bits(top, len + 1, sym) : 0;
+          r.nbits -= len + 1 + sym;
+          pred_y += c == 0 ? diff : 0;
+          pred_cb += c == 1 ? diff : 0;
+          pred_cr += c == 2 ? diff : 0;
+        }
+        const int dcv = c == 0 ? pred_y : (c == 1 ? pred_cb : pred_cr);
+        const uint16_t* qz = im.qz[t];
+        if (want) coef[0] = (int16_t)min(max(dcv * (int)(qz[0] & 255), -32767), 32767);
+        const HuffAc& h = im.ac[t];
+        for (int k = 1; k < 64;) {  // AC coefficients (F.2.2.2): run of zeros << 4 | size
+          fill(r);
+          const uint32_t top = peek32(r);
+          const int e = h.fast[top >> (32 - kFastBits)];
+          int len1 = e >> 8, rs = e & 255;
+          if (!e) {
+            const uint32_t x = top >> 16;
+            const int len = code_length<kFastBits>(h.limit, x);
+            if (len == 16) {
+              bad = true;
+              break;
+            }
+            rs = h.symbols[(h.delta[len] + (int)(x >> (15 - len))) & 255];
+            len1 = len + 1;
           }
           const int run = rs >> 4, size = rs & 15;
+          r.nbits -= len1 + size;
           if (size == 0) {
             if (run != 15) break;
             k += 16;
@@ -515,35 +599,54 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
             bad = true;
             break;
           }
-          const int v = receive_extend(r, size);
-          if (want)
-            coef[kZigzag[k] * kJpegThreads] =
-                (int16_t)min(max(v * (int)im.q[t][k], -32767), 32767);
+          if (want) {
+            const int zq = qz[k];
+            coef[(zq >> 8) * kJpegThreads] =
+                (int16_t)min(max(value_bits(top, len1, size) * (zq & 255), -32767), 32767);
+          }
           ++k;
         }
-        if (want) idct8x8(coef, pix + (blk < nblk ? blk : 4 + (blk - nblk)) * 64 * kJpegThreads);
-      }
-      if (!want) continue;
-      // colour conversion of the MCU into the region's rows; chroma repeated over hs x hs pixels
-      const int x0 = (mx - mx0) * mcu, y0 = row * mcu;
-      for (int y = 0; y < mcu; ++y) {
-        // rows of the region start on 4-byte boundaries (their width is a multiple of 8 pixels)
-        uint32_t* dst =
-            reinterpret_cast<uint32_t*>(region + ((int64_t)(y0 + y) * region_w + x0) * 3);
-        for (int x = 0; x < mcu; x += 4) {
-          uint32_t px[4];
+        if (!want) continue;
+        idct_columns(coef);
+        if (c < 2) {
+          uint8_t* out = pix + (c ? 4 : blk) * 64 * kJpegThreads;
+          for (int y = 0; y < 8; ++y) {
+            int v[8];
+            idct_row(coef, y, v);
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const int xx = x + j;
-            const int yb = (y >> 3) * hs + (xx >> 3);  // luma block inside the MCU
-            const int Y = pix[(yb * 64 + (y & 7) * 8 + (xx & 7)) * kJpegThreads];
-            const int ci = (y / hs) * 8 + (xx / hs);
-            px[j] = ycc_to_rgbx(Y, pix[(4 * 64 + ci) * kJpegThreads],
-                                pix[(5 * 64 + ci) * kJpegThreads]);
+            for (int x = 0; x < 8; ++x) out[(y * 8 + x) * kJpegThreads] = (uint8_t)v[x];
           }
-          dst[3 * (x >> 2)] = px[0] | (px[1] << 24);
-          dst[3 * (x >> 2) + 1] = (px[1] >> 8) | (px[2] << 16);
-          dst[3 * (x >> 2) + 2] = (px[2] >> 16) | (px[3] << 8);
+          continue;
+        }
+        // Cr is the MCU's last block: each of its rows is used at once for the colour conversion
+        // of the hs rows of pixels it covers (chroma repeated over hs x hs pixels)
+        for (int cy = 0; cy < 8; ++cy) {
+          int crv[8];
+          idct_row(coef, cy, crv);
+          for (int j = 0; j < hs; ++j) {
+            const int y = cy * hs + j;
+            // rows of the region start on 4-byte boundaries (their width is a multiple of 8 pixels)
+            uint32_t* dst =
+                reinterpret_cast<uint32_t*>(region + ((int64_t)(y0 + y) * region_w + x0) * 3);
+            const uint8_t* cb_row = pix + (4 * 64 + cy * 8) * kJpegThreads;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {  // four pixels = three words
+              if (g * 4 >= mcu) break;
+              uint32_t px[4];
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                const int xx = g * 4 + i;
+                const int yb = (y >> 3) * hs + (xx >> 3);  // luma block inside the MCU
+                const int Y = pix[(yb * 64 + (y & 7) * 8 + (xx & 7)) * kJpegThreads];
+                const int cx = hs == 2 ? xx >> 1 : xx & 7;
+                px[i] = ycc_to_rgbx(Y, cb_row[cx * kJpegThreads],
+                                    hs == 2 ? crv[xx >> 1] : crv[xx & 7]);
+              }
+              dst[3 * g] = px[0] | (px[1] << 24);
+              dst[3 * g + 1] = (px[1] >> 8) | (px[2] << 16);
+              dst[3 * g + 2] = (px[2] >> 16) | (px[3] << 8);
+            }
+          }
         }
       }
     }
