@@ -30,6 +30,7 @@
 namespace mae {
 
 constexpr int kJpegThreads = 64;  // one wavefront per workgroup
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 __constant__ uint8_t kZigzag[64] = {
     0,  1,  8,  16, 9,  2,  3,  10, 17, 24, 32, 25, 18, 11, 4,  5,  12, 19, 26, 33, 40, 48,
@@ -180,55 +181,108 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_header_kernel(JpegArgs a) {
 }
 
 // ---- entropy decoding ------------------------------------------------------------------------------
-// File bytes are read through two 8-byte windows on 8-byte boundaries of `files`: the one being
-// consumed and the one after it, loaded when the first is entered, so that the wait for memory
-// overlaps the decoding of eight bytes.
+// File bytes reach a lane through its column of a ring in LDS (128 bytes per lane, dword i of lane
+// l at ring[i][l], so that every access of a wavefront is free of bank conflicts).  The ring is fed
+// at points that all lanes pass together, the start of every block: the 32 bytes loaded at the
+// previous such point are written to the ring, and the next 32 are requested if the ring has
+// room.  The wait for memory is then one block of decoding long, whichever lanes asked.  A lane
+// that runs dry inside a block loads and waits on the spot.
+constexpr int kRingBytes = 128;
+constexpr int kRingStep = 32;  // bytes per load point: two 16-byte chunks
+typedef uint32_t u32x4_a8 __attribute__((ext_vector_type(4), aligned(8)));
+
 struct BitReader {
-  const uint8_t* files;
-  int64_t files_bytes;
-  int64_t origin;  // offset of this file
-  int n;           // file size
-  int pos;         // next byte of the file
-  int64_t window_at;  // offset of `window` in `files`
-  uint64_t window, ahead;
+  const uint8_t* chunks;  // 8-byte aligned start of the file's first chunk (at or before the file)
+  int64_t chunks_bytes;   // bytes from there to the end of the buffer of files
+  uint32_t* ring;         // this lane's column: dword i at ring[i * kJpegThreads]
+  int skew;               // file position pos is byte pos + skew from `chunks`
+  int n;                  // file size
+  int pos;                // next byte of the file
+  int have;               // the ring holds the bytes before this one (from `chunks`, multiple of 32)
+  bool pending;           // `next` holds the 32 bytes at `have`, not yet in the ring
+  u32x4_a8 next[2];
   uint64_t acc;  // the low nbits bits are the unread ones, oldest on top
   int nbits;
   bool ended;  // a marker was reached: zero bits from here on
 };
 
-__device__ static inline uint64_t load_window(const BitReader& r, int64_t base) {
-  if (base + 8 <= r.files_bytes) return *reinterpret_cast<const uint64_t*>(r.files + base);
-  uint64_t w = 0;  // the last bytes of the buffer
-  for (int i = 0; i < 8; ++i)
-    if (base + i < r.files_bytes) w |= (uint64_t)r.files[base + i] << (8 * i);
-  return w;
+// The 16 bytes at `chunks + at`; bytes beyond the buffer read as zero.
+__device__ static inline u32x4_a8 load_chunk(const BitReader& r, int at) {
+  if ((int64_t)at + 16 <= r.chunks_bytes) return *reinterpret_cast<const u32x4_a8*>(r.chunks + at);
+  uint32_t w[4] = {0u, 0u, 0u, 0u};
+  for (int i = 0; i < 16; ++i)
+    if ((int64_t)at + i < r.chunks_bytes) w[i >> 2] |= (uint32_t)r.chunks[at + i] << (8 * (i & 3));
+  return u32x4_a8{w[0], w[1], w[2], w[3]};
 }
-
+__device__ static inline void request_bytes(BitReader& r) {
+  r.next[0] = load_chunk(r, r.have);
+  r.next[1] = load_chunk(r, r.have + 16);
+  r.pending = true;
+}
+__device__ static inline void accept_bytes(BitReader& r) {
+  const int i = (r.have & (kRingBytes - 1)) >> 2;  // 32 bytes never wrap: both are powers of two
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    r.ring[(i + j) * kJpegThreads] = r.next[0][j];
+    r.ring[(i + 4 + j) * kJpegThreads] = r.next[1][j];
+  }
+  r.have += kRingStep;
+  r.pending = false;
+}
+// The point all lanes pass together (start of a block).
+__device__ static inline void feed_ring(BitReader& r) {
+  if (r.pending) accept_bytes(r);
+  // room: the 32 bytes to come replace those 128 bytes back, which must have been read
+  if (!r.ended && r.have - (r.pos + r.skew) <= kRingBytes - kRingStep && r.have < r.n + r.skew)
+    request_bytes(r);
+}
+// Makes the `count` <= 4 bytes at file position pos available in the ring.
+__device__ static inline void need_bytes(BitReader& r, int pos, int count) {
+  while (pos + r.skew + count > r.have) {
+    if (!r.pending) request_bytes(r);
+    accept_bytes(r);
+  }
+}
 __device__ static inline void open_reader(BitReader& r, int start) {
   r.pos = start;
-  r.window_at = (r.origin + start) & ~(int64_t)7;
-  r.window = load_window(r, r.window_at);
-  r.ahead = load_window(r, r.window_at + 8);
+  r.have = (start + r.skew) & ~(kRingStep - 1);
+  r.pending = false;
   r.acc = 0;
   r.nbits = 0;
-}
-
-// Byte `pos` of the file (pos < n); positions only move forward.
-__device__ static inline uint32_t file_byte(BitReader& r, int pos) {
-  const int64_t at = r.origin + pos;
-  const int64_t base = at & ~(int64_t)7;
-  if (base != r.window_at) {
-    r.window = base == r.window_at + 8 ? r.ahead : load_window(r, base);
-    r.window_at = base;
-    r.ahead = load_window(r, base + 8);
+  if (!r.ended) {
+    need_bytes(r, start, 4);
+    request_bytes(r);
   }
-  return (uint32_t)(r.window >> (8 * (int)(at & 7))) & 0xFFu;
+}
+__device__ static inline uint32_t ring_dword(const BitReader& r, int i) {
+  return r.ring[(i & (kRingBytes / 4 - 1)) * kJpegThreads];
+}
+// Byte `pos` of the file (pos < n).
+__device__ static inline uint32_t file_byte(BitReader& r, int pos) {
+  need_bytes(r, pos, 1);
+  const int q = pos + r.skew;
+  return (ring_dword(r, q >> 2) >> (8 * (q & 3))) & 0xFFu;
 }
 
 // Tops the bit buffer up to at least 33 bits: enough for the longest code (16) together with the
 // longest value (15).  0xFF00 stands for a data byte 0xFF; any other marker ends the data of this
-// row, and zero bits are supplied from there on.
+// row, and zero bits are supplied from there on.  Four bytes without a 0xFF among them, the usual
+// case, go in at once.
 __device__ static inline void fill(BitReader& r) {
+  if (r.nbits > 32) return;
+  if (!r.ended && r.pos + 4 <= r.n) {
+    need_bytes(r, r.pos, 4);
+    const int q = r.pos + r.skew;
+    const uint32_t x = __builtin_amdgcn_alignbyte(ring_dword(r, (q >> 2) + 1),
+                                                  ring_dword(r, q >> 2), (uint32_t)(q & 3));
+    const uint32_t inv = ~x;  // a byte 0xFF of x is a zero byte here
+    if (((inv - 0x01010101u) & ~inv & 0x80808080u) == 0u) {
+      r.acc = (r.acc << 32) | (uint64_t)__builtin_bswap32(x);
+      r.nbits += 32;
+      r.pos += 4;
+      return;
+    }
+  }
   while (r.nbits <= 32) {
     uint32_t byte = 0;
     if (!r.ended && r.pos < r.n) {
@@ -346,12 +400,9 @@ struct JpegImage {
 struct JpegLds {
   JpegImage img[kJpegGroup];
   int16_t coef[64][kJpegThreads];  // one block per lane, the lane is the fastest index
-  union {
-    // the blocks of one MCU per lane, Y (1 or 4) and Cb; Cr goes from registers to the pixels
-    uint8_t pix[5][64][kJpegThreads];
-    // before decoding starts: first byte of each of the crop's rows of MCUs, -1 = marker not found
-    int row_start[kJpegGroup][kJpegThreads];
-  };
+  // first byte of each of the crop's rows of MCUs, -1 = marker not found
+  int row_start[kJpegGroup][kJpegThreads];
+  uint32_t ring[kRingBytes / 4][kJpegThreads];  // file bytes on their way to the lanes
 };
 
 // Tables, crop geometry and restart-marker positions of image b into slot `im` (whole wavefront).
@@ -397,8 +448,9 @@ __device__ static void jpeg_prepare_image(const JpegArgs& a, int b, JpegImage& i
     im.live = 1;
     im.origin = a.offsets[b];
     im.region_off = a.region_offsets[b];
-    // region geometry for the resampling kernel
+    // region geometry for the colour kernel and the resampling kernel
     a.region_widths[b] = (mx1 - mx0 + 1) * mcu;
+    a.recs[b].region_h = (my1 - my0 + 1) * mcu;
     crop->top = cr.top - my0 * mcu;
     crop->left = cr.left - mx0 * mcu;
   }
@@ -491,11 +543,11 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
   for (int i = 0; i < kJpegGroup; ++i)
     first_task[i + 1] = first_task[i] + (i < nimg ? s.img[i].nrows : 0);
   const int ntasks = first_task[kJpegGroup];
-  // where this lane's rows start: read now, the pixel blocks take the place of the list
-  int starts[kJpegRounds];
-#pragma unroll
+  int16_t* coef = &s.coef[0][lane];  // element k at coef[k * 64]
+#pragma unroll 1
   for (int it = 0; it < kJpegRounds; ++it) {
     const int task = lane + it * kJpegThreads;
+    if (task >= ntasks) break;
     int slot = 0, slot_first = 0;
 #pragma unroll
     for (int i = 1; i < kJpegGroup; ++i) {
@@ -504,37 +556,23 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
         slot_first = first_task[i];
       }
     }
-    starts[it] =
-        task < ntasks ? s.row_start[slot][(task - slot_first) & (kJpegThreads - 1)] : -1;
-  }
-  __syncthreads();
-
-  int16_t* coef = &s.coef[0][lane];  // element k at coef[k * 64]
-  uint8_t* pix = &s.pix[0][0][lane];  // sample i of block blk at pix[(blk * 64 + i) * 64]
-#pragma unroll 1
-  for (int it = 0; it < kJpegRounds; ++it) {
-    const int task = lane + it * kJpegThreads;
-    if (task >= ntasks) break;
-    int slot = 0, slot_first = 0, start = starts[0];
-#pragma unroll
-    for (int i = 1; i < kJpegGroup; ++i) {
-      if (task >= first_task[i]) {
-        slot = i;
-        slot_first = first_task[i];
-      }
-      if (it == i) start = starts[i];
-    }
     const int row = task - slot_first;  // row of MCUs inside the crop's range
+    const int start = s.row_start[slot][row & (kJpegThreads - 1)];
     const JpegImage& im = s.img[slot];
     const int b = b0 + slot;
     const int hs = im.hs, mcu = 8 * hs;
     const int mx0 = im.mx0, mx1 = im.mx1, region_w = im.region_w;
-    uint8_t* region = a.regions + im.region_off;
+    // the image's slot of the plane buffer: Y (region_w wide), then Cb and Cr (region_w / hs wide)
+    const int chroma_w = region_w / hs;
+    uint8_t* plane_y = a.planes + im.region_off;
+    uint8_t* plane_cb = plane_y + (int64_t)im.nrows * mcu * region_w;
+    uint8_t* plane_cr = plane_cb + (int64_t)im.nrows * 8 * chroma_w;
     const bool found = start >= im.scan_off && start <= im.size;
     BitReader r;
-    r.files = a.files;
-    r.files_bytes = a.files_bytes;
-    r.origin = im.origin;
+    r.skew = (int)(im.origin & 7);
+    r.chunks = a.files + (im.origin - r.skew);
+    r.chunks_bytes = a.files_bytes - (im.origin - r.skew);
+    r.ring = &s.ring[0][lane];
     r.n = im.size;
     r.ended = !found;  // marker missing: zero bits, and the sample is flagged below
     open_reader(r, found ? start : im.scan_off);
@@ -549,6 +587,7 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
         const int t = c ? 1 : 0;                        // table set
         if (want)
           for (int i = 0; i < 64; ++i) coef[i * kJpegThreads] = 0;
+        feed_ring(r);
         {  // DC difference (T.81 F.2.2.1)
           const HuffDc& h = im.dc[t];
           fill(r);
@@ -608,45 +647,25 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
         }
         if (!want) continue;
         idct_columns(coef);
-        if (c < 2) {
-          uint8_t* out = pix + (c ? 4 : blk) * 64 * kJpegThreads;
-          for (int y = 0; y < 8; ++y) {
-            int v[8];
-            idct_row(coef, y, v);
-#pragma unroll
-            for (int x = 0; x < 8; ++x) out[(y * 8 + x) * kJpegThreads] = (uint8_t)v[x];
-          }
-          continue;
+        // the block's rows, eight samples = one 8-byte store each (rows of every plane start on
+        // 8-byte boundaries: widths are multiples of 8)
+        uint8_t* out;
+        int pitch;
+        if (c == 0) {
+          pitch = region_w;
+          out = plane_y + (int64_t)(y0 + (blk / hs) * 8) * region_w + x0 + (blk % hs) * 8;
+        } else {
+          pitch = chroma_w;
+          out = (c == 1 ? plane_cb : plane_cr) + (int64_t)row * 8 * chroma_w + (mx - mx0) * 8;
         }
-        // Cr is the MCU's last block: each of its rows is used at once for the colour conversion
-        // of the hs rows of pixels it covers (chroma repeated over hs x hs pixels)
-        for (int cy = 0; cy < 8; ++cy) {
-          int crv[8];
-          idct_row(coef, cy, crv);
-          for (int j = 0; j < hs; ++j) {
-            const int y = cy * hs + j;
-            // rows of the region start on 4-byte boundaries (their width is a multiple of 8 pixels)
-            uint32_t* dst =
-                reinterpret_cast<uint32_t*>(region + ((int64_t)(y0 + y) * region_w + x0) * 3);
-            const uint8_t* cb_row = pix + (4 * 64 + cy * 8) * kJpegThreads;
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {  // four pixels = three words
-              if (g * 4 >= mcu) break;
-              uint32_t px[4];
-#pragma unroll
-              for (int i = 0; i < 4; ++i) {
-                const int xx = g * 4 + i;
-                const int yb = (y >> 3) * hs + (xx >> 3);  // luma block inside the MCU
-                const int Y = pix[(yb * 64 + (y & 7) * 8 + (xx & 7)) * kJpegThreads];
-                const int cx = hs == 2 ? xx >> 1 : xx & 7;
-                px[i] = ycc_to_rgbx(Y, cb_row[cx * kJpegThreads],
-                                    hs == 2 ? crv[xx >> 1] : crv[xx & 7]);
-              }
-              dst[3 * g] = px[0] | (px[1] << 24);
-              dst[3 * g + 1] = (px[1] >> 8) | (px[2] << 16);
-              dst[3 * g + 2] = (px[2] >> 16) | (px[3] << 8);
-            }
-          }
+        for (int y = 0; y < 8; ++y) {
+          int v[8];
+          idct_row(coef, y, v);
+          const uint32_t lo = (uint32_t)v[0] | ((uint32_t)v[1] << 8) | ((uint32_t)v[2] << 16) |
+                              ((uint32_t)v[3] << 24);
+          const uint32_t hi = (uint32_t)v[4] | ((uint32_t)v[5] << 8) | ((uint32_t)v[6] << 16) |
+                              ((uint32_t)v[7] << 24);
+          *reinterpret_cast<u32x2*>(out + (int64_t)y * pitch) = u32x2{lo, hi};
         }
       }
     }
@@ -663,9 +682,61 @@ hipError_t launch_jpeg_header(const JpegArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
+// Planes -> interleaved RGB, the region's rows as the resampling kernel reads them.  One workgroup
+// per image and band of rows, four pixels per thread and step; chroma is repeated over hs x hs
+// pixels (T.81 A.1.1 leaves upsampling open; repetition is this library's definition).
+constexpr int kColourThreads = 256;
+constexpr int kColourBand = 32;
+__global__ __launch_bounds__(kColourThreads) void jpeg_colour_kernel(JpegArgs a, int bands) {
+  const int b = (int)(blockIdx.x / (uint32_t)bands);
+  const int band = (int)(blockIdx.x - (uint32_t)b * (uint32_t)bands);
+  const JpegRec rec = a.recs[b];
+  const int first = band * kColourBand;
+  if (!rec.valid || first >= rec.region_h) return;
+  const int region_w = a.region_widths[b], hs = rec.hs;
+  const int chroma_w = region_w / hs;
+  const int64_t off = a.region_offsets[b];
+  const uint8_t* plane_y = a.planes + off;
+  const uint8_t* plane_cb = plane_y + (int64_t)rec.region_h * region_w;
+  const uint8_t* plane_cr = plane_cb + (int64_t)(rec.region_h / hs) * chroma_w;
+  uint8_t* region = a.regions + off;
+  const int ng = region_w >> 2;
+  const int rows = min(kColourBand, rec.region_h - first);
+  for (int i = (int)threadIdx.x; i < rows * ng; i += kColourThreads) {
+    const int y = first + i / ng, g = i % ng;
+    const uint32_t yy = *reinterpret_cast<const uint32_t*>(plane_y + (int64_t)y * region_w + 4 * g);
+    uint32_t cb, cr;  // one byte per pixel
+    if (hs == 2) {
+      const int64_t o = (int64_t)(y >> 1) * chroma_w + 2 * g;
+      const uint32_t b2 = *reinterpret_cast<const uint16_t*>(plane_cb + o);
+      const uint32_t r2 = *reinterpret_cast<const uint16_t*>(plane_cr + o);
+      cb = (b2 & 0xFFu) * 0x0101u | (b2 >> 8) * 0x01010000u;
+      cr = (r2 & 0xFFu) * 0x0101u | (r2 >> 8) * 0x01010000u;
+    } else {
+      const int64_t o = (int64_t)y * chroma_w + 4 * g;
+      cb = *reinterpret_cast<const uint32_t*>(plane_cb + o);
+      cr = *reinterpret_cast<const uint32_t*>(plane_cr + o);
+    }
+    uint32_t px[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      px[j] = ycc_to_rgbx((int)((yy >> (8 * j)) & 0xFFu), (int)((cb >> (8 * j)) & 0xFFu),
+                          (int)((cr >> (8 * j)) & 0xFFu));
+    // rows of the region start on 4-byte boundaries (their width is a multiple of 8 pixels)
+    uint32_t* dst = reinterpret_cast<uint32_t*>(region + ((int64_t)y * region_w + 4 * g) * 3);
+    dst[0] = px[0] | (px[1] << 24);
+    dst[1] = (px[1] >> 8) | (px[2] << 16);
+    dst[2] = (px[2] >> 16) | (px[3] << 8);
+  }
+}
+
 hipError_t launch_jpeg_decode(const JpegArgs& a, hipStream_t stream) {
   dim3 grid((uint32_t)((a.B + kJpegGroup - 1) / kJpegGroup)), block(kJpegThreads);
   hipLaunchKernelGGL(jpeg_decode_kernel, grid, block, 0, stream, a);
+  if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+  const int bands = (a.slot_side + kColourBand - 1) / kColourBand;
+  hipLaunchKernelGGL(jpeg_colour_kernel, dim3((uint32_t)a.B * (uint32_t)bands),
+                     dim3(kColourThreads), 0, stream, a, bands);
   return hipGetLastError();
 }
 

@@ -89,7 +89,7 @@ struct JpegRec {
   int32_t scan_off, size;   // first entropy-coded byte, file length
   int32_t valid;
   int32_t dc_off[2], ac_off[2], q_off[2];  // luma, chroma: offsets of the table bodies in the file
-  int32_t pad;
+  int32_t region_h;  // rows of the decoded region (set by the decode kernel)
 };
 static_assert(sizeof(JpegRec) == 64, "JpegRec is 64 bytes");
 struct JpegArgs {
@@ -104,6 +104,7 @@ struct JpegArgs {
   int32_t* widths;
   int64_t* region_offsets;
   int32_t* region_widths;
+  uint8_t* planes;   // decoded Y, Cb, Cr planes, one slot per image like `regions`
   uint8_t* regions;
   uint8_t* workspace;  // header + CropRec[B]
   int32_t* crop_out;   // nullable, [B,6]: the valid flag is cleared for files that cannot be used
