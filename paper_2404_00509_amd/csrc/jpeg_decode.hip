@@ -268,21 +268,41 @@ __device__ static inline uint32_t file_byte(BitReader& r, int pos) {
 // longest value (15).  0xFF00 stands for a data byte 0xFF; any other marker ends the data of this
 // row, and zero bits are supplied from there on.  Four bytes without a 0xFF among them, the usual
 // case, go in at once.
+// The four bytes at the read position, as they would go into the bit buffer at once; `usable`
+// says whether they may (inside the file and the ring, no 0xFF among them).  Reading them early
+// costs nothing: the position only moves when the buffer is topped up.
+struct NextFour {
+  uint32_t bits;
+  bool usable;
+};
+__device__ static inline NextFour next_four(const BitReader& r) {
+  const int q = r.pos + r.skew;
+  const uint32_t x = __builtin_amdgcn_alignbyte(ring_dword(r, (q >> 2) + 1), ring_dword(r, q >> 2),
+                                                (uint32_t)(q & 3));
+  const uint32_t inv = ~x;  // a byte 0xFF of x is a zero byte here
+  NextFour f;
+  f.bits = __builtin_bswap32(x);
+  f.usable = !r.ended && r.pos + 4 <= r.n && q + 4 <= r.have &&
+             ((inv - 0x01010101u) & ~inv & 0x80808080u) == 0u;
+  return f;
+}
+__device__ static inline void fill_bytewise(BitReader& r);
+__device__ static inline void fill(BitReader& r, const NextFour& f) {
+  if (r.nbits > 32) return;
+  if (f.usable) {
+    r.acc = (r.acc << 32) | (uint64_t)f.bits;
+    r.nbits += 32;
+    r.pos += 4;
+    return;
+  }
+  fill_bytewise(r);
+}
 __device__ static inline void fill(BitReader& r) {
   if (r.nbits > 32) return;
-  if (!r.ended && r.pos + 4 <= r.n) {
-    need_bytes(r, r.pos, 4);
-    const int q = r.pos + r.skew;
-    const uint32_t x = __builtin_amdgcn_alignbyte(ring_dword(r, (q >> 2) + 1),
-                                                  ring_dword(r, q >> 2), (uint32_t)(q & 3));
-    const uint32_t inv = ~x;  // a byte 0xFF of x is a zero byte here
-    if (((inv - 0x01010101u) & ~inv & 0x80808080u) == 0u) {
-      r.acc = (r.acc << 32) | (uint64_t)__builtin_bswap32(x);
-      r.nbits += 32;
-      r.pos += 4;
-      return;
-    }
-  }
+  if (!r.ended && r.pos + 4 <= r.n) need_bytes(r, r.pos, 4);
+  fill(r, next_four(r));
+}
+__device__ static inline void fill_bytewise(BitReader& r) {
   while (r.nbits <= 32) {
     uint32_t byte = 0;
     if (!r.ended && r.pos < r.n) {
@@ -316,28 +336,37 @@ __device__ static inline int value_bits(uint32_t top, int len, int size) {
 
 // Canonical code (Annex C) in the form the decoder wants.  With every code left-aligned in 16
 // bits, the codes of one length are a range, and the ranges follow each other with the length:
-// limit[l] is the end of the range of length l + 1, so the length of the code that starts the
-// 16 bits x is one more than the number of limits that x has reached.  delta[l] turns the leading
-// l + 1 bits into the index of the symbol.
+// range[l].limit is the end of the range of length l + 1, so the length of the code that starts
+// the 16 bits x is one more than the number of limits that x has reached.  range[l].delta turns
+// the leading l + 1 bits into the index of the symbol.
+struct CodeRange {
+  uint32_t limit;
+  int32_t delta;
+};
 struct alignas(16) HuffDc {
-  uint32_t limit[16];
-  int32_t delta[16];
+  CodeRange range[16];
   uint8_t symbols[16];  // categories 0..11
 };
-constexpr int kFastBits = 8;
+constexpr int kFastBits = 10;
 struct alignas(16) HuffAc {
-  uint32_t limit[16];
-  int32_t delta[16];
+  CodeRange range[16];
   uint8_t symbols[256];
-  uint16_t fast[1 << kFastBits];  // per 8-bit prefix: length << 8 | symbol, 0 = a longer code
+  uint16_t fast[1 << kFastBits];  // per 10-bit prefix: length << 8 | symbol, 0 = a longer code
 };
 
-// Index (length - 1) of the code that starts x, looking at lengths above kFrom only; 16 = none.
+// The code that starts the 16 bits x, looking at lengths above kFrom only: index (length - 1) of
+// its length, 16 = none, and through `index` the position of its symbol in the table.
 template <int kFrom>
-__device__ static inline int code_length(const uint32_t* limit, uint32_t x) {
-  int len = kFrom;
+__device__ static inline int find_code(const CodeRange* range, uint32_t x, int& index) {
+  int len = kFrom, delta = range[kFrom].delta;
 #pragma unroll
-  for (int l = kFrom; l < 16; ++l) len += x >= limit[l] ? 1 : 0;
+  for (int l = kFrom; l < 16; ++l) {
+    if (x >= range[l].limit) {
+      len = l + 1;
+      delta = l + 1 < 16 ? range[l + 1].delta : 0;
+    }
+  }
+  index = delta + (int)(x >> (15 - min(len, 15)));
   return len;
 }
 
@@ -469,13 +498,12 @@ __device__ static void jpeg_prepare_image(const JpegArgs& a, int b, JpegImage& i
     const int t = lane & 1;
     const bool is_ac = lane >= 2;
     const int o = is_ac ? rec.ac_off[t] : rec.dc_off[t];
-    uint32_t* limit = is_ac ? im.ac[t].limit : im.dc[t].limit;
-    int32_t* delta = is_ac ? im.ac[t].delta : im.dc[t].delta;
+    CodeRange* range = is_ac ? im.ac[t].range : im.dc[t].range;
     int code = 0, index = 0;
     for (int len = 0; len < 16; ++len) {
       const int count = d[min(o + len, n - 1)];
-      delta[len] = index - code;
-      limit[len] = (uint32_t)(code + count) << (15 - len);
+      range[len].delta = index - code;
+      range[len].limit = (uint32_t)(code + count) << (15 - len);
       code = (code + count) << 1;
       index += count;
     }
@@ -483,15 +511,16 @@ __device__ static void jpeg_prepare_image(const JpegArgs& a, int b, JpegImage& i
   __syncthreads();
   for (int t = 0; t < 2; ++t) {
     HuffAc& h = im.ac[t];
-    // the codes of up to 8 bits: code i of length l + 1 owns the prefixes that start with it
+    // the codes of up to 10 bits: code i of length l + 1 owns the prefixes that start with it
     for (int i = lane; i < 256; i += kJpegThreads) {
       int len = 0;  // symbol i belongs to the first length whose symbols reach past it
       for (int l = 0; l < kFastBits; ++l) {
-        const int end = (int)(h.limit[l] >> (15 - l)) + h.delta[l];  // symbols up to this length
+        // symbols up to this length
+        const int end = (int)(h.range[l].limit >> (15 - l)) + h.range[l].delta;
         len += i >= end ? 1 : 0;
       }
       if (len >= kFastBits) continue;
-      const int code = i - h.delta[len];
+      const int code = i - h.range[len].delta;
       const int shift = kFastBits - (len + 1);
       const int first = (code << shift) & ((1 << kFastBits) - 1);
       for (int j = 0; j < (1 << shift); ++j)
@@ -593,9 +622,10 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
           fill(r);
           const uint32_t top = peek32(r);
           const uint32_t x = top >> 16;
-          int len = code_length<0>(h.limit, x);
+          int index;
+          int len = find_code<0>(h.range, x, index);
           int sym = 16;
-          if (len < 16) sym = h.symbols[(h.delta[len] + (int)(x >> (15 - len))) & 15];
+          if (len < 16) sym = h.symbols[index & 15];
           if (sym > 11) {  // no such code, or not a category of 8-bit data
             bad = true;
             sym = 0;
@@ -611,39 +641,46 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
         const uint16_t* qz = im.qz[t];
         if (want) coef[0] = (int16_t)min(max(dcv * (int)(qz[0] & 255), -32767), 32767);
         const HuffAc& h = im.ac[t];
-        for (int k = 1; k < 64;) {  // AC coefficients (F.2.2.2): run of zeros << 4 | size
-          fill(r);
+        fill(r);
+        // AC coefficients (F.2.2.2): a symbol is a run of zeros << 4 | size of the value.  The
+        // usual step -- short code, and the next four bytes ready if the buffer has to be topped
+        // up -- is straight-line code; everything else takes the one branch.
+        for (int k = 1; k < 64;) {
+          const NextFour ahead = next_four(r);  // in flight while the symbol is looked up
           const uint32_t top = peek32(r);
           const int e = h.fast[top >> (32 - kFastBits)];
           int len1 = e >> 8, rs = e & 255;
-          if (!e) {
-            const uint32_t x = top >> 16;
-            const int len = code_length<kFastBits>(h.limit, x);
-            if (len == 16) {
-              bad = true;
-              break;
+          const bool top_up = r.nbits - (len1 + (rs & 15)) <= 32;
+          if (e == 0 || (top_up && !ahead.usable)) {
+            if (!e) {
+              int index;
+              const int len = find_code<kFastBits>(h.range, top >> 16, index);
+              rs = h.symbols[index & 255];
+              len1 = len + 1;
+              if (len == 16) {  // no such code: flag the sample and end the block
+                bad = true;
+                rs = 0;
+                len1 = 0;
+              }
             }
-            rs = h.symbols[(h.delta[len] + (int)(x >> (15 - len))) & 255];
-            len1 = len + 1;
+            r.nbits -= len1 + (rs & 15);
+            fill(r, ahead);
+          } else {
+            r.nbits -= len1 + (rs & 15) - (top_up ? 32 : 0);
+            r.acc = top_up ? (r.acc << 32) | (uint64_t)ahead.bits : r.acc;
+            r.pos += top_up ? 4 : 0;
           }
           const int run = rs >> 4, size = rs & 15;
-          r.nbits -= len1 + size;
-          if (size == 0) {
-            if (run != 15) break;
-            k += 16;
-            continue;
-          }
-          k += run;
-          if (k > 63) {
-            bad = true;
-            break;
-          }
-          if (want) {
+          // size 0: sixteen zeros (run 15) or the end of the block
+          k += size ? run : (run == 15 ? 16 : 64);
+          const bool store = size != 0 && k <= 63;
+          bad = bad || (size != 0 && k > 63);
+          if (store && want) {
             const int zq = qz[k];
             coef[(zq >> 8) * kJpegThreads] =
                 (int16_t)min(max(value_bits(top, len1, size) * (zq & 255), -32767), 32767);
           }
-          ++k;
+          k += size ? 1 : 0;
         }
         if (!want) continue;
         idct_columns(coef);
