@@ -10,13 +10,17 @@
 //    sampling, restart interval, where the tables and the entropy-coded data start) plus the
 //    image's height and width for the crop-parameter kernel.
 //  * jpeg_decode_kernel: one wavefront per group of four images.  Per image the lanes build the
-//    Huffman tables in LDS (canonical codes of Annex F plus a direct table for codes of up to 8
+//    Huffman tables in LDS (the code ranges of Annex C plus a direct table for codes of up to 10
 //    bits) and find the restart markers (16 bytes per lane and step, positions ranked with a
 //    prefix sum); then the rows of MCUs that the crops touch are dealt to the lanes, one row per
-//    lane: Huffman decoding from a 32-bit bit buffer, DC prediction, zero runs, de-quantisation
-//    on insertion, fixed-point separable inverse DCT, repeated chroma, fixed-point JFIF colour
-//    matrix.  RGB bytes go to the image's slot of the decoded-region
-//    buffer, whose rows are the region's rows; the crop record is rewritten relative to the region.
+//    lane.  A lane's file bytes come through its column of a ring in LDS that is fed at the start
+//    of every block, where all lanes are at the same instruction; the bit buffer takes four bytes
+//    at a time unless one of them is 0xFF.  Per block: DC difference, AC symbols with one table
+//    look-up each (code and value bits out of the same 32-bit peek), de-quantisation on
+//    insertion, fixed-point separable inverse DCT in LDS, eight 8-byte stores into the image's
+//    Y, Cb or Cr plane.  The crop record is rewritten relative to the decoded region.
+//  * jpeg_colour_kernel: planes -> interleaved RGB rows of the region (repeated chroma,
+//    fixed-point JFIF colour matrix), which is what the resampling kernel reads.
 //
 // The integer arithmetic of the inverse DCT and of the colour conversion is part of the
 // definition of the output (a decoder is only specified up to that): 13-bit cosines, first pass
@@ -38,7 +42,7 @@ __constant__ uint8_t kZigzag[64] = {
     30, 37, 44, 51, 58, 59, 52, 45, 38, 31, 39, 46, 53, 60, 61, 54, 47, 55, 62, 63};
 
 // C(u) cos((2x+1) u pi / 16) * 2^13 rounded, C(0) = 1/sqrt 2: row x, column u
-__constant__ int16_t kBasis[64] = {
+__constant__ __attribute__((aligned(16))) int16_t kBasis[64] = {
     5793, 8035,  7568,  6811,  5793,  4551,  3135,  1598,   //
     5793, 6811,  3135,  -1598, -5793, -8035, -7568, -4551,  //
     5793, 4551,  -3135, -8035, -5793, 1598,  7568,  6811,   //
@@ -370,18 +374,26 @@ __device__ static inline int find_code(const CodeRange* range, uint32_t x, int& 
   return len;
 }
 
+// Sum over eight 16-bit values times one row of the basis, two products per instruction; the
+// sums stay below 2^31 (the row's absolute values add up to 43284, the values are at most 32767).
+typedef short s16x2 __attribute__((ext_vector_type(2)));
+__device__ static inline int basis_dot(const s16x2 v[4], int row) {
+  const s16x2* basis = reinterpret_cast<const s16x2*>(kBasis) + row * 4;
+  int acc = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) acc = __builtin_amdgcn_sdot2(v[i], basis[i], acc, false);
+  return acc;
+}
+
 // One row of the second pass of the inverse DCT below.
 __device__ static inline void idct_row(const int16_t* coef, int y, int out[8]) {
-  int t[8];
+  s16x2 t[4];
 #pragma unroll
-  for (int u = 0; u < 8; ++u) t[u] = coef[(y * 8 + u) * kJpegThreads];
+  for (int i = 0; i < 4; ++i)
+    t[i] = s16x2{coef[(y * 8 + 2 * i) * kJpegThreads], coef[(y * 8 + 2 * i + 1) * kJpegThreads]};
 #pragma unroll
-  for (int x = 0; x < 8; ++x) {
-    int acc = 0;
-#pragma unroll
-    for (int u = 0; u < 8; ++u) acc += __mul24((int)kBasis[x * 8 + u], t[u]);
-    out[x] = min(max(((acc + (1 << 16)) >> 17) + 128, 0), 255);
-  }
+  for (int x = 0; x < 8; ++x)
+    out[x] = min(max(((basis_dot(t, x) + (1 << 16)) >> 17) + 128, 0), 255);
 }
 
 // Dequantised coefficients (natural order, 16-bit) -> 64 samples, in two passes.  The coefficients
@@ -391,16 +403,14 @@ __device__ static inline void idct_row(const int16_t* coef, int y, int out[8]) {
 // the samples row by row.
 __device__ static inline void idct_columns(int16_t* coef) {
   for (int u = 0; u < 8; ++u) {
-    int c[8], t[8];
+    s16x2 c[4];
+    int t[8];
 #pragma unroll
-    for (int v = 0; v < 8; ++v) c[v] = coef[(v * 8 + u) * kJpegThreads];
+    for (int i = 0; i < 4; ++i)
+      c[i] = s16x2{coef[(2 * i * 8 + u) * kJpegThreads], coef[((2 * i + 1) * 8 + u) * kJpegThreads]};
 #pragma unroll
-    for (int y = 0; y < 8; ++y) {
-      int acc = 0;
-#pragma unroll
-      for (int v = 0; v < 8; ++v) acc += __mul24((int)kBasis[y * 8 + v], c[v]);
-      t[y] = min(max((acc + (1 << 10)) >> 11, -32767), 32767);
-    }
+    for (int y = 0; y < 8; ++y)
+      t[y] = min(max((basis_dot(c, y) + (1 << 10)) >> 11, -32767), 32767);
 #pragma unroll
     for (int y = 0; y < 8; ++y) coef[(y * 8 + u) * kJpegThreads] = (int16_t)t[y];
   }
