@@ -232,7 +232,20 @@ def time_jpeg(args, mae, synth, torch, wl, K):
     assert mae.mae_prep_status(buf.workspace) == 0
     ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
     crop = buf.crop.cpu().numpy().astype(np.int64)
+    cpu = None
+    if not args.no_cpu_baseline:
+        # the oracle beside it: whole-file decode (its definition of the input) of a small sample
+        import oracle
+
+        n = min(256, wl.B)
+        t0 = time.perf_counter()
+        for o, m in zip(offsets[:n], sizes[:n]):
+            oracle.jpeg_decode(files[o:o + m].tobytes())
+        dt = time.perf_counter() - t0
+        cpu = {"images_per_s": round(n / dt, 1), "cores": 1, "kind": "oracle",
+               "sample": f"whole-file decode of the first {n} files of the batch, decode only"}
     return {
+        "cpu_oracle_decode": cpu,
         "input": "baseline JPEG, quality 90, 4:2:0, restart interval = one row of MCUs",
         "file_bytes": int(files.size), "encode_s_on_host": round(enc_s, 1),
         "avg_ms": round(ms, 4), "images_per_s": round(wl.B / (ms * 1e-3), 1),

@@ -164,7 +164,10 @@ int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t
                    int32_t* ids_keep, float* target, int32_t* crop_out, void* workspace,
                    size_t workspace_bytes, void* hip_stream);
 
-/* Bytes of workspace mae_prep_batch needs for this descriptor (0 if the descriptor is invalid). */
+/* Bytes of workspace mae_prep_batch needs for this descriptor (0 if the descriptor is invalid).
+ * A few hundred bytes plus 32 per image; with augmentation also out_size^2 * 3 per image; with
+ * MAE_INPUT_JPEG also the decoded planes and the RGB regions, together 6 bytes per pixel of a
+ * square of side max_image_side rounded up to 16 (0 = 256), per image. */
 size_t mae_prep_workspace_bytes(const mae_prep_desc* d);
 
 /* Waits for `hip_stream`, then stores in *host_invalid_samples how many samples of the last

@@ -128,6 +128,44 @@ def test_prep_workspace_grows_with_the_augmentation(lib):
     assert _call_prep(lib, d, ws_bytes=plus - 1) == binding.MAE_ERR_WORKSPACE
 
 
+def _jpeg_desc(**over):
+    d = _prep_desc(heights=None, widths=None, input_format=binding.MAE_INPUT_JPEG, file_sizes=FAKE)
+    for k, v in over.items():
+        setattr(d, k, v)
+    return d
+
+
+@pytest.mark.parametrize("over,status", [
+    (dict(input_format=2), binding.MAE_ERR_RANGE),
+    (dict(input_format=-1), binding.MAE_ERR_RANGE),
+    (dict(file_sizes=None), binding.MAE_ERR_NULL),
+    (dict(images=FAKE + 4), binding.MAE_ERR_RANGE),     # files are read in aligned 8-byte pieces
+    (dict(offsets=None), binding.MAE_ERR_NULL),
+])
+def test_prep_rejects_bad_jpeg_descriptors(lib, over, status):
+    d = _jpeg_desc(**over)
+    assert _call_prep(lib, d, ws_bytes=1 << 30) == status
+    assert lib.mae_prep_workspace_bytes(C.byref(d)) == 0
+
+
+def test_jpeg_input_needs_no_sizes_and_a_slot_per_image(lib):
+    """Heights and widths come out of the files; the workspace holds, per image, one slot for the
+    decoded planes and one for the RGB region, each 3 bytes per pixel of a square whose side is
+    max_image_side rounded up to 16 (256 when the caller gives none)."""
+    up = lambda v: (v + 255) & ~255
+    B = 4
+    tables = 256 + B * 32
+    for step in (B * 64, B * 4, B * 4, B * 4, B * 8):    # file records, heights, widths, region widths, offsets
+        tables = up(tables) + step
+    for side, slot in ((0, 256), (500, 512), (512, 512), (513, 528)):
+        d = _jpeg_desc(max_image_side=side)
+        want = up(up(tables) + B * slot * slot * 3) + B * slot * slot * 3
+        assert lib.mae_prep_workspace_bytes(C.byref(d)) == want
+        assert _call_prep(lib, d, ws_bytes=want - 1) == binding.MAE_ERR_WORKSPACE
+    # decoded input with a file-size array is simply decoded input
+    assert lib.mae_prep_workspace_bytes(C.byref(_prep_desc(file_sizes=FAKE))) == 256 + B * 32
+
+
 def test_prep_rejects_bad_buffers(lib):
     d = _prep_desc()
     need = lib.mae_prep_workspace_bytes(C.byref(d))
