@@ -286,8 +286,9 @@ __device__ static inline NextFour next_four(const BitReader& r) {
   const uint32_t inv = ~x;  // a byte 0xFF of x is a zero byte here
   NextFour f;
   f.bits = __builtin_bswap32(x);
-  f.usable = !r.ended && r.pos + 4 <= r.n && q + 4 <= r.have &&
-             ((inv - 0x01010101u) & ~inv & 0x80808080u) == 0u;
+  // (no short-circuit: straight-line code lets the reads above overlap the table look-up)
+  f.usable = (int)!r.ended & (int)(r.pos + 4 <= r.n) & (int)(q + 4 <= r.have) &
+             (int)(((inv - 0x01010101u) & ~inv & 0x80808080u) == 0u);
   return f;
 }
 __device__ static inline void fill_bytewise(BitReader& r);
@@ -661,7 +662,7 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
           const int e = h.fast[top >> (32 - kFastBits)];
           int len1 = e >> 8, rs = e & 255;
           const bool top_up = r.nbits - (len1 + (rs & 15)) <= 32;
-          if (e == 0 || (top_up && !ahead.usable)) {
+          if ((int)(e == 0) | ((int)top_up & (int)!ahead.usable)) {
             if (!e) {
               int index;
               const int len = find_code<kFastBits>(h.range, top >> 16, index);
