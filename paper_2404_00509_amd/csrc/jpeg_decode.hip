@@ -439,7 +439,8 @@ struct JpegImage {
 
 struct JpegLds {
   JpegImage img[kJpegGroup];
-  int16_t coef[64][kJpegThreads];  // one block per lane, the lane is the fastest index
+  // one block per lane, the lane is the fastest index; row 64 takes the stores of skipped blocks
+  int16_t coef[65][kJpegThreads];
   // first byte of each of the crop's rows of MCUs, -1 = marker not found
   int row_start[kJpegGroup][kJpegThreads];
   uint32_t ring[kRingBytes / 4][kJpegThreads];  // file bytes on their way to the lanes
@@ -686,10 +687,10 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
           k += size ? run : (run == 15 ? 16 : 64);
           const bool store = size != 0 && k <= 63;
           bad = bad || (size != 0 && k > 63);
-          if (store && want) {
-            const int zq = qz[k];
-            coef[(zq >> 8) * kJpegThreads] =
-                (int16_t)min(max(value_bits(top, len1, size) * (zq & 255), -32767), 32767);
+          {  // no branch: what is not to be stored goes to the spare row 64
+            const int zq = qz[k & 63];
+            coef[(store && want ? zq >> 8 : 64) * kJpegThreads] = (int16_t)min(
+                max(value_bits(top, len1, size ? size : 1) * (zq & 255), -32767), 32767);
           }
           k += size ? 1 : 0;
         }
