@@ -80,6 +80,53 @@ def test_bf16_tokens_and_finetune_augmentation_from_jpeg():
     check_prep_against_oracle(prep_to_numpy(buf), ref, bf16=True, what="jpeg + 3 Aug+")
 
 
+@pytest.mark.parametrize("quality,optimize", [(50, True), (98, True), (98, False)])
+def test_tables_of_the_file_and_other_qualities(quality, optimize):
+    """Huffman tables fitted to each image (other code lengths than the standard tables', found
+    in the file) and quantisers from coarse to nearly lossless (values of up to 10 bits)."""
+    B, S = 12, 96
+    files, offsets, sizes = synth.make_jpegs("gradient", B, seed=64, quality=quality,
+                                             optimize=optimize)
+    L = (S // 16) ** 2
+    kw = dict(out_size=S, patch=16, num_keep=oracle.num_keep(L, 0.75), seed=17, batch_index=4)
+    ref = oracle.prep_batch(*_decode_all(files, offsets, sizes), **kw)
+    buf, _ = _gpu_jpeg_prep(files, offsets, sizes, **kw)
+    assert mae.mae_prep_status(buf.workspace) == 0
+    check_prep_against_oracle(prep_to_numpy(buf), ref, what=f"quality {quality}")
+
+
+def test_image_shapes_at_the_limits():
+    """64 rows of MCUs (the most a file may have) in both samplings, a row of 63 MCUs, images
+    smaller than one MCU and with ragged edges; one row of MCUs too many is flagged.  Several
+    lanes get more than one row here (the group's rows exceed the wavefront)."""
+    import io
+
+    from PIL import Image
+    shapes = [(512, 72, "4:4:4"), (1024, 48, "4:2:0"), (48, 1000, "4:2:0"), (8, 8, "4:4:4"),
+              (5, 7, "4:2:0"), (17, 23, "4:2:0"), (505, 131, "4:4:4"), (520, 64, "4:4:4")]
+    rng = np.random.default_rng(65)
+    chunks = []
+    for h, w, sub in shapes:
+        buf = io.BytesIO()
+        Image.fromarray(synth._one_image("gradient", h, w, rng)).save(
+            buf, format="JPEG", quality=90, subsampling=sub, restart_marker_rows=1)
+        chunks.append(np.frombuffer(buf.getvalue(), np.uint8))
+    sizes = np.array([c.size for c in chunks], np.int32)
+    offsets = np.zeros(len(chunks), np.int64)
+    offsets[1:] = np.cumsum(sizes.astype(np.int64))[:-1]
+    files = np.concatenate(chunks)
+    S = 64
+    L = (S // 16) ** 2
+    for scale in ((0.2, 1.0), (1.0, 1.0)):
+        kw = dict(out_size=S, patch=16, num_keep=L, scale=scale, seed=18, batch_index=5)
+        buf, _ = _gpu_jpeg_prep(files, offsets, sizes, max_image_side=1024, **kw)
+        crop = buf.crop.cpu().numpy()
+        assert list(np.nonzero(crop[:, 5] == 0)[0]) == [7]        # 65 rows of MCUs
+        keep = list(range(7))
+        ref = oracle.prep_batch(*_decode_all(files, offsets[:7], sizes[:7]), **kw)
+        check_prep_against_oracle(prep_to_numpy(buf, rows=keep), ref, what=f"limits {scale}")
+
+
 def test_files_the_decoder_does_not_take_are_flagged_and_the_rest_is_untouched():
     import io
 
