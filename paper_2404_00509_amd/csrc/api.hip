@@ -133,9 +133,9 @@ namespace {
 // starts on a 256-byte boundary.
 struct PrepWorkspace {
   size_t u8_offset, partials_offset, total;
-  // crop decode: per-file records, heights, widths, region widths, region offsets, planes, regions
+  // crop decode: per-file records, heights, widths, region widths, region offsets, tables, planes, regions
   size_t recs_offset, heights_offset, widths_offset, region_widths_offset, region_offsets_offset,
-      planes_offset, regions_offset;
+      prepared_offset, planes_offset, regions_offset;
   int slot_side;
 };
 PrepWorkspace prep_workspace(const mae_prep_desc* d) {
@@ -145,7 +145,7 @@ PrepWorkspace prep_workspace(const mae_prep_desc* d) {
   w.partials_offset = w.u8_offset;
   w.total = mae::kWorkspaceHeader + (size_t)d->B * sizeof(mae::CropRec);
   w.recs_offset = w.heights_offset = w.widths_offset = w.region_widths_offset = 0;
-  w.region_offsets_offset = w.planes_offset = w.regions_offset = 0;
+  w.region_offsets_offset = w.prepared_offset = w.planes_offset = w.regions_offset = 0;
   w.slot_side = 0;
   if (d->aug_mode != MAE_AUG_SIMPLE) {
     w.partials_offset = up(w.u8_offset + (size_t)d->B * d->out_size * d->out_size * 3);
@@ -162,7 +162,8 @@ PrepWorkspace prep_workspace(const mae_prep_desc* d) {
     w.widths_offset = up(w.heights_offset + B * 4);
     w.region_widths_offset = up(w.widths_offset + B * 4);
     w.region_offsets_offset = up(w.region_widths_offset + B * 4);
-    w.planes_offset = up(w.region_offsets_offset + B * 8);
+    w.prepared_offset = up(w.region_offsets_offset + B * 8);
+    w.planes_offset = up(w.prepared_offset + B * mae::jpeg_prepared_bytes());
     w.regions_offset = up(w.planes_offset + B * (size_t)w.slot_side * w.slot_side * 3);
     w.total = w.regions_offset + B * (size_t)w.slot_side * w.slot_side * 3;
   }
@@ -226,6 +227,7 @@ int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t
     ja.widths = reinterpret_cast<int32_t*>(ws + wsl.widths_offset);
     ja.region_offsets = reinterpret_cast<int64_t*>(ws + wsl.region_offsets_offset);
     ja.region_widths = reinterpret_cast<int32_t*>(ws + wsl.region_widths_offset);
+    ja.prepared = ws + wsl.prepared_offset;
     ja.planes = ws + wsl.planes_offset;
     ja.regions = ws + wsl.regions_offset;
     ja.workspace = ws;

@@ -437,12 +437,17 @@ struct JpegImage {
   int64_t origin, region_off;
 };
 
+// What the table kernel hands to the decode kernel per image (through the workspace).
+struct alignas(16) JpegPrepared {
+  JpegImage im;
+  int row_start[kJpegThreads];  // first byte of each of the crop's rows of MCUs, -1 = not found
+};
+static_assert(sizeof(JpegPrepared) % 16 == 0, "copied in 16-byte pieces");
+
 struct JpegLds {
-  JpegImage img[kJpegGroup];
+  JpegPrepared img[kJpegGroup];
   // one block per lane, the lane is the fastest index; row 64 takes the stores of skipped blocks
   int16_t coef[65][kJpegThreads];
-  // first byte of each of the crop's rows of MCUs, -1 = marker not found
-  int row_start[kJpegGroup][kJpegThreads];
   uint32_t ring[kRingBytes / 4][kJpegThreads];  // file bytes on their way to the lanes
 };
 
@@ -569,12 +574,34 @@ __device__ static void jpeg_prepare_image(const JpegArgs& a, int b, JpegImage& i
   if (my0 == 0 && lane == 0) row_start[0] = rec.scan_off;
 }
 
+// One wavefront per image: tables, crop geometry, row starts -> workspace.  Many of these fit a
+// CU at once, which hides the latency of the scattered header reads and of the marker scan.
+__global__ __launch_bounds__(kJpegThreads) void jpeg_tables_kernel(JpegArgs a) {
+  __shared__ JpegPrepared p;
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  const int b = (int)blockIdx.x;
+  for (int i = threadIdx.x; i < (int)(sizeof(JpegPrepared) / 16); i += kJpegThreads)
+    reinterpret_cast<u32x4*>(&p)[i] = u32x4{0u, 0u, 0u, 0u};
+  __syncthreads();
+  jpeg_prepare_image(a, b, p.im, p.row_start);
+  __syncthreads();
+  u32x4* dst = reinterpret_cast<u32x4*>(a.prepared + (size_t)b * sizeof(JpegPrepared));
+  for (int i = threadIdx.x; i < (int)(sizeof(JpegPrepared) / 16); i += kJpegThreads)
+    dst[i] = reinterpret_cast<const u32x4*>(&p)[i];
+}
+
 __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
   __shared__ JpegLds s;
   const int lane = threadIdx.x;
   const int b0 = (int)blockIdx.x * kJpegGroup;
   const int nimg = min(kJpegGroup, a.B - b0);
-  for (int i = 0; i < nimg; ++i) jpeg_prepare_image(a, b0 + i, s.img[i], s.row_start[i]);
+  {  // the images' tables and row starts, as the table kernel left them
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4* src = reinterpret_cast<const u32x4*>(a.prepared + (size_t)b0 * sizeof(JpegPrepared));
+    u32x4* dst = reinterpret_cast<u32x4*>(&s.img[0]);
+    const int n16 = nimg * (int)(sizeof(JpegPrepared) / 16);
+    for (int i = lane; i < n16; i += kJpegThreads) dst[i] = src[i];
+  }
   __syncthreads();
 
   // the rows of MCUs of the group's images, one after the other, are dealt to the lanes
@@ -582,7 +609,7 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
   first_task[0] = 0;
 #pragma unroll
   for (int i = 0; i < kJpegGroup; ++i)
-    first_task[i + 1] = first_task[i] + (i < nimg ? s.img[i].nrows : 0);
+    first_task[i + 1] = first_task[i] + (i < nimg ? s.img[i].im.nrows : 0);
   const int ntasks = first_task[kJpegGroup];
   int16_t* coef = &s.coef[0][lane];  // element k at coef[k * 64]
 #pragma unroll 1
@@ -598,8 +625,8 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
       }
     }
     const int row = task - slot_first;  // row of MCUs inside the crop's range
-    const int start = s.row_start[slot][row & (kJpegThreads - 1)];
-    const JpegImage& im = s.img[slot];
+    const int start = s.img[slot].row_start[row & (kJpegThreads - 1)];
+    const JpegImage& im = s.img[slot].im;
     const int b = b0 + slot;
     const int hs = im.hs, mcu = 8 * hs;
     const int mx0 = im.mx0, mx1 = im.mx1, region_w = im.region_w;
@@ -725,6 +752,8 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
   }
 }
 
+size_t jpeg_prepared_bytes() { return sizeof(JpegPrepared); }
+
 hipError_t launch_jpeg_header(const JpegArgs& a, hipStream_t stream) {
   dim3 grid((uint32_t)((a.B + kJpegThreads - 1) / kJpegThreads)), block(kJpegThreads);
   hipLaunchKernelGGL(jpeg_header_kernel, grid, block, 0, stream, a);
@@ -781,6 +810,8 @@ __global__ __launch_bounds__(kColourThreads) void jpeg_colour_kernel(JpegArgs a,
 
 hipError_t launch_jpeg_decode(const JpegArgs& a, hipStream_t stream) {
   dim3 grid((uint32_t)((a.B + kJpegGroup - 1) / kJpegGroup)), block(kJpegThreads);
+  hipLaunchKernelGGL(jpeg_tables_kernel, dim3((uint32_t)a.B), block, 0, stream, a);
+  if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
   hipLaunchKernelGGL(jpeg_decode_kernel, grid, block, 0, stream, a);
   if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
   const int bands = (a.slot_side + kColourBand - 1) / kColourBand;

@@ -104,11 +104,13 @@ struct JpegArgs {
   int32_t* widths;
   int64_t* region_offsets;
   int32_t* region_widths;
+  uint8_t* prepared; // per image: Huffman and quantiser tables, crop geometry, row starts
   uint8_t* planes;   // decoded Y, Cb, Cr planes, one slot per image like `regions`
   uint8_t* regions;
   uint8_t* workspace;  // header + CropRec[B]
   int32_t* crop_out;   // nullable, [B,6]: the valid flag is cleared for files that cannot be used
 };
+size_t jpeg_prepared_bytes();  // per image, in the workspace
 hipError_t launch_jpeg_header(const JpegArgs& a, hipStream_t stream);
 hipError_t launch_jpeg_decode(const JpegArgs& a, hipStream_t stream);
 

@@ -155,7 +155,8 @@ def test_jpeg_input_needs_no_sizes_and_a_slot_per_image(lib):
     up = lambda v: (v + 255) & ~255
     B = 4
     tables = 256 + B * 32
-    for step in (B * 64, B * 4, B * 4, B * 4, B * 8):    # file records, heights, widths, region widths, offsets
+    # file records, heights, widths, region widths, offsets, decoding tables (5728 bytes per image)
+    for step in (B * 64, B * 4, B * 4, B * 4, B * 8, B * 5728):
         tables = up(tables) + step
     for side, slot in ((0, 256), (500, 512), (512, 512), (513, 528)):
         d = _jpeg_desc(max_image_side=side)

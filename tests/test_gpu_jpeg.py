@@ -43,7 +43,7 @@ def _gpu_jpeg_prep(files, offsets, sizes, bf16=False, **kw):
 @pytest.mark.parametrize("sub", ["4:2:0", "4:4:4"])
 @pytest.mark.parametrize("kind,S", [("gradient", 112), ("uniform", 64)])
 def test_crop_decode_matches_full_decode(sub, kind, S):
-    B = 16
+    B = 16 if sub == "4:2:0" else 13      # 13: the last group of images is not full
     files, offsets, sizes = synth.make_jpegs(kind, B, seed=60, subsampling=sub)
     L = (S // 16) ** 2
     kw = dict(out_size=S, patch=16, num_keep=oracle.num_keep(L, 0.75), seed=13, batch_index=1)
