@@ -174,6 +174,49 @@ def test_files_the_decoder_does_not_take_are_flagged_and_the_rest_is_untouched()
         assert torch.isnan(buf.target[b]).all()
 
 
+def test_jpeg_input_on_a_side_stream_and_in_a_captured_graph():
+    """The JPEG path enqueues kernels only (header, crop draws, tables, decode, colour, resample,
+    augmentation): it can run on any stream and be captured; every replay is checked."""
+    B, S = 8, 96
+    files, offsets, sizes = synth.make_jpegs("gradient", B, seed=66)
+    L = (S // 16) ** 2
+    kw = dict(out_size=S, patch=16, num_keep=L, seed=19, batch_index=6,
+              aug_mode=mae.MAE_AUG_THREE_PLUS, jitter=0.3)
+    ref = oracle.prep_batch(*_decode_all(files, offsets, sizes), **kw)
+    dev = [torch.from_numpy(a).cuda() for a in (files, offsets, sizes)]
+    desc = mae.make_prep_desc(dev[0], dev[1], None, None, file_sizes=dev[2], **kw)
+    buf = mae.alloc_prep_buffers(desc)
+
+    def step(stream):
+        mae.mae_prep_batch(desc, buf.visible, buf.mask, buf.ids_restore, buf.ids_keep, buf.target,
+                           buf.crop, buf.workspace, stream=stream)
+
+    def wipe():
+        buf.visible.fill_(float("nan"))
+        buf.target.fill_(float("nan"))
+        buf.ids_restore.fill_(-1)
+        buf.workspace.zero_()
+        torch.cuda.synchronize()
+
+    side = torch.cuda.Stream()
+    wipe()
+    with torch.cuda.stream(side):
+        step(side)
+    side.synchronize()
+    check_prep_against_oracle(prep_to_numpy(buf), ref, what="side stream")
+    graph = torch.cuda.CUDAGraph()
+    wipe()
+    with torch.cuda.graph(graph):
+        step(torch.cuda.current_stream())
+    for replay in range(3):
+        wipe()
+        graph.replay()
+        torch.cuda.synchronize()
+        check_prep_against_oracle(prep_to_numpy(buf), ref, what=f"graph replay {replay}")
+        buf.target.mul_(1.0)          # eager work between replays
+        torch.cuda.synchronize()
+
+
 def test_crop_decode_full_size_sampled():
     """The bench's launch: 4096 files (max side 256, quality 90, 4:2:0) -> 224 px."""
     wl = synth.WORKLOADS["c4"]
