@@ -211,7 +211,7 @@ struct BitReader {
 };
 
 // The 16 bytes at `chunks + at`; bytes beyond the buffer read as zero.
-__device__ static inline u32x4_a8 load_chunk(const BitReader& r, int at) {
+__device__ static inline u32x4_a8 load_chunk(const BitReader& r, int64_t at) {
   if ((int64_t)at + 16 <= r.chunks_bytes) return *reinterpret_cast<const u32x4_a8*>(r.chunks + at);
   uint32_t w[4] = {0u, 0u, 0u, 0u};
   for (int i = 0; i < 16; ++i)
@@ -501,58 +501,78 @@ __device__ static void jpeg_prepare_image(const JpegArgs& a, int b, JpegImage& i
     crop->left = cr.left - mx0 * mcu;
   }
 
-  // tables: symbols and quantiser steps by all lanes, the code ranges by one lane per table
+  // tables: symbols and quantiser steps by all lanes
   for (int t = 0; t < 2; ++t) {
     if (lane < 16) im.dc[t].symbols[lane] = d[min(rec.dc_off[t] + 16 + lane, n - 1)];
     for (int i = lane; i < 256; i += kJpegThreads)
       im.ac[t].symbols[i] = d[min(rec.ac_off[t] + 16 + i, n - 1)];
-    for (int i = lane; i < (1 << kFastBits); i += kJpegThreads) im.ac[t].fast[i] = 0;
   }
   for (int i = lane; i < 128; i += kJpegThreads)
     im.qz[i >> 6][i & 63] =
         (uint16_t)(((int)kZigzag[i & 63] << 8) | d[min(rec.q_off[i >> 6] + (i & 63), n - 1)]);
-  if (lane < 4) {
-    const int t = lane & 1;
-    const bool is_ac = lane >= 2;
-    const int o = is_ac ? rec.ac_off[t] : rec.dc_off[t];
-    CodeRange* range = is_ac ? im.ac[t].range : im.dc[t].range;
+  {  // code ranges: lane = table * 16 + (length - 1); the counts of the shorter lengths come from
+     // the lanes before it (first code of a length = twice the end of the length before)
+    const int tt = lane >> 4, len = lane & 15;
+    const int t = tt & 1;
+    const bool is_ac = tt >= 2;
+    const int count = d[min((is_ac ? rec.ac_off[t] : rec.dc_off[t]) + len, n - 1)];
     int code = 0, index = 0;
-    for (int len = 0; len < 16; ++len) {
-      const int count = d[min(o + len, n - 1)];
-      range[len].delta = index - code;
-      range[len].limit = (uint32_t)(code + count) << (15 - len);
-      code = (code + count) << 1;
-      index += count;
+    for (int j = 0; j < 15; ++j) {
+      const int cj = __shfl(count, (tt << 4) + j);
+      if (j < len) {
+        code += cj << (len - j);
+        index += cj;
+      }
     }
+    CodeRange* range = is_ac ? im.ac[t].range : im.dc[t].range;
+    range[len].delta = index - code;
+    range[len].limit = (uint32_t)(code + count) << (15 - len);
   }
   __syncthreads();
   for (int t = 0; t < 2; ++t) {
     HuffAc& h = im.ac[t];
-    // the codes of up to 10 bits: code i of length l + 1 owns the prefixes that start with it
-    for (int i = lane; i < 256; i += kJpegThreads) {
-      int len = 0;  // symbol i belongs to the first length whose symbols reach past it
-      for (int l = 0; l < kFastBits; ++l) {
-        // symbols up to this length
-        const int end = (int)(h.range[l].limit >> (15 - l)) + h.range[l].delta;
-        len += i >= end ? 1 : 0;
-      }
-      if (len >= kFastBits) continue;
-      const int code = i - h.range[len].delta;
-      const int shift = kFastBits - (len + 1);
-      const int first = (code << shift) & ((1 << kFastBits) - 1);
-      for (int j = 0; j < (1 << shift); ++j)
-        h.fast[(first + j) & ((1 << kFastBits) - 1)] = (uint16_t)(((len + 1) << 8) | h.symbols[i]);
+    // direct table: the code that starts a 10-bit prefix is the one of the first length whose
+    // range the prefix (followed by zeros) falls into; none = a longer code
+    for (int i = lane; i < (1 << kFastBits); i += kJpegThreads) {
+      const uint32_t x = (uint32_t)i << (16 - kFastBits);
+      int len = kFastBits;
+      for (int l = kFastBits - 1; l >= 0; --l)
+        if (x < h.range[l].limit) len = l;
+      uint16_t e = 0;
+      if (len < kFastBits)
+        e = (uint16_t)(((len + 1) << 8) |
+                       h.symbols[(h.range[len].delta + (int)(x >> (15 - len))) & 255]);
+      h.fast[i] = e;
     }
   }
 
-  // restart markers: marker m (0-based) ends MCU row m; row r starts after marker r - 1
-  int seen = 0;  // markers before the current step
-  for (int base = rec.scan_off; base < n - 1 && seen <= my1; base += kJpegThreads * 16) {
-    uint32_t mask = 0;  // bit i: a restart marker starts at byte p0 + i
-    const int p0 = base + lane * 16;
+  // restart markers: marker m (0-based) ends MCU row m; row r starts after marker r - 1.  The
+  // file is scanned in aligned 16-byte pieces of the buffer, one per lane and step, the next
+  // step's pieces loaded while this step's are examined.
+  const int64_t origin = a.offsets[b];
+  BitReader all;  // only its view of the whole buffer is used
+  all.chunks = a.files;
+  all.chunks_bytes = a.files_bytes;
+  const int64_t first = (origin + rec.scan_off) & ~(int64_t)15;
+  const int64_t last = origin + n - 1;  // a marker starts before this byte
+  int seen = 0;                         // markers before the current step
+  u32x4_a8 cur = load_chunk(all, first + lane * 16);
+  for (int64_t base = first; base < last && seen <= my1; base += kJpegThreads * 16) {
+    const int64_t at = base + lane * 16;
+    const u32x4_a8 next = load_chunk(all, at + kJpegThreads * 16);
+    // the byte after this piece: the first of the next lane's, or of the next step's
+    uint32_t follow = (uint32_t)__shfl_down((int)(cur.x & 0xFFu), 1);
+    const uint32_t wrap = (uint32_t)__shfl((int)(next.x & 0xFFu), 0);
+    if (lane == kJpegThreads - 1) follow = wrap;
+    const int p0 = (int)(at - origin);  // file position of the piece (negative before the file)
+    uint32_t mask = 0;                  // bit i: a restart marker starts at byte p0 + i
+#pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const int p = p0 + i;
-      if (p + 1 < n && d[p] == 0xFF && (d[p + 1] & 0xF8) == 0xD0) mask |= 1u << i;
+      const uint32_t b0 = (cur[i >> 2] >> (8 * (i & 3))) & 0xFFu;
+      const uint32_t b1 = i < 15 ? (cur[(i + 1) >> 2] >> (8 * ((i + 1) & 3))) & 0xFFu : follow;
+      const int pp = p0 + i;
+      if (pp >= rec.scan_off && pp + 1 < n && b0 == 0xFFu && (b1 & 0xF8u) == 0xD0u)
+        mask |= 1u << i;
     }
     const int cnt = __popc(mask);
     // rank of this lane's first marker among the wavefront's: counts of the lanes before it
@@ -570,6 +590,7 @@ __device__ static void jpeg_prepare_image(const JpegArgs& a, int b, JpegImage& i
       if (row >= my0 && row <= my1) row_start[row - my0] = p0 + i + 2;
     }
     seen += total;
+    cur = next;
   }
   if (my0 == 0 && lane == 0) row_start[0] = rec.scan_off;
 }
