@@ -9,16 +9,19 @@
 //  * jpeg_header_kernel: one lane per file walks the marker segments and leaves a record (size,
 //    sampling, restart interval, where the tables and the entropy-coded data start) plus the
 //    image's height and width for the crop-parameter kernel.
-//  * jpeg_decode_kernel: one wavefront per group of four images.  Per image the lanes build the
-//    Huffman tables in LDS (the code ranges of Annex C plus a direct table for codes of up to 10
-//    bits) and find the restart markers (16 bytes per lane and step, positions ranked with a
-//    prefix sum); then the rows of MCUs that the crops touch are dealt to the lanes, one row per
-//    lane.  A lane's file bytes come through its column of a ring in LDS that is fed at the start
-//    of every block, where all lanes are at the same instruction; the bit buffer takes four bytes
-//    at a time unless one of them is 0xFF.  Per block: DC difference, AC symbols with one table
+//  * jpeg_tables_kernel: one wavefront per image builds what the decoder needs and leaves it in
+//    the workspace: the Huffman tables (the code ranges of Annex C plus a direct table for codes
+//    of up to 10 bits), the quantiser steps in zig-zag order, the crop's rows and columns of
+//    MCUs, and the restart markers (16 bytes per lane and step, positions ranked with a prefix
+//    sum).  The crop record is rewritten relative to the decoded region.
+//  * jpeg_decode_kernel: one wavefront per group of four images, their tables copied into LDS;
+//    the rows of MCUs that the crops touch are dealt to the lanes, one row per lane.  A lane's
+//    file bytes come through its column of a ring in LDS that is fed at the start of every
+//    block, where all lanes are at the same instruction; the bit buffer takes four bytes at a
+//    time unless one of them is 0xFF.  Per block: DC difference, AC symbols with one table
 //    look-up each (code and value bits out of the same 32-bit peek), de-quantisation on
 //    insertion, fixed-point separable inverse DCT in LDS, eight 8-byte stores into the image's
-//    Y, Cb or Cr plane.  The crop record is rewritten relative to the decoded region.
+//    Y, Cb or Cr plane.
 //  * jpeg_colour_kernel: planes -> interleaved RGB rows of the region (repeated chroma,
 //    fixed-point JFIF colour matrix), which is what the resampling kernel reads.
 //
