@@ -931,6 +931,26 @@ def test_colour_conversion_matches_the_jfif_matrix():
     assert oracle.ycc_to_rgb(100, 28, 128) == (100, 134, 0)     # 100 + 34.4136; 100 - 177.2 -> 0
 
 
+def _hand_jpeg(golden):
+    rows = {r[0]: r[1:] for r in golden("jpeg_hand_example.txt")}
+    data = bytes.fromhex("".join(rows.pop("file")))
+    return data, {k: [int(v) for v in r] for k, r in rows.items()}
+
+
+def test_jpeg_file_written_by_hand(golden):
+    """A file assembled segment by segment, and the pixels worked out from the standard's
+    formulas (both in the fixture, with the derivation): no encoder, no library."""
+    data, rows = _hand_jpeg(golden)
+    info = oracle.jpeg_info(data)
+    assert (info["H"], info["W"], info["luma_h"], info["restart_interval"]) == (8, 8, 1, 1)
+    ycc = oracle.jpeg_decode(data, ycc=True)
+    rgb = oracle.jpeg_decode(data)
+    for y in range(8):                                   # the coefficient varies along x only
+        assert list(ycc[y, :, 0]) == rows["row_y"]
+        assert set(ycc[y, :, 1]) == {128} and set(ycc[y, :, 2]) == {118}
+        assert [list(rgb[y, :, c]) for c in range(3)] == [rows["row_r"], rows["row_g"], rows["row_b"]]
+
+
 @pytest.mark.parametrize("sub,h,w", [("4:4:4", 61, 83), ("4:2:0", 61, 83), ("4:4:4", 128, 64),
                                      ("4:2:0", 96, 112)])
 def test_jpeg_decoder_against_the_imaging_library(sub, h, w):
