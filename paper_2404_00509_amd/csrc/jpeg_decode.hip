@@ -428,8 +428,8 @@ __device__ static inline uint32_t ycc_to_rgbx(int y, int cb, int cr) {
   return (uint32_t)R | ((uint32_t)G << 8) | ((uint32_t)B << 16);
 }
 
-constexpr int kJpegGroup = 4;  // images per workgroup: their rows of MCUs share the 64 lanes
-constexpr int kJpegRounds = kJpegGroup;  // a lane gets at most this many rows (64 rows per image)
+// Images per workgroup of the decode kernel (template parameter kGroup: 4, 2 or 1): their rows of
+// MCUs share the 64 lanes.  A lane gets at most kGroup rows (an image has at most 64).
 
 // What the wavefront keeps per image of its group.
 struct JpegImage {
@@ -447,8 +447,9 @@ struct alignas(16) JpegPrepared {
 };
 static_assert(sizeof(JpegPrepared) % 16 == 0, "copied in 16-byte pieces");
 
+template <int kGroup>
 struct JpegLds {
-  JpegPrepared img[kJpegGroup];
+  JpegPrepared img[kGroup];
   // one block per lane, the lane is the fastest index; row 64 takes the stores of skipped blocks
   int16_t coef[65][kJpegThreads];
   uint32_t ring[kRingBytes / 4][kJpegThreads];  // file bytes on their way to the lanes
@@ -614,11 +615,12 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_tables_kernel(JpegArgs a) {
     dst[i] = reinterpret_cast<const u32x4*>(&p)[i];
 }
 
+template <int kGroup>
 __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
-  __shared__ JpegLds s;
+  __shared__ JpegLds<kGroup> s;
   const int lane = threadIdx.x;
-  const int b0 = (int)blockIdx.x * kJpegGroup;
-  const int nimg = min(kJpegGroup, a.B - b0);
+  const int b0 = (int)blockIdx.x * kGroup;
+  const int nimg = min(kGroup, a.B - b0);
   {  // the images' tables and row starts, as the table kernel left them
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     const u32x4* src = reinterpret_cast<const u32x4*>(a.prepared + (size_t)b0 * sizeof(JpegPrepared));
@@ -629,20 +631,20 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
   __syncthreads();
 
   // the rows of MCUs of the group's images, one after the other, are dealt to the lanes
-  int first_task[kJpegGroup + 1];
+  int first_task[kGroup + 1];
   first_task[0] = 0;
 #pragma unroll
-  for (int i = 0; i < kJpegGroup; ++i)
+  for (int i = 0; i < kGroup; ++i)
     first_task[i + 1] = first_task[i] + (i < nimg ? s.img[i].im.nrows : 0);
-  const int ntasks = first_task[kJpegGroup];
+  const int ntasks = first_task[kGroup];
   int16_t* coef = &s.coef[0][lane];  // element k at coef[k * 64]
 #pragma unroll 1
-  for (int it = 0; it < kJpegRounds; ++it) {
+  for (int it = 0; it < kGroup; ++it) {
     const int task = lane + it * kJpegThreads;
     if (task >= ntasks) break;
     int slot = 0, slot_first = 0;
 #pragma unroll
-    for (int i = 1; i < kJpegGroup; ++i) {
+    for (int i = 1; i < kGroup; ++i) {
       if (task >= first_task[i]) {
         slot = i;
         slot_first = first_task[i];
@@ -833,10 +835,19 @@ __global__ __launch_bounds__(kColourThreads) void jpeg_colour_kernel(JpegArgs a,
 }
 
 hipError_t launch_jpeg_decode(const JpegArgs& a, hipStream_t stream) {
-  dim3 grid((uint32_t)((a.B + kJpegGroup - 1) / kJpegGroup)), block(kJpegThreads);
+  dim3 block(kJpegThreads);
   hipLaunchKernelGGL(jpeg_tables_kernel, dim3((uint32_t)a.B), block, 0, stream, a);
   if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
-  hipLaunchKernelGGL(jpeg_decode_kernel, grid, block, 0, stream, a);
+  // as many images per wavefront as fill its lanes with rows of MCUs: an image of the largest
+  // side allowed has slot_side / 16 rows of them when its luma is sampled 2x2
+  const int rows = a.slot_side / 16;
+  const uint32_t B = (uint32_t)a.B;
+  if (rows <= 16)
+    hipLaunchKernelGGL(jpeg_decode_kernel<4>, dim3((B + 3) / 4), block, 0, stream, a);
+  else if (rows <= 32)
+    hipLaunchKernelGGL(jpeg_decode_kernel<2>, dim3((B + 1) / 2), block, 0, stream, a);
+  else
+    hipLaunchKernelGGL(jpeg_decode_kernel<1>, dim3(B), block, 0, stream, a);
   if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
   const int bands = (a.slot_side + kColourBand - 1) / kColourBand;
   hipLaunchKernelGGL(jpeg_colour_kernel, dim3((uint32_t)a.B * (uint32_t)bands),

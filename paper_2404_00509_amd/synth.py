@@ -59,6 +59,12 @@ def image_shapes(kind: str, B: int, seed: int):
         landscape = second.integers(0, 2, size=B).astype(bool)
         h = np.where(landscape, other, 256)
         w = np.where(landscape, 256, other)
+    elif kind == "gradient500":
+        # the "maximum side 500" dataset variants (Table 3; the crop-decode benchmark of Sec. 4.1)
+        other = first.integers(313, 501, size=B)
+        landscape = second.integers(0, 2, size=B).astype(bool)
+        h = np.where(landscape, other, 500)
+        w = np.where(landscape, 500, other)
     else:
         raise ValueError(kind)
     return h.astype(np.int32), w.astype(np.int32)

@@ -182,6 +182,19 @@ def test_files_the_decoder_does_not_take_are_flagged_and_the_rest_is_untouched()
         assert torch.isnan(buf.target[b]).all()
 
 
+def test_files_of_maximum_side_500():
+    """The size of the paper's crop-decode benchmark: 24 to 32 rows of MCUs per image, so the four
+    images of a wavefront have more rows than it has lanes."""
+    B, S = 6, 224
+    files, offsets, sizes = synth.make_jpegs("gradient500", B, seed=67)
+    L = (S // 16) ** 2
+    kw = dict(out_size=S, patch=16, num_keep=oracle.num_keep(L, 0.75), seed=20, batch_index=7)
+    ref = oracle.prep_batch(*_decode_all(files, offsets, sizes), **kw)
+    buf, _ = _gpu_jpeg_prep(files, offsets, sizes, max_image_side=512, **kw)
+    assert mae.mae_prep_status(buf.workspace) == 0
+    check_prep_against_oracle(prep_to_numpy(buf), ref, what="side 500")
+
+
 def test_jpeg_input_on_a_side_stream_and_in_a_captured_graph():
     """The JPEG path enqueues kernels only (header, crop draws, tables, decode, colour, resample,
     augmentation): it can run on any stream and be captured; every replay is checked."""
