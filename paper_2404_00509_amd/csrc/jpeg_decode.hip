@@ -279,8 +279,9 @@ __device__ static inline uint32_t file_byte(BitReader& r, int pos) {
 // says whether they may (inside the file and the ring, no 0xFF among them).  Reading them early
 // costs nothing: the position only moves when the buffer is topped up.
 struct NextFour {
-  uint32_t bits;
+  uint32_t bits;   // first byte on top
   bool usable;
+  bool in_reach;   // the four bytes are inside the file and in the ring (they may hold a 0xFF)
 };
 __device__ static inline NextFour next_four(const BitReader& r) {
   const int q = r.pos + r.skew;
@@ -290,8 +291,8 @@ __device__ static inline NextFour next_four(const BitReader& r) {
   NextFour f;
   f.bits = __builtin_bswap32(x);
   // (no short-circuit: straight-line code lets the reads above overlap the table look-up)
-  f.usable = (int)!r.ended & (int)(r.pos + 4 <= r.n) & (int)(q + 4 <= r.have) &
-             (int)(((inv - 0x01010101u) & ~inv & 0x80808080u) == 0u);
+  f.in_reach = (int)!r.ended & (int)(r.pos + 4 <= r.n) & (int)(q + 4 <= r.have);
+  f.usable = (int)f.in_reach & (int)(((inv - 0x01010101u) & ~inv & 0x80808080u) == 0u);
   return f;
 }
 __device__ static inline void fill_bytewise(BitReader& r);
@@ -302,6 +303,28 @@ __device__ static inline void fill(BitReader& r, const NextFour& f) {
     r.nbits += 32;
     r.pos += 4;
     return;
+  }
+  if (f.in_reach) {
+    // a 0xFF among the four: byte by byte out of the register.  0xFF00 is a data byte 0xFF, any
+    // other follower a marker; a 0xFF in the last place waits for its follower.
+    bool skip = false, stop = false;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t b = (f.bits >> (24 - 8 * i)) & 0xFFu;
+      const uint32_t follower = i < 3 ? (f.bits >> (16 - 8 * i)) & 0xFFu : 1u;
+      const bool data = !skip && !stop && (b != 0xFFu || (i < 3 && follower == 0u));
+      const bool marker = !skip && !stop && b == 0xFFu && i < 3 && follower != 0u;
+      stop = stop || (!skip && b == 0xFFu && (i == 3 || follower != 0u));
+      r.ended = r.ended || marker;
+      const bool stuffed = data && b == 0xFFu;
+      if (data) {
+        r.acc = (r.acc << 8) | b;
+        r.nbits += 8;
+        r.pos += stuffed ? 2 : 1;
+      }
+      skip = stuffed;
+    }
+    if (r.nbits > 32) return;
   }
   fill_bytewise(r);
 }
