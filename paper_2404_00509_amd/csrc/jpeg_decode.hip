@@ -213,17 +213,18 @@ struct BitReader {
   bool ended;  // a marker was reached: zero bits from here on
 };
 
-// The 16 bytes at `chunks + at`; bytes beyond the buffer read as zero.
-__device__ static inline u32x4_a8 load_chunk(const BitReader& r, int64_t at) {
-  if ((int64_t)at + 16 <= r.chunks_bytes) return *reinterpret_cast<const u32x4_a8*>(r.chunks + at);
+// The 16 bytes at `base + at` (8-byte aligned) of a buffer of `bytes` bytes; bytes beyond its end
+// read as zero.
+__device__ static inline u32x4_a8 load_chunk(const uint8_t* base, int64_t bytes, int64_t at) {
+  if (at + 16 <= bytes) return *reinterpret_cast<const u32x4_a8*>(base + at);
   uint32_t w[4] = {0u, 0u, 0u, 0u};
   for (int i = 0; i < 16; ++i)
-    if ((int64_t)at + i < r.chunks_bytes) w[i >> 2] |= (uint32_t)r.chunks[at + i] << (8 * (i & 3));
+    if (at + i < bytes) w[i >> 2] |= (uint32_t)base[at + i] << (8 * (i & 3));
   return u32x4_a8{w[0], w[1], w[2], w[3]};
 }
 __device__ static inline void request_bytes(BitReader& r) {
-  r.next[0] = load_chunk(r, r.have);
-  r.next[1] = load_chunk(r, r.have + 16);
+  r.next[0] = load_chunk(r.chunks, r.chunks_bytes, r.have);
+  r.next[1] = load_chunk(r.chunks, r.chunks_bytes, r.have + 16);
   r.pending = true;
 }
 __device__ static inline void accept_bytes(BitReader& r) {
@@ -577,16 +578,13 @@ __device__ static void jpeg_prepare_image(const JpegArgs& a, int b, JpegImage& i
   // file is scanned in aligned 16-byte pieces of the buffer, one per lane and step, the next
   // step's pieces loaded while this step's are examined.
   const int64_t origin = a.offsets[b];
-  BitReader all;  // only its view of the whole buffer is used
-  all.chunks = a.files;
-  all.chunks_bytes = a.files_bytes;
   const int64_t first = (origin + rec.scan_off) & ~(int64_t)15;
   const int64_t last = origin + n - 1;  // a marker starts before this byte
   int seen = 0;                         // markers before the current step
-  u32x4_a8 cur = load_chunk(all, first + lane * 16);
+  u32x4_a8 cur = load_chunk(a.files, a.files_bytes, first + lane * 16);
   for (int64_t base = first; base < last && seen <= my1; base += kJpegThreads * 16) {
     const int64_t at = base + lane * 16;
-    const u32x4_a8 next = load_chunk(all, at + kJpegThreads * 16);
+    const u32x4_a8 next = load_chunk(a.files, a.files_bytes, at + kJpegThreads * 16);
     // the byte after this piece: the first of the next lane's, or of the next step's
     uint32_t follow = (uint32_t)__shfl_down((int)(cur.x & 0xFFu), 1);
     const uint32_t wrap = (uint32_t)__shfl((int)(next.x & 0xFFu), 0);
