@@ -214,6 +214,34 @@ int mae_normpix_loss(const mae_loss_desc* d, float* loss, void* grad, void* work
 size_t mae_loss_workspace_bytes(const mae_loss_desc* d);
 
 /* ------------------------------------------------------------------------------------------------
+ * mae_normpix_loss_from_images
+ *
+ * The same loss and gradient without a stored target: the masked patches' pixels are taken from
+ * the images again (same crop, resize, flip and normalisation, bit for bit what mae_prep_batch
+ * writes to `target`), normalised per patch and compared with the prediction in one kernel.  The
+ * model's forward and backward pass lies between mae_prep_batch and the loss, and the 8-bit images
+ * are several times smaller than the float target, so a caller that passes target = NULL to
+ * mae_prep_batch saves writing L * D floats per image there and reading the masked part of them
+ * here (Sec. 4: the input pipeline is what limits the training step).
+ *
+ * p               the descriptor of the mae_prep_batch call whose crops are meant (same images,
+ *                 same seed, batch_index and sizes; aug_mode MAE_AUG_SIMPLE; even patch size,
+ *                 MAE_ERR_SHAPE otherwise)
+ * prep_workspace  the workspace that call used, untouched since: it holds the crop boxes (and,
+ *                 for JPEG input, the decoded regions)
+ * d               as for mae_normpix_loss; d->target is not read (may be NULL); B, L, D must
+ *                 match p (MAE_ERR_SHAPE otherwise)
+ * Outputs as for mae_normpix_loss.  Samples flagged invalid by mae_prep_batch add nothing to the
+ * loss and get a zero gradient.  workspace: mae_loss_from_images_workspace_bytes(p, d) bytes,
+ * 256-byte aligned.
+ * ---------------------------------------------------------------------------------------------- */
+int mae_normpix_loss_from_images(const mae_prep_desc* p, const void* prep_workspace,
+                                 const mae_loss_desc* d, float* loss, void* grad, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream);
+
+size_t mae_loss_from_images_workspace_bytes(const mae_prep_desc* p, const mae_loss_desc* d);
+
+/* ------------------------------------------------------------------------------------------------
  * mae_patch_embed
  *
  * The first operation of the encoder on what mae_prep_batch hands it (Sec. 2: the encoder works on

@@ -28,8 +28,10 @@ from .binding import (  # noqa: F401
     mae_finetune_stage,
     mae_pretrain_stage,
     mae_stage_of_epoch,
+    mae_loss_from_images_workspace_bytes,
     mae_loss_workspace_bytes,
     mae_normpix_loss,
+    mae_normpix_loss_from_images,
     mae_num_keep,
     mae_patch_embed,
     mae_prep_batch,

@@ -27,7 +27,8 @@ IMAGENET_STD = (0.229, 0.224, 0.225)
 
 # Entry points declared in include/mae_hip.h.
 EXPORTS = ("mae_prep_batch", "mae_prep_workspace_bytes", "mae_prep_status", "mae_num_keep",
-           "mae_normpix_loss", "mae_loss_workspace_bytes", "mae_patch_embed", "mae_pretrain_stage",
+           "mae_normpix_loss", "mae_loss_workspace_bytes", "mae_normpix_loss_from_images",
+           "mae_loss_from_images_workspace_bytes", "mae_patch_embed", "mae_pretrain_stage",
            "mae_finetune_stage", "mae_stage_of_epoch", "mae_error_string", "mae_version")
 
 
@@ -124,6 +125,13 @@ def load():
                                          C.c_void_p, C.c_size_t, C.c_void_p]
         lib.mae_loss_workspace_bytes.restype = C.c_size_t
         lib.mae_loss_workspace_bytes.argtypes = [C.POINTER(MaeLossDesc)]
+        lib.mae_normpix_loss_from_images.restype = C.c_int
+        lib.mae_normpix_loss_from_images.argtypes = [
+            C.POINTER(MaePrepDesc), C.c_void_p, C.POINTER(MaeLossDesc), C.c_void_p, C.c_void_p,
+            C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.mae_loss_from_images_workspace_bytes.restype = C.c_size_t
+        lib.mae_loss_from_images_workspace_bytes.argtypes = [C.POINTER(MaePrepDesc),
+                                                             C.POINTER(MaeLossDesc)]
         lib.mae_patch_embed.restype = C.c_int
         lib.mae_patch_embed.argtypes = [C.POINTER(MaeEmbedDesc), C.c_void_p, C.c_void_p]
         lib.mae_pretrain_stage.restype = C.c_int
@@ -249,9 +257,10 @@ def mae_prep_status(workspace, stream=None) -> int:
 
 def make_loss_desc(pred, target, mask, *, num_masked, eps=1e-6, grad_scale=1.0,
                    norm_pix=True) -> MaeLossDesc:
+    """target may be None for mae_normpix_loss_from_images."""
     d = MaeLossDesc()
     d.B, d.L, d.D = (int(v) for v in pred.shape)
-    d.pred, d.target, d.mask = pred.data_ptr(), target.data_ptr(), mask.data_ptr()
+    d.pred, d.target, d.mask = pred.data_ptr(), _ptr(target), mask.data_ptr()
     d.num_masked = int(num_masked)
     d.eps, d.grad_scale = eps, grad_scale
     d.pred_dtype = MAE_BF16 if pred.dtype == torch.bfloat16 else MAE_F32
@@ -269,6 +278,20 @@ def mae_normpix_loss(desc: MaeLossDesc, loss, grad=None, workspace=None, stream=
                                  _stream(stream))
     if rc != MAE_OK:
         raise MaeError(rc, "mae_normpix_loss")
+
+
+def mae_loss_from_images_workspace_bytes(prep: MaePrepDesc, desc: MaeLossDesc) -> int:
+    return int(load().mae_loss_from_images_workspace_bytes(C.byref(prep), C.byref(desc)))
+
+
+def mae_normpix_loss_from_images(prep: MaePrepDesc, prep_workspace, desc: MaeLossDesc, loss,
+                                 grad=None, workspace=None, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load().mae_normpix_loss_from_images(C.byref(prep), _ptr(prep_workspace), C.byref(desc),
+                                             _ptr(loss), _ptr(grad), _ptr(workspace), ws_bytes,
+                                             _stream(stream))
+    if rc != MAE_OK:
+        raise MaeError(rc, "mae_normpix_loss_from_images")
 
 
 def make_embed_desc(visible, ids_keep, weight, bias=None, pos=None, *,

@@ -68,9 +68,9 @@ int validate_prep(const mae_prep_desc* d, PrepShape* shape) {
   return MAE_OK;
 }
 
-int validate_loss(const mae_loss_desc* d) {
+int validate_loss(const mae_loss_desc* d, bool need_target = true) {
   if (!d) return MAE_ERR_NULL;
-  if (!d->pred || !d->target || !d->mask) return MAE_ERR_NULL;
+  if (!d->pred || (need_target && !d->target) || !d->mask) return MAE_ERR_NULL;
   if (d->B <= 0 || d->L <= 0) return MAE_ERR_SHAPE;
   if (d->D < 2 || d->D > 3072) return MAE_ERR_RANGE;
   if (d->num_masked <= 0) return MAE_ERR_RANGE;
@@ -169,6 +169,44 @@ PrepWorkspace prep_workspace(const mae_prep_desc* d) {
   }
   return w;
 }
+// What the resampling kernel needs to know about the source, for both input formats: with JPEG
+// input its "images" are the decoded regions in the workspace.
+mae::CropArgs make_crop_args(const mae_prep_desc* d, const PrepShape& sh, const PrepWorkspace& wsl,
+                             const uint8_t* ws) {
+  mae::CropArgs ca;
+  memset(&ca, 0, sizeof(ca));
+  ca.B = d->B;
+  ca.S = d->out_size;
+  ca.p = d->patch;
+  ca.G = sh.G;
+  ca.L = sh.L;
+  ca.K = d->num_keep;
+  ca.D = sh.D;
+  ca.visible_bf16 = d->out_dtype == MAE_BF16;
+  const mae::CropPlan plan = mae::crop_plan(
+      d->out_size, d->patch,
+      d->input_format == MAE_INPUT_JPEG ? wsl.slot_side
+                                        : (d->max_image_side > 0 ? d->max_image_side : 256), 0);
+  ca.tile_pixels = plan.tile_pixels;
+  ca.col_parts = plan.col_parts;
+  ca.part_patches = plan.part_patches;
+  for (int c = 0; c < 3; ++c) {
+    ca.nscale[c] = (float)(1.0 / (255.0 * (double)d->std[c]));
+    ca.nbias[c] = (float)(-(double)d->mean[c] / (double)d->std[c]);
+  }
+  ca.images = d->images;
+  ca.images_bytes = d->images_bytes;
+  ca.offsets = d->offsets;
+  ca.widths = d->widths;
+  if (d->input_format == MAE_INPUT_JPEG && ws) {
+    ca.images = ws + wsl.regions_offset;
+    ca.images_bytes = (int64_t)d->B * wsl.slot_side * wsl.slot_side * 3;
+    ca.offsets = reinterpret_cast<const int64_t*>(ws + wsl.region_offsets_offset);
+    ca.widths = reinterpret_cast<const int32_t*>(ws + wsl.region_widths_offset);
+  }
+  ca.workspace = ws;
+  return ca;
+}
 }  // namespace
 
 size_t mae_prep_workspace_bytes(const mae_prep_desc* d) {
@@ -248,39 +286,8 @@ int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t
   if (d->input_format == MAE_INPUT_JPEG && mae::launch_jpeg_decode(ja, stream) != hipSuccess)
     return MAE_ERR_HIP;
 
-  mae::CropArgs ca;
-  memset(&ca, 0, sizeof(ca));
-  ca.B = d->B;
-  ca.S = d->out_size;
-  ca.p = d->patch;
-  ca.G = sh.G;
-  ca.L = sh.L;
-  ca.K = d->num_keep;
-  ca.D = sh.D;
-  ca.visible_bf16 = d->out_dtype == MAE_BF16;
-  const mae::CropPlan plan = mae::crop_plan(
-      d->out_size, d->patch,
-      d->input_format == MAE_INPUT_JPEG ? wsl.slot_side
-                                        : (d->max_image_side > 0 ? d->max_image_side : 256), 0);
-  ca.tile_pixels = plan.tile_pixels;
-  ca.col_parts = plan.col_parts;
-  ca.part_patches = plan.part_patches;
-  for (int c = 0; c < 3; ++c) {
-    ca.nscale[c] = (float)(1.0 / (255.0 * (double)d->std[c]));
-    ca.nbias[c] = (float)(-(double)d->mean[c] / (double)d->std[c]);
-  }
-  ca.images = d->images;
-  ca.images_bytes = d->images_bytes;
-  ca.offsets = d->offsets;
-  ca.widths = d->widths;
-  if (d->input_format == MAE_INPUT_JPEG) {
-    ca.images = ja.regions;
-    ca.images_bytes = pa.images_bytes;
-    ca.offsets = ja.region_offsets;
-    ca.widths = ja.region_widths;
-  }
+  mae::CropArgs ca = make_crop_args(d, sh, wsl, ws);
   ca.ids_restore = ids_restore;
-  ca.workspace = static_cast<const uint8_t*>(workspace);
   ca.visible = visible;
   ca.target = target;
   if (d->aug_mode == MAE_AUG_SIMPLE) {
@@ -387,6 +394,60 @@ int mae_normpix_loss(const mae_loss_desc* d, float* loss, void* grad, void* work
   la.num_partials = sh.waves;
   la.rows_per_iter = sh.rows_per_iter;
   if (mae::launch_normpix_loss(la, stream) != hipSuccess) return MAE_ERR_HIP;
+  return MAE_OK;
+}
+
+namespace {
+int validate_loss_from_images(const mae_prep_desc* p, const mae_loss_desc* d, PrepShape* sh) {
+  int rc = validate_prep(p, sh);
+  if (rc != MAE_OK) return rc;
+  rc = validate_loss(d, false);
+  if (rc != MAE_OK) return rc;
+  if (p->aug_mode != MAE_AUG_SIMPLE) return MAE_ERR_RANGE;  // the pretraining pipeline only
+  if ((sh->D & 3) != 0) return MAE_ERR_SHAPE;               // 16-byte groups: even patch sizes
+  if (d->B != p->B || d->L != sh->L || d->D != sh->D) return MAE_ERR_SHAPE;
+  return MAE_OK;
+}
+}  // namespace
+
+size_t mae_loss_from_images_workspace_bytes(const mae_prep_desc* p, const mae_loss_desc* d) {
+  PrepShape sh;
+  if (validate_loss_from_images(p, d, &sh) != MAE_OK) return 0;
+  const mae::CropArgs ca = make_crop_args(p, sh, prep_workspace(p), nullptr);
+  return (size_t)mae::crop_loss_partials(ca) * sizeof(double);
+}
+
+int mae_normpix_loss_from_images(const mae_prep_desc* p, const void* prep_workspace_ptr,
+                                 const mae_loss_desc* d, float* loss, void* grad, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream) {
+  PrepShape sh;
+  int rc = validate_loss_from_images(p, d, &sh);
+  if (rc != MAE_OK) return rc;
+  if (!loss || !prep_workspace_ptr) return MAE_ERR_NULL;
+  if (!aligned(d->pred, 16) || (grad && !aligned(grad, 16))) return MAE_ERR_RANGE;
+  if (!aligned(prep_workspace_ptr, 256)) return MAE_ERR_WORKSPACE;
+  if (!workspace || !aligned(workspace, 256) ||
+      workspace_bytes < mae_loss_from_images_workspace_bytes(p, d))
+    return MAE_ERR_WORKSPACE;
+  rc = have_device();
+  if (rc != MAE_OK) return rc;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+  mae::CropArgs ca = make_crop_args(p, sh, prep_workspace(p),
+                                    static_cast<const uint8_t*>(prep_workspace_ptr));
+  const double count = (double)d->D * (double)d->num_masked;
+  ca.pred = d->pred;
+  ca.grad = grad;
+  ca.mask = d->mask;
+  ca.partials = static_cast<double*>(workspace);
+  ca.eps = d->eps;
+  ca.gscale = (float)((double)d->grad_scale * 2.0 / count);
+  ca.pred_bf16 = d->pred_dtype == MAE_BF16;
+  ca.norm_pix = d->norm_pix;
+  if (mae::launch_crop_loss(ca, stream) != hipSuccess) return MAE_ERR_HIP;
+  if (mae::launch_loss_finish(ca.partials, (int)mae::crop_loss_partials(ca), 1.0 / count, loss,
+                              stream) != hipSuccess)
+    return MAE_ERR_HIP;
   return MAE_OK;
 }
 

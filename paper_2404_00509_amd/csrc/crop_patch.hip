@@ -167,6 +167,7 @@ __device__ static void produce_patches(const CropArgs& a, const uint32_t* tile, 
   for (int gx = 0; gx < npatch; ++gx) {
     const int l = gy * a.G + gx0 + gx;
     const int rank = __builtin_amdgcn_readlane(my_rank, gx);
+    if (!kU8 && !a.target && rank >= a.K) continue;  // a masked patch, and no target is wanted
     const u32x2 xa = xtab[gx * p + pxA], xb = xtab[gx * p + pxB];
     const float fxA = __uint_as_float(xa.y), fxB = __uint_as_float(xb.y);  // kU8: remainders
     uint32_t A00, A01, A10, A11, B00, B01, B10, B11;
@@ -239,10 +240,196 @@ __device__ static void produce_patches(const CropArgs& a, const uint32_t* tile, 
   }
 }
 
+// ---- the loss without a stored target ---------------------------------------------------------------
+// Same decomposition as produce_patches (a thread owns one 16-byte group position of every patch
+// of the part), but the values stay in registers: per patch the workgroup adds them up for the
+// mean, then the squared deviations for the variance (two block reductions for all patches of a
+// chunk at once), and the masked patches' normalised values meet the prediction: squared error
+// into the workgroup's partial sum, gradient written with the same contiguous 16-byte stores.
+// Visible patches get a zero gradient and are not resampled.  `masked` holds, in lane i, whether
+// patch i of this part is masked.
+constexpr int kLossChunk = 8;  // patches whose values a thread holds at once
+
+__device__ static inline f32x4 crop_load_pred4(const void* pred, int64_t elem, bool bf16) {
+  if (bf16) {
+    const u32x2 raw = *reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(pred) + elem);
+    return f32x4{bf16_lo(raw.x), bf16_hi(raw.x), bf16_lo(raw.y), bf16_hi(raw.y)};
+  }
+  return *reinterpret_cast<const f32x4*>(static_cast<const float*>(pred) + elem);
+}
+__device__ static inline void crop_store_grad4(void* grad, int64_t elem, f32x4 g, bool bf16) {
+  if (bf16)
+    *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(grad) + elem) =
+        u32x2{pack_bf16x2(g.x, g.y), pack_bf16x2(g.z, g.w)};
+  else
+    *reinterpret_cast<f32x4*>(static_cast<float*>(grad) + elem) = g;
+}
+
+// Sums of v[0 .. kLossChunk) over the workgroup, lanes by butterfly and wavefronts in index
+// order; every thread gets all of them.  red: kLossChunk floats per wavefront.
+__device__ static inline void block_sums(float* v, float* red, int lane, int wave, int nwaves) {
+#pragma unroll
+  for (int j = 0; j < kLossChunk; ++j) {
+    float t = v[j];
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) t += __shfl_xor(t, off, kWave);
+    v[j] = t;
+  }
+  __syncthreads();  // the previous round's sums have been read
+  if (lane == 0) {
+#pragma unroll
+    for (int j = 0; j < kLossChunk; ++j) red[wave * kLossChunk + j] = v[j];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < kLossChunk; ++j) {
+    float t = 0.f;
+    for (int w = 0; w < nwaves; ++w) t += red[w * kLossChunk + j];
+    v[j] = t;
+  }
+}
+
+template <bool kLds>
+__device__ static void produce_loss(const CropArgs& a, const uint32_t* tile, const u32x2* xtab,
+                                    const u32x4* ytab, const uint8_t* base, int b, int gy, int gx0,
+                                    int npatch, int cw, int masked, float* red, double* red64,
+                                    uint32_t tile_id) {
+  const int lane = threadIdx.x % kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int nwaves = (int)blockDim.x / kWave;
+  const int p = a.p, D = a.D;
+  const int D4 = D >> 2;
+  const int pp = p * p;
+  const float inv_p = 1.0f / (float)p;
+  const float ns0 = a.nscale[0], ns1 = a.nscale[1], ns2 = a.nscale[2];
+  const float nb0 = a.nbias[0], nb1 = a.nbias[1], nb2 = a.nbias[2];
+  const bool bf16 = a.pred_bf16 != 0;
+
+  // position inside the patch: as in produce_patches
+  const int e4 = wave * kWave + lane;
+  const bool active = e4 < D4;
+  const int e = active ? 4 * e4 : 0;
+  const int qA = e / 3;
+  const int cA = e - 3 * qA;
+  const int qB = min(qA + 1, pp - 1);
+  const int pyA = (int)(((float)qA + 0.5f) * inv_p);
+  const int pxA = qA - pyA * p;
+  const int pyB = (int)(((float)qB + 0.5f) * inv_p);
+  const int pxB = qB - pyB * p;
+  const u32x4 ya = ytab[pyA], yb = ytab[pyB];
+  const uint32_t rowA0 = ya.x, rowA1 = ya.y, rowB0 = yb.x, rowB1 = yb.y;
+  const float fyA = __uint_as_float(ya.z), fyB = __uint_as_float(yb.z);
+  const uint32_t sel = cA == 0 ? 0x04020100u : (cA == 1 ? 0x05040201u : 0x06050402u);
+  const int nA = 3 - cA;
+  float sc[4], bi[4], fy[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    int c = cA + j;
+    c = c >= 3 ? c - 3 : c;
+    c = c >= 3 ? c - 3 : c;
+    sc[j] = c == 0 ? ns0 : (c == 1 ? ns1 : ns2);
+    bi[j] = c == 0 ? nb0 : (c == 1 ? nb1 : nb2);
+    fy[j] = j == 0 ? fyA : (j == 3 ? fyB : (j < nA ? fyA : fyB));
+  }
+  const float inv_d = 1.0f / (float)D, inv_dm1 = 1.0f / (float)(D - 1);
+  const f32x4 zero = f32x4{0.f, 0.f, 0.f, 0.f};
+  double acc = 0.0;
+
+  for (int g0 = 0; g0 < npatch; g0 += kLossChunk) {
+    f32x4 val[kLossChunk], q[kLossChunk];
+    float s[kLossChunk];
+    bool m[kLossChunk];
+    // the predictions first: they are on their way while the pixels are resampled
+#pragma unroll
+    for (int j = 0; j < kLossChunk; ++j) {
+      m[j] = g0 + j < npatch && __builtin_amdgcn_readlane(masked, (g0 + j) & (kWave - 1)) != 0;
+      q[j] = zero;
+      if (m[j] && active)
+        q[j] = crop_load_pred4(a.pred, ((int64_t)b * a.L + gy * a.G + gx0 + g0 + j) * D + e, bf16);
+    }
+#pragma unroll
+    for (int j = 0; j < kLossChunk; ++j) {
+      val[j] = zero;
+      s[j] = 0.f;
+      if (!m[j]) continue;
+      const int gx = g0 + j;
+      const u32x2 xa = xtab[gx * p + pxA], xb = xtab[gx * p + pxB];
+      const float fxA = __uint_as_float(xa.y), fxB = __uint_as_float(xb.y);
+      uint32_t A00, A01, A10, A11, B00, B01, B10, B11;
+      fetch2<kLds>(tile, base, rowA0, (int)xa.x, cw, A00, A01);
+      fetch2<kLds>(tile, base, rowA1, (int)xa.x, cw, A10, A11);
+      fetch2<kLds>(tile, base, rowB0, (int)xb.x, cw, B00, B01);
+      fetch2<kLds>(tile, base, rowB1, (int)xb.x, cw, B10, B11);
+      const uint32_t P00 = __builtin_amdgcn_perm(B00, A00, sel);
+      const uint32_t P01 = __builtin_amdgcn_perm(B01, A01, sel);
+      const uint32_t P10 = __builtin_amdgcn_perm(B10, A10, sel);
+      const uint32_t P11 = __builtin_amdgcn_perm(B11, A11, sel);
+      float out[4];
+#define MAE_BLEND(J)                                                                 \
+{                                                                                  \
+  const float fx = (J) == 0 ? fxA : ((J) == 3 ? fxB : ((J) < nA ? fxA : fxB));     \
+  const float a00 = byte_to_float<J>(P00), a01 = byte_to_float<J>(P01);            \
+  const float a10 = byte_to_float<J>(P10), a11 = byte_to_float<J>(P11);            \
+  const float rt = a00 + fx * (a01 - a00);                                         \
+  const float rb = a10 + fx * (a11 - a10);                                         \
+  const float v = rt + fy[J] * (rb - rt);                                          \
+  out[J] = v * sc[J] + bi[J];                                                      \
+}
+      MAE_BLEND(0) MAE_BLEND(1) MAE_BLEND(2) MAE_BLEND(3)
+#undef MAE_BLEND
+      if (active) {
+        val[j] = f32x4{out[0], out[1], out[2], out[3]};
+        s[j] = (out[0] + out[1]) + (out[2] + out[3]);
+      }
+    }
+    float rstd[kLossChunk];
+#pragma unroll
+    for (int j = 0; j < kLossChunk; ++j) rstd[j] = 1.0f;
+    if (a.norm_pix) {
+      block_sums(s, red, lane, wave, nwaves);
+#pragma unroll
+      for (int j = 0; j < kLossChunk; ++j) {
+        const float mu = s[j] * inv_d;
+        val[j] = val[j] - mu;
+        s[j] = active ? (val[j].x * val[j].x + val[j].y * val[j].y) +
+                            (val[j].z * val[j].z + val[j].w * val[j].w)
+                      : 0.f;
+      }
+      block_sums(s, red, lane, wave, nwaves);
+#pragma unroll
+      for (int j = 0; j < kLossChunk; ++j) rstd[j] = 1.0f / sqrtf(s[j] * inv_dm1 + a.eps);
+    }
+    float sq = 0.f;
+#pragma unroll
+    for (int j = 0; j < kLossChunk; ++j) {
+      if (g0 + j >= npatch || !active) continue;
+      const int64_t elem = ((int64_t)b * a.L + gy * a.G + gx0 + g0 + j) * D + e;
+      f32x4 diff = zero;
+      if (m[j]) {
+        diff = q[j] - val[j] * rstd[j];
+        sq += (diff.x * diff.x + diff.y * diff.y) + (diff.z * diff.z + diff.w * diff.w);
+      }
+      if (a.grad) crop_store_grad4(a.grad, elem, diff * a.gscale, bf16);
+    }
+    acc += (double)sq;
+  }
+  // the workgroup's share of the loss: lanes by butterfly, wavefronts in index order
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off, kWave);
+  __syncthreads();
+  if (lane == 0) red64[wave] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = 0.0;
+    for (int w = 0; w < nwaves; ++w) t += red64[w];
+    a.partials[tile_id] = t;
+  }
+}
+
 // Dynamic LDS: [ tile: a.tile_pixels + 4 words | ytab: p x 16 bytes | xtab: a.part_patches p x 8 ].
-template <bool kBf16, bool kU8>
-__global__ __launch_bounds__(kCropMaxThreads) void crop_patch_kernel(CropArgs a) {
-  extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+// kLoss: instead of writing the patches, the loss and its gradient against a.pred (produce_loss).
+template <bool kBf16, bool kU8, bool kLoss>
+__device__ static inline void crop_band(const CropArgs& a, uint32_t* lds) {
   uint32_t* tile = lds;
   u32x4* ytab = reinterpret_cast<u32x4*>(lds + a.tile_pixels + 4);  // row y0, row y1, weight
   u32x2* xtab = reinterpret_cast<u32x2*>(ytab + a.p);                // x0, weight of x0 + 1
@@ -256,7 +443,18 @@ __global__ __launch_bounds__(kCropMaxThreads) void crop_patch_kernel(CropArgs a)
   const int gx1 = (part + 1) * a.G / a.col_parts;
   const int npatch = gx1 - gx0;
   const CropRec rec = reinterpret_cast<const CropRec*>(a.workspace + kWorkspaceHeader)[b];
-  if (!rec.valid || npatch <= 0) return;
+  if (!rec.valid || npatch <= 0) {
+    if constexpr (kLoss) {  // an unusable sample: nothing towards the loss, zero gradient
+      if (threadIdx.x == 0) a.partials[tile_id] = 0.0;
+      if (a.grad && npatch > 0) {
+        const int64_t first = ((int64_t)b * a.L + gy * a.G + gx0) * a.D;
+        for (int i = threadIdx.x; i < npatch * (a.D >> 2); i += (int)blockDim.x)
+          crop_store_grad4(a.grad, first + 4 * (int64_t)i, f32x4{0.f, 0.f, 0.f, 0.f},
+                           a.pred_bf16 != 0);
+      }
+    }
+    return;
+  }
 
   const int S = a.S, p = a.p;
   const int W = a.widths[b];
@@ -287,8 +485,11 @@ __global__ __launch_bounds__(kCropMaxThreads) void crop_patch_kernel(CropArgs a)
   u32x4* tile4 = reinterpret_cast<u32x4*>(tile);
 
   // noise rank of each patch of this part, one per lane; read back with readlane in the loop
-  const int my_rank =
-      lane < npatch ? a.ids_restore[(int64_t)b * a.L + gy * a.G + gx0 + lane] : 0x7fffffff;
+  int my_rank;
+  if (kLoss)  // whether the patch is masked
+    my_rank = lane < npatch ? (a.mask[(int64_t)b * a.L + gy * a.G + gx0 + lane] != 0 ? 1 : 0) : 0;
+  else
+    my_rank = lane < npatch ? a.ids_restore[(int64_t)b * a.L + gy * a.G + gx0 + lane] : 0x7fffffff;
 
   u32x4 d[kStageRows];
   if (batched) {  // these loads stay in flight while the tap tables are built
@@ -345,13 +546,35 @@ __global__ __launch_bounds__(kCropMaxThreads) void crop_patch_kernel(CropArgs a)
   }
   __syncthreads();
 
-  if (use_lds) {
+  if constexpr (kLoss) {
+    __shared__ float red[(kCropMaxThreads / kWave) * kLossChunk];
+    __shared__ double red64[kCropMaxThreads / kWave];
+    if (use_lds)
+      produce_loss<true>(a, tile, xtab, ytab, base, b, gy, gx0, npatch, rec.cw - xlo, my_rank, red,
+                         red64, tile_id);
+    else
+      produce_loss<false>(a, tile, xtab, ytab, base, b, gy, gx0, npatch, rec.cw - xlo, my_rank,
+                          red, red64, tile_id);
+  } else if (use_lds) {
     produce_patches<true, kBf16, kU8>(a, tile, xtab, ytab, base, b, gy, gx0, npatch,
                                       rec.cw - xlo, my_rank);
   } else {
     produce_patches<false, kBf16, kU8>(a, tile, xtab, ytab, base, b, gy, gx0, npatch,
                                        rec.cw - xlo, my_rank);
   }
+}
+
+template <bool kBf16, bool kU8>
+__global__ __launch_bounds__(kCropMaxThreads) void crop_patch_kernel(CropArgs a) {
+  extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+  crop_band<kBf16, kU8, false>(a, lds);
+}
+
+// The resampling kernel with the loss as its epilogue: what mae_normpix_loss computes, with the
+// masked patches' pixels taken from the images again instead of from a stored target.
+__global__ __launch_bounds__(kCropMaxThreads) void crop_loss_kernel(CropArgs a) {
+  extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+  crop_band<false, false, true>(a, lds);
 }
 
 // Patch sizes whose 3 p^2 values per patch are not a multiple of four (odd p): one value per
@@ -431,6 +654,16 @@ CropPlan crop_plan(int S, int p, int max_side, int force_parts) {
 
 size_t crop_lds_bytes(const CropArgs& a) {
   return (size_t)(a.tile_pixels + 4) * 4 + (size_t)a.p * 16 + (size_t)a.part_patches * a.p * 8;
+}
+
+// Partials: one double per workgroup, crop_loss_partials(a) of them.
+int64_t crop_loss_partials(const CropArgs& a) { return (int64_t)a.B * a.G * a.col_parts; }
+
+hipError_t launch_crop_loss(const CropArgs& a, hipStream_t stream) {
+  dim3 grid((uint32_t)a.B * (uint32_t)a.G * (uint32_t)a.col_parts);
+  dim3 block(kWave * (((a.D >> 2) + kWave - 1) / kWave));
+  hipLaunchKernelGGL(crop_loss_kernel, grid, block, crop_lds_bytes(a), stream, a);
+  return hipGetLastError();
 }
 
 hipError_t launch_crop_patch(const CropArgs& a, hipStream_t stream) {

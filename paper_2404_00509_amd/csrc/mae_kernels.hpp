@@ -46,6 +46,13 @@ struct CropArgs {
   void* visible;
   float* target;    // nullable
   uint8_t* u8_out;  // when set: write only the rounded 8-bit patch rows [B, L, D] here
+  // the loss as the kernel's epilogue (launch_crop_loss): nothing above from `visible` on is used
+  const void* pred;     // [B, L, D]
+  void* grad;           // [B, L, D], nullable
+  const uint8_t* mask;  // [B, L]
+  double* partials;     // one per workgroup
+  float eps, gscale;
+  int32_t pred_bf16, norm_pix;
 };
 struct CropPlan {
   int col_parts, part_patches, tile_pixels;
@@ -53,6 +60,8 @@ struct CropPlan {
 CropPlan crop_plan(int S, int p, int max_side, int force_parts);
 size_t crop_lds_bytes(const CropArgs& a);
 hipError_t launch_crop_patch(const CropArgs& a, hipStream_t stream);
+int64_t crop_loss_partials(const CropArgs& a);
+hipError_t launch_crop_loss(const CropArgs& a, hipStream_t stream);
 
 // ---- finetuning augmentation on the 8-bit resized crop ("3 Aug", "3 Aug+") ------------------------
 struct AugArgs {
@@ -138,6 +147,9 @@ struct LossShape {
 };
 LossShape loss_shape(int64_t rows, int D, bool pred_bf16);
 hipError_t launch_normpix_loss(const LossArgs& a, hipStream_t stream);
+// loss[0] = inv_count * (sum of n partials, added in a fixed order)
+hipError_t launch_loss_finish(const double* partials, int n, double inv_count, float* loss,
+                              hipStream_t stream);
 
 // ---- patch embedding of the visible tokens -----------------------------------------------------
 struct EmbedArgs {

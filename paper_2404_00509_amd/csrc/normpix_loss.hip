@@ -256,6 +256,13 @@ static void launch_any(const LossArgs& a, dim3 grid, dim3 block, hipStream_t str
   }
 }
 
+hipError_t launch_loss_finish(const double* partials, int n, double inv_count, float* loss,
+                              hipStream_t stream) {
+  hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(kLossThreads), 0, stream, partials, n,
+                     inv_count, loss);
+  return hipGetLastError();
+}
+
 hipError_t launch_normpix_loss(const LossArgs& a, hipStream_t stream) {
   dim3 grid(a.num_partials / kLossWaves), block(kLossThreads);
   if (a.pred_bf16) {
