@@ -199,6 +199,70 @@ def time_finetune(args, mae, torch, dev, wl):
     return rows
 
 
+def time_without_target(args, mae, torch, dev, wl, K, M, pred, grad, crop_bytes, want_loss):
+    """The same step without a stored target: mae_prep_batch with target = NULL (visible tokens,
+    mask and ids only) and mae_normpix_loss_from_images, which takes the masked patches' pixels
+    from the images again.  Same outputs except `target`; timed like the step above."""
+    import numpy as np
+
+    bf16 = wl.dtype == "bf16"
+    desc = mae.make_prep_desc(*dev, out_size=wl.out_size, patch=wl.patch, num_keep=K, seed=0,
+                              batch_index=0, out_dtype=mae.MAE_BF16 if bf16 else mae.MAE_F32)
+    buf = mae.alloc_prep_buffers(desc, want_target=False)
+    ldesc = mae.make_loss_desc(pred, None, buf.mask, num_masked=M)
+    lws = torch.empty(max(mae.mae_loss_from_images_workspace_bytes(desc, ldesc), 256),
+                      dtype=torch.uint8, device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step(i, ev=None):
+        desc.batch_index = i
+        if ev is not None:
+            ev[0].record(stream)
+        mae.mae_prep_batch(desc, buf.visible, buf.mask, buf.ids_restore, buf.ids_keep, None,
+                           buf.crop, buf.workspace, stream=stream)
+        if ev is not None:
+            ev[1].record(stream)
+        mae.mae_normpix_loss_from_images(desc, buf.workspace, ldesc, loss, grad, lws,
+                                         stream=stream)
+        if ev is not None:
+            ev[2].record(stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, events[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert mae.mae_prep_status(buf.workspace) == 0
+    got = float(loss.item())
+    assert abs(got - want_loss) <= 1e-5 + 1e-5 * abs(want_loss), (got, want_loss)
+    prep_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    loss_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+    e = 2 if bf16 else 4
+    # what this dataflow must move: the crop's bytes twice, the visible tokens, mask and ids;
+    # the masked rows of the prediction, the whole gradient
+    prep_bytes = crop_bytes + wl.B * (K * wl.D * e + wl.L * 5 + K * 4)
+    loss_bytes = crop_bytes + wl.B * ((wl.L - K) * wl.D * e + wl.L * wl.D * e + wl.L)
+    ms = elapsed * 1e3 / args.steps
+    return {
+        "what": "mae_prep_batch(target = NULL) + mae_normpix_loss_from_images",
+        "ms_per_step": round(ms, 4), "images_per_s": round(wl.B * args.steps / elapsed, 1),
+        "loss_value": got,
+        "kernels": {
+            "mae_prep_batch": {"avg_ms": round(prep_ms, 4), "algorithmic_bytes": prep_bytes,
+                               "achieved_GBps": round(prep_bytes / (prep_ms * 1e-3) / 1e9, 1)},
+            "mae_normpix_loss_from_images": {
+                "avg_ms": round(loss_ms, 4), "algorithmic_bytes": loss_bytes,
+                "achieved_GBps": round(loss_bytes / (loss_ms * 1e-3) / 1e9, 1),
+                "frac": round(loss_bytes / (loss_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
+        },
+    }
+
+
 def time_jpeg(args, mae, synth, torch, wl, K, kind=None, B=None):
     """mae_prep_batch fed with JPEG files ("crop decode", Sec. 4.1): the same batch written as
     baseline JPEG (quality 90, 4:2:0, one restart interval per row of MCUs), timed by itself with
@@ -408,6 +472,10 @@ def main() -> int:
                                        / HBM_PEAK_GBPS, 4),
         "loss_value": final_loss,
     }
+
+    if wl.patch % 2 == 0:
+        out["without_target"] = time_without_target(args, mae, torch, dev, wl, K, M, pred, grad,
+                                                    crop_bytes, final_loss)
 
     if args.embed > 0:
         out["patch_embed"] = time_embed(args, mae, synth, torch, dev, wl, K, args.embed)

@@ -250,19 +250,22 @@ __device__ static void produce_patches(const CropArgs& a, const uint32_t* tile, 
 // patch i of this part is masked.
 constexpr int kLossChunk = 8;  // patches whose values a thread holds at once
 
+// (read once, written once: the non-temporal hint keeps them from displacing the source rows)
 __device__ static inline f32x4 crop_load_pred4(const void* pred, int64_t elem, bool bf16) {
   if (bf16) {
-    const u32x2 raw = *reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(pred) + elem);
+    const u32x2 raw = __builtin_nontemporal_load(
+        reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(pred) + elem));
     return f32x4{bf16_lo(raw.x), bf16_hi(raw.x), bf16_lo(raw.y), bf16_hi(raw.y)};
   }
-  return *reinterpret_cast<const f32x4*>(static_cast<const float*>(pred) + elem);
+  return __builtin_nontemporal_load(
+      reinterpret_cast<const f32x4*>(static_cast<const float*>(pred) + elem));
 }
 __device__ static inline void crop_store_grad4(void* grad, int64_t elem, f32x4 g, bool bf16) {
   if (bf16)
-    *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(grad) + elem) =
-        u32x2{pack_bf16x2(g.x, g.y), pack_bf16x2(g.z, g.w)};
+    __builtin_nontemporal_store(u32x2{pack_bf16x2(g.x, g.y), pack_bf16x2(g.z, g.w)},
+                                reinterpret_cast<u32x2*>(static_cast<uint16_t*>(grad) + elem));
   else
-    *reinterpret_cast<f32x4*>(static_cast<float*>(grad) + elem) = g;
+    __builtin_nontemporal_store(g, reinterpret_cast<f32x4*>(static_cast<float*>(grad) + elem));
 }
 
 // Sums of v[0 .. kLossChunk) over the workgroup, lanes by butterfly and wavefronts in index
@@ -426,10 +429,150 @@ __device__ static void produce_loss(const CropArgs& a, const uint32_t* tile, con
   }
 }
 
+// The same for patches of up to 768 values (NV = groups per lane, D / 4 <= 64 NV): a wavefront
+// holds a whole patch, lane i its groups i, i + 64, ..., so the two reductions are wavefront
+// butterflies and the wavefronts of the workgroup work through the part's patches independently.
+template <bool kLds, int NV>
+__device__ static void produce_loss_wave(const CropArgs& a, const uint32_t* tile,
+                                         const u32x2* xtab, const u32x4* ytab, const uint8_t* base,
+                                         int b, int gy, int gx0, int npatch, int cw, int masked,
+                                         double* red64, uint32_t tile_id) {
+  const int lane = threadIdx.x % kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int nwaves = (int)blockDim.x / kWave;
+  const int p = a.p, D = a.D;
+  const int D4 = D >> 2;
+  const int pp = p * p;
+  const float inv_p = 1.0f / (float)p;
+  const bool bf16 = a.pred_bf16 != 0;
+
+  // what depends on the position inside the patch only, per group of the lane
+  bool active[NV];
+  int e[NV], pxA[NV], pxB[NV], nA[NV];
+  uint32_t rowA0[NV], rowA1[NV], rowB0[NV], rowB1[NV], sel[NV];
+  float sc[NV][4], bi[NV][4], fy[NV][4];
+#pragma unroll
+  for (int v = 0; v < NV; ++v) {
+    const int e4 = lane + v * kWave;
+    active[v] = e4 < D4;
+    e[v] = active[v] ? 4 * e4 : 0;
+    const int qA = e[v] / 3;
+    const int cA = e[v] - 3 * qA;
+    const int qB = min(qA + 1, pp - 1);
+    const int pyA = (int)(((float)qA + 0.5f) * inv_p);
+    pxA[v] = qA - pyA * p;
+    const int pyB = (int)(((float)qB + 0.5f) * inv_p);
+    pxB[v] = qB - pyB * p;
+    const u32x4 ya = ytab[pyA], yb = ytab[pyB];
+    rowA0[v] = ya.x;
+    rowA1[v] = ya.y;
+    rowB0[v] = yb.x;
+    rowB1[v] = yb.y;
+    const float fyA = __uint_as_float(ya.z), fyB = __uint_as_float(yb.z);
+    sel[v] = cA == 0 ? 0x04020100u : (cA == 1 ? 0x05040201u : 0x06050402u);
+    nA[v] = 3 - cA;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int c = cA + j;
+      c = c >= 3 ? c - 3 : c;
+      c = c >= 3 ? c - 3 : c;
+      sc[v][j] = a.nscale[c];
+      bi[v][j] = a.nbias[c];
+      fy[v][j] = j == 0 ? fyA : (j == 3 ? fyB : (j < nA[v] ? fyA : fyB));
+    }
+  }
+  const float inv_d = 1.0f / (float)D, inv_dm1 = 1.0f / (float)(D - 1);
+  const f32x4 zero = f32x4{0.f, 0.f, 0.f, 0.f};
+  double acc = 0.0;
+
+  for (int gx = wave; gx < npatch; gx += nwaves) {
+    const int64_t row_elem = ((int64_t)b * a.L + gy * a.G + gx0 + gx) * D;
+    if (__builtin_amdgcn_readlane(masked, gx & (kWave - 1)) == 0) {  // visible: zero gradient
+      if (a.grad) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v)
+          if (active[v]) crop_store_grad4(a.grad, row_elem + e[v], zero, bf16);
+      }
+      continue;
+    }
+    f32x4 q[NV], val[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v)
+      q[v] = active[v] ? crop_load_pred4(a.pred, row_elem + e[v], bf16) : zero;
+    float s = 0.f;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const u32x2 xa = xtab[gx * p + pxA[v]], xb = xtab[gx * p + pxB[v]];
+      const float fxA = __uint_as_float(xa.y), fxB = __uint_as_float(xb.y);
+      uint32_t A00, A01, A10, A11, B00, B01, B10, B11;
+      fetch2<kLds>(tile, base, rowA0[v], (int)xa.x, cw, A00, A01);
+      fetch2<kLds>(tile, base, rowA1[v], (int)xa.x, cw, A10, A11);
+      fetch2<kLds>(tile, base, rowB0[v], (int)xb.x, cw, B00, B01);
+      fetch2<kLds>(tile, base, rowB1[v], (int)xb.x, cw, B10, B11);
+      const uint32_t P00 = __builtin_amdgcn_perm(B00, A00, sel[v]);
+      const uint32_t P01 = __builtin_amdgcn_perm(B01, A01, sel[v]);
+      const uint32_t P10 = __builtin_amdgcn_perm(B10, A10, sel[v]);
+      const uint32_t P11 = __builtin_amdgcn_perm(B11, A11, sel[v]);
+      float out[4];
+#define MAE_BLEND(J)                                                                 \
+{                                                                                  \
+  const float fx = (J) == 0 ? fxA : ((J) == 3 ? fxB : ((J) < nA[v] ? fxA : fxB));  \
+  const float a00 = byte_to_float<J>(P00), a01 = byte_to_float<J>(P01);            \
+  const float a10 = byte_to_float<J>(P10), a11 = byte_to_float<J>(P11);            \
+  const float rt = a00 + fx * (a01 - a00);                                         \
+  const float rb = a10 + fx * (a11 - a10);                                         \
+  const float t = rt + fy[v][J] * (rb - rt);                                       \
+  out[J] = t * sc[v][J] + bi[v][J];                                                \
+}
+      MAE_BLEND(0) MAE_BLEND(1) MAE_BLEND(2) MAE_BLEND(3)
+#undef MAE_BLEND
+      val[v] = active[v] ? f32x4{out[0], out[1], out[2], out[3]} : zero;
+      s += (val[v].x + val[v].y) + (val[v].z + val[v].w);
+    }
+    float rstd = 1.0f;
+    if (a.norm_pix) {
+#pragma unroll
+      for (int off = kWave / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, kWave);
+      const float mu = s * inv_d;
+      float ss = 0.f;
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        val[v] = val[v] - mu;
+        if (active[v])
+          ss += (val[v].x * val[v].x + val[v].y * val[v].y) +
+                (val[v].z * val[v].z + val[v].w * val[v].w);
+      }
+#pragma unroll
+      for (int off = kWave / 2; off > 0; off >>= 1) ss += __shfl_xor(ss, off, kWave);
+      rstd = 1.0f / sqrtf(ss * inv_dm1 + a.eps);
+    }
+    float sq = 0.f;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      if (!active[v]) continue;
+      const f32x4 diff = q[v] - val[v] * rstd;
+      sq += (diff.x * diff.x + diff.y * diff.y) + (diff.z * diff.z + diff.w * diff.w);
+      if (a.grad) crop_store_grad4(a.grad, row_elem + e[v], diff * a.gscale, bf16);
+    }
+    acc += (double)sq;
+  }
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off, kWave);
+  if (lane == 0) red64[wave] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = 0.0;
+    for (int w = 0; w < nwaves; ++w) t += red64[w];
+    a.partials[tile_id] = t;
+  }
+}
+
 // Dynamic LDS: [ tile: a.tile_pixels + 4 words | ytab: p x 16 bytes | xtab: a.part_patches p x 8 ].
-// kLoss: instead of writing the patches, the loss and its gradient against a.pred (produce_loss).
-template <bool kBf16, bool kU8, bool kLoss>
+// kLossMode 1, 2: instead of writing the patches, the loss and its gradient against a.pred
+// (1: produce_loss, any patch size; 2: produce_loss_wave, patches of up to 768 values).
+template <bool kBf16, bool kU8, int kLossMode>
 __device__ static inline void crop_band(const CropArgs& a, uint32_t* lds) {
+  constexpr bool kLoss = kLossMode != 0;
   uint32_t* tile = lds;
   u32x4* ytab = reinterpret_cast<u32x4*>(lds + a.tile_pixels + 4);  // row y0, row y1, weight
   u32x2* xtab = reinterpret_cast<u32x2*>(ytab + a.p);                // x0, weight of x0 + 1
@@ -549,12 +692,25 @@ __device__ static inline void crop_band(const CropArgs& a, uint32_t* lds) {
   if constexpr (kLoss) {
     __shared__ float red[(kCropMaxThreads / kWave) * kLossChunk];
     __shared__ double red64[kCropMaxThreads / kWave];
-    if (use_lds)
+    if constexpr (kLossMode == 2) {
+      const int nv = ((a.D >> 2) + kWave - 1) / kWave;
+#define MAE_LOSS_WAVE(LDS, NV)                                                                  \
+  produce_loss_wave<LDS, NV>(a, tile, xtab, ytab, base, b, gy, gx0, npatch, rec.cw - xlo, my_rank, \
+                             red64, tile_id)
+      if (nv == 3 && use_lds) MAE_LOSS_WAVE(true, 3);
+      else if (nv == 3) MAE_LOSS_WAVE(false, 3);
+      else if (nv == 2 && use_lds) MAE_LOSS_WAVE(true, 2);
+      else if (nv == 2) MAE_LOSS_WAVE(false, 2);
+      else if (use_lds) MAE_LOSS_WAVE(true, 1);
+      else MAE_LOSS_WAVE(false, 1);
+#undef MAE_LOSS_WAVE
+    } else if (use_lds) {
       produce_loss<true>(a, tile, xtab, ytab, base, b, gy, gx0, npatch, rec.cw - xlo, my_rank, red,
                          red64, tile_id);
-    else
+    } else {
       produce_loss<false>(a, tile, xtab, ytab, base, b, gy, gx0, npatch, rec.cw - xlo, my_rank,
                           red, red64, tile_id);
+    }
   } else if (use_lds) {
     produce_patches<true, kBf16, kU8>(a, tile, xtab, ytab, base, b, gy, gx0, npatch,
                                       rec.cw - xlo, my_rank);
@@ -567,14 +723,19 @@ __device__ static inline void crop_band(const CropArgs& a, uint32_t* lds) {
 template <bool kBf16, bool kU8>
 __global__ __launch_bounds__(kCropMaxThreads) void crop_patch_kernel(CropArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
-  crop_band<kBf16, kU8, false>(a, lds);
+  crop_band<kBf16, kU8, 0>(a, lds);
 }
 
 // The resampling kernel with the loss as its epilogue: what mae_normpix_loss computes, with the
 // masked patches' pixels taken from the images again instead of from a stored target.
 __global__ __launch_bounds__(kCropMaxThreads) void crop_loss_kernel(CropArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
-  crop_band<false, false, true>(a, lds);
+  crop_band<false, false, 1>(a, lds);
+}
+// ... with a wavefront per patch (D <= 768): four wavefronts per workgroup
+__global__ __launch_bounds__(4 * kWave) void crop_loss_wave_kernel(CropArgs a) {
+  extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+  crop_band<false, false, 2>(a, lds);
 }
 
 // Patch sizes whose 3 p^2 values per patch are not a multiple of four (odd p): one value per
@@ -661,8 +822,12 @@ int64_t crop_loss_partials(const CropArgs& a) { return (int64_t)a.B * a.G * a.co
 
 hipError_t launch_crop_loss(const CropArgs& a, hipStream_t stream) {
   dim3 grid((uint32_t)a.B * (uint32_t)a.G * (uint32_t)a.col_parts);
-  dim3 block(kWave * (((a.D >> 2) + kWave - 1) / kWave));
-  hipLaunchKernelGGL(crop_loss_kernel, grid, block, crop_lds_bytes(a), stream, a);
+  const int nv = ((a.D >> 2) + kWave - 1) / kWave;
+  // patches of up to 768 values are a wavefront's work each: four wavefronts share a part
+  if (nv <= 3)
+    hipLaunchKernelGGL(crop_loss_wave_kernel, grid, dim3(4 * kWave), crop_lds_bytes(a), stream, a);
+  else
+    hipLaunchKernelGGL(crop_loss_kernel, grid, dim3(kWave * nv), crop_lds_bytes(a), stream, a);
   return hipGetLastError();
 }
 
