@@ -123,7 +123,8 @@ __device__ static inline u32x4 to_pixels(u32x4 d, uint32_t s) {
 // patch rows (a.u8_out, [B, L, D] bytes, the layout of `target`) for the finetuning augmentation;
 // the tap tables then hold the integer remainders instead of float weights.  All factors stay
 // below 2^24, so the products are 24-bit multiplies.
-template <bool kLds, bool kBf16, bool kU8>
+// kKeptOnly: no target is wanted, so the masked patches are skipped.
+template <bool kLds, bool kBf16, bool kU8, bool kKeptOnly>
 __device__ static void produce_patches(const CropArgs& a, const uint32_t* tile, const u32x2* xtab,
                                        const u32x4* ytab, const uint8_t* base, int b, int gy,
                                        int gx0, int npatch, int cw, int my_rank) {
@@ -167,7 +168,7 @@ __device__ static void produce_patches(const CropArgs& a, const uint32_t* tile, 
   for (int gx = 0; gx < npatch; ++gx) {
     const int l = gy * a.G + gx0 + gx;
     const int rank = __builtin_amdgcn_readlane(my_rank, gx);
-    if (!kU8 && !a.target && rank >= a.K) continue;  // a masked patch, and no target is wanted
+    if (kKeptOnly && rank >= a.K) continue;
     const u32x2 xa = xtab[gx * p + pxA], xb = xtab[gx * p + pxB];
     const float fxA = __uint_as_float(xa.y), fxB = __uint_as_float(xb.y);  // kU8: remainders
     uint32_t A00, A01, A10, A11, B00, B01, B10, B11;
@@ -570,9 +571,11 @@ __device__ static void produce_loss_wave(const CropArgs& a, const uint32_t* tile
 // Dynamic LDS: [ tile: a.tile_pixels + 4 words | ytab: p x 16 bytes | xtab: a.part_patches p x 8 ].
 // kLossMode 1, 2: instead of writing the patches, the loss and its gradient against a.pred
 // (1: produce_loss, any patch size; 2: produce_loss_wave, patches of up to 768 values).
+// kLossMode -1: the visible tokens only (no target).
 template <bool kBf16, bool kU8, int kLossMode>
 __device__ static inline void crop_band(const CropArgs& a, uint32_t* lds) {
-  constexpr bool kLoss = kLossMode != 0;
+  constexpr bool kLoss = kLossMode > 0;
+  constexpr bool kKeptOnly = kLossMode < 0;
   uint32_t* tile = lds;
   u32x4* ytab = reinterpret_cast<u32x4*>(lds + a.tile_pixels + 4);  // row y0, row y1, weight
   u32x2* xtab = reinterpret_cast<u32x2*>(ytab + a.p);                // x0, weight of x0 + 1
@@ -712,11 +715,11 @@ __device__ static inline void crop_band(const CropArgs& a, uint32_t* lds) {
                           red, red64, tile_id);
     }
   } else if (use_lds) {
-    produce_patches<true, kBf16, kU8>(a, tile, xtab, ytab, base, b, gy, gx0, npatch,
-                                      rec.cw - xlo, my_rank);
+    produce_patches<true, kBf16, kU8, kKeptOnly>(a, tile, xtab, ytab, base, b, gy, gx0, npatch,
+                                                 rec.cw - xlo, my_rank);
   } else {
-    produce_patches<false, kBf16, kU8>(a, tile, xtab, ytab, base, b, gy, gx0, npatch,
-                                       rec.cw - xlo, my_rank);
+    produce_patches<false, kBf16, kU8, kKeptOnly>(a, tile, xtab, ytab, base, b, gy, gx0, npatch,
+                                                  rec.cw - xlo, my_rank);
   }
 }
 
@@ -724,6 +727,12 @@ template <bool kBf16, bool kU8>
 __global__ __launch_bounds__(kCropMaxThreads) void crop_patch_kernel(CropArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
   crop_band<kBf16, kU8, 0>(a, lds);
+}
+// ... when no target is wanted: only the patches that are kept
+template <bool kBf16>
+__global__ __launch_bounds__(kCropMaxThreads) void crop_kept_kernel(CropArgs a) {
+  extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+  crop_band<kBf16, false, -1>(a, lds);
 }
 
 // The resampling kernel with the loss as its epilogue: what mae_normpix_loss computes, with the
@@ -838,6 +847,10 @@ hipError_t launch_crop_patch(const CropArgs& a, hipStream_t stream) {
     const size_t lds = crop_lds_bytes(a);
     if (a.u8_out) {
       hipLaunchKernelGGL((crop_patch_kernel<false, true>), grid, block, lds, stream, a);
+    } else if (!a.target && a.visible_bf16) {
+      hipLaunchKernelGGL(crop_kept_kernel<true>, grid, block, lds, stream, a);
+    } else if (!a.target) {
+      hipLaunchKernelGGL(crop_kept_kernel<false>, grid, block, lds, stream, a);
     } else if (a.visible_bf16) {
       hipLaunchKernelGGL((crop_patch_kernel<true, false>), grid, block, lds, stream, a);
     } else {

@@ -227,6 +227,39 @@ def test_loss_rejects_bad_buffers(lib):
     assert lib.mae_normpix_loss(None, FAKE, FAKE, FAKE, need, None) == binding.MAE_ERR_NULL
 
 
+def _call_loss_from_images(lib, p, d, prep_ws=FAKE, loss=FAKE, grad=FAKE, ws=FAKE, ws_bytes=1 << 20):
+    return lib.mae_normpix_loss_from_images(C.byref(p), prep_ws, C.byref(d), loss, grad, ws,
+                                            ws_bytes, None)
+
+
+def test_loss_from_images_validates_both_descriptors(lib):
+    p = _prep_desc(B=2)
+    d = _loss_desc(target=None)                     # the target is not read
+    need = lib.mae_loss_from_images_workspace_bytes(C.byref(p), C.byref(d))
+    assert need == 2 * 14 * 8                       # a double per image and row of patches
+    assert _call_loss_from_images(lib, p, d, ws_bytes=need) == binding.MAE_ERR_NO_DEVICE
+    assert _call_loss_from_images(lib, p, d, ws_bytes=need - 1) == binding.MAE_ERR_WORKSPACE
+    assert _call_loss_from_images(lib, p, d, prep_ws=None) == binding.MAE_ERR_NULL
+    assert _call_loss_from_images(lib, p, d, prep_ws=FAKE + 8) == binding.MAE_ERR_WORKSPACE
+    assert _call_loss_from_images(lib, p, d, loss=None) == binding.MAE_ERR_NULL
+    assert _call_loss_from_images(lib, p, d, grad=FAKE + 4) == binding.MAE_ERR_RANGE
+    assert _call_loss_from_images(lib, p, d, grad=None, ws_bytes=need) == binding.MAE_ERR_NO_DEVICE
+    for bad_p, status in ((_prep_desc(B=3), binding.MAE_ERR_SHAPE),            # other batch
+                          (_prep_desc(B=2, out_size=192, num_keep=36), binding.MAE_ERR_SHAPE),
+                          (_prep_desc(B=2, aug_mode=1), binding.MAE_ERR_RANGE),   # finetuning mode
+                          (_prep_desc(B=2, out_size=0), binding.MAE_ERR_SHAPE)):
+        assert _call_loss_from_images(lib, bad_p, d) == status
+        assert lib.mae_loss_from_images_workspace_bytes(C.byref(bad_p), C.byref(d)) == 0
+    for over, status in ((dict(pred=None), binding.MAE_ERR_NULL), (dict(mask=None), binding.MAE_ERR_NULL),
+                         (dict(D=588), binding.MAE_ERR_SHAPE), (dict(num_masked=0), binding.MAE_ERR_RANGE),
+                         (dict(pred_dtype=5), binding.MAE_ERR_DTYPE)):
+        assert _call_loss_from_images(lib, p, _loss_desc(target=None, **over)) == status
+    # an odd patch size has no 16-byte groups
+    odd = _prep_desc(B=2, out_size=225, patch=15, num_keep=56)
+    assert _call_loss_from_images(lib, odd, _loss_desc(target=None, L=225, D=675)) == \
+        binding.MAE_ERR_SHAPE
+
+
 def _embed_desc(**over):
     d = binding.MaeEmbedDesc()
     d.M, d.D, d.E, d.L = 196, 768, 768, 196
