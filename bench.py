@@ -33,8 +33,8 @@ LOSS_KERNEL_SOURCES = ("paper_2404_00509_amd/csrc/normpix_loss.hip",
                        "paper_2404_00509_amd/csrc/mae_device.hpp")
 MEASURED_TRAFFIC = {
     # workload: (sha256 of the sources above, bytes read + written per launch)
-    "c4": ("b4f6f61afcea57f562a490d6423f934502b2f1575bf58f5f2e631299e8ee005a", 6.172e9),
-    "c5": ("b4f6f61afcea57f562a490d6423f934502b2f1575bf58f5f2e631299e8ee005a", 4.416e9),
+    "c4": ("f3d523a5a507f86208dbb543cf73813f2700e950d9ea3024d7e6f9bcc4926460", 6.172e9),
+    "c5": ("f3d523a5a507f86208dbb543cf73813f2700e950d9ea3024d7e6f9bcc4926460", 4.415e9),
 }
 
 

@@ -444,10 +444,9 @@ int mae_normpix_loss_from_images(const mae_prep_desc* p, const void* prep_worksp
   ca.gscale = (float)((double)d->grad_scale * 2.0 / count);
   ca.pred_bf16 = d->pred_dtype == MAE_BF16;
   ca.norm_pix = d->norm_pix;
+  ca.loss_out = loss;
+  ca.inv_count = 1.0 / count;
   if (mae::launch_crop_loss(ca, stream) != hipSuccess) return MAE_ERR_HIP;
-  if (mae::launch_loss_finish(ca.partials, (int)mae::crop_loss_partials(ca), 1.0 / count, loss,
-                              stream) != hipSuccess)
-    return MAE_ERR_HIP;
   return MAE_OK;
 }
 

@@ -826,8 +826,30 @@ size_t crop_lds_bytes(const CropArgs& a) {
   return (size_t)(a.tile_pixels + 4) * 4 + (size_t)a.p * 16 + (size_t)a.part_patches * a.p * 8;
 }
 
-// Partials: one double per workgroup, crop_loss_partials(a) of them.
-int64_t crop_loss_partials(const CropArgs& a) { return (int64_t)a.B * a.G * a.col_parts; }
+// First stage of adding the workgroups' partial sums (there are tens of thousands): workgroup w
+// adds its contiguous share in a fixed order and leaves one double; the second stage is the
+// single-workgroup kernel that finishes the other loss, too.
+constexpr int kLossGroups = 128;
+__global__ __launch_bounds__(256) void crop_loss_reduce_kernel(const double* partials, int64_t n,
+                                                               double* out) {
+  __shared__ double red[256];
+  const int64_t chunk = (n + kLossGroups - 1) / kLossGroups;
+  const int64_t lo = (int64_t)blockIdx.x * chunk, hi = min(n, lo + chunk);
+  double s = 0.0;
+  for (int64_t i = lo + threadIdx.x; i < hi; i += 256) s += partials[i];
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[blockIdx.x] = red[0];
+}
+
+// Doubles of workspace: one per workgroup, then kLossGroups for the first stage of their sum.
+int64_t crop_loss_partials(const CropArgs& a) {
+  return (int64_t)a.B * a.G * a.col_parts + kLossGroups;
+}
 
 hipError_t launch_crop_loss(const CropArgs& a, hipStream_t stream) {
   dim3 grid((uint32_t)a.B * (uint32_t)a.G * (uint32_t)a.col_parts);
@@ -837,7 +859,12 @@ hipError_t launch_crop_loss(const CropArgs& a, hipStream_t stream) {
     hipLaunchKernelGGL(crop_loss_wave_kernel, grid, dim3(4 * kWave), crop_lds_bytes(a), stream, a);
   else
     hipLaunchKernelGGL(crop_loss_kernel, grid, dim3(kWave * nv), crop_lds_bytes(a), stream, a);
-  return hipGetLastError();
+  if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+  const int64_t n = (int64_t)grid.x;
+  hipLaunchKernelGGL(crop_loss_reduce_kernel, dim3(kLossGroups), dim3(256), 0, stream, a.partials,
+                     n, a.partials + n);
+  if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+  return launch_loss_finish(a.partials + n, kLossGroups, a.inv_count, a.loss_out, stream);
 }
 
 hipError_t launch_crop_patch(const CropArgs& a, hipStream_t stream) {

@@ -50,7 +50,9 @@ struct CropArgs {
   const void* pred;     // [B, L, D]
   void* grad;           // [B, L, D], nullable
   const uint8_t* mask;  // [B, L]
-  double* partials;     // one per workgroup
+  double* partials;     // crop_loss_partials() doubles
+  float* loss_out;      // [1]
+  double inv_count;     // 1 / (D * M)
   float eps, gscale;
   int32_t pred_bf16, norm_pix;
 };
@@ -60,7 +62,8 @@ struct CropPlan {
 CropPlan crop_plan(int S, int p, int max_side, int force_parts);
 size_t crop_lds_bytes(const CropArgs& a);
 hipError_t launch_crop_patch(const CropArgs& a, hipStream_t stream);
-int64_t crop_loss_partials(const CropArgs& a);
+int64_t crop_loss_partials(const CropArgs& a);  // doubles of workspace
+// the loss kernel, then the sum of its partials in a fixed order -> a.loss_out
 hipError_t launch_crop_loss(const CropArgs& a, hipStream_t stream);
 
 // ---- finetuning augmentation on the 8-bit resized crop ("3 Aug", "3 Aug+") ------------------------

@@ -236,7 +236,7 @@ def test_loss_from_images_validates_both_descriptors(lib):
     p = _prep_desc(B=2)
     d = _loss_desc(target=None)                     # the target is not read
     need = lib.mae_loss_from_images_workspace_bytes(C.byref(p), C.byref(d))
-    assert need == 2 * 14 * 8                       # a double per image and row of patches
+    assert need == (2 * 14 + 128) * 8               # a double per image and row of patches, + 128
     assert _call_loss_from_images(lib, p, d, ws_bytes=need) == binding.MAE_ERR_NO_DEVICE
     assert _call_loss_from_images(lib, p, d, ws_bytes=need - 1) == binding.MAE_ERR_WORKSPACE
     assert _call_loss_from_images(lib, p, d, prep_ws=None) == binding.MAE_ERR_NULL
