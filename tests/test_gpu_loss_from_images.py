@@ -191,3 +191,60 @@ def test_agrees_with_the_two_call_path_at_full_size():
         _, ref_grad, _ = oracle.normpix_loss(pred[b:b + 1].cpu().numpy(), ref["target"],
                                              ref["mask"], num_masked=M)
         check_grad(grad[b:b + 1].cpu().numpy(), ref_grad, wl.D, M, what=f"c4[{b}]")
+
+
+def test_on_a_side_stream_and_in_a_captured_graph():
+    """Kernels only (no memset, no copy, no sync): the pair of calls can be captured; every replay
+    is checked against the oracle, with eager work in between."""
+    wl = synth.WORKLOADS["c1"]
+    B = 24
+    data = synth.make_images(wl.kind, B, seed=12)
+    kw = dict(out_size=wl.out_size, patch=wl.patch, num_keep=oracle.num_keep(wl.L, 0.75), seed=13,
+              batch_index=8)
+    ref = oracle.prep_batch(*data, **kw)
+    pred_host = synth.make_pred(6, B, wl.L, wl.D)
+    M = B * (wl.L - kw["num_keep"])
+    ref_loss, ref_grad, _ = oracle.normpix_loss(pred_host, ref["target"], ref["mask"],
+                                                num_masked=M)
+    dimg = to_device(*data)
+    pred = torch.from_numpy(pred_host).cuda()
+    desc = mae.make_prep_desc(*dimg, **kw)
+    buf = mae.alloc_prep_buffers(desc, want_target=False)
+    ldesc = mae.make_loss_desc(pred, None, buf.mask, num_masked=M)
+    ws = torch.empty(max(mae.mae_loss_from_images_workspace_bytes(desc, ldesc), 256),
+                     dtype=torch.uint8, device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    grad = torch.empty_like(pred)
+
+    def step(stream):
+        mae.mae_prep_batch(desc, buf.visible, buf.mask, buf.ids_restore, buf.ids_keep, None,
+                           buf.crop, buf.workspace, stream=stream)
+        mae.mae_normpix_loss_from_images(desc, buf.workspace, ldesc, loss, grad, ws, stream=stream)
+
+    def check(what):
+        torch.cuda.synchronize()
+        assert abs(loss.item() - ref_loss) <= ATOL + RTOL * abs(ref_loss), what
+        check_grad(grad.cpu().numpy(), ref_grad, wl.D, M, what=what)
+
+    def wipe():
+        grad.fill_(float("nan"))
+        loss.fill_(-1.0)
+        buf.mask.fill_(0xEE)
+        torch.cuda.synchronize()
+
+    side = torch.cuda.Stream()
+    wipe()
+    with torch.cuda.stream(side):
+        step(side)
+    side.synchronize()
+    check("side stream")
+    graph = torch.cuda.CUDAGraph()
+    wipe()
+    with torch.cuda.graph(graph):
+        step(torch.cuda.current_stream())
+    for replay in range(3):
+        wipe()
+        graph.replay()
+        check(f"graph replay {replay}")
+        grad.mul_(1.0)
+        torch.cuda.synchronize()
