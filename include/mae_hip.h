@@ -227,8 +227,8 @@ size_t mae_loss_workspace_bytes(const mae_loss_desc* d);
  * p               the descriptor of the mae_prep_batch call whose crops are meant (same images,
  *                 same seed, batch_index and sizes; aug_mode MAE_AUG_SIMPLE; even patch size,
  *                 MAE_ERR_SHAPE otherwise)
- * prep_workspace  the workspace that call used, untouched since: it holds the crop boxes (and,
- *                 for JPEG input, the decoded regions)
+ * prep_workspace  the workspace that call used (and its size), untouched since: it holds the
+ *                 crop boxes (and, for JPEG input, the decoded regions)
  * d               as for mae_normpix_loss; d->target is not read (may be NULL); B, L, D must
  *                 match p (MAE_ERR_SHAPE otherwise)
  * Outputs as for mae_normpix_loss.  Samples flagged invalid by mae_prep_batch add nothing to the
@@ -236,8 +236,9 @@ size_t mae_loss_workspace_bytes(const mae_loss_desc* d);
  * 256-byte aligned.
  * ---------------------------------------------------------------------------------------------- */
 int mae_normpix_loss_from_images(const mae_prep_desc* p, const void* prep_workspace,
-                                 const mae_loss_desc* d, float* loss, void* grad, void* workspace,
-                                 size_t workspace_bytes, void* hip_stream);
+                                 size_t prep_workspace_bytes, const mae_loss_desc* d, float* loss,
+                                 void* grad, void* workspace, size_t workspace_bytes,
+                                 void* hip_stream);
 
 size_t mae_loss_from_images_workspace_bytes(const mae_prep_desc* p, const mae_loss_desc* d);
 

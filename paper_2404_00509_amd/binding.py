@@ -127,8 +127,8 @@ def load():
         lib.mae_loss_workspace_bytes.argtypes = [C.POINTER(MaeLossDesc)]
         lib.mae_normpix_loss_from_images.restype = C.c_int
         lib.mae_normpix_loss_from_images.argtypes = [
-            C.POINTER(MaePrepDesc), C.c_void_p, C.POINTER(MaeLossDesc), C.c_void_p, C.c_void_p,
-            C.c_void_p, C.c_size_t, C.c_void_p]
+            C.POINTER(MaePrepDesc), C.c_void_p, C.c_size_t, C.POINTER(MaeLossDesc), C.c_void_p,
+            C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         lib.mae_loss_from_images_workspace_bytes.restype = C.c_size_t
         lib.mae_loss_from_images_workspace_bytes.argtypes = [C.POINTER(MaePrepDesc),
                                                              C.POINTER(MaeLossDesc)]
@@ -287,9 +287,10 @@ def mae_loss_from_images_workspace_bytes(prep: MaePrepDesc, desc: MaeLossDesc) -
 def mae_normpix_loss_from_images(prep: MaePrepDesc, prep_workspace, desc: MaeLossDesc, loss,
                                  grad=None, workspace=None, stream=None) -> None:
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    rc = load().mae_normpix_loss_from_images(C.byref(prep), _ptr(prep_workspace), C.byref(desc),
-                                             _ptr(loss), _ptr(grad), _ptr(workspace), ws_bytes,
-                                             _stream(stream))
+    prep_bytes = prep_workspace.numel() * prep_workspace.element_size()
+    rc = load().mae_normpix_loss_from_images(C.byref(prep), _ptr(prep_workspace), prep_bytes,
+                                             C.byref(desc), _ptr(loss), _ptr(grad),
+                                             _ptr(workspace), ws_bytes, _stream(stream))
     if rc != MAE_OK:
         raise MaeError(rc, "mae_normpix_loss_from_images")
 

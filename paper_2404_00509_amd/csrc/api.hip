@@ -418,14 +418,16 @@ size_t mae_loss_from_images_workspace_bytes(const mae_prep_desc* p, const mae_lo
 }
 
 int mae_normpix_loss_from_images(const mae_prep_desc* p, const void* prep_workspace_ptr,
-                                 const mae_loss_desc* d, float* loss, void* grad, void* workspace,
-                                 size_t workspace_bytes, void* hip_stream) {
+                                 size_t prep_workspace_bytes, const mae_loss_desc* d, float* loss,
+                                 void* grad, void* workspace, size_t workspace_bytes,
+                                 void* hip_stream) {
   PrepShape sh;
   int rc = validate_loss_from_images(p, d, &sh);
   if (rc != MAE_OK) return rc;
   if (!loss || !prep_workspace_ptr) return MAE_ERR_NULL;
   if (!aligned(d->pred, 16) || (grad && !aligned(grad, 16))) return MAE_ERR_RANGE;
-  if (!aligned(prep_workspace_ptr, 256)) return MAE_ERR_WORKSPACE;
+  if (!aligned(prep_workspace_ptr, 256) || prep_workspace_bytes < mae_prep_workspace_bytes(p))
+    return MAE_ERR_WORKSPACE;
   if (!workspace || !aligned(workspace, 256) ||
       workspace_bytes < mae_loss_from_images_workspace_bytes(p, d))
     return MAE_ERR_WORKSPACE;

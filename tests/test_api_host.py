@@ -227,9 +227,10 @@ def test_loss_rejects_bad_buffers(lib):
     assert lib.mae_normpix_loss(None, FAKE, FAKE, FAKE, need, None) == binding.MAE_ERR_NULL
 
 
-def _call_loss_from_images(lib, p, d, prep_ws=FAKE, loss=FAKE, grad=FAKE, ws=FAKE, ws_bytes=1 << 20):
-    return lib.mae_normpix_loss_from_images(C.byref(p), prep_ws, C.byref(d), loss, grad, ws,
-                                            ws_bytes, None)
+def _call_loss_from_images(lib, p, d, prep_ws=FAKE, loss=FAKE, grad=FAKE, ws=FAKE, ws_bytes=1 << 20,
+                           prep_bytes=1 << 20):
+    return lib.mae_normpix_loss_from_images(C.byref(p), prep_ws, prep_bytes, C.byref(d), loss,
+                                            grad, ws, ws_bytes, None)
 
 
 def test_loss_from_images_validates_both_descriptors(lib):
@@ -241,6 +242,7 @@ def test_loss_from_images_validates_both_descriptors(lib):
     assert _call_loss_from_images(lib, p, d, ws_bytes=need - 1) == binding.MAE_ERR_WORKSPACE
     assert _call_loss_from_images(lib, p, d, prep_ws=None) == binding.MAE_ERR_NULL
     assert _call_loss_from_images(lib, p, d, prep_ws=FAKE + 8) == binding.MAE_ERR_WORKSPACE
+    assert _call_loss_from_images(lib, p, d, prep_bytes=256 + 2 * 32 - 1) == binding.MAE_ERR_WORKSPACE
     assert _call_loss_from_images(lib, p, d, loss=None) == binding.MAE_ERR_NULL
     assert _call_loss_from_images(lib, p, d, grad=FAKE + 4) == binding.MAE_ERR_RANGE
     assert _call_loss_from_images(lib, p, d, grad=None, ws_bytes=need) == binding.MAE_ERR_NO_DEVICE
