@@ -435,6 +435,9 @@ __device__ static void produce_loss(const CropArgs& a, const uint32_t* tile, con
   }
 }
 
+// (The per-group setup and the blend are written out again in each of these functions: behind a
+// shared helper the compiler keeps 40 more registers alive, which costs a wavefront per SIMD.)
+//
 // The same for patches of up to 768 values (NV = groups per lane, D / 4 <= 64 NV): a wavefront
 // holds a whole patch, lane i its groups i, i + 64, ..., so the two reductions are wavefront
 // butterflies and the wavefronts of the workgroup work through the part's patches independently.
