@@ -78,7 +78,8 @@ def test_small_configs(name):
 @pytest.mark.parametrize("S,p,ratio,bf16", [(224, 14, 0.75, True), (224, 14, 0.75, False),
                                             (192, 16, 0.8, True), (64, 32, 0.5, False),
                                             (96, 8, 0.66, False), (256, 16, 0.85, False),
-                                            (48, 4, 0.75, False)])
+                                            (48, 4, 0.75, False), (96, 12, 0.75, False),
+                                            (80, 20, 0.75, True), (96, 24, 0.5, False)])
 def test_patch_sizes_ratios_and_bf16(S, p, ratio, bf16):
     B = 12
     data = synth.make_images("gradient", B, seed=3)
