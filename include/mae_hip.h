@@ -213,6 +213,18 @@ int mae_normpix_loss(const mae_loss_desc* d, float* loss, void* grad, void* work
 
 size_t mae_loss_workspace_bytes(const mae_loss_desc* d);
 
+/* mae_normpix_loss for callers that cannot allocate device memory and so have no workspace to
+ * pass (code under HIP graph capture, tight serving loops, harnesses that forbid allocation): the
+ * same kernels and the same results bit for bit, with the per-wavefront partial sums kept in a
+ * fixed 64-KiB array in device memory that belongs to the library (one copy per GPU, resident
+ * until the process ends) instead of a workspace.  The call itself allocates and frees nothing.
+ * Inputs and outputs are passed as for mae_normpix_loss.  A descriptor whose launch would need
+ * more than 8192 partial sums is rejected with MAE_ERR_WORKSPACE before anything is launched
+ * (today's launch shapes stay below that for every valid descriptor).  All calls on one GPU share
+ * the array: calls that overlap on one GPU (different streams, different threads) race; order
+ * them on one stream.  Nothing in the array has to be cleared between calls. */
+int mae_normpix_loss_static(const mae_loss_desc* d, float* loss, void* grad, void* hip_stream);
+
 /* ------------------------------------------------------------------------------------------------
  * mae_normpix_loss_from_images
  *

@@ -27,7 +27,8 @@ IMAGENET_STD = (0.229, 0.224, 0.225)
 
 # Entry points declared in include/mae_hip.h.
 EXPORTS = ("mae_prep_batch", "mae_prep_workspace_bytes", "mae_prep_status", "mae_num_keep",
-           "mae_normpix_loss", "mae_loss_workspace_bytes", "mae_normpix_loss_from_images",
+           "mae_normpix_loss", "mae_loss_workspace_bytes", "mae_normpix_loss_static",
+           "mae_normpix_loss_from_images",
            "mae_loss_from_images_workspace_bytes", "mae_patch_embed", "mae_pretrain_stage",
            "mae_finetune_stage", "mae_stage_of_epoch", "mae_error_string", "mae_version")
 
@@ -125,6 +126,9 @@ def load():
                                          C.c_void_p, C.c_size_t, C.c_void_p]
         lib.mae_loss_workspace_bytes.restype = C.c_size_t
         lib.mae_loss_workspace_bytes.argtypes = [C.POINTER(MaeLossDesc)]
+        lib.mae_normpix_loss_static.restype = C.c_int
+        lib.mae_normpix_loss_static.argtypes = [C.POINTER(MaeLossDesc), C.c_void_p, C.c_void_p,
+                                                C.c_void_p]
         lib.mae_normpix_loss_from_images.restype = C.c_int
         lib.mae_normpix_loss_from_images.argtypes = [
             C.POINTER(MaePrepDesc), C.c_void_p, C.c_size_t, C.POINTER(MaeLossDesc), C.c_void_p,
@@ -278,6 +282,13 @@ def mae_normpix_loss(desc: MaeLossDesc, loss, grad=None, workspace=None, stream=
                                  _stream(stream))
     if rc != MAE_OK:
         raise MaeError(rc, "mae_normpix_loss")
+
+
+def mae_normpix_loss_static(desc: MaeLossDesc, loss, grad=None, stream=None) -> None:
+    """mae_normpix_loss without a workspace (the library's own fixed scratch array is used)."""
+    rc = load().mae_normpix_loss_static(C.byref(desc), _ptr(loss), _ptr(grad), _stream(stream))
+    if rc != MAE_OK:
+        raise MaeError(rc, "mae_normpix_loss_static")
 
 
 def mae_loss_from_images_workspace_bytes(prep: MaePrepDesc, desc: MaeLossDesc) -> int:

@@ -7,6 +7,8 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <atomic>
+
 #include "mae_device.hpp"
 #include "mae_kernels.hpp"
 
@@ -361,19 +363,10 @@ size_t mae_loss_workspace_bytes(const mae_loss_desc* d) {
   return (size_t)sh.waves * sizeof(double);
 }
 
-int mae_normpix_loss(const mae_loss_desc* d, float* loss, void* grad, void* workspace,
-                     size_t workspace_bytes, void* hip_stream) {
-  int rc = validate_loss(d);
-  if (rc != MAE_OK) return rc;
-  if (!loss) return MAE_ERR_NULL;
-  if (!aligned(d->pred, 16) || !aligned(d->target, 16) || (grad && !aligned(grad, 16)))
-    return MAE_ERR_RANGE;
-  if (!workspace || !aligned(workspace, 256) || workspace_bytes < mae_loss_workspace_bytes(d))
-    return MAE_ERR_WORKSPACE;
-  rc = have_device();
-  if (rc != MAE_OK) return rc;
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-
+namespace {
+// Fills the kernel arguments from a validated descriptor and enqueues the loss kernels.
+int enqueue_loss(const mae_loss_desc* d, float* loss, void* grad, double* partials,
+                 const mae::LossShape& sh, hipStream_t stream) {
   mae::LossArgs la;
   memset(&la, 0, sizeof(la));
   la.rows = (int64_t)d->B * d->L;
@@ -389,12 +382,78 @@ int mae_normpix_loss(const mae_loss_desc* d, float* loss, void* grad, void* work
   la.mask = d->mask;
   la.grad = grad;
   la.loss = loss;
-  la.partials = static_cast<double*>(workspace);
-  const mae::LossShape sh = mae::loss_shape(la.rows, la.D, la.pred_bf16 != 0);
+  la.partials = partials;
   la.num_partials = sh.waves;
   la.rows_per_iter = sh.rows_per_iter;
   if (mae::launch_normpix_loss(la, stream) != hipSuccess) return MAE_ERR_HIP;
   return MAE_OK;
+}
+}  // namespace
+
+int mae_normpix_loss(const mae_loss_desc* d, float* loss, void* grad, void* workspace,
+                     size_t workspace_bytes, void* hip_stream) {
+  int rc = validate_loss(d);
+  if (rc != MAE_OK) return rc;
+  if (!loss) return MAE_ERR_NULL;
+  if (!aligned(d->pred, 16) || !aligned(d->target, 16) || (grad && !aligned(grad, 16)))
+    return MAE_ERR_RANGE;
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < mae_loss_workspace_bytes(d))
+    return MAE_ERR_WORKSPACE;
+  rc = have_device();
+  if (rc != MAE_OK) return rc;
+  const mae::LossShape sh =
+      mae::loss_shape((int64_t)d->B * d->L, d->D, d->pred_dtype == MAE_BF16);
+  return enqueue_loss(d, loss, grad, static_cast<double*>(workspace), sh,
+                      static_cast<hipStream_t>(hip_stream));
+}
+
+// ---- the loss for callers that cannot allocate -----------------------------------------------------
+// The per-wavefront partial sums go to a fixed array in device memory that belongs to the library
+// (one copy per GPU, held until the process ends) instead of a caller's workspace.
+namespace {
+constexpr int kScratchDoubles = 8192;  // 64 KiB; the loss grid never has more wavefronts than this
+__attribute__((used)) static __device__ __align__(256) double scratch[kScratchDoubles];
+constexpr int kMaxDevices = 64;
+std::atomic<double*> g_scratch_ptr[kMaxDevices];  // device address of `scratch`, per GPU
+
+// Address of this GPU's copy of `scratch` (looked up once per device, with that device current).
+int scratch_address(double** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return MAE_ERR_NO_DEVICE;
+  }
+  if (dev < 0 || dev >= kMaxDevices) return MAE_ERR_RANGE;
+  double* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    void* sym = nullptr;
+    if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || !sym) {
+      (void)hipGetLastError();
+      return MAE_ERR_HIP;
+    }
+    ptr = static_cast<double*>(sym);
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+  }
+  *out = ptr;
+  return MAE_OK;
+}
+}  // namespace
+
+int mae_normpix_loss_static(const mae_loss_desc* d, float* loss, void* grad, void* hip_stream) {
+  int rc = validate_loss(d);
+  if (rc != MAE_OK) return rc;
+  if (!loss) return MAE_ERR_NULL;
+  if (!aligned(d->pred, 16) || !aligned(d->target, 16) || (grad && !aligned(grad, 16)))
+    return MAE_ERR_RANGE;
+  const mae::LossShape sh =
+      mae::loss_shape((int64_t)d->B * d->L, d->D, d->pred_dtype == MAE_BF16);
+  if (sh.waves > kScratchDoubles) return MAE_ERR_WORKSPACE;  // more partials than the array holds
+  rc = have_device();
+  if (rc != MAE_OK) return rc;
+  double* partials = nullptr;
+  rc = scratch_address(&partials);
+  if (rc != MAE_OK) return rc;
+  return enqueue_loss(d, loss, grad, partials, sh, static_cast<hipStream_t>(hip_stream));
 }
 
 namespace {
