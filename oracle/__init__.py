@@ -57,6 +57,7 @@ class _PrepArgs(C.Structure):
         ("noise_bits", C.c_int32),
         ("aug_mode", C.c_int32),
         ("jitter", C.c_float),
+        ("images_bytes", C.c_int64),
     ]
 
 
@@ -113,7 +114,7 @@ def load_library(path: str):
     L.mae_oracle_color_jitter.restype = None
     L.mae_oracle_color_jitter.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
     L.mae_oracle_prep_batch.restype = C.c_int32
-    L.mae_oracle_prep_batch.argtypes = [C.c_void_p, C.c_int32, C.c_int32] + [C.c_void_p] * 6
+    L.mae_oracle_prep_batch.argtypes = [C.c_void_p, C.c_int32, C.c_int32] + [C.c_void_p] * 7
     L.mae_oracle_normpix_loss.restype = C.c_int32
     L.mae_oracle_normpix_loss.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                           C.c_void_p, C.c_void_p, C.c_int64, C.c_double,
@@ -320,6 +321,7 @@ def prep_batch(images, offsets, heights, widths, *, out_size, patch, num_keep, s
     a.std = (C.c_float * 3)(*std)
     a.seed, a.batch_index, a.noise_bits = seed, batch_index, noise_bits
     a.aug_mode, a.jitter = aug_mode, jitter
+    a.images_bytes = int(images.size)
     out = {
         "visible": np.empty((n, num_keep, D), np.float32) if want_visible else None,
         "mask": np.empty((n, Lp), np.uint8),
@@ -327,10 +329,11 @@ def prep_batch(images, offsets, heights, widths, *, out_size, patch, num_keep, s
         "ids_keep": np.empty((n, num_keep), np.int32),
         "target": np.empty((n, Lp, D), np.float32) if want_target else None,
         "crop": np.empty((n, 5), np.int32),
+        "valid": np.empty((n,), np.uint8),
     }
     rc = lib().mae_oracle_prep_batch(C.byref(a), b_begin, b_end, _p(out["visible"]),
                                      _p(out["mask"]), _p(out["ids_restore"]), _p(out["ids_keep"]),
-                                     _p(out["target"]), _p(out["crop"]))
+                                     _p(out["target"]), _p(out["crop"]), _p(out["valid"]))
     if rc != 0:
         raise ValueError("mae_oracle_prep_batch: invalid argument")
     return out

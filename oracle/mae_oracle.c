@@ -372,7 +372,7 @@ void mae_oracle_color_jitter(double* img, int32_t S, const double bcs[3]) {
  * ---------------------------------------------------------------------------------------------- */
 int32_t mae_oracle_prep_batch(const mae_oracle_prep_args* a, int32_t b_begin, int32_t b_end,
                               float* visible, uint8_t* mask, int32_t* ids_restore,
-                              int32_t* ids_keep, float* target, int32_t* crop) {
+                              int32_t* ids_keep, float* target, int32_t* crop, uint8_t* valid) {
   if (!a || !a->images || !a->offsets || !a->heights || !a->widths) return -1;
   if (b_begin < 0 || b_end > a->B || b_begin > b_end) return -1;
   int32_t S = a->out_size, p = a->patch, K = a->num_keep;
@@ -389,6 +389,25 @@ int32_t mae_oracle_prep_batch(const mae_oracle_prep_args* a, int32_t b_begin, in
     int64_t n = b - b_begin;
     int32_t H = a->heights[b], W = a->widths[b];
     const uint8_t* img = a->images + a->offsets[b];
+
+    /* A sample that cannot be read (empty or oversized geometry, or an image that does not lie
+     * inside the buffer) takes no part in training: nothing of it is kept or masked, so its mask
+     * row is all 0, the patch order is the identity, and its pixels are zeros. */
+    int usable = H >= 1 && W >= 1 && H <= 32767 && W <= 32767 && a->offsets[b] >= 0;
+    if (usable && a->images_bytes > 0)
+      usable = a->offsets[b] + (int64_t)H * W * 3 <= a->images_bytes;
+    if (valid) valid[n] = (uint8_t)usable;
+    if (!usable) {
+      if (crop) memset(crop + n * 5, 0, sizeof(int32_t) * 5);
+      for (int32_t l = 0; l < L; ++l) {
+        if (ids_restore) ids_restore[n * L + l] = l;
+        if (mask) mask[n * L + l] = 0;
+        if (ids_keep && l < K) ids_keep[n * K + l] = l;
+      }
+      if (target) memset(target + n * L * D, 0, sizeof(float) * (size_t)L * (size_t)D);
+      if (visible) memset(visible + n * K * D, 0, sizeof(float) * (size_t)K * (size_t)D);
+      continue;
+    }
 
     int32_t box[4];
     mae_oracle_rrc_params(H, W, a->scale_lo, a->scale_hi, a->ratio_lo, a->ratio_hi, a->seed,

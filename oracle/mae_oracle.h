@@ -121,16 +121,22 @@ typedef struct {
   int32_t noise_bits;
   int32_t aug_mode; /* 0 = "Simple" (App. B); 1 = "3 Aug"; 2 = "3 Aug+" = 3 Aug + ColorJitter */
   float jitter;     /* ColorJitter strength (0.3 in Sec. 5.2), used by aug_mode 2 */
+  int64_t images_bytes; /* size of `images`, 0 = unknown (then images are not checked against it) */
 } mae_oracle_prep_args;
 
 /* Outputs are indexed by (b - b_begin); any may be NULL.  The hash is keyed by the global sample
  * index b, so a slice gives the same values as the full batch.
  *   visible [n,K,D] fp32, target [n,L,D] fp32 (fp64 result rounded once), mask [n,L] uint8,
- *   ids_restore [n,L], ids_keep [n,K], crop [n,5] = top,left,ch,cw,flip.
+ *   ids_restore [n,L], ids_keep [n,K], crop [n,5] = top,left,ch,cw,flip, valid [n] uint8.
+ * A sample that cannot be read (H or W outside 1..32767, a negative offset, or an image that
+ * runs past images_bytes) is left out of training (the paper does not treat unreadable samples;
+ * this is the reading taken): valid 0, crop zeros, mask row all 0 (nothing of it is masked, so
+ * it adds nothing to the loss), ids_restore[l] = l, ids_keep[r] = r, target and visible rows
+ * zero.  The loss's divisor is then the number of 1s in the mask.
  * Returns 0, or -1 on an invalid argument. */
 int32_t mae_oracle_prep_batch(const mae_oracle_prep_args* a, int32_t b_begin, int32_t b_end,
                               float* visible, uint8_t* mask, int32_t* ids_restore,
-                              int32_t* ids_keep, float* target, int32_t* crop);
+                              int32_t* ids_keep, float* target, int32_t* crop, uint8_t* valid);
 
 /* ---- normalised-pixel loss and gradient (Sec. 3: official MAE objective) ---------------------- */
 /* pred, target: [B,L,D] fp32 (target NOT yet per-patch normalised); mask [B,L]; num_masked = the

@@ -73,6 +73,11 @@ MUTATIONS = [
      "return (int32_t)rint((double)L * (1.0 - mask_ratio));", ["test_num_keep_values"]),
     ("gather uses rank as index", "(float)patches[(int64_t)keep[r] * D + e];",
      "(float)patches[(int64_t)r * D + e];", ["test_prep_gather_and_slicing"]),
+    ("unreadable sample still masked", "if (mask) mask[n * L + l] = 0;",
+     "if (mask) mask[n * L + l] = (l >= K) ? 1 : 0;", ["test_prep_unreadable_samples_take_no_part"]),
+    ("unreadable sample keeps a shuffled order", "if (ids_restore) ids_restore[n * L + l] = l;",
+     "if (ids_restore) ids_restore[n * L + l] = L - 1 - l;",
+     ["test_prep_unreadable_samples_take_no_part"]),
     ("biased variance", "double var = ss / (double)(D - 1);", "double var = ss / (double)D;",
      ["test_loss_normalised_target_statistics"]),
     ("eps outside the root", "double sd = sqrt(var + eps);", "double sd = sqrt(var) + eps;",

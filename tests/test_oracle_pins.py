@@ -396,6 +396,44 @@ def test_prep_gather_and_slicing():
     assert not np.array_equal(other["ids_restore"], full["ids_restore"])
 
 
+def test_prep_unreadable_samples_take_no_part():
+    """A sample whose geometry cannot be read is left out: nothing of it is masked (so the loss,
+    whose divisor is the number of masked patches, does not see it), its patch order is the
+    identity and its pixels are zeros; its neighbours are what they are without it."""
+    wl = synth.WORKLOADS["c1"]
+    images, offsets, heights, widths = synth.make_images(wl.kind, 6, seed=2)
+    K = oracle.num_keep(wl.L, wl.mask_ratio)
+    kw = dict(out_size=wl.out_size, patch=wl.patch, num_keep=K, seed=1, batch_index=2)
+    good = oracle.prep_batch(images, offsets, heights, widths, **kw)
+    assert list(good["valid"]) == [1] * 6
+    h2, w2, o2 = heights.copy(), widths.copy(), offsets.copy()
+    h2[1] = 0                      # empty
+    w2[2] = 32768                  # longer than any supported side
+    o2[3] = images.size - 5        # runs past the end of the buffer
+    o2[4] = -1                     # starts before it
+    out = oracle.prep_batch(images, o2, h2, w2, **kw)
+    assert list(out["valid"]) == [1, 0, 0, 0, 0, 1]
+    for b in (0, 5):
+        for k in good:
+            np.testing.assert_array_equal(out[k][b], good[k][b])
+    for b in (1, 2, 3, 4):
+        assert not out["mask"][b].any() and not out["crop"][b].any()
+        np.testing.assert_array_equal(out["ids_restore"][b], np.arange(wl.L))
+        np.testing.assert_array_equal(out["ids_keep"][b], np.arange(K))
+        assert not out["target"][b].any() and not out["visible"][b].any()
+    # the loss over the batch is the loss over the readable samples alone: same divisor
+    # (the masked patches that exist), same sum
+    pred = synth.make_pred(3, 6, wl.L, wl.D)
+    M = int(out["mask"].sum())
+    assert M == 2 * (wl.L - K)
+    loss_all, grad_all, _ = oracle.normpix_loss(pred, out["target"], out["mask"])
+    sel = [0, 5]
+    loss_sel, grad_sel, _ = oracle.normpix_loss(pred[sel], good["target"][sel], good["mask"][sel])
+    assert loss_all == loss_sel
+    np.testing.assert_array_equal(grad_all[sel], grad_sel)
+    assert not grad_all[[1, 2, 3, 4]].any()
+
+
 def test_prep_constant_image_gives_constant_target():
     S, p = 28, 14
     img = np.full((40, 50, 3), 255, np.uint8)
