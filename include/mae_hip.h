@@ -31,9 +31,13 @@
  *     is launched, so a failed call has no side effect.
  *   - Image geometry (heights, widths, offsets) lives in device memory and cannot be checked on
  *     the host.  The kernels check every sample (1 <= H, W <= 32767, the image lies inside
- *     [0, images_bytes)); a sample that fails is skipped (its outputs are left untouched), is
- *     reported with valid = 0 in crop_out, and is counted in the workspace status word that
- *     mae_prep_status reads back.
+ *     [0, images_bytes); for JPEG input: a file the decoder takes).  A sample that fails takes no
+ *     part in the batch and gets neutral outputs: its mask row is all 0 (nothing of it is masked,
+ *     so it adds nothing to the loss and its gradient rows are zero), ids_restore[l] = l,
+ *     ids_keep[r] = r, its rows of `target` and `visible` are zeros, crop_out is 0,0,0,0,0 with
+ *     valid = 0, and it is counted in the workspace status word that mae_prep_status reads back.
+ *     With such samples in a batch the number of masked patches is no longer B * (L - K): pass
+ *     num_masked = 0 to the loss calls to have it counted from the mask on the device.
  */
 #ifndef MAE_HIP_H
 #define MAE_HIP_H
@@ -196,7 +200,11 @@ typedef struct {
   const float* target;   /* [B, L, D] float, as written by mae_prep_batch                       */
   const uint8_t* mask;   /* [B, L], non-zero = masked                                           */
   int64_t num_masked;    /* M > 0: masked patches of the WHOLE batch (B_global * (L - K)); the
-                            caller knows it in closed form, so shards need no exchange for grad */
+                            caller knows it in closed form, so shards need no exchange for grad.
+                            0: M = the number of non-zero bytes of `mask`, counted on the device
+                            by a small kernel before the loss kernel (for batches that may hold
+                            unusable samples, whose mask rows are 0); if that is 0 too, the loss
+                            and the gradient are 0 */
   float eps;             /* >= 0, 1e-6 in the MAE recipe                                        */
   float grad_scale;      /* upstream derivative of the loss, normally 1                         */
   int32_t pred_dtype;    /* mae_dtype of pred and grad                                          */

@@ -14,7 +14,7 @@
 
 namespace {
 
-constexpr int kVersion = 400;  // 0.4.0
+constexpr int kVersion = 500;  // 0.5.0
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -75,7 +75,7 @@ int validate_loss(const mae_loss_desc* d, bool need_target = true) {
   if (!d->pred || (need_target && !d->target) || !d->mask) return MAE_ERR_NULL;
   if (d->B <= 0 || d->L <= 0) return MAE_ERR_SHAPE;
   if (d->D < 2 || d->D > 3072) return MAE_ERR_RANGE;
-  if (d->num_masked <= 0) return MAE_ERR_RANGE;
+  if (d->num_masked < 0) return MAE_ERR_RANGE;  // 0: counted on the device
   if (!(d->eps >= 0.0f) || !isfinite(d->eps) || !isfinite(d->grad_scale)) return MAE_ERR_RANGE;
   if (d->pred_dtype != MAE_F32 && d->pred_dtype != MAE_BF16) return MAE_ERR_DTYPE;
   if (d->norm_pix != 0 && d->norm_pix != 1) return MAE_ERR_RANGE;
@@ -292,6 +292,10 @@ int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t
   ca.ids_restore = ids_restore;
   ca.visible = visible;
   ca.target = target;
+  ca.mask_out = mask;
+  ca.order_out = ids_restore;
+  ca.keep_out = ids_keep;
+  ca.crop_out = crop_out;
   if (d->aug_mode == MAE_AUG_SIMPLE) {
     if (mae::launch_crop_patch(ca, stream) != hipSuccess) return MAE_ERR_HIP;
     return MAE_OK;
@@ -360,7 +364,8 @@ size_t mae_loss_workspace_bytes(const mae_loss_desc* d) {
   if (validate_loss(d) != MAE_OK) return 0;
   const mae::LossShape sh =
       mae::loss_shape((int64_t)d->B * d->L, d->D, d->pred_dtype == MAE_BF16);
-  return (size_t)sh.waves * sizeof(double);
+  // one partial sum per wavefront, then the partial counts of the mask (num_masked = 0)
+  return (size_t)sh.waves * sizeof(double) + (size_t)mae::kMaxCounts * sizeof(int32_t);
 }
 
 namespace {
@@ -374,7 +379,7 @@ int enqueue_loss(const mae_loss_desc* d, float* loss, void* grad, double* partia
   la.pred_bf16 = d->pred_dtype == MAE_BF16;
   la.norm_pix = d->norm_pix;
   la.eps = d->eps;
-  const double count = (double)d->D * (double)d->num_masked;
+  const double count = (double)d->D * (double)(d->num_masked > 0 ? d->num_masked : 1);
   la.gscale = (float)((double)d->grad_scale * 2.0 / count);
   la.inv_count = 1.0 / count;
   la.pred = d->pred;
@@ -385,6 +390,15 @@ int enqueue_loss(const mae_loss_desc* d, float* loss, void* grad, double* partia
   la.partials = partials;
   la.num_partials = sh.waves;
   la.rows_per_iter = sh.rows_per_iter;
+  if (d->num_masked == 0) {  // the divisor is the number of non-zero mask bytes, counted first
+    int32_t* counts = reinterpret_cast<int32_t*>(partials + sh.waves);
+    la.counts = counts;
+    la.ncounts = mae::mask_count_blocks(la.rows);
+    la.gscale_num = 2.0 * (double)d->grad_scale;
+    la.gscale = 0.0f;
+    la.inv_count = 0.0;
+    if (mae::launch_mask_count(d->mask, la.rows, counts, stream) != hipSuccess) return MAE_ERR_HIP;
+  }
   if (mae::launch_normpix_loss(la, stream) != hipSuccess) return MAE_ERR_HIP;
   return MAE_OK;
 }
@@ -447,7 +461,8 @@ int mae_normpix_loss_static(const mae_loss_desc* d, float* loss, void* grad, voi
     return MAE_ERR_RANGE;
   const mae::LossShape sh =
       mae::loss_shape((int64_t)d->B * d->L, d->D, d->pred_dtype == MAE_BF16);
-  if (sh.waves > kScratchDoubles) return MAE_ERR_WORKSPACE;  // more partials than the array holds
+  // more partials (and the mask's partial counts behind them) than the array holds
+  if (sh.waves + mae::kMaxCounts / 2 > kScratchDoubles) return MAE_ERR_WORKSPACE;
   rc = have_device();
   if (rc != MAE_OK) return rc;
   double* partials = nullptr;
@@ -473,7 +488,8 @@ size_t mae_loss_from_images_workspace_bytes(const mae_prep_desc* p, const mae_lo
   PrepShape sh;
   if (validate_loss_from_images(p, d, &sh) != MAE_OK) return 0;
   const mae::CropArgs ca = make_crop_args(p, sh, prep_workspace(p), nullptr);
-  return (size_t)mae::crop_loss_partials(ca) * sizeof(double);
+  return (size_t)mae::crop_loss_partials(ca) * sizeof(double) +
+         (size_t)mae::kMaxCounts * sizeof(int32_t);
 }
 
 int mae_normpix_loss_from_images(const mae_prep_desc* p, const void* prep_workspace_ptr,
@@ -496,7 +512,7 @@ int mae_normpix_loss_from_images(const mae_prep_desc* p, const void* prep_worksp
 
   mae::CropArgs ca = make_crop_args(p, sh, prep_workspace(p),
                                     static_cast<const uint8_t*>(prep_workspace_ptr));
-  const double count = (double)d->D * (double)d->num_masked;
+  const double count = (double)d->D * (double)(d->num_masked > 0 ? d->num_masked : 1);
   ca.pred = d->pred;
   ca.grad = grad;
   ca.mask = d->mask;
@@ -507,6 +523,16 @@ int mae_normpix_loss_from_images(const mae_prep_desc* p, const void* prep_worksp
   ca.norm_pix = d->norm_pix;
   ca.loss_out = loss;
   ca.inv_count = 1.0 / count;
+  if (d->num_masked == 0) {
+    int32_t* counts = reinterpret_cast<int32_t*>(ca.partials + mae::crop_loss_partials(ca));
+    const int64_t rows = (int64_t)d->B * d->L;
+    ca.counts = counts;
+    ca.ncounts = mae::mask_count_blocks(rows);
+    ca.gscale_num = 2.0 * (double)d->grad_scale;
+    ca.gscale = 0.0f;
+    ca.inv_count = 0.0;
+    if (mae::launch_mask_count(d->mask, rows, counts, stream) != hipSuccess) return MAE_ERR_HIP;
+  }
   if (mae::launch_crop_loss(ca, stream) != hipSuccess) return MAE_ERR_HIP;
   return MAE_OK;
 }

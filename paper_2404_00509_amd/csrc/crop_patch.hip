@@ -274,6 +274,13 @@ __device__ static inline void crop_store_grad4(void* grad, int64_t elem, f32x4 g
     __builtin_nontemporal_store(g, reinterpret_cast<f32x4*>(static_cast<float*>(grad) + elem));
 }
 
+// grad_scale * 2 / (D M): the host's value, or from the device-side count of masked patches
+__device__ static inline float loss_gscale(const CropArgs& a) {
+  if (!a.counts) return a.gscale;
+  const float g = (float)(a.gscale_num * inv_count_of(a.D, sum_counts(a.counts, a.ncounts)));
+  return __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(g)));
+}
+
 // Sums of v[0 .. kLossChunk) over the workgroup, lanes by butterfly and wavefronts in index
 // order; every thread gets all of them.  red: kLossChunk floats per wavefront.
 __device__ static inline void block_sums(float* v, float* red, int lane, int wave, int nwaves) {
@@ -342,6 +349,7 @@ __device__ static void produce_loss(const CropArgs& a, const uint32_t* tile, con
   }
   const float inv_d = 1.0f / (float)D, inv_dm1 = 1.0f / (float)(D - 1);
   const f32x4 zero = f32x4{0.f, 0.f, 0.f, 0.f};
+  const float gscale = loss_gscale(a);
   double acc = 0.0;
 
   for (int g0 = 0; g0 < npatch; g0 += kLossChunk) {
@@ -418,7 +426,7 @@ __device__ static void produce_loss(const CropArgs& a, const uint32_t* tile, con
         diff = q[j] - val[j] * rstd[j];
         sq += (diff.x * diff.x + diff.y * diff.y) + (diff.z * diff.z + diff.w * diff.w);
       }
-      if (a.grad) crop_store_grad4(a.grad, elem, diff * a.gscale, bf16);
+      if (a.grad) crop_store_grad4(a.grad, elem, diff * gscale, bf16);
     }
     acc += (double)sq;
   }
@@ -492,6 +500,7 @@ __device__ static void produce_loss_wave(const CropArgs& a, const uint32_t* tile
   }
   const float inv_d = 1.0f / (float)D, inv_dm1 = 1.0f / (float)(D - 1);
   const f32x4 zero = f32x4{0.f, 0.f, 0.f, 0.f};
+  const float gscale = loss_gscale(a);
   double acc = 0.0;
 
   for (int gx = wave; gx < npatch; gx += nwaves) {
@@ -561,7 +570,7 @@ __device__ static void produce_loss_wave(const CropArgs& a, const uint32_t* tile
       if (!active[v]) continue;
       const f32x4 diff = q[v] - val[v] * rstd;
       sq += (diff.x * diff.x + diff.y * diff.y) + (diff.z * diff.z + diff.w * diff.w);
-      if (a.grad) crop_store_grad4(a.grad, row_elem + e[v], diff * a.gscale, bf16);
+      if (a.grad) crop_store_grad4(a.grad, row_elem + e[v], diff * gscale, bf16);
     }
     acc += (double)sq;
   }
@@ -573,6 +582,36 @@ __device__ static void produce_loss_wave(const CropArgs& a, const uint32_t* tile
     double t = 0.0;
     for (int w = 0; w < nwaves; ++w) t += red64[w];
     a.partials[tile_id] = t;
+  }
+}
+
+// What a sample that cannot be used gets instead of pixels: zeros in its rows of `target` and, with
+// the identity as its patch order, in rows l < K of `visible`; the workgroup of the sample's first
+// part also writes the mask row (nothing masked) and the identity order.
+__device__ static void neutral_outputs(const CropArgs& a, int b, int gy, int gx0, int npatch,
+                                       int part) {
+  const int D4 = a.D >> 2;
+  const f32x4 zero = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int l0 = gy * a.G + gx0;
+  for (int i = threadIdx.x; i < npatch * D4; i += (int)blockDim.x) {
+    const int gx = i / D4, e = 4 * (i - gx * D4);
+    const int l = l0 + gx;
+    if (a.target) *reinterpret_cast<f32x4*>(a.target + ((int64_t)b * a.L + l) * a.D + e) = zero;
+    if (l < a.K && a.visible) {
+      const int64_t vo = ((int64_t)b * a.K + l) * a.D + e;
+      if (a.visible_bf16)
+        *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(a.visible) + vo) = u32x2{0u, 0u};
+      else
+        *reinterpret_cast<f32x4*>(static_cast<float*>(a.visible) + vo) = zero;
+    }
+  }
+  if (gy == 0 && part == 0) {
+    for (int l = threadIdx.x; l < a.L; l += (int)blockDim.x) {
+      if (a.mask_out) a.mask_out[(int64_t)b * a.L + l] = 0;
+      if (a.order_out) a.order_out[(int64_t)b * a.L + l] = l;
+      if (a.keep_out && l < a.K) a.keep_out[(int64_t)b * a.K + l] = l;
+    }
+    if (a.crop_out && threadIdx.x < 6) a.crop_out[(int64_t)b * 6 + threadIdx.x] = 0;
   }
 }
 
@@ -598,6 +637,10 @@ __device__ static inline void crop_band(const CropArgs& a, uint32_t* lds) {
   const int npatch = gx1 - gx0;
   const CropRec rec = reinterpret_cast<const CropRec*>(a.workspace + kWorkspaceHeader)[b];
   if (!rec.valid || npatch <= 0) {
+    if constexpr (!kLoss) {
+      // an unusable sample takes no part: zero pixels, nothing masked, identity order
+      if (!rec.valid && npatch > 0) neutral_outputs(a, b, gy, gx0, npatch, part);
+    }
     if constexpr (kLoss) {  // an unusable sample: nothing towards the loss, zero gradient
       if (threadIdx.x == 0) a.partials[tile_id] = 0.0;
       if (a.grad && npatch > 0) {
@@ -766,8 +809,23 @@ __global__ __launch_bounds__(kCropThreads) void crop_patch_scalar_kernel(CropArg
     const int b = (int)(idx / per_image);
     const int rem = (int)(idx - (int64_t)b * per_image);
     const CropRec rec = reinterpret_cast<const CropRec*>(a.workspace + kWorkspaceHeader)[b];
-    if (!rec.valid) continue;
     const int l = rem / a.D, e = rem - l * a.D;
+    if (!rec.valid) {  // takes no part: zero pixels, nothing masked, identity order
+      if (a.target) a.target[idx] = 0.0f;
+      if (l < a.K) {
+        const int64_t vo = ((int64_t)b * a.K + l) * a.D + e;
+        if (kBf16) static_cast<uint16_t*>(a.visible)[vo] = 0;
+        else static_cast<float*>(a.visible)[vo] = 0.0f;
+      }
+      if (e == 0) {
+        if (a.mask_out) a.mask_out[(int64_t)b * a.L + l] = 0;
+        if (a.order_out) a.order_out[(int64_t)b * a.L + l] = l;
+        if (a.keep_out && l < a.K) a.keep_out[(int64_t)b * a.K + l] = l;
+        if (a.crop_out && l == 0)
+          for (int i = 0; i < 6; ++i) a.crop_out[(int64_t)b * 6 + i] = 0;
+      }
+      continue;
+    }
     const int gy = l / a.G, gx = l - gy * a.G;
     const int q = e / 3, c = e - 3 * q;
     const int py = q / a.p, px = q - py * a.p;
@@ -872,7 +930,8 @@ hipError_t launch_crop_loss(const CropArgs& a, hipStream_t stream) {
   hipLaunchKernelGGL(crop_loss_reduce_kernel, dim3(kLossGroups), dim3(256), 0, stream, a.partials,
                      n, a.partials + n);
   if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
-  return launch_loss_finish(a.partials + n, kLossGroups, a.inv_count, a.loss_out, stream);
+  return launch_loss_finish(a.partials + n, kLossGroups, a.inv_count, a.loss_out, a.counts,
+                            a.ncounts, a.D, stream);
 }
 
 hipError_t launch_crop_patch(const CropArgs& a, hipStream_t stream) {

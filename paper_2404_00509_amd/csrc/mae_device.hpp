@@ -83,6 +83,23 @@ __device__ inline AugParams aug_params(uint64_t key1, uint32_t sample, float jit
   return ap;
 }
 
+// ---- the loss's divisor counted on the device ------------------------------------------------------
+// A first small kernel leaves n <= kMaxCounts partial counts of the mask's non-zero bytes; every
+// wavefront that needs the number of masked patches M adds them up (all lanes get the sum).
+constexpr int kMaxCounts = 256;
+__device__ inline int64_t sum_counts(const int32_t* counts, int n) {
+  const int lane = threadIdx.x % kWave;
+  int64_t s = 0;
+  for (int i = lane; i < n; i += kWave) s += counts[i];
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, kWave);
+  return s;
+}
+// 1 / (D M), and 0 when nothing is masked (the loss is then 0 and no gradient uses the factor)
+__device__ inline double inv_count_of(int D, int64_t M) {
+  return M > 0 ? 1.0 / ((double)D * (double)M) : 0.0;
+}
+
 // ---- workgroup id -> logical tile id, so that consecutive tiles share an XCD (and its L2) ------
 // Hardware hands workgroup i to XCD i % 8.  Tiles are split into 8 contiguous ranges, one per XCD.
 __device__ inline uint32_t xcd_remap(uint32_t wg, uint32_t n) {

@@ -55,6 +55,17 @@ struct CropArgs {
   double inv_count;     // 1 / (D * M)
   float eps, gscale;
   int32_t pred_bf16, norm_pix;
+  // when set, the number of masked patches is the sum of these partial counts (launch_mask_count)
+  // and gscale / inv_count are derived from it on the device: gscale = gscale_num * inv_count
+  const int32_t* counts;
+  int32_t ncounts;
+  double gscale_num;  // 2 * grad_scale
+  // outputs of a sample that cannot be used are set to their neutral values by the resampling
+  // kernel: mask row 0, identity order, zero pixels (all four pointers nullable)
+  uint8_t* mask_out;
+  int32_t* order_out;
+  int32_t* keep_out;
+  int32_t* crop_out;  // [B, 6]: zeros for such a sample
 };
 struct CropPlan {
   int col_parts, part_patches, tile_pixels;
@@ -143,16 +154,25 @@ struct LossArgs {
   double* partials;  // workspace: one per wavefront of the grid
   int32_t num_partials;
   int32_t rows_per_iter;  // adjacent rows a wavefront handles per pass (1 or 2)
+  // when set: M = sum of these partial counts, gscale = gscale_num / (D M), inv_count = 1 / (D M)
+  const int32_t* counts;
+  int32_t ncounts;
+  double gscale_num;  // 2 * grad_scale
 };
+// Partial counts of the non-zero bytes of mask[0 .. rows): returns how many were written (<= 256).
+int mask_count_blocks(int64_t rows);
+hipError_t launch_mask_count(const uint8_t* mask, int64_t rows, int32_t* counts,
+                             hipStream_t stream);
 struct LossShape {
   int waves;          // wavefronts of the grid = number of partials
   int rows_per_iter;
 };
 LossShape loss_shape(int64_t rows, int D, bool pred_bf16);
 hipError_t launch_normpix_loss(const LossArgs& a, hipStream_t stream);
-// loss[0] = inv_count * (sum of n partials, added in a fixed order)
+// loss[0] = inv_count * (sum of n partials, added in a fixed order); with counts given,
+// inv_count = 1 / (D * sum of the counts)
 hipError_t launch_loss_finish(const double* partials, int n, double inv_count, float* loss,
-                              hipStream_t stream);
+                              const int32_t* counts, int ncounts, int D, hipStream_t stream);
 
 // ---- patch embedding of the visible tokens -----------------------------------------------------
 struct EmbedArgs {

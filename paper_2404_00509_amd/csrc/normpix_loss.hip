@@ -67,6 +67,8 @@ __global__ __launch_bounds__(kLossThreads) void normpix_loss_kernel(LossArgs a) 
   const float inv_d = 1.0f / (float)D;
   const float inv_dm1 = 1.0f / (float)(D - 1);
   double acc = 0.0;
+  const float gscale =
+      a.counts ? (float)(a.gscale_num * inv_count_of(D, sum_counts(a.counts, a.ncounts))) : a.gscale;
 
   // kRowsPerIter adjacent rows per pass: all their loads are issued before the first reduction,
   // and each wavefront touches one contiguous span of every tensor.
@@ -131,7 +133,7 @@ __global__ __launch_bounds__(kLossThreads) void normpix_loss_kernel(LossArgs a) 
         const f32x4 diff = kNorm ? q[u][v] - t[u][v] * rstd : q[u][v] - t[u][v];
         if (g < D4) {
           sq += (diff.x * diff.x + diff.y * diff.y) + (diff.z * diff.z + diff.w * diff.w);
-          if (a.grad) store_grad4<kBf16>(a.grad, row_elem + 4 * g, diff * a.gscale);
+          if (a.grad) store_grad4<kBf16>(a.grad, row_elem + 4 * g, diff * gscale);
         }
       }
       acc += (double)sq;
@@ -149,6 +151,8 @@ __global__ __launch_bounds__(kLossThreads) void normpix_loss_scalar_kernel(LossA
   const int waves = gridDim.x * kLossWaves;
   const int D = a.D;
   double acc = 0.0;
+  const float gscale =
+      a.counts ? (float)(a.gscale_num * inv_count_of(D, sum_counts(a.counts, a.ncounts))) : a.gscale;
   for (int64_t row = wave_in_grid; row < a.rows; row += waves) {
     const int64_t row_elem = row * D;
     const float* t = a.target + row_elem;
@@ -179,8 +183,8 @@ __global__ __launch_bounds__(kLossThreads) void normpix_loss_scalar_kernel(LossA
       const float diff = kNorm ? q - (t[e] - mu) * rstd : q - t[e];
       sq += diff * diff;
       if (a.grad) {
-        if (kBf16) static_cast<uint16_t*>(a.grad)[row_elem + e] = (uint16_t)bf16_rne(diff * a.gscale);
-        else static_cast<float*>(a.grad)[row_elem + e] = diff * a.gscale;
+        if (kBf16) static_cast<uint16_t*>(a.grad)[row_elem + e] = (uint16_t)bf16_rne(diff * gscale);
+        else static_cast<float*>(a.grad)[row_elem + e] = diff * gscale;
       }
     }
     acc += (double)sq;
@@ -192,8 +196,11 @@ __global__ __launch_bounds__(kLossThreads) void normpix_loss_scalar_kernel(LossA
 // Adds the per-wavefront partials in a fixed order: thread i takes partials i, i + 256, ...,
 // then a tree over the 256 threads.
 __global__ __launch_bounds__(kLossThreads) void loss_finish_kernel(const double* partials, int n,
-                                                                  double inv_count, float* loss) {
+                                                                  double inv_count, float* loss,
+                                                                  const int32_t* counts,
+                                                                  int ncounts, int D) {
   __shared__ double red[kLossThreads];
+  if (counts) inv_count = inv_count_of(D, sum_counts(counts, ncounts));
   double s = 0.0;
   for (int i = threadIdx.x; i < n; i += kLossThreads) s += partials[i];
   red[threadIdx.x] = s;
@@ -257,9 +264,40 @@ static void launch_any(const LossArgs& a, dim3 grid, dim3 block, hipStream_t str
 }
 
 hipError_t launch_loss_finish(const double* partials, int n, double inv_count, float* loss,
-                              hipStream_t stream) {
+                              const int32_t* counts, int ncounts, int D, hipStream_t stream) {
   hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(kLossThreads), 0, stream, partials, n,
-                     inv_count, loss);
+                     inv_count, loss, counts, ncounts, D);
+  return hipGetLastError();
+}
+
+// Non-zero bytes of the mask, one partial count per workgroup (contiguous shares of 64 Ki rows or
+// more), for callers that leave the divisor to the device.
+constexpr int64_t kCountShare = 65536;
+__global__ __launch_bounds__(kLossThreads) void mask_count_kernel(const uint8_t* mask, int64_t rows,
+                                                                 int32_t* counts) {
+  __shared__ int red[kLossWaves];
+  const int64_t share = (rows + gridDim.x - 1) / gridDim.x;
+  const int64_t lo = (int64_t)blockIdx.x * share, hi = min(rows, lo + share);
+  int c = 0;
+  for (int64_t i = lo + threadIdx.x; i < hi; i += kLossThreads) c += mask[i] != 0 ? 1 : 0;
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) c += __shfl_xor(c, off, kWave);
+  if (threadIdx.x % kWave == 0) red[threadIdx.x / kWave] = c;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int t = 0;
+    for (int w = 0; w < kLossWaves; ++w) t += red[w];
+    counts[blockIdx.x] = t;
+  }
+}
+int mask_count_blocks(int64_t rows) {
+  int64_t n = (rows + kCountShare - 1) / kCountShare;
+  return (int)(n < 1 ? 1 : (n > kMaxCounts ? kMaxCounts : n));
+}
+hipError_t launch_mask_count(const uint8_t* mask, int64_t rows, int32_t* counts,
+                             hipStream_t stream) {
+  hipLaunchKernelGGL(mask_count_kernel, dim3(mask_count_blocks(rows)), dim3(kLossThreads), 0,
+                     stream, mask, rows, counts);
   return hipGetLastError();
 }
 
@@ -275,7 +313,7 @@ hipError_t launch_normpix_loss(const LossArgs& a, hipStream_t stream) {
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   hipLaunchKernelGGL(loss_finish_kernel, dim3(1), block, 0, stream, a.partials, a.num_partials,
-                     a.inv_count, a.loss);
+                     a.inv_count, a.loss, a.counts, a.ncounts, a.D);
   return hipGetLastError();
 }
 

@@ -104,3 +104,16 @@ def check_grad(gpu_grad, ref_grad, D, M, grad_scale=1.0, bf16=False, what=""):
     g = np.asarray(gpu_grad, np.float64) / unit
     r = np.asarray(ref_grad, np.float64) / unit
     assert_close(g, r, atol=ATOL, rtol=BF16_RTOL if bf16 else RTOL, what=what + " grad")
+
+
+def check_neutral_outputs(buf, b):
+    """What a sample that cannot be used must get: nothing masked, identity order, zero pixels,
+    zero crop record with valid = 0."""
+    L, K = buf.mask.shape[1], buf.ids_keep.shape[1]
+    assert not buf.mask[b].any(), f"sample {b}: mask"
+    assert torch.equal(buf.ids_restore[b].cpu(), torch.arange(L, dtype=torch.int32)), b
+    assert torch.equal(buf.ids_keep[b].cpu(), torch.arange(K, dtype=torch.int32)), b
+    assert not buf.visible[b].float().abs().sum().item(), f"sample {b}: visible"
+    if buf.target is not None:
+        assert not buf.target[b].abs().sum().item(), f"sample {b}: target"
+    assert not buf.crop[b].any(), f"sample {b}: crop record"

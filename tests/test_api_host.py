@@ -201,7 +201,7 @@ def _loss_desc(**over):
     (dict(L=0), binding.MAE_ERR_SHAPE),
     (dict(D=1), binding.MAE_ERR_RANGE),
     (dict(D=4000), binding.MAE_ERR_RANGE),
-    (dict(num_masked=0), binding.MAE_ERR_RANGE),
+    (dict(num_masked=-1), binding.MAE_ERR_RANGE),
     (dict(eps=-1.0), binding.MAE_ERR_RANGE),
     (dict(grad_scale=float("inf")), binding.MAE_ERR_RANGE),
     (dict(pred_dtype=2), binding.MAE_ERR_DTYPE),
@@ -237,7 +237,8 @@ def test_loss_from_images_validates_both_descriptors(lib):
     p = _prep_desc(B=2)
     d = _loss_desc(target=None)                     # the target is not read
     need = lib.mae_loss_from_images_workspace_bytes(C.byref(p), C.byref(d))
-    assert need == (2 * 14 + 128) * 8               # a double per image and row of patches, + 128
+    # a double per image and row of patches, + 128, + the mask's 256 partial counts
+    assert need == (2 * 14 + 128) * 8 + 256 * 4
     assert _call_loss_from_images(lib, p, d, ws_bytes=need) == binding.MAE_ERR_NO_DEVICE
     assert _call_loss_from_images(lib, p, d, ws_bytes=need - 1) == binding.MAE_ERR_WORKSPACE
     assert _call_loss_from_images(lib, p, d, prep_ws=None) == binding.MAE_ERR_NULL
@@ -253,7 +254,7 @@ def test_loss_from_images_validates_both_descriptors(lib):
         assert _call_loss_from_images(lib, bad_p, d) == status
         assert lib.mae_loss_from_images_workspace_bytes(C.byref(bad_p), C.byref(d)) == 0
     for over, status in ((dict(pred=None), binding.MAE_ERR_NULL), (dict(mask=None), binding.MAE_ERR_NULL),
-                         (dict(D=588), binding.MAE_ERR_SHAPE), (dict(num_masked=0), binding.MAE_ERR_RANGE),
+                         (dict(D=588), binding.MAE_ERR_SHAPE), (dict(num_masked=-1), binding.MAE_ERR_RANGE),
                          (dict(pred_dtype=5), binding.MAE_ERR_DTYPE)):
         assert _call_loss_from_images(lib, p, _loss_desc(target=None, **over)) == status
     # an odd patch size has no 16-byte groups

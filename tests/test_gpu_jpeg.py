@@ -10,7 +10,7 @@ import oracle
 import paper_2404_00509_amd as mae
 from paper_2404_00509_amd import synth
 
-from helpers import check_prep_against_oracle, prep_to_numpy
+from helpers import check_neutral_outputs, check_prep_against_oracle, prep_to_numpy
 
 pytestmark = pytest.mark.gpu
 
@@ -135,7 +135,7 @@ def test_image_shapes_at_the_limits():
         check_prep_against_oracle(prep_to_numpy(buf, rows=keep), sel, what=f"limits {scale}")
 
 
-def test_files_the_decoder_does_not_take_are_flagged_and_the_rest_is_untouched():
+def test_files_the_decoder_does_not_take_are_flagged_and_take_no_part():
     import io
 
     from PIL import Image
@@ -177,9 +177,9 @@ def test_files_the_decoder_does_not_take_are_flagged_and_the_rest_is_untouched()
     got = prep_to_numpy(buf, rows=keep)
     sel = {k: (v[keep] if v is not None else None) for k, v in ref.items()}
     check_prep_against_oracle(got, sel, what="good files next to bad ones")
-    # flagged samples leave their outputs untouched
-    for b in set(bad):
-        assert torch.isnan(buf.target[b]).all()
+    # flagged samples get the neutral outputs (nothing masked, identity order, zero pixels)
+    for b in flagged:
+        check_neutral_outputs(buf, b)
 
 
 def test_files_of_maximum_side_500():

@@ -151,6 +151,7 @@ def test_jpeg_input_and_samples_flagged_invalid():
     dev[0] = torch.from_numpy(bad).cuda()
     buf, loss, grad, _ = _run((dev[0], dev[1]), kw, pred, file_sizes=dev[2])
     assert mae.mae_prep_status(buf.workspace) == 1
+    assert not buf.mask[3].any()   # the flagged sample takes no part: nothing of it is masked
     without = ref["mask"].copy()
     without[3] = 0           # the sample's patches count as nothing; the divisor stays M
     want, _, _ = oracle.normpix_loss(pred_host, ref["target"], without, num_masked=M,

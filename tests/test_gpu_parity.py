@@ -8,7 +8,8 @@ import oracle
 import paper_2404_00509_amd as mae
 from paper_2404_00509_amd import synth
 
-from helpers import (ATOL, BF16_RTOL, RTOL, assert_close, check_grad, check_prep_against_oracle,
+from helpers import (ATOL, BF16_RTOL, RTOL, assert_close, check_grad, check_neutral_outputs,
+                     check_prep_against_oracle,
                      gpu_loss, gpu_prep, prep_to_numpy, to_device)
 
 pytestmark = pytest.mark.gpu
@@ -267,7 +268,11 @@ def test_prep_is_reproducible_and_keyed_by_batch_and_sample_base():
         assert torch.equal(getattr(s, k), getattr(a, k)[20:]), k
 
 
-def test_prep_rejects_bad_geometry_on_the_device_without_touching_it():
+@pytest.mark.parametrize("patch,bf16,aug", [(16, False, 0), (16, True, 0), (5, False, 0),
+                                            (5, True, 0), (8, False, 1), (8, False, 2)])
+def test_prep_gives_unreadable_samples_neutral_outputs(patch, bf16, aug):
+    """Geometry is checked on the device; a sample that fails takes no part in the batch (every
+    output defined, as the oracle defines it) and its neighbours are unaffected."""
     imgs = _random_images([(30, 30)] * 6, seed=3)
     images, offsets, heights, widths = _pack(imgs)
     heights = heights.copy()
@@ -277,18 +282,70 @@ def test_prep_rejects_bad_geometry_on_the_device_without_touching_it():
     widths[2] = 40000                    # wider than supported
     offsets[3] = images.size - 10        # runs past the end of the buffer
     offsets[4] = -3                      # negative offset
-    kw = dict(out_size=32, patch=16, num_keep=1, seed=1)
-    buf, _, _ = gpu_prep(images, offsets, heights, widths, **kw)
+    S = 40 if patch != 16 else 32
+    L = (S // patch) ** 2
+    kw = dict(out_size=S, patch=patch, num_keep=max(1, L // 4), seed=1, aug_mode=aug)
+    buf, _, _ = gpu_prep(images, offsets, heights, widths, bf16=bf16, **kw)
     assert mae.mae_prep_status(buf.workspace) == 4
     got = prep_to_numpy(buf)
     assert list(got["crop"][:, 5]) == [1, 0, 0, 0, 0, 1]
-    # good samples match the oracle, rejected ones keep the caller's bytes
-    for b in (0, 5):
-        ref = oracle.prep_batch(images, offsets, heights, widths, b_begin=b, b_end=b + 1, **kw)
-        check_prep_against_oracle({k: v[b:b + 1] for k, v in got.items()}, ref, what=f"good{b}")
+    ref = oracle.prep_batch(images, offsets, heights, widths, **kw)
+    assert list(ref["valid"]) == [1, 0, 0, 0, 0, 1]
+    got["crop"][:, 5] = 1   # the flags were compared above
+    check_prep_against_oracle(got, ref, bf16=bf16, what="unreadable samples")
     for b in (1, 2, 3, 4):
-        assert np.all(np.isnan(got["target"][b])) and np.all(np.isnan(got["visible"][b]))
-        assert np.all(got["ids_restore"][b] == -7) and np.all(got["mask"][b] == 0xEE)
+        check_neutral_outputs(buf, b)
+
+
+def test_loss_divisor_counted_on_the_device_leaves_unreadable_samples_out():
+    """num_masked = 0: the divisor is the number of masked patches that exist.  A batch with two
+    unreadable samples gives the loss and the gradient of the readable ones alone, through both
+    forms of the loss call and the one without a workspace."""
+    wl = synth.WORKLOADS["c1"]
+    B = 10
+    images, offsets, heights, widths = synth.make_images(wl.kind, B, seed=4)
+    heights = heights.copy()
+    offsets = offsets.copy()
+    heights[2] = -5
+    offsets[7] = images.size
+    K = oracle.num_keep(wl.L, wl.mask_ratio)
+    kw = dict(out_size=wl.out_size, patch=wl.patch, num_keep=K, seed=3, batch_index=1)
+    ref = oracle.prep_batch(images, offsets, heights, widths, **kw)
+    pred_host = synth.make_pred(6, B, wl.L, wl.D)
+    M = int(ref["mask"].sum())
+    assert M == (B - 2) * (wl.L - K)
+    ref_loss, ref_grad, _ = oracle.normpix_loss(pred_host, ref["target"], ref["mask"])
+    buf, desc, _ = gpu_prep(images, offsets, heights, widths, **kw)
+    pred = torch.from_numpy(pred_host).cuda()
+    results = {}
+    ldesc = mae.make_loss_desc(pred, buf.target, buf.mask, num_masked=0)
+    ws = torch.empty(mae.mae_loss_workspace_bytes(ldesc), dtype=torch.uint8, device="cuda")
+    for name in ("workspace", "static", "from_images"):
+        loss = torch.full((1,), float("nan"), device="cuda")
+        grad = torch.full_like(pred, float("nan"))
+        if name == "workspace":
+            mae.mae_normpix_loss(ldesc, loss, grad, ws)
+        elif name == "static":
+            mae.mae_normpix_loss_static(ldesc, loss, grad)
+        else:
+            fdesc = mae.make_loss_desc(pred, None, buf.mask, num_masked=0)
+            fws = torch.empty(mae.mae_loss_from_images_workspace_bytes(desc, fdesc),
+                              dtype=torch.uint8, device="cuda")
+            mae.mae_normpix_loss_from_images(desc, buf.workspace, fdesc, loss, grad, fws)
+        torch.cuda.synchronize()
+        results[name] = (loss.item(), grad.cpu().numpy())
+    for name, (loss, grad) in results.items():
+        assert abs(loss - ref_loss) <= ATOL + RTOL * abs(ref_loss), name
+        check_grad(grad, ref_grad, wl.D, M, what=name)
+        assert not grad[[2, 7]].any(), name
+    # nothing masked at all: loss 0, gradient 0, no NaN
+    none = torch.zeros_like(buf.mask)
+    ldesc = mae.make_loss_desc(pred, buf.target, none, num_masked=0)
+    loss = torch.full((1,), float("nan"), device="cuda")
+    grad = torch.full_like(pred, float("nan"))
+    mae.mae_normpix_loss(ldesc, loss, grad, ws)
+    torch.cuda.synchronize()
+    assert loss.item() == 0.0 and not grad.any()
 
 
 # ------------------------------------------------------------------------------------------------

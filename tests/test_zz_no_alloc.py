@@ -65,7 +65,7 @@ def test_static_scratch_loss_only_and_argument_errors():
     with pytest.raises(mae.MaeError) as e:
         mae.mae_normpix_loss_static(desc, None, None)
     assert e.value.status == mae.binding.MAE_ERR_NULL
-    desc.num_masked = 0
+    desc.num_masked = -1
     with pytest.raises(mae.MaeError) as e:
         mae.mae_normpix_loss_static(desc, b, None)
     assert e.value.status == mae.binding.MAE_ERR_RANGE
