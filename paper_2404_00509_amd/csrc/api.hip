@@ -134,36 +134,53 @@ namespace {
 // (jitter) one double per (image, row of patches, column part of the blur kernel); every part
 // starts on a 256-byte boundary.
 struct PrepWorkspace {
-  size_t u8_offset, partials_offset, total;
+  size_t u8_offset, partials_offset, crop_partials_offset, total;
   // crop decode: per-file records, heights, widths, region widths, region offsets, tables, planes, regions
   size_t recs_offset, heights_offset, widths_offset, region_widths_offset, region_offsets_offset,
       prepared_offset, planes_offset, regions_offset;
   int slot_side;
 };
+// Launch plan of the resampling kernel: from the side limit of the decoded-region slots for JPEG
+// input, else from the caller's hint.
+mae::CropPlan crop_plan_of(const mae_prep_desc* d, int slot_side) {
+  return mae::crop_plan(d->out_size, d->patch,
+                        d->input_format == MAE_INPUT_JPEG
+                            ? slot_side
+                            : (d->max_image_side > 0 ? d->max_image_side : 256),
+                        0);
+}
 PrepWorkspace prep_workspace(const mae_prep_desc* d) {
   auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
   PrepWorkspace w;
   w.u8_offset = up(mae::kWorkspaceHeader + (size_t)d->B * sizeof(mae::CropRec));
   w.partials_offset = w.u8_offset;
+  w.crop_partials_offset = w.u8_offset;
   w.total = mae::kWorkspaceHeader + (size_t)d->B * sizeof(mae::CropRec);
   w.recs_offset = w.heights_offset = w.widths_offset = w.region_widths_offset = 0;
   w.region_offsets_offset = w.prepared_offset = w.planes_offset = w.regions_offset = 0;
   w.slot_side = 0;
+  if (d->input_format == MAE_INPUT_JPEG)
+    w.slot_side = ((d->max_image_side > 0 ? d->max_image_side : 256) + 15) & ~15;
   if (d->aug_mode != MAE_AUG_SIMPLE) {
     w.partials_offset = up(w.u8_offset + (size_t)d->B * d->out_size * d->out_size * 3);
     w.total = w.partials_offset;
-    if (d->aug_mode == MAE_AUG_THREE_PLUS)
-      w.total += (size_t)d->B * (d->out_size / d->patch) *
-                 mae::three_aug_plan(d->out_size, d->patch).parts * sizeof(double);
+    if (d->aug_mode == MAE_AUG_THREE_PLUS) {
+      // luma sums per (image, row of patches, column part): of the blur kernel, then of the
+      // resampling kernel
+      const size_t rows = (size_t)d->B * (d->out_size / d->patch);
+      w.crop_partials_offset =
+          w.total + rows * mae::three_aug_plan(d->out_size, d->patch).parts * sizeof(double);
+      w.total = w.crop_partials_offset +
+                rows * (size_t)crop_plan_of(d, w.slot_side).col_parts * sizeof(double);
+    }
   }
   if (d->input_format == MAE_INPUT_JPEG) {
     const size_t B = (size_t)d->B;
-    w.slot_side = ((d->max_image_side > 0 ? d->max_image_side : 256) + 15) & ~15;
     w.recs_offset = up(w.total);
     w.heights_offset = up(w.recs_offset + B * sizeof(mae::JpegRec));
     w.widths_offset = up(w.heights_offset + B * 4);
     w.region_widths_offset = up(w.widths_offset + B * 4);
-    w.region_offsets_offset = up(w.region_widths_offset + B * 4);
+    w.region_offsets_offset = up(w.region_widths_offset + B * 8);
     w.prepared_offset = up(w.region_offsets_offset + B * 8);
     w.planes_offset = up(w.prepared_offset + B * mae::jpeg_prepared_bytes());
     w.regions_offset = up(w.planes_offset + B * (size_t)w.slot_side * w.slot_side * 3);
@@ -185,10 +202,7 @@ mae::CropArgs make_crop_args(const mae_prep_desc* d, const PrepShape& sh, const 
   ca.K = d->num_keep;
   ca.D = sh.D;
   ca.visible_bf16 = d->out_dtype == MAE_BF16;
-  const mae::CropPlan plan = mae::crop_plan(
-      d->out_size, d->patch,
-      d->input_format == MAE_INPUT_JPEG ? wsl.slot_side
-                                        : (d->max_image_side > 0 ? d->max_image_side : 256), 0);
+  const mae::CropPlan plan = crop_plan_of(d, wsl.slot_side);
   ca.tile_pixels = plan.tile_pixels;
   ca.col_parts = plan.col_parts;
   ca.part_patches = plan.part_patches;
@@ -301,10 +315,16 @@ int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t
     return MAE_OK;
   }
 
-  // finetuning augmentation: the resampling kernel leaves the rounded 8-bit crop in the
-  // workspace, a second kernel applies the per-image operation and writes the patch rows
+  // finetuning augmentation: grayscale and solarisation are the resampling kernel's epilogue; the
+  // images that drew the blur get their rounded 8-bit crop written to the workspace, and the
+  // blur kernel writes their patch rows.  "3 Aug+" needs every image's mean luma after the
+  // brightness step first: one pass that only adds it up, then the pass that writes.
   ca.u8_out = ws + wsl.u8_offset;
-  if (mae::launch_crop_patch(ca, stream) != hipSuccess) return MAE_ERR_HIP;
+  ca.aug_mode = d->aug_mode;
+  ca.jitter = d->jitter;
+  ca.sample_base = d->sample_base;
+  ca.key1 = pa.key1;
+  ca.luma_partials = reinterpret_cast<double*>(ws + wsl.crop_partials_offset);
   mae::AugArgs aa;
   memset(&aa, 0, sizeof(aa));
   aa.B = ca.B;
@@ -332,8 +352,13 @@ int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t
   aa.partials = reinterpret_cast<double*>(ws + wsl.partials_offset);
   aa.visible = visible;
   aa.target = target;
-  if (mae::launch_three_aug(aa, stream) != hipSuccess) return MAE_ERR_HIP;
-  return MAE_OK;
+  hipError_t err = mae::launch_crop_aug(ca, 0, stream);
+  if (err == hipSuccess && d->aug_mode == MAE_AUG_THREE_PLUS) {
+    err = mae::launch_aug_blur(aa, true, stream);
+    if (err == hipSuccess) err = mae::launch_crop_aug(ca, 1, stream);
+  }
+  if (err == hipSuccess) err = mae::launch_aug_blur(aa, false, stream);
+  return err == hipSuccess ? MAE_OK : MAE_ERR_HIP;
 }
 
 int mae_prep_status(const void* workspace, void* hip_stream, int32_t* host_invalid_samples) {

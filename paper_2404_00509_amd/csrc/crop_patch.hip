@@ -24,6 +24,7 @@
 //    (produce_loss_wave, produce_loss): the masked patches' values stay in registers, are
 //    normalised per patch and compared with the prediction, so that no float target is ever
 //    stored or read back.
+#include "aug_device.hpp"
 #include "mae_device.hpp"
 #include "mae_kernels.hpp"
 
@@ -585,6 +586,216 @@ __device__ static void produce_loss_wave(const CropArgs& a, const uint32_t* tile
   }
 }
 
+// ---- the finetuning augmentation as the epilogue ("3 Aug", "3 Aug+": Sec. 3, Sec. 4.4, Table 7) ----
+// The per-image operation acts on the resized crop rounded to bytes.  Grayscale and solarisation
+// are pointwise, so they are applied to the rounded values while these are still in registers and
+// the result goes straight to `target` / `visible`; the images that drew the blur only get their
+// rounded bytes written (patch order) for the blur kernel.
+//
+// Grayscale and the jitter's saturation step need whole pixels, so here a lane takes four
+// neighbouring pixels of a patch row (12 values) instead of four values, and the groups of the
+// part's patches are dealt to the lanes in order.  The 64 x 12 values of a wavefront go through a
+// wavefront-private strip of LDS so that every store instruction still writes 1 KiB of
+// contiguous memory.  Tables: xtab.y = horizontal remainder as a float, ytab.z / ytab.w = the
+// weights of the upper and the lower row over (2 S)^2.
+//
+// Rounding.  The bilinear value is num / den^2 with den = 2 S,
+//   top = (den - rx) a00 + rx a01, bot likewise, num = (den - ry) top + ry bot,
+// and it is rounded to the nearest integer, ties upwards, exactly.  top and bot stay below 2^24
+// and are exact in single precision; the quotient is then estimated in single precision with an
+// error below 6.9e-5 (the weight (den - ry) / den^2 and its product with top: 255 * 2^-23; the
+// weight ry / den^2: 255 * 2^-24; the multiply-add: 255 * 2^-24; adding one half before the
+// floor: 2^-17).  Only when the estimate lies within 2^-13 of a rounding boundary for some lane
+// of the wavefront is the integer computation run.
+constexpr float kNearTie = 1.0f / 8192.0f;
+constexpr int kStripFloats = kWave * 12;  // per wavefront
+
+// floor(n / d) for 0 <= n < 2^22 and small d, from the float reciprocal (inv = 1 / d)
+__device__ static inline int small_div(int n, float inv) { return (int)(((float)n + 0.5f) * inv); }
+
+// floor((2 num + den^2) / (2 den^2)) in integers (all products below 2^31; den <= 1024)
+__device__ static inline float round_exact(uint32_t w00, uint32_t w01, uint32_t w10, uint32_t w11,
+                                           int shift, int den, int rx, int ry) {
+  const int a00 = (int)((w00 >> shift) & 0xFFu), a01 = (int)((w01 >> shift) & 0xFFu);
+  const int a10 = (int)((w10 >> shift) & 0xFFu), a11 = (int)((w11 >> shift) & 0xFFu);
+  const int top = __mul24(den, a00) + __mul24(rx, a01 - a00);
+  const int bot = __mul24(den, a10) + __mul24(rx, a11 - a10);
+  const int num = den * top + ry * (bot - top);
+  const int dd2 = 2 * den * den;
+  const int x = 2 * num + den * den;
+  int q = (int)((float)x * (1.0f / (float)dd2));
+  const int r = x - q * dd2;
+  q += r < 0 ? -1 : (r >= dd2 ? 1 : 0);
+  return (float)q;
+}
+
+// kPass 0: "3 Aug", or the first pass of "3 Aug+" (kJitter: luma sums only); kPass 1: the second
+// pass of "3 Aug+".  `blur`: this image goes to the blur kernel (bytes only; not called in pass 1).
+template <bool kLds, bool kBf16, bool kJitter, int kPass>
+__device__ static void produce_aug(const CropArgs& a, const uint32_t* tile, const u32x2* xtab,
+                                   const u32x4* ytab, const uint8_t* base, int b, int gy, int gx0,
+                                   int npatch, int cw, int my_rank, const AugParams& ap, bool blur,
+                                   float mean, float* strips, double* red64, uint32_t tile_id) {
+  constexpr bool kReduce = kJitter && kPass == 0;
+  const int lane = threadIdx.x % kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int p = a.p, D = a.D;
+  const int den = 2 * a.S;
+  const float den_f = (float)den;
+  const int gpp = (p * p) >> 2;  // groups of four pixels per patch
+  const float inv_gpp = 1.0f / (float)gpp, inv_p = 1.0f / (float)p;
+  const int ngroups = npatch * gpp;
+  const int l0 = gy * a.G + gx0;
+  const bool gray = ap.op == kOpGray;
+  float* strip = strips + wave * kStripFloats;
+  float lsum = 0.0f;
+  // this image's rows of the outputs (uniform over the workgroup)
+  float* target_image = a.target ? a.target + (int64_t)b * a.L * D : nullptr;
+  uint8_t* u8_image = a.u8_out + (int64_t)b * a.L * D;
+  void* visible_image =
+      kBf16 ? static_cast<void*>(static_cast<uint16_t*>(a.visible) + (int64_t)b * a.K * D)
+            : static_cast<void*>(static_cast<float*>(a.visible) + (int64_t)b * a.K * D);
+
+  // whole wavefronts stay in the loop: the stores are a wavefront's joint work
+  for (int i0 = wave * kWave; i0 < ngroups; i0 += (int)blockDim.x) {
+    const bool have = i0 + lane < ngroups;
+    const int i = have ? i0 + lane : ngroups - 1;
+    const int gx = small_div(i, inv_gpp);
+    const int q = 4 * (i - __mul24(gx, gpp));  // first pixel of the group inside the patch
+    const int py = small_div(q, inv_p), px = q - __mul24(py, p);
+    const int xt0 = __mul24(gx, p) + px;
+    const u32x4 yt = ytab[py];
+    const float wy0 = __uint_as_float(yt.z), wy1 = __uint_as_float(yt.w);
+    uint32_t w00[4], w01[4], w10[4], w11[4];
+    float rx[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const u32x2 xt = xtab[xt0 + j];
+      rx[j] = __uint_as_float(xt.y);
+      fetch2<kLds>(tile, base, yt.x, (int)xt.x, cw, w00[j], w01[j]);
+      fetch2<kLds>(tile, base, yt.y, (int)xt.x, cw, w10[j], w11[j]);
+    }
+
+    float v[12], dmax = 0.0f;
+#define MAE_ROUND_FAST(J, C)                                                                   \
+{                                                                                              \
+  const float top = fmaf(rx[J], byte_to_float<C>(w01[J]), cx * byte_to_float<C>(w00[J]));      \
+  const float bot = fmaf(rx[J], byte_to_float<C>(w11[J]), cx * byte_to_float<C>(w10[J]));      \
+  const float est = fmaf(wy1, bot, wy0 * top);                                                 \
+  v[3 * J + C] = floorf(est + 0.5f);                                                           \
+  dmax = fmaxf(dmax, fabsf(est - v[3 * J + C]));                                               \
+}
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float cx = den_f - rx[j];
+      MAE_ROUND_FAST(j, 0) MAE_ROUND_FAST(j, 1) MAE_ROUND_FAST(j, 2)
+    }
+#undef MAE_ROUND_FAST
+    if (__builtin_amdgcn_ballot_w64(dmax > 0.5f - kNearTie) != 0) {
+      // some lane is too close to a rounding boundary to call: integers
+      const int iry = (int)rintf(wy1 * den_f * den_f);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int irx = (int)rx[j];
+#pragma unroll
+        for (int c = 0; c < 3; ++c)
+          v[3 * j + c] = round_exact(w00[j], w01[j], w10[j], w11[j], 8 * c, den, irx, iry);
+      }
+    }
+
+    if (blur) {  // the blur kernel's input: the twelve rounded values as bytes
+      if (have) {
+        uint32_t w[3];
+#pragma unroll
+        for (int k = 0; k < 3; ++k)
+          w[k] = (uint32_t)v[4 * k] | ((uint32_t)v[4 * k + 1] << 8) |
+                 ((uint32_t)v[4 * k + 2] << 16) | ((uint32_t)v[4 * k + 3] << 24);
+        // offsets inside one image stay below 2^22: 24-bit multiplies, one 64-bit base
+        uint32_t* dst = reinterpret_cast<uint32_t*>(
+            u8_image + (uint32_t)(__mul24(l0 + gx, D) + 3 * q));
+        dst[0] = w[0];
+        dst[1] = w[1];
+        dst[2] = w[2];
+      }
+      continue;
+    }
+
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      if (gray) {
+        // (299 R + 587 G + 114 B) / 1000 rounded to nearest: n + 1/2 is at least 0.0005 away from
+        // a multiple of 1000 on either side, far more than the error of the product (n < 2^18)
+        const float n =
+            fmaf(299.0f, v[3 * h], fmaf(587.0f, v[3 * h + 1], fmaf(114.0f, v[3 * h + 2], 500.5f)));
+        v[3 * h] = v[3 * h + 1] = v[3 * h + 2] = floorf(n * 0.001f);
+      } else {  // solarisation
+#pragma unroll
+        for (int c = 0; c < 3; ++c)
+          v[3 * h + c] = v[3 * h + c] >= 128.0f ? 255.0f - v[3 * h + c] : v[3 * h + c];
+      }
+      if (kJitter) {
+        const float lum = jitter_pixel<kReduce>(ap, mean, v[3 * h], v[3 * h + 1], v[3 * h + 2]);
+        if (kReduce) lsum += have ? lum : 0.0f;
+      }
+    }
+    if (kReduce) continue;
+
+    // normalise, then through the strip: 16-byte piece k of the strip belongs to group k / 3
+    f32x4* mine = reinterpret_cast<f32x4*>(strip + 12 * lane);
+    f32x4 o[3];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+      float t[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int idx = 4 * k + e;
+        t[e] = v[idx] * a.nscale[idx % 3] + a.nbias[idx % 3];
+      }
+      o[k] = f32x4{t[0], t[1], t[2], t[3]};
+    }
+    __builtin_amdgcn_wave_barrier();
+    mine[0] = o[0];
+    mine[1] = o[1];
+    mine[2] = o[2];
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+      const int piece = k * kWave + lane;
+      const int g = i0 + small_div(piece, 1.0f / 3.0f);
+      const f32x4 t = reinterpret_cast<const f32x4*>(strip)[piece];
+      const int pgx = small_div(min(g, ngroups - 1), inv_gpp);
+      const int rank = __shfl(my_rank, pgx, kWave);
+      if (g >= ngroups) continue;
+      // element offset inside the patch row, then inside the image (below 2^20: 24-bit multiplies)
+      const int eo = 12 * (g - __mul24(pgx, gpp)) + 4 * (piece - 3 * (g - i0));
+      if (a.target)
+        *reinterpret_cast<f32x4*>(target_image + (uint32_t)(__mul24(l0 + pgx, D) + eo)) = t;
+      if (rank < a.K) {
+        const uint32_t vo = (uint32_t)(__mul24(rank, D) + eo);
+        if (kBf16)
+          *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(visible_image) + vo) =
+              u32x2{pack_bf16x2(t.x, t.y), pack_bf16x2(t.z, t.w)};
+        else
+          *reinterpret_cast<f32x4*>(static_cast<float*>(visible_image) + vo) = t;
+      }
+    }
+  }
+  if (kReduce && !blur) {
+    // the part's share of the image's luma sum: lanes by butterfly, wavefronts in index order
+    double s = (double)lsum;
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, kWave);
+    if (lane == 0) red64[wave] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      double t = 0.0;
+      const int nwaves = (int)blockDim.x / kWave;
+      for (int w = 0; w < nwaves; ++w) t += red64[w];
+      a.luma_partials[tile_id] = t;
+    }
+  }
+}
+
 // What a sample that cannot be used gets instead of pixels: zeros in its rows of `target` and, with
 // the identity as its patch order, in rows l < K of `visible`; the workgroup of the sample's first
 // part also writes the mask row (nothing masked) and the identity order.
@@ -619,7 +830,9 @@ __device__ static void neutral_outputs(const CropArgs& a, int b, int gy, int gx0
 // kLossMode 1, 2: instead of writing the patches, the loss and its gradient against a.pred
 // (1: produce_loss, any patch size; 2: produce_loss_wave, patches of up to 768 values).
 // kLossMode -1: the visible tokens only (no target).
-template <bool kBf16, bool kU8, int kLossMode>
+// kAug: the finetuning augmentation as the epilogue (produce_aug): 1 = "3 Aug", 2 / 3 = first /
+// second pass of "3 Aug+".
+template <bool kBf16, bool kU8, int kLossMode, int kAug = 0>
 __device__ static inline void crop_band(const CropArgs& a, uint32_t* lds) {
   constexpr bool kLoss = kLossMode > 0;
   constexpr bool kKeptOnly = kLossMode < 0;
@@ -651,6 +864,15 @@ __device__ static inline void crop_band(const CropArgs& a, uint32_t* lds) {
       }
     }
     return;
+  }
+
+  AugParams ap;
+  bool blur = false;
+  if constexpr (kAug != 0) {
+    ap = aug_params(a.key1, a.sample_base + (uint32_t)b, a.jitter);
+    blur = ap.op == kOpBlur;
+    // second pass of "3 Aug+": the blur images' bytes are written already
+    if (kAug == 3 && blur) return;
   }
 
   const int S = a.S, p = a.p;
@@ -709,7 +931,8 @@ __device__ static inline void crop_band(const CropArgs& a, uint32_t* lds) {
     float f;
     resize_taps(rec.flip ? S - 1 - ox : ox, rec.cw, S, inv_den, x0, x1, f, rem);
     // at the right edge both taps are the last pixel: weight 0 makes the second tap irrelevant
-    const uint32_t wx = kU8 ? (uint32_t)rem : __float_as_uint(f);
+    const uint32_t wx =
+        kAug ? __float_as_uint((float)rem) : (kU8 ? (uint32_t)rem : __float_as_uint(f));
     xtab[i] = u32x2{(uint32_t)(x0 - xlo), x1 == x0 ? 0u : wx};
   }
   for (int py = tid; py < p; py += (int)blockDim.x) {
@@ -717,8 +940,13 @@ __device__ static inline void crop_band(const CropArgs& a, uint32_t* lds) {
     float f;
     resize_taps(gy * p + py, rec.ch, S, inv_den, y0, y1, f, rem);
     const uint32_t stride = use_lds ? (uint32_t)pitch : (uint32_t)row_bytes;
-    ytab[py] = u32x4{(uint32_t)(y0 - ylo) * stride, (uint32_t)(y1 - ylo) * stride,
-                     kU8 ? (uint32_t)rem : __float_as_uint(f), 0u};
+    if constexpr (kAug != 0)
+      ytab[py] = u32x4{(uint32_t)(y0 - ylo) * stride, (uint32_t)(y1 - ylo) * stride,
+                       __float_as_uint((float)(2 * S - rem) / (float)(4 * S * S)),
+                       __float_as_uint((float)rem / (float)(4 * S * S))};
+    else
+      ytab[py] = u32x4{(uint32_t)(y0 - ylo) * stride, (uint32_t)(y1 - ylo) * stride,
+                       kU8 ? (uint32_t)rem : __float_as_uint(f), 0u};
   }
 
   if (batched) {
@@ -743,7 +971,29 @@ __device__ static inline void crop_band(const CropArgs& a, uint32_t* lds) {
   }
   __syncthreads();
 
-  if constexpr (kLoss) {
+  if constexpr (kAug != 0) {
+    __shared__ double red64[kCropMaxThreads / kWave];
+    constexpr bool kJitter = kAug >= 2;
+    constexpr int kPass = kAug == 3 ? 1 : 0;
+    // the wavefronts' strips follow the tables (16-byte aligned)
+    float* strips = reinterpret_cast<float*>(
+        lds + ((a.tile_pixels + 4 + 4 * a.p + 2 * a.part_patches * a.p + 3) & ~3));
+    float mean = 0.0f;
+    if constexpr (kAug == 3) {  // mean luma after the brightness step, from the first pass
+      const int slots = a.G * a.col_parts;
+      double sum = 0.0;
+      for (int g = 0; g < slots; ++g) sum += a.luma_partials[(int64_t)b * slots + g];
+      mean = (float)(sum / ((double)S * (double)S));
+    }
+    if (use_lds)
+      produce_aug<true, kBf16, kJitter, kPass>(a, tile, xtab, ytab, base, b, gy, gx0, npatch,
+                                               rec.cw - xlo, my_rank, ap, blur, mean, strips,
+                                               red64, tile_id);
+    else
+      produce_aug<false, kBf16, kJitter, kPass>(a, tile, xtab, ytab, base, b, gy, gx0, npatch,
+                                                rec.cw - xlo, my_rank, ap, blur, mean, strips,
+                                                red64, tile_id);
+  } else if constexpr (kLoss) {
     __shared__ float red[(kCropMaxThreads / kWave) * kLossChunk];
     __shared__ double red64[kCropMaxThreads / kWave];
     if constexpr (kLossMode == 2) {
@@ -784,6 +1034,13 @@ template <bool kBf16>
 __global__ __launch_bounds__(kCropMaxThreads) void crop_kept_kernel(CropArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
   crop_band<kBf16, false, -1>(a, lds);
+}
+
+// ... with the finetuning augmentation's pointwise operations as the epilogue
+template <bool kBf16, int kAug>
+__global__ __launch_bounds__(kCropMaxThreads) void crop_aug_kernel(CropArgs a) {
+  extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+  crop_band<kBf16, false, 0, kAug>(a, lds);
 }
 
 // The resampling kernel with the loss as its epilogue: what mae_normpix_loss computes, with the
@@ -932,6 +1189,30 @@ hipError_t launch_crop_loss(const CropArgs& a, hipStream_t stream) {
   if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
   return launch_loss_finish(a.partials + n, kLossGroups, a.inv_count, a.loss_out, a.counts,
                             a.ncounts, a.D, stream);
+}
+
+hipError_t launch_crop_aug(const CropArgs& a, int pass, hipStream_t stream) {
+  dim3 grid((uint32_t)a.B * (uint32_t)a.G * (uint32_t)a.col_parts);
+  // the groups of four pixels are dealt to the lanes, so any number of wavefronts will do: at
+  // most four (their strips share the LDS with the tile)
+  const int waves = ((a.D >> 2) + kWave - 1) / kWave;
+  dim3 block(kWave * (waves < 4 ? waves : 4));
+  const size_t lds = ((crop_lds_bytes(a) + 15) & ~(size_t)15) +
+                     (size_t)(block.x / kWave) * kStripFloats * sizeof(float);
+  const int aug = a.aug_mode == 1 ? 1 : (pass == 0 ? 2 : 3);
+#define MAE_AUG_LAUNCH(BF, AUG) \
+  hipLaunchKernelGGL((crop_aug_kernel<BF, AUG>), grid, block, lds, stream, a)
+  if (a.visible_bf16) {
+    if (aug == 1) MAE_AUG_LAUNCH(true, 1);
+    else if (aug == 2) MAE_AUG_LAUNCH(true, 2);
+    else MAE_AUG_LAUNCH(true, 3);
+  } else {
+    if (aug == 1) MAE_AUG_LAUNCH(false, 1);
+    else if (aug == 2) MAE_AUG_LAUNCH(false, 2);
+    else MAE_AUG_LAUNCH(false, 3);
+  }
+#undef MAE_AUG_LAUNCH
+  return hipGetLastError();
 }
 
 hipError_t launch_crop_patch(const CropArgs& a, hipStream_t stream) {

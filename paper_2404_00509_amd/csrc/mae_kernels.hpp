@@ -45,7 +45,14 @@ struct CropArgs {
   const uint8_t* workspace;
   void* visible;
   float* target;    // nullable
-  uint8_t* u8_out;  // when set: write only the rounded 8-bit patch rows [B, L, D] here
+  uint8_t* u8_out;  // the rounded 8-bit patch rows [B, L, D] of the images that the blur kernel takes
+  // finetuning augmentation as this kernel's epilogue (launch_crop_aug): grayscale and
+  // solarisation are applied to the rounded value in registers, blur images go to u8_out
+  int32_t aug_mode;       // 1: "3 Aug", 2: "3 Aug+"
+  float jitter;
+  uint32_t sample_base;
+  uint64_t key1;
+  double* luma_partials;  // "3 Aug+": [B * G * col_parts] sums of luma after the brightness step
   // the loss as the kernel's epilogue (launch_crop_loss): nothing above from `visible` on is used
   const void* pred;     // [B, L, D]
   void* grad;           // [B, L, D], nullable
@@ -73,6 +80,10 @@ struct CropPlan {
 CropPlan crop_plan(int S, int p, int max_side, int force_parts);
 size_t crop_lds_bytes(const CropArgs& a);
 hipError_t launch_crop_patch(const CropArgs& a, hipStream_t stream);
+// The same with the finetuning augmentation's pointwise operations as the epilogue.  pass 0: the
+// only pass of "3 Aug" / the first pass of "3 Aug+" (luma sums, nothing stored but the 8-bit rows
+// of blur images); pass 1: the second pass of "3 Aug+".
+hipError_t launch_crop_aug(const CropArgs& a, int pass, hipStream_t stream);
 int64_t crop_loss_partials(const CropArgs& a);  // doubles of workspace
 // the loss kernel, then the sum of its partials in a fixed order -> a.loss_out
 hipError_t launch_crop_loss(const CropArgs& a, hipStream_t stream);
@@ -92,7 +103,7 @@ struct AugArgs {
   const uint8_t* u8;          // [B, L, D] bytes: the rounded resized crop in patch order
   const int32_t* ids_restore;
   const uint8_t* workspace;  // header + CropRec[B] (valid flags)
-  double* partials;          // [B * G * blur_parts] luma sums, mode 2
+  double* partials;          // [B * G * blur_parts] luma sums of the blur images, mode 2
   void* visible;
   float* target;  // nullable
 };
@@ -101,7 +112,8 @@ struct AugPlan {
   size_t lds_bytes;
 };
 AugPlan three_aug_plan(int S, int p);
-hipError_t launch_three_aug(const AugArgs& a, hipStream_t stream);
+// The blur images of a batch.  reduce: only their luma sums after the brightness step ("3 Aug+").
+hipError_t launch_aug_blur(const AugArgs& a, bool reduce, hipStream_t stream);
 
 // ---- crop decode of baseline JPEG files ----------------------------------------------------------
 struct JpegRec {

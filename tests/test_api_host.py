@@ -123,7 +123,9 @@ def test_prep_workspace_grows_with_the_augmentation(lib):
     three = lib.mae_prep_workspace_bytes(C.byref(_prep_desc(aug_mode=1)))
     plus = lib.mae_prep_workspace_bytes(C.byref(_prep_desc(aug_mode=2)))
     assert three == 512 + 4 * 224 * 224 * 3          # records rounded up to 256, then the bytes
-    assert plus == three + 4 * 14 * 2 * 8             # a double per row of patches and column part
+    # a double per row of patches and column part: two parts in the blur kernel, one in the
+    # resampling kernel
+    assert plus == three + 4 * 14 * (2 + 1) * 8
     d = _prep_desc(aug_mode=2)
     assert _call_prep(lib, d, ws_bytes=plus - 1) == binding.MAE_ERR_WORKSPACE
 
