@@ -134,7 +134,7 @@ namespace {
 // (jitter) one double per (image, row of patches, column part of the blur kernel); every part
 // starts on a 256-byte boundary.
 struct PrepWorkspace {
-  size_t u8_offset, partials_offset, crop_partials_offset, total;
+  size_t aug_offset, u8_offset, partials_offset, crop_partials_offset, total;
   // crop decode: per-file records, heights, widths, region widths, region offsets, tables, planes, regions
   size_t recs_offset, heights_offset, widths_offset, region_widths_offset, region_offsets_offset,
       prepared_offset, planes_offset, regions_offset;
@@ -152,7 +152,10 @@ mae::CropPlan crop_plan_of(const mae_prep_desc* d, int slot_side) {
 PrepWorkspace prep_workspace(const mae_prep_desc* d) {
   auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
   PrepWorkspace w;
-  w.u8_offset = up(mae::kWorkspaceHeader + (size_t)d->B * sizeof(mae::CropRec));
+  w.aug_offset = up(mae::kWorkspaceHeader + (size_t)d->B * sizeof(mae::CropRec));
+  w.u8_offset = w.aug_offset;
+  if (d->aug_mode != MAE_AUG_SIMPLE)
+    w.u8_offset = up(w.aug_offset + (size_t)d->B * sizeof(mae::AugParams));
   w.partials_offset = w.u8_offset;
   w.crop_partials_offset = w.u8_offset;
   w.total = mae::kWorkspaceHeader + (size_t)d->B * sizeof(mae::CropRec);
@@ -293,6 +296,10 @@ int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t
     pa.heights = ja.heights;
     pa.widths = ja.widths;
   }
+  if (d->aug_mode != MAE_AUG_SIMPLE) {
+    pa.aug_out = ws + wsl.aug_offset;
+    pa.jitter = d->jitter;
+  }
   pa.mask = mask;
   pa.ids_restore = ids_restore;
   pa.ids_keep = ids_keep;
@@ -325,6 +332,7 @@ int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t
   ca.sample_base = d->sample_base;
   ca.key1 = pa.key1;
   ca.luma_partials = reinterpret_cast<double*>(ws + wsl.crop_partials_offset);
+  ca.aug_recs = ws + wsl.aug_offset;
   mae::AugArgs aa;
   memset(&aa, 0, sizeof(aa));
   aa.B = ca.B;
@@ -349,6 +357,7 @@ int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t
   aa.u8 = ca.u8_out;
   aa.ids_restore = ids_restore;
   aa.workspace = ws;
+  aa.aug_recs = ws + wsl.aug_offset;
   aa.partials = reinterpret_cast<double*>(ws + wsl.partials_offset);
   aa.visible = visible;
   aa.target = target;

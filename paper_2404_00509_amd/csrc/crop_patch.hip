@@ -124,13 +124,8 @@ __device__ static inline u32x4 to_pixels(u32x4 d, uint32_t s) {
 // in bytes; crops too large to stage).  my_rank holds, in lane i, the noise rank of patch i of
 // this part (patches gx0 .. gx0 + npatch - 1); cw is the number of source columns from the
 // part's first tapped column to the crop's right edge.
-// kU8: instead of the normalised values, the bilinear value rounded to the nearest byte (ties
-// upwards, exact integer arithmetic on the numerator over (2 S)^2) goes to an 8-bit copy of the
-// patch rows (a.u8_out, [B, L, D] bytes, the layout of `target`) for the finetuning augmentation;
-// the tap tables then hold the integer remainders instead of float weights.  All factors stay
-// below 2^24, so the products are 24-bit multiplies.
 // kKeptOnly: no target is wanted, so the masked patches are skipped.
-template <bool kLds, bool kBf16, bool kU8, bool kKeptOnly>
+template <bool kLds, bool kBf16, bool kKeptOnly>
 __device__ static void produce_patches(const CropArgs& a, const uint32_t* tile, const u32x2* xtab,
                                        const u32x4* ytab, const uint8_t* base, int b, int gy,
                                        int gx0, int npatch, int cw, int my_rank) {
@@ -176,7 +171,7 @@ __device__ static void produce_patches(const CropArgs& a, const uint32_t* tile, 
     const int rank = __builtin_amdgcn_readlane(my_rank, gx);
     if (kKeptOnly && rank >= a.K) continue;
     const u32x2 xa = xtab[gx * p + pxA], xb = xtab[gx * p + pxB];
-    const float fxA = __uint_as_float(xa.y), fxB = __uint_as_float(xb.y);  // kU8: remainders
+    const float fxA = __uint_as_float(xa.y), fxB = __uint_as_float(xb.y);
     uint32_t A00, A01, A10, A11, B00, B01, B10, B11;
     fetch2<kLds>(tile, base, rowA0, (int)xa.x, cw, A00, A01);
     fetch2<kLds>(tile, base, rowA1, (int)xa.x, cw, A10, A11);
@@ -186,33 +181,6 @@ __device__ static void produce_patches(const CropArgs& a, const uint32_t* tile, 
     const uint32_t P01 = __builtin_amdgcn_perm(B01, A01, sel);
     const uint32_t P10 = __builtin_amdgcn_perm(B10, A10, sel);
     const uint32_t P11 = __builtin_amdgcn_perm(B11, A11, sel);
-
-    if (kU8) {
-      const uint32_t den = 2u * (uint32_t)a.S, dd2 = 2u * den * den;
-      const float inv_dd2 = 1.0f / (float)dd2;
-      const uint32_t ryA = ya.z, ryB = yb.z;
-      uint32_t word = 0;
-#define MAE_ROUND(J)                                                                 \
-{                                                                                  \
-  const uint32_t rx = (J) == 0 ? xa.y : ((J) == 3 ? xb.y : ((J) < nA ? xa.y : xb.y)); \
-  const uint32_t ry = (J) == 0 ? ryA : ((J) == 3 ? ryB : ((J) < nA ? ryA : ryB));  \
-  const uint32_t a00 = (P00 >> (8 * (J))) & 0xFFu, a01 = (P01 >> (8 * (J))) & 0xFFu; \
-  const uint32_t a10 = (P10 >> (8 * (J))) & 0xFFu, a11 = (P11 >> (8 * (J))) & 0xFFu; \
-  /* top = den a00 + rx (a01 - a00), bot likewise; num = den top + ry (bot - top) */ \
-  const int top = __mul24((int)den, (int)a00) + __mul24((int)rx, (int)a01 - (int)a00); \
-  const int bot = __mul24((int)den, (int)a10) + __mul24((int)rx, (int)a11 - (int)a10); \
-  const int num = __mul24((int)den, top) + __mul24((int)ry, bot - top);            \
-  const uint32_t x = 2u * (uint32_t)num + den * den; /* floor(x / (2 den^2)) = rounded value */ \
-  int q = (int)((float)x * inv_dd2);                                               \
-  const int r = (int)x - q * (int)dd2;                                             \
-  q += r < 0 ? -1 : (r >= (int)dd2 ? 1 : 0);                                       \
-  word |= (uint32_t)q << (8 * (J));                                                \
-}
-      MAE_ROUND(0) MAE_ROUND(1) MAE_ROUND(2) MAE_ROUND(3)
-#undef MAE_ROUND
-      if (active) *reinterpret_cast<uint32_t*>(a.u8_out + ((int64_t)b * a.L + l) * D + e) = word;
-      continue;
-    }
 
     float out[4];
 #define MAE_BLEND(J)                                                                 \
@@ -596,36 +564,38 @@ __device__ static void produce_loss_wave(const CropArgs& a, const uint32_t* tile
 // neighbouring pixels of a patch row (12 values) instead of four values, and the groups of the
 // part's patches are dealt to the lanes in order.  The 64 x 12 values of a wavefront go through a
 // wavefront-private strip of LDS so that every store instruction still writes 1 KiB of
-// contiguous memory.  Tables: xtab.y = horizontal remainder as a float, ytab.z / ytab.w = the
-// weights of the upper and the lower row over (2 S)^2.
+// contiguous memory.  Tables: xtab.y = horizontal remainder rx, ytab.z / ytab.w = the integer
+// weights den - ry, ry of the two rows (den = 2 S).
 //
-// Rounding.  The bilinear value is num / den^2 with den = 2 S,
-//   top = (den - rx) a00 + rx a01, bot likewise, num = (den - ry) top + ry bot,
-// and it is rounded to the nearest integer, ties upwards, exactly.  top and bot stay below 2^24
-// and are exact in single precision; the quotient is then estimated in single precision with an
-// error below 6.9e-5 (the weight (den - ry) / den^2 and its product with top: 255 * 2^-23; the
-// weight ry / den^2: 255 * 2^-24; the multiply-add: 255 * 2^-24; adding one half before the
-// floor: 2^-17).  Only when the estimate lies within 2^-13 of a rounding boundary for some lane
-// of the wavefront is the integer computation run.
-constexpr float kNearTie = 1.0f / 8192.0f;
+// Rounding.  The bilinear value is num / den^2,
+//   top = (den - rx) a00 + rx a01, bot likewise (two-product dot instructions on 16-bit pairs),
+//   num = (den - ry) top + ry bot (24-bit multiplies: top, bot < 2^18, the sum < 2^28),
+// rounded to the nearest integer, ties upwards: q = floor((num + den^2 / 2) / den^2), all in
+// integers.  The quotient is estimated in single precision with the divisor's reciprocal scaled
+// by (1 - 2^-21), which makes the estimate too small by at most 2e-4 and never too large, so its
+// integer part is q or q - 1 and one comparison of the remainder settles it.
 constexpr int kStripFloats = kWave * 12;  // per wavefront
 
 // floor(n / d) for 0 <= n < 2^22 and small d, from the float reciprocal (inv = 1 / d)
 __device__ static inline int small_div(int n, float inv) { return (int)(((float)n + 0.5f) * inv); }
 
-// floor((2 num + den^2) / (2 den^2)) in integers (all products below 2^31; den <= 1024)
-__device__ static inline float round_exact(uint32_t w00, uint32_t w01, uint32_t w10, uint32_t w11,
-                                           int shift, int den, int rx, int ry) {
-  const int a00 = (int)((w00 >> shift) & 0xFFu), a01 = (int)((w01 >> shift) & 0xFFu);
-  const int a10 = (int)((w10 >> shift) & 0xFFu), a11 = (int)((w11 >> shift) & 0xFFu);
-  const int top = __mul24(den, a00) + __mul24(rx, a01 - a00);
-  const int bot = __mul24(den, a10) + __mul24(rx, a11 - a10);
-  const int num = den * top + ry * (bot - top);
-  const int dd2 = 2 * den * den;
-  const int x = 2 * num + den * den;
-  int q = (int)((float)x * (1.0f / (float)dd2));
-  const int r = x - q * dd2;
-  q += r < 0 ? -1 : (r >= dd2 ? 1 : 0);
+// Channel C of the four taps (pixel words w00 w01 / w10 w11) blended and rounded, as a float.
+// wx = (den - rx) | rx << 16; cy, ry = the rows' weights; dd = den^2; inv_dd as described above.
+template <int C>
+__device__ static inline float round_blend(uint32_t w00, uint32_t w01, uint32_t w10, uint32_t w11,
+                                           uint32_t wx, int cy, int ry, int dd, float inv_dd) {
+  // bytes C of the two words as a pair of 16-bit values (selector 0x0c gives a zero byte)
+  constexpr uint32_t sel = 0x0c000c00u | ((4u + C) << 16) | (uint32_t)C;
+  const uint32_t t2 = __builtin_amdgcn_perm(w01, w00, sel);
+  const uint32_t b2 = __builtin_amdgcn_perm(w11, w10, sel);
+  // (the three-operand form with a zero addend: the accumulating form would need its
+  // destination cleared first)
+  int top, bot;
+  asm("v_dot2_i32_i16 %0, %1, %2, 0" : "=v"(top) : "v"(t2), "v"(wx));
+  asm("v_dot2_i32_i16 %0, %1, %2, 0" : "=v"(bot) : "v"(b2), "v"(wx));
+  const int num = __mul24(ry, bot) + (__mul24(cy, top) + (dd >> 1));
+  int q = (int)((float)num * inv_dd);
+  q += (num - __mul24(q, dd)) >= dd ? 1 : 0;
   return (float)q;
 }
 
@@ -640,13 +610,16 @@ __device__ static void produce_aug(const CropArgs& a, const uint32_t* tile, cons
   const int lane = threadIdx.x % kWave;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int p = a.p, D = a.D;
-  const int den = 2 * a.S;
-  const float den_f = (float)den;
+  const int den = 2 * a.S, dd = den * den;
+  const float inv_dd = (1.0f / (float)dd) * (1.0f - 1.0f / 2097152.0f);
   const int gpp = (p * p) >> 2;  // groups of four pixels per patch
   const float inv_gpp = 1.0f / (float)gpp, inv_p = 1.0f / (float)p;
   const int ngroups = npatch * gpp;
   const int l0 = gy * a.G + gx0;
   const bool gray = ap.op == kOpGray;
+  // patches of 16 x 16 or 32 x 32 pixels: the 64 groups of a wavefront's step lie in one patch
+  const bool whole = (p & 15) == 0;
+  const int gsh = __builtin_ctz(gpp), psh = __builtin_ctz(p);  // used when `whole`
   float* strip = strips + wave * kStripFloats;
   float lsum = 0.0f;
   // this image's rows of the outputs (uniform over the workgroup)
@@ -658,49 +631,37 @@ __device__ static void produce_aug(const CropArgs& a, const uint32_t* tile, cons
 
   // whole wavefronts stay in the loop: the stores are a wavefront's joint work
   for (int i0 = wave * kWave; i0 < ngroups; i0 += (int)blockDim.x) {
-    const bool have = i0 + lane < ngroups;
-    const int i = have ? i0 + lane : ngroups - 1;
-    const int gx = small_div(i, inv_gpp);
-    const int q = 4 * (i - __mul24(gx, gpp));  // first pixel of the group inside the patch
-    const int py = small_div(q, inv_p), px = q - __mul24(py, p);
+    bool have;
+    int gx, q, py, px;
+    if (whole) {
+      have = true;
+      gx = i0 >> gsh;  // uniform
+      q = 4 * ((i0 & (gpp - 1)) + lane);
+      py = q >> psh;
+      px = q & (p - 1);
+    } else {
+      have = i0 + lane < ngroups;
+      const int i = have ? i0 + lane : ngroups - 1;
+      gx = small_div(i, inv_gpp);
+      q = 4 * (i - __mul24(gx, gpp));  // first pixel of the group inside the patch
+      py = small_div(q, inv_p);
+      px = q - __mul24(py, p);
+    }
     const int xt0 = __mul24(gx, p) + px;
     const u32x4 yt = ytab[py];
-    const float wy0 = __uint_as_float(yt.z), wy1 = __uint_as_float(yt.w);
-    uint32_t w00[4], w01[4], w10[4], w11[4];
-    float rx[4];
+    const int cy = (int)yt.z, ry = (int)yt.w;
+
+    float v[12];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const u32x2 xt = xtab[xt0 + j];
-      rx[j] = __uint_as_float(xt.y);
-      fetch2<kLds>(tile, base, yt.x, (int)xt.x, cw, w00[j], w01[j]);
-      fetch2<kLds>(tile, base, yt.y, (int)xt.x, cw, w10[j], w11[j]);
-    }
-
-    float v[12], dmax = 0.0f;
-#define MAE_ROUND_FAST(J, C)                                                                   \
-{                                                                                              \
-  const float top = fmaf(rx[J], byte_to_float<C>(w01[J]), cx * byte_to_float<C>(w00[J]));      \
-  const float bot = fmaf(rx[J], byte_to_float<C>(w11[J]), cx * byte_to_float<C>(w10[J]));      \
-  const float est = fmaf(wy1, bot, wy0 * top);                                                 \
-  v[3 * J + C] = floorf(est + 0.5f);                                                           \
-  dmax = fmaxf(dmax, fabsf(est - v[3 * J + C]));                                               \
-}
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const float cx = den_f - rx[j];
-      MAE_ROUND_FAST(j, 0) MAE_ROUND_FAST(j, 1) MAE_ROUND_FAST(j, 2)
-    }
-#undef MAE_ROUND_FAST
-    if (__builtin_amdgcn_ballot_w64(dmax > 0.5f - kNearTie) != 0) {
-      // some lane is too close to a rounding boundary to call: integers
-      const int iry = (int)rintf(wy1 * den_f * den_f);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int irx = (int)rx[j];
-#pragma unroll
-        for (int c = 0; c < 3; ++c)
-          v[3 * j + c] = round_exact(w00[j], w01[j], w10[j], w11[j], 8 * c, den, irx, iry);
-      }
+      uint32_t w00, w01, w10, w11;
+      fetch2<kLds>(tile, base, yt.x, (int)xt.x, cw, w00, w01);
+      fetch2<kLds>(tile, base, yt.y, (int)xt.x, cw, w10, w11);
+      const uint32_t wx = (uint32_t)(den - (int)xt.y) | (xt.y << 16);
+      v[3 * j] = round_blend<0>(w00, w01, w10, w11, wx, cy, ry, dd, inv_dd);
+      v[3 * j + 1] = round_blend<1>(w00, w01, w10, w11, wx, cy, ry, dd, inv_dd);
+      v[3 * j + 2] = round_blend<2>(w00, w01, w10, w11, wx, cy, ry, dd, inv_dd);
     }
 
     if (blur) {  // the blur kernel's input: the twelve rounded values as bytes
@@ -728,10 +689,10 @@ __device__ static void produce_aug(const CropArgs& a, const uint32_t* tile, cons
         const float n =
             fmaf(299.0f, v[3 * h], fmaf(587.0f, v[3 * h + 1], fmaf(114.0f, v[3 * h + 2], 500.5f)));
         v[3 * h] = v[3 * h + 1] = v[3 * h + 2] = floorf(n * 0.001f);
-      } else {  // solarisation
+      } else {  // solarisation: v >= 128 -> 255 - v, which is the smaller of the two
 #pragma unroll
-        for (int c = 0; c < 3; ++c)
-          v[3 * h + c] = v[3 * h + c] >= 128.0f ? 255.0f - v[3 * h + c] : v[3 * h + c];
+        for (int c = 0; c < 3; ++c)  // (the median with zero of two non-negative numbers)
+          v[3 * h + c] = __builtin_amdgcn_fmed3f(v[3 * h + c], 255.0f - v[3 * h + c], 0.0f);
       }
       if (kJitter) {
         const float lum = jitter_pixel<kReduce>(ap, mean, v[3 * h], v[3 * h + 1], v[3 * h + 2]);
@@ -758,6 +719,28 @@ __device__ static void produce_aug(const CropArgs& a, const uint32_t* tile, cons
     mine[1] = o[1];
     mine[2] = o[2];
     __builtin_amdgcn_wave_barrier();
+    if (whole) {
+      // one patch, 768 consecutive floats of its row from element 12 (i0 mod gpp) on
+      const int gxs = __builtin_amdgcn_readfirstlane(gx);
+      const int rank = __builtin_amdgcn_readlane(my_rank, gxs);
+      const uint32_t e0 = 12u * (uint32_t)(i0 & (gpp - 1)) + 4u * (uint32_t)lane;
+      float* trow = a.target ? target_image + (l0 + gxs) * D : nullptr;
+#pragma unroll
+      for (int k = 0; k < 3; ++k) {
+        const f32x4 t = reinterpret_cast<const f32x4*>(strip)[k * kWave + lane];
+        const uint32_t eo = e0 + 4u * kWave * k;
+        if (trow) *reinterpret_cast<f32x4*>(trow + eo) = t;
+        if (rank < a.K) {
+          const uint32_t vo = (uint32_t)(rank * D) + eo;
+          if (kBf16)
+            *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(visible_image) + vo) =
+                u32x2{pack_bf16x2(t.x, t.y), pack_bf16x2(t.z, t.w)};
+          else
+            *reinterpret_cast<f32x4*>(static_cast<float*>(visible_image) + vo) = t;
+        }
+      }
+      continue;
+    }
 #pragma unroll
     for (int k = 0; k < 3; ++k) {
       const int piece = k * kWave + lane;
@@ -832,7 +815,7 @@ __device__ static void neutral_outputs(const CropArgs& a, int b, int gy, int gx0
 // kLossMode -1: the visible tokens only (no target).
 // kAug: the finetuning augmentation as the epilogue (produce_aug): 1 = "3 Aug", 2 / 3 = first /
 // second pass of "3 Aug+".
-template <bool kBf16, bool kU8, int kLossMode, int kAug = 0>
+template <bool kBf16, int kLossMode, int kAug = 0>
 __device__ static inline void crop_band(const CropArgs& a, uint32_t* lds) {
   constexpr bool kLoss = kLossMode > 0;
   constexpr bool kKeptOnly = kLossMode < 0;
@@ -869,7 +852,7 @@ __device__ static inline void crop_band(const CropArgs& a, uint32_t* lds) {
   AugParams ap;
   bool blur = false;
   if constexpr (kAug != 0) {
-    ap = aug_params(a.key1, a.sample_base + (uint32_t)b, a.jitter);
+    ap = static_cast<const AugParams*>(a.aug_recs)[b];
     blur = ap.op == kOpBlur;
     // second pass of "3 Aug+": the blur images' bytes are written already
     if (kAug == 3 && blur) return;
@@ -931,8 +914,7 @@ __device__ static inline void crop_band(const CropArgs& a, uint32_t* lds) {
     float f;
     resize_taps(rec.flip ? S - 1 - ox : ox, rec.cw, S, inv_den, x0, x1, f, rem);
     // at the right edge both taps are the last pixel: weight 0 makes the second tap irrelevant
-    const uint32_t wx =
-        kAug ? __float_as_uint((float)rem) : (kU8 ? (uint32_t)rem : __float_as_uint(f));
+    const uint32_t wx = kAug ? (uint32_t)rem : __float_as_uint(f);
     xtab[i] = u32x2{(uint32_t)(x0 - xlo), x1 == x0 ? 0u : wx};
   }
   for (int py = tid; py < p; py += (int)blockDim.x) {
@@ -940,13 +922,12 @@ __device__ static inline void crop_band(const CropArgs& a, uint32_t* lds) {
     float f;
     resize_taps(gy * p + py, rec.ch, S, inv_den, y0, y1, f, rem);
     const uint32_t stride = use_lds ? (uint32_t)pitch : (uint32_t)row_bytes;
-    if constexpr (kAug != 0)
+    if constexpr (kAug != 0)  // integer weights of the two rows: 2 S - rem, rem
       ytab[py] = u32x4{(uint32_t)(y0 - ylo) * stride, (uint32_t)(y1 - ylo) * stride,
-                       __float_as_uint((float)(2 * S - rem) / (float)(4 * S * S)),
-                       __float_as_uint((float)rem / (float)(4 * S * S))};
+                       (uint32_t)(2 * S - rem), (uint32_t)rem};
     else
       ytab[py] = u32x4{(uint32_t)(y0 - ylo) * stride, (uint32_t)(y1 - ylo) * stride,
-                       kU8 ? (uint32_t)rem : __float_as_uint(f), 0u};
+                       __float_as_uint(f), 0u};
   }
 
   if (batched) {
@@ -1016,43 +997,43 @@ __device__ static inline void crop_band(const CropArgs& a, uint32_t* lds) {
                           red, red64, tile_id);
     }
   } else if (use_lds) {
-    produce_patches<true, kBf16, kU8, kKeptOnly>(a, tile, xtab, ytab, base, b, gy, gx0, npatch,
+    produce_patches<true, kBf16, kKeptOnly>(a, tile, xtab, ytab, base, b, gy, gx0, npatch,
                                                  rec.cw - xlo, my_rank);
   } else {
-    produce_patches<false, kBf16, kU8, kKeptOnly>(a, tile, xtab, ytab, base, b, gy, gx0, npatch,
+    produce_patches<false, kBf16, kKeptOnly>(a, tile, xtab, ytab, base, b, gy, gx0, npatch,
                                                   rec.cw - xlo, my_rank);
   }
 }
 
-template <bool kBf16, bool kU8>
+template <bool kBf16>
 __global__ __launch_bounds__(kCropMaxThreads) void crop_patch_kernel(CropArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
-  crop_band<kBf16, kU8, 0>(a, lds);
+  crop_band<kBf16, 0>(a, lds);
 }
 // ... when no target is wanted: only the patches that are kept
 template <bool kBf16>
 __global__ __launch_bounds__(kCropMaxThreads) void crop_kept_kernel(CropArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
-  crop_band<kBf16, false, -1>(a, lds);
+  crop_band<kBf16, -1>(a, lds);
 }
 
 // ... with the finetuning augmentation's pointwise operations as the epilogue
 template <bool kBf16, int kAug>
 __global__ __launch_bounds__(kCropMaxThreads) void crop_aug_kernel(CropArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
-  crop_band<kBf16, false, 0, kAug>(a, lds);
+  crop_band<kBf16, 0, kAug>(a, lds);
 }
 
 // The resampling kernel with the loss as its epilogue: what mae_normpix_loss computes, with the
 // masked patches' pixels taken from the images again instead of from a stored target.
 __global__ __launch_bounds__(kCropMaxThreads) void crop_loss_kernel(CropArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
-  crop_band<false, false, 1>(a, lds);
+  crop_band<false, 1>(a, lds);
 }
 // ... with a wavefront per patch (D <= 768): four wavefronts per workgroup
 __global__ __launch_bounds__(4 * kWave) void crop_loss_wave_kernel(CropArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
-  crop_band<false, false, 2>(a, lds);
+  crop_band<false, 2>(a, lds);
 }
 
 // Patch sizes whose 3 p^2 values per patch are not a multiple of four (odd p): one value per
@@ -1220,16 +1201,14 @@ hipError_t launch_crop_patch(const CropArgs& a, hipStream_t stream) {
     dim3 grid((uint32_t)a.B * (uint32_t)a.G * (uint32_t)a.col_parts);
     dim3 block(kWave * (((a.D >> 2) + kWave - 1) / kWave));
     const size_t lds = crop_lds_bytes(a);
-    if (a.u8_out) {
-      hipLaunchKernelGGL((crop_patch_kernel<false, true>), grid, block, lds, stream, a);
-    } else if (!a.target && a.visible_bf16) {
+    if (!a.target && a.visible_bf16) {
       hipLaunchKernelGGL(crop_kept_kernel<true>, grid, block, lds, stream, a);
     } else if (!a.target) {
       hipLaunchKernelGGL(crop_kept_kernel<false>, grid, block, lds, stream, a);
     } else if (a.visible_bf16) {
-      hipLaunchKernelGGL((crop_patch_kernel<true, false>), grid, block, lds, stream, a);
+      hipLaunchKernelGGL(crop_patch_kernel<true>, grid, block, lds, stream, a);
     } else {
-      hipLaunchKernelGGL((crop_patch_kernel<false, false>), grid, block, lds, stream, a);
+      hipLaunchKernelGGL(crop_patch_kernel<false>, grid, block, lds, stream, a);
     }
   } else {
     const int64_t total = (int64_t)a.B * a.L * a.D;

@@ -67,7 +67,9 @@ struct AugParams {
   int32_t radius;  // of the blur: ceil(3 sigma), 1..6
   double sigma;
   float brightness, contrast, saturation;
+  float pad;
 };
+static_assert(sizeof(AugParams) == 32, "one 32-byte record per sample in the workspace");
 __device__ inline AugParams aug_params(uint64_t key1, uint32_t sample, float jitter) {
 #pragma clang fp contract(off)  // sigma decides the integer radius: no fused multiply-add here
   AugParams ap;
@@ -80,6 +82,7 @@ __device__ inline AugParams aug_params(uint64_t key1, uint32_t sample, float jit
   ap.brightness = (float)(1.0 + j * (2.0 * unit53(draw(key1, sample, kBrightness, 0)) - 1.0));
   ap.contrast = (float)(1.0 + j * (2.0 * unit53(draw(key1, sample, kContrast, 0)) - 1.0));
   ap.saturation = (float)(1.0 + j * (2.0 * unit53(draw(key1, sample, kSaturation, 0)) - 1.0));
+  ap.pad = 0.0f;
   return ap;
 }
 

@@ -25,6 +25,8 @@ struct ParamArgs {
   int32_t* ids_keep;   // nullable
   int32_t* crop_out;   // nullable, [B,6]
   uint8_t* workspace;  // header + CropRec[B]
+  void* aug_out;       // nullable: AugParams[B], the finetuning augmentation's draws per sample
+  float jitter;
 };
 hipError_t launch_params_mask(const ParamArgs& a, hipStream_t stream);
 
@@ -53,6 +55,7 @@ struct CropArgs {
   uint32_t sample_base;
   uint64_t key1;
   double* luma_partials;  // "3 Aug+": [B * G * col_parts] sums of luma after the brightness step
+  const void* aug_recs;   // AugParams[B], written by the parameter kernel
   // the loss as the kernel's epilogue (launch_crop_loss): nothing above from `visible` on is used
   const void* pred;     // [B, L, D]
   void* grad;           // [B, L, D], nullable
@@ -103,6 +106,7 @@ struct AugArgs {
   const uint8_t* u8;          // [B, L, D] bytes: the rounded resized crop in patch order
   const int32_t* ids_restore;
   const uint8_t* workspace;  // header + CropRec[B] (valid flags)
+  const void* aug_recs;      // AugParams[B], written by the parameter kernel
   double* partials;          // [B * G * blur_parts] luma sums of the blur images, mode 2
   void* visible;
   float* target;  // nullable

@@ -152,6 +152,8 @@ __global__ __launch_bounds__(kWave) void params_mask_kernel(ParamArgs a) {
       int32_t* c = a.crop_out + (int64_t)b * 6;
       c[0] = top; c[1] = left; c[2] = ch; c[3] = cw; c[4] = flip; c[5] = valid ? 1 : 0;
     }
+    // the finetuning augmentation's draws, once per sample instead of once per workgroup later
+    if (a.aug_out) static_cast<AugParams*>(a.aug_out)[b] = aug_params(a.key1, sample, a.jitter);
     if (b == 0) {  // header: lets the status query find the records of this call
       WorkspaceHeader* hdr = reinterpret_cast<WorkspaceHeader*>(a.workspace);
       hdr->magic = kWorkspaceMagic;

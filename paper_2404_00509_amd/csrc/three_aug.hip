@@ -35,6 +35,7 @@ constexpr int kTaps = 2 * kMaxRadius + 1;
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
 typedef u32x3 u32x3_a4 __attribute__((aligned(4)));
 
@@ -69,6 +70,40 @@ __device__ static inline void store_band_sum(const AugArgs& a, int b, int slot, 
 // ---- Gaussian blur ---------------------------------------------------------------------------------
 // Patches staged on either side of the part: enough for the largest radius.
 __host__ __device__ static inline int halo_patches(int p) { return (kMaxRadius + p - 1) / p; }
+
+// Copies `rows` image rows (first y_first, clamped into the image) of patches gxa .. gxa + nseg - 1
+// from the patch-order bytes `img` into `dst` in image order, in pieces of type T (wseg pieces per
+// patch row).  A thread issues four loads before it stores the first.
+template <typename T>
+__device__ static inline void stage_rows(uint8_t* dst, const uint8_t* img, int rows, int nseg,
+                                         int wseg, int y_first, int S, int p, int G, int gxa,
+                                         int D) {
+  T* out = reinterpret_cast<T*>(dst);
+  const int pitch = nseg * wseg, total = rows * pitch;
+  const float inv_pitch = 1.0f / (float)pitch, inv_wseg = 1.0f / (float)wseg;
+  const float inv_p = 1.0f / (float)p;
+  constexpr int kBatch = 4;
+  for (int i0 = threadIdx.x; i0 < total; i0 += kBatch * kAugThreads) {
+    T v[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int i = min(i0 + u * kAugThreads, total - 1);
+      const int j = fast_div(i, inv_pitch);
+      const int r = i - j * pitch;
+      const int seg = fast_div(r, inv_wseg);
+      const int yy = min(max(y_first + j, 0), S - 1);
+      const int gyy = fast_div(yy, inv_p);
+      v[u] = *reinterpret_cast<const T*>(
+          img + (uint32_t)((gyy * G + gxa + seg) * D + (yy - gyy * p) * 3 * p +
+                           (int)sizeof(T) * (r - seg * wseg)));
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int i = i0 + u * kAugThreads;
+      if (i < total) out[i] = v[u];
+    }
+  }
+}
 
 // Vertical pass: kRows output rows of one value column per item.
 template <int R, int kRows>
@@ -114,35 +149,11 @@ __device__ static void blur_part(const AugArgs& a, const AugParams& ap, int b, i
   const uint8_t* img = a.u8 + (int64_t)b * a.L * a.D;  // patch order
 
   // ---- staging: rows y0 - R .. y0 + p - 1 + R (clamped), patches gxa .. gxb ----------------------
-  {
-    uint32_t* sb32 = reinterpret_cast<uint32_t*>(scratch);
-    const int total = rows * pitch4;
-    const float inv_pitch4 = 1.0f / (float)pitch4, inv_w4 = 1.0f / (float)w4;
-    constexpr int kBatch = 4;
-    for (int i0 = tid; i0 < total; i0 += kBatch * kAugThreads) {
-      uint32_t v[kBatch];
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        const int i = i0 + u * kAugThreads;
-        v[u] = 0u;
-        if (i < total) {
-          const int j = fast_div(i, inv_pitch4);
-          const int r = i - j * pitch4;
-          const int seg = fast_div(r, inv_w4);
-          const int yy = min(max(y0 - R + j, 0), S - 1);
-          const int gyy = fast_div(yy, inv_p);
-          v[u] = *reinterpret_cast<const uint32_t*>(
-              img + (uint32_t)((gyy * G + gxa + seg) * a.D + (yy - gyy * p) * 3 * p +
-                               4 * (r - seg * w4)));
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        const int i = i0 + u * kAugThreads;
-        if (i < total) sb32[i] = v[u];
-      }
-    }
-  }
+  // in pieces of 16 bytes when a patch row is a multiple of that (p = 16, 32), else of 4 bytes
+  if ((p & 15) == 0)
+    stage_rows<u32x4>(scratch, img, rows, nseg, w4 >> 2, y0 - R, S, p, G, gxa, a.D);
+  else
+    stage_rows<uint32_t>(scratch, img, rows, nseg, w4, y0 - R, S, p, G, gxa, a.D);
   // taps -R .. R of this image's kernel (zero beyond its radius)
   float wt[2 * R + 1];
 #pragma unroll
@@ -268,8 +279,9 @@ __global__ __launch_bounds__(kAugThreads) void aug_blur_kernel(AugArgs a) {
   const int gx0 = part * G / parts, gx1 = (part + 1) * G / parts;
   const int npatch = gx1 - gx0;
   const bool valid = reinterpret_cast<const CropRec*>(a.workspace + kWorkspaceHeader)[b].valid != 0;
-  const AugParams ap = aug_params(a.key1, a.sample_base + (uint32_t)b, a.jitter);
-  if (!valid || ap.op != kOpBlur || npatch <= 0) return;
+  if (!valid || npatch <= 0) return;
+  const AugParams ap = static_cast<const AugParams*>(a.aug_recs)[b];
+  if (ap.op != kOpBlur) return;
 
   const int tid = threadIdx.x;
   const int radius = ap.radius;
