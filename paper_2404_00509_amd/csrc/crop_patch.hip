@@ -688,7 +688,19 @@ __device__ static void produce_aug(const CropArgs& a, const uint32_t* tile, cons
         // a multiple of 1000 on either side, far more than the error of the product (n < 2^18)
         const float n =
             fmaf(299.0f, v[3 * h], fmaf(587.0f, v[3 * h + 1], fmaf(114.0f, v[3 * h + 2], 500.5f)));
-        v[3 * h] = v[3 * h + 1] = v[3 * h + 2] = floorf(n * 0.001f);
+        float g = floorf(n * 0.001f);
+        if (kJitter) {
+          // equal channels stay equal under the jitter: one channel's arithmetic, and the
+          // saturation step leaves it as it is (the luma weights add up to one)
+          g = clamp255(g * ap.brightness);
+          if (kReduce) {
+            lsum += have ? g : 0.0f;
+          } else {
+            g = clamp255(ap.contrast * g + (1.0f - ap.contrast) * mean);
+          }
+        }
+        v[3 * h] = v[3 * h + 1] = v[3 * h + 2] = g;
+        continue;
       } else {  // solarisation: v >= 128 -> 255 - v, which is the smaller of the two
 #pragma unroll
         for (int c = 0; c < 3; ++c)  // (the median with zero of two non-negative numbers)

@@ -180,12 +180,25 @@ __device__ static void blur_part(const AugArgs& a, const AugParams& ap, int b, i
       kBf16 ? static_cast<void*>(static_cast<uint16_t*>(a.visible) + (int64_t)b * a.K * a.D)
             : static_cast<void*>(static_cast<float*>(a.visible) + (int64_t)b * a.K * a.D);
   float lsum = 0.0f;
+  // patches of 16 x 16 or 32 x 32 pixels: the 64 groups of a wavefront's step lie in one patch
+  const bool whole = (p & 15) == 0;
+  const int gsh = __builtin_ctz(gpp), psh = __builtin_ctz(p);  // used when `whole`
   for (int i0 = wave * kWave; i0 < ngroups; i0 += kAugThreads) {
-    const bool have = i0 + lane < ngroups;
-    const int i = have ? i0 + lane : ngroups - 1;
-    const int gxl = fast_div(i, inv_gpp);
-    const int q = 4 * (i - gxl * gpp);
-    const int py = fast_div(q, inv_p), x = gxl * p + (q - py * p);  // pixel inside the part
+    bool have;
+    int gxl, q, py;
+    if (whole) {
+      have = true;
+      gxl = i0 >> gsh;  // uniform
+      q = 4 * ((i0 & (gpp - 1)) + lane);
+      py = q >> psh;
+    } else {
+      have = i0 + lane < ngroups;
+      const int i = have ? i0 + lane : ngroups - 1;
+      gxl = fast_div(i, inv_gpp);
+      q = 4 * (i - gxl * gpp);
+      py = fast_div(q, inv_p);
+    }
+    const int x = gxl * p + (q - py * p);  // pixel inside the part
     // pixels x - R .. x + 3 + R of the row: (4 + 2 R) * 3 floats, 16-byte aligned
     const f32x4* src = reinterpret_cast<const f32x4*>(vbuf + py * vpitch + 3 * x);
     float n[(4 + 2 * R) * 3];
@@ -236,6 +249,28 @@ __device__ static void blur_part(const AugArgs& a, const AugParams& ap, int b, i
     mine[1] = o[1];
     mine[2] = o[2];
     __builtin_amdgcn_wave_barrier();
+    if (whole) {
+      // one patch, 768 consecutive floats of its row from element 12 (i0 mod gpp) on
+      const int gxs = __builtin_amdgcn_readfirstlane(gxl);
+      const int rank = __builtin_amdgcn_readlane(my_rank, gxs);
+      const uint32_t e0 = 12u * (uint32_t)(i0 & (gpp - 1)) + 4u * (uint32_t)lane;
+      float* trow = a.target ? target_image + (l0 + gxs) * a.D : nullptr;
+#pragma unroll
+      for (int k = 0; k < 3; ++k) {
+        const f32x4 t = reinterpret_cast<const f32x4*>(strip)[k * kWave + lane];
+        const uint32_t eo = e0 + 4u * kWave * k;
+        if (trow) *reinterpret_cast<f32x4*>(trow + eo) = t;
+        if (rank < a.K) {
+          const uint32_t vo = (uint32_t)(rank * a.D) + eo;
+          if (kBf16)
+            *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(visible_image) + vo) =
+                u32x2{pack_bf16x2(t.x, t.y), pack_bf16x2(t.z, t.w)};
+          else
+            *reinterpret_cast<f32x4*>(static_cast<float*>(visible_image) + vo) = t;
+        }
+      }
+      continue;
+    }
 #pragma unroll
     for (int k = 0; k < 3; ++k) {
       const int piece = k * kWave + lane;
