@@ -159,7 +159,7 @@ def time_finetune(args, mae, torch, dev, wl):
     import numpy as np
 
     rows = []
-    res, lo, hi = mae.mae_finetune_stage(1, 3)
+    res, lo, hi, _ = mae.mae_finetune_stage(1, 3)
     G = res // wl.patch
     L = G * G
     stream = torch.cuda.current_stream()

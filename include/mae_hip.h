@@ -307,11 +307,21 @@ int mae_patch_embed(const mae_embed_desc* d, void* tokens, void* hip_stream);
 int mae_pretrain_stage(int32_t scheme, int32_t stage, int32_t* host_out_size,
                        double* host_mask_ratio);
 
-/* Finetuning scheme 1 (also 1-, 1+, which differ in augmentation only) or 3, stage 1..3 ->
- * resolution and the bounds of the crop's side ratio sigma; the area-fraction bounds that
- * mae_prep_desc takes are sigma^2: *host_scale_lo = sigma_lo^2, *host_scale_hi = sigma_hi^2. */
+/* The finetuning schemes of Table 7.  1-, 1+ have the sizes of scheme 1 and differ from it in the
+ * augmentation column only. */
+typedef enum {
+  MAE_FINETUNE_SCHEME_1 = 1,
+  MAE_FINETUNE_SCHEME_3 = 3,
+  MAE_FINETUNE_SCHEME_1_MINUS = 10,
+  MAE_FINETUNE_SCHEME_1_PLUS = 11
+} mae_finetune_scheme;
+
+/* Finetuning scheme (mae_finetune_scheme), stage 1..3 -> resolution, the bounds of the crop's
+ * side ratio sigma as the area-fraction bounds that mae_prep_desc takes (*host_scale_lo =
+ * sigma_lo^2, *host_scale_hi = sigma_hi^2), and the stage's augmentation (*host_aug_mode, a
+ * mae_aug_mode for mae_prep_desc.aug_mode: MAE_AUG_THREE or MAE_AUG_THREE_PLUS; nullable). */
 int mae_finetune_stage(int32_t scheme, int32_t stage, int32_t* host_out_size,
-                       float* host_scale_lo, float* host_scale_hi);
+                       float* host_scale_lo, float* host_scale_hi, int32_t* host_aug_mode);
 
 /* 1-based stage that 0-based `epoch` falls in when the stages last host_lengths[0..n) epochs
  * (finetuning: 30, 30, 40; the paper gives none for pretraining).  Epochs past the end belong to

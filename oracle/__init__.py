@@ -126,7 +126,7 @@ def load_library(path: str):
     L.mae_oracle_pretrain_stage.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     L.mae_oracle_finetune_stage.restype = C.c_int32
     L.mae_oracle_finetune_stage.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
-                                            C.c_void_p]
+                                            C.c_void_p, C.c_void_p]
     L.mae_oracle_stage_of_epoch.restype = C.c_int32
     L.mae_oracle_stage_of_epoch.argtypes = [C.c_int32, C.c_void_p, C.c_int32]
     L.mae_oracle_patch_embed.restype = C.c_int32
@@ -384,13 +384,17 @@ def pretrain_stage(scheme: int, stage: int):
     return res.value, m.value
 
 
+FINETUNE_SCHEMES = {"1": 1, "3": 3, "1-": 10, "1+": 11}
+
+
 def finetune_stage(scheme: int, stage: int):
-    """-> (resolution, sigma_lo, sigma_hi) of Table 7, or None."""
-    res, lo, hi = C.c_int32(), C.c_double(), C.c_double()
-    if lib().mae_oracle_finetune_stage(scheme, stage, C.byref(res), C.byref(lo),
-                                       C.byref(hi)) != 0:
+    """-> (resolution, sigma_lo, sigma_hi, aug) of Table 7, or None.  scheme 10 / 11 are the
+    table's "1-" / "1+"; aug 1 = "3 Aug", 2 = "3 Aug+"."""
+    res, lo, hi, aug = C.c_int32(), C.c_double(), C.c_double(), C.c_int32()
+    if lib().mae_oracle_finetune_stage(scheme, stage, C.byref(res), C.byref(lo), C.byref(hi),
+                                       C.byref(aug)) != 0:
         return None
-    return res.value, lo.value, hi.value
+    return res.value, lo.value, hi.value, aug.value
 
 
 def stage_of_epoch(epoch: int, lengths) -> int:

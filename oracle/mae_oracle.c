@@ -565,14 +565,23 @@ int32_t mae_oracle_pretrain_stage(int32_t scheme, int32_t stage, int32_t* res, d
 }
 
 int32_t mae_oracle_finetune_stage(int32_t scheme, int32_t stage, int32_t* res, double* sigma_lo,
-                                  double* sigma_hi) {
-  if ((scheme != 1 && scheme != 3) || stage < 1 || stage > 3 || !res || !sigma_lo || !sigma_hi)
+                                  double* sigma_hi, int32_t* aug) {
+  /* scheme: 1, 3, and 10 / 11 for the table's "1-" / "1+" */
+  if ((scheme != 1 && scheme != 3 && scheme != 10 && scheme != 11) || stage < 1 || stage > 3 ||
+      !res || !sigma_lo || !sigma_hi)
     return -1;
   static const int32_t R[3] = {160, 192, 224};
   static const double hi3[3] = {0.68, 0.84, 1.0};
   *res = R[stage - 1];
   *sigma_lo = 0.28;
-  *sigma_hi = scheme == 1 ? 1.0 : hi3[stage - 1];
+  *sigma_hi = scheme == 3 ? hi3[stage - 1] : 1.0;
+  /* aug column: 1 = "3 Aug", 2 = "3 Aug+".  Schemes 1 and 3 strengthen it in the last stage;
+   * "1-" never does, "1+" uses the stronger one throughout. */
+  if (aug) {
+    if (scheme == 10) *aug = 1;
+    else if (scheme == 11) *aug = 2;
+    else *aug = stage == 3 ? 2 : 1;
+  }
   return 0;
 }
 

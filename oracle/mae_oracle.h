@@ -157,10 +157,11 @@ int32_t mae_oracle_pixel_loss(int32_t B, int32_t L, int32_t D, const float* pred
 /* Pretraining scheme 1..6, stage 1..3 -> training resolution and masking ratio.  Returns 0, or
  * -1 for an unknown scheme or stage. */
 int32_t mae_oracle_pretrain_stage(int32_t scheme, int32_t stage, int32_t* res, double* mask_ratio);
-/* Finetuning scheme (1 = scheme 1/1-/1+, 3 = scheme 3), stage 1..3 -> resolution and the bounds
- * sigma-, sigma+ of the crop's side ratio (the crop's area fraction is their square). */
+/* Finetuning scheme (1, 3; 10 = the table's "1-", 11 = "1+"), stage 1..3 -> resolution, the bounds
+ * sigma-, sigma+ of the crop's side ratio (the crop's area fraction is their square) and the
+ * stage's augmentation (aug, nullable: 1 = "3 Aug", 2 = "3 Aug+"). */
 int32_t mae_oracle_finetune_stage(int32_t scheme, int32_t stage, int32_t* res, double* sigma_lo,
-                                  double* sigma_hi);
+                                  double* sigma_hi, int32_t* aug);
 /* Stage (1-based) that epoch `epoch` (0-based) falls in when the stages last lengths[0..n) epochs;
  * epochs past the end belong to the last stage.  Returns -1 on bad arguments. */
 int32_t mae_oracle_stage_of_epoch(int32_t epoch, const int32_t* lengths, int32_t n);

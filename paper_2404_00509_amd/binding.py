@@ -21,6 +21,8 @@ MAE_ERR_WORKSPACE, MAE_ERR_NO_DEVICE, MAE_ERR_HIP = -5, -6, -7
 MAE_F32, MAE_BF16 = 0, 1
 MAE_AUG_SIMPLE, MAE_AUG_THREE, MAE_AUG_THREE_PLUS = 0, 1, 2
 MAE_INPUT_DECODED, MAE_INPUT_JPEG = 0, 1
+MAE_FINETUNE_SCHEME_1, MAE_FINETUNE_SCHEME_3 = 1, 3
+MAE_FINETUNE_SCHEME_1_MINUS, MAE_FINETUNE_SCHEME_1_PLUS = 10, 11
 
 IMAGENET_MEAN = (0.485, 0.456, 0.406)
 IMAGENET_STD = (0.229, 0.224, 0.225)
@@ -143,7 +145,8 @@ def load():
                                            C.POINTER(C.c_double)]
         lib.mae_finetune_stage.restype = C.c_int
         lib.mae_finetune_stage.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_int32),
-                                           C.POINTER(C.c_float), C.POINTER(C.c_float)]
+                                           C.POINTER(C.c_float), C.POINTER(C.c_float),
+                                           C.POINTER(C.c_int32)]
         lib.mae_stage_of_epoch.restype = C.c_int
         lib.mae_stage_of_epoch.argtypes = [C.c_int32, C.POINTER(C.c_int32), C.c_int32]
         lib.mae_error_string.restype = C.c_char_p
@@ -176,12 +179,14 @@ def mae_pretrain_stage(scheme: int, stage: int):
 
 
 def mae_finetune_stage(scheme: int, stage: int):
-    """-> (out_size, scale_lo, scale_hi): area-fraction bounds for mae_prep_desc."""
-    res, lo, hi = C.c_int32(), C.c_float(), C.c_float()
-    rc = load().mae_finetune_stage(scheme, stage, C.byref(res), C.byref(lo), C.byref(hi))
+    """-> (out_size, scale_lo, scale_hi, aug_mode): area-fraction bounds and augmentation for
+    mae_prep_desc.  scheme: MAE_FINETUNE_SCHEME_1, _3, _1_MINUS, _1_PLUS."""
+    res, lo, hi, aug = C.c_int32(), C.c_float(), C.c_float(), C.c_int32()
+    rc = load().mae_finetune_stage(scheme, stage, C.byref(res), C.byref(lo), C.byref(hi),
+                                   C.byref(aug))
     if rc != MAE_OK:
         raise MaeError(rc, "mae_finetune_stage")
-    return res.value, lo.value, hi.value
+    return res.value, lo.value, hi.value, aug.value
 
 
 def mae_stage_of_epoch(epoch: int, lengths) -> int:
@@ -194,6 +199,25 @@ def mae_stage_of_epoch(epoch: int, lengths) -> int:
 
 def _ptr(t):
     return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _check(t, name, dtypes=None, numel=None, optional=False):
+    """Marshalling checks: the library reads raw device pointers, so a tensor of the wrong type,
+    on the host, or with gaps would be read past its end."""
+    if t is None:
+        if optional:
+            return
+        raise TypeError(f"{name} is required")
+    if not isinstance(t, torch.Tensor):
+        raise TypeError(f"{name} must be a torch tensor")
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live in device memory")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtypes is not None and t.dtype not in (dtypes if isinstance(dtypes, tuple) else (dtypes,)):
+        raise TypeError(f"{name} has dtype {t.dtype}, expected {dtypes}")
+    if numel is not None and t.numel() < numel:
+        raise ValueError(f"{name} holds {t.numel()} elements, {numel} are needed")
 
 
 def _stream(stream):
@@ -210,6 +234,15 @@ def make_prep_desc(images, offsets, heights, widths, *, out_size, patch, num_kee
     """Decoded input: images / offsets / heights / widths as device tensors.  JPEG input ("crop
     decode"): images = the files back to back, offsets = their starts, file_sizes = their lengths
     (int32); heights and widths are then ignored (pass None)."""
+    _check(images, "images", torch.uint8)
+    _check(offsets, "offsets", torch.int64)
+    if file_sizes is None:
+        _check(heights, "heights", torch.int32)
+        _check(widths, "widths", torch.int32, numel=heights.numel())
+        _check(offsets, "offsets", torch.int64, numel=heights.numel())
+    else:
+        _check(file_sizes, "file_sizes", torch.int32)
+        _check(offsets, "offsets", torch.int64, numel=file_sizes.numel())
     d = MaePrepDesc()
     d.images = images.data_ptr()
     d.images_bytes = int(images.numel())
@@ -242,6 +275,16 @@ def mae_prep_workspace_bytes(desc: MaePrepDesc) -> int:
 def mae_prep_batch(desc: MaePrepDesc, visible, mask, ids_restore, ids_keep=None, target=None,
                    crop_out=None, workspace=None, stream=None) -> None:
     """Enqueue the input pipeline; all tensors are preallocated device tensors."""
+    B, p, K = desc.B, max(desc.patch, 1), desc.num_keep
+    L, D = (desc.out_size // p) ** 2, 3 * p * p
+    _check(visible, "visible", torch.bfloat16 if desc.out_dtype == MAE_BF16 else torch.float32,
+           numel=B * K * D)
+    _check(mask, "mask", torch.uint8, numel=B * L)
+    _check(ids_restore, "ids_restore", torch.int32, numel=B * L)
+    _check(ids_keep, "ids_keep", torch.int32, numel=B * K, optional=True)
+    _check(target, "target", torch.float32, numel=B * L * D, optional=True)
+    _check(crop_out, "crop_out", torch.int32, numel=B * 6, optional=True)
+    _check(workspace, "workspace", optional=True)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     rc = load().mae_prep_batch(C.byref(desc), _ptr(visible), _ptr(mask), _ptr(ids_restore),
                                _ptr(ids_keep), _ptr(target), _ptr(crop_out), _ptr(workspace),
@@ -262,6 +305,11 @@ def mae_prep_status(workspace, stream=None) -> int:
 def make_loss_desc(pred, target, mask, *, num_masked, eps=1e-6, grad_scale=1.0,
                    norm_pix=True) -> MaeLossDesc:
     """target may be None for mae_normpix_loss_from_images."""
+    _check(pred, "pred", (torch.float32, torch.bfloat16))
+    if pred.dim() != 3:
+        raise ValueError("pred must have shape [B, L, D]")
+    _check(target, "target", torch.float32, numel=pred.numel(), optional=True)
+    _check(mask, "mask", torch.uint8, numel=pred.shape[0] * pred.shape[1])
     d = MaeLossDesc()
     d.B, d.L, d.D = (int(v) for v in pred.shape)
     d.pred, d.target, d.mask = pred.data_ptr(), _ptr(target), mask.data_ptr()
@@ -276,7 +324,14 @@ def mae_loss_workspace_bytes(desc: MaeLossDesc) -> int:
     return int(load().mae_loss_workspace_bytes(C.byref(desc)))
 
 
+def _check_loss_outputs(desc, loss, grad):
+    _check(loss, "loss", torch.float32, numel=1)
+    _check(grad, "grad", torch.bfloat16 if desc.pred_dtype == MAE_BF16 else torch.float32,
+           numel=desc.B * desc.L * desc.D, optional=True)
+
+
 def mae_normpix_loss(desc: MaeLossDesc, loss, grad=None, workspace=None, stream=None) -> None:
+    _check_loss_outputs(desc, loss, grad)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     rc = load().mae_normpix_loss(C.byref(desc), _ptr(loss), _ptr(grad), _ptr(workspace), ws_bytes,
                                  _stream(stream))
@@ -286,6 +341,7 @@ def mae_normpix_loss(desc: MaeLossDesc, loss, grad=None, workspace=None, stream=
 
 def mae_normpix_loss_static(desc: MaeLossDesc, loss, grad=None, stream=None) -> None:
     """mae_normpix_loss without a workspace (the library's own fixed scratch array is used)."""
+    _check_loss_outputs(desc, loss, grad)
     rc = load().mae_normpix_loss_static(C.byref(desc), _ptr(loss), _ptr(grad), _stream(stream))
     if rc != MAE_OK:
         raise MaeError(rc, "mae_normpix_loss_static")
@@ -297,6 +353,8 @@ def mae_loss_from_images_workspace_bytes(prep: MaePrepDesc, desc: MaeLossDesc) -
 
 def mae_normpix_loss_from_images(prep: MaePrepDesc, prep_workspace, desc: MaeLossDesc, loss,
                                  grad=None, workspace=None, stream=None) -> None:
+    _check_loss_outputs(desc, loss, grad)
+    _check(prep_workspace, "prep_workspace")
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     prep_bytes = prep_workspace.numel() * prep_workspace.element_size()
     rc = load().mae_normpix_loss_from_images(C.byref(prep), _ptr(prep_workspace), prep_bytes,
@@ -310,6 +368,16 @@ def make_embed_desc(visible, ids_keep, weight, bias=None, pos=None, *,
                     out_dtype=MAE_BF16) -> MaeEmbedDesc:
     """visible [B, K, D] (or [M, D]) bf16, ids_keep [B, K] int32, weight [E, D] bf16,
     bias [E] float32, pos [L, E] float32."""
+    _check(visible, "visible", torch.bfloat16)
+    _check(weight, "weight", torch.bfloat16)
+    if weight.dim() != 2 or weight.shape[1] != visible.shape[-1]:
+        raise ValueError("weight must have shape [E, D] with D = visible.shape[-1]")
+    rows = visible.numel() // int(visible.shape[-1])
+    _check(ids_keep, "ids_keep", torch.int32, numel=rows, optional=pos is None)
+    _check(bias, "bias", torch.float32, numel=int(weight.shape[0]), optional=True)
+    _check(pos, "pos", torch.float32, optional=True)
+    if pos is not None and (pos.dim() != 2 or pos.shape[1] != weight.shape[0]):
+        raise ValueError("pos must have shape [L, E]")
     d = MaeEmbedDesc()
     d.D, d.E = int(visible.shape[-1]), int(weight.shape[0])
     d.M = visible.numel() // d.D
@@ -321,6 +389,8 @@ def make_embed_desc(visible, ids_keep, weight, bias=None, pos=None, *,
 
 
 def mae_patch_embed(desc: MaeEmbedDesc, tokens, stream=None) -> None:
+    _check(tokens, "tokens", torch.bfloat16 if desc.out_dtype == MAE_BF16 else torch.float32,
+           numel=desc.M * desc.E)
     rc = load().mae_patch_embed(C.byref(desc), _ptr(tokens), _stream(stream))
     if rc != MAE_OK:
         raise MaeError(rc, "mae_patch_embed")
@@ -362,7 +432,10 @@ class ProgressiveBuffers:
     5.3: the resolution and the masking ratio change between stages).  `stage(i)` returns views of
     the same storage shaped for stage i, so a stage switch allocates nothing."""
 
-    def __init__(self, B, patch, stages, device="cuda", bf16=False, want_target=True):
+    def __init__(self, B, patch, stages, device="cuda", bf16=False, want_target=True,
+                 aug_mode=MAE_AUG_SIMPLE, max_image_side=0, jpeg=False):
+        """aug_mode, max_image_side, jpeg: the most demanding values any stage will be called
+        with (they size the workspace)."""
         self.B, self.patch, self.bf16 = B, patch, bf16
         self.shapes = []
         for out_size, mask_ratio in stages:
@@ -380,7 +453,27 @@ class ProgressiveBuffers:
         self._target = (torch.empty(B * max_l * D, dtype=torch.float32, device=device)
                         if want_target else None)
         self._crop = torch.empty((B, 6), dtype=torch.int32, device=device)
-        self._workspace = torch.empty(256 + 32 * B, dtype=torch.uint8, device=device)
+        # the workspace of the most demanding stage, as the library sizes it (the pointers of the
+        # descriptor are not looked at for that)
+        need = 0
+        for out_size, _, num_keep, _ in self.shapes:
+            d = MaePrepDesc()
+            d.B, d.out_size, d.patch, d.num_keep = B, out_size, patch, num_keep
+            d.images = d.offsets = d.heights = d.widths = d.file_sizes = 8
+            d.images_bytes = 1
+            d.scale_lo, d.scale_hi, d.ratio_lo, d.ratio_hi, d.flip_p = 0.2, 1.0, 0.75, 4.0 / 3.0, 0.5
+            d.mean = (C.c_float * 3)(*IMAGENET_MEAN)
+            d.std = (C.c_float * 3)(*IMAGENET_STD)
+            d.noise_bits = 32
+            d.out_dtype = MAE_BF16 if bf16 else MAE_F32
+            d.max_image_side = max_image_side
+            d.aug_mode, d.jitter = aug_mode, 0.3
+            d.input_format = MAE_INPUT_JPEG if jpeg else MAE_INPUT_DECODED
+            size = mae_prep_workspace_bytes(d)
+            if size == 0:
+                raise ValueError(f"stage {out_size}px / keep {num_keep} is not a valid descriptor")
+            need = max(need, size)
+        self._workspace = torch.empty(need, dtype=torch.uint8, device=device)
 
     def stage(self, i) -> PrepBuffers:
         out_size, L, K, D = self.shapes[i]

@@ -95,13 +95,18 @@ int validate_embed(const mae_embed_desc* d) {
   return MAE_OK;
 }
 
+// Whether this process sees a HIP device; asked once (the answer does not change while the
+// process lives) so that the launch paths do not query the runtime on every call.
 int have_device() {
-  int n = 0;
-  if (hipGetDeviceCount(&n) != hipSuccess || n <= 0) {
-    (void)hipGetLastError();  // do not leave a sticky error for the caller's next HIP call
-    return MAE_ERR_NO_DEVICE;
-  }
-  return MAE_OK;
+  static const int status = [] {
+    int n = 0;
+    if (hipGetDeviceCount(&n) != hipSuccess || n <= 0) {
+      (void)hipGetLastError();  // do not leave a sticky error for the caller's next HIP call
+      return (int)MAE_ERR_NO_DEVICE;
+    }
+    return (int)MAE_OK;
+  }();
+  return status;
 }
 
 }  // namespace
@@ -624,15 +629,26 @@ int mae_pretrain_stage(int32_t scheme, int32_t stage, int32_t* host_out_size,
 }
 
 int mae_finetune_stage(int32_t scheme, int32_t stage, int32_t* host_out_size,
-                       float* host_scale_lo, float* host_scale_hi) {
+                       float* host_scale_lo, float* host_scale_hi, int32_t* host_aug_mode) {
   if (!host_out_size || !host_scale_lo || !host_scale_hi) return MAE_ERR_NULL;
-  if ((scheme != 1 && scheme != 3) || stage < 1 || stage > 3) return MAE_ERR_RANGE;
+  const bool known = scheme == MAE_FINETUNE_SCHEME_1 || scheme == MAE_FINETUNE_SCHEME_3 ||
+                     scheme == MAE_FINETUNE_SCHEME_1_MINUS || scheme == MAE_FINETUNE_SCHEME_1_PLUS;
+  if (!known || stage < 1 || stage > 3) return MAE_ERR_RANGE;
   // Table 7: sigma- = 0.28 throughout; scheme 3 raises sigma+ with the resolution
   const double sigma_lo = 0.28;
-  const double sigma_hi = scheme == 1 ? 1.0 : (stage == 1 ? 0.68 : (stage == 2 ? 0.84 : 1.0));
+  double sigma_hi = 1.0;
+  if (scheme == MAE_FINETUNE_SCHEME_3) sigma_hi = stage == 1 ? 0.68 : (stage == 2 ? 0.84 : 1.0);
   *host_out_size = 128 + 32 * stage;  // 160, 192, 224
   *host_scale_lo = (float)(sigma_lo * sigma_lo);
   *host_scale_hi = (float)(sigma_hi * sigma_hi);
+  if (host_aug_mode) {
+    // the table's aug column: schemes 1 and 3 add the colour jitter in the last stage only,
+    // "1-" never, "1+" in every stage
+    int32_t aug = stage == 3 ? MAE_AUG_THREE_PLUS : MAE_AUG_THREE;
+    if (scheme == MAE_FINETUNE_SCHEME_1_MINUS) aug = MAE_AUG_THREE;
+    if (scheme == MAE_FINETUNE_SCHEME_1_PLUS) aug = MAE_AUG_THREE_PLUS;
+    *host_aug_mode = aug;
+  }
   return MAE_OK;
 }
 

@@ -1175,11 +1175,13 @@ hipError_t launch_crop_loss(const CropArgs& a, hipStream_t stream) {
     hipLaunchKernelGGL(crop_loss_wave_kernel, grid, dim3(4 * kWave), crop_lds_bytes(a), stream, a);
   else
     hipLaunchKernelGGL(crop_loss_kernel, grid, dim3(kWave * nv), crop_lds_bytes(a), stream, a);
-  if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return err;
   const int64_t n = (int64_t)grid.x;
   hipLaunchKernelGGL(crop_loss_reduce_kernel, dim3(kLossGroups), dim3(256), 0, stream, a.partials,
                      n, a.partials + n);
-  if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+  err = hipGetLastError();
+  if (err != hipSuccess) return err;
   return launch_loss_finish(a.partials + n, kLossGroups, a.inv_count, a.loss_out, a.counts,
                             a.ncounts, a.D, stream);
 }

@@ -858,7 +858,8 @@ __global__ __launch_bounds__(kColourThreads) void jpeg_colour_kernel(JpegArgs a,
 hipError_t launch_jpeg_decode(const JpegArgs& a, hipStream_t stream) {
   dim3 block(kJpegThreads);
   hipLaunchKernelGGL(jpeg_tables_kernel, dim3((uint32_t)a.B), block, 0, stream, a);
-  if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return err;
   // as many images per wavefront as fill its lanes with rows of MCUs: an image of the largest
   // side allowed has slot_side / 16 rows of them when its luma is sampled 2x2
   const int rows = a.slot_side / 16;
@@ -869,7 +870,8 @@ hipError_t launch_jpeg_decode(const JpegArgs& a, hipStream_t stream) {
     hipLaunchKernelGGL(jpeg_decode_kernel<2>, dim3((B + 1) / 2), block, 0, stream, a);
   else
     hipLaunchKernelGGL(jpeg_decode_kernel<1>, dim3(B), block, 0, stream, a);
-  if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+  err = hipGetLastError();
+  if (err != hipSuccess) return err;
   const int bands = (a.slot_side + kColourBand - 1) / kColourBand;
   hipLaunchKernelGGL(jpeg_colour_kernel, dim3((uint32_t)a.B * (uint32_t)bands),
                      dim3(kColourThreads), 0, stream, a, bands);

@@ -117,3 +117,20 @@ def check_neutral_outputs(buf, b):
     if buf.target is not None:
         assert not buf.target[b].abs().sum().item(), f"sample {b}: target"
     assert not buf.crop[b].any(), f"sample {b}: crop record"
+
+
+def assert_close_device(gpu, ref, atol=ATOL, rtol=RTOL, scale=1.0, what=""):
+    """Element-by-element |gpu - ref| <= atol + rtol |ref| for large tensors: the oracle's values
+    (a NumPy array) are uploaded and the comparison runs on the device in double precision.
+    `scale` multiplies both sides first (gradients are compared in units of 2 / (D M))."""
+    r = torch.from_numpy(np.ascontiguousarray(ref)).to(gpu.device).double() * scale
+    g = gpu.double() * scale
+    assert g.shape == r.shape, (what, tuple(g.shape), tuple(r.shape))
+    err = (g - r).abs()
+    bound = atol + rtol * r.abs()
+    bad = err > bound
+    if bool(bad.any()):
+        i = int(torch.argmax(err - bound).item())
+        raise AssertionError(f"{what}: {int(bad.sum().item())} of {bad.numel()} values out of "
+                             f"tolerance; worst gpu {g.flatten()[i].item()!r} ref "
+                             f"{r.flatten()[i].item()!r} err {err.flatten()[i].item():.3e}")

@@ -334,10 +334,14 @@ def test_progressive_tables_match_the_paper(lib, golden):
         if row[0] == "pretrain":
             assert mae.mae_pretrain_stage(int(row[1]), int(row[2])) == (int(row[3]), float(row[4]))
         elif row[0] == "finetune":
-            res, lo, hi = mae.mae_finetune_stage(int(row[1]), int(row[2]))
+            scheme = {"1": mae.MAE_FINETUNE_SCHEME_1, "3": mae.MAE_FINETUNE_SCHEME_3,
+                      "1-": mae.MAE_FINETUNE_SCHEME_1_MINUS,
+                      "1+": mae.MAE_FINETUNE_SCHEME_1_PLUS}[row[1]]
+            res, lo, hi, aug = mae.mae_finetune_stage(scheme, int(row[2]))
             assert res == int(row[3])
             assert lo == pytest.approx(float(row[4]) ** 2, rel=1e-6)
             assert hi == pytest.approx(float(row[5]) ** 2, rel=1e-6)
+            assert aug == {"3Aug": mae.MAE_AUG_THREE, "3Aug+": mae.MAE_AUG_THREE_PLUS}[row[6]]
         elif row[0] == "lengths":
             lengths = [int(v) for v in row[1:]]
             for epoch in (0, 29, 30, 59, 60, 99, 100, 1000):
@@ -354,3 +358,21 @@ def test_progressive_tables_match_the_paper(lib, golden):
     with pytest.raises(mae.MaeError):
         mae.mae_stage_of_epoch(-1, [1, 2])
     assert mae.mae_stage_of_epoch(0, [0, 0, 5]) == 3
+
+
+def test_binding_rejects_host_tensors_before_any_call():
+    """The library takes raw device pointers: the binding refuses tensors it would misread."""
+    import torch
+
+    img = torch.zeros(100, dtype=torch.uint8)
+    off = torch.zeros(1, dtype=torch.int64)
+    hw = torch.ones(1, dtype=torch.int32)
+    with pytest.raises(ValueError, match="device memory"):
+        mae.make_prep_desc(img, off, hw, hw, out_size=32, patch=16, num_keep=1)
+    with pytest.raises(TypeError, match="torch tensor"):
+        mae.make_prep_desc(img.numpy(), off, hw, hw, out_size=32, patch=16, num_keep=1)
+    pred = torch.zeros(1, 4, 12)
+    with pytest.raises(ValueError, match="device memory"):
+        mae.make_loss_desc(pred, pred, torch.zeros(1, 4, dtype=torch.uint8), num_masked=1)
+    with pytest.raises(ValueError, match="device memory"):
+        mae.make_embed_desc(pred.to(torch.bfloat16), None, pred[0].to(torch.bfloat16))

@@ -9,7 +9,8 @@ import oracle
 import paper_2404_00509_amd as mae
 from paper_2404_00509_amd import synth
 
-from helpers import ATOL, RTOL, check_grad, check_prep_against_oracle, prep_to_numpy, to_device
+from helpers import (ATOL, RTOL, assert_close_device, check_grad, check_prep_against_oracle,
+                     prep_to_numpy, to_device)
 
 pytestmark = pytest.mark.gpu
 
@@ -188,11 +189,16 @@ def test_agrees_with_the_two_call_path_at_full_size():
     assert abs(loss - loss2.item()) <= 1e-6 * abs(loss2.item())
     unit = 2.0 / (wl.D * M)
     assert float((grad - grad2).abs().max().item()) / unit <= 2e-5
-    for b in (0, 1777, 4095):
-        ref = oracle.prep_batch(*data, b_begin=b, b_end=b + 1, **kw)
-        _, ref_grad, _ = oracle.normpix_loss(pred[b:b + 1].cpu().numpy(), ref["target"],
-                                             ref["mask"], num_masked=M)
-        check_grad(grad[b:b + 1].cpu().numpy(), ref_grad, wl.D, M, what=f"c4[{b}]")
+    # every image against the oracle's chain (its prep, then its loss on its own target)
+    oracle_loss = 0.0
+    for lo in range(0, wl.B, 256):
+        hi = min(lo + 256, wl.B)
+        ref = oracle.prep_batch(*data, b_begin=lo, b_end=hi, want_visible=False, **kw)
+        part, ref_grad, _ = oracle.normpix_loss(pred[lo:hi].cpu().numpy(), ref["target"],
+                                                ref["mask"], num_masked=M)
+        oracle_loss += part
+        assert_close_device(grad[lo:hi], ref_grad, scale=1.0 / unit, what=f"c4[{lo}:{hi}] grad")
+    assert abs(loss - oracle_loss) <= ATOL + RTOL * abs(oracle_loss)
 
 
 def test_on_a_side_stream_and_in_a_captured_graph():

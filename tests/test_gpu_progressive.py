@@ -18,10 +18,12 @@ B = 24
 PATCH = 16
 
 
-def _run_stage(dimg, data, bufs, stage_index, out_size, K, seed, batch_index, scale=(0.2, 1.0)):
+def _run_stage(dimg, data, bufs, stage_index, out_size, K, seed, batch_index, scale=(0.2, 1.0),
+               aug_mode=0, jitter=0.3):
     buf = bufs.stage(stage_index)
     desc = mae.make_prep_desc(*dimg, out_size=out_size, patch=PATCH, num_keep=K, scale=scale,
-                              seed=seed, batch_index=batch_index)
+                              seed=seed, batch_index=batch_index, aug_mode=aug_mode, jitter=jitter)
+    assert mae.mae_prep_workspace_bytes(desc) <= buf.workspace.numel()
     for t in (buf.visible, buf.target):
         t.fill_(float("nan"))
     buf.mask.fill_(0xEE)
@@ -31,7 +33,7 @@ def _run_stage(dimg, data, bufs, stage_index, out_size, K, seed, batch_index, sc
     torch.cuda.synchronize()
     assert mae.mae_prep_status(buf.workspace) == 0
     ref = oracle.prep_batch(*data, out_size=out_size, patch=PATCH, num_keep=K, scale=scale,
-                            seed=seed, batch_index=batch_index)
+                            seed=seed, batch_index=batch_index, aug_mode=aug_mode, jitter=jitter)
     check_prep_against_oracle(prep_to_numpy(buf), ref, what=f"stage{stage_index}")
     return buf, ref
 
@@ -87,22 +89,33 @@ def test_pretrain_schemes_switch_stages_without_reallocation(scheme):
     assert torch.cuda.memory_allocated() <= allocated + 4096   # only the 1-element loss tensors
 
 
-@pytest.mark.parametrize("scheme", [1, 3])
-def test_finetune_schemes_change_the_scale_range(scheme):
+@pytest.mark.parametrize("scheme", [mae.MAE_FINETUNE_SCHEME_1, mae.MAE_FINETUNE_SCHEME_3,
+                                    mae.MAE_FINETUNE_SCHEME_1_MINUS,
+                                    mae.MAE_FINETUNE_SCHEME_1_PLUS])
+def test_finetune_schemes_run_with_their_own_scale_range_and_augmentation(scheme):
+    """Table 7 through its stage switches: each stage runs at its resolution, with its crop range
+    and with the augmentation of its aug column, every patch kept, on buffers allocated once."""
     data = synth.make_images("gradient", B, seed=7)
     dimg = to_device(*data)
     plan = [mae.mae_finetune_stage(scheme, s) for s in (1, 2, 3)]
-    for s, (res, lo, hi) in enumerate(plan, start=1):
-        ores, sl, sh = oracle.finetune_stage(scheme, s)
+    for s, (res, lo, hi, aug) in enumerate(plan, start=1):
+        ores, sl, sh, oaug = oracle.finetune_stage(scheme, s)
         assert res == ores and lo == np.float32(sl * sl) and hi == np.float32(sh * sh)
-    bufs = mae.ProgressiveBuffers(B, PATCH, [(res, 0.75) for res, _, _ in plan])
+        assert aug == oaug
+    if scheme == mae.MAE_FINETUNE_SCHEME_1_MINUS:
+        assert [a for _, _, _, a in plan] == [mae.MAE_AUG_THREE] * 3
+    if scheme == mae.MAE_FINETUNE_SCHEME_1_PLUS:
+        assert [a for _, _, _, a in plan] == [mae.MAE_AUG_THREE_PLUS] * 3
+    bufs = mae.ProgressiveBuffers(B, PATCH, [(res, 0.0) for res, _, _, _ in plan],
+                                  aug_mode=mae.MAE_AUG_THREE_PLUS)
     lengths = [30, 30, 40]
     for epoch in (0, 29, 30, 59, 60, 99):
         stage = mae.mae_stage_of_epoch(epoch, lengths)
         assert stage == oracle.stage_of_epoch(epoch, lengths)
-        res, lo, hi = plan[stage - 1]
-        K = mae.mae_num_keep((res // PATCH) ** 2, 0.75)
-        _run_stage(dimg, data, bufs, stage - 1, res, K, seed=5, batch_index=epoch, scale=(lo, hi))
+        res, lo, hi, aug = plan[stage - 1]
+        L = (res // PATCH) ** 2
+        _run_stage(dimg, data, bufs, stage - 1, res, L, seed=5, batch_index=epoch, scale=(lo, hi),
+                   aug_mode=aug, jitter=0.3)
 
 
 @pytest.mark.parametrize("bf16", [False, True])

@@ -576,14 +576,15 @@ def test_progressive_schemes_match_the_printed_tables(golden):
             assert oracle.pretrain_stage(scheme, stage) == (res, m)
             seen += 1
         elif row[0] == "finetune":
-            scheme, stage, res = int(row[1]), int(row[2]), int(row[3])
-            assert oracle.finetune_stage(scheme, stage) == (res, float(row[4]), float(row[5]))
+            scheme, stage, res = oracle.FINETUNE_SCHEMES[row[1]], int(row[2]), int(row[3])
+            aug = {"3Aug": 1, "3Aug+": 2}[row[6]]
+            assert oracle.finetune_stage(scheme, stage) == (res, float(row[4]), float(row[5]), aug)
             seen += 1
         elif row[0] == "lengths":
             lengths = [int(v) for v in row[1:]]
             assert [oracle.stage_of_epoch(e, lengths) for e in (0, 29, 30, 59, 60, 99, 100, 500)] \
                 == [1, 1, 2, 2, 3, 3, 3, 3]
-    assert seen == 24
+    assert seen == 30
     assert oracle.pretrain_stage(0, 1) is None and oracle.pretrain_stage(7, 1) is None
     assert oracle.pretrain_stage(1, 0) is None and oracle.pretrain_stage(1, 4) is None
     assert oracle.finetune_stage(2, 1) is None
