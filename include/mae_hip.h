@@ -88,9 +88,12 @@ typedef enum { MAE_AUG_SIMPLE = 0, MAE_AUG_THREE = 1, MAE_AUG_THREE_PLUS = 2 } m
  *                      as decoding the whole image first.
  * Files the decoder takes: baseline sequential DCT, 8 bits, three components (JFIF YCbCr), luma
  * sampled 1x1 or 2x2 against 1x1 chroma ("4:4:4", "4:2:0"), the two chroma components sharing
- * their tables, ONE RESTART INTERVAL PER ROW OF MCUs (what makes the rows independent; a choice
- * of the dataset writer), at most 64 rows of MCUs, and no side longer than max_image_side rounded
- * up to 16 (in this mode the hint is a limit; 0 = 256).  Any other file makes its sample invalid
+ * their tables, any restart interval or none, and no side longer than max_image_side rounded up
+ * to 16 (in this mode the hint is a limit; 0 = 256).  A file with one restart interval per row
+ * of MCUs (a choice of the dataset writer that costs 0.2 % in size) has independent rows, and
+ * those outside the crop are never touched; in any other file the entropy-coded data above the
+ * crop has to be walked through once (symbol lengths only), which costs about as much again as
+ * the decoding itself.  Any other file makes its sample invalid
  * (valid = 0 in crop_out, counted by mae_prep_status).  A decoder is specified by the standard
  * only up to the accuracy of the inverse DCT, the chroma interpolation and the colour arithmetic;
  * here: 13-bit fixed-point separable inverse DCT (first pass kept with 3 fractional bits, inputs
@@ -169,9 +172,10 @@ int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t
                    size_t workspace_bytes, void* hip_stream);
 
 /* Bytes of workspace mae_prep_batch needs for this descriptor (0 if the descriptor is invalid).
- * A few hundred bytes plus 32 per image; with augmentation also out_size^2 * 3 per image; with
- * MAE_INPUT_JPEG also the decoded planes and the RGB regions, together 6 bytes per pixel of a
- * square of side max_image_side rounded up to 16 (0 = 256), per image. */
+ * A few hundred bytes plus 32 per image; with augmentation also out_size^2 * 3 + 32 per image;
+ * with MAE_INPUT_JPEG also the decoded planes and the RGB regions, together 6 bytes per pixel of
+ * a square of side max_image_side rounded up to 16 (0 = 256), per image (an upper bound: which
+ * part of it a call touches depends on the crops it draws), and about 6 KB of tables per image. */
 size_t mae_prep_workspace_bytes(const mae_prep_desc* d);
 
 /* Waits for `hip_stream`, then stores in *host_invalid_samples how many samples of the last

@@ -142,8 +142,9 @@ struct PrepWorkspace {
   size_t aug_offset, u8_offset, partials_offset, crop_partials_offset, total;
   // crop decode: per-file records, heights, widths, region widths, region offsets, tables, planes, regions
   size_t recs_offset, heights_offset, widths_offset, region_widths_offset, region_offsets_offset,
-      prepared_offset, planes_offset, regions_offset;
+      prepared_offset, row_states_offset, planes_offset, regions_offset;
   int slot_side;
+  int max_rows;  // rows of MCUs (8 pixels at least) of an image that fills a slot
 };
 // Launch plan of the resampling kernel: from the side limit of the decoded-region slots for JPEG
 // input, else from the caller's hint.
@@ -166,6 +167,8 @@ PrepWorkspace prep_workspace(const mae_prep_desc* d) {
   w.total = mae::kWorkspaceHeader + (size_t)d->B * sizeof(mae::CropRec);
   w.recs_offset = w.heights_offset = w.widths_offset = w.region_widths_offset = 0;
   w.region_offsets_offset = w.prepared_offset = w.planes_offset = w.regions_offset = 0;
+  w.row_states_offset = 0;
+  w.max_rows = 0;
   w.slot_side = 0;
   if (d->input_format == MAE_INPUT_JPEG)
     w.slot_side = ((d->max_image_side > 0 ? d->max_image_side : 256) + 15) & ~15;
@@ -190,7 +193,9 @@ PrepWorkspace prep_workspace(const mae_prep_desc* d) {
     w.region_widths_offset = up(w.widths_offset + B * 4);
     w.region_offsets_offset = up(w.region_widths_offset + B * 8);
     w.prepared_offset = up(w.region_offsets_offset + B * 8);
-    w.planes_offset = up(w.prepared_offset + B * mae::jpeg_prepared_bytes());
+    w.max_rows = w.slot_side / 8;
+    w.row_states_offset = up(w.prepared_offset + B * mae::jpeg_prepared_bytes());
+    w.planes_offset = up(w.row_states_offset + B * w.max_rows * mae::jpeg_row_state_bytes());
     w.regions_offset = up(w.planes_offset + B * (size_t)w.slot_side * w.slot_side * 3);
     w.total = w.regions_offset + B * (size_t)w.slot_side * w.slot_side * 3;
   }
@@ -290,6 +295,8 @@ int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t
     ja.region_offsets = reinterpret_cast<int64_t*>(ws + wsl.region_offsets_offset);
     ja.region_widths = reinterpret_cast<int32_t*>(ws + wsl.region_widths_offset);
     ja.prepared = ws + wsl.prepared_offset;
+    ja.row_states = ws + wsl.row_states_offset;
+    ja.max_rows = wsl.max_rows;
     ja.planes = ws + wsl.planes_offset;
     ja.regions = ws + wsl.regions_offset;
     ja.workspace = ws;

@@ -1,10 +1,12 @@
 // Crop decode (Sec. 4.1 "Crop Decode"): the loader's images are JPEG files, and only the region
 // that the random crop needs is decoded.  Baseline sequential DCT (ITU-T T.81), 8 bits, three
 // components (JFIF YCbCr), luma sampled 1x1 or 2x2 against 1x1 chroma, tables as found in the file,
-// and one restart interval per row of MCUs -- the dataset writer's choice, which is what makes the
-// rows independent: the rows of MCUs above and below the crop are never touched, a row is entropy-
-// decoded only up to the crop's right edge, and the inverse transform runs only for the MCUs
-// inside it.
+// any restart interval.  The rows of MCUs above and below the crop are not transformed, a row is
+// entropy-decoded only up to the crop's right edge, and the inverse transform runs only for the
+// MCUs inside it.  With one restart interval per row of MCUs (a choice of the dataset writer) the
+// rows are independent and those outside the crop are never touched; in any other file the
+// entropy-coded data is one chain, and a first kernel walks it (symbol lengths only) down to the
+// crop's last row to find where each row starts.
 //
 //  * jpeg_header_kernel: one lane per file walks the marker segments and leaves a record (size,
 //    sampling, restart interval, where the tables and the entropy-coded data start) plus the
@@ -12,8 +14,13 @@
 //  * jpeg_tables_kernel: one wavefront per image builds what the decoder needs and leaves it in
 //    the workspace: the Huffman tables (the code ranges of Annex C plus a direct table for codes
 //    of up to 10 bits), the quantiser steps in zig-zag order, the crop's rows and columns of
-//    MCUs, and the restart markers (16 bytes per lane and step, positions ranked with a prefix
-//    sum).  The crop record is rewritten relative to the decoded region.
+//    MCUs, and, for files with a restart interval per row, the restart markers (16 bytes per lane
+//    and step, positions ranked with a prefix sum) = the states at which the rows start.  The
+//    crop record is rewritten relative to the decoded region.
+//  * jpeg_scan_kernel (other files): one lane per file, eight files per wavefront with their
+//    tables in LDS, decodes code lengths and DC differences only, handles restart markers where
+//    they come, and records the state of the bit reader and the DC predictors at the start of
+//    each of the crop's rows of MCUs.
 //  * jpeg_decode_kernel: one wavefront per group of four images, their tables copied into LDS;
 //    the rows of MCUs that the crops touch are dealt to the lanes, one row per lane.  A lane's
 //    file bytes come through its column of a ring in LDS that is fed at the start of every
@@ -168,9 +175,8 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_header_kernel(JpegArgs a) {
     const int mcu = 8 * rec.hs;
     rec.mcux = (W + mcu - 1) / mcu;
     rec.mcuy = (H + mcu - 1) / mcu;
-    // rows must be independent, and the image has to fit its slot of the region buffer
-    ok = rec.restart == rec.mcux && rec.mcuy <= kJpegThreads && rec.mcux * mcu <= a.slot_side &&
-         rec.mcuy * mcu <= a.slot_side;
+    // the image has to fit its slot of the region buffer
+    ok = rec.mcux * mcu <= a.slot_side && rec.mcuy * mcu <= a.slot_side;
   }
   if (!ok) {
     H = 1;
@@ -354,6 +360,22 @@ __device__ static inline void fill_bytewise(BitReader& r) {
     r.nbits += 8;
   }
 }
+// At a restart boundary: what is left of the interval (the padding of its last byte, fill bytes)
+// is dropped, the marker skipped and the reader opened behind it.  Returns false when no restart
+// marker follows within a few bytes.
+__device__ static inline bool restart_reader(BitReader& r) {
+  int p = r.pos;  // the reader never loads a marker: it is at or behind this byte
+  bool found = false;
+  for (int i = 0; i < 16 && !found; ++i) {
+    if (p + 1 >= r.n) break;
+    if (file_byte(r, p) == 0xFFu && (file_byte(r, p + 1) & 0xF8u) == 0xD0u) found = true;
+    else ++p;
+  }
+  r.ended = !found;
+  open_reader(r, found ? p + 2 : r.pos);
+  return found;
+}
+
 // The next 32 bits (after fill()), the oldest on top.
 __device__ static inline uint32_t peek32(const BitReader& r) {
   return (uint32_t)(r.acc >> (r.nbits - 32));
@@ -461,15 +483,27 @@ struct JpegImage {
   HuffAc ac[2];
   uint16_t qz[2][64];  // per zig-zag position: natural position << 8 | quantiser step
   int my0, mx0, mx1, nrows, region_w, hs, size, scan_off, live;
+  int restart, mcux;  // restart interval in MCUs (0 = none), MCUs per row of the image
   int64_t origin, region_off;
 };
 
 // What the table kernel hands to the decode kernel per image (through the workspace).
 struct alignas(16) JpegPrepared {
   JpegImage im;
-  int row_start[kJpegThreads];  // first byte of each of the crop's rows of MCUs, -1 = not found
 };
 static_assert(sizeof(JpegPrepared) % 16 == 0, "copied in 16-byte pieces");
+
+// Where the entropy-coded data of one of the crop's rows of MCUs starts: the bit reader's state
+// and the DC predictors at that point (workspace; max_rows of them per image).
+struct alignas(16) RowState {
+  int32_t pos;        // next byte of the file that goes into the bit buffer; -1 = not known
+  int32_t nbits;      // unread bits in acc
+  uint64_t acc;
+  int16_t pred[3];    // Y, Cb, Cr
+  uint16_t rst_left;  // MCUs from here to the next restart marker (unused without an interval)
+  int32_t pad;
+};
+static_assert(sizeof(RowState) == 32, "32 bytes per row");
 
 template <int kGroup>
 struct JpegLds {
@@ -480,13 +514,12 @@ struct JpegLds {
 };
 
 // Tables, crop geometry and restart-marker positions of image b into slot `im` (whole wavefront).
-__device__ static void jpeg_prepare_image(const JpegArgs& a, int b, JpegImage& im,
-                                          int* row_start) {
+__device__ static void jpeg_prepare_image(const JpegArgs& a, int b, JpegImage& im) {
   const int lane = threadIdx.x;
   const JpegRec rec = a.recs[b];
   CropRec* crop = reinterpret_cast<CropRec*>(a.workspace + kWorkspaceHeader) + b;
   const CropRec cr = *crop;
-  row_start[lane] = -1;
+  RowState* states = reinterpret_cast<RowState*>(a.row_states) + (int64_t)b * a.max_rows;
   __syncthreads();  // everybody has read the record before lane 0 rewrites it
   if (!rec.valid) {
     if (lane == 0) {
@@ -519,6 +552,8 @@ __device__ static void jpeg_prepare_image(const JpegArgs& a, int b, JpegImage& i
     im.hs = rec.hs;
     im.size = n;
     im.scan_off = rec.scan_off;
+    im.restart = rec.restart;
+    im.mcux = rec.mcux;
     im.live = 1;
     im.origin = a.offsets[b];
     im.region_off = a.region_offsets[b];
@@ -574,9 +609,30 @@ __device__ static void jpeg_prepare_image(const JpegArgs& a, int b, JpegImage& i
     }
   }
 
+  // the rows' states: unknown until found below or by the scan kernel
+  {
+    RowState none;
+    none.pos = -1;
+    none.nbits = 0;
+    none.acc = 0;
+    none.pred[0] = none.pred[1] = none.pred[2] = 0;
+    none.rst_left = 0;
+    none.pad = 0;
+    const int nrows = min(my1 - my0 + 1, a.max_rows);
+    for (int i = lane; i < nrows; i += kJpegThreads) states[i] = none;
+  }
+  __syncthreads();  // (these stores are complete before a row's real state is written)
+  if (rec.restart != rec.mcux) return;  // rows not independent: the scan kernel finds the states
+
   // restart markers: marker m (0-based) ends MCU row m; row r starts after marker r - 1.  The
   // file is scanned in aligned 16-byte pieces of the buffer, one per lane and step, the next
   // step's pieces loaded while this step's are examined.
+  RowState start;
+  start.nbits = 0;
+  start.acc = 0;
+  start.pred[0] = start.pred[1] = start.pred[2] = 0;
+  start.rst_left = (uint16_t)rec.restart;
+  start.pad = 0;
   const int64_t origin = a.offsets[b];
   const int64_t first = (origin + rec.scan_off) & ~(int64_t)15;
   const int64_t last = origin + n - 1;  // a marker starts before this byte
@@ -612,12 +668,18 @@ __device__ static void jpeg_prepare_image(const JpegArgs& a, int b, JpegImage& i
       if (!((mask >> i) & 1u)) continue;
       // the row that starts after this marker
       const int row = seen + before + __popc(mask & ((1u << i) - 1u)) + 1;
-      if (row >= my0 && row <= my1) row_start[row - my0] = p0 + i + 2;
+      if (row >= my0 && row <= my1 && row - my0 < a.max_rows) {
+        start.pos = p0 + i + 2;
+        states[row - my0] = start;
+      }
     }
     seen += total;
     cur = next;
   }
-  if (my0 == 0 && lane == 0) row_start[0] = rec.scan_off;
+  if (my0 == 0 && lane == 0) {
+    start.pos = rec.scan_off;
+    states[0] = start;
+  }
 }
 
 // One wavefront per image: tables, crop geometry, row starts -> workspace.  Many of these fit a
@@ -629,11 +691,195 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_tables_kernel(JpegArgs a) {
   for (int i = threadIdx.x; i < (int)(sizeof(JpegPrepared) / 16); i += kJpegThreads)
     reinterpret_cast<u32x4*>(&p)[i] = u32x4{0u, 0u, 0u, 0u};
   __syncthreads();
-  jpeg_prepare_image(a, b, p.im, p.row_start);
+  jpeg_prepare_image(a, b, p.im);
   __syncthreads();
   u32x4* dst = reinterpret_cast<u32x4*>(a.prepared + (size_t)b * sizeof(JpegPrepared));
   for (int i = threadIdx.x; i < (int)(sizeof(JpegPrepared) / 16); i += kJpegThreads)
     dst[i] = reinterpret_cast<const u32x4*>(&p)[i];
+}
+
+// DC difference of the next block (T.81 F.2.2.1).  Returns false for a code that does not exist
+// or a category that 8-bit data does not have (the difference is then 0).
+__device__ static inline bool decode_dc(BitReader& r, const HuffDc& h, int& diff) {
+  fill(r);
+  const uint32_t top = peek32(r);
+  const uint32_t x = top >> 16;
+  int index;
+  int len = find_code<0>(h.range, x, index);
+  int sym = 16;
+  if (len < 16) sym = h.symbols[index & 15];
+  const bool ok = sym <= 11;
+  if (!ok) {
+    sym = 0;
+    len = -1;
+  }
+  diff = sym ? value_bits(top, len + 1, sym) : 0;
+  r.nbits -= len + 1 + sym;
+  return ok;
+}
+
+// AC coefficients of a block (F.2.2.2): a symbol is a run of zeros << 4 | size of the value.  The
+// usual step -- short code, and the next four bytes ready if the buffer has to be topped up -- is
+// straight-line code; everything else takes the one branch.  kStore: de-quantised values go to
+// the lane's column of `coef` (natural order; row 64 takes what is skipped); otherwise only the
+// symbols' lengths are followed.  Returns false for a code that does not exist or a run past the
+// end of the block.
+template <bool kStore>
+__device__ static inline bool decode_ac(BitReader& r, const HuffAc& h, const uint16_t* qz,
+                                        int16_t* coef, bool want) {
+  bool ok = true;
+  fill(r);
+  for (int k = 1; k < 64;) {
+    const NextFour ahead = next_four(r);  // in flight while the symbol is looked up
+    const uint32_t top = peek32(r);
+    const int e = h.fast[top >> (32 - kFastBits)];
+    int len1 = e >> 8, rs = e & 255;
+    const bool top_up = r.nbits - (len1 + (rs & 15)) <= 32;
+    if ((int)(e == 0) | ((int)top_up & (int)!ahead.usable)) {
+      if (!e) {
+        int index;
+        const int len = find_code<kFastBits>(h.range, top >> 16, index);
+        rs = h.symbols[index & 255];
+        len1 = len + 1;
+        if (len == 16) {  // no such code: flag the sample and end the block
+          ok = false;
+          rs = 0;
+          len1 = 0;
+        }
+      }
+      r.nbits -= len1 + (rs & 15);
+      fill(r, ahead);
+    } else {
+      r.nbits -= len1 + (rs & 15) - (top_up ? 32 : 0);
+      r.acc = top_up ? (r.acc << 32) | (uint64_t)ahead.bits : r.acc;
+      r.pos += top_up ? 4 : 0;
+    }
+    const int run = rs >> 4, size = rs & 15;
+    // size 0: sixteen zeros (run 15) or the end of the block
+    k += size ? run : (run == 15 ? 16 : 64);
+    ok = ok && !(size != 0 && k > 63);
+    if (kStore) {  // no branch: what is not to be stored goes to the spare row 64
+      const bool store = size != 0 && k <= 63;
+      const int zq = qz[k & 63];
+      coef[(store && want ? zq >> 8 : 64) * kJpegThreads] = (int16_t)min(
+          max(value_bits(top, len1, size ? size : 1) * (zq & 255), -32767), 32767);
+    }
+    k += size ? 1 : 0;
+  }
+  return ok;
+}
+
+__device__ static inline void reader_for(BitReader& r, const JpegArgs& a, const JpegImage& im,
+                                         uint32_t* ring) {
+  r.skew = (int)(im.origin & 7);
+  r.chunks = a.files + (im.origin - r.skew);
+  r.chunks_bytes = a.files_bytes - (im.origin - r.skew);
+  r.ring = ring;
+  r.n = im.size;
+}
+// Opens the reader in the state recorded for a row.
+__device__ static inline void open_at(BitReader& r, const RowState& st) {
+  open_reader(r, st.pos);
+  r.acc = st.acc;
+  r.nbits = st.nbits;
+}
+
+// ---- files whose rows of MCUs are not independent: where does each of the crop's rows start? ----
+// One lane per file, kScanImages files per wavefront (their tables fill the LDS).  The lane walks
+// the entropy-coded data from its start: per block the DC difference (the predictors run through
+// the whole interval) and the lengths of the AC symbols; at every restart boundary the marker is
+// skipped and the predictors cleared.  At the first MCU of each of the crop's rows the reader's
+// state goes to the workspace.  The walk ends with the crop's last row.
+constexpr int kScanImages = 8;
+struct JpegScanLds {
+  JpegPrepared img[kScanImages];
+  uint32_t ring[kRingBytes / 4][kJpegThreads];
+};
+
+__global__ __launch_bounds__(kJpegThreads) void jpeg_scan_kernel(JpegArgs a) {
+  __shared__ JpegScanLds s;
+  const int lane = threadIdx.x;
+  const int b0 = (int)blockIdx.x * kScanImages;
+  const int nimg = min(kScanImages, a.B - b0);
+  bool need = false;
+  if (lane < nimg) {
+    const JpegRec rec = a.recs[b0 + lane];
+    const CropRec cr = reinterpret_cast<const CropRec*>(a.workspace + kWorkspaceHeader)[b0 + lane];
+    need = rec.valid && cr.valid && rec.restart != rec.mcux;
+  }
+  if (__builtin_amdgcn_ballot_w64(need) == 0) return;  // every file here has independent rows
+  {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4* src = reinterpret_cast<const u32x4*>(a.prepared + (size_t)b0 * sizeof(JpegPrepared));
+    u32x4* dst = reinterpret_cast<u32x4*>(&s.img[0]);
+    const int n16 = nimg * (int)(sizeof(JpegPrepared) / 16);
+    for (int i = lane; i < n16; i += kJpegThreads) dst[i] = src[i];
+  }
+  __syncthreads();
+  if (!need) return;  // (no barrier below)
+
+  const JpegImage& im = s.img[lane].im;
+  const int b = b0 + lane;
+  RowState* states = reinterpret_cast<RowState*>(a.row_states) + (int64_t)b * a.max_rows;
+  BitReader r;
+  reader_for(r, a, im, &s.ring[0][lane]);
+  r.ended = false;
+  open_reader(r, im.scan_off);
+  const int nblk = im.hs * im.hs, per_mcu = nblk + 2;
+  const int rows = im.my0 + im.nrows;  // rows of MCUs down to the crop's last
+  const int mcux = im.mcux, interval = im.restart;
+  int pred[3] = {0, 0, 0};
+  int rst_left = interval;
+  bool bad = false;
+  // one block per iteration (every lane is at the start of a block here); the bounds do not
+  // depend on the data
+  int row = 0, mx = 0, blk = 0;
+  const int64_t blocks = (int64_t)rows * mcux * per_mcu;
+  for (int64_t it = 0; it < blocks; ++it) {
+    if (blk == 0) {  // first block of an MCU
+      if (interval) {
+        if (rst_left == 0) {
+          bad = bad || !restart_reader(r);
+          pred[0] = pred[1] = pred[2] = 0;
+          rst_left = interval;
+        }
+      }
+      if (mx == 0 && row >= im.my0 && row - im.my0 < a.max_rows) {
+        RowState st;
+        st.pos = r.pos;
+        st.nbits = r.nbits;
+        st.acc = r.acc;
+        st.pred[0] = (int16_t)pred[0];
+        st.pred[1] = (int16_t)pred[1];
+        st.pred[2] = (int16_t)pred[2];
+        st.rst_left = (uint16_t)rst_left;
+        st.pad = 0;
+        if (r.ended) st.pos = -1;  // the data ended before this row
+        states[row - im.my0] = st;
+      }
+      rst_left -= interval ? 1 : 0;
+    }
+    const int c = blk < nblk ? 0 : blk - nblk + 1;  // component
+    const int t = c ? 1 : 0;                        // table set
+    feed_ring(r);
+    int diff;
+    bad = bad || !decode_dc(r, im.dc[t], diff);
+    pred[0] += c == 0 ? diff : 0;
+    pred[1] += c == 1 ? diff : 0;
+    pred[2] += c == 2 ? diff : 0;
+    bad = bad || !decode_ac<false>(r, im.ac[t], nullptr, nullptr, false);
+    if (++blk == per_mcu) {
+      blk = 0;
+      if (++mx == mcux) {
+        mx = 0;
+        ++row;
+      }
+    }
+  }
+  if (bad) {
+    reinterpret_cast<CropRec*>(a.workspace + kWorkspaceHeader)[b].valid = 0;
+    if (a.crop_out) a.crop_out[(int64_t)b * 6 + 5] = 0;
+  }
 }
 
 template <int kGroup>
@@ -642,7 +888,7 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
   const int lane = threadIdx.x;
   const int b0 = (int)blockIdx.x * kGroup;
   const int nimg = min(kGroup, a.B - b0);
-  {  // the images' tables and row starts, as the table kernel left them
+  {  // the images' tables, as the table kernel left them
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     const u32x4* src = reinterpret_cast<const u32x4*>(a.prepared + (size_t)b0 * sizeof(JpegPrepared));
     u32x4* dst = reinterpret_cast<u32x4*>(&s.img[0]);
@@ -656,13 +902,11 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
   first_task[0] = 0;
 #pragma unroll
   for (int i = 0; i < kGroup; ++i)
-    first_task[i + 1] = first_task[i] + (i < nimg ? s.img[i].im.nrows : 0);
+    first_task[i + 1] = first_task[i] + (i < nimg ? min(s.img[i].im.nrows, a.max_rows) : 0);
   const int ntasks = first_task[kGroup];
   int16_t* coef = &s.coef[0][lane];  // element k at coef[k * 64]
 #pragma unroll 1
-  for (int it = 0; it < kGroup; ++it) {
-    const int task = lane + it * kJpegThreads;
-    if (task >= ntasks) break;
+  for (int task = lane; task < ntasks; task += kJpegThreads) {
     int slot = 0, slot_first = 0;
 #pragma unroll
     for (int i = 1; i < kGroup; ++i) {
@@ -672,9 +916,10 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
       }
     }
     const int row = task - slot_first;  // row of MCUs inside the crop's range
-    const int start = s.img[slot].row_start[row & (kJpegThreads - 1)];
     const JpegImage& im = s.img[slot].im;
     const int b = b0 + slot;
+    const RowState st = (reinterpret_cast<const RowState*>(a.row_states) +
+                         (int64_t)b * a.max_rows)[row];
     const int hs = im.hs, mcu = 8 * hs;
     const int mx0 = im.mx0, mx1 = im.mx1, region_w = im.region_w;
     // the image's slot of the plane buffer: Y (region_w wide), then Cb and Cr (region_w / hs wide)
@@ -682,19 +927,29 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
     uint8_t* plane_y = a.planes + im.region_off;
     uint8_t* plane_cb = plane_y + (int64_t)im.nrows * mcu * region_w;
     uint8_t* plane_cr = plane_cb + (int64_t)im.nrows * 8 * chroma_w;
-    const bool found = start >= im.scan_off && start <= im.size;
+    const bool found = st.pos >= im.scan_off && st.pos <= im.size;
     BitReader r;
-    r.skew = (int)(im.origin & 7);
-    r.chunks = a.files + (im.origin - r.skew);
-    r.chunks_bytes = a.files_bytes - (im.origin - r.skew);
-    r.ring = &s.ring[0][lane];
-    r.n = im.size;
-    r.ended = !found;  // marker missing: zero bits, and the sample is flagged below
-    open_reader(r, found ? start : im.scan_off);
-    int pred_y = 0, pred_cb = 0, pred_cr = 0;
+    reader_for(r, a, im, &s.ring[0][lane]);
+    r.ended = !found;  // start unknown: zero bits, and the sample is flagged below
+    if (found) {
+      open_at(r, st);
+    } else {
+      open_reader(r, im.scan_off);
+    }
+    int pred_y = st.pred[0], pred_cb = st.pred[1], pred_cr = st.pred[2];
+    const int interval = im.restart;
+    int rst_left = st.rst_left;
     const int nblk = hs * hs;  // luma blocks per MCU
     bool bad = !found;
     for (int mx = 0; mx <= mx1; ++mx) {
+      if (interval) {  // a restart boundary inside the row
+        if (mx > 0 && rst_left == 0) {
+          bad = bad || !restart_reader(r);
+          pred_y = pred_cb = pred_cr = 0;
+          rst_left = interval;
+        }
+        --rst_left;
+      }
       const bool want = mx >= mx0;
       const int x0 = (mx - mx0) * mcu, y0 = row * mcu;
       for (int blk = 0; blk < nblk + 2; ++blk) {
@@ -703,71 +958,15 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
         if (want)
           for (int i = 0; i < 64; ++i) coef[i * kJpegThreads] = 0;
         feed_ring(r);
-        {  // DC difference (T.81 F.2.2.1)
-          const HuffDc& h = im.dc[t];
-          fill(r);
-          const uint32_t top = peek32(r);
-          const uint32_t x = top >> 16;
-          int index;
-          int len = find_code<0>(h.range, x, index);
-          int sym = 16;
-          if (len < 16) sym = h.symbols[index & 15];
-          if (sym > 11) {  // no such code, or not a category of 8-bit data
-            bad = true;
-            sym = 0;
-            len = -1;
-          }
-          const int diff = sym ? value_bits(top, len + 1, sym) : 0;
-          r.nbits -= len + 1 + sym;
-          pred_y += c == 0 ? diff : 0;
-          pred_cb += c == 1 ? diff : 0;
-          pred_cr += c == 2 ? diff : 0;
-        }
+        int diff;
+        bad = bad || !decode_dc(r, im.dc[t], diff);
+        pred_y += c == 0 ? diff : 0;
+        pred_cb += c == 1 ? diff : 0;
+        pred_cr += c == 2 ? diff : 0;
         const int dcv = c == 0 ? pred_y : (c == 1 ? pred_cb : pred_cr);
         const uint16_t* qz = im.qz[t];
         if (want) coef[0] = (int16_t)min(max(dcv * (int)(qz[0] & 255), -32767), 32767);
-        const HuffAc& h = im.ac[t];
-        fill(r);
-        // AC coefficients (F.2.2.2): a symbol is a run of zeros << 4 | size of the value.  The
-        // usual step -- short code, and the next four bytes ready if the buffer has to be topped
-        // up -- is straight-line code; everything else takes the one branch.
-        for (int k = 1; k < 64;) {
-          const NextFour ahead = next_four(r);  // in flight while the symbol is looked up
-          const uint32_t top = peek32(r);
-          const int e = h.fast[top >> (32 - kFastBits)];
-          int len1 = e >> 8, rs = e & 255;
-          const bool top_up = r.nbits - (len1 + (rs & 15)) <= 32;
-          if ((int)(e == 0) | ((int)top_up & (int)!ahead.usable)) {
-            if (!e) {
-              int index;
-              const int len = find_code<kFastBits>(h.range, top >> 16, index);
-              rs = h.symbols[index & 255];
-              len1 = len + 1;
-              if (len == 16) {  // no such code: flag the sample and end the block
-                bad = true;
-                rs = 0;
-                len1 = 0;
-              }
-            }
-            r.nbits -= len1 + (rs & 15);
-            fill(r, ahead);
-          } else {
-            r.nbits -= len1 + (rs & 15) - (top_up ? 32 : 0);
-            r.acc = top_up ? (r.acc << 32) | (uint64_t)ahead.bits : r.acc;
-            r.pos += top_up ? 4 : 0;
-          }
-          const int run = rs >> 4, size = rs & 15;
-          // size 0: sixteen zeros (run 15) or the end of the block
-          k += size ? run : (run == 15 ? 16 : 64);
-          const bool store = size != 0 && k <= 63;
-          bad = bad || (size != 0 && k > 63);
-          {  // no branch: what is not to be stored goes to the spare row 64
-            const int zq = qz[k & 63];
-            coef[(store && want ? zq >> 8 : 64) * kJpegThreads] = (int16_t)min(
-                max(value_bits(top, len1, size ? size : 1) * (zq & 255), -32767), 32767);
-          }
-          k += size ? 1 : 0;
-        }
+        bad = bad || !decode_ac<true>(r, im.ac[t], qz, coef, want);
         if (!want) continue;
         idct_columns(coef);
         // the block's rows, eight samples = one 8-byte store each (rows of every plane start on
@@ -800,6 +999,7 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_decode_kernel(JpegArgs a) {
 }
 
 size_t jpeg_prepared_bytes() { return sizeof(JpegPrepared); }
+size_t jpeg_row_state_bytes() { return sizeof(RowState); }
 
 hipError_t launch_jpeg_header(const JpegArgs& a, hipStream_t stream) {
   dim3 grid((uint32_t)((a.B + kJpegThreads - 1) / kJpegThreads)), block(kJpegThreads);
@@ -859,6 +1059,11 @@ hipError_t launch_jpeg_decode(const JpegArgs& a, hipStream_t stream) {
   dim3 block(kJpegThreads);
   hipLaunchKernelGGL(jpeg_tables_kernel, dim3((uint32_t)a.B), block, 0, stream, a);
   hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  // files whose rows are not independent (its wavefronts leave at once where there are none)
+  hipLaunchKernelGGL(jpeg_scan_kernel, dim3((uint32_t)((a.B + kScanImages - 1) / kScanImages)),
+                     block, 0, stream, a);
+  err = hipGetLastError();
   if (err != hipSuccess) return err;
   // as many images per wavefront as fill its lanes with rows of MCUs: an image of the largest
   // side allowed has slot_side / 16 rows of them when its luma is sampled 2x2

@@ -143,13 +143,16 @@ struct JpegArgs {
   int32_t* widths;
   int64_t* region_offsets;
   int32_t* region_widths;
-  uint8_t* prepared; // per image: Huffman and quantiser tables, crop geometry, row starts
+  uint8_t* prepared; // per image: Huffman and quantiser tables, crop geometry
+  uint8_t* row_states;  // per image max_rows records of 32 bytes: where the crop's rows start
+  int32_t max_rows;     // rows of MCUs an image of the largest side allowed can have
   uint8_t* planes;   // decoded Y, Cb, Cr planes, one slot per image like `regions`
   uint8_t* regions;
   uint8_t* workspace;  // header + CropRec[B]
   int32_t* crop_out;   // nullable, [B,6]: the valid flag is cleared for files that cannot be used
 };
 size_t jpeg_prepared_bytes();  // per image, in the workspace
+size_t jpeg_row_state_bytes();  // per row of MCUs, in the workspace
 hipError_t launch_jpeg_header(const JpegArgs& a, hipStream_t stream);
 hipError_t launch_jpeg_decode(const JpegArgs& a, hipStream_t stream);
 

@@ -144,11 +144,12 @@ def make_ids(seed: int, M: int, L: int) -> np.ndarray:
 
 
 def make_jpegs(kind: str, B: int, seed: int = 0, quality: int = 90, subsampling: str = "4:2:0",
-               restart_rows: int = 1, optimize: bool = False):
+               restart_rows: int = 1, optimize: bool = False, restart_blocks: int = 0):
     """The images of make_images(kind, B, seed) as baseline JPEG files (Sec. 4.1: the dataset is
     stored as JPEG at a chosen quality, 90 in the headline configuration), written by the imaging
-    library with one restart interval per row of MCUs.  Returns (files, offsets, sizes): the
-    concatenated bytes [sum] uint8, byte offsets [B] int64 and lengths [B] int32."""
+    library with one restart interval per `restart_rows` rows of MCUs (0: no restart markers, what
+    an encoder writes by default) or per `restart_blocks` MCUs.  Returns (files, offsets, sizes):
+    the concatenated bytes [sum] uint8, byte offsets [B] int64 and lengths [B] int32."""
     import io
 
     from PIL import Image
@@ -158,6 +159,8 @@ def make_jpegs(kind: str, B: int, seed: int = 0, quality: int = 90, subsampling:
     for b in range(B):
         buf = io.BytesIO()
         kw = {} if restart_rows <= 0 else {"restart_marker_rows": restart_rows}
+        if restart_blocks > 0:
+            kw = {"restart_marker_blocks": restart_blocks}
         Image.fromarray(image_view(images, offs, hs, ws, b)).save(
             buf, format="JPEG", quality=quality, subsampling=subsampling, optimize=optimize, **kw)
         chunks.append(np.frombuffer(buf.getvalue(), np.uint8))

@@ -158,12 +158,14 @@ def test_jpeg_input_needs_no_sizes_and_a_slot_per_image(lib):
     max_image_side rounded up to 16 (256 when the caller gives none)."""
     up = lambda v: (v + 255) & ~255
     B = 4
-    tables = 256 + B * 32
-    # file records, heights, widths, region widths, offsets, decoding tables (5728 bytes per image)
-    for step in (B * 64, B * 4, B * 4, B * 4, B * 8, B * 5728):
-        tables = up(tables) + step
+    head = 256 + B * 32
+    # file records, heights, widths, region widths, offsets, decoding tables (5488 bytes per image)
+    for step in (B * 64, B * 4, B * 4, B * 4, B * 8, B * 5488):
+        head = up(head) + step
     for side, slot in ((0, 256), (500, 512), (512, 512), (513, 528)):
         d = _jpeg_desc(max_image_side=side)
+        # ... the states at which the crop's rows of MCUs start: 32 bytes per 8 pixels of the side
+        tables = up(head) + B * (slot // 8) * 32
         want = up(up(tables) + B * slot * slot * 3) + B * slot * slot * 3
         assert lib.mae_prep_workspace_bytes(C.byref(d)) == want
         assert _call_prep(lib, d, ws_bytes=want - 1) == binding.MAE_ERR_WORKSPACE

@@ -95,41 +95,94 @@ def test_tables_of_the_file_and_other_qualities(quality, optimize):
     check_prep_against_oracle(prep_to_numpy(buf), ref, what=f"quality {quality}")
 
 
-def test_image_shapes_at_the_limits():
-    """64 rows of MCUs (the most a file may have) in both samplings, a row of 63 MCUs, images
-    smaller than one MCU and with ragged edges; one row of MCUs too many is flagged.  Several
-    lanes get more than one row here (the group's rows exceed the wavefront)."""
+@pytest.mark.parametrize("rows,blocks", [(0, 0), (2, 0), (0, 3), (0, 1), (3, 0)])
+@pytest.mark.parametrize("sub", ["4:2:0", "4:4:4"])
+def test_files_whose_rows_are_not_independent(rows, blocks, sub):
+    """No restart markers at all (what an encoder writes by default), a restart interval of several
+    rows of MCUs, and intervals of a few MCUs that end inside rows: the bytes decoded are the
+    oracle's, so every output matches to the path's tolerance."""
+    B, S = 14, 96
+    kind = "uniform" if blocks == 1 else "gradient"
+    files, offsets, sizes = synth.make_jpegs(kind, B, seed=66, subsampling=sub,
+                                             restart_rows=rows, restart_blocks=blocks)
+    decoded = _decode_all(files, offsets, sizes)
+    L = (S // 16) ** 2
+    for scale in ((0.2, 1.0), (1.0, 1.0), (0.02, 0.06)):
+        kw = dict(out_size=S, patch=16, num_keep=oracle.num_keep(L, 0.75), scale=scale, seed=19,
+                  batch_index=6)
+        ref = oracle.prep_batch(*decoded, **kw)
+        buf, _ = _gpu_jpeg_prep(files, offsets, sizes, **kw)
+        assert mae.mae_prep_status(buf.workspace) == 0
+        check_prep_against_oracle(prep_to_numpy(buf), ref,
+                                  what=f"restart rows {rows} blocks {blocks} {sub} scale {scale}")
+
+
+def test_a_batch_that_mixes_how_its_files_are_organised():
     import io
 
     from PIL import Image
-    shapes = [(512, 72, "4:4:4"), (1024, 48, "4:2:0"), (48, 1000, "4:2:0"), (8, 8, "4:4:4"),
-              (5, 7, "4:2:0"), (17, 23, "4:2:0"), (505, 131, "4:4:4"), (520, 64, "4:4:4")]
+    B, S = 12, 112
+    imgs = synth.make_images("gradient", B, seed=68)
+    variants = [dict(restart_marker_rows=1), dict(), dict(restart_marker_blocks=5),
+                dict(restart_marker_rows=4), dict(optimize=True), dict(restart_marker_blocks=2,
+                                                                       subsampling="4:4:4")]
+    chunks = []
+    for b in range(B):
+        buf = io.BytesIO()
+        args = dict(format="JPEG", quality=85, subsampling="4:2:0")
+        args.update(variants[b % len(variants)])
+        Image.fromarray(synth.image_view(*imgs, b)).save(buf, **args)
+        chunks.append(np.frombuffer(buf.getvalue(), np.uint8))
+    sizes = np.array([c.size for c in chunks], np.int32)
+    offsets = np.zeros(B, np.int64)
+    offsets[1:] = np.cumsum(sizes.astype(np.int64))[:-1]
+    files = np.concatenate(chunks)
+    L = (S // 16) ** 2
+    kw = dict(out_size=S, patch=16, num_keep=oracle.num_keep(L, 0.75), seed=21, batch_index=8)
+    ref = oracle.prep_batch(*_decode_all(files, offsets, sizes), **kw)
+    buf, _ = _gpu_jpeg_prep(files, offsets, sizes, **kw)
+    assert mae.mae_prep_status(buf.workspace) == 0
+    check_prep_against_oracle(prep_to_numpy(buf), ref, what="mixed batch")
+
+
+def test_image_shapes_at_the_limits():
+    """Up to 128 rows of MCUs in a file (more rows than a wavefront has lanes), a row of 63 MCUs,
+    images smaller than one MCU and with ragged edges, with and without restart markers; an image
+    that does not fit the side limit is flagged."""
+    import io
+
+    from PIL import Image
+    shapes = [(512, 72, "4:4:4", 1), (1024, 48, "4:2:0", 1), (48, 1000, "4:2:0", 1),
+              (8, 8, "4:4:4", 1), (5, 7, "4:2:0", 0), (17, 23, "4:2:0", 0), (505, 131, "4:4:4", 0),
+              (1040, 64, "4:4:4", 1), (1024, 40, "4:4:4", 1), (1000, 56, "4:4:4", 0)]
     rng = np.random.default_rng(65)
     chunks = []
-    for h, w, sub in shapes:
+    for h, w, sub, rst in shapes:
         buf = io.BytesIO()
+        kw = dict(restart_marker_rows=1) if rst else {}
         Image.fromarray(synth._one_image("gradient", h, w, rng)).save(
-            buf, format="JPEG", quality=90, subsampling=sub, restart_marker_rows=1)
+            buf, format="JPEG", quality=90, subsampling=sub, **kw)
         chunks.append(np.frombuffer(buf.getvalue(), np.uint8))
     # and the file written by hand (its own small tables, 162 bytes), after the one that is flagged
     from conftest import read_golden
     hand = next(r[1:] for r in read_golden("jpeg_hand_example.txt") if r[0] == "file")
     chunks.append(np.frombuffer(bytes.fromhex("".join(hand)), np.uint8))
+    n = len(chunks)
     sizes = np.array([c.size for c in chunks], np.int32)
-    offsets = np.zeros(len(chunks), np.int64)
+    offsets = np.zeros(n, np.int64)
     offsets[1:] = np.cumsum(sizes.astype(np.int64))[:-1]
     files = np.concatenate(chunks)
     S = 64
     L = (S // 16) ** 2
-    keep = [0, 1, 2, 3, 4, 5, 6, 8]
-    # the oracle gets the hand-written image in place of the file it would refuse
-    stand_in = [8 if b == 7 else b for b in range(9)]
+    keep = [b for b in range(n) if b != 7]
+    # the oracle gets the hand-written image in place of the file that is too large
+    stand_in = [n - 1 if b == 7 else b for b in range(n)]
     decoded = _decode_all(files, offsets[stand_in], sizes[stand_in])
     for scale in ((0.2, 1.0), (1.0, 1.0)):
         kw = dict(out_size=S, patch=16, num_keep=L, scale=scale, seed=18, batch_index=5)
         buf, _ = _gpu_jpeg_prep(files, offsets, sizes, max_image_side=1024, **kw)
         crop = buf.crop.cpu().numpy()
-        assert list(np.nonzero(crop[:, 5] == 0)[0]) == [7]        # 65 rows of MCUs
+        assert list(np.nonzero(crop[:, 5] == 0)[0]) == [7]        # 1040 rows: beyond the limit
         ref = oracle.prep_batch(*decoded, **kw)
         sel = {k: (v[keep] if v is not None else None) for k, v in ref.items()}
         check_prep_against_oracle(prep_to_numpy(buf, rows=keep), sel, what=f"limits {scale}")
@@ -150,7 +203,9 @@ def test_files_the_decoder_does_not_take_are_flagged_and_take_no_part():
         return np.frombuffer(buf.getvalue(), np.uint8)
 
     good = [enc(b) for b in range(B)]
-    bad = {1: enc(1, restart_marker_rows=0),          # rows not independent
+    gray = io.BytesIO()
+    Image.fromarray(synth.image_view(*imgs, 1)).convert("L").save(gray, format="JPEG", quality=90)
+    bad = {1: np.frombuffer(gray.getvalue(), np.uint8),   # one component
            3: enc(3, progressive=True),
            4: good[4][:200].copy(),                   # cut inside the tables
            6: enc(6, subsampling="4:2:2")}
