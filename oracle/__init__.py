@@ -145,6 +145,8 @@ def load_library(path: str):
     L.mae_oracle_huff_codes.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
     L.mae_oracle_threads.restype = C.c_int32
     L.mae_oracle_threads.argtypes = []
+    L.mae_oracle_set_threads.restype = None
+    L.mae_oracle_set_threads.argtypes = [C.c_int32]
     return L
 
 
@@ -471,3 +473,8 @@ def huff_codes(counts):
 
 def threads() -> int:
     return int(lib().mae_oracle_threads())
+
+
+def set_threads(n: int) -> None:
+    """Threads for the loops over samples and rows from now on (0 = the default)."""
+    lib().mae_oracle_set_threads(int(n))

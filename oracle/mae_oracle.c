@@ -985,3 +985,13 @@ int32_t mae_oracle_threads(void) {
   return 1;
 #endif
 }
+
+/* Number of threads the loops over samples and rows may use from now on (timing only: results
+ * do not depend on it); n < 1 restores the default. */
+void mae_oracle_set_threads(int32_t n) {
+#ifdef _OPENMP
+  omp_set_num_threads(n >= 1 ? n : omp_get_num_procs());
+#else
+  (void)n;
+#endif
+}

@@ -204,6 +204,8 @@ void mae_oracle_ycc_to_rgb(int32_t y, int32_t cb, int32_t cr, uint8_t rgb[3]);
 int32_t mae_oracle_huff_codes(const uint8_t counts[16], uint16_t* codes, uint8_t* lengths);
 
 int32_t mae_oracle_threads(void);
+/* Threads for the loops over samples and rows from now on (results do not depend on it). */
+void mae_oracle_set_threads(int32_t n);
 
 #ifdef __cplusplus
 }
