@@ -436,6 +436,7 @@ int enqueue_loss(const mae_loss_desc* d, float* loss, void* grad, double* partia
   la.partials = partials;
   la.num_partials = sh.waves;
   la.rows_per_iter = sh.rows_per_iter;
+  la.pair_groups = sh.pair_groups;
   if (d->num_masked == 0) {  // the divisor is the number of non-zero mask bytes, counted first
     int32_t* counts = reinterpret_cast<int32_t*>(partials + sh.waves);
     la.counts = counts;

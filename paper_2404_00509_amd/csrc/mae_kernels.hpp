@@ -173,6 +173,7 @@ struct LossArgs {
   double* partials;  // workspace: one per wavefront of the grid
   int32_t num_partials;
   int32_t rows_per_iter;  // adjacent rows a wavefront handles per pass (1 or 2)
+  int32_t pair_groups;    // non-zero: the two rows as one run of groups, this many per lane
   // when set: M = sum of these partial counts, gscale = gscale_num / (D M), inv_count = 1 / (D M)
   const int32_t* counts;
   int32_t ncounts;
@@ -185,6 +186,7 @@ hipError_t launch_mask_count(const uint8_t* mask, int64_t rows, int32_t* counts,
 struct LossShape {
   int waves;          // wavefronts of the grid = number of partials
   int rows_per_iter;
+  int pair_groups;
 };
 LossShape loss_shape(int64_t rows, int D, bool pred_bf16);
 hipError_t launch_normpix_loss(const LossArgs& a, hipStream_t stream);

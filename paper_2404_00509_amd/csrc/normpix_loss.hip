@@ -143,6 +143,84 @@ __global__ __launch_bounds__(kLossThreads) void normpix_loss_kernel(LossArgs a) 
   if (lane == 0) a.partials[wave_in_grid] = acc;
 }
 
+// Rows whose number of 16-byte groups is not a multiple of 64 leave part of a wavefront's last
+// load and store per row idle (D = 588: 147 groups, the third instruction moves 19 of 64).  Two
+// adjacent rows are contiguous in memory, so here a wavefront takes them as one run of 2 D / 4
+// groups, lane i holding groups i, i + 64, ...: every instruction but the run's last is full.
+// A group lies in one row (rows are whole groups), the two rows' sums are kept apart, and a
+// lane's group takes the statistics of the row it lies in.  NVF = groups per lane.
+template <int NVF, bool kBf16, bool kNorm>
+__global__ __launch_bounds__(kLossThreads) void normpix_loss_pair_kernel(LossArgs a) {
+  const int lane = threadIdx.x % kWave;
+  const int wave_in_grid = blockIdx.x * kLossWaves + threadIdx.x / kWave;
+  const int waves = gridDim.x * kLossWaves;
+  const int D = a.D, D4 = a.D >> 2;
+  const float inv_d = 1.0f / (float)D;
+  const float inv_dm1 = 1.0f / (float)(D - 1);
+  double acc = 0.0;
+  const float gscale =
+      a.counts ? (float)(a.gscale_num * inv_count_of(D, sum_counts(a.counts, a.ncounts))) : a.gscale;
+  const f32x4 zero = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  for (int64_t row0 = 2 * (int64_t)wave_in_grid; row0 < a.rows; row0 += 2 * (int64_t)waves) {
+    const bool have1 = row0 + 1 < a.rows;
+    const bool m0 = a.mask[row0] != 0, m1 = have1 && a.mask[row0 + 1] != 0;
+    const int64_t elem0 = row0 * D;
+    f32x4 t[NVF], q[NVF];
+    bool second[NVF], live[NVF];
+#pragma unroll
+    for (int v = 0; v < NVF; ++v) {
+      const int g = lane + v * kWave;
+      second[v] = g >= D4;
+      live[v] = g < (have1 ? 2 * D4 : D4);
+      t[v] = zero;
+      q[v] = zero;
+      if (live[v] && (second[v] ? m1 : m0)) {
+        t[v] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(a.target + elem0 + 4 * g));
+        q[v] = load_pred4<kBf16>(a.pred, elem0 + 4 * g);
+      }
+    }
+    float rstd0 = 1.0f, rstd1 = 1.0f;
+    if (kNorm) {
+      float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+      for (int v = 0; v < NVF; ++v) {
+        const float s = (t[v].x + t[v].y) + (t[v].z + t[v].w);  // zero where nothing was loaded
+        s0 += second[v] ? 0.f : s;
+        s1 += second[v] ? s : 0.f;
+      }
+      const float mu0 = wave_sum(s0) * inv_d, mu1 = wave_sum(s1) * inv_d;
+      float ss0 = 0.f, ss1 = 0.f;
+#pragma unroll
+      for (int v = 0; v < NVF; ++v) {
+        t[v] = t[v] - (second[v] ? mu1 : mu0);
+        const float ss = (t[v].x * t[v].x + t[v].y * t[v].y) + (t[v].z * t[v].z + t[v].w * t[v].w);
+        const bool counted = live[v] && (second[v] ? m1 : m0);
+        ss0 += (counted && !second[v]) ? ss : 0.f;
+        ss1 += (counted && second[v]) ? ss : 0.f;
+      }
+      rstd0 = 1.0f / sqrtf(wave_sum(ss0) * inv_dm1 + a.eps);
+      rstd1 = 1.0f / sqrtf(wave_sum(ss1) * inv_dm1 + a.eps);
+    }
+    float sq = 0.f;
+#pragma unroll
+    for (int v = 0; v < NVF; ++v) {
+      if (!live[v]) continue;
+      const int g = lane + v * kWave;
+      const bool masked = second[v] ? m1 : m0;
+      f32x4 diff = zero;  // visible rows: zero gradient, nothing towards the loss
+      if (masked) {
+        diff = kNorm ? q[v] - t[v] * (second[v] ? rstd1 : rstd0) : q[v] - t[v];
+        sq += (diff.x * diff.x + diff.y * diff.y) + (diff.z * diff.z + diff.w * diff.w);
+      }
+      if (a.grad) store_grad4<kBf16>(a.grad, elem0 + 4 * g, diff * gscale);
+    }
+    acc += (double)sq;
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) a.partials[wave_in_grid] = acc;
+}
+
 // Any D (not a multiple of four, or too long for registers): three passes over the row.
 template <bool kBf16, bool kNorm>
 __global__ __launch_bounds__(kLossThreads) void normpix_loss_scalar_kernel(LossArgs a) {
@@ -212,19 +290,35 @@ __global__ __launch_bounds__(kLossThreads) void loss_finish_kernel(const double*
   if (threadIdx.x == 0) *loss = (float)(red[0] * inv_count);
 }
 
+// Groups per lane of the pair kernel for rows of D values, 0 when pairing saves nothing (a row
+// is a whole number of 64-group instructions, or two rows need as many as one row twice) or does
+// not fit the registers.
+static int pair_groups(int D) {
+  const int d4 = D >> 2;
+  const int single = (d4 + kWave - 1) / kWave, pair = (2 * d4 + kWave - 1) / kWave;
+  return (pair < 2 * single && pair <= 6) ? pair : 0;
+}
+
 // Launch shape.  What counts is the amount of row data in flight per compute unit (about 144 KiB
 // measured best on MI355X) and that every compute unit gets the same number of workgroups.  Rows
 // that bring 6 KiB or more of loads (D = 768 in fp32) go two per pass with 3 workgroups per compute
-// unit; shorter rows one per pass with 6.
+// unit; shorter rows one per pass with 6, or, when their groups do not fill whole instructions,
+// as pairs in one run of groups with 4.
 LossShape loss_shape(int64_t rows, int D, bool pred_bf16) {
   LossShape sh;
   const int nv = ((D >> 2) + kWave - 1) / kWave;
   const int64_t load_bytes = (int64_t)D * (pred_bf16 ? 6 : 8);
   const bool vec = (D & 3) == 0 && (D >> 2) <= 12 * kWave;
   sh.rows_per_iter = (vec && nv <= 4 && load_bytes >= 6144) ? 2 : 1;
+  // rows as pairs in one run of groups: when that saves a load and a store instruction per pair
+  sh.pair_groups = (vec && sh.rows_per_iter == 1) ? pair_groups(D) : 0;
+  if (sh.pair_groups) sh.rows_per_iter = 2;
+  // workgroups per compute unit (measured best: D = 768 fp32 two rows at 3, D = 588 bf16 pairs
+  // at 4, single rows at 6)
+  const int per_cu = sh.pair_groups ? 4 : (sh.rows_per_iter == 2 ? 3 : 6);
   const int64_t rows_per_block = (int64_t)kLossWaves * sh.rows_per_iter;
   int64_t blocks = (rows + rows_per_block - 1) / rows_per_block;
-  const int64_t cap = (int64_t)kComputeUnits * (sh.rows_per_iter == 2 ? 3 : 6);
+  const int64_t cap = (int64_t)kComputeUnits * per_cu;
   if (blocks > cap) blocks = cap;
   if (blocks < 1) blocks = 1;
   sh.waves = (int)blocks * kLossWaves;
@@ -234,6 +328,19 @@ LossShape loss_shape(int64_t rows, int D, bool pred_bf16) {
 template <bool kBf16, bool kNorm>
 static void launch_vec(const LossArgs& a, dim3 grid, dim3 block, hipStream_t stream) {
   const int nv = ((a.D >> 2) + kWave - 1) / kWave;
+  const int nvf = a.pair_groups;
+  if (nvf != 0) {
+#define MAE_LAUNCH_PAIR(NVF) \
+  hipLaunchKernelGGL((normpix_loss_pair_kernel<NVF, kBf16, kNorm>), grid, block, 0, stream, a)
+    if (nvf <= 1) MAE_LAUNCH_PAIR(1);
+    else if (nvf == 2) MAE_LAUNCH_PAIR(2);
+    else if (nvf == 3) MAE_LAUNCH_PAIR(3);
+    else if (nvf == 4) MAE_LAUNCH_PAIR(4);
+    else if (nvf == 5) MAE_LAUNCH_PAIR(5);
+    else MAE_LAUNCH_PAIR(6);
+#undef MAE_LAUNCH_PAIR
+    return;
+  }
 #define MAE_LAUNCH(NV, RPI) \
   hipLaunchKernelGGL((normpix_loss_kernel<NV, RPI, kBf16, kNorm>), grid, block, 0, stream, a)
   if (a.rows_per_iter == 2) {
