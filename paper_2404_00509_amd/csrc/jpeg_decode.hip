@@ -228,12 +228,12 @@ __device__ static inline u32x4_a8 load_chunk(const uint8_t* base, int64_t bytes,
     if (at + i < bytes) w[i >> 2] |= (uint32_t)base[at + i] << (8 * (i & 3));
   return u32x4_a8{w[0], w[1], w[2], w[3]};
 }
-__device__ static inline void request_bytes(BitReader& r) {
+__device__ static __forceinline__ void request_bytes(BitReader& r) {
   r.next[0] = load_chunk(r.chunks, r.chunks_bytes, r.have);
   r.next[1] = load_chunk(r.chunks, r.chunks_bytes, r.have + 16);
   r.pending = true;
 }
-__device__ static inline void accept_bytes(BitReader& r) {
+__device__ static __forceinline__ void accept_bytes(BitReader& r) {
   const int i = (r.have & (kRingBytes - 1)) >> 2;  // 32 bytes never wrap: both are powers of two
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
@@ -244,20 +244,20 @@ __device__ static inline void accept_bytes(BitReader& r) {
   r.pending = false;
 }
 // The point all lanes pass together (start of a block).
-__device__ static inline void feed_ring(BitReader& r) {
+__device__ static __forceinline__ void feed_ring(BitReader& r) {
   if (r.pending) accept_bytes(r);
   // room: the 32 bytes to come replace those 128 bytes back, which must have been read
   if (!r.ended && r.have - (r.pos + r.skew) <= kRingBytes - kRingStep && r.have < r.n + r.skew)
     request_bytes(r);
 }
 // Makes the `count` <= 4 bytes at file position pos available in the ring.
-__device__ static inline void need_bytes(BitReader& r, int pos, int count) {
+__device__ static __forceinline__ void need_bytes(BitReader& r, int pos, int count) {
   while (pos + r.skew + count > r.have) {
     if (!r.pending) request_bytes(r);
     accept_bytes(r);
   }
 }
-__device__ static inline void open_reader(BitReader& r, int start) {
+__device__ static __forceinline__ void open_reader(BitReader& r, int start) {
   r.pos = start;
   r.have = (start + r.skew) & ~(kRingStep - 1);
   r.pending = false;
@@ -272,7 +272,7 @@ __device__ static inline uint32_t ring_dword(const BitReader& r, int i) {
   return r.ring[(i & (kRingBytes / 4 - 1)) * kJpegThreads];
 }
 // Byte `pos` of the file (pos < n).
-__device__ static inline uint32_t file_byte(BitReader& r, int pos) {
+__device__ static __forceinline__ uint32_t file_byte(BitReader& r, int pos) {
   need_bytes(r, pos, 1);
   const int q = pos + r.skew;
   return (ring_dword(r, q >> 2) >> (8 * (q & 3))) & 0xFFu;
@@ -302,8 +302,8 @@ __device__ static inline NextFour next_four(const BitReader& r) {
   f.usable = (int)f.in_reach & (int)(((inv - 0x01010101u) & ~inv & 0x80808080u) == 0u);
   return f;
 }
-__device__ static inline void fill_bytewise(BitReader& r);
-__device__ static inline void fill(BitReader& r, const NextFour& f) {
+__device__ static __forceinline__ void fill_bytewise(BitReader& r);
+__device__ static __forceinline__ void fill(BitReader& r, const NextFour& f) {
   if (r.nbits > 32) return;
   if (f.usable) {
     r.acc = (r.acc << 32) | (uint64_t)f.bits;
@@ -335,12 +335,12 @@ __device__ static inline void fill(BitReader& r, const NextFour& f) {
   }
   fill_bytewise(r);
 }
-__device__ static inline void fill(BitReader& r) {
+__device__ static __forceinline__ void fill(BitReader& r) {
   if (r.nbits > 32) return;
   if (!r.ended && r.pos + 4 <= r.n) need_bytes(r, r.pos, 4);
   fill(r, next_four(r));
 }
-__device__ static inline void fill_bytewise(BitReader& r) {
+__device__ static __forceinline__ void fill_bytewise(BitReader& r) {
   while (r.nbits <= 32) {
     uint32_t byte = 0;
     if (!r.ended && r.pos < r.n) {
@@ -363,7 +363,7 @@ __device__ static inline void fill_bytewise(BitReader& r) {
 // At a restart boundary: what is left of the interval (the padding of its last byte, fill bytes)
 // is dropped, the marker skipped and the reader opened behind it.  Returns false when no restart
 // marker follows within a few bytes.
-__device__ static inline bool restart_reader(BitReader& r) {
+__device__ static __forceinline__ bool restart_reader(BitReader& r) {
   int p = r.pos;  // the reader never loads a marker: it is at or behind this byte
   bool found = false;
   for (int i = 0; i < 16 && !found; ++i) {
@@ -700,7 +700,7 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_tables_kernel(JpegArgs a) {
 
 // DC difference of the next block (T.81 F.2.2.1).  Returns false for a code that does not exist
 // or a category that 8-bit data does not have (the difference is then 0).
-__device__ static inline bool decode_dc(BitReader& r, const HuffDc& h, int& diff) {
+__device__ static __forceinline__ bool decode_dc(BitReader& r, const HuffDc& h, int& diff) {
   fill(r);
   const uint32_t top = peek32(r);
   const uint32_t x = top >> 16;
@@ -725,7 +725,7 @@ __device__ static inline bool decode_dc(BitReader& r, const HuffDc& h, int& diff
 // symbols' lengths are followed.  Returns false for a code that does not exist or a run past the
 // end of the block.
 template <bool kStore>
-__device__ static inline bool decode_ac(BitReader& r, const HuffAc& h, const uint16_t* qz,
+__device__ static __forceinline__ bool decode_ac(BitReader& r, const HuffAc& h, const uint16_t* qz,
                                         int16_t* coef, bool want) {
   bool ok = true;
   fill(r);
@@ -769,7 +769,7 @@ __device__ static inline bool decode_ac(BitReader& r, const HuffAc& h, const uin
   return ok;
 }
 
-__device__ static inline void reader_for(BitReader& r, const JpegArgs& a, const JpegImage& im,
+__device__ static __forceinline__ void reader_for(BitReader& r, const JpegArgs& a, const JpegImage& im,
                                          uint32_t* ring) {
   r.skew = (int)(im.origin & 7);
   r.chunks = a.files + (im.origin - r.skew);
@@ -778,7 +778,7 @@ __device__ static inline void reader_for(BitReader& r, const JpegArgs& a, const 
   r.n = im.size;
 }
 // Opens the reader in the state recorded for a row.
-__device__ static inline void open_at(BitReader& r, const RowState& st) {
+__device__ static __forceinline__ void open_at(BitReader& r, const RowState& st) {
   open_reader(r, st.pos);
   r.acc = st.acc;
   r.nbits = st.nbits;
@@ -790,7 +790,7 @@ __device__ static inline void open_at(BitReader& r, const RowState& st) {
 // the whole interval) and the lengths of the AC symbols; at every restart boundary the marker is
 // skipped and the predictors cleared.  At the first MCU of each of the crop's rows the reader's
 // state goes to the workspace.  The walk ends with the crop's last row.
-constexpr int kScanImages = 8;
+constexpr int kScanImages = 16;
 struct JpegScanLds {
   JpegPrepared img[kScanImages];
   uint32_t ring[kRingBytes / 4][kJpegThreads];
