@@ -564,8 +564,8 @@ __device__ static void produce_loss_wave(const CropArgs& a, const uint32_t* tile
 // neighbouring pixels of a patch row (12 values) instead of four values, and the groups of the
 // part's patches are dealt to the lanes in order.  The 64 x 12 values of a wavefront go through a
 // wavefront-private strip of LDS so that every store instruction still writes 1 KiB of
-// contiguous memory.  Tables: xtab.y = horizontal remainder rx, ytab.z / ytab.w = the integer
-// weights den - ry, ry of the two rows (den = 2 S).
+// contiguous memory.  Tables: xtab.y = the integer weights den - rx, rx of the two columns as a pair
+// of 16-bit values, ytab.z / ytab.w = the weights den - ry, ry of the two rows (den = 2 S).
 //
 // Rounding.  The bilinear value is num / den^2,
 //   top = (den - rx) a00 + rx a01, bot likewise (two-product dot instructions on 16-bit pairs),
@@ -593,10 +593,13 @@ __device__ static inline float round_blend(uint32_t w00, uint32_t w01, uint32_t 
   int top, bot;
   asm("v_dot2_i32_i16 %0, %1, %2, 0" : "=v"(top) : "v"(t2), "v"(wx));
   asm("v_dot2_i32_i16 %0, %1, %2, 0" : "=v"(bot) : "v"(b2), "v"(wx));
-  const int num = __mul24(ry, bot) + (__mul24(cy, top) + (dd >> 1));
-  int q = (int)((float)num * inv_dd);
-  q += (num - __mul24(q, dd)) >= dd ? 1 : 0;
-  return (float)q;
+  // 24-bit multiply-adds, written out because the compiler splits them into multiply + add
+  int half_top, num, r;
+  asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(half_top) : "v"(cy), "v"(top), "s"(dd >> 1));
+  asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(num) : "v"(ry), "v"(bot), "v"(half_top));
+  const int q = (int)((float)num * inv_dd);
+  asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(r) : "v"(q), "s"(-dd), "v"(num));  // dd < 2^23
+  return (float)(q + (r >= dd ? 1 : 0));
 }
 
 // kPass 0: "3 Aug", or the first pass of "3 Aug+" (kJitter: luma sums only); kPass 1: the second
@@ -658,7 +661,7 @@ __device__ static void produce_aug(const CropArgs& a, const uint32_t* tile, cons
       uint32_t w00, w01, w10, w11;
       fetch2<kLds>(tile, base, yt.x, (int)xt.x, cw, w00, w01);
       fetch2<kLds>(tile, base, yt.y, (int)xt.x, cw, w10, w11);
-      const uint32_t wx = (uint32_t)(den - (int)xt.y) | (xt.y << 16);
+      const uint32_t wx = xt.y;
       v[3 * j] = round_blend<0>(w00, w01, w10, w11, wx, cy, ry, dd, inv_dd);
       v[3 * j + 1] = round_blend<1>(w00, w01, w10, w11, wx, cy, ry, dd, inv_dd);
       v[3 * j + 2] = round_blend<2>(w00, w01, w10, w11, wx, cy, ry, dd, inv_dd);
@@ -926,8 +929,12 @@ __device__ static inline void crop_band(const CropArgs& a, uint32_t* lds) {
     float f;
     resize_taps(rec.flip ? S - 1 - ox : ox, rec.cw, S, inv_den, x0, x1, f, rem);
     // at the right edge both taps are the last pixel: weight 0 makes the second tap irrelevant
-    const uint32_t wx = kAug ? (uint32_t)rem : __float_as_uint(f);
-    xtab[i] = u32x2{(uint32_t)(x0 - xlo), x1 == x0 ? 0u : wx};
+    if constexpr (kAug != 0) {  // the two integer weights 2 S - rem, rem as a pair of 16-bit values
+      const uint32_t r = x1 == x0 ? 0u : (uint32_t)rem;
+      xtab[i] = u32x2{(uint32_t)(x0 - xlo), ((uint32_t)(2 * S) - r) | (r << 16)};
+    } else {
+      xtab[i] = u32x2{(uint32_t)(x0 - xlo), x1 == x0 ? 0u : __float_as_uint(f)};
+    }
   }
   for (int py = tid; py < p; py += (int)blockDim.x) {
     int y0, y1, rem;

@@ -68,8 +68,11 @@ struct AugParams {
   double sigma;
   float brightness, contrast, saturation;
   float pad;
+  // blur images: tap |k| of the kernel exp(-k^2 / (2 sigma^2)) scaled to sum 1, zero beyond the
+  // radius (filled in by the parameter kernel, see blur_taps)
+  float tap[8];
 };
-static_assert(sizeof(AugParams) == 32, "one 32-byte record per sample in the workspace");
+static_assert(sizeof(AugParams) == 64, "one 64-byte record per sample in the workspace");
 __device__ inline AugParams aug_params(uint64_t key1, uint32_t sample, float jitter) {
 #pragma clang fp contract(off)  // sigma decides the integer radius: no fused multiply-add here
   AugParams ap;
@@ -83,7 +86,19 @@ __device__ inline AugParams aug_params(uint64_t key1, uint32_t sample, float jit
   ap.contrast = (float)(1.0 + j * (2.0 * unit53(draw(key1, sample, kContrast, 0)) - 1.0));
   ap.saturation = (float)(1.0 + j * (2.0 * unit53(draw(key1, sample, kSaturation, 0)) - 1.0));
   ap.pad = 0.0f;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) ap.tap[k] = 0.0f;
   return ap;
+}
+// Tap `lane` (0..6) of the blur kernel of an image, by the first lanes of a wavefront together:
+// exp(-k^2 / (2 sigma^2)) in double precision, summed over -radius .. radius in index order,
+// scaled to sum 1.  Returns zero for lanes beyond the radius.
+__device__ inline float blur_taps(const AugParams& ap, int lane) {
+  const double k = (double)lane;
+  const double e = lane <= ap.radius ? exp(-(k * k) / (2.0 * ap.sigma * ap.sigma)) : 0.0;
+  double sum = 0.0;
+  for (int j = -6; j <= 6; ++j) sum += __shfl(e, j < 0 ? -j : j, kWave);
+  return (float)(e / sum);
 }
 
 // ---- the loss's divisor counted on the device ------------------------------------------------------

@@ -152,13 +152,20 @@ __global__ __launch_bounds__(kWave) void params_mask_kernel(ParamArgs a) {
       int32_t* c = a.crop_out + (int64_t)b * 6;
       c[0] = top; c[1] = left; c[2] = ch; c[3] = cw; c[4] = flip; c[5] = valid ? 1 : 0;
     }
-    // the finetuning augmentation's draws, once per sample instead of once per workgroup later
-    if (a.aug_out) static_cast<AugParams*>(a.aug_out)[b] = aug_params(a.key1, sample, a.jitter);
     if (b == 0) {  // header: lets the status query find the records of this call
       WorkspaceHeader* hdr = reinterpret_cast<WorkspaceHeader*>(a.workspace);
       hdr->magic = kWorkspaceMagic;
       hdr->B = a.B;
     }
+  }
+  // the finetuning augmentation's draws and the blur's taps, once per sample instead of once per
+  // workgroup later: every lane makes the same draws, lane k computes tap k
+  if (a.aug_out) {
+    AugParams ap = aug_params(a.key1, sample, a.jitter);
+    const float t = ap.op == kOpBlur ? blur_taps(ap, lane) : 0.0f;
+#pragma unroll
+    for (int k = 0; k < 7; ++k) ap.tap[k] = __shfl(t, k, kWave);
+    if (lane == 0) static_cast<AugParams*>(a.aug_out)[b] = ap;
   }
   if (!valid) return;
 

@@ -30,7 +30,6 @@ namespace mae {
 
 constexpr int kAugThreads = 256;
 constexpr int kMaxRadius = 6;  // ceil(3 * 2.0)
-constexpr int kTaps = 2 * kMaxRadius + 1;
 
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -73,34 +72,39 @@ __host__ __device__ static inline int halo_patches(int p) { return (kMaxRadius +
 
 // Copies `rows` image rows (first y_first, clamped into the image) of patches gxa .. gxa + nseg - 1
 // from the patch-order bytes `img` into `dst` in image order, in pieces of type T (wseg pieces per
-// patch row).  A thread issues four loads before it stores the first.
+// patch row).  A wavefront takes whole rows, a lane one piece of the row, so that everything that
+// depends on the row is the same for all lanes and a piece costs one address addition; a lane
+// issues four loads (four rows) before it stores the first.
 template <typename T>
 __device__ static inline void stage_rows(uint8_t* dst, const uint8_t* img, int rows, int nseg,
                                          int wseg, int y_first, int S, int p, int G, int gxa,
                                          int D) {
   T* out = reinterpret_cast<T*>(dst);
-  const int pitch = nseg * wseg, total = rows * pitch;
-  const float inv_pitch = 1.0f / (float)pitch, inv_wseg = 1.0f / (float)wseg;
-  const float inv_p = 1.0f / (float)p;
-  constexpr int kBatch = 4;
-  for (int i0 = threadIdx.x; i0 < total; i0 += kBatch * kAugThreads) {
-    T v[kBatch];
+  const int lane = threadIdx.x % kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int pitch = nseg * wseg;
+  const float inv_wseg = 1.0f / (float)wseg, inv_p = 1.0f / (float)p;
+  constexpr int kBatch = 4, kWaves = kAugThreads / kWave;
+  for (int l0 = 0; l0 < pitch; l0 += kWave) {
+    const bool have = l0 + lane < pitch;
+    const int l = have ? l0 + lane : pitch - 1;
+    const int seg = fast_div(l, inv_wseg);
+    const uint32_t piece = (uint32_t)(__mul24(gxa + seg, D) + (int)sizeof(T) * (l - seg * wseg));
+    for (int j0 = wave; j0 < rows; j0 += kBatch * kWaves) {
+      T v[kBatch];
 #pragma unroll
-    for (int u = 0; u < kBatch; ++u) {
-      const int i = min(i0 + u * kAugThreads, total - 1);
-      const int j = fast_div(i, inv_pitch);
-      const int r = i - j * pitch;
-      const int seg = fast_div(r, inv_wseg);
-      const int yy = min(max(y_first + j, 0), S - 1);
-      const int gyy = fast_div(yy, inv_p);
-      v[u] = *reinterpret_cast<const T*>(
-          img + (uint32_t)((gyy * G + gxa + seg) * D + (yy - gyy * p) * 3 * p +
-                           (int)sizeof(T) * (r - seg * wseg)));
-    }
+      for (int u = 0; u < kBatch; ++u) {
+        const int j = min(j0 + u * kWaves, rows - 1);
+        const int yy = min(max(y_first + j, 0), S - 1);
+        const int gyy = fast_div(yy, inv_p);
+        const uint32_t row = (uint32_t)(__mul24(__mul24(gyy, G), D) + (yy - gyy * p) * 3 * p);
+        v[u] = *reinterpret_cast<const T*>(img + (row + piece));
+      }
 #pragma unroll
-    for (int u = 0; u < kBatch; ++u) {
-      const int i = i0 + u * kAugThreads;
-      if (i < total) out[i] = v[u];
+      for (int u = 0; u < kBatch; ++u) {
+        const int j = j0 + u * kWaves;
+        if (j < rows && have) out[j * pitch + l] = v[u];
+      }
     }
   }
 }
@@ -135,7 +139,7 @@ __device__ static inline void blur_vertical(const uint8_t* sbytes, float* vbuf, 
 template <int R, bool kReduce, bool kBf16>
 __device__ static void blur_part(const AugArgs& a, const AugParams& ap, int b, int gy, int part,
                                  int gx0, int npatch, float* vbuf, uint8_t* scratch,
-                                 const float* wf, double* red) {
+                                 double* red) {
   const int S = a.S, p = a.p, G = a.G;
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int Wp = npatch * p, x_lo = gx0 * p, y0 = gy * p;
@@ -154,10 +158,11 @@ __device__ static void blur_part(const AugArgs& a, const AugParams& ap, int b, i
     stage_rows<u32x4>(scratch, img, rows, nseg, w4 >> 2, y0 - R, S, p, G, gxa, a.D);
   else
     stage_rows<uint32_t>(scratch, img, rows, nseg, w4, y0 - R, S, p, G, gxa, a.D);
-  // taps -R .. R of this image's kernel (zero beyond its radius)
+  // taps -R .. R of this image's kernel as the parameter kernel left them (zero beyond the
+  // image's radius); the record is the same for the whole workgroup
   float wt[2 * R + 1];
 #pragma unroll
-  for (int k = 0; k <= 2 * R; ++k) wt[k] = wf[kMaxRadius - R + k];
+  for (int k = 0; k <= 2 * R; ++k) wt[k] = ap.tap[k < R ? R - k : k - R];
   __syncthreads();
 
   const int vpitch = (Wp + 2 * R) * 3;  // a multiple of four floats
@@ -301,8 +306,6 @@ __device__ static void blur_part(const AugArgs& a, const AugParams& ap, int b, i
 template <bool kReduce, bool kBf16>
 __global__ __launch_bounds__(kAugThreads) void aug_blur_kernel(AugArgs a) {
   extern __shared__ __attribute__((aligned(16))) float vals[];
-  __shared__ double wd[kTaps];
-  __shared__ float wf[kTaps];  // tap k - 6 at index k; zero beyond the radius
   __shared__ double red[kAugThreads / kWave];
 
   const int p = a.p, G = a.G, parts = a.blur_parts;
@@ -318,30 +321,16 @@ __global__ __launch_bounds__(kAugThreads) void aug_blur_kernel(AugArgs a) {
   const AugParams ap = static_cast<const AugParams*>(a.aug_recs)[b];
   if (ap.op != kOpBlur) return;
 
-  const int tid = threadIdx.x;
   const int radius = ap.radius;
-  // taps exp(-k^2 / (2 sigma^2)) in double precision, summed in index order, scaled to sum 1
-  if (tid < kTaps) {
-    const double k = (double)(tid - kMaxRadius);
-    wd[tid] = abs(tid - kMaxRadius) <= radius ? exp(-(k * k) / (2.0 * ap.sigma * ap.sigma)) : 0.0;
-  }
-  __syncthreads();
-  if (tid < kTaps) {
-    double sum = 0.0;
-    for (int k = kMaxRadius - radius; k <= kMaxRadius + radius; ++k) sum += wd[k];
-    wf[tid] = (float)(wd[tid] / sum);
-  }
-  __syncthreads();
-
   float* vbuf = vals;
   uint8_t* scratch = reinterpret_cast<uint8_t*>(
       vals + p * 3 * (a.blur_part_patches * p + 2 * kMaxRadius));
   if (radius <= 2)
-    blur_part<2, kReduce, kBf16>(a, ap, b, gy, part, gx0, npatch, vbuf, scratch, wf, red);
+    blur_part<2, kReduce, kBf16>(a, ap, b, gy, part, gx0, npatch, vbuf, scratch, red);
   else if (radius <= 4)
-    blur_part<4, kReduce, kBf16>(a, ap, b, gy, part, gx0, npatch, vbuf, scratch, wf, red);
+    blur_part<4, kReduce, kBf16>(a, ap, b, gy, part, gx0, npatch, vbuf, scratch, red);
   else
-    blur_part<6, kReduce, kBf16>(a, ap, b, gy, part, gx0, npatch, vbuf, scratch, wf, red);
+    blur_part<6, kReduce, kBf16>(a, ap, b, gy, part, gx0, npatch, vbuf, scratch, red);
 }
 
 // Bytes of dynamic LDS of the blur kernel for parts of n patches: the vertically blurred rows,

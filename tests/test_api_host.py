@@ -122,7 +122,7 @@ def test_prep_workspace_grows_with_the_augmentation(lib):
     assert plain == 256 + 4 * 32
     three = lib.mae_prep_workspace_bytes(C.byref(_prep_desc(aug_mode=1)))
     plus = lib.mae_prep_workspace_bytes(C.byref(_prep_desc(aug_mode=2)))
-    # crop records rounded up to 256, the augmentation's draws (32 bytes per sample) likewise,
+    # crop records rounded up to 256, the augmentation's draws and taps (64 bytes per sample) likewise,
     # then the 8-bit crops
     assert three == 512 + 256 + 4 * 224 * 224 * 3
     # a double per row of patches and column part: two parts in the blur kernel, one in the
