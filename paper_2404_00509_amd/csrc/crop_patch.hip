@@ -579,27 +579,49 @@ constexpr int kStripFloats = kWave * 12;  // per wavefront
 // floor(n / d) for 0 <= n < 2^22 and small d, from the float reciprocal (inv = 1 / d)
 __device__ static inline int small_div(int n, float inv) { return (int)(((float)n + 0.5f) * inv); }
 
-// Channel C of the four taps (pixel words w00 w01 / w10 w11) blended and rounded, as a float.
-// wx = (den - rx) | rx << 16; cy, ry = the rows' weights; dd = den^2; inv_dd as described above.
-template <int C>
-__device__ static inline float round_blend(uint32_t w00, uint32_t w01, uint32_t w10, uint32_t w11,
-                                           uint32_t wx, int cy, int ry, int dd, float inv_dd) {
-  // bytes C of the two words as a pair of 16-bit values (selector 0x0c gives a zero byte)
-  constexpr uint32_t sel = 0x0c000c00u | ((4u + C) << 16) | (uint32_t)C;
-  const uint32_t t2 = __builtin_amdgcn_perm(w01, w00, sel);
-  const uint32_t b2 = __builtin_amdgcn_perm(w11, w10, sel);
-  // (the three-operand form with a zero addend: the accumulating form would need its
-  // destination cleared first)
-  int top, bot;
-  asm("v_dot2_i32_i16 %0, %1, %2, 0" : "=v"(top) : "v"(t2), "v"(wx));
-  asm("v_dot2_i32_i16 %0, %1, %2, 0" : "=v"(bot) : "v"(b2), "v"(wx));
-  // 24-bit multiply-adds, written out because the compiler splits them into multiply + add
-  int half_top, num, r;
-  asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(half_top) : "v"(cy), "v"(top), "s"(dd >> 1));
-  asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(num) : "v"(ry), "v"(bot), "v"(half_top));
-  const int q = (int)((float)num * inv_dd);
-  asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(r) : "v"(q), "s"(-dd), "v"(num));  // dd < 2^23
-  return (float)(q + (r >= dd ? 1 : 0));
+// The three channels of the four taps (pixel words w00 w01 / w10 w11) blended and rounded, as
+// floats.  wx = (den - rx) | rx << 16; cy, ry = the rows' weights; dd = den^2 < 2^23; inv_dd as
+// described above.
+// The dot and multiply-add instructions are written out as one block: the three-operand dot with
+// a zero addend (the accumulating form would need its destination cleared first) and 24-bit
+// multiply-adds (the compiler splits them into multiply + add).  A dot product's result may only
+// be read by another kind of instruction three or more instructions later; inside the block every
+// result is read five or more instructions after it is written, whatever is scheduled around it.
+__device__ static inline void round_blend3(uint32_t w00, uint32_t w01, uint32_t w10, uint32_t w11,
+                                           uint32_t wx, int cy, int ry, int dd, float inv_dd,
+                                           float* out) {
+  // byte C of the two words as a pair of 16-bit values (selector 0x0c gives a zero byte)
+  uint32_t t[3], b[3];
+#pragma unroll
+  for (int c = 0; c < 3; ++c) {
+    const uint32_t sel = 0x0c000c00u | ((4u + (uint32_t)c) << 16) | (uint32_t)c;
+    t[c] = __builtin_amdgcn_perm(w01, w00, sel);
+    b[c] = __builtin_amdgcn_perm(w11, w10, sel);
+  }
+  int n0, n1, n2, h0, h1, h2;
+  asm("v_dot2_i32_i16 %3, %6, %12, 0\n\t"
+      "v_dot2_i32_i16 %0, %7, %12, 0\n\t"
+      "v_dot2_i32_i16 %4, %8, %12, 0\n\t"
+      "v_dot2_i32_i16 %1, %9, %12, 0\n\t"
+      "v_dot2_i32_i16 %5, %10, %12, 0\n\t"
+      "v_dot2_i32_i16 %2, %11, %12, 0\n\t"
+      "v_mad_i32_i24 %3, %13, %3, %15\n\t"
+      "v_mad_i32_i24 %0, %14, %0, %3\n\t"
+      "v_mad_i32_i24 %4, %13, %4, %15\n\t"
+      "v_mad_i32_i24 %1, %14, %1, %4\n\t"
+      "v_mad_i32_i24 %5, %13, %5, %15\n\t"
+      "v_mad_i32_i24 %2, %14, %2, %5"
+      : "=&v"(n0), "=&v"(n1), "=&v"(n2), "=&v"(h0), "=&v"(h1), "=&v"(h2)
+      : "v"(t[0]), "v"(b[0]), "v"(t[1]), "v"(b[1]), "v"(t[2]), "v"(b[2]), "v"(wx), "v"(cy),
+        "v"(ry), "s"(dd >> 1));
+  const int num[3] = {n0, n1, n2};
+#pragma unroll
+  for (int c = 0; c < 3; ++c) {
+    const int q = (int)((float)num[c] * inv_dd);
+    int r;
+    asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(r) : "v"(q), "s"(-dd), "v"(num[c]));
+    out[c] = (float)(q + (r >= dd ? 1 : 0));
+  }
 }
 
 // kPass 0: "3 Aug", or the first pass of "3 Aug+" (kJitter: luma sums only); kPass 1: the second
@@ -661,10 +683,7 @@ __device__ static void produce_aug(const CropArgs& a, const uint32_t* tile, cons
       uint32_t w00, w01, w10, w11;
       fetch2<kLds>(tile, base, yt.x, (int)xt.x, cw, w00, w01);
       fetch2<kLds>(tile, base, yt.y, (int)xt.x, cw, w10, w11);
-      const uint32_t wx = xt.y;
-      v[3 * j] = round_blend<0>(w00, w01, w10, w11, wx, cy, ry, dd, inv_dd);
-      v[3 * j + 1] = round_blend<1>(w00, w01, w10, w11, wx, cy, ry, dd, inv_dd);
-      v[3 * j + 2] = round_blend<2>(w00, w01, w10, w11, wx, cy, ry, dd, inv_dd);
+      round_blend3(w00, w01, w10, w11, xt.y, cy, ry, dd, inv_dd, v + 3 * j);
     }
 
     if (blur) {  // the blur kernel's input: the twelve rounded values as bytes
