@@ -9,9 +9,10 @@ gradient), on synthetic images already resident in HBM.  Prints ONE JSON line.
 `value` is measured on the headline workload (c4).  The other workloads with a loss (c3, c5) are
 timed the same way and reported under "configs".  The first consumer of the path's output,
 mae_patch_embed, the finetuning-mode input pipeline ("3 Aug", "3 Aug+"), the input pipeline on
-JPEG files ("crop decode") and the stages of a progressive schedule are timed by themselves after
-the steps and reported under "patch_embed", "finetune_prep", "jpeg_prep*" and "stages"; they are
-not part of the step or of `value`.
+JPEG files ("crop decode"), the stages of a progressive schedule and a patch size that takes the
+element-wise kernel are timed by themselves after the steps and reported under "patch_embed",
+"finetune_prep", "jpeg_prep*", "stages" and "odd_patch_prep"; they are not part of the step or of
+`value`.
 
 Every duration comes from events recorded on the stream the library launches on; mean, median and
 minimum are given.  Bytes counted by hardware counters come from the summaries under profiles/
@@ -306,6 +307,12 @@ def time_embed(args, mae, synth, torch, w, E):
     st = stats(timed(torch, stream, lambda i: mae.mae_patch_embed(edesc, tokens, stream=stream),
                      args.steps, args.warmup))
     M = wl.B * K
+    # for scale only: the vendor library's bare product of the same shape (no bias, no positional
+    # rows, no gather), through torch.mm on the same stream
+    vis2 = buf.visible.view(M, wl.D)
+    ref = torch.empty((M, E), dtype=torch.bfloat16, device="cuda")
+    lib = stats(timed(torch, stream, lambda i: torch.mm(vis2, wt.t(), out=ref), args.steps,
+                      args.warmup))
     flops = 2.0 * M * wl.D * E
     nbytes = 2 * M * wl.D + 2 * M * E + 2 * E * wl.D + 4 * M + 4 * wl.L * E + 4 * E
     tflops = flops / (st["avg_ms"] * 1e-3) / 1e12
@@ -318,6 +325,8 @@ def time_embed(args, mae, synth, torch, w, E):
         "traffic": traffic_of(profile_counters("embed", wl.name)),
         "achieved_GBps": round(nbytes / (st["avg_ms"] * 1e-3) / 1e9, 1),
         "checksum": float(tokens.float().abs().mean().item()),
+        "library_bare_product": dict(lib, what="torch.mm of the same operands: no bias, no "
+                                               "positional rows; for scale"),
     })
 
 
@@ -378,6 +387,33 @@ def time_finetune(args, mae, torch, w):
                          alu=alu_roofline("finetune", key, st["avg_ms"])))
         del buf
     return rows
+
+
+def time_odd_patch(args, mae, torch, w):
+    """mae_prep_batch with a patch size whose rows are not whole 16-byte groups (3 p p % 4 != 0):
+    the same images to 225 px in patches of 15 (D = 675), keep a quarter.  These shapes take the
+    element-wise kernel instead of the staged one; this is what that costs."""
+    wl, dev = w.wl, w.dev
+    S, p = 225, 15
+    L = (S // p) ** 2
+    K = mae.mae_num_keep(L, 0.75)
+    desc = mae.make_prep_desc(*dev, out_size=S, patch=p, num_keep=K, seed=0, batch_index=0)
+    buf = mae.alloc_prep_buffers(desc)
+    stream = torch.cuda.current_stream()
+
+    def run(i):
+        desc.batch_index = i
+        mae.mae_prep_batch(desc, buf.visible, buf.mask, buf.ids_restore, buf.ids_keep, buf.target,
+                           buf.crop, buf.workspace, stream=stream)
+
+    st = stats(timed(torch, stream, run, max(5, args.steps // 3), 2))
+    assert mae.mae_prep_status(buf.workspace) == 0
+    D = 3 * p * p
+    nbytes = w.crop_bytes + wl.B * (K * D * 4 + L * D * 4 + L * 5 + K * 4)
+    gbps = nbytes / (st["avg_ms"] * 1e-3) / 1e9
+    return dict(st, out_size=S, patch=p, D=D, algorithmic_bytes=nbytes,
+                achieved_GBps=round(gbps, 1), frac=round(gbps / HBM_PEAK_GBPS, 4),
+                images_per_s=round(wl.B / (st["avg_ms"] * 1e-3), 1))
 
 
 def time_without_target(args, mae, torch, w, want_loss):
@@ -558,7 +594,7 @@ def main() -> int:
     ap.add_argument("--only", default="",
                     help="comma-separated extras to run after the steps instead of all of them "
                          "(embed, jpeg, jpeg_no_markers, jpeg_500, finetune, configs, stages, "
-                         "without_target, none); for profiling runs")
+                         "without_target, odd_patch, none); for profiling runs")
     ap.add_argument("--source-hashes", action="store_true",
                     help="print the hashes that key the rows of profiles/counters.md and exit")
     args = ap.parse_args()
@@ -648,6 +684,8 @@ def main() -> int:
                                              name="jpeg_prep_500")
     if not args.no_finetune and wl.patch % 4 == 0 and want("finetune"):
         out["finetune_prep"] = time_finetune(args, mae, torch, w)
+    if want("odd_patch"):
+        out["odd_patch_prep"] = time_odd_patch(args, mae, torch, w)
     if not args.no_configs and want("stages"):
         out["stages"] = time_stages(args, mae, torch, w)
     if not args.no_cpu_baseline:

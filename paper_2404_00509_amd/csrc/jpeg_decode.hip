@@ -17,7 +17,7 @@
 //    MCUs, and, for files with a restart interval per row, the restart markers (16 bytes per lane
 //    and step, positions ranked with a prefix sum) = the states at which the rows start.  The
 //    crop record is rewritten relative to the decoded region.
-//  * jpeg_scan_kernel (other files): one lane per file, eight files per wavefront with their
+//  * jpeg_scan_kernel (other files): one lane per file, sixteen files per wavefront with their
 //    tables in LDS, decodes code lengths and DC differences only, handles restart markers where
 //    they come, and records the state of the bit reader and the DC predictors at the start of
 //    each of the crop's rows of MCUs.
