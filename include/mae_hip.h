@@ -234,7 +234,8 @@ size_t mae_loss_workspace_bytes(const mae_loss_desc* d);
  * more than 8192 partial sums is rejected with MAE_ERR_WORKSPACE before anything is launched
  * (today's launch shapes stay below that for every valid descriptor).  All calls on one GPU share
  * the array: calls that overlap on one GPU (different streams, different threads) race; order
- * them on one stream.  Nothing in the array has to be cleared between calls. */
+ * them on one stream.  Nothing in the array has to be cleared between calls.  The first call on a
+ * device looks up the array's device address (no stream work); make it before a capture starts. */
 int mae_normpix_loss_static(const mae_loss_desc* d, float* loss, void* grad, void* hip_stream);
 
 /* ------------------------------------------------------------------------------------------------

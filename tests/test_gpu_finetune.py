@@ -106,6 +106,48 @@ def test_shard_of_a_batch_and_reproducibility():
     assert torch.equal(part.ids_restore, full.ids_restore[8:])
 
 
+def test_three_aug_plus_on_a_side_stream_and_in_a_captured_graph():
+    # the mode's four launches (two passes each of the resampling and the blur kernel) enqueue
+    # kernels only, so the call can be captured; every replay is checked against the oracle
+    S, B = 160, 12
+    L = (S // 16) ** 2
+    data = synth.make_images("gradient", B, seed=61)
+    kw = dict(out_size=S, patch=16, num_keep=L, seed=10, batch_index=5,
+              aug_mode=mae.MAE_AUG_THREE_PLUS, jitter=0.3)
+    ref = oracle.prep_batch(*data, **kw)
+    assert set(_ops(10, 5, B)) == {0, 1, 2}
+    buf, desc, _ = gpu_prep(*data, **kw)
+
+    def call(stream):
+        mae.mae_prep_batch(desc, buf.visible, buf.mask, buf.ids_restore, buf.ids_keep, buf.target,
+                           buf.crop, buf.workspace, stream=stream)
+
+    def wipe():
+        buf.visible.fill_(float("nan"))
+        buf.target.fill_(float("nan"))
+        buf.ids_restore.fill_(-1)
+        torch.cuda.synchronize()
+
+    side = torch.cuda.Stream()
+    wipe()
+    with torch.cuda.stream(side):
+        call(side)
+    side.synchronize()
+    check_prep_against_oracle(prep_to_numpy(buf), ref, what="side stream")
+
+    graph = torch.cuda.CUDAGraph()
+    wipe()
+    with torch.cuda.graph(graph):
+        call(torch.cuda.current_stream())
+    for replay in range(3):
+        wipe()
+        graph.replay()
+        torch.cuda.synchronize()
+        check_prep_against_oracle(prep_to_numpy(buf), ref, what=f"graph replay {replay}")
+        buf.target.mul_(1.0)  # eager work between replays
+        torch.cuda.synchronize()
+
+
 @pytest.mark.parametrize("mode", [mae.MAE_AUG_THREE, mae.MAE_AUG_THREE_PLUS])
 def test_full_size_batch_every_image(mode):
     """The bench's launch (B = 4096, 224 px, every patch kept): every image against the oracle."""

@@ -70,3 +70,31 @@ def test_static_scratch_loss_only_and_argument_errors():
     with pytest.raises(mae.MaeError) as e:
         mae.mae_normpix_loss_static(desc, b, None)
     assert e.value.status == mae.binding.MAE_ERR_RANGE
+
+
+def test_static_scratch_in_a_captured_graph():
+    # what the entry point is for: a caller under graph capture.  The first call on a device
+    # looks up the array's address, so one call is made before the capture starts.
+    pred, target, mask, _, mask_host = _inputs(11, 24, 100, 768, False)
+    desc = mae.make_loss_desc(pred, target, mask, num_masked=0)  # divisor counted on the device
+    ws = torch.empty(max(mae.mae_loss_workspace_bytes(desc), 256), dtype=torch.uint8, device="cuda")
+    loss_ref = torch.zeros(1, device="cuda")
+    grad_ref = torch.empty_like(pred)
+    mae.mae_normpix_loss(desc, loss_ref, grad_ref, ws)
+    loss = torch.zeros(1, device="cuda")
+    grad = torch.empty_like(pred)
+    mae.mae_normpix_loss_static(desc, loss, grad)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        mae.mae_normpix_loss_static(desc, loss, grad, stream=torch.cuda.current_stream())
+    for replay in range(3):
+        loss.fill_(float("nan"))
+        grad.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(loss, loss_ref), replay
+        assert torch.equal(grad.view(torch.int32), grad_ref.view(torch.int32)), replay
+        grad_ref.mul_(1.0)  # eager work between replays
+        torch.cuda.synchronize()
