@@ -222,10 +222,17 @@ struct BitReader {
 // The 16 bytes at `base + at` (8-byte aligned) of a buffer of `bytes` bytes; bytes beyond its end
 // read as zero.
 __device__ static inline u32x4_a8 load_chunk(const uint8_t* base, int64_t bytes, int64_t at) {
-  if (at + 16 <= bytes) return *reinterpret_cast<const u32x4_a8*>(base + at);
+  if (__builtin_expect(at + 16 <= bytes, 1)) return *reinterpret_cast<const u32x4_a8*>(base + at);
+  // the last bytes of the buffer of files: a rolled loop, this code is inlined in many places
   uint32_t w[4] = {0u, 0u, 0u, 0u};
-  for (int i = 0; i < 16; ++i)
-    if (at + i < bytes) w[i >> 2] |= (uint32_t)base[at + i] << (8 * (i & 3));
+#pragma unroll 1
+  for (int j = 0; j < 4; ++j) {
+    uint32_t v = 0;
+#pragma unroll 1
+    for (int i = 0; i < 4; ++i)
+      if (at + 4 * j + i < bytes) v |= (uint32_t)base[at + 4 * j + i] << (8 * i);
+    w[j] = v;
+  }
   return u32x4_a8{w[0], w[1], w[2], w[3]};
 }
 __device__ static __forceinline__ void request_bytes(BitReader& r) {
