@@ -479,11 +479,13 @@ def time_without_target(args, mae, torch, w, want_loss):
     }
 
 
-def time_jpeg(args, mae, synth, torch, w, kind=None, restart_rows=1, name="jpeg_prep"):
+def time_jpeg(args, mae, synth, torch, w, kind=None, restart_rows=1, name="jpeg_prep",
+              indexed=False):
     """mae_prep_batch fed with JPEG files ("crop decode", Sec. 4.1): the same batch written as
     baseline JPEG (quality 90, 4:2:0; one restart interval per row of MCUs, or no restart markers
     at all, which is what an encoder writes by default), timed by itself with events on the
-    launch stream.  Not part of the step above."""
+    launch stream.  indexed: the call is given the files' row index, which mae_jpeg_index computes
+    once (timed beside it).  Not part of the step above."""
     import numpy as np
 
     wl, K = w.wl, w.K
@@ -493,12 +495,21 @@ def time_jpeg(args, mae, synth, torch, w, kind=None, restart_rows=1, name="jpeg_
     files, offsets, sizes = synth.make_jpegs(kind, B, seed=0, restart_rows=restart_rows)
     enc_s = time.time() - t0
     dev = [torch.from_numpy(a).cuda() for a in (files, offsets, sizes)]
-    desc = mae.make_prep_desc(dev[0], dev[1], None, None, file_sizes=dev[2], out_size=wl.out_size,
-                              patch=wl.patch, num_keep=K, seed=0, batch_index=0,
-                              max_image_side=512 if kind == "gradient500" else 0,
-                              out_dtype=mae.MAE_BF16 if wl.dtype == "bf16" else mae.MAE_F32)
-    buf = mae.alloc_prep_buffers(desc)
     stream = torch.cuda.current_stream()
+    kw = dict(file_sizes=dev[2], out_size=wl.out_size, patch=wl.patch, num_keep=K, seed=0,
+              batch_index=0, max_image_side=512 if kind == "gradient500" else 0,
+              out_dtype=mae.MAE_BF16 if wl.dtype == "bf16" else mae.MAE_F32)
+    index, index_ms = None, None
+    if indexed:
+        # the files' row index: computed once per file (here: once, timed), reused by every call
+        d0 = mae.make_prep_desc(dev[0], dev[1], None, None, **kw)
+        index = torch.empty(mae.mae_jpeg_index_bytes(d0), dtype=torch.uint8, device="cuda")
+        ws0 = torch.empty(mae.mae_prep_workspace_bytes(d0), dtype=torch.uint8, device="cuda")
+        index_ms = stats(timed(torch, stream, lambda i: mae.mae_jpeg_index(d0, index, ws0,
+                                                                           stream=stream), 3, 1))
+        del ws0
+    desc = mae.make_prep_desc(dev[0], dev[1], None, None, row_index=index, **kw)
+    buf = mae.alloc_prep_buffers(desc)
 
     def run(i):
         desc.batch_index = i
@@ -519,6 +530,10 @@ def time_jpeg(args, mae, synth, torch, w, kind=None, restart_rows=1, name="jpeg_
         "mean_crop_area_px": round(float((crop[:, 2] * crop[:, 3]).mean()), 1),
         "roofline": alu_roofline("jpeg", name, st["avg_ms"]),
     })
+    if indexed:
+        out["input"] += ", with the files' row index (mae_jpeg_index)"
+        out["index_once"] = dict(index_ms, bytes=int(index.numel()),
+                                 what="mae_jpeg_index over the batch's files, once per file")
     if not args.no_cpu_baseline and name == "jpeg_prep":
         # the oracle beside it: whole-file decode (its definition of the input) of a small sample
         import oracle
@@ -593,7 +608,7 @@ def main() -> int:
                     help="skip the other workloads ('configs') and the schedules ('stages')")
     ap.add_argument("--only", default="",
                     help="comma-separated extras to run after the steps instead of all of them "
-                         "(embed, jpeg, jpeg_no_markers, jpeg_500, finetune, configs, stages, "
+                         "(embed, jpeg, jpeg_no_markers, jpeg_indexed, jpeg_500, finetune, configs, stages, "
                          "without_target, odd_patch, none); for profiling runs")
     ap.add_argument("--source-hashes", action="store_true",
                     help="print the hashes that key the rows of profiles/counters.md and exit")
@@ -678,6 +693,10 @@ def main() -> int:
         if want("jpeg_no_markers"):
             out["jpeg_prep_no_markers"] = time_jpeg(args, mae, synth, torch, w, restart_rows=0,
                                                     name="jpeg_prep_no_markers")
+        if want("jpeg_indexed"):
+            out["jpeg_prep_no_markers_indexed"] = time_jpeg(
+                args, mae, synth, torch, w, restart_rows=0, name="jpeg_prep_no_markers_indexed",
+                indexed=True)
         if want("jpeg_500"):
             # the paper's crop-decode benchmark reads files of maximum side 500 (Sec. 4.1)
             out["jpeg_prep_500"] = time_jpeg(args, mae, synth, torch, w, kind="gradient500",

@@ -91,9 +91,12 @@ typedef enum { MAE_AUG_SIMPLE = 0, MAE_AUG_THREE = 1, MAE_AUG_THREE_PLUS = 2 } m
  * their tables, any restart interval or none, and no side longer than max_image_side rounded up
  * to 16 (in this mode the hint is a limit; 0 = 256).  A file with one restart interval per row
  * of MCUs (a choice of the dataset writer that costs 0.2 % in size) has independent rows, and
- * those outside the crop are never touched; in any other file the entropy-coded data above the
- * crop has to be walked through once (symbol lengths only), which costs about as much again as
- * the decoding itself.  Any other file makes its sample invalid
+ * those outside the crop are never touched; in any other file the entropy-coded data has to be
+ * walked through from its start down to the crop's last row to find where the rows begin (symbol
+ * lengths only, one lane per file: several times the cost of the decoding itself), unless the
+ * caller passes the file's row index (mae_jpeg_index, jpeg_row_index below), which is computed
+ * once per file and makes every file decode like one with independent rows.  Any other file makes
+ * its sample invalid
  * (valid = 0 in crop_out, counted by mae_prep_status).  A decoder is specified by the standard
  * only up to the accuracy of the inverse DCT, the chroma interpolation and the colour arithmetic;
  * here: 13-bit fixed-point separable inverse DCT (first pass kept with 3 fractional bits, inputs
@@ -150,6 +153,13 @@ typedef struct {
                               offsets[b] the start of file b; heights and widths are not read
                               (may be NULL)                                                      */
   const int32_t* file_sizes; /* [B] length of each file in bytes; MAE_INPUT_JPEG only            */
+  const void* jpeg_row_index; /* nullable, MAE_INPUT_JPEG only: [B] entries of
+                              mae_jpeg_index_bytes(d) / B bytes each, entry b being what
+                              mae_jpeg_index wrote for file b (with the same max_image_side);
+                              16-byte aligned.  With it no file is walked through.  Entries are
+                              checked before use: one that does not fit its file gives a sample
+                              flagged invalid or wrong pixels, never an access outside the
+                              buffers                                                           */
 } mae_prep_desc;
 
 /* Outputs (device):
@@ -177,6 +187,23 @@ int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t
  * a square of side max_image_side rounded up to 16 (0 = 256), per image (an upper bound: which
  * part of it a call touches depends on the crops it draws), and about 6 KB of tables per image. */
 size_t mae_prep_workspace_bytes(const mae_prep_desc* d);
+
+/* Row index of JPEG files (crop decode, Sec. 4.1: the loader decodes only the crop's region; Sec.
+ * 4.2: datasets are prepared once).  For every file of the descriptor (input_format must be
+ * MAE_INPUT_JPEG; the crop, output and augmentation fields are validated but not used) and every
+ * row of MCUs of it: where the row's entropy-coded data starts -- byte position, pending bits,
+ * DC predictors, MCUs left in the restart interval -- 32 bytes per row,
+ * (max_image_side rounded up to 16) / 8 rows per file whatever the file's size, rows the file
+ * does not have and every row of a file the decoder does not take marked unknown.  An entry
+ * depends on nothing but its file, so it is computed once per file, stored with it, and gathered
+ * per batch like the file itself into `jpeg_row_index` of later mae_prep_batch calls.  The format
+ * of an entry belongs to this version of the library (mae_version).
+ *   index      mae_jpeg_index_bytes(d) bytes, 16-byte aligned, device      required
+ *   workspace  mae_prep_workspace_bytes(d) bytes, 256-byte aligned         required
+ * mae_jpeg_index_bytes returns 0 for an invalid descriptor. */
+size_t mae_jpeg_index_bytes(const mae_prep_desc* d);
+int mae_jpeg_index(const mae_prep_desc* d, void* index, size_t index_bytes, void* workspace,
+                   size_t workspace_bytes, void* hip_stream);
 
 /* Waits for `hip_stream`, then stores in *host_invalid_samples how many samples of the last
  * mae_prep_batch call on this workspace failed the device-side geometry check.  Synchronises. */

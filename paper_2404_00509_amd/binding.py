@@ -29,6 +29,7 @@ IMAGENET_STD = (0.229, 0.224, 0.225)
 
 # Entry points declared in include/mae_hip.h.
 EXPORTS = ("mae_prep_batch", "mae_prep_workspace_bytes", "mae_prep_status", "mae_num_keep",
+           "mae_jpeg_index", "mae_jpeg_index_bytes",
            "mae_normpix_loss", "mae_loss_workspace_bytes", "mae_normpix_loss_static",
            "mae_normpix_loss_from_images",
            "mae_loss_from_images_workspace_bytes", "mae_patch_embed", "mae_pretrain_stage",
@@ -63,6 +64,7 @@ class MaePrepDesc(C.Structure):
         ("jitter", C.c_float),
         ("input_format", C.c_int32),
         ("file_sizes", C.c_void_p),
+        ("jpeg_row_index", C.c_void_p),
     ]
 
 
@@ -121,6 +123,11 @@ def load():
         lib.mae_prep_workspace_bytes.argtypes = [C.POINTER(MaePrepDesc)]
         lib.mae_prep_status.restype = C.c_int
         lib.mae_prep_status.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32)]
+        lib.mae_jpeg_index_bytes.restype = C.c_size_t
+        lib.mae_jpeg_index_bytes.argtypes = [C.POINTER(MaePrepDesc)]
+        lib.mae_jpeg_index.restype = C.c_int
+        lib.mae_jpeg_index.argtypes = [C.POINTER(MaePrepDesc), C.c_void_p, C.c_size_t, C.c_void_p,
+                                       C.c_size_t, C.c_void_p]
         lib.mae_num_keep.restype = C.c_int32
         lib.mae_num_keep.argtypes = [C.c_int32, C.c_double]
         lib.mae_normpix_loss.restype = C.c_int
@@ -230,10 +237,11 @@ def make_prep_desc(images, offsets, heights, widths, *, out_size, patch, num_kee
                    scale=(0.2, 1.0), ratio=(3.0 / 4.0, 4.0 / 3.0), flip_p=0.5, mean=IMAGENET_MEAN,
                    std=IMAGENET_STD, seed=0, batch_index=0, sample_base=0, noise_bits=32,
                    out_dtype=MAE_F32, max_image_side=0, aug_mode=0, jitter=0.3,
-                   file_sizes=None) -> MaePrepDesc:
+                   file_sizes=None, row_index=None) -> MaePrepDesc:
     """Decoded input: images / offsets / heights / widths as device tensors.  JPEG input ("crop
     decode"): images = the files back to back, offsets = their starts, file_sizes = their lengths
-    (int32); heights and widths are then ignored (pass None)."""
+    (int32); heights and widths are then ignored (pass None).  row_index: what mae_jpeg_index
+    wrote for these files with the same max_image_side (uint8 tensor), or None."""
     _check(images, "images", torch.uint8)
     _check(offsets, "offsets", torch.int64)
     if file_sizes is None:
@@ -265,7 +273,27 @@ def make_prep_desc(images, offsets, heights, widths, *, out_size, patch, num_kee
     d.noise_bits, d.out_dtype = noise_bits, out_dtype
     d.max_image_side = max_image_side
     d.aug_mode, d.jitter = aug_mode, jitter
+    if row_index is not None:
+        if file_sizes is None:
+            raise ValueError("row_index goes with JPEG input (file_sizes)")
+        _check(row_index, "row_index", torch.uint8, numel=mae_jpeg_index_bytes(d))
+        d.jpeg_row_index = row_index.data_ptr()
     return d
+
+
+def mae_jpeg_index_bytes(desc: MaePrepDesc) -> int:
+    return int(load().mae_jpeg_index_bytes(C.byref(desc)))
+
+
+def mae_jpeg_index(desc: MaePrepDesc, index, workspace, stream=None) -> None:
+    """Enqueue the computation of the row index of the descriptor's JPEG files into `index`
+    (uint8 device tensor of mae_jpeg_index_bytes(desc) bytes)."""
+    _check(index, "index", torch.uint8, numel=mae_jpeg_index_bytes(desc))
+    _check(workspace, "workspace")
+    rc = load().mae_jpeg_index(C.byref(desc), _ptr(index), index.numel(), _ptr(workspace),
+                               workspace.numel() * workspace.element_size(), _stream(stream))
+    if rc != MAE_OK:
+        raise MaeError(rc, "mae_jpeg_index")
 
 
 def mae_prep_workspace_bytes(desc: MaePrepDesc) -> int:

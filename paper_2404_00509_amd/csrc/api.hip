@@ -14,7 +14,7 @@
 
 namespace {
 
-constexpr int kVersion = 500;  // 0.5.0
+constexpr int kVersion = 600;  // 0.6.0
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -32,6 +32,9 @@ int validate_prep(const mae_prep_desc* d, PrepShape* shape) {
   if (d->input_format == MAE_INPUT_JPEG && !d->file_sizes) return MAE_ERR_NULL;
   // the decoder reads the files through aligned 8-byte windows
   if (d->input_format == MAE_INPUT_JPEG && !aligned(d->images, 8)) return MAE_ERR_RANGE;
+  if (d->jpeg_row_index &&
+      (d->input_format != MAE_INPUT_JPEG || !aligned(d->jpeg_row_index, 16)))
+    return MAE_ERR_RANGE;
   if (d->B <= 0 || d->out_size <= 0 || d->patch <= 0) return MAE_ERR_SHAPE;
   if (d->B > (1 << 20)) return MAE_ERR_RANGE;  // keeps every grid size below 2^31
   if (d->out_size % d->patch != 0) return MAE_ERR_SHAPE;
@@ -201,6 +204,33 @@ PrepWorkspace prep_workspace(const mae_prep_desc* d) {
   }
   return w;
 }
+// The crop-decode kernels' view of the descriptor and the workspace.
+mae::JpegArgs make_jpeg_args(const mae_prep_desc* d, const PrepWorkspace& wsl, uint8_t* ws,
+                             int32_t* crop_out) {
+  mae::JpegArgs ja;
+  memset(&ja, 0, sizeof(ja));
+  ja.B = d->B;
+  ja.slot_side = wsl.slot_side;
+  ja.files = d->images;
+  ja.files_bytes = d->images_bytes;
+  ja.offsets = d->offsets;
+  ja.sizes = d->file_sizes;
+  ja.recs = reinterpret_cast<mae::JpegRec*>(ws + wsl.recs_offset);
+  ja.heights = reinterpret_cast<int32_t*>(ws + wsl.heights_offset);
+  ja.widths = reinterpret_cast<int32_t*>(ws + wsl.widths_offset);
+  ja.region_offsets = reinterpret_cast<int64_t*>(ws + wsl.region_offsets_offset);
+  ja.region_widths = reinterpret_cast<int32_t*>(ws + wsl.region_widths_offset);
+  ja.prepared = ws + wsl.prepared_offset;
+  ja.row_states = ws + wsl.row_states_offset;
+  ja.max_rows = wsl.max_rows;
+  ja.planes = ws + wsl.planes_offset;
+  ja.regions = ws + wsl.regions_offset;
+  ja.workspace = ws;
+  ja.crop_out = crop_out;
+  ja.row_index = static_cast<const uint8_t*>(d->jpeg_row_index);
+  ja.whole_image = 0;
+  return ja;
+}
 // What the resampling kernel needs to know about the source, for both input formats: with JPEG
 // input its "images" are the decoded regions in the workspace.
 mae::CropArgs make_crop_args(const mae_prep_desc* d, const PrepShape& sh, const PrepWorkspace& wsl,
@@ -283,24 +313,7 @@ int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t
   memset(&ja, 0, sizeof(ja));
   if (d->input_format == MAE_INPUT_JPEG) {
     // file headers first: the crop parameters need the image sizes
-    ja.B = d->B;
-    ja.slot_side = wsl.slot_side;
-    ja.files = d->images;
-    ja.files_bytes = d->images_bytes;
-    ja.offsets = d->offsets;
-    ja.sizes = d->file_sizes;
-    ja.recs = reinterpret_cast<mae::JpegRec*>(ws + wsl.recs_offset);
-    ja.heights = reinterpret_cast<int32_t*>(ws + wsl.heights_offset);
-    ja.widths = reinterpret_cast<int32_t*>(ws + wsl.widths_offset);
-    ja.region_offsets = reinterpret_cast<int64_t*>(ws + wsl.region_offsets_offset);
-    ja.region_widths = reinterpret_cast<int32_t*>(ws + wsl.region_widths_offset);
-    ja.prepared = ws + wsl.prepared_offset;
-    ja.row_states = ws + wsl.row_states_offset;
-    ja.max_rows = wsl.max_rows;
-    ja.planes = ws + wsl.planes_offset;
-    ja.regions = ws + wsl.regions_offset;
-    ja.workspace = ws;
-    ja.crop_out = crop_out;
+    ja = make_jpeg_args(d, wsl, ws, crop_out);
     if (mae::launch_jpeg_header(ja, stream) != hipSuccess) return MAE_ERR_HIP;
     // from here on the "images" are the slots of the decoded-region buffer
     pa.images_bytes = (int64_t)d->B * wsl.slot_side * wsl.slot_side * 3;
@@ -380,6 +393,35 @@ int mae_prep_batch(const mae_prep_desc* d, void* visible, uint8_t* mask, int32_t
   }
   if (err == hipSuccess) err = mae::launch_aug_blur(aa, false, stream);
   return err == hipSuccess ? MAE_OK : MAE_ERR_HIP;
+}
+
+size_t mae_jpeg_index_bytes(const mae_prep_desc* d) {
+  if (validate_prep(d, nullptr) != MAE_OK || d->input_format != MAE_INPUT_JPEG) return 0;
+  const PrepWorkspace wsl = prep_workspace(d);
+  return (size_t)d->B * (size_t)wsl.max_rows * mae::jpeg_row_state_bytes();
+}
+
+int mae_jpeg_index(const mae_prep_desc* d, void* index, size_t index_bytes, void* workspace,
+                   size_t workspace_bytes, void* hip_stream) {
+  int rc = validate_prep(d, nullptr);
+  if (rc != MAE_OK) return rc;
+  if (d->input_format != MAE_INPUT_JPEG) return MAE_ERR_RANGE;
+  if (!index || !workspace) return MAE_ERR_NULL;
+  if (!aligned(index, 16) || !aligned(workspace, 256)) return MAE_ERR_RANGE;
+  const PrepWorkspace wsl = prep_workspace(d);
+  if (index_bytes < (size_t)d->B * (size_t)wsl.max_rows * mae::jpeg_row_state_bytes() ||
+      workspace_bytes < wsl.total)
+    return MAE_ERR_WORKSPACE;
+  rc = have_device();
+  if (rc != MAE_OK) return rc;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  mae::JpegArgs ja = make_jpeg_args(d, wsl, static_cast<uint8_t*>(workspace), nullptr);
+  ja.row_states = static_cast<uint8_t*>(index);  // every row of every file: the index itself
+  ja.row_index = nullptr;
+  ja.whole_image = 1;
+  if (mae::launch_jpeg_header(ja, stream) != hipSuccess) return MAE_ERR_HIP;
+  if (mae::launch_jpeg_index(ja, stream) != hipSuccess) return MAE_ERR_HIP;
+  return MAE_OK;
 }
 
 int mae_prep_status(const void* workspace, void* hip_stream, int32_t* host_invalid_samples) {

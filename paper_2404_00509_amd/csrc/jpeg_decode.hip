@@ -525,9 +525,28 @@ __device__ static void jpeg_prepare_image(const JpegArgs& a, int b, JpegImage& i
   const int lane = threadIdx.x;
   const JpegRec rec = a.recs[b];
   CropRec* crop = reinterpret_cast<CropRec*>(a.workspace + kWorkspaceHeader) + b;
-  const CropRec cr = *crop;
+  CropRec cr = *crop;
   RowState* states = reinterpret_cast<RowState*>(a.row_states) + (int64_t)b * a.max_rows;
   __syncthreads();  // everybody has read the record before lane 0 rewrites it
+  if (a.whole_image) {
+    // index run: the "crop" is the whole image, and every row of the index gets a defined value
+    // whatever becomes of the file
+    cr.top = 0;
+    cr.left = 0;
+    cr.ch = rec.H;
+    cr.cw = rec.W;
+    cr.flip = 0;
+    cr.valid = 1;
+    RowState none;
+    none.pos = -1;
+    none.nbits = 0;
+    none.acc = 0;
+    none.pred[0] = none.pred[1] = none.pred[2] = 0;
+    none.rst_left = 0;
+    none.pad = 0;
+    for (int i = lane; i < a.max_rows; i += kJpegThreads) states[i] = none;
+    __syncthreads();
+  }
   if (!rec.valid) {
     if (lane == 0) {
       crop->valid = 0;
@@ -629,6 +648,20 @@ __device__ static void jpeg_prepare_image(const JpegArgs& a, int b, JpegImage& i
     for (int i = lane; i < nrows; i += kJpegThreads) states[i] = none;
   }
   __syncthreads();  // (these stores are complete before a row's real state is written)
+  if (a.row_index) {
+    // the states come from the caller's index of the file (row r of the file at entry r).  It is
+    // the caller's memory: an entry that does not point into the entropy-coded data or whose bit
+    // count is impossible is left unknown, which flags the sample in the decode kernel.
+    const RowState* index = reinterpret_cast<const RowState*>(a.row_index) + (int64_t)b * a.max_rows;
+    const int nrows = min(my1 - my0 + 1, a.max_rows);
+    for (int i = lane; i < nrows; i += kJpegThreads) {
+      if (my0 + i >= a.max_rows) continue;
+      RowState st = index[my0 + i];
+      const bool ok = st.pos >= rec.scan_off && st.pos <= n && st.nbits >= 0 && st.nbits <= 64;
+      if (ok) states[i] = st;
+    }
+    return;
+  }
   if (rec.restart != rec.mcux) return;  // rows not independent: the scan kernel finds the states
 
   // restart markers: marker m (0-based) ends MCU row m; row r starts after marker r - 1.  The
@@ -812,7 +845,7 @@ __global__ __launch_bounds__(kJpegThreads) void jpeg_scan_kernel(JpegArgs a) {
   if (lane < nimg) {
     const JpegRec rec = a.recs[b0 + lane];
     const CropRec cr = reinterpret_cast<const CropRec*>(a.workspace + kWorkspaceHeader)[b0 + lane];
-    need = rec.valid && cr.valid && rec.restart != rec.mcux;
+    need = rec.valid && (cr.valid || a.whole_image) && rec.restart != rec.mcux && !a.row_index;
   }
   if (__builtin_amdgcn_ballot_w64(need) == 0) return;  // every file here has independent rows
   {
@@ -1060,6 +1093,16 @@ __global__ __launch_bounds__(kColourThreads) void jpeg_colour_kernel(JpegArgs a,
     dst[1] = (px[1] >> 8) | (px[2] << 16);
     dst[2] = (px[2] >> 16) | (px[3] << 8);
   }
+}
+
+hipError_t launch_jpeg_index(const JpegArgs& a, hipStream_t stream) {
+  dim3 block(kJpegThreads);
+  hipLaunchKernelGGL(jpeg_tables_kernel, dim3((uint32_t)a.B), block, 0, stream, a);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  hipLaunchKernelGGL(jpeg_scan_kernel, dim3((uint32_t)((a.B + kScanImages - 1) / kScanImages)),
+                     block, 0, stream, a);
+  return hipGetLastError();
 }
 
 hipError_t launch_jpeg_decode(const JpegArgs& a, hipStream_t stream) {

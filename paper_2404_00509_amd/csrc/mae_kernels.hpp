@@ -150,11 +150,18 @@ struct JpegArgs {
   uint8_t* regions;
   uint8_t* workspace;  // header + CropRec[B]
   int32_t* crop_out;   // nullable, [B,6]: the valid flag is cleared for files that cannot be used
+  // nullable: per image max_rows row states for rows of MCUs 0, 1, ... of the whole file, as an
+  // earlier index run left them (the caller's memory: checked before use)
+  const uint8_t* row_index;
+  int32_t whole_image;  // index run: every row of every file is wanted, there are no crop records
 };
 size_t jpeg_prepared_bytes();  // per image, in the workspace
 size_t jpeg_row_state_bytes();  // per row of MCUs, in the workspace
 hipError_t launch_jpeg_header(const JpegArgs& a, hipStream_t stream);
 hipError_t launch_jpeg_decode(const JpegArgs& a, hipStream_t stream);
+// Index run (after launch_jpeg_header): the row states of every row of MCUs of every file go to
+// a.row_states; nothing is decoded.
+hipError_t launch_jpeg_index(const JpegArgs& a, hipStream_t stream);
 
 // ---- normalised-pixel loss ---------------------------------------------------------------------
 struct LossArgs {

@@ -173,6 +173,31 @@ def test_jpeg_input_needs_no_sizes_and_a_slot_per_image(lib):
     assert lib.mae_prep_workspace_bytes(C.byref(_prep_desc(file_sizes=FAKE))) == 256 + B * 32
 
 
+def test_jpeg_row_index_sizes_and_argument_errors(lib):
+    """32 bytes per 8 pixels of the side limit and file; only JPEG descriptors have an index; the
+    index call checks its buffers before it touches the device."""
+    B = 4
+    for side, slot in ((0, 256), (500, 512)):
+        d = _jpeg_desc(max_image_side=side)
+        assert lib.mae_jpeg_index_bytes(C.byref(d)) == B * (slot // 8) * 32
+    assert lib.mae_jpeg_index_bytes(C.byref(_prep_desc())) == 0      # decoded input
+    assert lib.mae_jpeg_index_bytes(None) == 0
+    d = _jpeg_desc()
+    need, ws = lib.mae_jpeg_index_bytes(C.byref(d)), lib.mae_prep_workspace_bytes(C.byref(d))
+    call = lambda desc, index=FAKE, nbytes=need, w=FAKE, wbytes=ws: lib.mae_jpeg_index(
+        C.byref(desc), index, nbytes, w, wbytes, None)
+    assert call(_prep_desc()) == binding.MAE_ERR_RANGE               # decoded input
+    assert call(d, index=None) == binding.MAE_ERR_NULL
+    assert call(d, w=None) == binding.MAE_ERR_NULL
+    assert call(d, index=FAKE + 8) == binding.MAE_ERR_RANGE          # 16-byte alignment
+    assert call(d, nbytes=need - 1) == binding.MAE_ERR_WORKSPACE
+    assert call(d, wbytes=ws - 1) == binding.MAE_ERR_WORKSPACE
+    # the index as an input: JPEG descriptors only, 16-byte aligned
+    assert _call_prep(lib, _prep_desc(jpeg_row_index=FAKE)) == binding.MAE_ERR_RANGE
+    assert _call_prep(lib, _jpeg_desc(jpeg_row_index=FAKE + 8),
+                      ws_bytes=1 << 30) == binding.MAE_ERR_RANGE
+
+
 def test_prep_rejects_bad_buffers(lib):
     d = _prep_desc()
     need = lib.mae_prep_workspace_bytes(C.byref(d))

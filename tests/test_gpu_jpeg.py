@@ -324,3 +324,128 @@ def test_crop_decode_full_size_every_image():
         np.testing.assert_array_equal(buf.crop[lo:hi, :5].cpu().numpy(), ref["crop"], err_msg=what)
         assert_close_device(buf.target[lo:hi], ref["target"], what=what + " target")
         assert_close_device(buf.visible[lo:hi], ref["visible"], what=what + " visible")
+
+
+# ---- the files' row index ------------------------------------------------------------------------
+def _row_index(files, offsets, sizes, max_image_side=0):
+    """mae_jpeg_index over the files: (index tensor [B, bytes per file], device inputs)."""
+    dev = [torch.from_numpy(a).cuda() for a in (files, offsets, sizes)]
+    desc = mae.make_prep_desc(dev[0], dev[1], None, None, file_sizes=dev[2], out_size=32, patch=16,
+                              num_keep=1, max_image_side=max_image_side)
+    index = torch.full((mae.mae_jpeg_index_bytes(desc),), 0xEE, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(mae.mae_prep_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    mae.mae_jpeg_index(desc, index, ws)
+    torch.cuda.synchronize()
+    return index.view(len(sizes), -1), dev
+
+
+def _prep_with_index(dev, index, **kw):
+    desc = mae.make_prep_desc(dev[0], dev[1], None, None, file_sizes=dev[2], row_index=index, **kw)
+    buf = mae.alloc_prep_buffers(desc)
+    buf.visible.fill_(float("nan"))
+    buf.target.fill_(float("nan"))
+    buf.crop.fill_(-7)
+    mae.mae_prep_batch(desc, buf.visible, buf.mask, buf.ids_restore, buf.ids_keep, buf.target,
+                       buf.crop, buf.workspace)
+    torch.cuda.synchronize()
+    return buf
+
+
+@pytest.mark.parametrize("sub", ["4:2:0", "4:4:4"])
+def test_row_index_replaces_the_walk_through_the_file(sub):
+    """The index of a file (computed once, whatever crops come later) gives the decoder the same
+    row starts as walking through the file does: same outputs bit for bit, for files without
+    restart markers, with odd intervals and with a marker per row, mixed in one batch, for
+    several batches of crops, and for a batch gathered from the indexed files in another order."""
+    B, S = 15, 96
+    parts = [synth.make_jpegs("gradient", B, seed=70, subsampling=sub, restart_rows=r,
+                              restart_blocks=k) for r, k in ((0, 0), (1, 0), (0, 3))]
+    pick = np.arange(B) % 3  # file b comes from organisation b mod 3
+    blobs = [parts[pick[b]][0][parts[pick[b]][1][b]:parts[pick[b]][1][b] + parts[pick[b]][2][b]]
+             for b in range(B)]
+    sizes = np.array([len(x) for x in blobs], np.int32)
+    offsets = np.zeros(B, np.int64)
+    offsets[1:] = np.cumsum((sizes.astype(np.int64) + 7) // 8 * 8)[:-1]
+    files = np.zeros(int(offsets[-1] + (sizes[-1] + 7) // 8 * 8), np.uint8)
+    for b in range(B):
+        files[offsets[b]:offsets[b] + sizes[b]] = blobs[b]
+    decoded = _decode_all(files, offsets, sizes)
+    index, dev = _row_index(files, offsets, sizes)
+    L = (S // 16) ** 2
+    for batch_index, scale in ((0, (0.2, 1.0)), (1, (1.0, 1.0)), (2, (0.03, 0.1))):
+        kw = dict(out_size=S, patch=16, num_keep=oracle.num_keep(L, 0.75), scale=scale, seed=23,
+                  batch_index=batch_index)
+        ref = oracle.prep_batch(*decoded, **kw)
+        plain, _ = _gpu_jpeg_prep(files, offsets, sizes, **kw)
+        got = _prep_with_index(dev, index, **kw)
+        assert mae.mae_prep_status(got.workspace) == 0
+        check_prep_against_oracle(prep_to_numpy(got), ref, what=f"index, batch {batch_index}")
+        assert torch.equal(got.target, plain.target) and torch.equal(got.visible, plain.visible)
+    # another batch of the same files: reversed order, index entries gathered like the files
+    order = np.arange(B)[::-1].copy()
+    sizes2 = sizes[order]
+    offsets2 = np.zeros(B, np.int64)
+    offsets2[1:] = np.cumsum((sizes2.astype(np.int64) + 7) // 8 * 8)[:-1]
+    files2 = np.zeros(int(offsets2[-1] + (sizes2[-1] + 7) // 8 * 8), np.uint8)
+    for i, b in enumerate(order):
+        files2[offsets2[i]:offsets2[i] + sizes2[i]] = blobs[b]
+    dev2 = [torch.from_numpy(a).cuda() for a in (files2, offsets2, sizes2)]
+    index2 = index[torch.from_numpy(order).cuda()].contiguous()
+    kw = dict(out_size=S, patch=16, num_keep=L, seed=24, batch_index=5)
+    ref = oracle.prep_batch(*_decode_all(files2, offsets2, sizes2), **kw)
+    got = _prep_with_index(dev2, index2, **kw)
+    assert mae.mae_prep_status(got.workspace) == 0
+    check_prep_against_oracle(prep_to_numpy(got), ref, what="gathered index")
+
+
+def test_row_index_entries_are_checked_before_use():
+    """The index is the caller's memory.  Entries that cannot belong to their file (zeros, noise,
+    the entries of another file) give samples flagged invalid or wrong pixels; the call returns,
+    every output is written, and good entries next to them still decode exactly."""
+    B, S = 12, 64
+    files, offsets, sizes = synth.make_jpegs("gradient", B, seed=71, restart_rows=0)
+    decoded = _decode_all(files, offsets, sizes)
+    index, dev = _row_index(files, offsets, sizes)
+    bad = index.clone()
+    bad[1].zero_()                                       # position 0: before the scan data
+    rng = np.random.default_rng(5)
+    bad[4] = torch.from_numpy(rng.integers(0, 256, bad.shape[1], dtype=np.uint8)).cuda()
+    bad[7] = index[8]                                    # another file's row starts
+    bad[10].fill_(0xFF)                                  # negative position and bit count
+    L = (S // 16) ** 2
+    kw = dict(out_size=S, patch=16, num_keep=L, seed=25, batch_index=0)
+    ref = oracle.prep_batch(*decoded, **kw)
+    got = _prep_with_index(dev, bad.contiguous(), **kw)
+    n_bad = mae.mae_prep_status(got.workspace)
+    assert 3 <= n_bad <= 4            # only another file's entries may decode (to wrong pixels)
+    out = prep_to_numpy(got)
+    assert np.isfinite(out["target"]).all() and np.isfinite(out["visible"]).all()
+    good = np.array([b for b in range(B) if b not in (1, 4, 7, 10)])
+    assert np.all(out["crop"][good, 5] == 1)
+    np.testing.assert_array_equal(out["ids_restore"][good], ref["ids_restore"][good])
+    assert_close_device(got.target[torch.from_numpy(good).cuda()], ref["target"][good],
+                        what="good entries")
+    for b in (1, 4, 10):
+        check_neutral_outputs(got, b)
+
+
+def test_row_index_of_files_the_decoder_does_not_take():
+    """A file that is not decodable gets an index of unknown rows, and so does every row a file
+    does not have; with such an index the sample is flagged exactly as without one."""
+    B = 6
+    files, offsets, sizes = synth.make_jpegs("gradient", B, seed=72, restart_rows=0)
+    files = files.copy()
+    files[offsets[2] + 2:offsets[2] + 40] = 0            # the header of file 2 destroyed
+    index, dev = _row_index(files, offsets, sizes)
+    rows = index.view(B, -1, 32)
+    pos = rows[:, :, :4].contiguous().view(torch.int32).view(B, -1).cpu().numpy()
+    assert np.all(pos[2] == -1)
+    for b in (0, 1, 3, 4, 5):
+        h = oracle.jpeg_decode(files[offsets[b]:offsets[b] + sizes[b]].tobytes()).shape[0]
+        n_rows = (h + 15) // 16
+        assert np.all(pos[b, :n_rows] > 0) and np.all(pos[b, n_rows:] == -1)
+        assert np.all(np.diff(pos[b, :n_rows]) > 0)      # rows follow each other in the file
+    kw = dict(out_size=64, patch=16, num_keep=4, seed=26, batch_index=0)
+    got = _prep_with_index(dev, index, **kw)
+    assert mae.mae_prep_status(got.workspace) == 1
+    assert prep_to_numpy(got)["crop"][2, 5] == 0
