@@ -52,10 +52,15 @@ COUNTERS_FILE = os.path.join(ROOT, "profiles", "counters.md")
 
 
 def source_hash(key):
+    """Hash of the code of the sources behind a counter row: `//` comments, indentation and empty
+    lines do not count, so that rewording a comment does not retire the measurements."""
     h = hashlib.sha256()
     for rel in COUNTER_SOURCES[key]:
-        with open(os.path.join(ROOT, rel), "rb") as f:
-            h.update(f.read())
+        with open(os.path.join(ROOT, rel), "r") as f:
+            for line in f:
+                code = line.split("//", 1)[0].strip()
+                if code:
+                    h.update(code.encode() + b"\n")
     return h.hexdigest()[:16]
 
 

@@ -19,8 +19,10 @@
 //    ds_read2_b32 per row, and one byte-permute per tap row pulls exactly the four bytes needed
 //    out of the two pixel words.  Nothing inside the loop reads global memory, so the stores of
 //    one patch never have to complete before the next patch is computed.
-//  * Variants of the last phase on the same staged tile: the rounded 8-bit patch rows for the
-//    finetuning augmentation; the kept patches only (no target wanted); and the loss itself
+//  * Variants of the last phase on the same staged tile: the finetuning augmentation as the
+//    epilogue (produce_aug: values rounded to bytes in integers, grayscale / solarisation, colour
+//    jitter; only the images that drew the blur leave as bytes for the blur kernel); the kept
+//    patches only (no target wanted); and the loss itself
 //    (produce_loss_wave, produce_loss): the masked patches' values stay in registers, are
 //    normalised per patch and compared with the prediction, so that no float target is ever
 //    stored or read back.

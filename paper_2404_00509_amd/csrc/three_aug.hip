@@ -18,7 +18,8 @@
 //  * Horizontal pass, folded into the walk over the part in output order: a lane reads the
 //    4 + 2 R pixels around its four with aligned 16-byte LDS reads and applies the taps.
 // R is the smallest of 2, 4, 6 that holds the image's radius ceil(3 sigma), so that an image with
-// a small sigma does not pay for 13 taps.
+// a small sigma does not pay for 13 taps.  The taps themselves come with the image's draws from
+// the parameter kernel (one record per image) and sit in scalar registers.
 // The contrast step needs the mean luma of the whole image after the brightness step: with jitter
 // on, a first launch of the same kernel (kReduce) only accumulates that sum per part in double
 // precision, and the second launch adds the partial sums of its image in fixed order.
