@@ -449,3 +449,44 @@ def test_row_index_of_files_the_decoder_does_not_take():
     got = _prep_with_index(dev, index, **kw)
     assert mae.mae_prep_status(got.workspace) == 1
     assert prep_to_numpy(got)["crop"][2, 5] == 0
+
+
+def test_row_index_with_large_files_augmentation_and_the_loss_without_target():
+    """The index under the other modes of the call: files of maximum side 500 (two images per
+    wavefront in the decode kernel, 64 index rows per file), the finetuning augmentation, and the
+    loss that reads the decoded regions again."""
+    B, S = 6, 128
+    files, offsets, sizes = synth.make_jpegs("gradient500", B, seed=73, restart_rows=0)
+    decoded = _decode_all(files, offsets, sizes)
+    index, dev = _row_index(files, offsets, sizes, max_image_side=512)
+    assert index.shape[1] == 64 * 32
+    L = (S // 16) ** 2
+    kw = dict(out_size=S, patch=16, num_keep=L, seed=27, batch_index=1, max_image_side=512,
+              aug_mode=mae.MAE_AUG_THREE_PLUS, jitter=0.3)
+    ref = oracle.prep_batch(*decoded, **{k: v for k, v in kw.items() if k != "max_image_side"})
+    got = _prep_with_index(dev, index, **kw)
+    assert mae.mae_prep_status(got.workspace) == 0
+    check_prep_against_oracle(prep_to_numpy(got), ref, what="index, side 500, 3 Aug+")
+
+    # pretraining step without a stored target on the same files
+    K = oracle.num_keep(L, 0.75)
+    kw = dict(out_size=S, patch=16, num_keep=K, seed=28, batch_index=2, max_image_side=512)
+    ref = oracle.prep_batch(*decoded, **{k: v for k, v in kw.items() if k != "max_image_side"})
+    desc = mae.make_prep_desc(dev[0], dev[1], None, None, file_sizes=dev[2], row_index=index, **kw)
+    buf = mae.alloc_prep_buffers(desc, want_target=False)
+    mae.mae_prep_batch(desc, buf.visible, buf.mask, buf.ids_restore, buf.ids_keep, None, buf.crop,
+                       buf.workspace)
+    M = B * (L - K)
+    pred_host = synth.make_pred(9, B, L, 768)
+    pred = torch.from_numpy(pred_host).cuda()
+    ldesc = mae.make_loss_desc(pred, None, buf.mask, num_masked=M)
+    lws = torch.empty(mae.mae_loss_from_images_workspace_bytes(desc, ldesc), dtype=torch.uint8,
+                      device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    grad = torch.empty_like(pred)
+    mae.mae_normpix_loss_from_images(desc, buf.workspace, ldesc, loss, grad, lws)
+    torch.cuda.synchronize()
+    ref_loss, ref_grad, _ = oracle.normpix_loss(pred_host, ref["target"], ref["mask"], num_masked=M)
+    assert abs(loss.item() - ref_loss) <= 1e-5 + 1e-5 * abs(ref_loss)
+    from helpers import check_grad
+    check_grad(grad.cpu().numpy(), ref_grad, 768, M, what="index + loss from images")
