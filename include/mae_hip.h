@@ -160,6 +160,8 @@ typedef struct {
                               checked before use: one that does not fit its file gives a sample
                               flagged invalid or wrong pixels, never an access outside the
                               buffers                                                           */
+  int64_t jpeg_row_index_bytes; /* size of that buffer; less than mae_jpeg_index_bytes(d) is
+                              refused (MAE_ERR_WORKSPACE)                                       */
 } mae_prep_desc;
 
 /* Outputs (device):

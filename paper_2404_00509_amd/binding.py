@@ -65,6 +65,7 @@ class MaePrepDesc(C.Structure):
         ("input_format", C.c_int32),
         ("file_sizes", C.c_void_p),
         ("jpeg_row_index", C.c_void_p),
+        ("jpeg_row_index_bytes", C.c_int64),
     ]
 
 
@@ -278,6 +279,7 @@ def make_prep_desc(images, offsets, heights, widths, *, out_size, patch, num_kee
             raise ValueError("row_index goes with JPEG input (file_sizes)")
         _check(row_index, "row_index", torch.uint8, numel=mae_jpeg_index_bytes(d))
         d.jpeg_row_index = row_index.data_ptr()
+        d.jpeg_row_index_bytes = int(row_index.numel())
     return d
 
 

@@ -35,6 +35,11 @@ int validate_prep(const mae_prep_desc* d, PrepShape* shape) {
   if (d->jpeg_row_index &&
       (d->input_format != MAE_INPUT_JPEG || !aligned(d->jpeg_row_index, 16)))
     return MAE_ERR_RANGE;
+  if (d->jpeg_row_index && d->B > 0 && d->max_image_side >= 0 && d->max_image_side <= 32767) {
+    // one 32-byte entry per 8 pixels of the side limit (rounded up to 16) and file
+    const int64_t slot = ((d->max_image_side > 0 ? d->max_image_side : 256) + 15) & ~15;
+    if (d->jpeg_row_index_bytes < (int64_t)d->B * (slot / 8) * 32) return MAE_ERR_WORKSPACE;
+  }
   if (d->B <= 0 || d->out_size <= 0 || d->patch <= 0) return MAE_ERR_SHAPE;
   if (d->B > (1 << 20)) return MAE_ERR_RANGE;  // keeps every grid size below 2^31
   if (d->out_size % d->patch != 0) return MAE_ERR_SHAPE;

@@ -194,8 +194,13 @@ def test_jpeg_row_index_sizes_and_argument_errors(lib):
     assert call(d, wbytes=ws - 1) == binding.MAE_ERR_WORKSPACE
     # the index as an input: JPEG descriptors only, 16-byte aligned
     assert _call_prep(lib, _prep_desc(jpeg_row_index=FAKE)) == binding.MAE_ERR_RANGE
-    assert _call_prep(lib, _jpeg_desc(jpeg_row_index=FAKE + 8),
+    assert _call_prep(lib, _jpeg_desc(jpeg_row_index=FAKE + 8, jpeg_row_index_bytes=need),
                       ws_bytes=1 << 30) == binding.MAE_ERR_RANGE
+    # ... and as large as the descriptor's side limit makes it
+    assert _call_prep(lib, _jpeg_desc(jpeg_row_index=FAKE, jpeg_row_index_bytes=need - 1),
+                      ws_bytes=1 << 30) == binding.MAE_ERR_WORKSPACE
+    assert _call_prep(lib, _jpeg_desc(jpeg_row_index=FAKE, jpeg_row_index_bytes=need,
+                                      max_image_side=500), ws_bytes=1 << 32) == binding.MAE_ERR_WORKSPACE
 
 
 def test_prep_rejects_bad_buffers(lib):
