@@ -197,6 +197,7 @@ def run_steps(mae, torch, w, steps, warmup):
         out["traffic"] = traffic_of(profile_counters(key, wl.name))
         if out["traffic"]:
             out["counter_GBps"] = round(out["traffic"] / (st["avg_ms"] * 1e-3) / 1e9, 1)
+            out["counter_frac"] = round(out["counter_GBps"] / HBM_PEAK_GBPS, 4)
         return out
 
     ms_per_step = elapsed * 1e3 / steps
@@ -211,6 +212,11 @@ def run_steps(mae, torch, w, steps, warmup):
                                        / HBM_PEAK_GBPS, 4),
         "loss_value": float(w.loss.item()),
     }
+    counted = [k["traffic"] for k in report["kernels"].values()]
+    if all(counted):  # the step on the bytes the hardware counters saw
+        gbps = sum(counted) / (ms_per_step * 1e-3) / 1e9
+        report["step_counter_GBps"] = round(gbps, 1)
+        report["step_counter_frac_of_hbm_peak"] = round(gbps / HBM_PEAK_GBPS, 4)
     return report, elapsed
 
 
@@ -684,6 +690,8 @@ def main() -> int:
         "kernels": report["kernels"],
         "step_GBps": report["step_GBps"],
         "step_frac_of_hbm_peak": report["step_frac_of_hbm_peak"],
+        "step_counter_GBps": report.get("step_counter_GBps"),
+        "step_counter_frac_of_hbm_peak": report.get("step_counter_frac_of_hbm_peak"),
         "loss_value": report["loss_value"],
         "hbm_copy_ceiling": time_copy(torch, w, 10),
     }
