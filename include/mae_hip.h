@@ -17,12 +17,17 @@
  *                      the masked patches, and its gradient with respect to the prediction.
  *   mae_patch_embed    linear patch embedding of the visible tokens with bias and positional
  *                      embedding (Sec. 2, Sec. 5), on the matrix cores.
+ * mae_prep_batch also takes JPEG files and decodes only the region each crop needs ("crop
+ * decode", Sec. 4.1; mae_jpeg_index prepares files once for it) and applies the finetuning
+ * augmentation (Sec. 4.4); mae_normpix_loss_from_images is the loss without a stored target;
+ * mae_pretrain_stage / mae_finetune_stage / mae_stage_of_epoch are the paper's schedules.
  *
  * Conventions
  *   - Every pointer is a DEVICE pointer unless its name starts with host_.  The descriptor
  *     structs themselves live in host memory and are read during the call only.
  *   - The caller allocates and owns every buffer, the workspace included.  The library keeps no
- *     global state, never allocates or frees device memory and keeps no pointer after a call.
+ *     global state, never allocates or frees device memory and keeps no pointer after a call
+ *     (one exception, stated there: the fixed scratch array of mae_normpix_loss_static).
  *   - Calls validate their arguments on the host, enqueue kernels on `hip_stream` (a hipStream_t
  *     passed as void*, NULL = the default stream) and return without synchronising.  Outputs are
  *     valid once the stream has reached that point.  Calls are re-entrant; two calls that share a
