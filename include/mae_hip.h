@@ -150,8 +150,8 @@ typedef struct {
   int32_t max_image_side;  /* tuning hint: largest H or W in the batch, 0 = 256 (the "maximum
                               side 256" dataset variant).  It sizes the on-chip staging buffer;
                               larger images than hinted stay correct but take a slower path     */
-  int32_t aug_mode;        /* mae_aug_mode.  Other than MAE_AUG_SIMPLE needs p % 4 == 0
-                              (MAE_ERR_SHAPE otherwise)                                         */
+  int32_t aug_mode;        /* mae_aug_mode.  Other than MAE_AUG_SIMPLE needs an even p
+                              (MAE_ERR_SHAPE otherwise; multiples of 4 run fastest)             */
   float jitter;            /* MAE_AUG_THREE_PLUS: strength in [0, 1], 0.3 in the paper            */
   int32_t input_format;    /* mae_input_format.  MAE_INPUT_JPEG: `images` holds the files back to
                               back (8-byte aligned buffer), images_bytes their total size,

@@ -67,8 +67,8 @@ int validate_prep(const mae_prep_desc* d, PrepShape* shape) {
     return MAE_ERR_RANGE;
   if (d->aug_mode != MAE_AUG_SIMPLE) {
     if (!(d->jitter >= 0.0f) || !(d->jitter <= 1.0f)) return MAE_ERR_RANGE;
-    // four-pixel groups (12 bytes) must not straddle rows of a patch
-    if (d->patch % 4 != 0) return MAE_ERR_SHAPE;
+    // groups of four or two pixels must tile the rows of a patch
+    if (d->patch % 2 != 0) return MAE_ERR_SHAPE;
   }
   if (shape) {
     shape->G = (int32_t)G;

@@ -563,10 +563,11 @@ __device__ static void produce_loss_wave(const CropArgs& a, const uint32_t* tile
 // rounded bytes written (patch order) for the blur kernel.
 //
 // Grayscale and the jitter's saturation step need whole pixels, so here a lane takes four
-// neighbouring pixels of a patch row (12 values) instead of four values, and the groups of the
-// part's patches are dealt to the lanes in order.  The 64 x 12 values of a wavefront go through a
-// wavefront-private strip of LDS so that every store instruction still writes 1 KiB of
-// contiguous memory.  Tables: xtab.y = the integer weights den - rx, rx of the two columns as a pair
+// neighbouring pixels of a patch row (12 values) instead of four values -- two pixels when the
+// patch size is even but no multiple of four (p = 14) --, and the groups of the part's patches
+// are dealt to the lanes in order.  The 64 x 12 values of a wavefront go through a
+// wavefront-private strip of LDS so that every store instruction still writes 1 KiB (512 bytes
+// with two pixels per lane) of contiguous memory.  Tables: xtab.y = the integer weights den - rx, rx of the two columns as a pair
 // of 16-bit values, ytab.z / ytab.w = the weights den - ry, ry of the two rows (den = 2 S).
 //
 // Rounding.  The bilinear value is num / den^2,
@@ -628,26 +629,41 @@ __device__ static inline void round_blend3(uint32_t w00, uint32_t w01, uint32_t 
 
 // kPass 0: "3 Aug", or the first pass of "3 Aug+" (kJitter: luma sums only); kPass 1: the second
 // pass of "3 Aug+".  `blur`: this image goes to the blur kernel (bytes only; not called in pass 1).
-template <bool kLds, bool kBf16, bool kJitter, int kPass>
+// kPx: neighbouring pixels of a patch row per lane, 4 when p is a multiple of 4, else 2 (p even):
+// a lane's values are 3 kPx floats = three pieces of kPx floats (16 or 8 bytes).
+template <int kPx>
+struct AugPiece;
+template <>
+struct AugPiece<4> {
+  typedef f32x4 type;
+};
+template <>
+struct AugPiece<2> {
+  typedef float type __attribute__((ext_vector_type(2)));
+};
+
+template <bool kLds, bool kBf16, bool kJitter, int kPass, int kPx>
 __device__ static void produce_aug(const CropArgs& a, const uint32_t* tile, const u32x2* xtab,
                                    const u32x4* ytab, const uint8_t* base, int b, int gy, int gx0,
                                    int npatch, int cw, int my_rank, const AugParams& ap, bool blur,
                                    float mean, float* strips, double* red64, uint32_t tile_id) {
+  typedef typename AugPiece<kPx>::type piece_t;
   constexpr bool kReduce = kJitter && kPass == 0;
+  constexpr int kVals = 3 * kPx;  // values per lane and step
   const int lane = threadIdx.x % kWave;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int p = a.p, D = a.D;
   const int den = 2 * a.S, dd = den * den;
   const float inv_dd = (1.0f / (float)dd) * (1.0f - 1.0f / 2097152.0f);
-  const int gpp = (p * p) >> 2;  // groups of four pixels per patch
+  const int gpp = (p * p) / kPx;  // groups of kPx pixels per patch
   const float inv_gpp = 1.0f / (float)gpp, inv_p = 1.0f / (float)p;
   const int ngroups = npatch * gpp;
   const int l0 = gy * a.G + gx0;
   const bool gray = ap.op == kOpGray;
   // patches of 16 x 16 or 32 x 32 pixels: the 64 groups of a wavefront's step lie in one patch
-  const bool whole = (p & 15) == 0;
+  const bool whole = kPx == 4 && (p & 15) == 0;
   const int gsh = __builtin_ctz(gpp), psh = __builtin_ctz(p);  // used when `whole`
-  float* strip = strips + wave * kStripFloats;
+  float* strip = strips + wave * (kWave * kVals);
   float lsum = 0.0f;
   // this image's rows of the outputs (uniform over the workgroup)
   float* target_image = a.target ? a.target + (int64_t)b * a.L * D : nullptr;
@@ -655,6 +671,21 @@ __device__ static void produce_aug(const CropArgs& a, const uint32_t* tile, cons
   void* visible_image =
       kBf16 ? static_cast<void*>(static_cast<uint16_t*>(a.visible) + (int64_t)b * a.K * D)
             : static_cast<void*>(static_cast<float*>(a.visible) + (int64_t)b * a.K * D);
+  // one piece of a patch row of `target` / `visible` (element offsets inside the image)
+  auto store_piece = [&](uint32_t target_off, int rank, uint32_t visible_off, piece_t t) {
+    if (a.target) *reinterpret_cast<piece_t*>(target_image + target_off) = t;
+    if (rank < a.K) {
+      if (kBf16) {
+        uint16_t* dst = static_cast<uint16_t*>(visible_image) + visible_off;
+        if constexpr (kPx == 4)
+          *reinterpret_cast<u32x2*>(dst) = u32x2{pack_bf16x2(t[0], t[1]), pack_bf16x2(t[2], t[3])};
+        else
+          *reinterpret_cast<uint32_t*>(dst) = pack_bf16x2(t[0], t[1]);
+      } else {
+        *reinterpret_cast<piece_t*>(static_cast<float*>(visible_image) + visible_off) = t;
+      }
+    }
+  };
 
   // whole wavefronts stay in the loop: the stores are a wavefront's joint work
   for (int i0 = wave * kWave; i0 < ngroups; i0 += (int)blockDim.x) {
@@ -670,7 +701,7 @@ __device__ static void produce_aug(const CropArgs& a, const uint32_t* tile, cons
       have = i0 + lane < ngroups;
       const int i = have ? i0 + lane : ngroups - 1;
       gx = small_div(i, inv_gpp);
-      q = 4 * (i - __mul24(gx, gpp));  // first pixel of the group inside the patch
+      q = kPx * (i - __mul24(gx, gpp));  // first pixel of the group inside the patch
       py = small_div(q, inv_p);
       px = q - __mul24(py, p);
     }
@@ -678,9 +709,9 @@ __device__ static void produce_aug(const CropArgs& a, const uint32_t* tile, cons
     const u32x4 yt = ytab[py];
     const int cy = (int)yt.z, ry = (int)yt.w;
 
-    float v[12];
+    float v[kVals];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < kPx; ++j) {
       const u32x2 xt = xtab[xt0 + j];
       uint32_t w00, w01, w10, w11;
       fetch2<kLds>(tile, base, yt.x, (int)xt.x, cw, w00, w01);
@@ -688,25 +719,28 @@ __device__ static void produce_aug(const CropArgs& a, const uint32_t* tile, cons
       round_blend3(w00, w01, w10, w11, xt.y, cy, ry, dd, inv_dd, v + 3 * j);
     }
 
-    if (blur) {  // the blur kernel's input: the twelve rounded values as bytes
+    if (blur) {  // the blur kernel's input: the rounded values as bytes
       if (have) {
-        uint32_t w[3];
-#pragma unroll
-        for (int k = 0; k < 3; ++k)
-          w[k] = (uint32_t)v[4 * k] | ((uint32_t)v[4 * k + 1] << 8) |
-                 ((uint32_t)v[4 * k + 2] << 16) | ((uint32_t)v[4 * k + 3] << 24);
         // offsets inside one image stay below 2^22: 24-bit multiplies, one 64-bit base
-        uint32_t* dst = reinterpret_cast<uint32_t*>(
-            u8_image + (uint32_t)(__mul24(l0 + gx, D) + 3 * q));
-        dst[0] = w[0];
-        dst[1] = w[1];
-        dst[2] = w[2];
+        uint8_t* dst = u8_image + (uint32_t)(__mul24(l0 + gx, D) + 3 * q);
+        if constexpr (kPx == 4) {
+#pragma unroll
+          for (int k = 0; k < 3; ++k)
+            reinterpret_cast<uint32_t*>(dst)[k] =
+                (uint32_t)v[4 * k] | ((uint32_t)v[4 * k + 1] << 8) |
+                ((uint32_t)v[4 * k + 2] << 16) | ((uint32_t)v[4 * k + 3] << 24);
+        } else {
+#pragma unroll
+          for (int k = 0; k < 3; ++k)
+            reinterpret_cast<uint16_t*>(dst)[k] =
+                (uint16_t)((uint32_t)v[2 * k] | ((uint32_t)v[2 * k + 1] << 8));
+        }
       }
       continue;
     }
 
 #pragma unroll
-    for (int h = 0; h < 4; ++h) {
+    for (int h = 0; h < kPx; ++h) {
       if (gray) {
         // (299 R + 587 G + 114 B) / 1000 rounded to nearest: n + 1/2 is at least 0.0005 away from
         // a multiple of 1000 on either side, far more than the error of the product (n < 2^18)
@@ -737,19 +771,16 @@ __device__ static void produce_aug(const CropArgs& a, const uint32_t* tile, cons
     }
     if (kReduce) continue;
 
-    // normalise, then through the strip: 16-byte piece k of the strip belongs to group k / 3
-    f32x4* mine = reinterpret_cast<f32x4*>(strip + 12 * lane);
-    f32x4 o[3];
+    // normalise, then through the strip: piece k of the strip belongs to group k / 3
+    piece_t* mine = reinterpret_cast<piece_t*>(strip + kVals * lane);
+    piece_t o[3];
 #pragma unroll
-    for (int k = 0; k < 3; ++k) {
-      float t[4];
+    for (int k = 0; k < 3; ++k)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int idx = 4 * k + e;
-        t[e] = v[idx] * a.nscale[idx % 3] + a.nbias[idx % 3];
+      for (int e = 0; e < kPx; ++e) {
+        const int idx = kPx * k + e;
+        o[k][e] = v[idx] * a.nscale[idx % 3] + a.nbias[idx % 3];
       }
-      o[k] = f32x4{t[0], t[1], t[2], t[3]};
-    }
     __builtin_amdgcn_wave_barrier();
     mine[0] = o[0];
     mine[1] = o[1];
@@ -760,20 +791,11 @@ __device__ static void produce_aug(const CropArgs& a, const uint32_t* tile, cons
       const int gxs = __builtin_amdgcn_readfirstlane(gx);
       const int rank = __builtin_amdgcn_readlane(my_rank, gxs);
       const uint32_t e0 = 12u * (uint32_t)(i0 & (gpp - 1)) + 4u * (uint32_t)lane;
-      float* trow = a.target ? target_image + (l0 + gxs) * D : nullptr;
 #pragma unroll
       for (int k = 0; k < 3; ++k) {
-        const f32x4 t = reinterpret_cast<const f32x4*>(strip)[k * kWave + lane];
+        const piece_t t = reinterpret_cast<const piece_t*>(strip)[k * kWave + lane];
         const uint32_t eo = e0 + 4u * kWave * k;
-        if (trow) *reinterpret_cast<f32x4*>(trow + eo) = t;
-        if (rank < a.K) {
-          const uint32_t vo = (uint32_t)(rank * D) + eo;
-          if (kBf16)
-            *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(visible_image) + vo) =
-                u32x2{pack_bf16x2(t.x, t.y), pack_bf16x2(t.z, t.w)};
-          else
-            *reinterpret_cast<f32x4*>(static_cast<float*>(visible_image) + vo) = t;
-        }
+        store_piece((uint32_t)((l0 + gxs) * D) + eo, rank, (uint32_t)(rank * D) + eo, t);
       }
       continue;
     }
@@ -781,22 +803,13 @@ __device__ static void produce_aug(const CropArgs& a, const uint32_t* tile, cons
     for (int k = 0; k < 3; ++k) {
       const int piece = k * kWave + lane;
       const int g = i0 + small_div(piece, 1.0f / 3.0f);
-      const f32x4 t = reinterpret_cast<const f32x4*>(strip)[piece];
+      const piece_t t = reinterpret_cast<const piece_t*>(strip)[piece];
       const int pgx = small_div(min(g, ngroups - 1), inv_gpp);
       const int rank = __shfl(my_rank, pgx, kWave);
       if (g >= ngroups) continue;
       // element offset inside the patch row, then inside the image (below 2^20: 24-bit multiplies)
-      const int eo = 12 * (g - __mul24(pgx, gpp)) + 4 * (piece - 3 * (g - i0));
-      if (a.target)
-        *reinterpret_cast<f32x4*>(target_image + (uint32_t)(__mul24(l0 + pgx, D) + eo)) = t;
-      if (rank < a.K) {
-        const uint32_t vo = (uint32_t)(__mul24(rank, D) + eo);
-        if (kBf16)
-          *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(visible_image) + vo) =
-              u32x2{pack_bf16x2(t.x, t.y), pack_bf16x2(t.z, t.w)};
-        else
-          *reinterpret_cast<f32x4*>(static_cast<float*>(visible_image) + vo) = t;
-      }
+      const int eo = kVals * (g - __mul24(pgx, gpp)) + kPx * (piece - 3 * (g - i0));
+      store_piece((uint32_t)(__mul24(l0 + pgx, D) + eo), rank, (uint32_t)(__mul24(rank, D) + eo), t);
     }
   }
   if (kReduce && !blur) {
@@ -851,7 +864,8 @@ __device__ static void neutral_outputs(const CropArgs& a, int b, int gy, int gx0
 // kLossMode -1: the visible tokens only (no target).
 // kAug: the finetuning augmentation as the epilogue (produce_aug): 1 = "3 Aug", 2 / 3 = first /
 // second pass of "3 Aug+".
-template <bool kBf16, int kLossMode, int kAug = 0>
+// kAugPx: pixels per lane of that epilogue (4 when p is a multiple of 4, else 2).
+template <bool kBf16, int kLossMode, int kAug = 0, int kAugPx = 4>
 __device__ static inline void crop_band(const CropArgs& a, uint32_t* lds) {
   constexpr bool kLoss = kLossMode > 0;
   constexpr bool kKeptOnly = kLossMode < 0;
@@ -1006,14 +1020,13 @@ __device__ static inline void crop_band(const CropArgs& a, uint32_t* lds) {
       for (int g = 0; g < slots; ++g) sum += a.luma_partials[(int64_t)b * slots + g];
       mean = (float)(sum / ((double)S * (double)S));
     }
-    if (use_lds)
-      produce_aug<true, kBf16, kJitter, kPass>(a, tile, xtab, ytab, base, b, gy, gx0, npatch,
-                                               rec.cw - xlo, my_rank, ap, blur, mean, strips,
-                                               red64, tile_id);
-    else
-      produce_aug<false, kBf16, kJitter, kPass>(a, tile, xtab, ytab, base, b, gy, gx0, npatch,
-                                                rec.cw - xlo, my_rank, ap, blur, mean, strips,
-                                                red64, tile_id);
+#define MAE_PRODUCE_AUG(LDS)                                                                      \
+  produce_aug<LDS, kBf16, kJitter, kPass, kAugPx>(a, tile, xtab, ytab, base, b, gy, gx0, npatch,  \
+                                                  rec.cw - xlo, my_rank, ap, blur, mean, strips,  \
+                                                  red64, tile_id)
+    if (use_lds) MAE_PRODUCE_AUG(true);
+    else MAE_PRODUCE_AUG(false);
+#undef MAE_PRODUCE_AUG
   } else if constexpr (kLoss) {
     __shared__ float red[(kCropMaxThreads / kWave) * kLossChunk];
     __shared__ double red64[kCropMaxThreads / kWave];
@@ -1058,10 +1071,10 @@ __global__ __launch_bounds__(kCropMaxThreads) void crop_kept_kernel(CropArgs a) 
 }
 
 // ... with the finetuning augmentation's pointwise operations as the epilogue
-template <bool kBf16, int kAug>
+template <bool kBf16, int kAug, int kPx>
 __global__ __launch_bounds__(kCropMaxThreads) void crop_aug_kernel(CropArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
-  crop_band<kBf16, 0, kAug>(a, lds);
+  crop_band<kBf16, 0, kAug, kPx>(a, lds);
 }
 
 // The resampling kernel with the loss as its epilogue: what mae_normpix_loss computes, with the
@@ -1223,8 +1236,14 @@ hipError_t launch_crop_aug(const CropArgs& a, int pass, hipStream_t stream) {
   const size_t lds = ((crop_lds_bytes(a) + 15) & ~(size_t)15) +
                      (size_t)(block.x / kWave) * kStripFloats * sizeof(float);
   const int aug = a.aug_mode == 1 ? 1 : (pass == 0 ? 2 : 3);
-#define MAE_AUG_LAUNCH(BF, AUG) \
-  hipLaunchKernelGGL((crop_aug_kernel<BF, AUG>), grid, block, lds, stream, a)
+  // four pixels per lane when they tile a patch row, else two (even patch sizes)
+#define MAE_AUG_LAUNCH(BF, AUG)                                                          \
+  do {                                                                                   \
+    if ((a.p & 3) == 0)                                                                  \
+      hipLaunchKernelGGL((crop_aug_kernel<BF, AUG, 4>), grid, block, lds, stream, a);    \
+    else                                                                                 \
+      hipLaunchKernelGGL((crop_aug_kernel<BF, AUG, 2>), grid, block, lds, stream, a);    \
+  } while (0)
   if (a.visible_bf16) {
     if (aug == 1) MAE_AUG_LAUNCH(true, 1);
     else if (aug == 2) MAE_AUG_LAUNCH(true, 2);

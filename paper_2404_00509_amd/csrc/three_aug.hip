@@ -39,6 +39,18 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
 typedef u32x3 u32x3_a4 __attribute__((aligned(4)));
 
+// A lane's kPx neighbouring pixels are 3 kPx floats = three pieces of kPx floats.
+template <int kPx>
+struct BlurPiece;
+template <>
+struct BlurPiece<4> {
+  typedef f32x4 type;
+};
+template <>
+struct BlurPiece<2> {
+  typedef f32x2 type;
+};
+
 // floor(n / d) for 0 <= n < 2^22 and small d, from the float reciprocal (inv = 1 / d)
 __device__ static inline int fast_div(int n, float inv) { return (int)(((float)n + 0.5f) * inv); }
 
@@ -123,10 +135,14 @@ __device__ static inline void blur_vertical(const uint8_t* sbytes, float* vbuf, 
     const int px = fast_div(vx, 1.0f / 3.0f);
     const int c = vx - 3 * px;
     const int xa = min(max(x_lo - R + px, 0), S - 1);  // border column repeated
-    const uint8_t* src = sbytes + (yc * kRows) * pitchb + (xa - xs0) * 3 + c;
+    // (32-bit offsets, stepped row by row: no multiplication per row)
+    uint32_t at = (uint32_t)(__mul24(yc * kRows, pitchb) + (xa - xs0) * 3 + c);
     float in[kRows + 2 * R];
 #pragma unroll
-    for (int j = 0; j < kRows + 2 * R; ++j) in[j] = (float)src[j * pitchb];
+    for (int j = 0; j < kRows + 2 * R; ++j) {
+      in[j] = (float)sbytes[at];
+      at += (uint32_t)pitchb;
+    }
 #pragma unroll
     for (int y = 0; y < kRows; ++y) {
       float acc = 0.f;
@@ -137,28 +153,35 @@ __device__ static inline void blur_vertical(const uint8_t* sbytes, float* vbuf, 
   }
 }
 
-template <int R, bool kReduce, bool kBf16>
+// kPx: pixels per lane in the horizontal pass, 4 when p is a multiple of 4, else 2 (p even).
+template <int R, bool kReduce, bool kBf16, int kPx>
 __device__ static void blur_part(const AugArgs& a, const AugParams& ap, int b, int gy, int part,
                                  int gx0, int npatch, float* vbuf, uint8_t* scratch,
                                  double* red) {
+  typedef typename BlurPiece<kPx>::type piece_t;
+  constexpr int kVals = 3 * kPx;
   const int S = a.S, p = a.p, G = a.G;
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int Wp = npatch * p, x_lo = gx0 * p, y0 = gy * p;
   const int hp = halo_patches(p);
   const int gxa = max(gx0 - hp, 0), gxb = min(gx0 + npatch - 1 + hp, G - 1);
   const int nseg = gxb - gxa + 1, xs0 = gxa * p;
-  const int w4 = (3 * p) >> 2;      // dwords per patch row
-  const int pitch4 = nseg * w4;     // dwords per staged row
+  const int pitchb = nseg * 3 * p;  // bytes per staged row
   const int rows = p + 2 * R;
   const float inv_p = 1.0f / (float)p;
   const uint8_t* img = a.u8 + (int64_t)b * a.L * a.D;  // patch order
 
   // ---- staging: rows y0 - R .. y0 + p - 1 + R (clamped), patches gxa .. gxb ----------------------
-  // in pieces of 16 bytes when a patch row is a multiple of that (p = 16, 32), else of 4 bytes
-  if ((p & 15) == 0)
-    stage_rows<u32x4>(scratch, img, rows, nseg, w4 >> 2, y0 - R, S, p, G, gxa, a.D);
-  else
-    stage_rows<uint32_t>(scratch, img, rows, nseg, w4, y0 - R, S, p, G, gxa, a.D);
+  // in pieces of 16 bytes when a patch row is a multiple of that (p = 16, 32), else of 4 bytes,
+  // else (p even, no multiple of 4) of 2 bytes
+  if constexpr (kPx == 4) {
+    if ((p & 15) == 0)
+      stage_rows<u32x4>(scratch, img, rows, nseg, (3 * p) >> 4, y0 - R, S, p, G, gxa, a.D);
+    else
+      stage_rows<uint32_t>(scratch, img, rows, nseg, (3 * p) >> 2, y0 - R, S, p, G, gxa, a.D);
+  } else {
+    stage_rows<uint16_t>(scratch, img, rows, nseg, (3 * p) >> 1, y0 - R, S, p, G, gxa, a.D);
+  }
   // taps -R .. R of this image's kernel as the parameter kernel left them (zero beyond the
   // image's radius); the record is the same for the whole workgroup
   float wt[2 * R + 1];
@@ -166,28 +189,47 @@ __device__ static void blur_part(const AugArgs& a, const AugParams& ap, int b, i
   for (int k = 0; k <= 2 * R; ++k) wt[k] = ap.tap[k < R ? R - k : k - R];
   __syncthreads();
 
-  const int vpitch = (Wp + 2 * R) * 3;  // a multiple of four floats
-  if ((p & 7) == 0)
-    blur_vertical<R, 8>(scratch, vbuf, wt, p, S, x_lo, xs0, Wp, 4 * pitch4, vpitch);
-  else
-    blur_vertical<R, 4>(scratch, vbuf, wt, p, S, x_lo, xs0, Wp, 4 * pitch4, vpitch);
+  const int vpitch = (Wp + 2 * R) * 3;  // a multiple of kPx floats
+  if constexpr (kPx == 4) {
+    if ((p & 7) == 0)
+      blur_vertical<R, 8>(scratch, vbuf, wt, p, S, x_lo, xs0, Wp, pitchb, vpitch);
+    else
+      blur_vertical<R, 4>(scratch, vbuf, wt, p, S, x_lo, xs0, Wp, pitchb, vpitch);
+  } else {
+    blur_vertical<R, 2>(scratch, vbuf, wt, p, S, x_lo, xs0, Wp, pitchb, vpitch);
+  }
   // noise rank of each patch of the part, one per lane (read back with a shuffle at the stores)
   const int l0 = gy * G + gx0;
   const int my_rank = lane < npatch ? a.ids_restore[(int64_t)b * a.L + l0 + lane] : 0x7fffffff;
   __syncthreads();  // the staged bytes are dead from here on: their space serves as the strips
 
   const float mean = (!kReduce && a.mode == 2) ? image_mean(a, b) : 0.0f;
-  const int gpp = (p * p) >> 2;
+  const int gpp = (p * p) / kPx;
   const float inv_gpp = 1.0f / (float)gpp;
   const int ngroups = npatch * gpp;
-  float* strip = reinterpret_cast<float*>(scratch) + wave * (kWave * 12);
+  float* strip = reinterpret_cast<float*>(scratch) + wave * (kWave * kVals);
   float* target_image = a.target ? a.target + (int64_t)b * a.L * a.D : nullptr;
   void* visible_image =
       kBf16 ? static_cast<void*>(static_cast<uint16_t*>(a.visible) + (int64_t)b * a.K * a.D)
             : static_cast<void*>(static_cast<float*>(a.visible) + (int64_t)b * a.K * a.D);
+  // one piece of a patch row of `target` / `visible` (element offsets inside the image)
+  auto store_piece = [&](uint32_t target_off, int rank, uint32_t visible_off, piece_t t) {
+    if (a.target) *reinterpret_cast<piece_t*>(target_image + target_off) = t;
+    if (rank < a.K) {
+      if (kBf16) {
+        uint16_t* dst = static_cast<uint16_t*>(visible_image) + visible_off;
+        if constexpr (kPx == 4)
+          *reinterpret_cast<u32x2*>(dst) = u32x2{pack_bf16x2(t[0], t[1]), pack_bf16x2(t[2], t[3])};
+        else
+          *reinterpret_cast<uint32_t*>(dst) = pack_bf16x2(t[0], t[1]);
+      } else {
+        *reinterpret_cast<piece_t*>(static_cast<float*>(visible_image) + visible_off) = t;
+      }
+    }
+  };
   float lsum = 0.0f;
   // patches of 16 x 16 or 32 x 32 pixels: the 64 groups of a wavefront's step lie in one patch
-  const bool whole = (p & 15) == 0;
+  const bool whole = kPx == 4 && (p & 15) == 0;
   const int gsh = __builtin_ctz(gpp), psh = __builtin_ctz(p);  // used when `whole`
   for (int i0 = wave * kWave; i0 < ngroups; i0 += kAugThreads) {
     bool have;
@@ -201,24 +243,23 @@ __device__ static void blur_part(const AugArgs& a, const AugParams& ap, int b, i
       have = i0 + lane < ngroups;
       const int i = have ? i0 + lane : ngroups - 1;
       gxl = fast_div(i, inv_gpp);
-      q = 4 * (i - gxl * gpp);
+      q = kPx * (i - gxl * gpp);
       py = fast_div(q, inv_p);
     }
     const int x = gxl * p + (q - py * p);  // pixel inside the part
-    // pixels x - R .. x + 3 + R of the row: (4 + 2 R) * 3 floats, 16-byte aligned
-    const f32x4* src = reinterpret_cast<const f32x4*>(vbuf + py * vpitch + 3 * x);
-    float n[(4 + 2 * R) * 3];
+    // pixels x - R .. x + kPx - 1 + R of the row: (kPx + 2 R) * 3 floats, aligned to a piece
+    constexpr int kIn = (kPx + 2 * R) * 3;
+    const piece_t* src = reinterpret_cast<const piece_t*>(vbuf + py * vpitch + 3 * x);
+    float n[kIn];
 #pragma unroll
-    for (int j = 0; j < (4 + 2 * R) * 3 / 4; ++j) {
-      const f32x4 t = src[j];
-      n[4 * j] = t.x;
-      n[4 * j + 1] = t.y;
-      n[4 * j + 2] = t.z;
-      n[4 * j + 3] = t.w;
+    for (int j = 0; j < kIn / kPx; ++j) {
+      const piece_t t = src[j];
+#pragma unroll
+      for (int e = 0; e < kPx; ++e) n[kPx * j + e] = t[e];
     }
-    float v[12];
+    float v[kVals];
 #pragma unroll
-    for (int h = 0; h < 4; ++h) {
+    for (int h = 0; h < kPx; ++h) {
       float r = 0.f, g = 0.f, bl = 0.f;
 #pragma unroll
       for (int k = 0; k <= 2 * R; ++k) {
@@ -236,20 +277,18 @@ __device__ static void blur_part(const AugArgs& a, const AugParams& ap, int b, i
     }
     if (kReduce) continue;
 
-    // normalise, then through the wavefront's strip: every store instruction writes 1 KiB of
-    // contiguous memory; 16-byte piece k of the strip belongs to group k / 3
-    f32x4 o[3];
+    // normalise, then through the wavefront's strip: every store instruction writes 1 KiB (512
+    // bytes with two pixels per lane) of contiguous memory; piece k of the strip belongs to
+    // group k / 3
+    piece_t o[3];
 #pragma unroll
-    for (int k = 0; k < 3; ++k) {
-      float t[4];
+    for (int k = 0; k < 3; ++k)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int idx = 4 * k + e;
-        t[e] = v[idx] * a.nscale[idx % 3] + a.nbias[idx % 3];
+      for (int e = 0; e < kPx; ++e) {
+        const int idx = kPx * k + e;
+        o[k][e] = v[idx] * a.nscale[idx % 3] + a.nbias[idx % 3];
       }
-      o[k] = f32x4{t[0], t[1], t[2], t[3]};
-    }
-    f32x4* mine = reinterpret_cast<f32x4*>(strip + 12 * lane);
+    piece_t* mine = reinterpret_cast<piece_t*>(strip + kVals * lane);
     __builtin_amdgcn_wave_barrier();
     mine[0] = o[0];
     mine[1] = o[1];
@@ -260,20 +299,11 @@ __device__ static void blur_part(const AugArgs& a, const AugParams& ap, int b, i
       const int gxs = __builtin_amdgcn_readfirstlane(gxl);
       const int rank = __builtin_amdgcn_readlane(my_rank, gxs);
       const uint32_t e0 = 12u * (uint32_t)(i0 & (gpp - 1)) + 4u * (uint32_t)lane;
-      float* trow = a.target ? target_image + (l0 + gxs) * a.D : nullptr;
 #pragma unroll
       for (int k = 0; k < 3; ++k) {
-        const f32x4 t = reinterpret_cast<const f32x4*>(strip)[k * kWave + lane];
+        const piece_t t = reinterpret_cast<const piece_t*>(strip)[k * kWave + lane];
         const uint32_t eo = e0 + 4u * kWave * k;
-        if (trow) *reinterpret_cast<f32x4*>(trow + eo) = t;
-        if (rank < a.K) {
-          const uint32_t vo = (uint32_t)(rank * a.D) + eo;
-          if (kBf16)
-            *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(visible_image) + vo) =
-                u32x2{pack_bf16x2(t.x, t.y), pack_bf16x2(t.z, t.w)};
-          else
-            *reinterpret_cast<f32x4*>(static_cast<float*>(visible_image) + vo) = t;
-        }
+        store_piece((uint32_t)((l0 + gxs) * a.D) + eo, rank, (uint32_t)(rank * a.D) + eo, t);
       }
       continue;
     }
@@ -281,21 +311,13 @@ __device__ static void blur_part(const AugArgs& a, const AugParams& ap, int b, i
     for (int k = 0; k < 3; ++k) {
       const int piece = k * kWave + lane;
       const int g = i0 + fast_div(piece, 1.0f / 3.0f);
-      const f32x4 t = reinterpret_cast<const f32x4*>(strip)[piece];
+      const piece_t t = reinterpret_cast<const piece_t*>(strip)[piece];
       const int pgx = fast_div(min(g, ngroups - 1), inv_gpp);
       const int rank = __shfl(my_rank, pgx, kWave);
       if (g >= ngroups) continue;
-      const int eo = 12 * (g - __mul24(pgx, gpp)) + 4 * (piece - 3 * (g - i0));
-      if (a.target)
-        *reinterpret_cast<f32x4*>(target_image + (uint32_t)(__mul24(l0 + pgx, a.D) + eo)) = t;
-      if (rank < a.K) {
-        const uint32_t vo = (uint32_t)(__mul24(rank, a.D) + eo);
-        if (kBf16)
-          *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(visible_image) + vo) =
-              u32x2{pack_bf16x2(t.x, t.y), pack_bf16x2(t.z, t.w)};
-        else
-          *reinterpret_cast<f32x4*>(static_cast<float*>(visible_image) + vo) = t;
-      }
+      const int eo = kVals * (g - __mul24(pgx, gpp)) + kPx * (piece - 3 * (g - i0));
+      store_piece((uint32_t)(__mul24(l0 + pgx, a.D) + eo), rank,
+                  (uint32_t)(__mul24(rank, a.D) + eo), t);
     }
   }
   if (kReduce) store_band_sum<kAugThreads>(a, b, gy * a.blur_parts + part, lsum, red);
@@ -304,7 +326,7 @@ __device__ static void blur_part(const AugArgs& a, const AugParams& ap, int b, i
 // Dynamic LDS: [ vbuf: p rows of 3 (W + 12) floats, W = widest part in pixels | scratch: the
 // staged bytes ((p + 12) rows of the part's patches and their neighbours), later the four
 // wavefronts' strips ].
-template <bool kReduce, bool kBf16>
+template <bool kReduce, bool kBf16, int kPx>
 __global__ __launch_bounds__(kAugThreads) void aug_blur_kernel(AugArgs a) {
   extern __shared__ __attribute__((aligned(16))) float vals[];
   __shared__ double red[kAugThreads / kWave];
@@ -327,11 +349,11 @@ __global__ __launch_bounds__(kAugThreads) void aug_blur_kernel(AugArgs a) {
   uint8_t* scratch = reinterpret_cast<uint8_t*>(
       vals + p * 3 * (a.blur_part_patches * p + 2 * kMaxRadius));
   if (radius <= 2)
-    blur_part<2, kReduce, kBf16>(a, ap, b, gy, part, gx0, npatch, vbuf, scratch, red);
+    blur_part<2, kReduce, kBf16, kPx>(a, ap, b, gy, part, gx0, npatch, vbuf, scratch, red);
   else if (radius <= 4)
-    blur_part<4, kReduce, kBf16>(a, ap, b, gy, part, gx0, npatch, vbuf, scratch, red);
+    blur_part<4, kReduce, kBf16, kPx>(a, ap, b, gy, part, gx0, npatch, vbuf, scratch, red);
   else
-    blur_part<6, kReduce, kBf16>(a, ap, b, gy, part, gx0, npatch, vbuf, scratch, red);
+    blur_part<6, kReduce, kBf16, kPx>(a, ap, b, gy, part, gx0, npatch, vbuf, scratch, red);
 }
 
 // Bytes of dynamic LDS of the blur kernel for parts of n patches: the vertically blurred rows,
@@ -365,12 +387,18 @@ hipError_t launch_aug_blur(const AugArgs& a, bool reduce, hipStream_t stream) {
   dim3 block(kAugThreads);
   dim3 bgrid((uint32_t)a.B * (uint32_t)a.G * (uint32_t)a.blur_parts);
   const size_t lds = blur_lds_bytes(a.p, a.blur_part_patches);
-  if (reduce)
-    hipLaunchKernelGGL((aug_blur_kernel<true, false>), bgrid, block, lds, stream, a);
-  else if (a.visible_bf16)
-    hipLaunchKernelGGL((aug_blur_kernel<false, true>), bgrid, block, lds, stream, a);
-  else
-    hipLaunchKernelGGL((aug_blur_kernel<false, false>), bgrid, block, lds, stream, a);
+  // four pixels per lane when they tile a patch row, else two (even patch sizes)
+#define MAE_BLUR_LAUNCH(RED, BF)                                                           \
+  do {                                                                                     \
+    if ((a.p & 3) == 0)                                                                    \
+      hipLaunchKernelGGL((aug_blur_kernel<RED, BF, 4>), bgrid, block, lds, stream, a);     \
+    else                                                                                   \
+      hipLaunchKernelGGL((aug_blur_kernel<RED, BF, 2>), bgrid, block, lds, stream, a);     \
+  } while (0)
+  if (reduce) MAE_BLUR_LAUNCH(true, false);
+  else if (a.visible_bf16) MAE_BLUR_LAUNCH(false, true);
+  else MAE_BLUR_LAUNCH(false, false);
+#undef MAE_BLUR_LAUNCH
   return hipGetLastError();
 }
 

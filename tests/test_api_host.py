@@ -109,7 +109,7 @@ def _call_prep(lib, d, visible=FAKE, mask=FAKE, ids_restore=FAKE, workspace=FAKE
     (dict(aug_mode=-1), binding.MAE_ERR_RANGE),
     (dict(aug_mode=2, jitter=-0.1), binding.MAE_ERR_RANGE),
     (dict(aug_mode=2, jitter=float("nan")), binding.MAE_ERR_RANGE),
-    (dict(aug_mode=1, out_size=224, patch=14, num_keep=64), binding.MAE_ERR_SHAPE),  # 3 p % 4 != 0
+    (dict(aug_mode=1, out_size=225, patch=15, num_keep=64), binding.MAE_ERR_SHAPE),  # odd patch
 ])
 def test_prep_rejects_bad_descriptors(lib, over, status):
     d = _prep_desc(**over)

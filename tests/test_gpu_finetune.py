@@ -89,6 +89,33 @@ def test_other_patch_sizes_and_resolutions():
         check_prep_against_oracle(prep_to_numpy(buf), ref, what=f"S{S} p{p}")
 
 
+@pytest.mark.parametrize("mode", [mae.MAE_AUG_THREE, mae.MAE_AUG_THREE_PLUS])
+def test_patch_sizes_that_are_even_but_no_multiple_of_four(mode):
+    # p = 14 (the other ViT patch size), 6, 10 and 2: a lane then takes two pixels instead of four
+    # and the blur stages its bytes in 2-byte pieces
+    for S, p, kind in ((224, 14, "gradient"), (196, 14, "gradient"), (60, 6, "uniform"),
+                       (100, 10, "gradient"), (32, 2, "uniform")):
+        L = (S // p) ** 2
+        B = 9 if S > 100 else 16
+        data = synth.make_images(kind, B, seed=54)
+        kw = dict(out_size=S, patch=p, num_keep=L, seed=12, batch_index=1, aug_mode=mode,
+                  jitter=0.3)
+        ref = oracle.prep_batch(*data, **kw)
+        assert set(_ops(12, 1, B)) == {0, 1, 2}
+        buf, _, _ = gpu_prep(*data, **kw)
+        assert mae.mae_prep_status(buf.workspace) == 0
+        check_prep_against_oracle(prep_to_numpy(buf), ref, what=f"S{S} p{p} mode {mode}")
+    # bf16 tokens and masking at p = 14
+    S, p, B = 224, 14, 9
+    L = (S // p) ** 2
+    K = oracle.num_keep(L, 0.75)
+    data = synth.make_images("gradient", B, seed=55)
+    kw = dict(out_size=S, patch=p, num_keep=K, seed=13, batch_index=2, aug_mode=mode, jitter=0.3)
+    ref = oracle.prep_batch(*data, **kw)
+    buf, _, _ = gpu_prep(*data, bf16=True, **kw)
+    check_prep_against_oracle(prep_to_numpy(buf), ref, bf16=True, what=f"p14 bf16 mode {mode}")
+
+
 def test_shard_of_a_batch_and_reproducibility():
     S, B = 160, 16
     L = (S // 16) ** 2
