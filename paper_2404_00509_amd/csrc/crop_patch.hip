@@ -1089,26 +1089,32 @@ __global__ __launch_bounds__(4 * kWave) void crop_loss_wave_kernel(CropArgs a) {
   crop_band<false, 2>(a, lds);
 }
 
-// Patch sizes whose 3 p^2 values per patch are not a multiple of four (odd p): one value per
-// thread, taps straight from global memory.  Correct for every shape, not tuned.
+// Patch sizes whose 3 p^2 values per patch are not a multiple of four (odd p): one output pixel
+// per thread, taps straight from global memory.  Correct for every shape, not tuned further.
 template <bool kBf16>
 __global__ __launch_bounds__(kCropThreads) void crop_patch_scalar_kernel(CropArgs a) {
-  const int64_t per_image = (int64_t)a.L * a.D;
+  // one output pixel (three values) per thread and pass: the taps are worked out once per pixel
+  const int pp = a.p * a.p;
+  const int64_t per_image = (int64_t)a.L * pp;
   const int64_t total = (int64_t)a.B * per_image;
+  const float inv_den = 1.0f / (float)(2 * a.S);
   for (int64_t idx = (int64_t)blockIdx.x * kCropThreads + threadIdx.x; idx < total;
        idx += (int64_t)gridDim.x * kCropThreads) {
     const int b = (int)(idx / per_image);
     const int rem = (int)(idx - (int64_t)b * per_image);
     const CropRec rec = reinterpret_cast<const CropRec*>(a.workspace + kWorkspaceHeader)[b];
-    const int l = rem / a.D, e = rem - l * a.D;
+    const int l = rem / pp, q = rem - l * pp;
+    const int64_t to = ((int64_t)b * a.L + l) * a.D + 3 * q;  // the pixel's values in `target`
     if (!rec.valid) {  // takes no part: zero pixels, nothing masked, identity order
-      if (a.target) a.target[idx] = 0.0f;
-      if (l < a.K) {
-        const int64_t vo = ((int64_t)b * a.K + l) * a.D + e;
-        if (kBf16) static_cast<uint16_t*>(a.visible)[vo] = 0;
-        else static_cast<float*>(a.visible)[vo] = 0.0f;
+      const int64_t vo = ((int64_t)b * a.K + l) * a.D + 3 * q;
+      for (int c = 0; c < 3; ++c) {
+        if (a.target) a.target[to + c] = 0.0f;
+        if (l < a.K) {
+          if (kBf16) static_cast<uint16_t*>(a.visible)[vo + c] = 0;
+          else static_cast<float*>(a.visible)[vo + c] = 0.0f;
+        }
       }
-      if (e == 0) {
+      if (q == 0) {
         if (a.mask_out) a.mask_out[(int64_t)b * a.L + l] = 0;
         if (a.order_out) a.order_out[(int64_t)b * a.L + l] = l;
         if (a.keep_out && l < a.K) a.keep_out[(int64_t)b * a.K + l] = l;
@@ -1118,31 +1124,30 @@ __global__ __launch_bounds__(kCropThreads) void crop_patch_scalar_kernel(CropArg
       continue;
     }
     const int gy = l / a.G, gx = l - gy * a.G;
-    const int q = e / 3, c = e - 3 * q;
     const int py = q / a.p, px = q - py * a.p;
     const int oy = gy * a.p + py, ox = gx * a.p + px;
     int x0, x1, y0, y1;
     float fx, fy;
-    const float inv_den = 1.0f / (float)(2 * a.S);
     resize_taps(rec.flip ? a.S - 1 - ox : ox, rec.cw, a.S, inv_den, x0, x1, fx);
     resize_taps(oy, rec.ch, a.S, inv_den, y0, y1, fy);
     const int W = a.widths[b];
     const uint8_t* img = a.images + a.offsets[b];
-    const float a00 = img[((int64_t)(rec.top + y0) * W + rec.left + x0) * 3 + c];
-    const float a01 = img[((int64_t)(rec.top + y0) * W + rec.left + x1) * 3 + c];
-    const float a10 = img[((int64_t)(rec.top + y1) * W + rec.left + x0) * 3 + c];
-    const float a11 = img[((int64_t)(rec.top + y1) * W + rec.left + x1) * 3 + c];
-    const float rt = a00 + fx * (a01 - a00);
-    const float rb = a10 + fx * (a11 - a10);
-    const float v = (rt + fy * (rb - rt)) * a.nscale[c] + a.nbias[c];
-    if (a.target) a.target[idx] = v;
+    const uint8_t* p00 = img + ((int64_t)(rec.top + y0) * W + rec.left + x0) * 3;
+    const uint8_t* p01 = img + ((int64_t)(rec.top + y0) * W + rec.left + x1) * 3;
+    const uint8_t* p10 = img + ((int64_t)(rec.top + y1) * W + rec.left + x0) * 3;
+    const uint8_t* p11 = img + ((int64_t)(rec.top + y1) * W + rec.left + x1) * 3;
     const int rank = a.ids_restore[(int64_t)b * a.L + l];
-    if (rank < a.K) {
-      const int64_t vo = ((int64_t)b * a.K + rank) * a.D + e;
-      if (kBf16) {
-        static_cast<uint16_t*>(a.visible)[vo] = (uint16_t)bf16_rne(v);
-      } else {
-        static_cast<float*>(a.visible)[vo] = v;
+    const int64_t vo = ((int64_t)b * a.K + rank) * a.D + 3 * q;
+#pragma unroll
+    for (int c = 0; c < 3; ++c) {
+      const float a00 = p00[c], a01 = p01[c], a10 = p10[c], a11 = p11[c];
+      const float rt = a00 + fx * (a01 - a00);
+      const float rb = a10 + fx * (a11 - a10);
+      const float v = (rt + fy * (rb - rt)) * a.nscale[c] + a.nbias[c];
+      if (a.target) a.target[to + c] = v;
+      if (rank < a.K) {
+        if (kBf16) static_cast<uint16_t*>(a.visible)[vo + c] = (uint16_t)bf16_rne(v);
+        else static_cast<float*>(a.visible)[vo + c] = v;
       }
     }
   }
@@ -1272,7 +1277,7 @@ hipError_t launch_crop_patch(const CropArgs& a, hipStream_t stream) {
       hipLaunchKernelGGL(crop_patch_kernel<false>, grid, block, lds, stream, a);
     }
   } else {
-    const int64_t total = (int64_t)a.B * a.L * a.D;
+    const int64_t total = (int64_t)a.B * a.L * a.p * a.p;  // output pixels
     int64_t blocks = (total + kCropThreads - 1) / kCropThreads;
     if (blocks > 256 * 64) blocks = 256 * 64;
     dim3 grid((uint32_t)blocks), block(kCropThreads);
