@@ -17,7 +17,7 @@
 //    MCUs, and, for files with a restart interval per row, the restart markers (16 bytes per lane
 //    and step, positions ranked with a prefix sum) = the states at which the rows start.  The
 //    crop record is rewritten relative to the decoded region.
-//  * jpeg_scan_kernel (other files): one lane per file, sixteen files per wavefront with their
+//  * jpeg_scan_kernel (other files): one lane per file, two files per wavefront with their
 //    tables in LDS, decodes code lengths and DC differences only, handles restart markers where
 //    they come, and records the state of the bit reader and the DC predictors at the start of
 //    each of the crop's rows of MCUs.
@@ -825,12 +825,13 @@ __device__ static __forceinline__ void open_at(BitReader& r, const RowState& st)
 }
 
 // ---- files whose rows of MCUs are not independent: where does each of the crop's rows start? ----
-// One lane per file, kScanImages files per wavefront (their tables fill the LDS).  The lane walks
+// One lane per file, kScanImages files per wavefront (two: a batch then gives every SIMD two
+// wavefronts to switch between, and a lane rarely waits for the other's longer block).  The lane walks
 // the entropy-coded data from its start: per block the DC difference (the predictors run through
 // the whole interval) and the lengths of the AC symbols; at every restart boundary the marker is
 // skipped and the predictors cleared.  At the first MCU of each of the crop's rows the reader's
 // state goes to the workspace.  The walk ends with the crop's last row.
-constexpr int kScanImages = 16;
+constexpr int kScanImages = 2;
 struct JpegScanLds {
   JpegPrepared img[kScanImages];
   uint32_t ring[kRingBytes / 4][kJpegThreads];
