@@ -221,7 +221,7 @@ def run_steps(mae, torch, w, steps, warmup):
 
 
 def time_copy(torch, w, steps):
-    """A plain device copy of the size of the loss call's tensors (grad <- pred): what this box's
+    """A plain device copy of the size of the loss call's tensors (grad <- pred): what this machine's
     memory system delivers to the simplest kernel there is (read + write, same size)."""
     stream = torch.cuda.current_stream()
     st = stats(timed(torch, stream, lambda i: w.grad.copy_(w.pred), steps, 2))
